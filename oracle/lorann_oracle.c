@@ -1,0 +1,333 @@
+/*
+ * CPU oracle for the query phase of LoRANN (clustering-based ANN search with reduced-rank-regression
+ * score computation and 8-bit quantization).
+ *
+ * THIS IS TEST INFRASTRUCTURE.  It is a plain, slow, step-by-step statement of what the search computes,
+ * used only by the tests, the smoke check and the benchmark's CPU-baseline leg.  It shares no code with the
+ * HIP library and must never serve as a fallback for it.
+ *
+ * The search is an approximation whose result depends on every rounding step, so the oracle follows the
+ * algorithm in the paper's order (Sec. 2.2 template; Sec. 3.2 scores; Sec. 3.3 quantization; Sec. 4.1
+ * dimensionality reduction).  Floating-point contractions accumulate in double and round once to float;
+ * the integer stages are exact.  Notation: q query, q' = P^T q its d'-dimensional projection, mu_l
+ * centroids, A_c [d' x r] and B_c [r x m_c] the int8 factors of cluster c with step sizes DeltaA_c and
+ * DeltaB_c (real value ~= Delta * code), w clusters probed, m candidates kept (the paper's t), k returned.
+ *
+ * Readings of points the paper leaves open (all stated again in the tests):
+ *   - rounding of the query quantization: round-half-to-even (rintf), codes clamped to [-127, 127];
+ *   - the intermediate vector x'^T A is re-quantized per (query, cluster) pair; with one scalar DeltaA per
+ *     cluster the de-quantize / re-quantize pair of Sec. 3.3 cancels to an integer expression:
+ *     z_j = round_half_away(127 R_j / max|R|);
+ *   - a zero vector (max = 0) gets all-zero codes and scale 0;
+ *   - ties in each of the three selections go to the lower index;
+ *   - returned dissimilarities: squared Euclidean, negative inner product, 1 - <q, c> / |q| (cosine
+ *     corpora are unit-norm by construction, Sec. 3.1).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+enum { ORACLE_IP = 0, ORACLE_L2 = 1, ORACLE_COS = 2 };
+
+typedef struct {
+    int32_t metric;
+    int64_t n;
+    int32_t d, dp, r, L;
+    const float *centroids;        /* [L][dp] */
+    const float *P;                /* [d][dp] or NULL (identity, dp == d) */
+    const int8_t *A;               /* [L][r][dp] */
+    const int8_t *B;               /* [n][r] */
+    const float *scale_A;          /* [L] */
+    const float *scale_B;          /* [L] */
+    const int64_t *offsets;        /* [L+1] */
+    const float *corpus;           /* [n][d] rows in cluster order */
+    const int64_t *ids;            /* [n] or NULL */
+    const float *sqnorms;          /* [n] squared row norms from oracle_corpus_sqnorms (Euclidean), or NULL */
+} oracle_index;
+
+/* Optional per-stage outputs of oracle_search; any pointer may be NULL. */
+typedef struct {
+    float *qproj;        /* [nq][dp]      projected queries                     */
+    int8_t *q8;          /* [nq][dp]      quantized projected queries           */
+    float *dx;           /* [nq]          query step size                       */
+    int32_t *sel;        /* [nq][w]       selected clusters, best first         */
+    float *sel_g;        /* [nq][w]       their centroid dissimilarities        */
+    int32_t *R;          /* [nq][w][r]    int32 accumulators of q'_i8^T A_c     */
+    int8_t *z;           /* [nq][w][r]    re-quantized intermediate vectors     */
+    float *sigma;        /* [nq][w]       combined scale of each pair           */
+    int64_t *cand_rows;  /* [nq][m]       candidate rows (score desc, row asc), -1 padded */
+    float *cand_scores;  /* [nq][m]       their estimated scores (0 where padded) */
+} oracle_dump;
+
+/* ---- Step 1 (Sec. 4.1): q' = P^T q, double accumulation over i ascending, one rounding to float. ---- */
+void oracle_project(const float *q, int32_t d, int32_t dp, const float *P, float *qp)
+{
+    if (!P) { memcpy(qp, q, sizeof(float) * (size_t)dp); return; }
+    for (int32_t j = 0; j < dp; ++j) {
+        double acc = 0.0;
+        for (int32_t i = 0; i < d; ++i) acc += (double)q[i] * (double)P[(size_t)i * dp + j];
+        qp[j] = (float)acc;
+    }
+}
+
+/* ---- Step 2 (Sec. 2.2 routing, Sec. 3.1 reduction to inner products, Sec. 4.1 routing in d' dims). ---- */
+/* Dissimilarity of q' to every centroid: inner product / cosine -> -<q', mu>; Euclidean -> |mu|^2 - 2<q', mu>
+ * (the |q'|^2 term is common to all centroids). */
+void oracle_centroid_dissim(const float *qp, int32_t dp, const float *centroids, int32_t L, int32_t metric, float *g)
+{
+    for (int32_t l = 0; l < L; ++l) {
+        const float *mu = centroids + (size_t)l * dp;
+        double dot = 0.0, nrm = 0.0;
+        for (int32_t i = 0; i < dp; ++i) { dot += (double)qp[i] * (double)mu[i]; nrm += (double)mu[i] * (double)mu[i]; }
+        g[l] = (metric == ORACLE_L2) ? (float)(nrm - 2.0 * dot) : (float)(-dot);
+    }
+}
+
+typedef struct { float key; int64_t idx; } keyidx;
+static int cmp_key_asc(const void *a, const void *b)
+{
+    const keyidx *x = (const keyidx *)a, *y = (const keyidx *)b;
+    if (x->key < y->key) return -1;
+    if (x->key > y->key) return 1;
+    return (x->idx > y->idx) - (x->idx < y->idx);
+}
+static int cmp_key_desc(const void *a, const void *b)
+{
+    const keyidx *x = (const keyidx *)a, *y = (const keyidx *)b;
+    if (x->key > y->key) return -1;
+    if (x->key < y->key) return 1;
+    return (x->idx > y->idx) - (x->idx < y->idx);
+}
+
+/* The w smallest dissimilarities, ordered (g ascending, cluster id ascending). */
+void oracle_select_clusters(const float *g, int32_t L, int32_t w, int32_t *sel, float *sel_g)
+{
+    keyidx *t = (keyidx *)malloc(sizeof(keyidx) * (size_t)L);
+    for (int32_t l = 0; l < L; ++l) { t[l].key = g[l]; t[l].idx = l; }
+    qsort(t, (size_t)L, sizeof(keyidx), cmp_key_asc);
+    for (int32_t j = 0; j < w; ++j) { sel[j] = (int32_t)t[j].idx; if (sel_g) sel_g[j] = t[j].key; }
+    free(t);
+}
+
+/* ---- Step 3 (Sec. 3.3 absmax quantization of the query): codes = rint(c_x q'), c_x = 127 / |q'|_inf. ---- */
+void oracle_quantize_query(const float *qp, int32_t dp, int8_t *q8, float *dx)
+{
+    float a = 0.0f;
+    for (int32_t i = 0; i < dp; ++i) { float v = fabsf(qp[i]); if (v > a) a = v; }
+    if (!(a > 0.0f)) { memset(q8, 0, (size_t)dp); *dx = 0.0f; return; }
+    float cx = 127.0f / a;
+    for (int32_t i = 0; i < dp; ++i) {
+        float s = qp[i] * cx;
+        int v = (int)rintf(s);
+        if (v > 127) v = 127;
+        if (v < -127) v = -127;
+        q8[i] = (int8_t)v;
+    }
+    *dx = a / 127.0f;
+}
+
+/* ---- Step 4 (Sec. 3.3, first 8-bit product and re-quantization) for one (query, cluster) pair. ---- */
+/* R_j = sum_i q8[i] A_c[i][j] exactly; M = max|R_j|; z_j = sign(R_j) floor((254|R_j| + M) / (2M));
+ * sigma = M/127 * Delta_x * DeltaA_c * DeltaB_c evaluated left to right in double, rounded once. */
+void oracle_stage_a(const int8_t *q8, int32_t dp, int32_t r, const int8_t *A_c /* [r][dp] */, float dx,
+                    float dA, float dB, int32_t *R, int8_t *z, float *sigma)
+{
+    int64_t M = 0;
+    for (int32_t j = 0; j < r; ++j) {
+        int32_t acc = 0;
+        const int8_t *col = A_c + (size_t)j * dp;
+        for (int32_t i = 0; i < dp; ++i) acc += (int32_t)q8[i] * (int32_t)col[i];
+        R[j] = acc;
+        int64_t a = acc < 0 ? -(int64_t)acc : (int64_t)acc;
+        if (a > M) M = a;
+    }
+    if (M == 0) { memset(z, 0, (size_t)r); *sigma = 0.0f; return; }
+    for (int32_t j = 0; j < r; ++j) {
+        int64_t a = R[j] < 0 ? -(int64_t)R[j] : (int64_t)R[j];
+        int64_t v = (254 * a + M) / (2 * M);
+        z[j] = (int8_t)(R[j] < 0 ? -v : v);
+    }
+    *sigma = (float)((double)M / 127.0 * (double)dx * (double)dA * (double)dB);
+}
+
+/* ---- Step 5 (Sec. 3.2 prediction y = (x^T A) B in its 8-bit form, Sec. 3.1 Euclidean reduction). ---- */
+/* int32 accumulators of one pair: Y_j = sum_t z_t B[row_j][t]. */
+void oracle_pair_accumulators(const int8_t *z, int32_t r, const int8_t *B_c /* [m_c][r] */, int64_t m_c, int32_t *Y)
+{
+    for (int64_t j = 0; j < m_c; ++j) {
+        int32_t acc = 0;
+        const int8_t *code = B_c + (size_t)j * r;
+        for (int32_t t = 0; t < r; ++t) acc += (int32_t)z[t] * (int32_t)code[t];
+        Y[j] = acc;
+    }
+}
+
+/* Squared norm of a corpus row: double accumulation over i ascending, rounded to float. */
+float oracle_row_sqnorm(const float *c, int32_t d)
+{
+    double acc = 0.0;
+    for (int32_t i = 0; i < d; ++i) acc += (double)c[i] * (double)c[i];
+    return (float)acc;
+}
+
+void oracle_corpus_sqnorms(const float *corpus, int64_t n, int32_t d, float *out)
+{
+    for (int64_t j = 0; j < n; ++j) out[j] = oracle_row_sqnorm(corpus + (size_t)j * d, d);
+}
+
+/* Estimated score (higher = better): inner product / cosine: sigma * Y; Euclidean: 2 sigma Y - |c|^2,
+ * each as ONE fused multiply-add in float. */
+float oracle_score(int32_t Y, float sigma, int32_t metric, float sqnorm)
+{
+    if (metric == ORACLE_L2) return fmaf((float)Y, 2.0f * sigma, -sqnorm);
+    return fmaf((float)Y, sigma, -0.0f);
+}
+
+/* ---- Step 7 (Sec. 2.1 dissimilarities; Sec. 4.1: the original d-dimensional query is used). ---- */
+float oracle_exact_dissim(const float *q, const float *c, int32_t d, int32_t metric)
+{
+    double acc = 0.0;
+    if (metric == ORACLE_L2) {
+        for (int32_t i = 0; i < d; ++i) { double t = (double)q[i] - (double)c[i]; acc += t * t; }
+        return (float)acc;
+    }
+    for (int32_t i = 0; i < d; ++i) acc += (double)q[i] * (double)c[i];
+    if (metric == ORACLE_IP) return (float)(-acc);
+    double qn = 0.0;
+    for (int32_t i = 0; i < d; ++i) qn += (double)q[i] * (double)q[i];
+    if (!(qn > 0.0)) return 1.0f;
+    return (float)(1.0 - acc / sqrt(qn));
+}
+
+/* ---- The whole query phase for one query (steps 1-7). ---- */
+static void search_one(const oracle_index *ix, const float *q, int32_t k, int32_t w, int32_t m,
+                       int64_t *out_ids, float *out_dists, const oracle_dump *dump, int64_t qi)
+{
+    const int32_t d = ix->d, dp = ix->dp, r = ix->r, L = ix->L;
+    float *qp = (float *)malloc(sizeof(float) * (size_t)dp);
+    float *g = (float *)malloc(sizeof(float) * (size_t)L);
+    int32_t *sel = (int32_t *)malloc(sizeof(int32_t) * (size_t)w);
+    float *sel_g = (float *)malloc(sizeof(float) * (size_t)w);
+    int8_t *q8 = (int8_t *)malloc((size_t)dp);
+    int32_t *R = (int32_t *)malloc(sizeof(int32_t) * (size_t)r);
+    int8_t *z = (int8_t *)malloc((size_t)r);
+    float dx, sigma;
+
+    oracle_project(q, d, dp, ix->P, qp);                                   /* step 1 */
+    oracle_centroid_dissim(qp, dp, ix->centroids, L, ix->metric, g);       /* step 2 */
+    oracle_select_clusters(g, L, w, sel, sel_g);
+    oracle_quantize_query(qp, dp, q8, &dx);                                /* step 3 */
+
+    int64_t total = 0, max_mc = 0;
+    for (int32_t j = 0; j < w; ++j) {
+        int64_t mc = ix->offsets[sel[j] + 1] - ix->offsets[sel[j]];
+        total += mc;
+        if (mc > max_mc) max_mc = mc;
+    }
+    keyidx *sc = (keyidx *)malloc(sizeof(keyidx) * (size_t)(total > 0 ? total : 1));
+    int32_t *Y = (int32_t *)malloc(sizeof(int32_t) * (size_t)(max_mc > 0 ? max_mc : 1));
+    int64_t pos = 0;
+    for (int32_t j = 0; j < w; ++j) {                                      /* steps 4-5 per selected cluster */
+        const int32_t c = sel[j];
+        const int64_t off = ix->offsets[c], mc = ix->offsets[c + 1] - off;
+        oracle_stage_a(q8, dp, r, ix->A + (size_t)c * r * dp, dx, ix->scale_A[c], ix->scale_B[c], R, z, &sigma);
+        if (dump) {
+            if (dump->R) memcpy(dump->R + ((size_t)qi * w + j) * r, R, sizeof(int32_t) * (size_t)r);
+            if (dump->z) memcpy(dump->z + ((size_t)qi * w + j) * r, z, (size_t)r);
+            if (dump->sigma) dump->sigma[(size_t)qi * w + j] = sigma;
+        }
+        oracle_pair_accumulators(z, r, ix->B + (size_t)off * r, mc, Y);
+        for (int64_t t = 0; t < mc; ++t) {
+            float sq = 0.0f;   /* Sec. 3.1: the norms |c_j|^2 "can be precomputed" */
+            if (ix->metric == ORACLE_L2)
+                sq = ix->sqnorms ? ix->sqnorms[off + t] : oracle_row_sqnorm(ix->corpus + (size_t)(off + t) * d, d);
+            sc[pos].key = oracle_score(Y[t], sigma, ix->metric, sq);
+            sc[pos].idx = off + t;
+            ++pos;
+        }
+    }
+    /* step 6: the m highest estimated scores, order (score descending, row ascending) */
+    qsort(sc, (size_t)total, sizeof(keyidx), cmp_key_desc);
+    int64_t nc = total < m ? total : m;
+    keyidx *fin = (keyidx *)malloc(sizeof(keyidx) * (size_t)(nc > 0 ? nc : 1));
+    for (int64_t t = 0; t < nc; ++t) {                                     /* step 7: exact re-rank */
+        int64_t row = sc[t].idx;
+        fin[t].key = oracle_exact_dissim(q, ix->corpus + (size_t)row * d, d, ix->metric);
+        fin[t].idx = ix->ids ? ix->ids[row] : row;
+    }
+    qsort(fin, (size_t)nc, sizeof(keyidx), cmp_key_asc);
+    for (int32_t t = 0; t < k; ++t) {
+        if (t < nc) { out_ids[t] = fin[t].idx; out_dists[t] = fin[t].key; }
+        else { out_ids[t] = -1; out_dists[t] = INFINITY; }
+    }
+    if (dump) {
+        if (dump->qproj) memcpy(dump->qproj + (size_t)qi * dp, qp, sizeof(float) * (size_t)dp);
+        if (dump->q8) memcpy(dump->q8 + (size_t)qi * dp, q8, (size_t)dp);
+        if (dump->dx) dump->dx[qi] = dx;
+        if (dump->sel) memcpy(dump->sel + (size_t)qi * w, sel, sizeof(int32_t) * (size_t)w);
+        if (dump->sel_g) memcpy(dump->sel_g + (size_t)qi * w, sel_g, sizeof(float) * (size_t)w);
+        for (int32_t t = 0; t < m; ++t) {
+            if (dump->cand_rows) dump->cand_rows[(size_t)qi * m + t] = t < nc ? sc[t].idx : -1;
+            if (dump->cand_scores) dump->cand_scores[(size_t)qi * m + t] = t < nc ? sc[t].key : 0.0f;
+        }
+    }
+    free(fin); free(Y); free(sc); free(z); free(R); free(q8); free(sel_g); free(sel); free(g); free(qp);
+}
+
+/* Search a batch.  Parallel over queries only; each query runs the sequential algorithm above.
+ * Returns 0, or -1 on invalid arguments. */
+int oracle_search(const oracle_index *ix, const float *Q, int64_t nq, int32_t k, int32_t w, int32_t m,
+                  int64_t *out_ids, float *out_dists, const oracle_dump *dump, int32_t threads)
+{
+    if (!ix || !Q || nq < 0 || k < 1 || m < 1 || k > m || w < 1 || w > ix->L || !out_ids || !out_dists) return -1;
+    if (!ix->P && ix->dp != ix->d) return -1;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(dynamic, 4) num_threads(threads > 0 ? threads : 1)
+#endif
+    for (int64_t qi = 0; qi < nq; ++qi)
+        search_one(ix, Q + (size_t)qi * ix->d, k, w, m, out_ids + (size_t)qi * k, out_dists + (size_t)qi * k, dump, qi);
+    return 0;
+}
+
+/* ---- Exact k-NN by exhaustive evaluation (Sec. 2.1, Eq. 1): ground truth for recall. ---- */
+int oracle_exact_knn(const float *corpus, int64_t n, int32_t d, int32_t metric, const int64_t *ids, const float *Q,
+                     int64_t nq, int32_t k, int64_t *out_ids, float *out_dists, int32_t threads)
+{
+    if (!corpus || !Q || n < 0 || nq < 0 || k < 1) return -1;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(dynamic, 1) num_threads(threads > 0 ? threads : 1)
+#endif
+    for (int64_t qi = 0; qi < nq; ++qi) {
+        keyidx *t = (keyidx *)malloc(sizeof(keyidx) * (size_t)(n > 0 ? n : 1));
+        for (int64_t j = 0; j < n; ++j) {
+            t[j].key = oracle_exact_dissim(Q + (size_t)qi * d, corpus + (size_t)j * d, d, metric);
+            t[j].idx = ids ? ids[j] : j;
+        }
+        qsort(t, (size_t)n, sizeof(keyidx), cmp_key_asc);
+        for (int32_t j = 0; j < k; ++j) {
+            out_ids[(size_t)qi * k + j] = j < n ? t[j].idx : -1;
+            out_dists[(size_t)qi * k + j] = j < n ? t[j].key : INFINITY;
+        }
+        free(t);
+    }
+    return 0;
+}
+
+/* ---- Unquantized prediction y = (x^T A) B (Sec. 3.2) in double, for the full-rank and Theorem-1 checks. ---- */
+void oracle_rrr_predict_f64(const double *x, int32_t s, int32_t r, const double *A /* [s][r] */,
+                            const double *B /* [r][m_c] */, int64_t m_c, double *y)
+{
+    double *t = (double *)malloc(sizeof(double) * (size_t)r);
+    for (int32_t j = 0; j < r; ++j) {
+        double acc = 0.0;
+        for (int32_t i = 0; i < s; ++i) acc += x[i] * A[(size_t)i * r + j];
+        t[j] = acc;
+    }
+    for (int64_t c = 0; c < m_c; ++c) {
+        double acc = 0.0;
+        for (int32_t j = 0; j < r; ++j) acc += t[j] * B[(size_t)j * m_c + c];
+        y[c] = acc;
+    }
+    free(t);
+}

@@ -1,0 +1,381 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix (no GPU, no HIP library).
+
+Each test names the passage it checks.  Independent evidence used: numpy/Python-integer re-computation,
+library eigh/SVD, brute force, closed-form error bounds.
+"""
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+from oracle import oracle as O
+from oracle import rrr_fit as F
+
+IP, L2, COS = 0, 1, 2
+rng = np.random.default_rng(20241018)
+
+
+# ------------------------------------------------------------------ Sec. 3.2: the score model
+def _cluster(n_l=90, m_l=70, d=24, seed=0):
+    g = np.random.default_rng(seed)
+    scales = np.linspace(3.0, 0.3, d)                  # distinct spectrum => unique leading subspaces
+    C = g.normal(size=(m_l, d)) * scales + 0.5
+    X = g.normal(size=(n_l, d)) * scales[::-1] * 0.7 + 0.2
+    return X, C
+
+
+def test_full_rank_reproduces_exact_inner_products():
+    """Sec. 3.2: the unconstrained least-squares solution beta = C^T gives y = x^T C^T.  At r = d the
+    factorised prediction (x^T A) B must equal the exact inner products."""
+    X, C = _cluster()
+    d = C.shape[1]
+    A, B = F.rrr_fit(X, C, r=d)
+    for _ in range(5):
+        x = rng.normal(size=d)
+        y = O.rrr_predict_f64(x, A, B)
+        np.testing.assert_allclose(y, C @ x, rtol=1e-8, atol=1e-9)
+
+
+def test_theorem1_training_on_cluster_equals_projected_inner_products():
+    """Appendix A, Theorem 1: with X = C the RRR prediction equals the inner products of query and cluster
+    points after projecting both on the first r eigenvectors of C^T C (library eigh as the reference)."""
+    _, C = _cluster(seed=3)
+    r = 6
+    A, B = F.rrr_fit(C, C, r=r)
+    evals, evecs = np.linalg.eigh(C.T @ C)
+    Wr = evecs[:, np.argsort(evals)[::-1][:r]]
+    for _ in range(5):
+        x = rng.normal(size=C.shape[1])
+        y = O.rrr_predict_f64(x, A, B)
+        np.testing.assert_allclose(y, (Wr.T @ x) @ (C @ Wr).T, rtol=1e-7, atol=1e-8)
+
+
+def test_rrr_beats_other_rank_r_factorisations_on_training_loss():
+    """Sec. 3.2 / Appendix A: beta_RRR minimises |Y - X beta|_F over rank-r matrices; in particular it is
+    no worse than the truncated SVD of C^T and than perturbed rank-r candidates when X != C."""
+    X, C = _cluster(seed=5)
+    r = 5
+    A, B = F.rrr_fit(X, C, r=r)
+    Y = X @ C.T
+    loss = np.linalg.norm(Y - X @ (A @ B)) ** 2
+    U, S, Vt = np.linalg.svd(C.T, full_matrices=False)
+    beta_svd = (U[:, :r] * S[:r]) @ Vt[:r]
+    assert loss <= np.linalg.norm(Y - X @ beta_svd) ** 2 * (1 + 1e-12)
+    assert loss < np.linalg.norm(Y - X @ beta_svd) ** 2 * 0.999     # and strictly better here (X != C)
+    for t in range(10):
+        g = np.random.default_rng(t)
+        cand = (A + 0.05 * g.normal(size=A.shape)) @ (B + 0.05 * g.normal(size=B.shape))
+        assert loss <= np.linalg.norm(Y - X @ cand) ** 2
+
+
+def test_rrr_with_dimensionality_reduction_is_least_squares_on_projected_inputs():
+    """Sec. 4.1: A = (X W_s)^+ Y V_r with the TRUE inner products as outputs.  Checked through the normal
+    equations (residual orthogonal to the projected inputs), V_r orthonormal, and B = V_r^T spanning the
+    leading right singular subspace of Y."""
+    X, C = _cluster(seed=7)
+    s, r = 10, 4
+    W = F.projection_matrix(X, s)
+    evals = np.linalg.eigvalsh(X.T @ X)[::-1]
+    np.testing.assert_allclose(np.sort(np.diag(W.T @ (X.T @ X) @ W))[::-1], evals[:s], rtol=1e-9)
+    A, B = F.rrr_fit(X, C, r, W)
+    assert A.shape == (s, r) and B.shape == (r, C.shape[0])
+    Y = X @ C.T
+    np.testing.assert_allclose(B @ B.T, np.eye(r), atol=1e-10)
+    resid = Y @ B.T - (X @ W) @ A
+    np.testing.assert_allclose((X @ W).T @ resid, 0, atol=1e-6)
+    sv = np.linalg.svd(Y, compute_uv=False)
+    np.testing.assert_allclose(np.linalg.norm(Y @ B.T) ** 2, (sv[:r] ** 2).sum(), rtol=1e-9)
+
+
+# ------------------------------------------------------------------ Sec. 3.3: quantization
+def test_query_quantization_properties():
+    """Sec. 3.3 absmax: codes = round(127/|x|_inf * x): the largest code is +-127, every element is within
+    half a step of its code, the step is |x|_inf / 127; the zero vector maps to zero codes and step 0."""
+    for trial in range(50):
+        qp = (rng.normal(size=64) * rng.uniform(1e-3, 1e3)).astype(np.float32)
+        q8, dx = O.quantize_query(qp)
+        a = np.abs(qp).max()
+        assert np.abs(q8.astype(int)).max() == 127
+        assert dx == np.float32(a) / np.float32(127)
+        err = np.abs(qp.astype(np.float64) - float(dx) * q8.astype(np.float64))
+        assert err.max() <= 0.5 * float(dx) * (1 + 1e-5)
+        assert q8[np.argmax(np.abs(qp))] == 127 * np.sign(qp[np.argmax(np.abs(qp))])
+    q8, dx = O.quantize_query(np.zeros(16, np.float32))
+    assert not q8.any() and dx == 0
+
+
+def test_query_quantization_rounds_half_to_even():
+    """Reading of the paper's 'rounding to the nearest integer': ties go to the even code."""
+    # max = 127 => multiplier exactly 1; values k + 0.5 are exact in float
+    qp = np.array([127.0, 0.5, 1.5, 2.5, -0.5, -1.5, -2.5, 3.49], np.float32)
+    q8, dx = O.quantize_query(qp)
+    assert q8.tolist() == [127, 0, 2, 2, 0, -2, -2, 3] and dx == 1.0
+
+
+def test_stage_a_accumulators_and_requantization_exact():
+    """Sec. 3.3: r_i32 = x_i8^T A_i8 exactly (int64 matmul as reference); the re-quantized vector is
+    round-half-away(127 R_j / max|R|) checked in exact rational arithmetic; codes stay within +-127."""
+    for trial in range(30):
+        dp, r = int(rng.integers(1, 70)), int(rng.integers(1, 40))
+        q8 = rng.integers(-127, 128, size=dp).astype(np.int8)
+        A_c = rng.integers(-127, 128, size=(r, dp)).astype(np.int8)
+        R, z, sigma = O.stage_a(q8, A_c, 0.25, 0.5, 2.0)
+        ref = A_c.astype(np.int64) @ q8.astype(np.int64)
+        assert np.array_equal(R.astype(np.int64), ref)
+        M = int(np.abs(ref).max())
+        for j in range(r):
+            if M == 0:
+                assert z[j] == 0
+                continue
+            x = Fraction(127 * abs(int(ref[j])), M)
+            expect = int(x + Fraction(1, 2))            # floor(x + 1/2): half away from zero on |.|
+            assert int(z[j]) == (expect if ref[j] >= 0 else -expect)
+        assert np.abs(z.astype(int)).max() == (127 if M else 0)
+        # combined scale: (M/127) * dx * dA * dB; these factors are exact in binary
+        assert sigma == np.float32(M / 127.0 * 0.25 * 0.5 * 2.0)
+
+
+def test_stage_a_exhaustive_rounding_small():
+    """All (R, M) with M <= 40: integer formula == exact rational rounding, including the .5 ties."""
+    for M in range(1, 41):
+        q8 = np.array([1], np.int8)
+        col = np.arange(-M, M + 1)
+        col = col[np.abs(col) <= 127]
+        A_c = col.astype(np.int8).reshape(-1, 1)
+        R, z, _ = O.stage_a(q8, A_c, 1.0, 1.0, 1.0)
+        for Rj, zj in zip(R.tolist(), z.tolist()):
+            e = int(Fraction(127 * abs(Rj), M) + Fraction(1, 2))
+            assert zj == (e if Rj >= 0 else -e)
+
+
+def test_zero_intermediate_vector():
+    R, z, sigma = O.stage_a(np.zeros(8, np.int8), np.ones((4, 8), np.int8), 1.0, 1.0, 1.0)
+    assert not R.any() and not z.any() and sigma == 0
+
+
+def test_pair_accumulators_exact():
+    """Sec. 3.3 / 4.2: y_i32 = r_i8^T B_i8 exactly, for r that is and is not a multiple of 32."""
+    for r in (8, 24, 32, 48, 64):
+        z = rng.integers(-127, 128, size=r).astype(np.int8)
+        B_c = rng.integers(-127, 128, size=(257, r)).astype(np.int8)
+        Y = O.pair_accumulators(z, B_c)
+        assert np.array_equal(Y.astype(np.int64), B_c.astype(np.int64) @ z.astype(np.int64))
+    # extreme values: no int32 overflow at r = 64
+    z = np.full(64, -127, np.int8)
+    B_c = np.full((3, 64), 127, np.int8)
+    assert O.pair_accumulators(z, B_c).tolist() == [-64 * 127 * 127] * 3
+
+
+def test_quantized_scores_track_float_model_within_quantization_bound(small_indexes):
+    """Sec. 3.3: the 8-bit pipeline approximates (x'^T A) B.  With A, B taken at their de-quantized values
+    the only errors are the query quantization (<= Delta_x / 2 per element) and the re-quantization of the
+    intermediate vector (<= half a step); propagate both bounds exactly and require the oracle's score
+    sigma * Y to lie inside.  A dropped or misplaced scale factor, a transposed operand or a wrong sign
+    breaks this."""
+    for name, (wl, ix, corpus, queries) in small_indexes.items():
+        a = ix.numpy()
+        oix = O.OracleIndex(a)
+        ids, dists, st = O.search(oix, queries, wl.k, wl.w, wl.m, stages=True)
+        for qi in range(0, len(queries), 7):
+            for j in range(wl.w):
+                c = int(st["sel"][qi, j])
+                o0, o1 = int(a["cluster_offsets"][c]), int(a["cluster_offsets"][c + 1])
+                if o1 == o0:
+                    continue
+                dA, dB, dx = float(a["scale_A"][c]), float(a["scale_B"][c]), float(st["dx"][qi])
+                A_real = dA * a["A"][c].astype(np.float64).T            # [dp][r]
+                B_real = dB * a["B"][o0:o1].astype(np.float64).T        # [r][m_c]
+                qp = st["qproj"][qi].astype(np.float64)
+                y_ref = (qp @ A_real) @ B_real
+                err_r = 0.5 * dx * np.abs(A_real).sum(0)                 # query quantization, per j
+                M = np.abs(st["R"][qi, j].astype(np.int64)).max()
+                err_r = err_r + 0.5 * dx * dA * M / 127.0                # re-quantization half step
+                bound = err_r @ np.abs(B_real)
+                Y = O.pair_accumulators(st["z"][qi, j], a["B"][o0:o1])
+                s_hat = float(st["sigma"][qi, j]) * Y.astype(np.float64)
+                assert np.all(np.abs(s_hat - y_ref) <= bound * (1 + 1e-4) + 1e-6 * np.abs(y_ref).max()), name
+
+
+def test_quantized_scores_approximate_true_inner_products(small_indexes):
+    """End-to-end sanity of the score model on the anisotropic workloads: the estimated scores correlate
+    strongly with the true inner products q.c of the scored points (Sec. 3.1: it suffices to estimate inner
+    products)."""
+    wl, ix, corpus, queries = small_indexes["ip_P"]
+    a = ix.numpy()
+    oix = O.OracleIndex(a)
+    _, _, st = O.search(oix, queries, wl.k, wl.w, wl.m, stages=True)
+    cors = []
+    for qi in range(10):
+        c = int(st["sel"][qi, 0])
+        o0, o1 = int(a["cluster_offsets"][c]), int(a["cluster_offsets"][c + 1])
+        if o1 - o0 < 10:
+            continue
+        Y = O.pair_accumulators(st["z"][qi, 0], a["B"][o0:o1]).astype(np.float64) * float(st["sigma"][qi, 0])
+        true = a["corpus"][o0:o1].astype(np.float64) @ queries[qi].astype(np.float64)
+        cors.append(np.corrcoef(Y, true)[0, 1])
+    assert np.mean(cors) > 0.8
+
+
+# ------------------------------------------------------------------ Sec. 2.2 / 3.1 / 4.1: routing, selection, re-rank
+def test_projection_is_matrix_product():
+    """Sec. 4.1: x' = W_s^T x."""
+    q = rng.normal(size=37).astype(np.float32)
+    P = rng.normal(size=(37, 11)).astype(np.float32)
+    np.testing.assert_array_equal(O.project(q, P), (q.astype(np.float64) @ P.astype(np.float64)).astype(np.float32))
+    np.testing.assert_array_equal(O.project(q, None), q)
+
+
+def test_centroid_dissimilarities_and_routing_order():
+    """Sec. 2.2 (w nearest centroids), Sec. 3.1 (Euclidean ranking through -2 x^T c + |c|^2): the routing
+    order equals the order of true squared distances / negative inner products; ties go to the lower id."""
+    dp, L = 20, 50
+    cent = rng.normal(size=(L, dp)).astype(np.float32)
+    cent[17] = cent[3]                                        # exact tie between clusters 3 and 17
+    qp = rng.normal(size=dp).astype(np.float32)
+    c64, q64 = cent.astype(np.float64), qp.astype(np.float64)
+    g_ip = O.centroid_dissim(qp, cent, IP)
+    np.testing.assert_allclose(g_ip, -(c64 @ q64), rtol=1e-6)
+    np.testing.assert_array_equal(O.centroid_dissim(qp, cent, COS), g_ip)
+    g_l2 = O.centroid_dissim(qp, cent, L2)
+    d2 = ((c64 - q64) ** 2).sum(1)
+    np.testing.assert_allclose(g_l2 + (q64 @ q64), d2, rtol=1e-5, atol=1e-5)
+    for g in (g_ip, g_l2):
+        sel, sg = O.select_clusters(g, 12)
+        order = np.lexsort((np.arange(L), g))[:12]
+        np.testing.assert_array_equal(sel, order)
+        np.testing.assert_array_equal(sg, g[order])
+    sel, _ = O.select_clusters(g_l2, L)
+    assert list(sel).index(3) + 1 == list(sel).index(17)       # tie: lower id first
+
+
+def test_dissimilarity_identities():
+    """Sec. 2.1 + 3.1: |q - c|^2 = |q|^2 + |c|^2 - 2<q,c>; cosine distance equals 1 - <q,c>/|q| for a
+    unit-norm corpus point and is scale-invariant in q."""
+    for _ in range(20):
+        d = int(rng.integers(1, 200))
+        q = rng.normal(size=d).astype(np.float32)
+        c = rng.normal(size=d).astype(np.float32)
+        l2, ip = float(O.exact_dissim(q, c, L2)), float(O.exact_dissim(q, c, IP))
+        qn, cn = float(O.row_sqnorm(q)), float(O.row_sqnorm(c))
+        assert l2 == pytest.approx(qn + cn + 2 * ip, rel=1e-5, abs=1e-5)
+        cu = (c / np.linalg.norm(c)).astype(np.float32)
+        cos = float(O.exact_dissim(q, cu, COS))
+        ref = 1 - float(q.astype(np.float64) @ cu.astype(np.float64)) / np.linalg.norm(q.astype(np.float64))
+        assert cos == pytest.approx(ref, abs=1e-6)
+        assert float(O.exact_dissim((3 * q).astype(np.float32), cu, COS)) == pytest.approx(cos, abs=1e-6)
+    assert O.exact_dissim(np.zeros(4, np.float32), np.ones(4, np.float32), COS) == 1.0
+
+
+def test_score_is_one_fused_multiply_add():
+    """Sec. 3.1: Euclidean candidates are ranked by 2 x^T c - |c|^2 (negated argmin form); inner product and
+    cosine by the estimate itself."""
+    assert O.score(1000, 0.5, IP) == 500.0
+    assert O.score(-7, 0.25, COS) == -1.75
+    assert O.score(1000, 0.5, L2, 10.0) == 990.0
+    # single rounding: 2*sigma*Y - n differs from the twice-rounded product-then-subtract
+    Y, s, nrm = 12345, np.float32(0.1), np.float32(2468.9)
+    exact = float(np.float32(Y)) * float(np.float32(2) * s) - float(nrm)
+    assert O.score(Y, s, L2, nrm) == np.float32(exact)
+
+
+def _numpy_knn(corpus, q, metric, k, ids):
+    c, x = corpus.astype(np.float64), q.astype(np.float64)
+    if metric == L2:
+        dis = ((c - x) ** 2).sum(1)
+    elif metric == IP:
+        dis = -(c @ x)
+    else:
+        dis = 1 - (c @ x) / np.linalg.norm(x)
+    dis32 = dis.astype(np.float32)
+    order = np.lexsort((ids, dis32))[:k]
+    return ids[order], dis32[order]
+
+
+def test_probing_everything_returns_exact_knn(small_indexes):
+    """Sec. 2.1 Eq. (1) + Sec. 2.2: with every cluster probed and every point kept as candidate the
+    pipeline reduces to exact k-NN, whatever the quality of the 8-bit scores: brute force in numpy."""
+    for name, (wl, ix, corpus, queries) in small_indexes.items():
+        a = ix.numpy()
+        oix = O.OracleIndex(a)
+        ids, dists = O.search(oix, queries[:15], wl.k, wl.L, wl.n)
+        for qi in range(15):
+            e_ids, e_d = _numpy_knn(a["corpus"], queries[qi], wl.metric, wl.k, a["ids"])
+            np.testing.assert_allclose(dists[qi], e_d, rtol=1e-5, atol=1e-6, err_msg=name)
+            assert np.array_equal(ids[qi], e_ids) or np.allclose(dists[qi], e_d, rtol=1e-6), name
+        # the oracle's own exhaustive k-NN (used for recall) agrees as well
+        k_ids, k_d = O.exact_knn(a["corpus"], queries[:15], wl.metric, wl.k, ids=a["ids"])
+        np.testing.assert_array_equal(k_ids, ids)
+        np.testing.assert_array_equal(k_d, dists)
+
+
+def test_returned_ids_refer_to_original_corpus(small_indexes):
+    """Rows are stored in cluster order; returned ids are original corpus indices."""
+    wl, ix, corpus, queries = small_indexes["ip_P"]
+    a = ix.numpy()
+    np.testing.assert_array_equal(corpus[a["ids"]], a["corpus"])
+    ids, dists = O.search(O.OracleIndex(a), queries[:5], wl.k, wl.w, wl.m)
+    for qi in range(5):
+        for t in range(wl.k):
+            ref = -float(corpus[ids[qi, t]].astype(np.float64) @ queries[qi].astype(np.float64))
+            assert dists[qi, t] == pytest.approx(ref, rel=1e-6, abs=1e-7)
+
+
+def test_candidate_set_and_rerank_follow_the_template(small_indexes):
+    """Sec. 2.2: score the points of the w selected clusters, keep the m best, re-rank them with the true
+    dissimilarity of the ORIGINAL query (Sec. 4.1), return the k best.  Recomputed here step by step in
+    numpy from the stage outputs."""
+    for name, (wl, ix, corpus, queries) in small_indexes.items():
+        a = ix.numpy()
+        oix = O.OracleIndex(a)
+        ids, dists, st = O.search(oix, queries, wl.k, wl.w, wl.m, stages=True)
+        off = a["cluster_offsets"]
+        for qi in range(0, len(queries), 5):
+            rows, scores = [], []
+            for j in range(wl.w):
+                c = int(st["sel"][qi, j])
+                o0, o1 = int(off[c]), int(off[c + 1])
+                Y = a["B"][o0:o1].astype(np.int64) @ st["z"][qi, j].astype(np.int64)
+                sg = np.float32(st["sigma"][qi, j])
+                if wl.metric == L2:
+                    nrm = (a["corpus"][o0:o1].astype(np.float64) ** 2).sum(1).astype(np.float32)
+                    s = (Y.astype(np.float64) * float(np.float32(2) * sg) - nrm.astype(np.float64)).astype(np.float32)
+                else:
+                    s = (Y.astype(np.float64) * float(sg)).astype(np.float32)
+                rows.append(np.arange(o0, o1))
+                scores.append(s)
+            rows, scores = np.concatenate(rows), np.concatenate(scores)
+            order = np.lexsort((rows, -scores.astype(np.float64)))[:wl.m]
+            nc = len(order)
+            np.testing.assert_array_equal(st["cand_rows"][qi, :nc], rows[order], err_msg=name)
+            assert np.all(st["cand_rows"][qi, nc:] == -1)
+            np.testing.assert_array_equal(st["cand_scores"][qi, :nc], scores[order])
+            e_ids, e_d = _numpy_knn(a["corpus"][rows[order]], queries[qi], wl.metric, wl.k, a["ids"][rows[order]])
+            np.testing.assert_array_equal(ids[qi, :len(e_ids)], e_ids)
+            np.testing.assert_allclose(dists[qi, :len(e_ids)], e_d, rtol=1e-6, atol=1e-7)
+
+
+def test_fewer_candidates_than_k_pads():
+    """Fewer scored points than k: remaining slots hold id -1 and distance +inf."""
+    d, L = 8, 3
+    corpus = rng.normal(size=(4, d)).astype(np.float32)
+    ix = dict(metric=IP, n=4, d=d, dp=d, r=8, L=L, centroids=rng.normal(size=(L, d)).astype(np.float32), P=None,
+              A=rng.integers(-127, 128, size=(L, 8, d)).astype(np.int8),
+              B=rng.integers(-127, 128, size=(4, 8)).astype(np.int8), scale_A=np.ones(L, np.float32),
+              scale_B=np.ones(L, np.float32), cluster_offsets=np.array([0, 2, 2, 4], np.int64), corpus=corpus, ids=None)
+    q = corpus[:1] * 2
+    ids, dists = O.search(O.OracleIndex(ix), q, 6, 3, 10)
+    assert sorted(ids[0, :4].tolist()) == [0, 1, 2, 3] and ids[0, 4:].tolist() == [-1, -1]
+    assert np.isinf(dists[0, 4:]).all() and np.all(np.diff(dists[0, :4]) >= 0)
+    with pytest.raises(ValueError):
+        O.search(O.OracleIndex(ix), q, 6, 4, 10)          # w > L
+    with pytest.raises(ValueError):
+        O.search(O.OracleIndex(ix), q, 6, 2, 5)           # k > m
+
+
+# ------------------------------------------------------------------ Sec. 3.3 / 4.2: memory
+def test_index_bytes_match_memory_model(small_indexes):
+    """Sec. 4.2: the factors take L*s*r + r*m bytes."""
+    for name, (wl, ix, _, _) in small_indexes.items():
+        a = ix.numpy()
+        assert a["A"].nbytes + a["B"].nbytes == wl.L * wl.dp * wl.r + wl.r * wl.n
+        assert a["A"].dtype == np.int8 and a["B"].dtype == np.int8
