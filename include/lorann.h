@@ -1,0 +1,147 @@
+/*
+ * lorann.h - C ABI of the MI355X (gfx950) implementation of LoRANN's query phase.
+ *
+ * LoRANN (arXiv 2410.18926) is clustering-based approximate nearest-neighbour search whose score computation
+ * is reduced-rank regression: for a query q routed to cluster c, the inner products with the cluster's
+ * points are estimated as (q'^T A_c) B_c with q' = P^T q (Sec. 3.2, 4.1), evaluated as two 8-bit integer
+ * products with absmax scales (Sec. 3.3), followed by candidate selection and an exact re-rank (Sec. 2.2).
+ *
+ * Conventions shared by every entry point
+ *   - Pointers may be host or device pointers unless stated otherwise; the library finds out which with
+ *     hipPointerGetAttributes.  Device pointers must belong to the current HIP device.
+ *   - The library never keeps a caller pointer: lorann_load_index copies everything it needs into device
+ *     memory it owns; search inputs/outputs are only used during the call.
+ *   - Return value: LORANN_OK (0) or a negative error code; on error the outputs are untouched and
+ *     lorann_last_error() describes the problem (thread-local string, valid until the next failing call).
+ *   - One search at a time per index (the workspace belongs to the index).  Distinct indexes are independent.
+ *   - Work is enqueued on the index's stream (default: the null stream, see lorann_set_stream) and
+ *     lorann_search returns after the results are complete (it synchronises that stream).
+ */
+#ifndef LORANN_H
+#define LORANN_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct lorann_index lorann_index;   /* opaque; owns device memory */
+
+/* Dissimilarity measures of Sec. 2.1.  Returned distances: LORANN_IP  -> -<q, c>,
+ * LORANN_L2 -> squared Euclidean distance |q - c|^2, LORANN_COS -> 1 - <q, c> / |q| (corpus rows are
+ * expected to be unit-norm, Sec. 3.1). */
+enum { LORANN_IP = 0, LORANN_L2 = 1, LORANN_COS = 2 };
+
+enum {
+    LORANN_OK = 0,
+    LORANN_E_INVAL = -1,        /* bad argument (NULL, size, range, layout) */
+    LORANN_E_NOMEM = -2,        /* device or host allocation failed */
+    LORANN_E_DEVICE = -3,       /* a HIP call failed, or no gfx950 device */
+    LORANN_E_UNSUPPORTED = -4   /* valid request outside the implemented limits */
+};
+
+/* Limits of this implementation. */
+#define LORANN_MAX_W 256         /* clusters probed per query */
+#define LORANN_MAX_M 4096        /* candidates re-ranked per query */
+#define LORANN_MAX_R 64          /* RRR rank (multiple of 8) */
+#define LORANN_MAX_DP 1024       /* reduced dimension d' (multiple of 16) */
+
+/*
+ * lorann_load_index - copy an index to the GPU (Sec. 2.2 partition, Sec. 3.2-3.3 quantized factors,
+ * Sec. 4.1 projection and d'-dimensional centroids) and prepare it for searching.
+ *
+ *   metric           LORANN_IP / LORANN_L2 / LORANN_COS
+ *   n, d             corpus size (1 <= n < 2^31) and dimension (d >= 1)
+ *   dp               reduced dimension d' (the paper's s); multiple of 16, <= LORANN_MAX_DP
+ *   r                rank of the factors; multiple of 8, <= LORANN_MAX_R
+ *   L                number of clusters (>= 1)
+ *   centroids        [L][dp] float, row-major: cluster centroids in the projected space
+ *   P                [d][dp] float, row-major: projection matrix (the paper's W_s, any rotation already
+ *                    folded in); NULL means identity and requires dp == d
+ *   A                [L][r][dp] int8: A_c transposed, i.e. element (c, j, i) is A_c[i][j]
+ *   B                [n][r] int8: one r-byte code per corpus row (column of B_c), rows in cluster order
+ *   scale_A, scale_B [L] float each: absmax step sizes, real A_c ~= scale_A[c] * A, same for B
+ *   cluster_offsets  [L+1] int64: cluster c owns rows [cluster_offsets[c], cluster_offsets[c+1]);
+ *                    non-decreasing, first 0, last n.  Empty clusters are allowed.
+ *   corpus           [n][d] float, row-major, rows in the same cluster order (kept for the re-rank)
+ *   ids              [n] int64 caller id of each row, or NULL (then the row number is returned)
+ *
+ * On success *out receives the index (release it with lorann_free_index).  Errors: LORANN_E_INVAL for NULL
+ * or inconsistent arguments (including non-monotone offsets), LORANN_E_UNSUPPORTED beyond the limits above,
+ * LORANN_E_NOMEM / LORANN_E_DEVICE from the runtime.  Nothing is allocated on failure.
+ */
+int lorann_load_index(lorann_index **out, int32_t metric, int64_t n, int32_t d, int32_t dp, int32_t r, int32_t L,
+                      const float *centroids, const float *P, const int8_t *A, const int8_t *B,
+                      const float *scale_A, const float *scale_B, const int64_t *cluster_offsets,
+                      const float *corpus, const int64_t *ids);
+
+/*
+ * lorann_search - the query phase (Sec. 2.2 template with the score computation of Sec. 3.2-3.3, 4.1):
+ * project each query, route it to its w nearest centroids, estimate the scores of all points of those
+ * clusters with the 8-bit reduced-rank model, keep the m best (the paper's t), re-rank them with the exact
+ * dissimilarity to the original query and return the k best.
+ *
+ *   queries    [nq][d] float, row-major
+ *   nq         number of queries (0 is allowed and does nothing)
+ *   k, w, m    1 <= k <= m <= LORANN_MAX_M;  1 <= w <= min(L, LORANN_MAX_W)
+ *   out_ids    [nq][k] int64: ids of the neighbours, nearest first; ties by distance go to the lower id;
+ *              slots beyond the number of scored points hold -1
+ *   out_dists  [nq][k] float: their dissimilarities (see the metric enum), ascending; +inf where id is -1
+ *
+ * All selections break ties toward the lower index (cluster id, corpus row, returned id).  m larger than the
+ * number of points in the selected clusters is legal: all of them become candidates.
+ */
+int lorann_search(lorann_index *ix, const float *queries, int64_t nq, int32_t k, int32_t w, int32_t m,
+                  int64_t *out_ids, float *out_dists);
+
+/* Release an index and its workspace.  NULL is ignored. */
+void lorann_free_index(lorann_index *ix);
+
+/* Message of the last failing call on this thread ("" if none). */
+const char *lorann_last_error(void);
+
+/* Use `hip_stream` (a hipStream_t, e.g. the caller framework's current stream) for all later work of this
+ * index.  NULL selects the null stream.  The stream must stay valid while the index uses it. */
+int lorann_set_stream(lorann_index *ix, void *hip_stream);
+
+/*
+ * Intermediate results of one search, for verification against a reference implementation.  Every pointer
+ * may be NULL (skipped) and may be a host or device pointer.  Layouts, with slot = query * w + rank:
+ */
+typedef struct lorann_stages {
+    float *qproj;          /* [nq][dp]      projected queries q' (Sec. 4.1)                               */
+    int8_t *q8;            /* [nq][dp]      absmax codes of q' (Sec. 3.3)                                 */
+    float *dx;             /* [nq]          step size of each query's codes                               */
+    int32_t *sel;          /* [nq][w]       selected clusters, nearest centroid first (Sec. 2.2)          */
+    int8_t *z;             /* [nq][w][r]    re-quantized intermediate vectors of each pair (Sec. 3.3)     */
+    float *sigma;          /* [nq][w]       combined scale of each pair: score = sigma * integer score    */
+    int32_t *cand_rows;    /* [nq][m]       candidate corpus rows, unordered, -1 padded (Sec. 2.2)        */
+    const int64_t *y_off;  /* [nq*w + 1]    caller-chosen offsets into y (needs sel known beforehand)     */
+    int32_t *y;            /* [y_off[nq*w]] int32 score accumulators of every point of every pair, in     */
+                           /*               cluster row order: y[y_off[slot] + t] (Sec. 3.3, 4.2)         */
+} lorann_stages;
+
+/* lorann_search that also exports the intermediate results named in `st`.  Same arguments and errors as
+ * lorann_search; y_off[slot+1] - y_off[slot] must equal the size of the slot's cluster. */
+int lorann_search_stages(lorann_index *ix, const float *queries, int64_t nq, int32_t k, int32_t w, int32_t m,
+                         int64_t *out_ids, float *out_dists, const lorann_stages *st);
+
+/*
+ * Per-kernel timing of the searches of one index, taken with HIP events on the index's stream.
+ * lorann_profile_enable(ix, 1) starts recording (and clears the totals), 0 stops.  lorann_profile_get
+ * writes up to `cap` records and returns how many kernels exist (or a negative error code).
+ */
+typedef struct lorann_kernel_time {
+    char name[48];      /* kernel name */
+    double ms;          /* total time of its launches since profiling was enabled */
+    int64_t launches;
+} lorann_kernel_time;
+
+int lorann_profile_enable(lorann_index *ix, int32_t on);
+int lorann_profile_get(lorann_index *ix, lorann_kernel_time *out, int32_t cap);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LORANN_H */

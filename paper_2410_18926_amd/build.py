@@ -1,0 +1,42 @@
+"""Build the HIP library: hipcc for gfx950 -> paper_2410_18926_amd/liblorann.so (in-tree)."""
+from __future__ import annotations
+
+import pathlib
+import shutil
+import subprocess
+
+HERE = pathlib.Path(__file__).resolve().parent
+SRC = HERE / "csrc" / "lorann.hip"
+LIB = HERE / "liblorann.so"
+
+FLAGS = [
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC",
+    # packed fp32 instructions are kept off: some of their forms have produced wrong results on the test machines
+    "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    "-Wall", "-Wno-unused-function",
+]
+
+
+def sources():
+    return [SRC] + sorted((HERE / "csrc").glob("*.hpp")) + [HERE.parent / "include" / "lorann.h"]
+
+
+def build(force: bool = True, verbose: bool = False) -> pathlib.Path:
+    hipcc = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
+    if not force and LIB.exists() and all(LIB.stat().st_mtime >= s.stat().st_mtime for s in sources()):
+        return LIB
+    cmd = [hipcc, *FLAGS, "-o", str(LIB), str(SRC)]
+    if verbose:
+        print(" ".join(cmd))
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    noise = "packed-fp32-ops"
+    err = "\n".join(l for l in res.stderr.splitlines() if noise not in l)
+    if res.returncode != 0:
+        raise RuntimeError(f"hipcc failed:\n{err}")
+    if verbose and err.strip():
+        print(err)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build(verbose=True))

@@ -1,0 +1,472 @@
+// C ABI (include/lorann.h) and host orchestration of LoRANN's query phase on one MI355X (gfx950).
+//
+// Kernel sequence of one batch, all on the index's stream, no host synchronisation in between:
+//   project (fp64 matrix cores) -> quantize -> centroid dissimilarities (fp64 matrix cores) -> select w
+//   clusters (+ bucket histogram) -> scan -> scatter pairs into cluster buckets -> first int8 product +
+//   re-quantization (int8 matrix cores, per cluster) -> int8 scores + exact top-m -> exact re-rank + top-k.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "../../include/lorann.h"
+#include "common.hpp"
+#include "gemm_f64.hpp"
+#include "rerank.hpp"
+#include "route.hpp"
+#include "select_exact.hpp"
+#include "stage_a.hpp"
+
+using namespace lorann;
+
+namespace {
+
+thread_local std::string g_err;
+
+int fail(int code, const char* fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_err = buf;
+    return code;
+}
+
+#define HIP_TRY(expr)                                                                                      \
+    do {                                                                                                   \
+        hipError_t e_ = (expr);                                                                            \
+        if (e_ != hipSuccess)                                                                              \
+            return fail(e_ == hipErrorOutOfMemory ? LORANN_E_NOMEM : LORANN_E_DEVICE, "%s failed: %s", #expr, \
+                        hipGetErrorString(e_));                                                            \
+    } while (0)
+
+bool is_device_ptr(const void* p) {
+    hipPointerAttribute_t at;
+    hipError_t e = hipPointerGetAttributes(&at, p);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();   // plain host memory: clear the sticky error
+        return false;
+    }
+    return at.type == hipMemoryTypeDevice || at.type == hipMemoryTypeManaged;
+}
+
+// Device buffer that grows on demand and is freed with its owner.
+struct DevBuf {
+    void* p = nullptr;
+    size_t cap = 0;
+    int reserve(size_t bytes) {
+        if (bytes <= cap) return LORANN_OK;
+        if (p) { (void)hipFree(p); p = nullptr; cap = 0; }
+        size_t want = bytes + bytes / 8 + 256;
+        hipError_t e = hipMalloc(&p, want);
+        if (e != hipSuccess) { (void)hipGetLastError(); p = nullptr; return fail(LORANN_E_NOMEM, "hipMalloc of %zu bytes failed: %s", want, hipGetErrorString(e)); }
+        cap = want;
+        return LORANN_OK;
+    }
+    void release() { if (p) (void)hipFree(p); p = nullptr; cap = 0; }
+    template <typename T> T* as() const { return reinterpret_cast<T*>(p); }
+};
+
+enum KernelId { K_PROJECT, K_QUANTIZE, K_CENTROID, K_SELECT_W, K_SCAN, K_SCATTER, K_STAGE_A, K_SELECT_M, K_RERANK, K_ZERO, K_COUNT };
+const char* const kKernelNames[K_COUNT] = {"project_f64", "quantize_rows", "centroid_dissim_f64", "select_clusters",
+                                            "scan_buckets", "scatter_pairs", "stage_a_i8", "score_select_exact",
+                                            "rerank", "zero_counters"};
+
+struct EventPair { hipEvent_t a, b; int kid; };
+
+}  // namespace
+
+struct lorann_index {
+    int32_t metric = 0, d = 0, dp = 0, r = 0, r_pad = 0, L = 0;
+    int64_t n = 0;
+    hipStream_t stream = nullptr;
+    // index data (device)
+    float* centroids = nullptr;     // [L][dp]
+    double* cent_sqnorm = nullptr;  // [L] (Euclidean)
+    float* Pt = nullptr;            // [dp][d] transposed projection, or NULL
+    int8_t* A = nullptr;            // [L][r][dp]
+    int8_t* Bp = nullptr;           // [n][r_pad] codes padded with zeros to r_pad bytes
+    float *sA = nullptr, *sB = nullptr;
+    int64_t* off = nullptr;         // [L+1]
+    float* corpus = nullptr;        // [n][d]
+    int64_t* ids = nullptr;         // [n] or NULL
+    float* sqnorm = nullptr;        // [n] (Euclidean)
+    // workspace (device), sized for `chunk` queries
+    DevBuf qproj, q8, dx, gscore, sel, count, cursor, bucket_off, tile_off, slot_of_pos, pos_of_slot, Z, sigma, cand;
+    DevBuf stage_q, stage_ids, stage_dists;   // staging when the caller passes host memory
+    // profiling
+    bool prof_on = false;
+    std::vector<EventPair> ev_used, ev_free;
+    double prof_ms[K_COUNT] = {0};
+    int64_t prof_launches[K_COUNT] = {0};
+};
+
+namespace {
+
+void free_all(lorann_index* ix) {
+    void* ptrs[] = {ix->centroids, ix->cent_sqnorm, ix->Pt, ix->A, ix->Bp, ix->sA, ix->sB, ix->off, ix->corpus, ix->ids, ix->sqnorm};
+    for (void* p : ptrs) if (p) (void)hipFree(p);
+    DevBuf* bufs[] = {&ix->qproj, &ix->q8, &ix->dx, &ix->gscore, &ix->sel, &ix->count, &ix->cursor, &ix->bucket_off, &ix->tile_off,
+                      &ix->slot_of_pos, &ix->pos_of_slot, &ix->Z, &ix->sigma, &ix->cand, &ix->stage_q, &ix->stage_ids, &ix->stage_dists};
+    for (DevBuf* b : bufs) b->release();
+    for (auto& e : ix->ev_used) { (void)hipEventDestroy(e.a); (void)hipEventDestroy(e.b); }
+    for (auto& e : ix->ev_free) { (void)hipEventDestroy(e.a); (void)hipEventDestroy(e.b); }
+    delete ix;
+}
+
+template <typename T>
+int dev_copy(T** dst, const T* src, size_t count) {
+    HIP_TRY(hipMalloc(reinterpret_cast<void**>(dst), std::max<size_t>(count, 1) * sizeof(T)));
+    if (count) HIP_TRY(hipMemcpy(*dst, src, count * sizeof(T), hipMemcpyDefault));
+    return LORANN_OK;
+}
+
+__global__ void k_pad_codes(const int8_t* __restrict__ B, int8_t* __restrict__ Bp, int64_t n, int r, int r_pad) {
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= n * r_pad) return;
+    const int64_t row = t / r_pad;
+    const int j = (int)(t - row * r_pad);
+    Bp[t] = j < r ? B[row * r + j] : (int8_t)0;
+}
+
+struct Prof {
+    lorann_index* ix;
+    int idx = -1;
+    Prof(lorann_index* ix_, int kid) : ix(ix_) {
+        if (!ix->prof_on) return;
+        EventPair ep;
+        if (!ix->ev_free.empty()) { ep = ix->ev_free.back(); ix->ev_free.pop_back(); }
+        else if (hipEventCreate(&ep.a) != hipSuccess || hipEventCreate(&ep.b) != hipSuccess) return;
+        ep.kid = kid;
+        ix->ev_used.push_back(ep);
+        idx = (int)ix->ev_used.size() - 1;
+        (void)hipEventRecord(ep.a, ix->stream);
+    }
+    ~Prof() { if (idx >= 0) (void)hipEventRecord(ix->ev_used[idx].b, ix->stream); }
+};
+
+void prof_collect(lorann_index* ix) {   // the stream has been synchronised
+    for (auto& e : ix->ev_used) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, e.a, e.b) == hipSuccess) { ix->prof_ms[e.kid] += ms; ix->prof_launches[e.kid] += 1; }
+        ix->ev_free.push_back(e);
+    }
+    ix->ev_used.clear();
+}
+
+int next_pow2(int v) { int p = 1; while (p < v) p <<= 1; return p; }
+
+// One batch of at most `chunk` queries, device pointers only.
+int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, int m, int64_t* d_ids, float* d_dists,
+                 const lorann_stages* st, int64_t q_base) {
+    const int L = ix->L, dp = ix->dp, d = ix->d, r_pad = ix->r_pad;
+    const int64_t npairs = nq * w;
+    hipStream_t s = ix->stream;
+    int rc;
+    if ((rc = ix->qproj.reserve((size_t)nq * dp * 4))) return rc;
+    if ((rc = ix->q8.reserve((size_t)nq * dp))) return rc;
+    if ((rc = ix->dx.reserve((size_t)nq * 4))) return rc;
+    if ((rc = ix->gscore.reserve((size_t)nq * L * 4))) return rc;
+    if ((rc = ix->sel.reserve((size_t)npairs * 4))) return rc;
+    if ((rc = ix->count.reserve((size_t)L * 4))) return rc;
+    if ((rc = ix->cursor.reserve((size_t)L * 4))) return rc;
+    if ((rc = ix->bucket_off.reserve((size_t)(L + 1) * 4))) return rc;
+    if ((rc = ix->tile_off.reserve((size_t)(L + 1) * 4))) return rc;
+    if ((rc = ix->slot_of_pos.reserve((size_t)npairs * 4))) return rc;
+    if ((rc = ix->pos_of_slot.reserve((size_t)npairs * 4))) return rc;
+    if ((rc = ix->Z.reserve((size_t)npairs * r_pad))) return rc;
+    if ((rc = ix->sigma.reserve((size_t)npairs * 4))) return rc;
+    if ((rc = ix->cand.reserve((size_t)nq * m * 4))) return rc;
+
+    const float* qp = dQ;   // projected queries
+    if (ix->Pt) {
+        Prof p(ix, K_PROJECT);
+        dim3 grid((dp + GM_BN - 1) / GM_BN, (unsigned)((nq + GM_BM - 1) / GM_BM));
+        hipLaunchKernelGGL(k_gemm_nt_f64<EPI_PLAIN>, grid, dim3(256), 0, s, dQ, ix->Pt, ix->qproj.as<float>(), (const double*)nullptr, (int)nq, dp, d);
+        qp = ix->qproj.as<float>();
+    }
+    {
+        Prof p(ix, K_ZERO);
+        hipLaunchKernelGGL(k_zero_i32, dim3((L + 255) / 256), dim3(256), 0, s, ix->count.as<int32_t>(), (int64_t)L);
+    }
+    {
+        Prof p(ix, K_QUANTIZE);
+        hipLaunchKernelGGL(k_quantize_rows, dim3((unsigned)((nq + 3) / 4)), dim3(256), 0, s, qp, ix->q8.as<int8_t>(), ix->dx.as<float>(), (int)nq, dp);
+    }
+    {
+        Prof p(ix, K_CENTROID);
+        dim3 grid((L + GM_BN - 1) / GM_BN, (unsigned)((nq + GM_BM - 1) / GM_BM));
+        if (ix->metric == LORANN_L2)
+            hipLaunchKernelGGL(k_gemm_nt_f64<EPI_L2>, grid, dim3(256), 0, s, qp, ix->centroids, ix->gscore.as<float>(), (const double*)ix->cent_sqnorm, (int)nq, L, dp);
+        else
+            hipLaunchKernelGGL(k_gemm_nt_f64<EPI_NEG>, grid, dim3(256), 0, s, qp, ix->centroids, ix->gscore.as<float>(), (const double*)nullptr, (int)nq, L, dp);
+    }
+    {
+        Prof p(ix, K_SELECT_W);
+        hipLaunchKernelGGL(k_select_clusters, dim3((unsigned)nq), dim3(256), 0, s, ix->gscore.as<float>(), L, w, ix->sel.as<int32_t>(), ix->count.as<int32_t>());
+    }
+    {
+        Prof p(ix, K_SCAN);
+        hipLaunchKernelGGL(k_scan_buckets, dim3(1), dim3(1024), 0, s, ix->count.as<int32_t>(), L, ix->bucket_off.as<int32_t>(), ix->tile_off.as<int32_t>(), ix->cursor.as<int32_t>());
+    }
+    {
+        Prof p(ix, K_SCATTER);
+        hipLaunchKernelGGL(k_scatter_pairs, dim3((unsigned)((npairs + 255) / 256)), dim3(256), 0, s, ix->sel.as<int32_t>(), npairs, ix->bucket_off.as<int32_t>(),
+                           ix->cursor.as<int32_t>(), ix->slot_of_pos.as<int32_t>(), ix->pos_of_slot.as<int32_t>());
+    }
+    {
+        Prof p(ix, K_STAGE_A);
+        const int64_t max_tiles = npairs / 16 + L + 1;      // sum_c ceil(count_c / 16) <= npairs / 16 + L
+        dim3 grid((unsigned)((max_tiles + 3) / 4));
+        if (r_pad == 32)
+            hipLaunchKernelGGL(k_stage_a<2>, grid, dim3(256), 0, s, ix->q8.as<int8_t>(), ix->dx.as<float>(), ix->A, ix->sA, ix->sB, ix->bucket_off.as<int32_t>(),
+                               ix->tile_off.as<int32_t>(), ix->slot_of_pos.as<int32_t>(), L, dp, ix->r, w, ix->Z.as<int8_t>(), ix->sigma.as<float>());
+        else
+            hipLaunchKernelGGL(k_stage_a<4>, grid, dim3(256), 0, s, ix->q8.as<int8_t>(), ix->dx.as<float>(), ix->A, ix->sA, ix->sB, ix->bucket_off.as<int32_t>(),
+                               ix->tile_off.as<int32_t>(), ix->slot_of_pos.as<int32_t>(), L, dp, ix->r, w, ix->Z.as<int8_t>(), ix->sigma.as<float>());
+    }
+    {
+        Prof p(ix, K_SELECT_M);
+        SelectArgs a;
+        a.qlist = nullptr; a.qcount = nullptr; a.sel = ix->sel.as<int32_t>(); a.pos_of_slot = ix->pos_of_slot.as<int32_t>();
+        a.Z = ix->Z.as<int8_t>(); a.sigma = ix->sigma.as<float>(); a.Bp = ix->Bp; a.off = ix->off;
+        a.sqnorm = ix->metric == LORANN_L2 ? ix->sqnorm : nullptr; a.cand = ix->cand.as<int32_t>(); a.w = w; a.m = m;
+        if (r_pad == 32) hipLaunchKernelGGL(k_select_exact<2>, dim3((unsigned)nq), dim3(256), 0, s, a);
+        else hipLaunchKernelGGL(k_select_exact<4>, dim3((unsigned)nq), dim3(256), 0, s, a);
+    }
+    {
+        Prof p(ix, K_RERANK);
+        const int mp2 = std::max(256, next_pow2(m));
+        const size_t lds = (size_t)d * 4 + (size_t)mp2 * 12;
+        const int32_t* cand = ix->cand.as<int32_t>();
+        if (ix->metric == LORANN_IP)
+            hipLaunchKernelGGL(k_rerank<0>, dim3((unsigned)nq), dim3(256), lds, s, dQ, ix->corpus, ix->ids, cand, d, m, mp2, k, d_ids, d_dists);
+        else if (ix->metric == LORANN_L2)
+            hipLaunchKernelGGL(k_rerank<1>, dim3((unsigned)nq), dim3(256), lds, s, dQ, ix->corpus, ix->ids, cand, d, m, mp2, k, d_ids, d_dists);
+        else
+            hipLaunchKernelGGL(k_rerank<2>, dim3((unsigned)nq), dim3(256), lds, s, dQ, ix->corpus, ix->ids, cand, d, m, mp2, k, d_ids, d_dists);
+    }
+    HIP_TRY(hipGetLastError());
+
+    if (st) {   // export intermediate results (verification only; not part of the timed path)
+        HIP_TRY(hipStreamSynchronize(s));
+        if (st->qproj) HIP_TRY(hipMemcpy(st->qproj + (size_t)q_base * dp, qp, (size_t)nq * dp * 4, hipMemcpyDefault));
+        if (st->q8) HIP_TRY(hipMemcpy(st->q8 + (size_t)q_base * dp, ix->q8.p, (size_t)nq * dp, hipMemcpyDefault));
+        if (st->dx) HIP_TRY(hipMemcpy(st->dx + q_base, ix->dx.p, (size_t)nq * 4, hipMemcpyDefault));
+        if (st->sel) HIP_TRY(hipMemcpy(st->sel + (size_t)q_base * w, ix->sel.p, (size_t)npairs * 4, hipMemcpyDefault));
+        if (st->cand_rows) HIP_TRY(hipMemcpy(st->cand_rows + (size_t)q_base * m, ix->cand.p, (size_t)nq * m * 4, hipMemcpyDefault));
+        if (st->z || st->sigma) {   // bucket order -> slot order on the host
+            std::vector<int32_t> pos(npairs);
+            std::vector<int8_t> Zh((size_t)npairs * r_pad);
+            std::vector<float> sg(npairs);
+            HIP_TRY(hipMemcpy(pos.data(), ix->pos_of_slot.p, (size_t)npairs * 4, hipMemcpyDeviceToHost));
+            HIP_TRY(hipMemcpy(Zh.data(), ix->Z.p, (size_t)npairs * r_pad, hipMemcpyDeviceToHost));
+            HIP_TRY(hipMemcpy(sg.data(), ix->sigma.p, (size_t)npairs * 4, hipMemcpyDeviceToHost));
+            std::vector<int8_t> zo((size_t)npairs * ix->r);
+            std::vector<float> so(npairs);
+            for (int64_t p = 0; p < npairs; ++p) {
+                memcpy(zo.data() + (size_t)p * ix->r, Zh.data() + (size_t)pos[p] * r_pad, (size_t)ix->r);
+                so[p] = sg[pos[p]];
+            }
+            if (st->z) HIP_TRY(hipMemcpy(st->z + (size_t)q_base * w * ix->r, zo.data(), zo.size(), hipMemcpyDefault));
+            if (st->sigma) HIP_TRY(hipMemcpy(st->sigma + (size_t)q_base * w, so.data(), so.size() * 4, hipMemcpyDefault));
+        }
+        if (st->y && st->y_off) {
+            // the caller's offsets may live on the host: stage the slice of this chunk on the device
+            std::vector<int64_t> yo(npairs + 1);
+            HIP_TRY(hipMemcpy(yo.data(), st->y_off + (size_t)q_base * w, (size_t)(npairs + 1) * 8, hipMemcpyDefault));
+            const int64_t y0 = yo[0], y1 = yo[npairs];
+            for (auto& v : yo) v -= y0;
+            int64_t* d_yo = nullptr; int32_t* d_y = nullptr;
+            HIP_TRY(hipMalloc((void**)&d_yo, (size_t)(npairs + 1) * 8));
+            hipError_t e = hipMalloc((void**)&d_y, std::max<size_t>((size_t)(y1 - y0), 1) * 4);
+            if (e != hipSuccess) { (void)hipFree(d_yo); return fail(LORANN_E_NOMEM, "hipMalloc for the score dump failed"); }
+            (void)hipMemcpy(d_yo, yo.data(), (size_t)(npairs + 1) * 8, hipMemcpyHostToDevice);
+            if (r_pad == 32) hipLaunchKernelGGL(k_dump_pair_scores<2>, dim3((unsigned)npairs), dim3(256), 0, s, ix->sel.as<int32_t>(), ix->pos_of_slot.as<int32_t>(), ix->Z.as<int8_t>(), ix->Bp, ix->off, d_yo, d_y);
+            else hipLaunchKernelGGL(k_dump_pair_scores<4>, dim3((unsigned)npairs), dim3(256), 0, s, ix->sel.as<int32_t>(), ix->pos_of_slot.as<int32_t>(), ix->Z.as<int8_t>(), ix->Bp, ix->off, d_yo, d_y);
+            e = hipStreamSynchronize(s);
+            if (e == hipSuccess) e = hipMemcpy(st->y + y0, d_y, (size_t)(y1 - y0) * 4, hipMemcpyDefault);
+            (void)hipFree(d_yo); (void)hipFree(d_y);
+            if (e != hipSuccess) return fail(LORANN_E_DEVICE, "score dump failed: %s", hipGetErrorString(e));
+        }
+    }
+    return LORANN_OK;
+}
+
+int search_impl(lorann_index* ix, const float* queries, int64_t nq, int32_t k, int32_t w, int32_t m, int64_t* out_ids,
+                float* out_dists, const lorann_stages* st) {
+    if (!ix) return fail(LORANN_E_INVAL, "index is NULL");
+    if (nq < 0) return fail(LORANN_E_INVAL, "nq = %lld is negative", (long long)nq);
+    if (k < 1 || m < 1 || k > m) return fail(LORANN_E_INVAL, "need 1 <= k <= m (k = %d, m = %d)", k, m);
+    if (w < 1 || w > ix->L) return fail(LORANN_E_INVAL, "need 1 <= w <= L (w = %d, L = %d)", w, ix->L);
+    if (w > LORANN_MAX_W) return fail(LORANN_E_UNSUPPORTED, "w = %d exceeds LORANN_MAX_W = %d", w, LORANN_MAX_W);
+    if (m > LORANN_MAX_M) return fail(LORANN_E_UNSUPPORTED, "m = %d exceeds LORANN_MAX_M = %d", m, LORANN_MAX_M);
+    if (nq == 0) return LORANN_OK;
+    if (!queries || !out_ids || !out_dists) return fail(LORANN_E_INVAL, "queries / out_ids / out_dists must not be NULL");
+    {
+        const int mp2 = std::max(256, next_pow2(m));
+        if ((size_t)ix->d * 4 + (size_t)mp2 * 12 > 64 * 1024)
+            return fail(LORANN_E_UNSUPPORTED, "d = %d with m = %d needs more than 64 KiB of LDS in the re-rank", ix->d, m);
+    }
+    // batches are processed in chunks that keep nq * w and nq * L within 32-bit indexing and a bounded workspace
+    int64_t chunk = 32768;
+    while (chunk > 1 && (chunk * w > (1ll << 30) || chunk * (int64_t)ix->L > (1ll << 31))) chunk >>= 1;
+
+    const bool q_dev = is_device_ptr(queries), i_dev = is_device_ptr(out_ids), d_dev = is_device_ptr(out_dists);
+    for (int64_t q0 = 0; q0 < nq; q0 += chunk) {
+        const int64_t cn = std::min(chunk, nq - q0);
+        const float* dQ = queries + (size_t)q0 * ix->d;
+        int64_t* dI = out_ids + (size_t)q0 * k;
+        float* dD = out_dists + (size_t)q0 * k;
+        int rc;
+        if (!q_dev) {
+            if ((rc = ix->stage_q.reserve((size_t)cn * ix->d * 4))) return rc;
+            HIP_TRY(hipMemcpyAsync(ix->stage_q.p, dQ, (size_t)cn * ix->d * 4, hipMemcpyHostToDevice, ix->stream));
+            dQ = ix->stage_q.as<float>();
+        }
+        if (!i_dev) { if ((rc = ix->stage_ids.reserve((size_t)cn * k * 8))) return rc; dI = ix->stage_ids.as<int64_t>(); }
+        if (!d_dev) { if ((rc = ix->stage_dists.reserve((size_t)cn * k * 4))) return rc; dD = ix->stage_dists.as<float>(); }
+        if ((rc = search_chunk(ix, dQ, cn, k, w, m, dI, dD, st, q0))) return rc;
+        if (!i_dev) HIP_TRY(hipMemcpyAsync(out_ids + (size_t)q0 * k, dI, (size_t)cn * k * 8, hipMemcpyDeviceToHost, ix->stream));
+        if (!d_dev) HIP_TRY(hipMemcpyAsync(out_dists + (size_t)q0 * k, dD, (size_t)cn * k * 4, hipMemcpyDeviceToHost, ix->stream));
+        HIP_TRY(hipStreamSynchronize(ix->stream));
+        if (ix->prof_on) prof_collect(ix);
+    }
+    return LORANN_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* lorann_last_error(void) { return g_err.c_str(); }
+
+int lorann_load_index(lorann_index** out, int32_t metric, int64_t n, int32_t d, int32_t dp, int32_t r, int32_t L,
+                      const float* centroids, const float* P, const int8_t* A, const int8_t* B, const float* scale_A,
+                      const float* scale_B, const int64_t* cluster_offsets, const float* corpus, const int64_t* ids) {
+    if (!out) return fail(LORANN_E_INVAL, "out is NULL");
+    if (metric != LORANN_IP && metric != LORANN_L2 && metric != LORANN_COS) return fail(LORANN_E_INVAL, "unknown metric %d", metric);
+    if (n < 1 || d < 1 || dp < 1 || r < 1 || L < 1) return fail(LORANN_E_INVAL, "n, d, dp, r, L must be positive");
+    if (!centroids || !A || !B || !scale_A || !scale_B || !cluster_offsets || !corpus) return fail(LORANN_E_INVAL, "a required array is NULL");
+    if (!P && dp != d) return fail(LORANN_E_INVAL, "P = NULL (identity) requires dp == d (dp = %d, d = %d)", dp, d);
+    if (dp % 16 != 0) return fail(LORANN_E_INVAL, "dp = %d must be a multiple of 16", dp);
+    if (r % 8 != 0) return fail(LORANN_E_INVAL, "r = %d must be a multiple of 8", r);
+    if (dp > LORANN_MAX_DP) return fail(LORANN_E_UNSUPPORTED, "dp = %d exceeds LORANN_MAX_DP = %d", dp, LORANN_MAX_DP);
+    if (r > LORANN_MAX_R) return fail(LORANN_E_UNSUPPORTED, "r = %d exceeds LORANN_MAX_R = %d", r, LORANN_MAX_R);
+    if (n >= (1ll << 31)) return fail(LORANN_E_UNSUPPORTED, "n = %lld must be below 2^31", (long long)n);
+
+    std::vector<int64_t> off(L + 1);
+    if (is_device_ptr(cluster_offsets)) {
+        hipError_t e = hipMemcpy(off.data(), cluster_offsets, (size_t)(L + 1) * 8, hipMemcpyDeviceToHost);
+        if (e != hipSuccess) { (void)hipGetLastError(); return fail(LORANN_E_DEVICE, "reading cluster_offsets failed: %s", hipGetErrorString(e)); }
+    } else {
+        memcpy(off.data(), cluster_offsets, (size_t)(L + 1) * 8);
+    }
+    if (off[0] != 0 || off[L] != n) return fail(LORANN_E_INVAL, "cluster_offsets must start at 0 and end at n");
+    for (int c = 0; c < L; ++c)
+        if (off[c + 1] < off[c]) return fail(LORANN_E_INVAL, "cluster_offsets decrease at cluster %d", c);
+
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || ndev < 1) { (void)hipGetLastError(); return fail(LORANN_E_DEVICE, "no HIP device"); }
+
+    lorann_index* ix = new (std::nothrow) lorann_index();
+    if (!ix) return fail(LORANN_E_NOMEM, "out of host memory");
+    ix->metric = metric; ix->n = n; ix->d = d; ix->dp = dp; ix->r = r; ix->L = L;
+    ix->r_pad = r <= 32 ? 32 : 64;
+    int rc = LORANN_OK;
+    auto body = [&]() -> int {
+        int e;
+        if ((e = dev_copy(&ix->centroids, centroids, (size_t)L * dp))) return e;
+        if ((e = dev_copy(&ix->A, A, (size_t)L * r * dp))) return e;
+        if ((e = dev_copy(&ix->sA, scale_A, (size_t)L))) return e;
+        if ((e = dev_copy(&ix->sB, scale_B, (size_t)L))) return e;
+        if ((e = dev_copy(&ix->off, off.data(), (size_t)L + 1))) return e;
+        if ((e = dev_copy(&ix->corpus, corpus, (size_t)n * d))) return e;
+        if (ids && (e = dev_copy(&ix->ids, ids, (size_t)n))) return e;
+        {   // codes padded to r_pad bytes per point so that every point is one or two aligned 32-byte operands
+            int8_t* Braw = nullptr;
+            if ((e = dev_copy(&Braw, B, (size_t)n * r))) return e;
+            hipError_t he = hipMalloc((void**)&ix->Bp, (size_t)n * ix->r_pad);
+            if (he != hipSuccess) { (void)hipFree(Braw); return fail(LORANN_E_NOMEM, "hipMalloc of padded codes failed"); }
+            const int64_t tot = n * ix->r_pad;
+            hipLaunchKernelGGL(k_pad_codes, dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, 0, Braw, ix->Bp, n, r, ix->r_pad);
+            he = hipDeviceSynchronize();
+            (void)hipFree(Braw);
+            if (he != hipSuccess) return fail(LORANN_E_DEVICE, "padding the codes failed: %s", hipGetErrorString(he));
+        }
+        if (P) {
+            float* Praw = nullptr;
+            if ((e = dev_copy(&Praw, P, (size_t)d * dp))) return e;
+            hipError_t he = hipMalloc((void**)&ix->Pt, (size_t)d * dp * 4);
+            if (he != hipSuccess) { (void)hipFree(Praw); return fail(LORANN_E_NOMEM, "hipMalloc of the projection failed"); }
+            const int64_t tot = (int64_t)d * dp;
+            hipLaunchKernelGGL(k_transpose, dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, 0, Praw, ix->Pt, d, dp);
+            he = hipDeviceSynchronize();
+            (void)hipFree(Praw);
+            if (he != hipSuccess) return fail(LORANN_E_DEVICE, "transposing the projection failed: %s", hipGetErrorString(he));
+        }
+        if (metric == LORANN_L2) {   // Sec. 3.1: the norms |c_j|^2 (and |mu_l|^2 for routing) are precomputed
+            HIP_TRY(hipMalloc((void**)&ix->sqnorm, (size_t)n * 4));
+            HIP_TRY(hipMalloc((void**)&ix->cent_sqnorm, (size_t)L * 8));
+            hipLaunchKernelGGL(k_row_sqnorm<float>, dim3((unsigned)((n + 3) / 4)), dim3(256), 0, 0, ix->corpus, ix->sqnorm, n, d);
+            hipLaunchKernelGGL(k_row_sqnorm<double>, dim3((unsigned)((L + 3) / 4)), dim3(256), 0, 0, ix->centroids, ix->cent_sqnorm, (int64_t)L, dp);
+            HIP_TRY(hipDeviceSynchronize());
+        }
+        return LORANN_OK;
+    };
+    rc = body();
+    if (rc != LORANN_OK) { std::string keep = g_err; free_all(ix); g_err = keep; return rc; }
+    *out = ix;
+    return LORANN_OK;
+}
+
+void lorann_free_index(lorann_index* ix) {
+    if (!ix) return;
+    (void)hipStreamSynchronize(ix->stream);
+    free_all(ix);
+}
+
+int lorann_set_stream(lorann_index* ix, void* hip_stream) {
+    if (!ix) return fail(LORANN_E_INVAL, "index is NULL");
+    HIP_TRY(hipStreamSynchronize(ix->stream));
+    ix->stream = reinterpret_cast<hipStream_t>(hip_stream);
+    return LORANN_OK;
+}
+
+int lorann_search(lorann_index* ix, const float* queries, int64_t nq, int32_t k, int32_t w, int32_t m, int64_t* out_ids,
+                  float* out_dists) {
+    return search_impl(ix, queries, nq, k, w, m, out_ids, out_dists, nullptr);
+}
+
+int lorann_search_stages(lorann_index* ix, const float* queries, int64_t nq, int32_t k, int32_t w, int32_t m,
+                         int64_t* out_ids, float* out_dists, const lorann_stages* st) {
+    return search_impl(ix, queries, nq, k, w, m, out_ids, out_dists, st);
+}
+
+int lorann_profile_enable(lorann_index* ix, int32_t on) {
+    if (!ix) return fail(LORANN_E_INVAL, "index is NULL");
+    HIP_TRY(hipStreamSynchronize(ix->stream));
+    prof_collect(ix);
+    ix->prof_on = on != 0;
+    if (on) for (int i = 0; i < K_COUNT; ++i) { ix->prof_ms[i] = 0.0; ix->prof_launches[i] = 0; }
+    return LORANN_OK;
+}
+
+int lorann_profile_get(lorann_index* ix, lorann_kernel_time* out, int32_t cap) {
+    if (!ix) return fail(LORANN_E_INVAL, "index is NULL");
+    if (cap > 0 && !out) return fail(LORANN_E_INVAL, "out is NULL");
+    for (int i = 0; i < K_COUNT && i < cap; ++i) {
+        memset(out[i].name, 0, sizeof out[i].name);
+        strncpy(out[i].name, kKernelNames[i], sizeof out[i].name - 1);
+        out[i].ms = ix->prof_ms[i];
+        out[i].launches = ix->prof_launches[i];
+    }
+    return K_COUNT;
+}
+
+}  // extern "C"

@@ -1,0 +1,172 @@
+// Routing-side kernels: absmax quantization of the projected queries (Sec. 3.3), selection of the w nearest
+// centroids per query (Sec. 2.2), and the counting sort that groups (query, cluster) pairs by cluster so that
+// each cluster's factors are read once per batch.
+#pragma once
+#include "common.hpp"
+
+namespace lorann {
+
+// ---- Sec. 3.3: x_i8 = round(c_x x), c_x = 127 / |x|_inf; step size Delta_x = |x|_inf / 127. ----
+// One wavefront per query row; block = 256 (4 rows).  Round-half-to-even, codes clamped to [-127, 127];
+// a zero row gives zero codes and step 0.  The quotients are formed in double and rounded once, which equals
+// IEEE float division.
+__global__ __launch_bounds__(256) void k_quantize_rows(const float* __restrict__ qp, int8_t* __restrict__ q8,
+                                                        float* __restrict__ dx, int nq, int dp) {
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= nq) return;
+    const float* p = qp + (size_t)row * dp;
+    float a = 0.0f;
+    for (int i = lane; i < dp; i += 64) a = fmaxf(a, fabsf(p[i]));
+    a = wave_max_f32(a);
+    int8_t* o = q8 + (size_t)row * dp;
+    if (!(a > 0.0f)) {
+        for (int i = lane; i < dp; i += 64) o[i] = 0;
+        if (lane == 0) dx[row] = 0.0f;
+        return;
+    }
+    const float cx = (float)(127.0 / (double)a);
+    for (int i = lane; i < dp; i += 64) {
+        int v = (int)rintf(__fmul_rn(p[i], cx));
+        v = max(-127, min(127, v));
+        o[i] = (int8_t)v;
+    }
+    if (lane == 0) dx[row] = (float)((double)a / 127.0);
+}
+
+// ---- Sec. 2.2: tau(x) = the w centroids of smallest dissimilarity. ----
+// One block (256 threads) per query.  g [nq][L] holds the centroid dissimilarities.  Exact selection by a
+// 4-pass radix select on order-preserving keys, ties at the threshold resolved toward the lower cluster id;
+// the result is written ordered (dissimilarity ascending, cluster id ascending) and every selected cluster's
+// pair counter is incremented (first step of the counting sort).
+__global__ __launch_bounds__(256) void k_select_clusters(const float* __restrict__ g, int L, int w,
+                                                          int32_t* __restrict__ sel, int32_t* __restrict__ count) {
+    __shared__ int hist[256];
+    __shared__ int wsum[4];
+    __shared__ uint32_t s_prefix;
+    __shared__ int s_need;
+    __shared__ uint32_t selk[256];
+    __shared__ int seli[256];
+    __shared__ int s_nless;
+    const int tid = threadIdx.x;
+    const float* row = g + (size_t)blockIdx.x * L;
+
+    if (tid == 0) { s_prefix = 0u; s_need = w; s_nless = 0; }
+    uint32_t mask = 0u;
+    for (int shift = 24; shift >= 0; shift -= 8) {
+        hist[tid] = 0;
+        __syncthreads();
+        const uint32_t prefix = s_prefix;
+        for (int l = tid; l < L; l += 256) {
+            const uint32_t key = float_key_asc(row[l]);
+            if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1);
+        }
+        __syncthreads();
+        if (tid < 64) {   // first wavefront: find the digit where the ascending cumulative count reaches need
+            const int need = s_need;
+            const int h0 = hist[4 * tid], h1 = hist[4 * tid + 1], h2 = hist[4 * tid + 2], h3 = hist[4 * tid + 3];
+            const int mine = h0 + h1 + h2 + h3;
+            int incl = mine;
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) { const int t = __shfl_up(incl, o, 64); if (tid >= o) incl += t; }
+            const int excl = incl - mine;
+            if (excl < need && incl >= need) {
+                int cum = excl, dgt = 4 * tid;
+                if (cum + h0 >= need) { dgt += 0; }
+                else { cum += h0; if (cum + h1 >= need) { dgt += 1; } else { cum += h1; if (cum + h2 >= need) { dgt += 2; } else { cum += h2; dgt += 3; } } }
+                s_prefix = prefix | ((uint32_t)dgt << shift);
+                s_need = need - cum;      // still to take among keys with this longer prefix
+            }
+        }
+        mask |= 255u << shift;
+        __syncthreads();
+    }
+    // s_prefix = key of the w-th smallest; s_need of the keys equal to it are taken, lowest cluster id first.
+    const uint32_t T = s_prefix;
+    const int need_ties = s_need;
+    const int n_less = w - need_ties;
+    int tie_base = 0;
+    for (int l0 = 0; l0 < L; l0 += 256) {
+        const int l = l0 + tid;
+        uint32_t key = 0xFFFFFFFFu;
+        bool in = l < L;
+        if (in) key = float_key_asc(row[l]);
+        const bool less = in && key < T;
+        const bool tie = in && key == T;
+        if (less) { const int p = atomicAdd(&s_nless, 1); selk[p] = key; seli[p] = l; }
+        int tot;
+        const int rank = block_flag_scan<4>(tie, wsum, tot);
+        if (tie && tie_base + rank < need_ties) { selk[n_less + tie_base + rank] = key; seli[n_less + tie_base + rank] = l; }
+        tie_base += tot;
+    }
+    __syncthreads();
+    if (tid < w) {   // order the w selected by (key, id): rank by counting
+        const uint32_t k = selk[tid];
+        const int id = seli[tid];
+        int rank = 0;
+        for (int u = 0; u < w; ++u) {
+            const uint32_t ku = selk[u];
+            const int iu = seli[u];
+            rank += (ku < k || (ku == k && iu < id)) ? 1 : 0;
+        }
+        sel[(size_t)blockIdx.x * w + rank] = id;
+        atomicAdd(&count[id], 1);
+    }
+}
+
+// ---- Counting sort, step 2: exclusive scans over the clusters (single block of 1024 threads). ----
+// bucket_off[c]  = number of pairs routed to clusters < c           (bucket_off[L] = number of pairs)
+// tile_off[c]    = number of 16-pair tiles of clusters < c          (tile_off[L]   = number of tiles)
+// Also clears the scatter cursors.
+__global__ __launch_bounds__(1024) void k_scan_buckets(const int32_t* __restrict__ count, int L,
+                                                        int32_t* __restrict__ bucket_off, int32_t* __restrict__ tile_off,
+                                                        int32_t* __restrict__ cursor) {
+    __shared__ int sa[1024], sb[1024];
+    __shared__ int carry_a, carry_b;
+    const int tid = threadIdx.x;
+    if (tid == 0) { carry_a = 0; carry_b = 0; }
+    __syncthreads();
+    for (int c0 = 0; c0 < L; c0 += 1024) {
+        const int c = c0 + tid;
+        const int a = c < L ? count[c] : 0;
+        const int b = (a + 15) >> 4;
+        sa[tid] = a; sb[tid] = b;
+        __syncthreads();
+        for (int o = 1; o < 1024; o <<= 1) {
+            int ta = 0, tb = 0;
+            if (tid >= o) { ta = sa[tid - o]; tb = sb[tid - o]; }
+            __syncthreads();
+            sa[tid] += ta; sb[tid] += tb;
+            __syncthreads();
+        }
+        if (c < L) {
+            bucket_off[c] = carry_a + sa[tid] - a;
+            tile_off[c] = carry_b + sb[tid] - b;
+            cursor[c] = 0;
+        }
+        __syncthreads();
+        if (tid == 1023) { carry_a += sa[1023]; carry_b += sb[1023]; }
+        __syncthreads();
+    }
+    if (tid == 0) { bucket_off[L] = carry_a; tile_off[L] = carry_b; }
+}
+
+// ---- Counting sort, step 3: place every pair (slot = query * w + rank) into its cluster's bucket. ----
+// The order inside a bucket is arbitrary (atomic cursor); no result depends on it.
+__global__ __launch_bounds__(256) void k_scatter_pairs(const int32_t* __restrict__ sel, int64_t npairs,
+                                                        const int32_t* __restrict__ bucket_off, int32_t* __restrict__ cursor,
+                                                        int32_t* __restrict__ slot_of_pos, int32_t* __restrict__ pos_of_slot) {
+    const int64_t p = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (p >= npairs) return;
+    const int c = sel[p];
+    const int pos = bucket_off[c] + atomicAdd(&cursor[c], 1);
+    slot_of_pos[pos] = (int32_t)p;
+    pos_of_slot[p] = pos;
+}
+
+__global__ void k_zero_i32(int32_t* __restrict__ p, int64_t n) {
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t < n) p[t] = 0;
+}
+
+}  // namespace lorann

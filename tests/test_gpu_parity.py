@@ -1,0 +1,175 @@
+"""Parity of the HIP library against the CPU oracle on the same seeded inputs (needs an MI355X).
+
+Bars: integer stages (query codes, selected clusters, re-quantized vectors, int32 score accumulators,
+candidate sets) bit-exact; combined scales bit-exact (same double expression); re-rank distances within 1e-4
+relative; returned ids identical except at distance ties within 1e-5.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle as O
+from tests.parity_util import assert_topk_equal, y_offsets
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2410_18926_amd import binding
+    assert binding.LIB_PATH.exists(), "build the HIP library first (python -m paper_2410_18926_amd.build)"
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    return binding
+
+
+def _stagewise(B, wl, ix, queries, k=None, w=None, m=None, device_inputs=True):
+    a = ix.numpy()
+    k, w, m = k or wl.k, w or wl.w, m or wl.m
+    oix = O.OracleIndex(a)
+    o_ids, o_d, ost = O.search(oix, queries, k, w, m, stages=True)
+    src = ix.to("cuda") if device_inputs else ix.to("cpu")
+    gix = B.Index.from_arrays(src)
+    yo = y_offsets(ost["sel"], a["cluster_offsets"])
+    q_in = torch.from_numpy(queries).cuda() if device_inputs else queries
+    g_ids, g_d, gst = gix.search_stages(q_in, k, w, m, y_off=yo)
+    tag = wl.name
+    np.testing.assert_array_equal(gst["qproj"], ost["qproj"], err_msg=f"{tag}: projected queries")
+    np.testing.assert_array_equal(gst["q8"], ost["q8"], err_msg=f"{tag}: query codes")
+    np.testing.assert_array_equal(gst["dx"], ost["dx"], err_msg=f"{tag}: query step sizes")
+    np.testing.assert_array_equal(gst["sel"], ost["sel"], err_msg=f"{tag}: selected clusters")
+    np.testing.assert_array_equal(gst["z"], ost["z"], err_msg=f"{tag}: re-quantized vectors")
+    np.testing.assert_array_equal(gst["sigma"], ost["sigma"], err_msg=f"{tag}: pair scales")
+    # int32 score accumulators of every point of every selected cluster
+    nq = queries.shape[0]
+    y_ref = np.empty_like(gst["y"])
+    for s in range(nq * w):
+        qi, j = divmod(s, w)
+        c = int(ost["sel"][qi, j])
+        o0, o1 = int(a["cluster_offsets"][c]), int(a["cluster_offsets"][c + 1])
+        y_ref[yo[s]:yo[s + 1]] = O.pair_accumulators(ost["z"][qi, j], a["B"][o0:o1])
+    np.testing.assert_array_equal(gst["y"], y_ref, err_msg=f"{tag}: int32 score accumulators")
+    # candidate sets (the library returns them unordered)
+    np.testing.assert_array_equal(np.sort(gst["cand_rows"].astype(np.int64), axis=1), np.sort(ost["cand_rows"], axis=1),
+                                  err_msg=f"{tag}: candidate sets")
+    n_tie = assert_topk_equal(g_ids, g_d, o_ids, o_d, tag)
+    # plain entry point returns the same as the staged one; second call is bitwise identical (determinism)
+    p_ids, p_d = gix.search(q_in, k, w, m)
+    p_ids2, p_d2 = gix.search(q_in, k, w, m)
+    if device_inputs:
+        p_ids, p_d, p_ids2, p_d2 = (t.cpu().numpy() for t in (p_ids, p_d, p_ids2, p_d2))
+    np.testing.assert_array_equal(p_ids, g_ids)
+    np.testing.assert_array_equal(p_d, g_d)
+    np.testing.assert_array_equal(p_ids2, p_ids)
+    np.testing.assert_array_equal(p_d2, p_d)
+    gix.close()
+    return n_tie
+
+
+def test_small_workloads_stagewise(B, small_indexes):
+    """Four small configurations: Euclidean without projection, inner product and cosine with projection
+    (d not a multiple of the tile sizes, ragged clusters), heavy-tailed norms."""
+    for name, (wl, ix, corpus, queries) in small_indexes.items():
+        _stagewise(B, wl, ix, queries)
+
+
+def test_small_workloads_host_pointers(B, small_indexes):
+    wl, ix, corpus, queries = small_indexes["cos_P"]
+    _stagewise(B, wl, ix, queries, device_inputs=False)
+
+
+def test_tiny_config_stagewise(B):
+    """BASELINE config 1 (20 000 x 128, 64 clusters, r = 32, w = 8, m = 100, Euclidean), all 1000 queries."""
+    from paper_2410_18926_amd.synth import get_workload, make_dataset, build_index
+    wl = get_workload("tiny")
+    corpus, queries = make_dataset(wl)
+    ix = build_index(corpus, wl)
+    _stagewise(B, wl, ix, queries.numpy())
+
+
+@pytest.mark.parametrize("r,dp,d", [(8, 16, 30), (24, 48, 48), (48, 64, 100), (64, 128, 128), (16, 1024, 1024)])
+def test_rank_and_dimension_variants(B, r, dp, d):
+    """Ranks that need K padding on the matrix cores (24, 48), minimum and maximum d', d not a multiple of 4."""
+    from paper_2410_18926_amd.synth import make_dataset, build_index
+    from paper_2410_18926_amd.synth.workloads import Workload, IP
+    wl = Workload(f"v-r{r}-dp{dp}", 70 + r, n=1500, d=d, nq=33, G=6, alpha=1.0, normalize=True, lognormal_norms=None,
+                  metric=IP, L=7, dp=dp, r=r, w=3, m=37, n_train=800, w_train=3)
+    corpus, queries = make_dataset(wl)
+    ix = build_index(corpus, wl)
+    _stagewise(B, wl, ix, queries.numpy())
+
+
+def test_probe_everything_equals_exact_knn(B, small_indexes):
+    """w = L and m = n: the library must return the exact k-NN (checked against the oracle's brute force)."""
+    for name in ("l2_noP", "ip_P"):
+        wl, ix, corpus, queries = small_indexes[name]
+        a = ix.numpy()
+        gix = B.Index.from_arrays(ix.to("cuda"))
+        ids, d = gix.search(queries[:16], wl.k, wl.L, wl.n)
+        e_ids, e_d = O.exact_knn(a["corpus"], queries[:16], wl.metric, wl.k, ids=a["ids"])
+        assert_topk_equal(ids, d, e_ids, e_d, name)
+        gix.close()
+
+
+def test_edge_cases(B, small_indexes):
+    wl, ix, corpus, queries = small_indexes["l2_P_norms"]
+    a = ix.numpy()
+    oix = O.OracleIndex(a)
+    gix = B.Index.from_arrays(ix.to("cuda"))
+    # empty batch
+    ids, d = gix.search(np.zeros((0, wl.d), np.float32), 5, 2, 10)
+    assert ids.shape == (0, 5)
+    # single query, k == m, w == 1
+    for (k, w, m) in [(1, 1, 1), (7, 1, 7), (10, wl.L, 4096), (3, 2, 3)]:
+        o_ids, o_d = O.search(oix, queries[:3], k, w, m)
+        g_ids, g_d = gix.search(queries[:3], k, w, m)
+        assert_topk_equal(g_ids, g_d, o_ids, o_d, f"k={k} w={w} m={m}")
+    # zero query: all codes zero, all scores equal -> candidates are the lowest rows of the selected clusters
+    zq = np.zeros((2, wl.d), np.float32)
+    o_ids, o_d = O.search(oix, zq, 5, 3, 20)
+    g_ids, g_d = gix.search(zq, 5, 3, 20)
+    assert_topk_equal(g_ids, g_d, o_ids, o_d, "zero query")
+    # invalid arguments
+    for (k, w, m, code) in [(0, 1, 1, -1), (5, 1, 4, -1), (1, 0, 1, -1), (1, wl.L + 1, 1, -1), (1, 1, 5000, -4)]:
+        with pytest.raises(B.LorannError) as e:
+            gix.search(queries[:2], k, w, m)
+        assert e.value.code == code
+    gix.close()
+
+
+def test_empty_clusters_and_few_points(B):
+    """Clusters without points, fewer scored points than m and than k (padding with -1 / +inf)."""
+    rng = np.random.default_rng(5)
+    d, L, r = 16, 5, 8
+    corpus = rng.normal(size=(9, d)).astype(np.float32)
+    ix = dict(metric=0, n=9, d=d, dp=d, r=r, L=L, centroids=rng.normal(size=(L, d)).astype(np.float32), P=None,
+              A=rng.integers(-127, 128, size=(L, r, d)).astype(np.int8), B=rng.integers(-127, 128, size=(9, r)).astype(np.int8),
+              scale_A=rng.uniform(0.01, 0.1, L).astype(np.float32), scale_B=rng.uniform(0.01, 0.1, L).astype(np.float32),
+              cluster_offsets=np.array([0, 0, 4, 4, 4, 9], np.int64), corpus=corpus, ids=np.arange(100, 109, dtype=np.int64))
+    q = rng.normal(size=(6, d)).astype(np.float32)
+    gix = B.Index(**ix)
+    oix = O.OracleIndex(ix)
+    for (k, w, m) in [(4, 5, 30), (12, 5, 30), (3, 2, 5), (2, 1, 2)]:
+        o_ids, o_d = O.search(oix, q, k, w, m)
+        g_ids, g_d = gix.search(q, k, w, m)
+        assert_topk_equal(g_ids, g_d, o_ids, o_d, f"k={k} w={w} m={m}")
+    gix.close()
+
+
+def test_score_ties_resolve_to_lower_rows(B):
+    """Many equal estimated scores (duplicate codes): the candidate set must take the lower rows."""
+    rng = np.random.default_rng(9)
+    d, L, r, n = 16, 3, 8, 600
+    corpus = rng.normal(size=(n, d)).astype(np.float32)
+    codes = rng.integers(-3, 4, size=(n, r)).astype(np.int8)          # tiny alphabet => massive score ties
+    ix = dict(metric=0, n=n, d=d, dp=d, r=r, L=L, centroids=rng.normal(size=(L, d)).astype(np.float32), P=None,
+              A=rng.integers(-127, 128, size=(L, r, d)).astype(np.int8), B=codes,
+              scale_A=np.full(L, 0.01, np.float32), scale_B=np.full(L, 0.02, np.float32),
+              cluster_offsets=np.array([0, 250, 400, n], np.int64), corpus=corpus, ids=None)
+    q = rng.normal(size=(20, d)).astype(np.float32)
+    gix = B.Index(**ix)
+    oix = O.OracleIndex(ix)
+    o_ids, o_d, ost = O.search(oix, q, 10, 3, 64, stages=True)
+    g_ids, g_d, gst = gix.search_stages(q, 10, 3, 64)
+    np.testing.assert_array_equal(np.sort(gst["cand_rows"].astype(np.int64), axis=1), np.sort(ost["cand_rows"], axis=1))
+    assert_topk_equal(g_ids, g_d, o_ids, o_d, "ties")
+    gix.close()
