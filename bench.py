@@ -1,0 +1,203 @@
+#!/usr/bin/env python3
+"""Benchmark of the LoRANN query phase on one MI355X.
+
+A "step" is one lorann_search call over one batch of synthetic queries (all stages: projection, routing,
+int8 scoring, top-m, exact re-rank), with index, queries and outputs resident in HBM.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload embed-ip]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
+PEAK_FP64_MFMA_TFLOPS = 78.6
+PEAK_INT8_MFMA_TOPS = 5000.0
+PEAK_VALU_LANE_TOPS = 256 * 64 * 2.4e9 / 1e12   # 256 CUs x 64 lanes x 2.4 GHz = 39.3 T lane-ops/s
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def recall_at_k(ids, dists, gt_dists):
+    """Fraction of returned points that are true k-NN; a returned point counts when its exact distance does
+    not exceed the k-th true distance (tolerance 1e-5 relative), so ties are not punished."""
+    kth = gt_dists[:, -1:].astype(np.float64)
+    ok = (dists.astype(np.float64) <= kth + 1e-5 * np.abs(kth)) & (ids >= 0)
+    return float(ok.mean())
+
+
+def kernel_models(wl, nq, touched_rows, npairs):
+    """Algorithmic work of one launch of each kernel: (bound, amount, unit-peak)."""
+    d, dp, r, L, m = wl.d, wl.dp, wl.r, wl.L, wl.m
+    return {
+        "project_f64": ("mfma", 2.0 * nq * d * dp / 1e12, PEAK_FP64_MFMA_TFLOPS, "TFLOP/s"),
+        "centroid_dissim_f64": ("mfma", 2.0 * nq * dp * L / 1e12, PEAK_FP64_MFMA_TFLOPS, "TFLOP/s"),
+        "quantize_rows": ("hbm", nq * dp * 5 / 1e9, PEAK_HBM_GBS, "GB/s"),
+        "select_clusters": ("hbm", nq * L * 4 / 1e9, PEAK_HBM_GBS, "GB/s"),
+        "scatter_pairs": ("hbm", npairs * 12 / 1e9, PEAK_HBM_GBS, "GB/s"),
+        "stage_a_i8": ("hbm", (L * dp * r + npairs * (dp + r + 4)) / 1e9, PEAK_HBM_GBS, "GB/s"),
+        # B_c scoring: every touched code once + the pairs' z / sigma (+ |c|^2 for Euclidean)
+        "score_select_exact": ("hbm", (touched_rows * (r + (4 if wl.metric == 1 else 0)) + npairs * (r + 4)) / 1e9,
+                               PEAK_HBM_GBS, "GB/s"),
+        "rerank": ("hbm", nq * m * d * 4 / 1e9, PEAK_HBM_GBS, "GB/s"),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="embed-ip")
+    ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (development only)")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target duration of the oracle baseline")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (query-sharded data parallelism would "
+              "replicate the index and split the batch); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2410_18926_amd import binding
+    from paper_2410_18926_amd.synth import get_workload, make_dataset, build_index
+    from paper_2410_18926_amd.synth.data import brute_force_topk
+
+    if not torch.cuda.is_available():
+        print("bench.py needs the GPU (no CPU fallback exists for the search)", file=sys.stderr)
+        sys.exit(2)
+    binding.lib()
+    dev = torch.device("cuda:0")
+    wl = get_workload(args.workload)
+    if args.scale != 1.0:
+        wl = wl.scaled(args.scale)
+    K, W = args.steps, args.warmup
+
+    t0 = time.time()
+    nb = max(1, min(K + W, 8))
+    corpus, queries, extra = make_dataset(wl, dev, extra_batches=nb - 1) if nb > 1 else (*make_dataset(wl, dev), [])
+    batches = [queries] + list(extra)
+    torch.cuda.synchronize()
+    log(f"[bench] data {wl.name}: corpus {tuple(corpus.shape)}, {nb} batches of {wl.nq} queries in {time.time() - t0:.1f}s")
+    t0 = time.time()
+    ix = build_index(corpus, wl, progress=lambda s: log(f"[bench]   index: {s}"))
+    torch.cuda.synchronize()
+    build_s = time.time() - t0
+    log(f"[bench] index built in {build_s:.1f}s")
+    gt_ids, gt_d = brute_force_topk(corpus, queries, wl.metric, wl.k)
+    gt_d = gt_d.cpu().numpy()
+    del corpus
+
+    gix = binding.Index.from_arrays(ix)
+    gix.use_torch_stream()
+    nq, k, w, m = wl.nq, wl.k, min(wl.w, wl.L), wl.m
+    out = (torch.empty((nq, k), dtype=torch.int64, device=dev), torch.empty((nq, k), dtype=torch.float32, device=dev))
+
+    for s in range(W):
+        gix.search(batches[s % nb], k, w, m, out=out)
+    torch.cuda.synchronize()
+    gix.profile_enable(True)
+    t0 = time.perf_counter()
+    for s in range(K):
+        gix.search(batches[(W + s) % nb], k, w, m, out=out)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    prof = gix.profile_get()
+    gix.profile_enable(False)
+    # the same loop without per-kernel events, to show what the events cost
+    t0 = time.perf_counter()
+    for s in range(K):
+        gix.search(batches[(W + s) % nb], k, w, m, out=out)
+    torch.cuda.synchronize()
+    elapsed_noprof = time.perf_counter() - t0
+
+    ids, dists = gix.search(queries, k, w, m)
+    ids_h, dists_h = ids.cpu().numpy(), dists.cpu().numpy()
+    recall = recall_at_k(ids_h, dists_h, gt_d)
+    # map returned ids (original corpus indices) check: true top-k ids overlap, as a second recall definition
+    gt_ids_h = gt_ids.cpu().numpy()
+    recall_ids = float(np.mean([len(set(ids_h[i]) & set(gt_ids_h[i])) / k for i in range(0, nq, max(1, nq // 2000))]))
+
+    # per-kernel roofline figures from the events recorded over the timed region
+    sizes = (ix.cluster_offsets[1:] - ix.cluster_offsets[:-1]).cpu().numpy()
+    # clusters touched by the batch (their codes are what the scoring kernel has to read at least once)
+    sel_all = gix.search_stages(queries[:20000], k, w, m)[2]["sel"]
+    touched = np.zeros(wl.L, bool)
+    touched[np.unique(sel_all)] = True
+    touched_rows = int(sizes[touched].sum())
+    models = kernel_models(wl, nq, touched_rows, nq * w)
+    kernels = []
+    for name, (ms, launches) in prof.items():
+        if launches == 0:
+            continue
+        avg_ms = ms / launches
+        ent = {"kernel": name, "avg_ms": round(avg_ms, 5), "launches_per_step": launches / K}
+        if name in models:
+            bound, amount, peak, unit = models[name]
+            ach = amount / (avg_ms / 1e3)
+            ent.update({"bound": bound, "achieved": round(ach, 3), "peak": peak, "unit": unit, "frac": round(ach / peak, 4)})
+        kernels.append(ent)
+    kernels.sort(key=lambda e: -e["avg_ms"])
+    dom = next((e for e in kernels if "bound" in e), None)
+    roofline = None
+    if dom:
+        roofline = {"kernel": dom["kernel"], "bound": dom["bound"], "achieved": dom["achieved"], "peak": dom["peak"],
+                    "unit": dom["unit"], "frac": dom["frac"], "traffic": None}
+
+    cpu_baseline = None
+    oracle_match = None
+    if not args.no_cpu_baseline:
+        from oracle import oracle as O
+        t0 = time.time()
+        a = ix.numpy()
+        oix = O.OracleIndex(a)
+        qh = queries.cpu().numpy()
+        threads = O.default_threads()
+        O.search(oix, qh[:threads * 2], k, w, m, threads=threads)            # warm pass
+        t1 = time.perf_counter()
+        n_cal = min(nq, threads * 8)
+        O.search(oix, qh[:n_cal], k, w, m, threads=threads)
+        rate = n_cal / (time.perf_counter() - t1)
+        n_s = int(max(n_cal, min(nq, rate * args.cpu_seconds)))
+        t1 = time.perf_counter()
+        o_ids, o_d = O.search(oix, qh[:n_s], k, w, m, threads=threads)
+        dt = time.perf_counter() - t1
+        cpu_baseline = {"value": round(n_s / dt, 1), "unit": "queries/s", "cores": threads, "kind": "oracle",
+                        "sample": f"first {n_s} of the {nq} queries of the timed batch shape, same index, one pass of {dt:.1f}s"}
+        oracle_match = {"queries": n_s, "id_lists_identical": float(np.mean(np.all(o_ids == ids_h[:n_s], axis=1))),
+                        "ids_equal": float(np.mean(o_ids == ids_h[:n_s])),
+                        "max_rel_dist_err": float(np.max(np.abs(o_d - dists_h[:n_s]) / np.maximum(np.abs(o_d), 1e-3)))}
+        log(f"[bench] oracle baseline done in {time.time() - t0:.1f}s")
+
+    metric_names = {0: "inner product", 1: "squared Euclidean", 2: "cosine"}
+    res = {
+        "metric": "queries/sec at recall@10>=0.9 (1 MI355X, batch 10k)",
+        "value": round(nq * K / elapsed, 1),
+        "unit": "queries/s",
+        "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": round(elapsed / K * 1e3, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int8", "data": "synthetic",
+        "config": {"workload": f"{wl.name}: corpus {wl.n}x{wl.d} fp32, {wl.G}-component anisotropic Gaussian mixture, "
+                               f"{metric_names[wl.metric]}, L={wl.L} clusters, d'={wl.dp}, r={wl.r} int8, batch {nq}, "
+                               f"w={w}, m={m}, k={k}",
+                   "n": wl.n, "d": wl.d, "batch": nq, "L": wl.L, "dp": wl.dp, "r": wl.r, "w": w, "m": m, "k": k},
+        "recall_at_10": round(recall, 4), "recall_at_10_by_id": round(recall_ids, 4),
+        "roofline": roofline, "cpu_baseline": cpu_baseline,
+        "kernels": kernels, "oracle_match": oracle_match,
+        "ms_per_step_without_kernel_events": round(elapsed_noprof / K * 1e3, 4),
+        "index_build_s": round(build_s, 1),
+    }
+    print(json.dumps(res), flush=True)
+
+
+if __name__ == "__main__":
+    main()

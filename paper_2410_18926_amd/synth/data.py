@@ -71,8 +71,11 @@ class _Mixture:
         return out
 
 
-def make_dataset(wl: Workload, device: str | torch.device = "cpu", nq: int | None = None):
+def make_dataset(wl: Workload, device: str | torch.device = "cpu", nq: int | None = None, extra_batches: int = 0):
     """Return (corpus [n, d] fp32, queries [nq, d] fp32) on `device` for workload `wl`.
+
+    With extra_batches > 0 a third value is returned: a list of further, distinct query batches of the same
+    size (independent streams), for timing loops that must not repeat a batch.
 
     The values depend on the device type (torch's CPU and GPU generators are different streams); a given
     device type always reproduces the same arrays.
@@ -80,8 +83,12 @@ def make_dataset(wl: Workload, device: str | torch.device = "cpu", nq: int | Non
     device = torch.device(device)
     mix = _Mixture(wl, device)
     corpus = mix.draw(wl.n, _STREAM_CORPUS)
-    queries = mix.draw(wl.nq if nq is None else nq, _STREAM_QUERIES)
-    return corpus, queries
+    count = wl.nq if nq is None else nq
+    queries = mix.draw(count, _STREAM_QUERIES)
+    if extra_batches <= 0:
+        return corpus, queries
+    extra = [mix.draw(count, _STREAM_QUERIES + 1 + b) for b in range(extra_batches)]
+    return corpus, queries, extra
 
 
 def brute_force_topk(corpus: torch.Tensor, queries: torch.Tensor, metric: int, k: int, chunk: int = 2048):
