@@ -37,6 +37,7 @@ def recall_at_k(ids, dists, gt_dists):
 def kernel_models(wl, nq, touched_rows, npairs):
     """Algorithmic work of one launch of each kernel: (bound, amount, unit-peak)."""
     d, dp, r, L, m = wl.d, wl.dp, wl.r, wl.L, wl.m
+    b_bytes = touched_rows * (r + (4 if wl.metric == 1 else 0)) + npairs * (r + 4)
     return {
         "project_f64": ("mfma", 2.0 * nq * d * dp / 1e12, PEAK_FP64_MFMA_TFLOPS, "TFLOP/s"),
         "centroid_dissim_f64": ("mfma", 2.0 * nq * dp * L / 1e12, PEAK_FP64_MFMA_TFLOPS, "TFLOP/s"),
@@ -44,9 +45,10 @@ def kernel_models(wl, nq, touched_rows, npairs):
         "select_clusters": ("hbm", nq * L * 4 / 1e9, PEAK_HBM_GBS, "GB/s"),
         "scatter_pairs": ("hbm", npairs * 12 / 1e9, PEAK_HBM_GBS, "GB/s"),
         "stage_a_i8": ("hbm", (L * dp * r + npairs * (dp + r + 4)) / 1e9, PEAK_HBM_GBS, "GB/s"),
-        # B_c scoring: every touched code once + the pairs' z / sigma (+ |c|^2 for Euclidean)
-        "score_select_exact": ("hbm", (touched_rows * (r + (4 if wl.metric == 1 else 0)) + npairs * (r + 4)) / 1e9,
-                               PEAK_HBM_GBS, "GB/s"),
+        # B_c scoring (each of the two passes): every touched code once + the pairs' z / sigma (+ |c|^2 for Euclidean)
+        "score_bound_i8": ("hbm", b_bytes / 1e9, PEAK_HBM_GBS, "GB/s"),
+        "score_filter_i8": ("hbm", b_bytes / 1e9, PEAK_HBM_GBS, "GB/s"),
+        "score_select_exact": ("hbm", b_bytes / 1e9, PEAK_HBM_GBS, "GB/s"),
         "rerank": ("hbm", nq * m * d * 4 / 1e9, PEAK_HBM_GBS, "GB/s"),
     }
 

@@ -105,6 +105,11 @@ const char *lorann_last_error(void);
  * index.  NULL selects the null stream.  The stream must stay valid while the index uses it. */
 int lorann_set_stream(lorann_index *ix, void *hip_stream);
 
+/* Candidate selection normally runs batched by cluster (each cluster's codes are read once per batch) and
+ * hands the rare queries it cannot finish to an exact per-query kernel.  on != 0 makes every query take the
+ * per-query kernel (same results, much slower); used to verify one path against the other. */
+int lorann_set_exact_selection(lorann_index *ix, int32_t on);
+
 /*
  * Intermediate results of one search, for verification against a reference implementation.  Every pointer
  * may be NULL (skipped) and may be a host or device pointer.  Layouts, with slot = query * w + rank:

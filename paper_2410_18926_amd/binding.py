@@ -22,7 +22,7 @@ LORANN_IP, LORANN_L2, LORANN_COS = 0, 1, 2
 LORANN_OK, LORANN_E_INVAL, LORANN_E_NOMEM, LORANN_E_DEVICE, LORANN_E_UNSUPPORTED = 0, -1, -2, -3, -4
 
 EXPORTS = ["lorann_load_index", "lorann_search", "lorann_free_index", "lorann_last_error", "lorann_set_stream",
-           "lorann_search_stages", "lorann_profile_enable", "lorann_profile_get"]
+           "lorann_search_stages", "lorann_profile_enable", "lorann_profile_get", "lorann_set_exact_selection"]
 
 
 class LorannError(RuntimeError):
@@ -61,6 +61,8 @@ def lib() -> C.CDLL:
         L.lorann_last_error.restype = C.c_char_p
         L.lorann_set_stream.restype = C.c_int
         L.lorann_set_stream.argtypes = [vp, vp]
+        L.lorann_set_exact_selection.restype = C.c_int
+        L.lorann_set_exact_selection.argtypes = [vp, i32]
         L.lorann_profile_enable.restype = C.c_int
         L.lorann_profile_enable.argtypes = [vp, i32]
         L.lorann_profile_get.restype = C.c_int
@@ -173,6 +175,9 @@ class Index:
             cs.y_off, cs.y = y_off.ctypes.data, st["y"].ctypes.data
         _check(lib().lorann_search_stages(self._h, qptr, nq, k, w, m, ids.ctypes.data, dists.ctypes.data, C.byref(cs)))
         return ids, dists, st
+
+    def set_exact_selection(self, on: bool):
+        _check(lib().lorann_set_exact_selection(self._h, 1 if on else 0))
 
     def profile_enable(self, on: bool = True):
         _check(lib().lorann_profile_enable(self._h, 1 if on else 0))

@@ -18,7 +18,9 @@
 #include "gemm_f64.hpp"
 #include "rerank.hpp"
 #include "route.hpp"
+#include "score_mfma.hpp"
 #include "select_exact.hpp"
+#include "select_final.hpp"
 #include "stage_a.hpp"
 
 using namespace lorann;
@@ -72,9 +74,10 @@ struct DevBuf {
     template <typename T> T* as() const { return reinterpret_cast<T*>(p); }
 };
 
-enum KernelId { K_PROJECT, K_QUANTIZE, K_CENTROID, K_SELECT_W, K_SCAN, K_SCATTER, K_STAGE_A, K_SELECT_M, K_RERANK, K_ZERO, K_COUNT };
+enum KernelId { K_PROJECT, K_QUANTIZE, K_CENTROID, K_SELECT_W, K_SCAN, K_SCATTER, K_STAGE_A, K_SCORE_BOUND, K_QUERY_BOUND, K_SCORE_FILTER, K_SELECT_FINAL, K_SELECT_M, K_RERANK, K_ZERO, K_COUNT };
 const char* const kKernelNames[K_COUNT] = {"project_f64", "quantize_rows", "centroid_dissim_f64", "select_clusters",
-                                            "scan_buckets", "scatter_pairs", "stage_a_i8", "score_select_exact",
+                                            "scan_buckets", "scatter_pairs", "stage_a_i8", "score_bound_i8",
+                                            "query_bound", "score_filter_i8", "select_final", "score_select_exact",
                                             "rerank", "zero_counters"};
 
 struct EventPair { hipEvent_t a, b; int kid; };
@@ -97,7 +100,9 @@ struct lorann_index {
     int64_t* ids = nullptr;         // [n] or NULL
     float* sqnorm = nullptr;        // [n] (Euclidean)
     // workspace (device), sized for `chunk` queries
-    DevBuf qproj, q8, dx, gscore, sel, count, cursor, bucket_off, tile_off, slot_of_pos, pos_of_slot, Z, sigma, cand;
+    DevBuf qproj, q8, dx, gscore, sel, count, cursor, bucket_off, tile_off, unit_off, slot_of_pos, pos_of_slot, Z, sigma, cand;
+    DevBuf pmax, tau, surv_cnt, surv_score, surv_row, fb_list;
+    int32_t force_exact = 0;        // 1: score + select with the per-query kernel only (verification)
     DevBuf stage_q, stage_ids, stage_dists;   // staging when the caller passes host memory
     // profiling
     bool prof_on = false;
@@ -112,7 +117,8 @@ void free_all(lorann_index* ix) {
     void* ptrs[] = {ix->centroids, ix->cent_sqnorm, ix->Pt, ix->A, ix->Bp, ix->sA, ix->sB, ix->off, ix->corpus, ix->ids, ix->sqnorm};
     for (void* p : ptrs) if (p) (void)hipFree(p);
     DevBuf* bufs[] = {&ix->qproj, &ix->q8, &ix->dx, &ix->gscore, &ix->sel, &ix->count, &ix->cursor, &ix->bucket_off, &ix->tile_off,
-                      &ix->slot_of_pos, &ix->pos_of_slot, &ix->Z, &ix->sigma, &ix->cand, &ix->stage_q, &ix->stage_ids, &ix->stage_dists};
+                      &ix->unit_off, &ix->slot_of_pos, &ix->pos_of_slot, &ix->Z, &ix->sigma, &ix->cand, &ix->pmax, &ix->tau,
+                      &ix->surv_cnt, &ix->surv_score, &ix->surv_row, &ix->fb_list, &ix->stage_q, &ix->stage_ids, &ix->stage_dists};
     for (DevBuf* b : bufs) b->release();
     for (auto& e : ix->ev_used) { (void)hipEventDestroy(e.a); (void)hipEventDestroy(e.b); }
     for (auto& e : ix->ev_free) { (void)hipEventDestroy(e.a); (void)hipEventDestroy(e.b); }
@@ -161,6 +167,9 @@ void prof_collect(lorann_index* ix) {   // the stream has been synchronised
 
 int next_pow2(int v) { int p = 1; while (p < v) p <<= 1; return p; }
 
+constexpr int kNZ = 2;                 // 32-pair tiles per scoring unit
+constexpr int kUnitPairs = 32 * kNZ;
+
 // One batch of at most `chunk` queries, device pointers only.
 int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, int m, int64_t* d_ids, float* d_dists,
                  const lorann_stages* st, int64_t q_base) {
@@ -173,10 +182,11 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
     if ((rc = ix->dx.reserve((size_t)nq * 4))) return rc;
     if ((rc = ix->gscore.reserve((size_t)nq * L * 4))) return rc;
     if ((rc = ix->sel.reserve((size_t)npairs * 4))) return rc;
-    if ((rc = ix->count.reserve((size_t)L * 4))) return rc;
+    if ((rc = ix->count.reserve((size_t)(L + 1) * 4))) return rc;   // [L] pair counters + the fallback-list counter
     if ((rc = ix->cursor.reserve((size_t)L * 4))) return rc;
     if ((rc = ix->bucket_off.reserve((size_t)(L + 1) * 4))) return rc;
     if ((rc = ix->tile_off.reserve((size_t)(L + 1) * 4))) return rc;
+    if ((rc = ix->unit_off.reserve((size_t)(L + 1) * 4))) return rc;
     if ((rc = ix->slot_of_pos.reserve((size_t)npairs * 4))) return rc;
     if ((rc = ix->pos_of_slot.reserve((size_t)npairs * 4))) return rc;
     if ((rc = ix->Z.reserve((size_t)npairs * r_pad))) return rc;
@@ -192,7 +202,7 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
     }
     {
         Prof p(ix, K_ZERO);
-        hipLaunchKernelGGL(k_zero_i32, dim3((L + 255) / 256), dim3(256), 0, s, ix->count.as<int32_t>(), (int64_t)L);
+        hipLaunchKernelGGL(k_zero_i32, dim3((L + 256) / 256), dim3(256), 0, s, ix->count.as<int32_t>(), (int64_t)L + 1);
     }
     {
         Prof p(ix, K_QUANTIZE);
@@ -212,7 +222,8 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
     }
     {
         Prof p(ix, K_SCAN);
-        hipLaunchKernelGGL(k_scan_buckets, dim3(1), dim3(1024), 0, s, ix->count.as<int32_t>(), L, ix->bucket_off.as<int32_t>(), ix->tile_off.as<int32_t>(), ix->cursor.as<int32_t>());
+        hipLaunchKernelGGL(k_scan_buckets, dim3(1), dim3(1024), 0, s, ix->count.as<int32_t>(), L, kUnitPairs, ix->bucket_off.as<int32_t>(), ix->tile_off.as<int32_t>(),
+                           ix->unit_off.as<int32_t>(), ix->cursor.as<int32_t>());
     }
     {
         Prof p(ix, K_SCATTER);
@@ -230,14 +241,68 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
             hipLaunchKernelGGL(k_stage_a<4>, grid, dim3(256), 0, s, ix->q8.as<int8_t>(), ix->dx.as<float>(), ix->A, ix->sA, ix->sB, ix->bucket_off.as<int32_t>(),
                                ix->tile_off.as<int32_t>(), ix->slot_of_pos.as<int32_t>(), L, dp, ix->r, w, ix->Z.as<int8_t>(), ix->sigma.as<float>());
     }
-    {
+    // Scores + candidate selection.  Batched path: bound pass -> per-query threshold -> filter pass -> exact
+    // selection among the survivors; the exact per-query kernel finishes what the batched path cannot.
+    SelectArgs sa_;
+    sa_.qlist = nullptr; sa_.qcount = nullptr; sa_.sel = ix->sel.as<int32_t>(); sa_.pos_of_slot = ix->pos_of_slot.as<int32_t>();
+    sa_.Z = ix->Z.as<int8_t>(); sa_.sigma = ix->sigma.as<float>(); sa_.Bp = ix->Bp; sa_.off = ix->off;
+    sa_.sqnorm = ix->metric == LORANN_L2 ? ix->sqnorm : nullptr; sa_.cand = ix->cand.as<int32_t>(); sa_.w = w; sa_.m = m;
+    const int G = (8 * (int64_t)w >= m) ? 4 : ((32 * (int64_t)w >= m) ? 16 : 0);   // subset maxima per lane; 2G per pair
+    if (G == 0 || ix->force_exact) {
         Prof p(ix, K_SELECT_M);
-        SelectArgs a;
-        a.qlist = nullptr; a.qcount = nullptr; a.sel = ix->sel.as<int32_t>(); a.pos_of_slot = ix->pos_of_slot.as<int32_t>();
-        a.Z = ix->Z.as<int8_t>(); a.sigma = ix->sigma.as<float>(); a.Bp = ix->Bp; a.off = ix->off;
-        a.sqnorm = ix->metric == LORANN_L2 ? ix->sqnorm : nullptr; a.cand = ix->cand.as<int32_t>(); a.w = w; a.m = m;
-        if (r_pad == 32) hipLaunchKernelGGL(k_select_exact<2>, dim3((unsigned)nq), dim3(256), 0, s, a);
-        else hipLaunchKernelGGL(k_select_exact<4>, dim3((unsigned)nq), dim3(256), 0, s, a);
+        const unsigned grid = (unsigned)std::min<int64_t>(nq, 65536);
+        if (r_pad == 32) hipLaunchKernelGGL(k_select_exact<2>, dim3(grid), dim3(256), 0, s, sa_, (int)nq);
+        else hipLaunchKernelGGL(k_select_exact<4>, dim3(grid), dim3(256), 0, s, sa_, (int)nq);
+    } else {
+        const int cap = std::min(4096, std::max(1024, next_pow2(4 * m)));
+        if ((rc = ix->pmax.reserve((size_t)npairs * 2 * G * 4))) return rc;
+        if ((rc = ix->tau.reserve((size_t)nq * 4))) return rc;
+        if ((rc = ix->surv_cnt.reserve((size_t)nq * 4))) return rc;
+        if ((rc = ix->surv_score.reserve((size_t)nq * cap * 4))) return rc;
+        if ((rc = ix->surv_row.reserve((size_t)nq * cap * 4))) return rc;
+        if ((rc = ix->fb_list.reserve((size_t)nq * 4))) return rc;
+        ScoreArgs sc;
+        sc.Bp = ix->Bp; sc.Z = ix->Z.as<int8_t>(); sc.sigma = ix->sigma.as<float>(); sc.off = ix->off;
+        sc.bucket_off = ix->bucket_off.as<int32_t>(); sc.unit_off = ix->unit_off.as<int32_t>(); sc.slot_of_pos = ix->slot_of_pos.as<int32_t>();
+        sc.sqnorm = ix->metric == LORANN_L2 ? ix->sqnorm : nullptr; sc.pmax = ix->pmax.as<float>(); sc.tau = ix->tau.as<float>();
+        sc.surv_cnt = ix->surv_cnt.as<int32_t>(); sc.surv_score = ix->surv_score.as<float>(); sc.surv_row = ix->surv_row.as<int32_t>();
+        sc.L = L; sc.w = w; sc.cap = cap;
+        const int64_t max_units = npairs / kUnitPairs + L + 1;
+        const dim3 ugrid((unsigned)((max_units + 3) / 4));
+        const bool l2 = ix->metric == LORANN_L2;
+        const int ks = r_pad / 32;
+        {
+            Prof p(ix, K_SCORE_BOUND);
+#define LAUNCH_BOUND(KS_, G_, L2_) hipLaunchKernelGGL((k_score_pass<kNZ, KS_, G_, false, L2_>), ugrid, dim3(256), 0, s, sc)
+            if (ks == 1) { if (G == 4) { if (l2) LAUNCH_BOUND(1, 4, true); else LAUNCH_BOUND(1, 4, false); } else { if (l2) LAUNCH_BOUND(1, 16, true); else LAUNCH_BOUND(1, 16, false); } }
+            else         { if (G == 4) { if (l2) LAUNCH_BOUND(2, 4, true); else LAUNCH_BOUND(2, 4, false); } else { if (l2) LAUNCH_BOUND(2, 16, true); else LAUNCH_BOUND(2, 16, false); } }
+#undef LAUNCH_BOUND
+        }
+        {
+            Prof p(ix, K_QUERY_BOUND);
+            hipLaunchKernelGGL(k_query_bound, dim3((unsigned)nq), dim3(256), (size_t)w * 2 * G * 4, s, ix->pmax.as<float>(), ix->pos_of_slot.as<int32_t>(), w, 2 * G, m,
+                               ix->tau.as<float>(), ix->surv_cnt.as<int32_t>());
+        }
+        {
+            Prof p(ix, K_SCORE_FILTER);
+#define LAUNCH_FILTER(KS_, L2_) hipLaunchKernelGGL((k_score_pass<kNZ, KS_, 4, true, L2_>), ugrid, dim3(256), 0, s, sc)
+            if (ks == 1) { if (l2) LAUNCH_FILTER(1, true); else LAUNCH_FILTER(1, false); }
+            else         { if (l2) LAUNCH_FILTER(2, true); else LAUNCH_FILTER(2, false); }
+#undef LAUNCH_FILTER
+        }
+        {
+            Prof p(ix, K_SELECT_FINAL);
+            hipLaunchKernelGGL(k_select_final, dim3((unsigned)nq), dim3(256), (size_t)cap * 12, s, ix->surv_score.as<float>(), ix->surv_row.as<int32_t>(),
+                               ix->surv_cnt.as<int32_t>(), ix->tau.as<float>(), cap, m, ix->cand.as<int32_t>(), ix->fb_list.as<int32_t>(),
+                               ix->count.as<int32_t>() + L);
+        }
+        {
+            Prof p(ix, K_SELECT_M);
+            sa_.qlist = ix->fb_list.as<int32_t>(); sa_.qcount = ix->count.as<int32_t>() + L;
+            const unsigned grid = (unsigned)std::min<int64_t>(nq, 1024);
+            if (r_pad == 32) hipLaunchKernelGGL(k_select_exact<2>, dim3(grid), dim3(256), 0, s, sa_, (int)nq);
+            else hipLaunchKernelGGL(k_select_exact<4>, dim3(grid), dim3(256), 0, s, sa_, (int)nq);
+        }
     }
     {
         Prof p(ix, K_RERANK);
@@ -371,6 +436,21 @@ int lorann_load_index(lorann_index** out, int32_t metric, int64_t n, int32_t d, 
     for (int c = 0; c < L; ++c)
         if (off[c + 1] < off[c]) return fail(LORANN_E_INVAL, "cluster_offsets decrease at cluster %d", c);
 
+    {   // absmax step sizes are non-negative by construction; the integer-domain score comparisons rely on it
+        std::vector<float> sc(2 * (size_t)L);
+        const float* src[2] = {scale_A, scale_B};
+        for (int t = 0; t < 2; ++t) {
+            if (is_device_ptr(src[t])) {
+                hipError_t e = hipMemcpy(sc.data() + (size_t)t * L, src[t], (size_t)L * 4, hipMemcpyDeviceToHost);
+                if (e != hipSuccess) { (void)hipGetLastError(); return fail(LORANN_E_DEVICE, "reading the scales failed: %s", hipGetErrorString(e)); }
+            } else {
+                memcpy(sc.data() + (size_t)t * L, src[t], (size_t)L * 4);
+            }
+        }
+        for (size_t i = 0; i < sc.size(); ++i)
+            if (!(sc[i] >= 0.0f) || sc[i] > 3.0e38f) return fail(LORANN_E_INVAL, "scale_%c[%zu] must be finite and >= 0", i < (size_t)L ? 'A' : 'B', i % L);
+    }
+
     int ndev = 0;
     if (hipGetDeviceCount(&ndev) != hipSuccess || ndev < 1) { (void)hipGetLastError(); return fail(LORANN_E_DEVICE, "no HIP device"); }
 
@@ -446,6 +526,12 @@ int lorann_search(lorann_index* ix, const float* queries, int64_t nq, int32_t k,
 int lorann_search_stages(lorann_index* ix, const float* queries, int64_t nq, int32_t k, int32_t w, int32_t m,
                          int64_t* out_ids, float* out_dists, const lorann_stages* st) {
     return search_impl(ix, queries, nq, k, w, m, out_ids, out_dists, st);
+}
+
+int lorann_set_exact_selection(lorann_index* ix, int32_t on) {
+    if (!ix) return fail(LORANN_E_INVAL, "index is NULL");
+    ix->force_exact = on != 0;
+    return LORANN_OK;
 }
 
 int lorann_profile_enable(lorann_index* ix, int32_t on) {

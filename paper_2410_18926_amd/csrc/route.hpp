@@ -115,40 +115,43 @@ __global__ __launch_bounds__(256) void k_select_clusters(const float* __restrict
 }
 
 // ---- Counting sort, step 2: exclusive scans over the clusters (single block of 1024 threads). ----
-// bucket_off[c]  = number of pairs routed to clusters < c           (bucket_off[L] = number of pairs)
-// tile_off[c]    = number of 16-pair tiles of clusters < c          (tile_off[L]   = number of tiles)
+// bucket_off[c]  = number of pairs routed to clusters < c                  (bucket_off[L] = number of pairs)
+// tile_off[c]    = number of 16-pair tiles of clusters < c                 (tile_off[L]   = number of tiles)
+// unit_off[c]    = number of unit_pairs-sized pair groups of clusters < c  (unit_off[L]   = number of units)
 // Also clears the scatter cursors.
-__global__ __launch_bounds__(1024) void k_scan_buckets(const int32_t* __restrict__ count, int L,
+__global__ __launch_bounds__(1024) void k_scan_buckets(const int32_t* __restrict__ count, int L, int unit_pairs,
                                                         int32_t* __restrict__ bucket_off, int32_t* __restrict__ tile_off,
-                                                        int32_t* __restrict__ cursor) {
-    __shared__ int sa[1024], sb[1024];
-    __shared__ int carry_a, carry_b;
+                                                        int32_t* __restrict__ unit_off, int32_t* __restrict__ cursor) {
+    __shared__ int sa[1024], sb[1024], sc[1024];
+    __shared__ int carry_a, carry_b, carry_c;
     const int tid = threadIdx.x;
-    if (tid == 0) { carry_a = 0; carry_b = 0; }
+    if (tid == 0) { carry_a = 0; carry_b = 0; carry_c = 0; }
     __syncthreads();
     for (int c0 = 0; c0 < L; c0 += 1024) {
         const int c = c0 + tid;
         const int a = c < L ? count[c] : 0;
         const int b = (a + 15) >> 4;
-        sa[tid] = a; sb[tid] = b;
+        const int u = (a + unit_pairs - 1) / unit_pairs;
+        sa[tid] = a; sb[tid] = b; sc[tid] = u;
         __syncthreads();
         for (int o = 1; o < 1024; o <<= 1) {
-            int ta = 0, tb = 0;
-            if (tid >= o) { ta = sa[tid - o]; tb = sb[tid - o]; }
+            int ta = 0, tb = 0, tc = 0;
+            if (tid >= o) { ta = sa[tid - o]; tb = sb[tid - o]; tc = sc[tid - o]; }
             __syncthreads();
-            sa[tid] += ta; sb[tid] += tb;
+            sa[tid] += ta; sb[tid] += tb; sc[tid] += tc;
             __syncthreads();
         }
         if (c < L) {
             bucket_off[c] = carry_a + sa[tid] - a;
             tile_off[c] = carry_b + sb[tid] - b;
+            unit_off[c] = carry_c + sc[tid] - u;
             cursor[c] = 0;
         }
         __syncthreads();
-        if (tid == 1023) { carry_a += sa[1023]; carry_b += sb[1023]; }
+        if (tid == 1023) { carry_a += sa[1023]; carry_b += sb[1023]; carry_c += sc[1023]; }
         __syncthreads();
     }
-    if (tid == 0) { bucket_off[L] = carry_a; tile_off[L] = carry_b; }
+    if (tid == 0) { bucket_off[L] = carry_a; tile_off[L] = carry_b; unit_off[L] = carry_c; }
 }
 
 // ---- Counting sort, step 3: place every pair (slot = query * w + rank) into its cluster's bucket. ----

@@ -34,8 +34,8 @@ __device__ __forceinline__ int point_score(const int8_t* __restrict__ code, cons
 }
 
 struct SelectArgs {
-    const int32_t* qlist;        // optional list of query numbers handled by this launch (NULL: block b -> query b)
-    const int32_t* qcount;       // optional device count of entries in qlist (blocks beyond it exit)
+    const int32_t* qlist;        // optional list of query numbers to process (NULL: queries 0..nq-1)
+    const int32_t* qcount;       // device count of entries in qlist (used only with qlist)
     const int32_t* sel;          // [nq][w]
     const int32_t* pos_of_slot;  // [nq*w]
     const int8_t* Z;             // [npairs][r_pad], bucket order
@@ -47,9 +47,9 @@ struct SelectArgs {
     int w, m;
 };
 
-// grid = number of queries (or list capacity), block = 256.  RB = r_pad / 16.
+// One query: the whole block works on query q.  RB = r_pad / 16.
 template <int RB>
-__global__ __launch_bounds__(256) void k_select_exact(SelectArgs a) {
+__device__ __forceinline__ void select_exact_query(const SelectArgs& a, const int q) {
     constexpr int ZW = RB * 4;                    // 32-bit words per z vector
     __shared__ int pc[256], ppos[256], pcnt[256], pstart[257];
     __shared__ int64_t prow0[256];
@@ -61,11 +61,6 @@ __global__ __launch_bounds__(256) void k_select_exact(SelectArgs a) {
     __shared__ int s_need, s_above;
 
     const int tid = threadIdx.x;
-    int q = blockIdx.x;
-    if (a.qlist) {
-        if (q >= *a.qcount) return;
-        q = a.qlist[q];
-    }
     const int w = a.w, m = a.m;
     const bool l2 = a.sqnorm != nullptr;
 
@@ -168,6 +163,17 @@ __global__ __launch_bounds__(256) void k_select_exact(SelectArgs a) {
                 tie_base += tot;
             }
         }
+    }
+}
+
+// grid = any (blocks stride over the work), block = 256.  Work = queries 0..nq-1, or the entries of a.qlist
+// (their number is read from a.qcount on the device).
+template <int RB>
+__global__ __launch_bounds__(256) void k_select_exact(SelectArgs a, int nq) {
+    const int total = a.qlist ? *a.qcount : nq;
+    for (int e = blockIdx.x; e < total; e += gridDim.x) {
+        select_exact_query<RB>(a, a.qlist ? a.qlist[e] : e);
+        __syncthreads();
     }
 }
 

@@ -1,0 +1,140 @@
+// Per-query selection kernels of the batched scoring path (Sec. 2.2: "the t highest scoring points are
+// selected into the candidate set"; t is called m here):
+//   k_query_bound   : tau_q = the m-th largest of the query's subset maxima (a valid lower bound on its m-th
+//                     best score), or -inf when fewer than m finite maxima exist;
+//   k_select_final  : exact top-m of the query's survivor list, order (score descending, row ascending);
+//                     queries whose list overflowed are put on the list for the exact per-query kernel.
+#pragma once
+#include "common.hpp"
+
+namespace lorann {
+
+// m-th largest key among keys[0..n) held in LDS (n >= m >= 1).  Returns the key; need_ties = how many of the
+// keys equal to it belong to the top m.  hist: 256 ints of LDS; sh: 2 words of LDS.  Block = 256 threads;
+// contains barriers, so every thread must call it with the same arguments.
+__device__ __forceinline__ uint32_t block_mth_largest(const uint32_t* keys, int n, int m, int* hist, uint32_t* sh, int& need_ties) {
+    const int tid = threadIdx.x;
+    if (tid == 0) { sh[0] = 0u; sh[1] = (uint32_t)m; }
+    uint32_t mask = 0u;
+    for (int shift = 24; shift >= 0; shift -= 8) {
+        hist[tid] = 0;
+        __syncthreads();
+        const uint32_t prefix = sh[0];
+        for (int i = tid; i < n; i += 256) {
+            const uint32_t key = keys[i];
+            if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1);
+        }
+        __syncthreads();
+        if (tid < 64) {
+            const int need = (int)sh[1];
+            const int h0 = hist[255 - 4 * tid], h1 = hist[254 - 4 * tid], h2 = hist[253 - 4 * tid], h3 = hist[252 - 4 * tid];
+            const int mine = h0 + h1 + h2 + h3;
+            int incl = mine;
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) { const int t = __shfl_up(incl, o, 64); if (tid >= o) incl += t; }
+            const int excl = incl - mine;
+            if (excl < need && incl >= need) {
+                int cum = excl, dgt = 255 - 4 * tid;
+                if (cum + h0 >= need) { }
+                else { cum += h0; if (cum + h1 >= need) { dgt -= 1; } else { cum += h1; if (cum + h2 >= need) { dgt -= 2; } else { cum += h2; dgt -= 3; } } }
+                sh[0] = prefix | ((uint32_t)dgt << shift);
+                sh[1] = (uint32_t)(need - cum);
+            }
+        }
+        mask |= 255u << shift;
+        __syncthreads();
+    }
+    need_ties = (int)sh[1];
+    const uint32_t T = sh[0];
+    __syncthreads();
+    return T;
+}
+
+// grid = nq, block = 256.  nvals = 2G values per pair; dynamic LDS = w * nvals * 4 bytes.
+__global__ __launch_bounds__(256) void k_query_bound(const float* __restrict__ pmax, const int32_t* __restrict__ pos_of_slot,
+                                                      int w, int nvals, int m, float* __restrict__ tau,
+                                                      int32_t* __restrict__ surv_cnt) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    uint32_t* keys = reinterpret_cast<uint32_t*>(smem);
+    __shared__ int hist[256];
+    __shared__ uint32_t sh[2];
+    __shared__ int s_finite;
+    const int tid = threadIdx.x;
+    const int q = blockIdx.x;
+    const int n = w * nvals;
+    if (tid == 0) { s_finite = 0; surv_cnt[q] = 0; }
+    __syncthreads();
+    int fin = 0;
+    for (int i = tid; i < n; i += 256) {
+        const int jp = i / nvals, g = i - jp * nvals;
+        const float v = pmax[(size_t)pos_of_slot[(size_t)q * w + jp] * nvals + g];
+        keys[i] = float_key_asc(v);
+        fin += (v > -INFINITY) ? 1 : 0;
+    }
+    atomicAdd(&s_finite, fin);
+    __syncthreads();
+    if (s_finite < m) {            // not enough real scores to bound the m-th best: no threshold
+        if (tid == 0) tau[q] = -INFINITY;
+        return;
+    }
+    int need_ties;
+    const uint32_t T = block_mth_largest(keys, n, m, hist, sh, need_ties);
+    if (tid == 0) {
+        const uint32_t u = (T & 0x80000000u) ? (T & 0x7fffffffu) : ~T;   // inverse of float_key_asc
+        tau[q] = __uint_as_float(u);
+    }
+}
+
+// grid = nq, block = 256, dynamic LDS = cap * 12 bytes (keys, rows, tie keys).
+__global__ __launch_bounds__(256) void k_select_final(const float* __restrict__ surv_score, const int32_t* __restrict__ surv_row,
+                                                       const int32_t* __restrict__ surv_cnt, const float* __restrict__ tau,
+                                                       int cap, int m, int32_t* __restrict__ cand,
+                                                       int32_t* __restrict__ fb_list, int32_t* __restrict__ fb_count) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    uint32_t* keys = reinterpret_cast<uint32_t*>(smem);
+    int32_t* rows = reinterpret_cast<int32_t*>(smem + (size_t)cap * 4);
+    uint32_t* tkeys = reinterpret_cast<uint32_t*>(smem + (size_t)cap * 8);
+    __shared__ int hist[256];
+    __shared__ uint32_t sh[2];
+    __shared__ int s_out, s_nt;
+    const int tid = threadIdx.x;
+    const int q = blockIdx.x;
+    const int cnt = surv_cnt[q];
+    int32_t* out = cand + (size_t)q * m;
+    // A query without a bound kept every score; if that (or anything else) overflowed the list, or if fewer
+    // than m survivors exist although a bound was set (cannot happen), the exact per-query kernel finishes it.
+    if (cnt > cap) {
+        if (tid == 0) fb_list[atomicAdd(fb_count, 1)] = q;
+        return;
+    }
+    for (int i = tid; i < cnt; i += 256) {
+        keys[i] = float_key_asc(surv_score[(size_t)q * cap + i]);
+        rows[i] = surv_row[(size_t)q * cap + i];
+    }
+    if (tid == 0) { s_out = 0; s_nt = 0; }
+    __syncthreads();
+    if (cnt <= m) {     // every scored point is a candidate (tau = -inf and few points)
+        for (int i = tid; i < m; i += 256) out[i] = i < cnt ? rows[i] : -1;
+        return;
+    }
+    int need_ties;
+    const uint32_t T = block_mth_largest(keys, cnt, m, hist, sh, need_ties);
+    const int n_above = m - need_ties;
+    // ties at the threshold: the need_ties lowest rows win.  Collect ~row of the tied entries and select again.
+    for (int i = tid; i < cnt; i += 256)
+        if (keys[i] == T) tkeys[atomicAdd(&s_nt, 1)] = ~(uint32_t)rows[i];
+    __syncthreads();
+    const int nt = s_nt;
+    uint32_t RT = 0u;      // threshold on ~row: tied entries with ~row >= RT are taken
+    if (nt > need_ties) {
+        int dummy;
+        RT = block_mth_largest(tkeys, nt, need_ties, hist, sh, dummy);
+    }
+    for (int i = tid; i < cnt; i += 256) {
+        const uint32_t key = keys[i];
+        if (key > T) out[atomicAdd(&s_out, 1)] = rows[i];
+        else if (key == T && (~(uint32_t)rows[i]) >= RT) out[n_above + atomicAdd(&s_nt, 1) - nt] = rows[i];
+    }
+}
+
+}  // namespace lorann

@@ -52,6 +52,14 @@ def _stagewise(B, wl, ix, queries, k=None, w=None, m=None, device_inputs=True):
     np.testing.assert_array_equal(np.sort(gst["cand_rows"].astype(np.int64), axis=1), np.sort(ost["cand_rows"], axis=1),
                                   err_msg=f"{tag}: candidate sets")
     n_tie = assert_topk_equal(g_ids, g_d, o_ids, o_d, tag)
+    # the exact per-query selection kernel (the fallback of the batched path) must give the same candidates
+    gix.set_exact_selection(True)
+    e_ids, e_d, est = gix.search_stages(q_in, k, w, m)
+    gix.set_exact_selection(False)
+    np.testing.assert_array_equal(np.sort(est["cand_rows"].astype(np.int64), axis=1), np.sort(ost["cand_rows"], axis=1),
+                                  err_msg=f"{tag}: candidate sets (per-query kernel)")
+    np.testing.assert_array_equal(e_ids, g_ids)
+    np.testing.assert_array_equal(e_d, g_d)
     # plain entry point returns the same as the staged one; second call is bitwise identical (determinism)
     p_ids, p_d = gix.search(q_in, k, w, m)
     p_ids2, p_d2 = gix.search(q_in, k, w, m)
@@ -172,4 +180,42 @@ def test_score_ties_resolve_to_lower_rows(B):
     g_ids, g_d, gst = gix.search_stages(q, 10, 3, 64)
     np.testing.assert_array_equal(np.sort(gst["cand_rows"].astype(np.int64), axis=1), np.sort(ost["cand_rows"], axis=1))
     assert_topk_equal(g_ids, g_d, o_ids, o_d, "ties")
+    gix.close()
+
+
+def test_survivor_overflow_falls_back_to_exact_kernel(B):
+    """All estimated scores equal: the bound equals that score, every point of the probed clusters survives the
+    filter, the survivor lists overflow, and the exact per-query kernel must finish those queries - with the
+    lowest rows as candidates."""
+    rng = np.random.default_rng(11)
+    d, L, r, n = 16, 4, 8, 9000
+    corpus = rng.normal(size=(n, d)).astype(np.float32)
+    ix = dict(metric=0, n=n, d=d, dp=d, r=r, L=L, centroids=rng.normal(size=(L, d)).astype(np.float32), P=None,
+              A=rng.integers(-127, 128, size=(L, r, d)).astype(np.int8), B=np.ones((n, r), np.int8),
+              scale_A=np.full(L, 0.01, np.float32), scale_B=np.full(L, 0.02, np.float32),
+              cluster_offsets=np.array([0, 3000, 5000, 5000, n], np.int64), corpus=corpus, ids=None)
+    q = rng.normal(size=(40, d)).astype(np.float32)
+    gix = B.Index(**ix)
+    oix = O.OracleIndex(ix)
+    for (k, w, m) in [(10, 3, 64), (5, 4, 200)]:
+        o_ids, o_d, ost = O.search(oix, q, k, w, m, stages=True)
+        g_ids, g_d, gst = gix.search_stages(q, k, w, m)
+        np.testing.assert_array_equal(np.sort(gst["cand_rows"].astype(np.int64), axis=1), np.sort(ost["cand_rows"], axis=1))
+        assert_topk_equal(g_ids, g_d, o_ids, o_d, "overflow")
+    gix.close()
+
+
+def test_mixed_batch_some_queries_fall_back(B, small_indexes):
+    """m close to the number of scored points and m / w beyond what the bound pass covers (no bound at all):
+    both routes must agree with the oracle."""
+    wl, ix, corpus, queries = small_indexes["ip_P"]
+    a = ix.numpy()
+    oix = O.OracleIndex(a)
+    gix = B.Index.from_arrays(ix.to("cuda"))
+    for (k, w, m) in [(10, 2, 70), (10, 1, 40), (10, 3, 1000), (10, wl.L, 2900), (3, 4, 31)]:
+        o_ids, o_d, ost = O.search(oix, queries, k, w, m, stages=True)
+        g_ids, g_d, gst = gix.search_stages(queries, k, w, m)
+        np.testing.assert_array_equal(np.sort(gst["cand_rows"].astype(np.int64), axis=1), np.sort(ost["cand_rows"], axis=1),
+                                      err_msg=f"k={k} w={w} m={m}")
+        assert_topk_equal(g_ids, g_d, o_ids, o_d, f"k={k} w={w} m={m}")
     gix.close()
