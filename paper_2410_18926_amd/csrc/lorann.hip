@@ -74,10 +74,10 @@ struct DevBuf {
     template <typename T> T* as() const { return reinterpret_cast<T*>(p); }
 };
 
-enum KernelId { K_PROJECT, K_QUANTIZE, K_CENTROID, K_SELECT_W, K_SCAN, K_SCATTER, K_STAGE_A, K_SCORE_BOUND, K_QUERY_BOUND, K_SCORE_FILTER, K_SELECT_FINAL, K_SELECT_M, K_RERANK, K_ZERO, K_COUNT };
+enum KernelId { K_PROJECT, K_QUANTIZE, K_CENTROID, K_SELECT_W, K_SCAN, K_SCATTER, K_STAGE_A, K_SEED, K_SCORE_FILTER, K_SELECT_FINAL, K_SELECT_M, K_RERANK, K_ZERO, K_COUNT };
 const char* const kKernelNames[K_COUNT] = {"project_f64", "quantize_rows", "centroid_dissim_f64", "select_clusters",
-                                            "scan_buckets", "scatter_pairs", "stage_a_i8", "score_bound_i8",
-                                            "query_bound", "score_filter_i8", "select_final", "score_select_exact",
+                                            "scan_buckets", "scatter_pairs", "stage_a_i8", "seed_threshold",
+                                            "score_filter_i8", "select_final", "score_select_exact",
                                             "rerank", "zero_counters"};
 
 struct EventPair { hipEvent_t a, b; int kid; };
@@ -101,7 +101,7 @@ struct lorann_index {
     float* sqnorm = nullptr;        // [n] (Euclidean)
     // workspace (device), sized for `chunk` queries
     DevBuf qproj, q8, dx, gscore, sel, count, cursor, bucket_off, tile_off, unit_off, slot_of_pos, pos_of_slot, Z, sigma, cand;
-    DevBuf pmax, tau, surv_cnt, surv_score, surv_row, fb_list;
+    DevBuf tau, surv_cnt, surv_score, surv_row, fb_list;
     int32_t force_exact = 0;        // 1: score + select with the per-query kernel only (verification)
     DevBuf stage_q, stage_ids, stage_dists;   // staging when the caller passes host memory
     // profiling
@@ -117,7 +117,7 @@ void free_all(lorann_index* ix) {
     void* ptrs[] = {ix->centroids, ix->cent_sqnorm, ix->Pt, ix->A, ix->Bp, ix->sA, ix->sB, ix->off, ix->corpus, ix->ids, ix->sqnorm};
     for (void* p : ptrs) if (p) (void)hipFree(p);
     DevBuf* bufs[] = {&ix->qproj, &ix->q8, &ix->dx, &ix->gscore, &ix->sel, &ix->count, &ix->cursor, &ix->bucket_off, &ix->tile_off,
-                      &ix->unit_off, &ix->slot_of_pos, &ix->pos_of_slot, &ix->Z, &ix->sigma, &ix->cand, &ix->pmax, &ix->tau,
+                      &ix->unit_off, &ix->slot_of_pos, &ix->pos_of_slot, &ix->Z, &ix->sigma, &ix->cand, &ix->tau,
                       &ix->surv_cnt, &ix->surv_score, &ix->surv_row, &ix->fb_list, &ix->stage_q, &ix->stage_ids, &ix->stage_dists};
     for (DevBuf* b : bufs) b->release();
     for (auto& e : ix->ev_used) { (void)hipEventDestroy(e.a); (void)hipEventDestroy(e.b); }
@@ -241,51 +241,46 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
             hipLaunchKernelGGL(k_stage_a<4>, grid, dim3(256), 0, s, ix->q8.as<int8_t>(), ix->dx.as<float>(), ix->A, ix->sA, ix->sB, ix->bucket_off.as<int32_t>(),
                                ix->tile_off.as<int32_t>(), ix->slot_of_pos.as<int32_t>(), L, dp, ix->r, w, ix->Z.as<int8_t>(), ix->sigma.as<float>());
     }
-    // Scores + candidate selection.  Batched path: bound pass -> per-query threshold -> filter pass -> exact
+    // Scores + candidate selection.  Batched path: per-query threshold from the nearest clusters -> filter pass -> exact
     // selection among the survivors; the exact per-query kernel finishes what the batched path cannot.
     SelectArgs sa_;
     sa_.qlist = nullptr; sa_.qcount = nullptr; sa_.sel = ix->sel.as<int32_t>(); sa_.pos_of_slot = ix->pos_of_slot.as<int32_t>();
     sa_.Z = ix->Z.as<int8_t>(); sa_.sigma = ix->sigma.as<float>(); sa_.Bp = ix->Bp; sa_.off = ix->off;
     sa_.sqnorm = ix->metric == LORANN_L2 ? ix->sqnorm : nullptr; sa_.cand = ix->cand.as<int32_t>(); sa_.w = w; sa_.m = m;
-    const int G = (8 * (int64_t)w >= m) ? 4 : ((32 * (int64_t)w >= m) ? 16 : 0);   // subset maxima per lane; 2G per pair
-    if (G == 0 || ix->force_exact) {
+    if (ix->force_exact) {
         Prof p(ix, K_SELECT_M);
         const unsigned grid = (unsigned)std::min<int64_t>(nq, 65536);
         if (r_pad == 32) hipLaunchKernelGGL(k_select_exact<2>, dim3(grid), dim3(256), 0, s, sa_, (int)nq);
         else hipLaunchKernelGGL(k_select_exact<4>, dim3(grid), dim3(256), 0, s, sa_, (int)nq);
     } else {
         const int cap = std::min(4096, std::max(1024, next_pow2(4 * m)));
-        if ((rc = ix->pmax.reserve((size_t)npairs * 2 * G * 4))) return rc;
         if ((rc = ix->tau.reserve((size_t)nq * 4))) return rc;
         if ((rc = ix->surv_cnt.reserve((size_t)nq * 4))) return rc;
         if ((rc = ix->surv_score.reserve((size_t)nq * cap * 4))) return rc;
         if ((rc = ix->surv_row.reserve((size_t)nq * cap * 4))) return rc;
         if ((rc = ix->fb_list.reserve((size_t)nq * 4))) return rc;
+        const bool l2 = ix->metric == LORANN_L2;
+        {
+            Prof p(ix, K_SEED);
+            SeedArgs se;
+            se.sel = ix->sel.as<int32_t>(); se.pos_of_slot = ix->pos_of_slot.as<int32_t>(); se.Z = ix->Z.as<int8_t>(); se.sigma = ix->sigma.as<float>();
+            se.Bp = ix->Bp; se.off = ix->off; se.sqnorm = l2 ? ix->sqnorm : nullptr; se.tau = ix->tau.as<float>(); se.surv_cnt = ix->surv_cnt.as<int32_t>();
+            se.w = w; se.m = m;
+            if (r_pad == 32) hipLaunchKernelGGL(k_seed_threshold<2>, dim3((unsigned)nq), dim3(256), 0, s, se);
+            else hipLaunchKernelGGL(k_seed_threshold<4>, dim3((unsigned)nq), dim3(256), 0, s, se);
+        }
         ScoreArgs sc;
         sc.Bp = ix->Bp; sc.Z = ix->Z.as<int8_t>(); sc.sigma = ix->sigma.as<float>(); sc.off = ix->off;
         sc.bucket_off = ix->bucket_off.as<int32_t>(); sc.unit_off = ix->unit_off.as<int32_t>(); sc.slot_of_pos = ix->slot_of_pos.as<int32_t>();
-        sc.sqnorm = ix->metric == LORANN_L2 ? ix->sqnorm : nullptr; sc.pmax = ix->pmax.as<float>(); sc.tau = ix->tau.as<float>();
+        sc.sqnorm = l2 ? ix->sqnorm : nullptr; sc.tau = ix->tau.as<float>();
         sc.surv_cnt = ix->surv_cnt.as<int32_t>(); sc.surv_score = ix->surv_score.as<float>(); sc.surv_row = ix->surv_row.as<int32_t>();
         sc.L = L; sc.w = w; sc.cap = cap;
         const int64_t max_units = npairs / kUnitPairs + L + 1;
         const dim3 ugrid((unsigned)((max_units + 3) / 4));
-        const bool l2 = ix->metric == LORANN_L2;
         const int ks = r_pad / 32;
         {
-            Prof p(ix, K_SCORE_BOUND);
-#define LAUNCH_BOUND(KS_, G_, L2_) hipLaunchKernelGGL((k_score_pass<kNZ, KS_, G_, false, L2_>), ugrid, dim3(256), 0, s, sc)
-            if (ks == 1) { if (G == 4) { if (l2) LAUNCH_BOUND(1, 4, true); else LAUNCH_BOUND(1, 4, false); } else { if (l2) LAUNCH_BOUND(1, 16, true); else LAUNCH_BOUND(1, 16, false); } }
-            else         { if (G == 4) { if (l2) LAUNCH_BOUND(2, 4, true); else LAUNCH_BOUND(2, 4, false); } else { if (l2) LAUNCH_BOUND(2, 16, true); else LAUNCH_BOUND(2, 16, false); } }
-#undef LAUNCH_BOUND
-        }
-        {
-            Prof p(ix, K_QUERY_BOUND);
-            hipLaunchKernelGGL(k_query_bound, dim3((unsigned)nq), dim3(256), (size_t)w * 2 * G * 4, s, ix->pmax.as<float>(), ix->pos_of_slot.as<int32_t>(), w, 2 * G, m,
-                               ix->tau.as<float>(), ix->surv_cnt.as<int32_t>());
-        }
-        {
             Prof p(ix, K_SCORE_FILTER);
-#define LAUNCH_FILTER(KS_, L2_) hipLaunchKernelGGL((k_score_pass<kNZ, KS_, 4, true, L2_>), ugrid, dim3(256), 0, s, sc)
+#define LAUNCH_FILTER(KS_, L2_) hipLaunchKernelGGL((k_score_filter<kNZ, KS_, L2_>), ugrid, dim3(256), 0, s, sc)
             if (ks == 1) { if (l2) LAUNCH_FILTER(1, true); else LAUNCH_FILTER(1, false); }
             else         { if (l2) LAUNCH_FILTER(2, true); else LAUNCH_FILTER(2, false); }
 #undef LAUNCH_FILTER

@@ -7,15 +7,13 @@
 // Register layout of that instruction (measured on gfx950): both operands give lane l sixteen consecutive
 // k-bytes (k-half l/32) of row / column l%32; result register v of lane l holds
 // D[8*(v/4) + 4*(l/32) + v%4][l%32].  With points as rows and pairs as columns every lane owns ONE pair and
-// sees 16 of its scores per tile, so per-pair state (scale, threshold, running maxima) lives in registers.
+// sees 16 of its scores per tile, so per-pair state (scale, threshold) lives in registers.
 //
-// Exact top-m without materialising the scores, in two passes over the (cheap) products:
-//   pass BOUND : per pair, the maxima of 2*G disjoint subsets of its points (G register groups x 2 lane
-//                halves).  All are real scores of distinct points, so the m-th largest of a query's w*2G
-//                subset maxima is a lower bound tau_q on its m-th best score.
-//   pass FILTER: recompute the products, keep only scores >= tau_q (a few per cent), append them to the
-//                query's survivor list.  The exact top-m of the survivors is the exact top-m overall.
-// Queries whose survivor list overflows, or that have no bound, are finished by the exact per-query kernel.
+// Exact top-m without materialising the scores: a lower bound tau_q on each query's m-th best score is known
+// before this kernel runs (the m-th best score inside the query's nearest cluster(s), k_seed_threshold), so
+// only scores >= tau_q - typically little more than m per query - are appended to the query's survivor list.
+// The exact top-m of the survivors is the exact top-m overall.  Queries whose survivor list overflows are
+// finished by the exact per-query kernel.
 #pragma once
 #include "common.hpp"
 #include "stage_a.hpp"
@@ -31,24 +29,21 @@ struct ScoreArgs {
     const int32_t* unit_off;     // [L+1] 32*NZ-pair units of each cluster
     const int32_t* slot_of_pos;  // [npairs]
     const float* sqnorm;         // [n] (Euclidean) or NULL
-    float* pmax;                 // BOUND out: [npairs][2G] subset maxima (-inf where a subset is empty)
-    const float* tau;            // FILTER in: [nq] lower bounds
-    int32_t* surv_cnt;           // FILTER out: [nq] survivors found (may exceed cap)
-    float* surv_score;           // FILTER out: [nq][cap]
-    int32_t* surv_row;           // FILTER out: [nq][cap]
+    const float* tau;            // in:  [nq] lower bounds on the m-th best score
+    int32_t* surv_cnt;           // out: [nq] survivors found (may exceed cap; only the first cap are stored)
+    float* surv_score;           // out: [nq][cap]
+    int32_t* surv_row;           // out: [nq][cap]
     int L, w, cap;
 };
-
-__device__ __forceinline__ int max3i(int a, int b, int c) { return max(max(a, b), c); }
 
 // Row (within the 32-point tile) of result register v for lane half h.
 __device__ __forceinline__ int tile_row(int v, int h) { return 8 * (v >> 2) + 4 * h + (v & 3); }
 
 // grid = ceil(max_units / 4), block = 256 (one unit per wavefront).
-// NZ pair tiles per unit, KS = r_pad / 32 k-steps, G in {4, 16} maxima groups, FILTER pass or BOUND pass,
-// L2 = Euclidean score epilogue (per-point bias, float domain).
-template <int NZ, int KS, int G, bool FILTER, bool L2>
-__global__ __launch_bounds__(256) void k_score_pass(ScoreArgs a) {
+// NZ pair tiles per unit, KS = r_pad / 32 k-steps, L2 = Euclidean score epilogue (per-point bias, float domain;
+// inner product and cosine compare in the integer domain, where sigma > 0 is constant per pair).
+template <int NZ, int KS, bool L2>
+__global__ __launch_bounds__(256) void k_score_filter(ScoreArgs a) {
     const int lane = threadIdx.x & 63;
     const int unit = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (unit >= a.unit_off[a.L]) return;
@@ -63,8 +58,8 @@ __global__ __launch_bounds__(256) void k_score_pass(ScoreArgs a) {
     i32x4 zreg[NZ][KS];
     float sg[NZ];
     bool pok[NZ];
-    int thr[NZ];          // FILTER, inner product: integer threshold (no false negatives)
-    float tauf[NZ];       // FILTER, Euclidean: float threshold
+    int thr[NZ];          // inner product / cosine: integer threshold (no false negatives)
+    float tauf[NZ];       // Euclidean: float threshold
     int qn[NZ];
 #pragma unroll
     for (int z = 0; z < NZ; ++z) {
@@ -78,31 +73,21 @@ __global__ __launch_bounds__(256) void k_score_pass(ScoreArgs a) {
             for (int ks = 0; ks < KS; ++ks) zreg[z][ks] = load16(a.Z + (size_t)p * RP + 32 * ks + 16 * h);
             const float s = a.sigma[p];
             sg[z] = L2 ? 2.0f * s : s;
-            if (FILTER) {
-                qn[z] = a.slot_of_pos[p] / a.w;
-                const float t = a.tau[qn[z]];
-                tauf[z] = t;
-                if (!L2) {
-                    // smallest integer score that can reach t, minus a safety margin of 2 (the survivors are
-                    // re-selected exactly later, so passing a few extra scores is harmless)
-                    if (s > 0.0f) {
-                        const float y = t / s;
-                        thr[z] = !(y > -2.0e6f) ? (int)0x80000000 : (y > 2.0e6f ? 0x7fffffff : (int)floorf(y) - 2);
-                    } else {
-                        thr[z] = (0.0f >= t) ? (int)0x80000000 : 0x7fffffff;   // every score of the pair is 0
-                    }
+            qn[z] = a.slot_of_pos[p] / a.w;
+            const float t = a.tau[qn[z]];
+            tauf[z] = t;
+            if (!L2) {
+                // smallest integer score that can reach t, minus a safety margin of 2 (the survivors are
+                // re-selected exactly later, so passing a few extra scores is harmless)
+                if (s > 0.0f) {
+                    const float y = t / s;
+                    thr[z] = !(y > -2.0e6f) ? (int)0x80000000 : (y > 2.0e6f ? 0x7fffffff : (int)floorf(y) - 2);
+                } else {
+                    thr[z] = (0.0f >= t) ? (int)0x80000000 : 0x7fffffff;   // every score of the pair is 0
                 }
             }
         }
     }
-
-    // BOUND state: running maxima per (pair tile, group)
-    int gmax_i[NZ][G];
-    float gmax_f[NZ][G];
-#pragma unroll
-    for (int z = 0; z < NZ; ++z)
-#pragma unroll
-        for (int g = 0; g < G; ++g) { gmax_i[z][g] = (int)0x80000000; gmax_f[z][g] = -INFINITY; }
 
     const int ntiles = (m_c + 31) >> 5;
     i32x4 bnext[KS];
@@ -140,26 +125,8 @@ __global__ __launch_bounds__(256) void k_score_pass(ScoreArgs a) {
                 for (int v = 0; v < 16; ++v)
                     if (32 * t + tile_row(v, h) >= m_c) acc[v] = (int)0x80000000;   // marks "no point"
             }
-            if (!FILTER) {
-                if (!L2) {
-                    if (G == 4) {
-#pragma unroll
-                        for (int g = 0; g < 4; ++g)
-                            gmax_i[z][g] = max3i(max3i(gmax_i[z][g], acc[4 * g], acc[4 * g + 1]), acc[4 * g + 2], acc[4 * g + 3]);
-                    } else {
-#pragma unroll
-                        for (int g = 0; g < 16; ++g) gmax_i[z][g] = max(gmax_i[z][g], acc[g]);
-                    }
-                } else {
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        const float s = acc[v] == (int)0x80000000 ? -INFINITY : __fmaf_rn((float)acc[v], sg[z], -bias[v]);
-                        const int g = G == 4 ? (v >> 2) : v;
-                        gmax_f[z][g] = fmaxf(gmax_f[z][g], s);
-                    }
-                }
-            } else {
-                // FILTER: count this lane's survivors of the tile, reserve room with one atomic, write them
+            {
+                // count this lane's survivors of the tile, reserve room with one atomic, write them
                 unsigned mask = 0;
                 float sc[16];
 #pragma unroll
@@ -189,22 +156,6 @@ __global__ __launch_bounds__(256) void k_score_pass(ScoreArgs a) {
                         }
                     }
                 }
-            }
-        }
-    }
-
-    if (!FILTER) {
-#pragma unroll
-        for (int z = 0; z < NZ; ++z) {
-            if (!pok[z]) continue;
-            const int p = pb + 32 * z + j;
-            float* o = a.pmax + (size_t)p * (2 * G) + h * G;
-#pragma unroll
-            for (int g = 0; g < G; ++g) {
-                float s;
-                if (!L2) s = gmax_i[z][g] == (int)0x80000000 ? -INFINITY : __fmaf_rn((float)gmax_i[z][g], sg[z], -0.0f);
-                else s = gmax_f[z][g];
-                o[g] = s;
             }
         }
     }

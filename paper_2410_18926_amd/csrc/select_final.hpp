@@ -1,11 +1,12 @@
 // Per-query selection kernels of the batched scoring path (Sec. 2.2: "the t highest scoring points are
 // selected into the candidate set"; t is called m here):
-//   k_query_bound   : tau_q = the m-th largest of the query's subset maxima (a valid lower bound on its m-th
-//                     best score), or -inf when fewer than m finite maxima exist;
+//   k_seed_threshold: tau_q = the m-th best score within the query's nearest cluster(s), a valid lower bound on
+//                     its m-th best score overall;
 //   k_select_final  : exact top-m of the query's survivor list, order (score descending, row ascending);
 //                     queries whose list overflowed are put on the list for the exact per-query kernel.
 #pragma once
 #include "common.hpp"
+#include "select_exact.hpp"
 
 namespace lorann {
 
@@ -50,38 +51,65 @@ __device__ __forceinline__ uint32_t block_mth_largest(const uint32_t* keys, int 
     return T;
 }
 
-// grid = nq, block = 256.  nvals = 2G values per pair; dynamic LDS = w * nvals * 4 bytes.
-__global__ __launch_bounds__(256) void k_query_bound(const float* __restrict__ pmax, const int32_t* __restrict__ pos_of_slot,
-                                                      int w, int nvals, int m, float* __restrict__ tau,
-                                                      int32_t* __restrict__ surv_cnt) {
-    extern __shared__ __align__(16) unsigned char smem[];
-    uint32_t* keys = reinterpret_cast<uint32_t*>(smem);
+constexpr int kSeedCap = 8192;    // scores of the seed clusters held in LDS (32 KiB)
+
+struct SeedArgs {
+    const int32_t* sel;          // [nq][w] clusters, nearest centroid first
+    const int32_t* pos_of_slot;  // [nq*w]
+    const int8_t* Z;             // [npairs][r_pad] bucket order
+    const float* sigma;          // [npairs] bucket order
+    const int8_t* Bp;            // [n][r_pad]
+    const int64_t* off;          // [L+1]
+    const float* sqnorm;         // [n] (Euclidean) or NULL
+    float* tau;                  // out [nq]
+    int32_t* surv_cnt;           // out [nq]: cleared
+    int w, m;
+};
+
+// tau_q = the m-th best estimated score among the points of the query's nearest clusters ("seed": the shortest
+// prefix of its ranked cluster list that holds at least m points, at most kSeedCap of them).  Every seed score is
+// a real score of the query, so at least m scores are >= tau_q: it is a valid lower bound on the m-th best
+// score overall, and a tight one whenever the nearest clusters hold most of the best candidates.  -inf when all
+// w clusters together hold fewer than m points.     grid = nq, block = 256.  RB = r_pad / 16.
+template <int RB>
+__global__ __launch_bounds__(256) void k_seed_threshold(SeedArgs a) {
+    constexpr int ZW = RB * 4;
+    __shared__ uint32_t keys[kSeedCap];
+    __shared__ int zw[ZW];
     __shared__ int hist[256];
     __shared__ uint32_t sh[2];
-    __shared__ int s_finite;
     const int tid = threadIdx.x;
     const int q = blockIdx.x;
-    const int n = w * nvals;
-    if (tid == 0) { s_finite = 0; surv_cnt[q] = 0; }
-    __syncthreads();
-    int fin = 0;
-    for (int i = tid; i < n; i += 256) {
-        const int jp = i / nvals, g = i - jp * nvals;
-        const float v = pmax[(size_t)pos_of_slot[(size_t)q * w + jp] * nvals + g];
-        keys[i] = float_key_asc(v);
-        fin += (v > -INFINITY) ? 1 : 0;
+    const bool l2 = a.sqnorm != nullptr;
+    if (tid == 0) a.surv_cnt[q] = 0;
+    int n = 0;
+    for (int jp = 0; jp < a.w && n < a.m; ++jp) {        // uniform loop: n is the same in every thread
+        const int c = a.sel[(size_t)q * a.w + jp];
+        const int64_t r0 = a.off[c];
+        const int cnt = min((int)(a.off[c + 1] - r0), kSeedCap - n);
+        const int pos = a.pos_of_slot[(size_t)q * a.w + jp];
+        __syncthreads();
+        if (tid < ZW) zw[tid] = reinterpret_cast<const int*>(a.Z)[(size_t)pos * ZW + tid];
+        __syncthreads();
+        const float s = a.sigma[pos];
+        const float sp = l2 ? 2.0f * s : s;
+        for (int t = tid; t < cnt; t += 256) {
+            const int y = point_score<RB>(a.Bp + (size_t)(r0 + t) * (RB * 16), zw);
+            const float bias = l2 ? a.sqnorm[r0 + t] : 0.0f;
+            keys[n + t] = float_key_asc(__fmaf_rn((float)y, sp, -bias));
+        }
+        n += cnt;
     }
-    atomicAdd(&s_finite, fin);
     __syncthreads();
-    if (s_finite < m) {            // not enough real scores to bound the m-th best: no threshold
-        if (tid == 0) tau[q] = -INFINITY;
+    if (n < a.m) {
+        if (tid == 0) a.tau[q] = -INFINITY;
         return;
     }
     int need_ties;
-    const uint32_t T = block_mth_largest(keys, n, m, hist, sh, need_ties);
+    const uint32_t T = block_mth_largest(keys, n, a.m, hist, sh, need_ties);
     if (tid == 0) {
         const uint32_t u = (T & 0x80000000u) ? (T & 0x7fffffffu) : ~T;   // inverse of float_key_asc
-        tau[q] = __uint_as_float(u);
+        a.tau[q] = __uint_as_float(u);
     }
 }
 
