@@ -113,6 +113,7 @@ def main():
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     prof = gix.profile_get()
+    fallback_queries = gix.profile_fallback_queries()
     gix.profile_enable(False)
     # the same loop without per-kernel events, to show what the events cost
     t0 = time.perf_counter()
@@ -196,6 +197,7 @@ def main():
         "roofline": roofline, "cpu_baseline": cpu_baseline,
         "kernels": kernels, "oracle_match": oracle_match,
         "ms_per_step_without_kernel_events": round(elapsed_noprof / K * 1e3, 4),
+        "fallback_queries_per_step": fallback_queries / K,
         "index_build_s": round(build_s, 1),
     }
     print(json.dumps(res), flush=True)

@@ -145,6 +145,9 @@ typedef struct lorann_kernel_time {
 
 int lorann_profile_enable(lorann_index *ix, int32_t on);
 int lorann_profile_get(lorann_index *ix, lorann_kernel_time *out, int32_t cap);
+/* Number of queries that the batched selection handed to the exact per-query kernel since profiling was
+ * enabled (-1 if ix is NULL). */
+int64_t lorann_profile_fallback_queries(lorann_index *ix);
 
 #ifdef __cplusplus
 }

@@ -22,7 +22,8 @@ LORANN_IP, LORANN_L2, LORANN_COS = 0, 1, 2
 LORANN_OK, LORANN_E_INVAL, LORANN_E_NOMEM, LORANN_E_DEVICE, LORANN_E_UNSUPPORTED = 0, -1, -2, -3, -4
 
 EXPORTS = ["lorann_load_index", "lorann_search", "lorann_free_index", "lorann_last_error", "lorann_set_stream",
-           "lorann_search_stages", "lorann_profile_enable", "lorann_profile_get", "lorann_set_exact_selection"]
+           "lorann_search_stages", "lorann_profile_enable", "lorann_profile_get", "lorann_set_exact_selection",
+           "lorann_profile_fallback_queries"]
 
 
 class LorannError(RuntimeError):
@@ -65,6 +66,8 @@ def lib() -> C.CDLL:
         L.lorann_set_exact_selection.argtypes = [vp, i32]
         L.lorann_profile_enable.restype = C.c_int
         L.lorann_profile_enable.argtypes = [vp, i32]
+        L.lorann_profile_fallback_queries.restype = C.c_int64
+        L.lorann_profile_fallback_queries.argtypes = [vp]
         L.lorann_profile_get.restype = C.c_int
         L.lorann_profile_get.argtypes = [vp, C.POINTER(_KernelTime), i32]
         _lib = L
@@ -181,6 +184,9 @@ class Index:
 
     def profile_enable(self, on: bool = True):
         _check(lib().lorann_profile_enable(self._h, 1 if on else 0))
+
+    def profile_fallback_queries(self) -> int:
+        return int(lib().lorann_profile_fallback_queries(self._h))
 
     def profile_get(self) -> dict:
         """{kernel name: (total ms, launches)} since profiling was enabled."""

@@ -101,7 +101,7 @@ struct lorann_index {
     float* sqnorm = nullptr;        // [n] (Euclidean)
     // workspace (device), sized for `chunk` queries
     DevBuf qproj, q8, dx, gscore, sel, count, cursor, bucket_off, tile_off, unit_off, slot_of_pos, pos_of_slot, Z, sigma, cand;
-    DevBuf tau, surv_cnt, surv_score, surv_row, fb_list;
+    DevBuf tau, surv_cnt, surv_score, surv_row, fb_list, big_list;
     int32_t force_exact = 0;        // 1: score + select with the per-query kernel only (verification)
     DevBuf stage_q, stage_ids, stage_dists;   // staging when the caller passes host memory
     // profiling
@@ -109,6 +109,7 @@ struct lorann_index {
     std::vector<EventPair> ev_used, ev_free;
     double prof_ms[K_COUNT] = {0};
     int64_t prof_launches[K_COUNT] = {0};
+    int64_t prof_fallback_queries = 0;   // queries finished by the exact per-query kernel while profiling
 };
 
 namespace {
@@ -118,7 +119,7 @@ void free_all(lorann_index* ix) {
     for (void* p : ptrs) if (p) (void)hipFree(p);
     DevBuf* bufs[] = {&ix->qproj, &ix->q8, &ix->dx, &ix->gscore, &ix->sel, &ix->count, &ix->cursor, &ix->bucket_off, &ix->tile_off,
                       &ix->unit_off, &ix->slot_of_pos, &ix->pos_of_slot, &ix->Z, &ix->sigma, &ix->cand, &ix->tau,
-                      &ix->surv_cnt, &ix->surv_score, &ix->surv_row, &ix->fb_list, &ix->stage_q, &ix->stage_ids, &ix->stage_dists};
+                      &ix->surv_cnt, &ix->surv_score, &ix->surv_row, &ix->fb_list, &ix->big_list, &ix->stage_q, &ix->stage_ids, &ix->stage_dists};
     for (DevBuf* b : bufs) b->release();
     for (auto& e : ix->ev_used) { (void)hipEventDestroy(e.a); (void)hipEventDestroy(e.b); }
     for (auto& e : ix->ev_free) { (void)hipEventDestroy(e.a); (void)hipEventDestroy(e.b); }
@@ -169,6 +170,7 @@ int next_pow2(int v) { int p = 1; while (p < v) p <<= 1; return p; }
 
 constexpr int kNZ = 2;                 // 32-pair tiles per scoring unit
 constexpr int kUnitPairs = 32 * kNZ;
+constexpr int kSmallCap = 1024;       // survivors the first selection launch holds in LDS
 
 // One batch of at most `chunk` queries, device pointers only.
 int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, int m, int64_t* d_ids, float* d_dists,
@@ -182,7 +184,7 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
     if ((rc = ix->dx.reserve((size_t)nq * 4))) return rc;
     if ((rc = ix->gscore.reserve((size_t)nq * L * 4))) return rc;
     if ((rc = ix->sel.reserve((size_t)npairs * 4))) return rc;
-    if ((rc = ix->count.reserve((size_t)(L + 1) * 4))) return rc;   // [L] pair counters + the fallback-list counter
+    if ((rc = ix->count.reserve((size_t)(L + 2) * 4))) return rc;   // [L] pair counters + fallback-list and big-list counters
     if ((rc = ix->cursor.reserve((size_t)L * 4))) return rc;
     if ((rc = ix->bucket_off.reserve((size_t)(L + 1) * 4))) return rc;
     if ((rc = ix->tile_off.reserve((size_t)(L + 1) * 4))) return rc;
@@ -202,7 +204,7 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
     }
     {
         Prof p(ix, K_ZERO);
-        hipLaunchKernelGGL(k_zero_i32, dim3((L + 256) / 256), dim3(256), 0, s, ix->count.as<int32_t>(), (int64_t)L + 1);
+        hipLaunchKernelGGL(k_zero_i32, dim3((L + 257) / 256), dim3(256), 0, s, ix->count.as<int32_t>(), (int64_t)L + 2);
     }
     {
         Prof p(ix, K_QUANTIZE);
@@ -253,12 +255,13 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
         if (r_pad == 32) hipLaunchKernelGGL(k_select_exact<2>, dim3(grid), dim3(256), 0, s, sa_, (int)nq);
         else hipLaunchKernelGGL(k_select_exact<4>, dim3(grid), dim3(256), 0, s, sa_, (int)nq);
     } else {
-        const int cap = std::min(4096, std::max(1024, next_pow2(4 * m)));
+        const int cap = 4096;               // survivors kept per query (>= LORANN_MAX_M)
         if ((rc = ix->tau.reserve((size_t)nq * 4))) return rc;
         if ((rc = ix->surv_cnt.reserve((size_t)nq * 4))) return rc;
         if ((rc = ix->surv_score.reserve((size_t)nq * cap * 4))) return rc;
         if ((rc = ix->surv_row.reserve((size_t)nq * cap * 4))) return rc;
         if ((rc = ix->fb_list.reserve((size_t)nq * 4))) return rc;
+        if ((rc = ix->big_list.reserve((size_t)nq * 4))) return rc;
         const bool l2 = ix->metric == LORANN_L2;
         {
             Prof p(ix, K_SEED);
@@ -287,9 +290,16 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
         }
         {
             Prof p(ix, K_SELECT_FINAL);
-            hipLaunchKernelGGL(k_select_final, dim3((unsigned)nq), dim3(256), (size_t)cap * 12, s, ix->surv_score.as<float>(), ix->surv_row.as<int32_t>(),
-                               ix->surv_cnt.as<int32_t>(), ix->tau.as<float>(), cap, m, ix->cand.as<int32_t>(), ix->fb_list.as<int32_t>(),
-                               ix->count.as<int32_t>() + L);
+            int32_t* counters = ix->count.as<int32_t>() + L;    // [0] fallback count, [1] big-list count
+            FinalArgs fa;
+            fa.surv_score = ix->surv_score.as<float>(); fa.surv_row = ix->surv_row.as<int32_t>(); fa.surv_cnt = ix->surv_cnt.as<int32_t>();
+            fa.cand = ix->cand.as<int32_t>(); fa.qlist = nullptr; fa.qcount = nullptr;
+            fa.big_list = ix->big_list.as<int32_t>(); fa.big_count = counters + 1; fa.fb_list = ix->fb_list.as<int32_t>(); fa.fb_count = counters;
+            fa.nq = (int)nq; fa.cap = cap; fa.lds_cap = kSmallCap; fa.m = m;
+            hipLaunchKernelGGL(k_select_final, dim3((unsigned)nq), dim3(256), (size_t)kSmallCap * 12, s, fa);
+            // second tier: the few queries with more survivors than the first launch holds in LDS
+            fa.qlist = ix->big_list.as<int32_t>(); fa.qcount = counters + 1; fa.big_list = nullptr; fa.big_count = nullptr; fa.lds_cap = cap;
+            hipLaunchKernelGGL(k_select_final, dim3((unsigned)std::min<int64_t>(nq, 512)), dim3(256), (size_t)cap * 12, s, fa);
         }
         {
             Prof p(ix, K_SELECT_M);
@@ -395,7 +405,14 @@ int search_impl(lorann_index* ix, const float* queries, int64_t nq, int32_t k, i
         if (!i_dev) HIP_TRY(hipMemcpyAsync(out_ids + (size_t)q0 * k, dI, (size_t)cn * k * 8, hipMemcpyDeviceToHost, ix->stream));
         if (!d_dev) HIP_TRY(hipMemcpyAsync(out_dists + (size_t)q0 * k, dD, (size_t)cn * k * 4, hipMemcpyDeviceToHost, ix->stream));
         HIP_TRY(hipStreamSynchronize(ix->stream));
-        if (ix->prof_on) prof_collect(ix);
+        if (ix->prof_on) {
+            prof_collect(ix);
+            if (!ix->force_exact) {
+                int32_t fb = 0;
+                HIP_TRY(hipMemcpy(&fb, ix->count.as<int32_t>() + ix->L, 4, hipMemcpyDeviceToHost));
+                ix->prof_fallback_queries += fb;
+            }
+        }
     }
     return LORANN_OK;
 }
@@ -534,8 +551,12 @@ int lorann_profile_enable(lorann_index* ix, int32_t on) {
     HIP_TRY(hipStreamSynchronize(ix->stream));
     prof_collect(ix);
     ix->prof_on = on != 0;
-    if (on) for (int i = 0; i < K_COUNT; ++i) { ix->prof_ms[i] = 0.0; ix->prof_launches[i] = 0; }
+    if (on) { for (int i = 0; i < K_COUNT; ++i) { ix->prof_ms[i] = 0.0; ix->prof_launches[i] = 0; } ix->prof_fallback_queries = 0; }
     return LORANN_OK;
+}
+
+int64_t lorann_profile_fallback_queries(lorann_index* ix) {
+    return ix ? ix->prof_fallback_queries : -1;
 }
 
 int lorann_profile_get(lorann_index* ix, lorann_kernel_time* out, int32_t cap) {

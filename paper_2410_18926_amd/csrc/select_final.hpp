@@ -113,55 +113,76 @@ __global__ __launch_bounds__(256) void k_seed_threshold(SeedArgs a) {
     }
 }
 
-// grid = nq, block = 256, dynamic LDS = cap * 12 bytes (keys, rows, tie keys).
-__global__ __launch_bounds__(256) void k_select_final(const float* __restrict__ surv_score, const int32_t* __restrict__ surv_row,
-                                                       const int32_t* __restrict__ surv_cnt, const float* __restrict__ tau,
-                                                       int cap, int m, int32_t* __restrict__ cand,
-                                                       int32_t* __restrict__ fb_list, int32_t* __restrict__ fb_count) {
+struct FinalArgs {
+    const float* surv_score;     // [nq][cap]
+    const int32_t* surv_row;     // [nq][cap]
+    const int32_t* surv_cnt;     // [nq]
+    int32_t* cand;               // [nq][m] out
+    const int32_t* qlist;        // queries to process (NULL: 0..nq-1) and their number on the device
+    const int32_t* qcount;
+    int32_t* big_list;           // out: queries with lds_cap < survivors <= cap (NULL: none expected)
+    int32_t* big_count;
+    int32_t* fb_list;            // out: queries whose survivor list overflowed cap
+    int32_t* fb_count;
+    int nq, cap, lds_cap, m;
+};
+
+// Exact top-m of one query's survivors, order (score descending, row ascending).  Block = 256,
+// dynamic LDS = lds_cap * 12 bytes (keys, rows, tie keys).  Blocks stride over the work list.
+// Queries with more than lds_cap survivors go to big_list (a second launch with more LDS takes them); queries
+// whose list overflowed cap go to fb_list (the exact per-query kernel takes them).
+__global__ __launch_bounds__(256) void k_select_final(FinalArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     uint32_t* keys = reinterpret_cast<uint32_t*>(smem);
-    int32_t* rows = reinterpret_cast<int32_t*>(smem + (size_t)cap * 4);
-    uint32_t* tkeys = reinterpret_cast<uint32_t*>(smem + (size_t)cap * 8);
+    int32_t* rows = reinterpret_cast<int32_t*>(smem + (size_t)a.lds_cap * 4);
+    uint32_t* tkeys = reinterpret_cast<uint32_t*>(smem + (size_t)a.lds_cap * 8);
     __shared__ int hist[256];
     __shared__ uint32_t sh[2];
     __shared__ int s_out, s_nt;
     const int tid = threadIdx.x;
-    const int q = blockIdx.x;
-    const int cnt = surv_cnt[q];
-    int32_t* out = cand + (size_t)q * m;
-    // A query without a bound kept every score; if that (or anything else) overflowed the list, or if fewer
-    // than m survivors exist although a bound was set (cannot happen), the exact per-query kernel finishes it.
-    if (cnt > cap) {
-        if (tid == 0) fb_list[atomicAdd(fb_count, 1)] = q;
-        return;
-    }
-    for (int i = tid; i < cnt; i += 256) {
-        keys[i] = float_key_asc(surv_score[(size_t)q * cap + i]);
-        rows[i] = surv_row[(size_t)q * cap + i];
-    }
-    if (tid == 0) { s_out = 0; s_nt = 0; }
-    __syncthreads();
-    if (cnt <= m) {     // every scored point is a candidate (tau = -inf and few points)
-        for (int i = tid; i < m; i += 256) out[i] = i < cnt ? rows[i] : -1;
-        return;
-    }
-    int need_ties;
-    const uint32_t T = block_mth_largest(keys, cnt, m, hist, sh, need_ties);
-    const int n_above = m - need_ties;
-    // ties at the threshold: the need_ties lowest rows win.  Collect ~row of the tied entries and select again.
-    for (int i = tid; i < cnt; i += 256)
-        if (keys[i] == T) tkeys[atomicAdd(&s_nt, 1)] = ~(uint32_t)rows[i];
-    __syncthreads();
-    const int nt = s_nt;
-    uint32_t RT = 0u;      // threshold on ~row: tied entries with ~row >= RT are taken
-    if (nt > need_ties) {
-        int dummy;
-        RT = block_mth_largest(tkeys, nt, need_ties, hist, sh, dummy);
-    }
-    for (int i = tid; i < cnt; i += 256) {
-        const uint32_t key = keys[i];
-        if (key > T) out[atomicAdd(&s_out, 1)] = rows[i];
-        else if (key == T && (~(uint32_t)rows[i]) >= RT) out[n_above + atomicAdd(&s_nt, 1) - nt] = rows[i];
+    const int total = a.qlist ? *a.qcount : a.nq;
+    const int m = a.m;
+    for (int e = blockIdx.x; e < total; e += gridDim.x) {
+        const int q = a.qlist ? a.qlist[e] : e;
+        const int cnt = a.surv_cnt[q];
+        int32_t* out = a.cand + (size_t)q * m;
+        __syncthreads();                       // LDS of the previous query is no longer read
+        if (cnt > a.cap) {
+            if (tid == 0) a.fb_list[atomicAdd(a.fb_count, 1)] = q;
+            continue;
+        }
+        if (cnt > a.lds_cap) {
+            if (tid == 0) a.big_list[atomicAdd(a.big_count, 1)] = q;
+            continue;
+        }
+        for (int i = tid; i < cnt; i += 256) {
+            keys[i] = float_key_asc(a.surv_score[(size_t)q * a.cap + i]);
+            rows[i] = a.surv_row[(size_t)q * a.cap + i];
+        }
+        if (tid == 0) { s_out = 0; s_nt = 0; }
+        __syncthreads();
+        if (cnt <= m) {     // every survivor is a candidate
+            for (int i = tid; i < m; i += 256) out[i] = i < cnt ? rows[i] : -1;
+            continue;
+        }
+        int need_ties;
+        const uint32_t T = block_mth_largest(keys, cnt, m, hist, sh, need_ties);
+        const int n_above = m - need_ties;
+        // ties at the threshold: the need_ties lowest rows win.  Collect ~row of the tied entries and select again.
+        for (int i = tid; i < cnt; i += 256)
+            if (keys[i] == T) tkeys[atomicAdd(&s_nt, 1)] = ~(uint32_t)rows[i];
+        __syncthreads();
+        const int nt = s_nt;
+        uint32_t RT = 0u;      // threshold on ~row: tied entries with ~row >= RT are taken
+        if (nt > need_ties) {
+            int dummy;
+            RT = block_mth_largest(tkeys, nt, need_ties, hist, sh, dummy);
+        }
+        for (int i = tid; i < cnt; i += 256) {
+            const uint32_t key = keys[i];
+            if (key > T) out[atomicAdd(&s_out, 1)] = rows[i];
+            else if (key == T && (~(uint32_t)rows[i]) >= RT) out[n_above + atomicAdd(&s_nt, 1) - nt] = rows[i];
+        }
     }
 }
 
