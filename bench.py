@@ -46,8 +46,7 @@ def kernel_models(wl, nq, touched_rows, npairs):
         "scatter_pairs": ("hbm", npairs * 12 / 1e9, PEAK_HBM_GBS, "GB/s"),
         "stage_a_i8": ("hbm", (L * dp * r + npairs * (dp + r + 4)) / 1e9, PEAK_HBM_GBS, "GB/s"),
         # B_c scoring (each of the two passes): every touched code once + the pairs' z / sigma (+ |c|^2 for Euclidean)
-        "score_bound_i8": ("hbm", b_bytes / 1e9, PEAK_HBM_GBS, "GB/s"),
-        "score_filter_i8": ("hbm", b_bytes / 1e9, PEAK_HBM_GBS, "GB/s"),
+        "pair_max_i8": ("hbm", b_bytes / 1e9, PEAK_HBM_GBS, "GB/s"),
         "score_select_exact": ("hbm", b_bytes / 1e9, PEAK_HBM_GBS, "GB/s"),
         "rerank": ("hbm", nq * m * d * 4 / 1e9, PEAK_HBM_GBS, "GB/s"),
     }

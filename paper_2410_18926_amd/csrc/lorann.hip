@@ -74,10 +74,10 @@ struct DevBuf {
     template <typename T> T* as() const { return reinterpret_cast<T*>(p); }
 };
 
-enum KernelId { K_PROJECT, K_QUANTIZE, K_CENTROID, K_SELECT_W, K_SCAN, K_SCATTER, K_STAGE_A, K_SEED, K_SCORE_FILTER, K_SELECT_FINAL, K_SELECT_M, K_RERANK, K_ZERO, K_COUNT };
+enum KernelId { K_PROJECT, K_QUANTIZE, K_CENTROID, K_SELECT_W, K_SCAN, K_SCATTER, K_STAGE_A, K_SEED, K_PAIR_MAX, K_EXTRACT, K_SELECT_FINAL, K_SELECT_M, K_RERANK, K_ZERO, K_COUNT };
 const char* const kKernelNames[K_COUNT] = {"project_f64", "quantize_rows", "centroid_dissim_f64", "select_clusters",
                                             "scan_buckets", "scatter_pairs", "stage_a_i8", "seed_threshold",
-                                            "score_filter_i8", "select_final", "score_select_exact",
+                                            "pair_max_i8", "extract_hot", "select_final", "score_select_exact",
                                             "rerank", "zero_counters"};
 
 struct EventPair { hipEvent_t a, b; int kid; };
@@ -101,7 +101,7 @@ struct lorann_index {
     float* sqnorm = nullptr;        // [n] (Euclidean)
     // workspace (device), sized for `chunk` queries
     DevBuf qproj, q8, dx, gscore, sel, count, cursor, bucket_off, tile_off, unit_off, slot_of_pos, pos_of_slot, Z, sigma, cand;
-    DevBuf tau, surv_cnt, surv_score, surv_row, fb_list, big_list;
+    DevBuf tau, surv_cnt, surv_score, surv_row, fb_list, big_list, hot_flag, hot_list;
     int32_t force_exact = 0;        // 1: score + select with the per-query kernel only (verification)
     DevBuf stage_q, stage_ids, stage_dists;   // staging when the caller passes host memory
     // profiling
@@ -119,7 +119,7 @@ void free_all(lorann_index* ix) {
     for (void* p : ptrs) if (p) (void)hipFree(p);
     DevBuf* bufs[] = {&ix->qproj, &ix->q8, &ix->dx, &ix->gscore, &ix->sel, &ix->count, &ix->cursor, &ix->bucket_off, &ix->tile_off,
                       &ix->unit_off, &ix->slot_of_pos, &ix->pos_of_slot, &ix->Z, &ix->sigma, &ix->cand, &ix->tau,
-                      &ix->surv_cnt, &ix->surv_score, &ix->surv_row, &ix->fb_list, &ix->big_list, &ix->stage_q, &ix->stage_ids, &ix->stage_dists};
+                      &ix->surv_cnt, &ix->surv_score, &ix->surv_row, &ix->fb_list, &ix->big_list, &ix->hot_flag, &ix->hot_list, &ix->stage_q, &ix->stage_ids, &ix->stage_dists};
     for (DevBuf* b : bufs) b->release();
     for (auto& e : ix->ev_used) { (void)hipEventDestroy(e.a); (void)hipEventDestroy(e.b); }
     for (auto& e : ix->ev_free) { (void)hipEventDestroy(e.a); (void)hipEventDestroy(e.b); }
@@ -170,6 +170,7 @@ int next_pow2(int v) { int p = 1; while (p < v) p <<= 1; return p; }
 
 constexpr int kNZ = 2;                 // 32-pair tiles per scoring unit
 constexpr int kUnitPairs = 32 * kNZ;
+constexpr int kChunkTiles = 16;       // 32-point tiles per scoring work item
 constexpr int kSmallCap = 1024;       // survivors the first selection launch holds in LDS
 
 // One batch of at most `chunk` queries, device pointers only.
@@ -184,7 +185,9 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
     if ((rc = ix->dx.reserve((size_t)nq * 4))) return rc;
     if ((rc = ix->gscore.reserve((size_t)nq * L * 4))) return rc;
     if ((rc = ix->sel.reserve((size_t)npairs * 4))) return rc;
-    if ((rc = ix->count.reserve((size_t)(L + 2) * 4))) return rc;   // [L] pair counters + fallback-list and big-list counters
+    if ((rc = ix->count.reserve((size_t)(L + 3) * 4))) return rc;   // [L] pair counters + fallback-list, big-list and hot-list counters
+    if ((rc = ix->hot_flag.reserve((size_t)npairs * 4))) return rc;
+    if ((rc = ix->hot_list.reserve((size_t)npairs * 4))) return rc;
     if ((rc = ix->cursor.reserve((size_t)L * 4))) return rc;
     if ((rc = ix->bucket_off.reserve((size_t)(L + 1) * 4))) return rc;
     if ((rc = ix->tile_off.reserve((size_t)(L + 1) * 4))) return rc;
@@ -204,7 +207,7 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
     }
     {
         Prof p(ix, K_ZERO);
-        hipLaunchKernelGGL(k_zero_i32, dim3((L + 257) / 256), dim3(256), 0, s, ix->count.as<int32_t>(), (int64_t)L + 2);
+        hipLaunchKernelGGL(k_zero_i32, dim3((L + 258) / 256), dim3(256), 0, s, ix->count.as<int32_t>(), (int64_t)L + 3);
     }
     {
         Prof p(ix, K_QUANTIZE);
@@ -224,13 +227,13 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
     }
     {
         Prof p(ix, K_SCAN);
-        hipLaunchKernelGGL(k_scan_buckets, dim3(1), dim3(1024), 0, s, ix->count.as<int32_t>(), L, kUnitPairs, ix->bucket_off.as<int32_t>(), ix->tile_off.as<int32_t>(),
+        hipLaunchKernelGGL(k_scan_buckets, dim3(1), dim3(1024), 0, s, ix->count.as<int32_t>(), ix->off, L, kUnitPairs, 32 * kChunkTiles, ix->bucket_off.as<int32_t>(), ix->tile_off.as<int32_t>(),
                            ix->unit_off.as<int32_t>(), ix->cursor.as<int32_t>());
     }
     {
         Prof p(ix, K_SCATTER);
         hipLaunchKernelGGL(k_scatter_pairs, dim3((unsigned)((npairs + 255) / 256)), dim3(256), 0, s, ix->sel.as<int32_t>(), npairs, ix->bucket_off.as<int32_t>(),
-                           ix->cursor.as<int32_t>(), ix->slot_of_pos.as<int32_t>(), ix->pos_of_slot.as<int32_t>());
+                           ix->cursor.as<int32_t>(), ix->slot_of_pos.as<int32_t>(), ix->pos_of_slot.as<int32_t>(), ix->hot_flag.as<int32_t>());
     }
     {
         Prof p(ix, K_STAGE_A);
@@ -243,7 +246,7 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
             hipLaunchKernelGGL(k_stage_a<4>, grid, dim3(256), 0, s, ix->q8.as<int8_t>(), ix->dx.as<float>(), ix->A, ix->sA, ix->sB, ix->bucket_off.as<int32_t>(),
                                ix->tile_off.as<int32_t>(), ix->slot_of_pos.as<int32_t>(), L, dp, ix->r, w, ix->Z.as<int8_t>(), ix->sigma.as<float>());
     }
-    // Scores + candidate selection.  Batched path: per-query threshold from the nearest clusters -> filter pass -> exact
+    // Scores + candidate selection.  Batched path: per-query threshold from the nearest clusters -> pair maxima (MFMA) -> survivors of the hot pairs -> exact
     // selection among the survivors; the exact per-query kernel finishes what the batched path cannot.
     SelectArgs sa_;
     sa_.qlist = nullptr; sa_.qcount = nullptr; sa_.sel = ix->sel.as<int32_t>(); sa_.pos_of_slot = ix->pos_of_slot.as<int32_t>();
@@ -277,16 +280,23 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
         sc.bucket_off = ix->bucket_off.as<int32_t>(); sc.unit_off = ix->unit_off.as<int32_t>(); sc.slot_of_pos = ix->slot_of_pos.as<int32_t>();
         sc.sqnorm = l2 ? ix->sqnorm : nullptr; sc.tau = ix->tau.as<float>();
         sc.surv_cnt = ix->surv_cnt.as<int32_t>(); sc.surv_score = ix->surv_score.as<float>(); sc.surv_row = ix->surv_row.as<int32_t>();
-        sc.L = L; sc.w = w; sc.cap = cap;
-        const int64_t max_units = npairs / kUnitPairs + L + 1;
-        const dim3 ugrid((unsigned)((max_units + 3) / 4));
+        sc.hot_flag = ix->hot_flag.as<int32_t>(); sc.hot_list = ix->hot_list.as<int32_t>(); sc.hot_count = ix->count.as<int32_t>() + L + 2;
+        sc.L = L; sc.w = w; sc.cap = cap; sc.chunk_tiles = kChunkTiles;
+        const dim3 ugrid(2048);             // persistent: 8192 wavefronts stride over the work items
         const int ks = r_pad / 32;
         {
-            Prof p(ix, K_SCORE_FILTER);
-#define LAUNCH_FILTER(KS_, L2_) hipLaunchKernelGGL((k_score_filter<kNZ, KS_, L2_>), ugrid, dim3(256), 0, s, sc)
-            if (ks == 1) { if (l2) LAUNCH_FILTER(1, true); else LAUNCH_FILTER(1, false); }
-            else         { if (l2) LAUNCH_FILTER(2, true); else LAUNCH_FILTER(2, false); }
-#undef LAUNCH_FILTER
+            Prof p(ix, K_PAIR_MAX);
+#define LAUNCH_PM(KS_, L2_) hipLaunchKernelGGL((k_pair_max<kNZ, KS_, L2_>), ugrid, dim3(256), 0, s, sc)
+            if (ks == 1) { if (l2) LAUNCH_PM(1, true); else LAUNCH_PM(1, false); }
+            else         { if (l2) LAUNCH_PM(2, true); else LAUNCH_PM(2, false); }
+#undef LAUNCH_PM
+        }
+        {
+            Prof p(ix, K_EXTRACT);
+#define LAUNCH_EX(RB_, L2_) hipLaunchKernelGGL((k_extract_hot<RB_, L2_>), ugrid, dim3(256), 0, s, sc)
+            if (ks == 1) { if (l2) LAUNCH_EX(2, true); else LAUNCH_EX(2, false); }
+            else         { if (l2) LAUNCH_EX(4, true); else LAUNCH_EX(4, false); }
+#undef LAUNCH_EX
         }
         {
             Prof p(ix, K_SELECT_FINAL);

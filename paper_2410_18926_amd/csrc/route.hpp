@@ -117,9 +117,11 @@ __global__ __launch_bounds__(256) void k_select_clusters(const float* __restrict
 // ---- Counting sort, step 2: exclusive scans over the clusters (single block of 1024 threads). ----
 // bucket_off[c]  = number of pairs routed to clusters < c                  (bucket_off[L] = number of pairs)
 // tile_off[c]    = number of 16-pair tiles of clusters < c                 (tile_off[L]   = number of tiles)
-// unit_off[c]    = number of unit_pairs-sized pair groups of clusters < c  (unit_off[L]   = number of units)
+// unit_off[c]    = number of scoring work items of clusters < c            (unit_off[L]   = number of items);
+//                  a cluster with a pairs and m_c points has ceil(a / unit_pairs) * ceil(m_c / chunk_points) items
 // Also clears the scatter cursors.
-__global__ __launch_bounds__(1024) void k_scan_buckets(const int32_t* __restrict__ count, int L, int unit_pairs,
+__global__ __launch_bounds__(1024) void k_scan_buckets(const int32_t* __restrict__ count, const int64_t* __restrict__ off,
+                                                        int L, int unit_pairs, int chunk_points,
                                                         int32_t* __restrict__ bucket_off, int32_t* __restrict__ tile_off,
                                                         int32_t* __restrict__ unit_off, int32_t* __restrict__ cursor) {
     __shared__ int sa[1024], sb[1024], sc[1024];
@@ -131,7 +133,11 @@ __global__ __launch_bounds__(1024) void k_scan_buckets(const int32_t* __restrict
         const int c = c0 + tid;
         const int a = c < L ? count[c] : 0;
         const int b = (a + 15) >> 4;
-        const int u = (a + unit_pairs - 1) / unit_pairs;
+        int u = 0;
+        if (c < L) {
+            const int m_c = (int)(off[c + 1] - off[c]);
+            u = ((a + unit_pairs - 1) / unit_pairs) * ((m_c + chunk_points - 1) / chunk_points);
+        }
         sa[tid] = a; sb[tid] = b; sc[tid] = u;
         __syncthreads();
         for (int o = 1; o < 1024; o <<= 1) {
@@ -155,16 +161,19 @@ __global__ __launch_bounds__(1024) void k_scan_buckets(const int32_t* __restrict
 }
 
 // ---- Counting sort, step 3: place every pair (slot = query * w + rank) into its cluster's bucket. ----
-// The order inside a bucket is arbitrary (atomic cursor); no result depends on it.
+// The order inside a bucket is arbitrary (atomic cursor); no result depends on it.  Also clears the pair's
+// hot flag for the scoring kernels.
 __global__ __launch_bounds__(256) void k_scatter_pairs(const int32_t* __restrict__ sel, int64_t npairs,
                                                         const int32_t* __restrict__ bucket_off, int32_t* __restrict__ cursor,
-                                                        int32_t* __restrict__ slot_of_pos, int32_t* __restrict__ pos_of_slot) {
+                                                        int32_t* __restrict__ slot_of_pos, int32_t* __restrict__ pos_of_slot,
+                                                        int32_t* __restrict__ hot_flag) {
     const int64_t p = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (p >= npairs) return;
     const int c = sel[p];
     const int pos = bucket_off[c] + atomicAdd(&cursor[c], 1);
     slot_of_pos[pos] = (int32_t)p;
     pos_of_slot[p] = pos;
+    hot_flag[p] = 0;
 }
 
 __global__ void k_zero_i32(int32_t* __restrict__ p, int64_t n) {
