@@ -122,6 +122,10 @@ typedef struct lorann_stages {
     int8_t *z;             /* [nq][w][r]    re-quantized intermediate vectors of each pair (Sec. 3.3)     */
     float *sigma;          /* [nq][w]       combined scale of each pair: score = sigma * integer score    */
     int32_t *cand_rows;    /* [nq][m]       candidate corpus rows, unordered, -1 padded (Sec. 2.2)        */
+    float *tau;            /* [nq]          estimated score of the m-th candidate found by the batched    */
+                           /*               selection (-inf: fewer than m points); untouched otherwise    */
+    int32_t *n_survivors;  /* [nq]          scores the batched selection still held when it finished      */
+                           /*               (-1: the query was finished by the exact per-query kernel)    */
     const int64_t *y_off;  /* [nq*w + 1]    caller-chosen offsets into y (needs sel known beforehand)     */
     int32_t *y;            /* [y_off[nq*w]] int32 score accumulators of every point of every pair, in     */
                            /*               cluster row order: y[y_off[slot] + t] (Sec. 3.3, 4.2)         */

@@ -33,7 +33,7 @@ class LorannError(RuntimeError):
 
 
 class _Stages(C.Structure):
-    _fields_ = [(n, C.c_void_p) for n in ("qproj", "q8", "dx", "sel", "z", "sigma", "cand_rows", "y_off", "y")]
+    _fields_ = [(n, C.c_void_p) for n in ("qproj", "q8", "dx", "sel", "z", "sigma", "cand_rows", "tau", "n_survivors", "y_off", "y")]
 
 
 class _KernelTime(C.Structure):
@@ -167,7 +167,8 @@ class Index:
         ids, dists = np.empty((nq, k), np.int64), np.empty((nq, k), np.float32)
         st = dict(qproj=np.zeros((nq, self.dp), np.float32), q8=np.zeros((nq, self.dp), np.int8),
                   dx=np.zeros(nq, np.float32), sel=np.zeros((nq, w), np.int32), z=np.zeros((nq, w, self.r), np.int8),
-                  sigma=np.zeros((nq, w), np.float32), cand_rows=np.zeros((nq, m), np.int32))
+                  sigma=np.zeros((nq, w), np.float32), cand_rows=np.zeros((nq, m), np.int32),
+                  tau=np.zeros(nq, np.float32), n_survivors=np.zeros(nq, np.int32))
         cs = _Stages()
         for name in st:
             setattr(cs, name, st[name].ctypes.data)

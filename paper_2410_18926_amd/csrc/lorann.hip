@@ -20,7 +20,7 @@
 #include "route.hpp"
 #include "score_mfma.hpp"
 #include "select_exact.hpp"
-#include "select_final.hpp"
+#include "select_query.hpp"
 #include "stage_a.hpp"
 
 using namespace lorann;
@@ -74,10 +74,9 @@ struct DevBuf {
     template <typename T> T* as() const { return reinterpret_cast<T*>(p); }
 };
 
-enum KernelId { K_PROJECT, K_QUANTIZE, K_CENTROID, K_SELECT_W, K_SCAN, K_SCATTER, K_STAGE_A, K_SEED, K_PAIR_MAX, K_EXTRACT, K_SELECT_FINAL, K_SELECT_M, K_RERANK, K_ZERO, K_COUNT };
+enum KernelId { K_PROJECT, K_QUANTIZE, K_CENTROID, K_SELECT_W, K_SCAN, K_SCATTER, K_STAGE_A, K_PAIR_MAX, K_SELECT_QUERY, K_SELECT_M, K_RERANK, K_ZERO, K_COUNT };
 const char* const kKernelNames[K_COUNT] = {"project_f64", "quantize_rows", "centroid_dissim_f64", "select_clusters",
-                                            "scan_buckets", "scatter_pairs", "stage_a_i8", "seed_threshold",
-                                            "pair_max_i8", "extract_hot", "select_final", "score_select_exact",
+                                            "scan_buckets", "scatter_pairs", "stage_a_i8", "pair_max_i8", "select_query", "score_select_exact",
                                             "rerank", "zero_counters"};
 
 struct EventPair { hipEvent_t a, b; int kid; };
@@ -101,7 +100,7 @@ struct lorann_index {
     float* sqnorm = nullptr;        // [n] (Euclidean)
     // workspace (device), sized for `chunk` queries
     DevBuf qproj, q8, dx, gscore, sel, count, cursor, bucket_off, tile_off, unit_off, slot_of_pos, pos_of_slot, Z, sigma, cand;
-    DevBuf tau, surv_cnt, surv_score, surv_row, fb_list, big_list, hot_flag, hot_list;
+    DevBuf tau, n_kept, fb_list, pmax;
     int32_t force_exact = 0;        // 1: score + select with the per-query kernel only (verification)
     DevBuf stage_q, stage_ids, stage_dists;   // staging when the caller passes host memory
     // profiling
@@ -119,7 +118,7 @@ void free_all(lorann_index* ix) {
     for (void* p : ptrs) if (p) (void)hipFree(p);
     DevBuf* bufs[] = {&ix->qproj, &ix->q8, &ix->dx, &ix->gscore, &ix->sel, &ix->count, &ix->cursor, &ix->bucket_off, &ix->tile_off,
                       &ix->unit_off, &ix->slot_of_pos, &ix->pos_of_slot, &ix->Z, &ix->sigma, &ix->cand, &ix->tau,
-                      &ix->surv_cnt, &ix->surv_score, &ix->surv_row, &ix->fb_list, &ix->big_list, &ix->hot_flag, &ix->hot_list, &ix->stage_q, &ix->stage_ids, &ix->stage_dists};
+                      &ix->n_kept, &ix->fb_list, &ix->pmax, &ix->stage_q, &ix->stage_ids, &ix->stage_dists};
     for (DevBuf* b : bufs) b->release();
     for (auto& e : ix->ev_used) { (void)hipEventDestroy(e.a); (void)hipEventDestroy(e.b); }
     for (auto& e : ix->ev_free) { (void)hipEventDestroy(e.a); (void)hipEventDestroy(e.b); }
@@ -171,7 +170,6 @@ int next_pow2(int v) { int p = 1; while (p < v) p <<= 1; return p; }
 constexpr int kNZ = 2;                 // 32-pair tiles per scoring unit
 constexpr int kUnitPairs = 32 * kNZ;
 constexpr int kChunkTiles = 16;       // 32-point tiles per scoring work item
-constexpr int kSmallCap = 1024;       // survivors the first selection launch holds in LDS
 
 // One batch of at most `chunk` queries, device pointers only.
 int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, int m, int64_t* d_ids, float* d_dists,
@@ -185,9 +183,8 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
     if ((rc = ix->dx.reserve((size_t)nq * 4))) return rc;
     if ((rc = ix->gscore.reserve((size_t)nq * L * 4))) return rc;
     if ((rc = ix->sel.reserve((size_t)npairs * 4))) return rc;
-    if ((rc = ix->count.reserve((size_t)(L + 3) * 4))) return rc;   // [L] pair counters + fallback-list, big-list and hot-list counters
-    if ((rc = ix->hot_flag.reserve((size_t)npairs * 4))) return rc;
-    if ((rc = ix->hot_list.reserve((size_t)npairs * 4))) return rc;
+    if ((rc = ix->count.reserve((size_t)(L + 1) * 4))) return rc;   // [L] pair counters + the fallback-list counter
+    if ((rc = ix->pmax.reserve((size_t)npairs * 4))) return rc;
     if ((rc = ix->cursor.reserve((size_t)L * 4))) return rc;
     if ((rc = ix->bucket_off.reserve((size_t)(L + 1) * 4))) return rc;
     if ((rc = ix->tile_off.reserve((size_t)(L + 1) * 4))) return rc;
@@ -207,7 +204,7 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
     }
     {
         Prof p(ix, K_ZERO);
-        hipLaunchKernelGGL(k_zero_i32, dim3((L + 258) / 256), dim3(256), 0, s, ix->count.as<int32_t>(), (int64_t)L + 3);
+        hipLaunchKernelGGL(k_zero_i32, dim3((L + 256) / 256), dim3(256), 0, s, ix->count.as<int32_t>(), (int64_t)L + 1);
     }
     {
         Prof p(ix, K_QUANTIZE);
@@ -233,7 +230,7 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
     {
         Prof p(ix, K_SCATTER);
         hipLaunchKernelGGL(k_scatter_pairs, dim3((unsigned)((npairs + 255) / 256)), dim3(256), 0, s, ix->sel.as<int32_t>(), npairs, ix->bucket_off.as<int32_t>(),
-                           ix->cursor.as<int32_t>(), ix->slot_of_pos.as<int32_t>(), ix->pos_of_slot.as<int32_t>(), ix->hot_flag.as<int32_t>());
+                           ix->cursor.as<int32_t>(), ix->slot_of_pos.as<int32_t>(), ix->pos_of_slot.as<int32_t>(), ix->pmax.as<uint32_t>());
     }
     {
         Prof p(ix, K_STAGE_A);
@@ -246,8 +243,7 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
             hipLaunchKernelGGL(k_stage_a<4>, grid, dim3(256), 0, s, ix->q8.as<int8_t>(), ix->dx.as<float>(), ix->A, ix->sA, ix->sB, ix->bucket_off.as<int32_t>(),
                                ix->tile_off.as<int32_t>(), ix->slot_of_pos.as<int32_t>(), L, dp, ix->r, w, ix->Z.as<int8_t>(), ix->sigma.as<float>());
     }
-    // Scores + candidate selection.  Batched path: per-query threshold from the nearest clusters -> pair maxima (MFMA) -> survivors of the hot pairs -> exact
-    // selection among the survivors; the exact per-query kernel finishes what the batched path cannot.
+    // Scores + candidate selection.  Batched path: pair maxima (MFMA) -> per-query walk over the few clusters whose maximum reaches the running m-th best score; the exact per-query kernel finishes what the batched path cannot.
     SelectArgs sa_;
     sa_.qlist = nullptr; sa_.qcount = nullptr; sa_.sel = ix->sel.as<int32_t>(); sa_.pos_of_slot = ix->pos_of_slot.as<int32_t>();
     sa_.Z = ix->Z.as<int8_t>(); sa_.sigma = ix->sigma.as<float>(); sa_.Bp = ix->Bp; sa_.off = ix->off;
@@ -258,58 +254,32 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
         if (r_pad == 32) hipLaunchKernelGGL(k_select_exact<2>, dim3(grid), dim3(256), 0, s, sa_, (int)nq);
         else hipLaunchKernelGGL(k_select_exact<4>, dim3(grid), dim3(256), 0, s, sa_, (int)nq);
     } else {
-        const int cap = 4096;               // survivors kept per query (>= LORANN_MAX_M)
         if ((rc = ix->tau.reserve((size_t)nq * 4))) return rc;
-        if ((rc = ix->surv_cnt.reserve((size_t)nq * 4))) return rc;
-        if ((rc = ix->surv_score.reserve((size_t)nq * cap * 4))) return rc;
-        if ((rc = ix->surv_row.reserve((size_t)nq * cap * 4))) return rc;
+        if ((rc = ix->n_kept.reserve((size_t)nq * 4))) return rc;
         if ((rc = ix->fb_list.reserve((size_t)nq * 4))) return rc;
-        if ((rc = ix->big_list.reserve((size_t)nq * 4))) return rc;
         const bool l2 = ix->metric == LORANN_L2;
-        {
-            Prof p(ix, K_SEED);
-            SeedArgs se;
-            se.sel = ix->sel.as<int32_t>(); se.pos_of_slot = ix->pos_of_slot.as<int32_t>(); se.Z = ix->Z.as<int8_t>(); se.sigma = ix->sigma.as<float>();
-            se.Bp = ix->Bp; se.off = ix->off; se.sqnorm = l2 ? ix->sqnorm : nullptr; se.tau = ix->tau.as<float>(); se.surv_cnt = ix->surv_cnt.as<int32_t>();
-            se.w = w; se.m = m;
-            if (r_pad == 32) hipLaunchKernelGGL(k_seed_threshold<2>, dim3((unsigned)nq), dim3(256), 0, s, se);
-            else hipLaunchKernelGGL(k_seed_threshold<4>, dim3((unsigned)nq), dim3(256), 0, s, se);
-        }
-        ScoreArgs sc;
-        sc.Bp = ix->Bp; sc.Z = ix->Z.as<int8_t>(); sc.sigma = ix->sigma.as<float>(); sc.off = ix->off;
-        sc.bucket_off = ix->bucket_off.as<int32_t>(); sc.unit_off = ix->unit_off.as<int32_t>(); sc.slot_of_pos = ix->slot_of_pos.as<int32_t>();
-        sc.sqnorm = l2 ? ix->sqnorm : nullptr; sc.tau = ix->tau.as<float>();
-        sc.surv_cnt = ix->surv_cnt.as<int32_t>(); sc.surv_score = ix->surv_score.as<float>(); sc.surv_row = ix->surv_row.as<int32_t>();
-        sc.hot_flag = ix->hot_flag.as<int32_t>(); sc.hot_list = ix->hot_list.as<int32_t>(); sc.hot_count = ix->count.as<int32_t>() + L + 2;
-        sc.L = L; sc.w = w; sc.cap = cap; sc.chunk_tiles = kChunkTiles;
-        const dim3 ugrid(2048);             // persistent: 8192 wavefronts stride over the work items
         const int ks = r_pad / 32;
         {
             Prof p(ix, K_PAIR_MAX);
+            ScoreArgs sc;
+            sc.Bp = ix->Bp; sc.Z = ix->Z.as<int8_t>(); sc.sigma = ix->sigma.as<float>(); sc.off = ix->off;
+            sc.bucket_off = ix->bucket_off.as<int32_t>(); sc.unit_off = ix->unit_off.as<int32_t>();
+            sc.sqnorm = l2 ? ix->sqnorm : nullptr; sc.pmax = ix->pmax.as<uint32_t>(); sc.L = L; sc.chunk_tiles = kChunkTiles;
+            const dim3 ugrid(2048);             // persistent: 8192 wavefronts stride over the work items
 #define LAUNCH_PM(KS_, L2_) hipLaunchKernelGGL((k_pair_max<kNZ, KS_, L2_>), ugrid, dim3(256), 0, s, sc)
             if (ks == 1) { if (l2) LAUNCH_PM(1, true); else LAUNCH_PM(1, false); }
             else         { if (l2) LAUNCH_PM(2, true); else LAUNCH_PM(2, false); }
 #undef LAUNCH_PM
         }
         {
-            Prof p(ix, K_EXTRACT);
-#define LAUNCH_EX(RB_, L2_) hipLaunchKernelGGL((k_extract_hot<RB_, L2_>), ugrid, dim3(256), 0, s, sc)
-            if (ks == 1) { if (l2) LAUNCH_EX(2, true); else LAUNCH_EX(2, false); }
-            else         { if (l2) LAUNCH_EX(4, true); else LAUNCH_EX(4, false); }
-#undef LAUNCH_EX
-        }
-        {
-            Prof p(ix, K_SELECT_FINAL);
-            int32_t* counters = ix->count.as<int32_t>() + L;    // [0] fallback count, [1] big-list count
-            FinalArgs fa;
-            fa.surv_score = ix->surv_score.as<float>(); fa.surv_row = ix->surv_row.as<int32_t>(); fa.surv_cnt = ix->surv_cnt.as<int32_t>();
-            fa.cand = ix->cand.as<int32_t>(); fa.qlist = nullptr; fa.qcount = nullptr;
-            fa.big_list = ix->big_list.as<int32_t>(); fa.big_count = counters + 1; fa.fb_list = ix->fb_list.as<int32_t>(); fa.fb_count = counters;
-            fa.nq = (int)nq; fa.cap = cap; fa.lds_cap = kSmallCap; fa.m = m;
-            hipLaunchKernelGGL(k_select_final, dim3((unsigned)nq), dim3(256), (size_t)kSmallCap * 12, s, fa);
-            // second tier: the few queries with more survivors than the first launch holds in LDS
-            fa.qlist = ix->big_list.as<int32_t>(); fa.qcount = counters + 1; fa.big_list = nullptr; fa.big_count = nullptr; fa.lds_cap = cap;
-            hipLaunchKernelGGL(k_select_final, dim3((unsigned)std::min<int64_t>(nq, 512)), dim3(256), (size_t)cap * 12, s, fa);
+            Prof p(ix, K_SELECT_QUERY);
+            QuerySelectArgs qa;
+            qa.sel = ix->sel.as<int32_t>(); qa.pos_of_slot = ix->pos_of_slot.as<int32_t>(); qa.pmax = ix->pmax.as<uint32_t>();
+            qa.Z = ix->Z.as<int8_t>(); qa.sigma = ix->sigma.as<float>(); qa.Bp = ix->Bp; qa.off = ix->off; qa.sqnorm = l2 ? ix->sqnorm : nullptr;
+            qa.cand = ix->cand.as<int32_t>(); qa.tau = ix->tau.as<float>(); qa.n_kept = ix->n_kept.as<int32_t>();
+            qa.fb_list = ix->fb_list.as<int32_t>(); qa.fb_count = ix->count.as<int32_t>() + L; qa.w = w; qa.m = m;
+            if (ks == 1) hipLaunchKernelGGL(k_select_query<2>, dim3((unsigned)nq), dim3(256), 0, s, qa);
+            else hipLaunchKernelGGL(k_select_query<4>, dim3((unsigned)nq), dim3(256), 0, s, qa);
         }
         {
             Prof p(ix, K_SELECT_M);
@@ -340,6 +310,8 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
         if (st->dx) HIP_TRY(hipMemcpy(st->dx + q_base, ix->dx.p, (size_t)nq * 4, hipMemcpyDefault));
         if (st->sel) HIP_TRY(hipMemcpy(st->sel + (size_t)q_base * w, ix->sel.p, (size_t)npairs * 4, hipMemcpyDefault));
         if (st->cand_rows) HIP_TRY(hipMemcpy(st->cand_rows + (size_t)q_base * m, ix->cand.p, (size_t)nq * m * 4, hipMemcpyDefault));
+        if (st->tau && !ix->force_exact) HIP_TRY(hipMemcpy(st->tau + q_base, ix->tau.p, (size_t)nq * 4, hipMemcpyDefault));
+        if (st->n_survivors && !ix->force_exact) HIP_TRY(hipMemcpy(st->n_survivors + q_base, ix->n_kept.p, (size_t)nq * 4, hipMemcpyDefault));
         if (st->z || st->sigma) {   // bucket order -> slot order on the host
             std::vector<int32_t> pos(npairs);
             std::vector<int8_t> Zh((size_t)npairs * r_pad);

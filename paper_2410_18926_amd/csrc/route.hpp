@@ -162,18 +162,18 @@ __global__ __launch_bounds__(1024) void k_scan_buckets(const int32_t* __restrict
 
 // ---- Counting sort, step 3: place every pair (slot = query * w + rank) into its cluster's bucket. ----
 // The order inside a bucket is arbitrary (atomic cursor); no result depends on it.  Also clears the pair's
-// hot flag for the scoring kernels.
+// best-score key for the scoring kernels.
 __global__ __launch_bounds__(256) void k_scatter_pairs(const int32_t* __restrict__ sel, int64_t npairs,
                                                         const int32_t* __restrict__ bucket_off, int32_t* __restrict__ cursor,
                                                         int32_t* __restrict__ slot_of_pos, int32_t* __restrict__ pos_of_slot,
-                                                        int32_t* __restrict__ hot_flag) {
+                                                        uint32_t* __restrict__ pmax) {
     const int64_t p = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (p >= npairs) return;
     const int c = sel[p];
     const int pos = bucket_off[c] + atomicAdd(&cursor[c], 1);
     slot_of_pos[pos] = (int32_t)p;
     pos_of_slot[p] = pos;
-    hot_flag[p] = 0;
+    pmax[p] = 0u;
 }
 
 __global__ void k_zero_i32(int32_t* __restrict__ p, int64_t n) {

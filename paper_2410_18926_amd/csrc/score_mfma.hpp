@@ -9,19 +9,12 @@
 // D[8*(v/4) + 4*(l/32) + v%4][l%32].  With pairs as rows and points as columns, lane l owns ONE point of the
 // tile and register v belongs to ONE pair (per lane half).
 //
-// Exact top-m without materialising the scores.  A lower bound tau_q on each query's m-th best score is known
-// before these kernels run (k_seed_threshold).  A score below tau_q can never be a candidate, so:
-//   k_pair_max    : for every pair, the maximum score over the cluster's points - one integer max per MFMA
-//                   result register, no per-score branch.  A pair whose maximum is below its threshold is
-//                   finished (the great majority: a query's best candidates sit in very few of its w clusters);
-//                   the others are put on the hot list.
-//   k_extract_hot : one wavefront per hot pair recomputes its scores point-parallel and appends those >= tau_q
-//                   to the query's survivor list (LDS-buffered, one atomic slot reservation per flush).
-// The exact top-m of the survivors (k_select_final) is the exact top-m overall; queries whose list overflows
-// are finished by the exact per-query kernel.
+// Exact top-m without materialising the scores: this kernel only computes, for every pair, the MAXIMUM score
+// over the cluster's points - one integer max per MFMA result register, no per-score branch.  The per-query
+// kernel (select_query.hpp) then needs to score point by point only the very few clusters of a query whose
+// maximum reaches its running m-th best score; every other pair is dismissed by its maximum alone.
 #pragma once
 #include "common.hpp"
-#include "select_exact.hpp"
 #include "stage_a.hpp"
 
 namespace lorann {
@@ -33,16 +26,9 @@ struct ScoreArgs {
     const int64_t* off;          // [L+1] corpus rows of each cluster
     const int32_t* bucket_off;   // [L+1] pairs of each cluster
     const int32_t* unit_off;     // [L+1] work items (pair group x point chunk) of each cluster
-    const int32_t* slot_of_pos;  // [npairs]
     const float* sqnorm;         // [n] (Euclidean) or NULL
-    const float* tau;            // [nq] lower bounds on the m-th best score
-    int32_t* hot_flag;           // [npairs] 0 on entry; set once a pair is on the hot list
-    int32_t* hot_list;           // out: [npairs] bucket positions of the hot pairs
-    int32_t* hot_count;          // out: their number (0 on entry)
-    int32_t* surv_cnt;           // [nq] survivors found (may exceed cap; only the first cap are stored)
-    float* surv_score;           // [nq][cap]
-    int32_t* surv_row;           // [nq][cap]
-    int L, w, cap;
+    uint32_t* pmax;              // out: [npairs] order-preserving key of the pair's best score (0 on entry)
+    int L;
     int chunk_tiles;             // 32-point tiles per work item
 };
 
@@ -195,82 +181,18 @@ __global__ __launch_bounds__(256) void k_pair_max(ScoreArgs a) {
         for (int p = lane; p < NP; p += 64) {
             const int gp = pb + p;
             if (gp < pend) {
-                const float s = a.sigma[gp];
-                const float t = a.tau[a.slot_of_pos[gp] / a.w];
-                bool hot;
+                uint32_t key = 0u;       // 0 = no point seen (below the key of every float)
                 if (!L2) {
                     const int y = s_red[wv][p];
-                    hot = y != IMIN && __fmaf_rn((float)y, s, -0.0f) >= t;   // sigma >= 0: the max score is the score of max Y
+                    // sigma >= 0: the best score of the pair is the score of its largest integer score
+                    if (y != IMIN) key = float_key_asc(__fmaf_rn((float)y, a.sigma[gp], -0.0f));
                 } else {
-                    hot = __int_as_float(s_red[wv][p]) >= t;
+                    const float f = __int_as_float(s_red[wv][p]);
+                    if (f > -INFINITY) key = float_key_asc(f);
                 }
-                if (hot && atomicExch(&a.hot_flag[gp], 1) == 0) a.hot_list[atomicAdd(a.hot_count, 1)] = gp;
+                if (key != 0u) atomicMax(&a.pmax[gp], key);      // the cluster's other point chunks contribute too
             }
         }
-    }
-}
-
-// grid = any (persistent: wavefronts stride over the hot list), block = 256, one hot pair per wavefront.
-// RB = r_pad / 16.  Scores are recomputed with 4-way int8 dot products, lanes = points.
-template <int RB, bool L2>
-__global__ __launch_bounds__(256) void k_extract_hot(ScoreArgs a) {
-    constexpr int ZW = RB * 4;
-    constexpr int CW = 512;            // survivors buffered per wavefront between flushes
-    __shared__ int s_z[4][ZW];
-    __shared__ float s_es[4][CW];
-    __shared__ int s_er[4][CW];
-    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-    const int n_hot = *a.hot_count;
-    for (int e = blockIdx.x * 4 + wv; e < n_hot; e += gridDim.x * 4) {
-        const int gp = a.hot_list[e];
-        const int q = a.slot_of_pos[gp] / a.w;
-        if (a.surv_cnt[q] > a.cap) continue;               // the list has already overflowed: the query goes to the exact kernel
-        const int c = find_bucket(a.bucket_off, a.L, gp);
-        const int64_t row0 = a.off[c];
-        const int m_c = (int)(a.off[c + 1] - row0);
-        const float s = a.sigma[gp];
-        const float sp = L2 ? 2.0f * s : s;
-        const float t = a.tau[q];
-        wave_lds_sync();
-        if (lane < ZW) s_z[wv][lane] = reinterpret_cast<const int*>(a.Z)[(size_t)gp * ZW + lane];
-        wave_lds_sync();
-        int wcount = 0;
-        auto flush = [&]() {
-            wave_lds_sync();
-            int base = 0;
-            if (lane == 0) base = atomicAdd(&a.surv_cnt[q], wcount);
-            base = __shfl(base, 0, 64);
-            for (int i = lane; i < wcount; i += 64) {
-                if (base + i < a.cap) {
-                    a.surv_score[(size_t)q * a.cap + base + i] = s_es[wv][i];
-                    a.surv_row[(size_t)q * a.cap + base + i] = s_er[wv][i];
-                }
-            }
-            wave_lds_sync();
-            wcount = 0;
-        };
-        for (int p0 = 0; p0 < m_c; p0 += 64) {
-            const int pt = p0 + lane;
-            bool keep = false;
-            float sc = 0.0f;
-            if (pt < m_c) {
-                const int y = point_score<RB>(a.Bp + (size_t)(row0 + pt) * (RB * 16), s_z[wv]);
-                const float bias = L2 ? a.sqnorm[row0 + pt] : 0.0f;
-                sc = __fmaf_rn((float)y, sp, -bias);
-                keep = sc >= t;
-            }
-            const unsigned long long m64 = __ballot(keep);
-            if (m64 != 0ull) {
-                if (wcount + 64 > CW) flush();
-                if (keep) {
-                    const int pos = wcount + __popcll(m64 & ((1ull << lane) - 1ull));
-                    s_es[wv][pos] = sc;
-                    s_er[wv][pos] = (int32_t)(row0 + pt);
-                }
-                wcount += __popcll(m64);
-            }
-        }
-        if (wcount > 0) flush();
     }
 }
 

@@ -1,0 +1,212 @@
+// Per-query candidate selection of the batched scoring path (Sec. 2.2: "the t highest scoring points are
+// selected into the candidate set"; t is called m here).
+//
+// k_pair_max has already computed, for every (query, cluster) pair, the best score of the cluster.  One block
+// per query now walks the query's pairs in descending order of that best score and keeps a running threshold T =
+// the m-th best score seen so far: a cluster whose best score is below T cannot contribute a candidate, and
+// because the pairs are sorted the walk stops at the first such cluster.  A query's best candidates sit in very
+// few of its w clusters, so typically one or two clusters are scored here (point-parallel, 4-way int8 dot
+// products); all the others were dismissed by their maxima alone.  The scores that reach T are held in LDS, the
+// threshold is tightened by an exact radix select whenever new ones arrive, and the final exact top-m (score
+// descending, row ascending) is written out.  Only if more scores tie with T than LDS can hold does the query go
+// to the exact per-query kernel.
+#pragma once
+#include "common.hpp"
+#include "select_exact.hpp"
+
+namespace lorann {
+
+// m-th largest among the keys f(i), i in [0, n), for which f returns true (at least m of them, m >= 1).
+// f(i, key&) -> bool.  Returns the key; need_ties = how many of the keys equal to it belong to the top m.
+// hist: 256 ints of LDS; sh: 2 words of LDS.  Block = 256 threads; contains barriers, so every thread must
+// call it with the same arguments.
+template <typename F>
+__device__ __forceinline__ uint32_t block_mth_largest(int n, int m, int* hist, uint32_t* sh, int& need_ties, F f) {
+    const int tid = threadIdx.x;
+    if (tid == 0) { sh[0] = 0u; sh[1] = (uint32_t)m; }
+    uint32_t mask = 0u;
+    for (int shift = 24; shift >= 0; shift -= 8) {
+        hist[tid] = 0;
+        __syncthreads();
+        const uint32_t prefix = sh[0];
+        for (int i = tid; i < n; i += 256) {
+            uint32_t key;
+            if (f(i, key) && (key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1);
+        }
+        __syncthreads();
+        if (tid < 64) {     // descending digit walk: the digit where the count from the top reaches need
+            const int need = (int)sh[1];
+            const int h0 = hist[255 - 4 * tid], h1 = hist[254 - 4 * tid], h2 = hist[253 - 4 * tid], h3 = hist[252 - 4 * tid];
+            const int mine = h0 + h1 + h2 + h3;
+            int incl = mine;
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) { const int t = __shfl_up(incl, o, 64); if (tid >= o) incl += t; }
+            const int excl = incl - mine;
+            if (excl < need && incl >= need) {
+                int cum = excl, dgt = 255 - 4 * tid;
+                if (cum + h0 >= need) { }
+                else { cum += h0; if (cum + h1 >= need) { dgt -= 1; } else { cum += h1; if (cum + h2 >= need) { dgt -= 2; } else { cum += h2; dgt -= 3; } } }
+                sh[0] = prefix | ((uint32_t)dgt << shift);
+                sh[1] = (uint32_t)(need - cum);
+            }
+        }
+        mask |= 255u << shift;
+        __syncthreads();
+    }
+    need_ties = (int)sh[1];
+    const uint32_t T = sh[0];
+    __syncthreads();
+    return T;
+}
+
+__device__ __forceinline__ float key_to_float(uint32_t key) {   // inverse of float_key_asc
+    return __uint_as_float((key & 0x80000000u) ? (key & 0x7fffffffu) : ~key);
+}
+
+constexpr int kQCap = 4096;       // (score, row) entries a query holds in LDS
+constexpr int kQChunk = 1024;     // points scored between capacity checks
+
+struct QuerySelectArgs {
+    const int32_t* sel;          // [nq][w] clusters of each query
+    const int32_t* pos_of_slot;  // [nq*w]
+    const uint32_t* pmax;        // [npairs] key of each pair's best score (0: the cluster is empty), bucket order
+    const int8_t* Z;             // [npairs][r_pad] bucket order
+    const float* sigma;          // [npairs] bucket order
+    const int8_t* Bp;            // [n][r_pad]
+    const int64_t* off;          // [L+1]
+    const float* sqnorm;         // [n] (Euclidean) or NULL
+    int32_t* cand;               // out [nq][m]: candidate rows, unordered, -1 padded
+    float* tau;                  // out [nq]: score of the m-th candidate (-inf if fewer than m points were scored)
+    int32_t* n_kept;             // out [nq]: scores held in LDS when the walk ended (-1: handed to the exact kernel)
+    int32_t* fb_list;            // out: queries that need the exact per-query kernel
+    int32_t* fb_count;           //      and their number (0 on entry)
+    int w, m;
+};
+
+// grid = nq, block = 256.  RB = r_pad / 16.
+template <int RB>
+__global__ __launch_bounds__(256) void k_select_query(QuerySelectArgs a) {
+    constexpr int ZW = RB * 4;
+    __shared__ uint32_t keys[kQCap];
+    __shared__ int32_t rows[kQCap];
+    __shared__ int zw[ZW];
+    __shared__ int hist[256];
+    __shared__ int wsum[4];
+    __shared__ uint32_t sh[2];
+    __shared__ uint32_t pk[256];      // best-score keys of the query's pairs
+    __shared__ int ppos[256], order[256];
+    __shared__ int s_count, s_out, s_ties;
+    const int tid = threadIdx.x;
+    const int q = blockIdx.x;
+    const int w = a.w, m = a.m;
+    const bool l2 = a.sqnorm != nullptr;
+    if (tid == 0) s_count = 0;
+    if (tid < w) {
+        const int pos = a.pos_of_slot[(size_t)q * w + tid];
+        ppos[tid] = pos;
+        pk[tid] = a.pmax[pos];
+    }
+    __syncthreads();
+    if (tid < w) {      // order the pairs by best score, descending (ties: lower rank first)
+        const uint32_t k = pk[tid];
+        int rank = 0;
+        for (int u = 0; u < w; ++u) rank += (pk[u] > k || (pk[u] == k && u < tid)) ? 1 : 0;
+        order[rank] = tid;
+    }
+    __syncthreads();
+
+    uint32_t T = 0u;          // running threshold key: the m-th best score seen so far (0: none yet)
+    int count = 0;            // entries in keys/rows, all >= T (uniform)
+    bool overflow = false;
+
+    // Tighten T to the m-th largest stored key and drop the entries below it (stable, in place).
+    auto compact = [&]() {
+        if (count < m) return;
+        int need_ties;
+        const uint32_t Tn = block_mth_largest(count, m, hist, sh, need_ties, [&](int i, uint32_t& key) { key = keys[i]; return true; });
+        int kept = 0;
+        for (int base = 0; base < count; base += 256) {
+            const int i = base + tid;
+            uint32_t k = 0u;
+            int32_t r = 0;
+            if (i < count) { k = keys[i]; r = rows[i]; }
+            const bool keep = i < count && k >= Tn;
+            int tot;
+            const int rank = block_flag_scan<4>(keep, wsum, tot);     // barriers: the chunk is in registers before any write
+            if (keep) { keys[kept + rank] = k; rows[kept + rank] = r; }
+            kept += tot;
+        }
+        __syncthreads();
+        T = Tn;
+        count = kept;
+        if (tid == 0) s_count = kept;
+        __syncthreads();
+    };
+
+    for (int o = 0; o < w && !overflow; ++o) {
+        const int jp = order[o];
+        if (pk[jp] == 0u || pk[jp] < T) break;           // sorted: no later cluster can reach T either
+        const int c = a.sel[(size_t)q * w + jp];
+        const int64_t r0 = a.off[c];
+        const int m_c = (int)(a.off[c + 1] - r0);
+        const int pos = ppos[jp];
+        __syncthreads();
+        if (tid < ZW) zw[tid] = reinterpret_cast<const int*>(a.Z)[(size_t)pos * ZW + tid];
+        __syncthreads();
+        const float s = a.sigma[pos];
+        const float sp = l2 ? 2.0f * s : s;
+        for (int p0 = 0; p0 < m_c; p0 += kQChunk) {
+            if (count > kQCap - kQChunk) {
+                compact();
+                if (count > kQCap - kQChunk) { overflow = true; break; }   // too many scores tie with the threshold
+            }
+            const int pe = min(m_c, p0 + kQChunk);
+            for (int t = p0 + tid; t < pe; t += 256) {
+                const int y = point_score<RB>(a.Bp + (size_t)(r0 + t) * (RB * 16), zw);
+                const float bias = l2 ? a.sqnorm[r0 + t] : 0.0f;
+                const uint32_t key = float_key_asc(__fmaf_rn((float)y, sp, -bias));
+                if (key >= T) {
+                    const int at = atomicAdd(&s_count, 1);
+                    keys[at] = key;
+                    rows[at] = (int32_t)(r0 + t);
+                }
+            }
+            __syncthreads();
+            count = s_count;
+        }
+        if (!overflow) compact();     // new scores arrived: raise the threshold before looking at the next cluster
+    }
+
+    int32_t* out = a.cand + (size_t)q * m;
+    if (overflow) {
+        if (tid == 0) { a.fb_list[atomicAdd(a.fb_count, 1)] = q; a.n_kept[q] = -1; a.tau[q] = key_to_float(T); }
+        return;
+    }
+    if (tid == 0) { a.n_kept[q] = count; a.tau[q] = count >= m ? key_to_float(T) : -INFINITY; s_out = 0; s_ties = 0; }
+    if (count <= m) {       // every kept score is a candidate (count < m: all scored points)
+        for (int i = tid; i < m; i += 256) out[i] = i < count ? rows[i] : -1;
+        return;
+    }
+    // count > m: T is the m-th largest key (compact() ran after the last arrivals); ties at T go to the lower rows
+    __syncthreads();
+    int above = 0;
+    for (int i = tid; i < count; i += 256) above += keys[i] > T ? 1 : 0;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) above += __shfl_xor(above, o, 64);
+    if ((tid & 63) == 0) atomicAdd(&s_out, above);
+    __syncthreads();
+    const int n_above = s_out;
+    const int need_ties = m - n_above;
+    __syncthreads();
+    if (tid == 0) s_out = 0;
+    int dummy;
+    const uint32_t RT = block_mth_largest(count, need_ties, hist, sh, dummy,
+                                          [&](int i, uint32_t& key) { key = ~(uint32_t)rows[i]; return keys[i] == T; });
+    for (int i = tid; i < count; i += 256) {
+        const uint32_t key = keys[i];
+        if (key > T) out[atomicAdd(&s_out, 1)] = rows[i];
+        else if ((~(uint32_t)rows[i]) >= RT) out[n_above + atomicAdd(&s_ties, 1)] = rows[i];
+    }
+}
+
+}  // namespace lorann
