@@ -99,7 +99,7 @@ struct lorann_index {
     int64_t* ids = nullptr;         // [n] or NULL
     float* sqnorm = nullptr;        // [n] (Euclidean)
     // workspace (device), sized for `chunk` queries
-    DevBuf qproj, q8, dx, gscore, sel, count, cursor, bucket_off, tile_off, unit_off, slot_of_pos, pos_of_slot, Z, sigma, cand;
+    DevBuf qproj, q8, dx, gscore, sel, count, rank_in_bucket, qrank, qorder, off0, bucket_off, tile_off, unit_off, slot_of_pos, pos_of_slot, Z, sigma, cand;
     DevBuf tau, n_kept, fb_list, pmax;
     int32_t force_exact = 0;        // 1: score + select with the per-query kernel only (verification)
     DevBuf stage_q, stage_ids, stage_dists;   // staging when the caller passes host memory
@@ -116,7 +116,7 @@ namespace {
 void free_all(lorann_index* ix) {
     void* ptrs[] = {ix->centroids, ix->cent_sqnorm, ix->Pt, ix->A, ix->Bp, ix->sA, ix->sB, ix->off, ix->corpus, ix->ids, ix->sqnorm};
     for (void* p : ptrs) if (p) (void)hipFree(p);
-    DevBuf* bufs[] = {&ix->qproj, &ix->q8, &ix->dx, &ix->gscore, &ix->sel, &ix->count, &ix->cursor, &ix->bucket_off, &ix->tile_off,
+    DevBuf* bufs[] = {&ix->qproj, &ix->q8, &ix->dx, &ix->gscore, &ix->sel, &ix->count, &ix->rank_in_bucket, &ix->qrank, &ix->qorder, &ix->off0, &ix->bucket_off, &ix->tile_off,
                       &ix->unit_off, &ix->slot_of_pos, &ix->pos_of_slot, &ix->Z, &ix->sigma, &ix->cand, &ix->tau,
                       &ix->n_kept, &ix->fb_list, &ix->pmax, &ix->stage_q, &ix->stage_ids, &ix->stage_dists};
     for (DevBuf* b : bufs) b->release();
@@ -183,9 +183,12 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
     if ((rc = ix->dx.reserve((size_t)nq * 4))) return rc;
     if ((rc = ix->gscore.reserve((size_t)nq * L * 4))) return rc;
     if ((rc = ix->sel.reserve((size_t)npairs * 4))) return rc;
-    if ((rc = ix->count.reserve((size_t)(L + 1) * 4))) return rc;   // [L] pair counters + the fallback-list counter
+    if ((rc = ix->count.reserve((size_t)(2 * L + 1) * 4))) return rc;   // [L] pair counters, [L] nearest-cluster counters, fallback-list counter
+    if ((rc = ix->rank_in_bucket.reserve((size_t)npairs * 4))) return rc;
+    if ((rc = ix->qrank.reserve((size_t)nq * 4))) return rc;
+    if ((rc = ix->qorder.reserve((size_t)nq * 4))) return rc;
+    if ((rc = ix->off0.reserve((size_t)L * 4))) return rc;
     if ((rc = ix->pmax.reserve((size_t)npairs * 4))) return rc;
-    if ((rc = ix->cursor.reserve((size_t)L * 4))) return rc;
     if ((rc = ix->bucket_off.reserve((size_t)(L + 1) * 4))) return rc;
     if ((rc = ix->tile_off.reserve((size_t)(L + 1) * 4))) return rc;
     if ((rc = ix->unit_off.reserve((size_t)(L + 1) * 4))) return rc;
@@ -204,7 +207,7 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
     }
     {
         Prof p(ix, K_ZERO);
-        hipLaunchKernelGGL(k_zero_i32, dim3((L + 256) / 256), dim3(256), 0, s, ix->count.as<int32_t>(), (int64_t)L + 1);
+        hipLaunchKernelGGL(k_zero_i32, dim3((2 * L + 256) / 256), dim3(256), 0, s, ix->count.as<int32_t>(), (int64_t)2 * L + 1);
     }
     {
         Prof p(ix, K_QUANTIZE);
@@ -220,17 +223,19 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
     }
     {
         Prof p(ix, K_SELECT_W);
-        hipLaunchKernelGGL(k_select_clusters, dim3((unsigned)nq), dim3(256), 0, s, ix->gscore.as<float>(), L, w, ix->sel.as<int32_t>(), ix->count.as<int32_t>());
+        hipLaunchKernelGGL(k_select_clusters, dim3((unsigned)nq), dim3(256), 0, s, ix->gscore.as<float>(), L, w, ix->sel.as<int32_t>(), ix->count.as<int32_t>(),
+                           ix->rank_in_bucket.as<int32_t>(), ix->count.as<int32_t>() + L, ix->qrank.as<int32_t>());
     }
     {
         Prof p(ix, K_SCAN);
-        hipLaunchKernelGGL(k_scan_buckets, dim3(1), dim3(1024), 0, s, ix->count.as<int32_t>(), ix->off, L, kUnitPairs, 32 * kChunkTiles, ix->bucket_off.as<int32_t>(), ix->tile_off.as<int32_t>(),
-                           ix->unit_off.as<int32_t>(), ix->cursor.as<int32_t>());
+        hipLaunchKernelGGL(k_scan_buckets, dim3(1), dim3(1024), 0, s, ix->count.as<int32_t>(), ix->count.as<int32_t>() + L, ix->off, L, kUnitPairs, 32 * kChunkTiles, ix->bucket_off.as<int32_t>(),
+                           ix->tile_off.as<int32_t>(), ix->unit_off.as<int32_t>(), ix->off0.as<int32_t>());
     }
     {
         Prof p(ix, K_SCATTER);
-        hipLaunchKernelGGL(k_scatter_pairs, dim3((unsigned)((npairs + 255) / 256)), dim3(256), 0, s, ix->sel.as<int32_t>(), npairs, ix->bucket_off.as<int32_t>(),
-                           ix->cursor.as<int32_t>(), ix->slot_of_pos.as<int32_t>(), ix->pos_of_slot.as<int32_t>(), ix->pmax.as<uint32_t>());
+        hipLaunchKernelGGL(k_scatter_pairs, dim3((unsigned)((npairs + 255) / 256)), dim3(256), 0, s, ix->sel.as<int32_t>(), npairs, w, ix->bucket_off.as<int32_t>(),
+                           ix->rank_in_bucket.as<int32_t>(), ix->off0.as<int32_t>(), ix->qrank.as<int32_t>(), ix->slot_of_pos.as<int32_t>(),
+                           ix->pos_of_slot.as<int32_t>(), ix->pmax.as<uint32_t>(), ix->qorder.as<int32_t>());
     }
     {
         Prof p(ix, K_STAGE_A);
@@ -277,13 +282,13 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
             qa.sel = ix->sel.as<int32_t>(); qa.pos_of_slot = ix->pos_of_slot.as<int32_t>(); qa.pmax = ix->pmax.as<uint32_t>();
             qa.Z = ix->Z.as<int8_t>(); qa.sigma = ix->sigma.as<float>(); qa.Bp = ix->Bp; qa.off = ix->off; qa.sqnorm = l2 ? ix->sqnorm : nullptr;
             qa.cand = ix->cand.as<int32_t>(); qa.tau = ix->tau.as<float>(); qa.n_kept = ix->n_kept.as<int32_t>();
-            qa.fb_list = ix->fb_list.as<int32_t>(); qa.fb_count = ix->count.as<int32_t>() + L; qa.w = w; qa.m = m;
+            qa.fb_list = ix->fb_list.as<int32_t>(); qa.fb_count = ix->count.as<int32_t>() + 2 * L; qa.w = w; qa.m = m;
             if (ks == 1) hipLaunchKernelGGL(k_select_query<2>, dim3((unsigned)nq), dim3(256), 0, s, qa);
             else hipLaunchKernelGGL(k_select_query<4>, dim3((unsigned)nq), dim3(256), 0, s, qa);
         }
         {
             Prof p(ix, K_SELECT_M);
-            sa_.qlist = ix->fb_list.as<int32_t>(); sa_.qcount = ix->count.as<int32_t>() + L;
+            sa_.qlist = ix->fb_list.as<int32_t>(); sa_.qcount = ix->count.as<int32_t>() + 2 * L;
             const unsigned grid = (unsigned)std::min<int64_t>(nq, 1024);
             if (r_pad == 32) hipLaunchKernelGGL(k_select_exact<2>, dim3(grid), dim3(256), 0, s, sa_, (int)nq);
             else hipLaunchKernelGGL(k_select_exact<4>, dim3(grid), dim3(256), 0, s, sa_, (int)nq);
@@ -294,12 +299,13 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
         const int mp2 = std::max(256, next_pow2(m));
         const size_t lds = (size_t)d * 4 + (size_t)mp2 * 12;
         const int32_t* cand = ix->cand.as<int32_t>();
+        const dim3 rgrid((unsigned)(8 * ((nq + 7) / 8)));
         if (ix->metric == LORANN_IP)
-            hipLaunchKernelGGL(k_rerank<0>, dim3((unsigned)nq), dim3(256), lds, s, dQ, ix->corpus, ix->ids, cand, d, m, mp2, k, d_ids, d_dists);
+            hipLaunchKernelGGL(k_rerank<0>, rgrid, dim3(256), lds, s, dQ, ix->corpus, ix->ids, cand, ix->qorder.as<int32_t>(), (int)nq, d, m, mp2, k, d_ids, d_dists);
         else if (ix->metric == LORANN_L2)
-            hipLaunchKernelGGL(k_rerank<1>, dim3((unsigned)nq), dim3(256), lds, s, dQ, ix->corpus, ix->ids, cand, d, m, mp2, k, d_ids, d_dists);
+            hipLaunchKernelGGL(k_rerank<1>, rgrid, dim3(256), lds, s, dQ, ix->corpus, ix->ids, cand, ix->qorder.as<int32_t>(), (int)nq, d, m, mp2, k, d_ids, d_dists);
         else
-            hipLaunchKernelGGL(k_rerank<2>, dim3((unsigned)nq), dim3(256), lds, s, dQ, ix->corpus, ix->ids, cand, d, m, mp2, k, d_ids, d_dists);
+            hipLaunchKernelGGL(k_rerank<2>, rgrid, dim3(256), lds, s, dQ, ix->corpus, ix->ids, cand, ix->qorder.as<int32_t>(), (int)nq, d, m, mp2, k, d_ids, d_dists);
     }
     HIP_TRY(hipGetLastError());
 
@@ -391,7 +397,7 @@ int search_impl(lorann_index* ix, const float* queries, int64_t nq, int32_t k, i
             prof_collect(ix);
             if (!ix->force_exact) {
                 int32_t fb = 0;
-                HIP_TRY(hipMemcpy(&fb, ix->count.as<int32_t>() + ix->L, 4, hipMemcpyDeviceToHost));
+                HIP_TRY(hipMemcpy(&fb, ix->count.as<int32_t>() + 2 * ix->L, 4, hipMemcpyDeviceToHost));
                 ix->prof_fallback_queries += fb;
             }
         }

@@ -15,11 +15,15 @@ __device__ __forceinline__ bool rr_less(float da, int64_t ia, float db, int64_t 
     return da < db || (da == db && ia < ib);
 }
 
-// grid = nq, block = 256, dynamic LDS = d*4 + mp2*(4 + 8) bytes (mp2 = power of two >= m, >= 256).
+// grid = 8 * ceil(nq / 8), block = 256, dynamic LDS = d*4 + mp2*(4 + 8) bytes (mp2 = power of two >= m, >= 256).
 // METRIC: 0 inner product, 1 squared Euclidean, 2 cosine.
+// Queries are taken in the order of `qorder` (grouped by nearest cluster: queries that share candidates run at
+// the same time, so a corpus row gathered for one of them is still in cache for the others), and consecutive
+// entries of that order go to the same XCD (workgroups are dealt round-robin over the 8 XCDs, each with its own L2).
 template <int METRIC>
 __global__ __launch_bounds__(256) void k_rerank(const float* __restrict__ Q, const float* __restrict__ corpus,
                                                  const int64_t* __restrict__ ids, const int32_t* __restrict__ cand,
+                                                 const int32_t* __restrict__ qorder, int nq,
                                                  int d, int m, int mp2, int k, int64_t* __restrict__ out_ids,
                                                  float* __restrict__ out_dists) {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -29,7 +33,10 @@ __global__ __launch_bounds__(256) void k_rerank(const float* __restrict__ Q, con
     __shared__ float s_qnorm;
 
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    const int64_t q = blockIdx.x;
+    const int per_xcd = (nq + 7) >> 3;
+    const int si = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
+    if (si >= nq) return;
+    const int64_t q = qorder[si];
     const float* qrow = Q + (size_t)q * d;
     for (int i = tid; i < d; i += 256) qs[i] = qrow[i];
     for (int t = tid; t < mp2; t += 256) { sdist[t] = INFINITY; sid[t] = kPadId; }

@@ -37,10 +37,13 @@ __global__ __launch_bounds__(256) void k_quantize_rows(const float* __restrict__
 // ---- Sec. 2.2: tau(x) = the w centroids of smallest dissimilarity. ----
 // One block (256 threads) per query.  g [nq][L] holds the centroid dissimilarities.  Exact selection by a
 // 4-pass radix select on order-preserving keys, ties at the threshold resolved toward the lower cluster id;
-// the result is written ordered (dissimilarity ascending, cluster id ascending) and every selected cluster's
-// pair counter is incremented (first step of the counting sort).
+// the result is written ordered (dissimilarity ascending, cluster id ascending).  First step of two counting
+// sorts: every selected cluster's pair counter is incremented and the old value kept as the pair's rank inside
+// its bucket; the same is done for the query itself under its nearest cluster (used to order the re-rank).
 __global__ __launch_bounds__(256) void k_select_clusters(const float* __restrict__ g, int L, int w,
-                                                          int32_t* __restrict__ sel, int32_t* __restrict__ count) {
+                                                          int32_t* __restrict__ sel, int32_t* __restrict__ count,
+                                                          int32_t* __restrict__ rank_in_bucket, int32_t* __restrict__ count0,
+                                                          int32_t* __restrict__ qrank) {
     __shared__ int hist[256];
     __shared__ int wsum[4];
     __shared__ uint32_t s_prefix;
@@ -110,7 +113,8 @@ __global__ __launch_bounds__(256) void k_select_clusters(const float* __restrict
             rank += (ku < k || (ku == k && iu < id)) ? 1 : 0;
         }
         sel[(size_t)blockIdx.x * w + rank] = id;
-        atomicAdd(&count[id], 1);
+        rank_in_bucket[(size_t)blockIdx.x * w + rank] = atomicAdd(&count[id], 1);
+        if (rank == 0) qrank[blockIdx.x] = atomicAdd(&count0[id], 1);
     }
 }
 
@@ -119,15 +123,15 @@ __global__ __launch_bounds__(256) void k_select_clusters(const float* __restrict
 // tile_off[c]    = number of 16-pair tiles of clusters < c                 (tile_off[L]   = number of tiles)
 // unit_off[c]    = number of scoring work items of clusters < c            (unit_off[L]   = number of items);
 //                  a cluster with a pairs and m_c points has ceil(a / unit_pairs) * ceil(m_c / chunk_points) items
-// Also clears the scatter cursors.
-__global__ __launch_bounds__(1024) void k_scan_buckets(const int32_t* __restrict__ count, const int64_t* __restrict__ off,
-                                                        int L, int unit_pairs, int chunk_points,
+// off0[c]        = number of queries whose nearest cluster is < c
+__global__ __launch_bounds__(1024) void k_scan_buckets(const int32_t* __restrict__ count, const int32_t* __restrict__ count0,
+                                                        const int64_t* __restrict__ off, int L, int unit_pairs, int chunk_points,
                                                         int32_t* __restrict__ bucket_off, int32_t* __restrict__ tile_off,
-                                                        int32_t* __restrict__ unit_off, int32_t* __restrict__ cursor) {
-    __shared__ int sa[1024], sb[1024], sc[1024];
-    __shared__ int carry_a, carry_b, carry_c;
+                                                        int32_t* __restrict__ unit_off, int32_t* __restrict__ off0) {
+    __shared__ int sa[1024], sb[1024], sc[1024], sd[1024];
+    __shared__ int carry_a, carry_b, carry_c, carry_d;
     const int tid = threadIdx.x;
-    if (tid == 0) { carry_a = 0; carry_b = 0; carry_c = 0; }
+    if (tid == 0) { carry_a = 0; carry_b = 0; carry_c = 0; carry_d = 0; }
     __syncthreads();
     for (int c0 = 0; c0 < L; c0 += 1024) {
         const int c = c0 + tid;
@@ -138,42 +142,45 @@ __global__ __launch_bounds__(1024) void k_scan_buckets(const int32_t* __restrict
             const int m_c = (int)(off[c + 1] - off[c]);
             u = ((a + unit_pairs - 1) / unit_pairs) * ((m_c + chunk_points - 1) / chunk_points);
         }
-        sa[tid] = a; sb[tid] = b; sc[tid] = u;
+        const int d0 = c < L ? count0[c] : 0;
+        sa[tid] = a; sb[tid] = b; sc[tid] = u; sd[tid] = d0;
         __syncthreads();
         for (int o = 1; o < 1024; o <<= 1) {
-            int ta = 0, tb = 0, tc = 0;
-            if (tid >= o) { ta = sa[tid - o]; tb = sb[tid - o]; tc = sc[tid - o]; }
+            int ta = 0, tb = 0, tc = 0, td = 0;
+            if (tid >= o) { ta = sa[tid - o]; tb = sb[tid - o]; tc = sc[tid - o]; td = sd[tid - o]; }
             __syncthreads();
-            sa[tid] += ta; sb[tid] += tb; sc[tid] += tc;
+            sa[tid] += ta; sb[tid] += tb; sc[tid] += tc; sd[tid] += td;
             __syncthreads();
         }
         if (c < L) {
             bucket_off[c] = carry_a + sa[tid] - a;
             tile_off[c] = carry_b + sb[tid] - b;
             unit_off[c] = carry_c + sc[tid] - u;
-            cursor[c] = 0;
+            off0[c] = carry_d + sd[tid] - d0;
         }
         __syncthreads();
-        if (tid == 1023) { carry_a += sa[1023]; carry_b += sb[1023]; carry_c += sc[1023]; }
+        if (tid == 1023) { carry_a += sa[1023]; carry_b += sb[1023]; carry_c += sc[1023]; carry_d += sd[1023]; }
         __syncthreads();
     }
     if (tid == 0) { bucket_off[L] = carry_a; tile_off[L] = carry_b; unit_off[L] = carry_c; }
 }
 
-// ---- Counting sort, step 3: place every pair (slot = query * w + rank) into its cluster's bucket. ----
-// The order inside a bucket is arbitrary (atomic cursor); no result depends on it.  Also clears the pair's
-// best-score key for the scoring kernels.
-__global__ __launch_bounds__(256) void k_scatter_pairs(const int32_t* __restrict__ sel, int64_t npairs,
-                                                        const int32_t* __restrict__ bucket_off, int32_t* __restrict__ cursor,
+// ---- Counting sort, step 3: place every pair (slot = query * w + rank) into its cluster's bucket, at the rank
+// it drew in step 1 (the order inside a bucket is arbitrary; no result depends on it).  Also clears the pair's
+// best-score key for the scoring kernels, and places every query into the list ordered by nearest cluster.
+__global__ __launch_bounds__(256) void k_scatter_pairs(const int32_t* __restrict__ sel, int64_t npairs, int w,
+                                                        const int32_t* __restrict__ bucket_off, const int32_t* __restrict__ rank_in_bucket,
+                                                        const int32_t* __restrict__ off0, const int32_t* __restrict__ qrank,
                                                         int32_t* __restrict__ slot_of_pos, int32_t* __restrict__ pos_of_slot,
-                                                        uint32_t* __restrict__ pmax) {
+                                                        uint32_t* __restrict__ pmax, int32_t* __restrict__ qorder) {
     const int64_t p = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (p >= npairs) return;
     const int c = sel[p];
-    const int pos = bucket_off[c] + atomicAdd(&cursor[c], 1);
+    const int pos = bucket_off[c] + rank_in_bucket[p];
     slot_of_pos[pos] = (int32_t)p;
     pos_of_slot[p] = pos;
     pmax[p] = 0u;
+    if (p % w == 0) { const int q = (int)(p / w); qorder[off0[c] + qrank[q]] = q; }
 }
 
 __global__ void k_zero_i32(int32_t* __restrict__ p, int64_t n) {
