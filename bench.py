@@ -61,6 +61,8 @@ def main():
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (development only)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target duration of the oracle baseline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run a plain 1 GiB elementwise copy (calibrates the HBM byte counters under rocprofv3 --pmc)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (query-sharded data parallelism would "
@@ -178,6 +180,14 @@ def main():
                         "ids_equal": float(np.mean(o_ids == ids_h[:n_s])),
                         "max_rel_dist_err": float(np.max(np.abs(o_d - dists_h[:n_s]) / np.maximum(np.abs(o_d), 1e-3)))}
         log(f"[bench] oracle baseline done in {time.time() - t0:.1f}s")
+
+    if args.copy_probe:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)      # 1 GiB read + 1 GiB written per launch
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.mul(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
 
     metric_names = {0: "inner product", 1: "squared Euclidean", 2: "cosine"}
     res = {

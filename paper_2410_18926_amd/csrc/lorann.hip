@@ -74,9 +74,9 @@ struct DevBuf {
     template <typename T> T* as() const { return reinterpret_cast<T*>(p); }
 };
 
-enum KernelId { K_PROJECT, K_QUANTIZE, K_CENTROID, K_SELECT_W, K_SCAN, K_SCATTER, K_STAGE_A, K_PAIR_MAX, K_SELECT_QUERY, K_SELECT_M, K_RERANK, K_ZERO, K_COUNT };
+enum KernelId { K_PROJECT, K_QUANTIZE, K_CENTROID, K_SELECT_W, K_BUCKET_COUNT, K_SCAN, K_SCATTER, K_STAGE_A, K_PAIR_MAX, K_SELECT_QUERY, K_SELECT_M, K_RERANK, K_ZERO, K_COUNT };
 const char* const kKernelNames[K_COUNT] = {"project_f64", "quantize_rows", "centroid_dissim_f64", "select_clusters",
-                                            "scan_buckets", "scatter_pairs", "stage_a_i8", "pair_max_i8", "select_query", "score_select_exact",
+                                            "bucket_count", "scan_buckets", "scatter_pairs", "stage_a_i8", "pair_max_i8", "select_query", "score_select_exact",
                                             "rerank", "zero_counters"};
 
 struct EventPair { hipEvent_t a, b; int kid; };
@@ -99,7 +99,7 @@ struct lorann_index {
     int64_t* ids = nullptr;         // [n] or NULL
     float* sqnorm = nullptr;        // [n] (Euclidean)
     // workspace (device), sized for `chunk` queries
-    DevBuf qproj, q8, dx, gscore, sel, count, rank_in_bucket, qrank, qorder, off0, bucket_off, tile_off, unit_off, slot_of_pos, pos_of_slot, Z, sigma, cand;
+    DevBuf qproj, q8, dx, gscore, sel, count, rank_in_bucket, qrank, qorder, off0, base_tab, bucket_off, tile_off, unit_off, slot_of_pos, pos_of_slot, Z, sigma, cand;
     DevBuf tau, n_kept, fb_list, pmax;
     int32_t force_exact = 0;        // 1: score + select with the per-query kernel only (verification)
     DevBuf stage_q, stage_ids, stage_dists;   // staging when the caller passes host memory
@@ -116,7 +116,7 @@ namespace {
 void free_all(lorann_index* ix) {
     void* ptrs[] = {ix->centroids, ix->cent_sqnorm, ix->Pt, ix->A, ix->Bp, ix->sA, ix->sB, ix->off, ix->corpus, ix->ids, ix->sqnorm};
     for (void* p : ptrs) if (p) (void)hipFree(p);
-    DevBuf* bufs[] = {&ix->qproj, &ix->q8, &ix->dx, &ix->gscore, &ix->sel, &ix->count, &ix->rank_in_bucket, &ix->qrank, &ix->qorder, &ix->off0, &ix->bucket_off, &ix->tile_off,
+    DevBuf* bufs[] = {&ix->qproj, &ix->q8, &ix->dx, &ix->gscore, &ix->sel, &ix->count, &ix->rank_in_bucket, &ix->qrank, &ix->qorder, &ix->off0, &ix->base_tab, &ix->bucket_off, &ix->tile_off,
                       &ix->unit_off, &ix->slot_of_pos, &ix->pos_of_slot, &ix->Z, &ix->sigma, &ix->cand, &ix->tau,
                       &ix->n_kept, &ix->fb_list, &ix->pmax, &ix->stage_q, &ix->stage_ids, &ix->stage_dists};
     for (DevBuf* b : bufs) b->release();
@@ -223,8 +223,27 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
     }
     {
         Prof p(ix, K_SELECT_W);
-        hipLaunchKernelGGL(k_select_clusters, dim3((unsigned)nq), dim3(256), 0, s, ix->gscore.as<float>(), L, w, ix->sel.as<int32_t>(), ix->count.as<int32_t>(),
-                           ix->rank_in_bucket.as<int32_t>(), ix->count.as<int32_t>() + L, ix->qrank.as<int32_t>());
+        if (L <= 1024)
+            hipLaunchKernelGGL(k_select_clusters_wave<16>, dim3((unsigned)((nq + 3) / 4)), dim3(256), 0, s, ix->gscore.as<float>(), (int)nq, L, w, ix->sel.as<int32_t>());
+        else if (L <= 4096)
+            hipLaunchKernelGGL(k_select_clusters_wave<64>, dim3((unsigned)((nq + 3) / 4)), dim3(256), 0, s, ix->gscore.as<float>(), (int)nq, L, w, ix->sel.as<int32_t>());
+        else
+            hipLaunchKernelGGL(k_select_clusters, dim3((unsigned)nq), dim3(256), 0, s, ix->gscore.as<float>(), L, w, ix->sel.as<int32_t>());
+    }
+    const bool lds_hist = (size_t)L * 8 <= 64 * 1024;
+    const int nbb = (int)((nq + kBucketQueries - 1) / kBucketQueries);
+    if (lds_hist && (rc = ix->base_tab.reserve((size_t)2 * nbb * L * 4))) return rc;
+    int32_t* base_tab = lds_hist ? ix->base_tab.as<int32_t>() : nullptr;
+    int32_t* base0_tab = lds_hist ? base_tab + (size_t)nbb * L : nullptr;
+    {
+        Prof p(ix, K_BUCKET_COUNT);
+        int32_t* cnt = ix->count.as<int32_t>();
+        if (lds_hist)
+            hipLaunchKernelGGL(k_bucket_count, dim3((unsigned)nbb), dim3(1024), (size_t)L * 8, s, ix->sel.as<int32_t>(), (int)nq, w, L, cnt, cnt + L,
+                               ix->rank_in_bucket.as<int32_t>(), ix->qrank.as<int32_t>(), base_tab, base0_tab);
+        else
+            hipLaunchKernelGGL(k_bucket_count_global, dim3((unsigned)((npairs + 255) / 256)), dim3(256), 0, s, ix->sel.as<int32_t>(), npairs, w, cnt, cnt + L,
+                               ix->rank_in_bucket.as<int32_t>(), ix->qrank.as<int32_t>());
     }
     {
         Prof p(ix, K_SCAN);
@@ -233,8 +252,8 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
     }
     {
         Prof p(ix, K_SCATTER);
-        hipLaunchKernelGGL(k_scatter_pairs, dim3((unsigned)((npairs + 255) / 256)), dim3(256), 0, s, ix->sel.as<int32_t>(), npairs, w, ix->bucket_off.as<int32_t>(),
-                           ix->rank_in_bucket.as<int32_t>(), ix->off0.as<int32_t>(), ix->qrank.as<int32_t>(), ix->slot_of_pos.as<int32_t>(),
+        hipLaunchKernelGGL(k_scatter_pairs, dim3((unsigned)((npairs + 255) / 256)), dim3(256), 0, s, ix->sel.as<int32_t>(), npairs, w, L, ix->bucket_off.as<int32_t>(),
+                           ix->rank_in_bucket.as<int32_t>(), ix->off0.as<int32_t>(), ix->qrank.as<int32_t>(), base_tab, base0_tab, ix->slot_of_pos.as<int32_t>(),
                            ix->pos_of_slot.as<int32_t>(), ix->pmax.as<uint32_t>(), ix->qorder.as<int32_t>());
     }
     {

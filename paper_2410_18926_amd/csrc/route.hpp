@@ -37,13 +37,9 @@ __global__ __launch_bounds__(256) void k_quantize_rows(const float* __restrict__
 // ---- Sec. 2.2: tau(x) = the w centroids of smallest dissimilarity. ----
 // One block (256 threads) per query.  g [nq][L] holds the centroid dissimilarities.  Exact selection by a
 // 4-pass radix select on order-preserving keys, ties at the threshold resolved toward the lower cluster id;
-// the result is written ordered (dissimilarity ascending, cluster id ascending).  First step of two counting
-// sorts: every selected cluster's pair counter is incremented and the old value kept as the pair's rank inside
-// its bucket; the same is done for the query itself under its nearest cluster (used to order the re-rank).
+// the result is written ordered (dissimilarity ascending, cluster id ascending).
 __global__ __launch_bounds__(256) void k_select_clusters(const float* __restrict__ g, int L, int w,
-                                                          int32_t* __restrict__ sel, int32_t* __restrict__ count,
-                                                          int32_t* __restrict__ rank_in_bucket, int32_t* __restrict__ count0,
-                                                          int32_t* __restrict__ qrank) {
+                                                          int32_t* __restrict__ sel) {
     __shared__ int hist[256];
     __shared__ int wsum[4];
     __shared__ uint32_t s_prefix;
@@ -113,9 +109,137 @@ __global__ __launch_bounds__(256) void k_select_clusters(const float* __restrict
             rank += (ku < k || (ku == k && iu < id)) ? 1 : 0;
         }
         sel[(size_t)blockIdx.x * w + rank] = id;
-        rank_in_bucket[(size_t)blockIdx.x * w + rank] = atomicAdd(&count[id], 1);
-        if (rank == 0) qrank[blockIdx.x] = atomicAdd(&count0[id], 1);
     }
+}
+
+// Same selection, one WAVEFRONT per query with the L keys held in registers (KPL keys per lane, L <= 64 * KPL):
+// no re-reading of the scores and no block barriers.  4-pass radix select with a wavefront-private LDS
+// histogram; ties at the threshold go to the lower cluster id; ordered output.
+// grid = ceil(nq / 4), block = 256 (4 queries per block).
+template <int KPL>
+__global__ __launch_bounds__(256) void k_select_clusters_wave(const float* __restrict__ g, int nq, int L, int w,
+                                                               int32_t* __restrict__ sel) {
+    __shared__ int hist[4][256];
+    __shared__ uint32_t selk[4][256];
+    __shared__ int seli[4][256];
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int q = blockIdx.x * 4 + wv;
+    if (q >= nq) return;                       // wavefronts are independent: no block barrier below
+    const float* row = g + (size_t)q * L;
+    uint32_t key[KPL];                         // element l = 64 * i + lane
+#pragma unroll
+    for (int i = 0; i < KPL; ++i) {
+        const int l = 64 * i + lane;
+        key[i] = l < L ? float_key_asc(row[l]) : 0xFFFFFFFFu;     // padding sorts last (and is never selected: w <= L)
+    }
+    uint32_t prefix = 0u, mask = 0u;
+    int need = w;
+    for (int shift = 24; shift >= 0; shift -= 8) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront"); __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int b = 0; b < 4; ++b) hist[wv][lane + 64 * b] = 0;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront"); __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int i = 0; i < KPL; ++i)
+            if (64 * i + lane < L && (key[i] & mask) == prefix) atomicAdd(&hist[wv][(key[i] >> shift) & 255u], 1);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront"); __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        const int h0 = hist[wv][4 * lane], h1 = hist[wv][4 * lane + 1], h2 = hist[wv][4 * lane + 2], h3 = hist[wv][4 * lane + 3];
+        const int mine = h0 + h1 + h2 + h3;
+        int incl = mine;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) { const int t = __shfl_up(incl, o, 64); if (lane >= o) incl += t; }
+        const int excl = incl - mine;
+        const bool owner = excl < need && incl >= need;
+        int cum = excl, dgt = 4 * lane;
+        if (owner) {
+            if (cum + h0 >= need) { }
+            else { cum += h0; if (cum + h1 >= need) { dgt += 1; } else { cum += h1; if (cum + h2 >= need) { dgt += 2; } else { cum += h2; dgt += 3; } } }
+        }
+        const int src = __ffsll((unsigned long long)__ballot(owner)) - 1;      // exactly one owner lane
+        dgt = __shfl(dgt, src, 64);
+        cum = __shfl(cum, src, 64);
+        prefix |= (uint32_t)dgt << shift;
+        need -= cum;
+        mask |= 255u << shift;
+    }
+    // prefix = key of the w-th smallest; `need` of the keys equal to it are taken, lowest cluster id first
+    const uint32_t T = prefix;
+    int n_out = 0, ties_left = need;
+#pragma unroll
+    for (int i = 0; i < KPL; ++i) {
+        const int l = 64 * i + lane;
+        const bool in = l < L;
+        const bool less = in && key[i] < T;
+        const bool tie = in && key[i] == T;
+        const unsigned long long ml = __ballot(less), mt = __ballot(tie);
+        const unsigned long long below = (1ull << lane) - 1ull;
+        if (less) { const int p = n_out + __popcll(ml & below); selk[wv][p] = key[i]; seli[wv][p] = l; }
+        n_out += __popcll(ml);
+        const int trank = __popcll(mt & below);
+        if (tie && trank < ties_left) { const int p = n_out + trank; selk[wv][p] = key[i]; seli[wv][p] = l; }
+        const int took = min(ties_left, __popcll(mt));
+        n_out += took;
+        ties_left -= took;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront"); __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    for (int t = lane; t < w; t += 64) {       // order the w selected by (key, id): rank by counting
+        const uint32_t k = selk[wv][t];
+        const int id = seli[wv][t];
+        int rank = 0;
+        for (int u = 0; u < w; ++u) {
+            const uint32_t ku = selk[wv][u];
+            const int iu = seli[wv][u];
+            rank += (ku < k || (ku == k && iu < id)) ? 1 : 0;
+        }
+        sel[(size_t)q * w + rank] = id;
+    }
+}
+
+// ---- Counting sort, step 1: count the pairs of every cluster. ----
+// Two sorts share the machinery: (query, cluster) pairs by cluster, and queries by their nearest cluster (the
+// order in which the re-rank visits them).  Each block takes kBucketQueries queries, histograms their pairs in
+// LDS (the old value of the LDS counter is the pair's rank among the block's pairs of that cluster), then adds
+// each non-zero LDS count to the global counter once; the value that add returns is the block's offset inside
+// the cluster's bucket.  Global atomics per cluster drop from one per pair to one per block.
+// grid = ceil(nq / kBucketQueries), block = 1024, dynamic LDS = 8 * L bytes.
+constexpr int kBucketQueries = 256;
+__global__ __launch_bounds__(1024) void k_bucket_count(const int32_t* __restrict__ sel, int nq, int w, int L,
+                                                        int32_t* __restrict__ count, int32_t* __restrict__ count0,
+                                                        int32_t* __restrict__ rank_in_bucket, int32_t* __restrict__ qrank,
+                                                        int32_t* __restrict__ base_tab, int32_t* __restrict__ base0_tab) {
+    extern __shared__ int lh[];          // [L] pairs per cluster, [L] nearest-cluster queries per cluster
+    int* lh0 = lh + L;
+    const int tid = threadIdx.x;
+    for (int c = tid; c < 2 * L; c += 1024) lh[c] = 0;
+    __syncthreads();
+    const int q0 = blockIdx.x * kBucketQueries;
+    const int q1 = min(nq, q0 + kBucketQueries);
+    const int64_t p0 = (int64_t)q0 * w, p1 = (int64_t)q1 * w;
+    for (int64_t p = p0 + tid; p < p1; p += 1024) {
+        const int c = sel[p];
+        rank_in_bucket[p] = atomicAdd(&lh[c], 1);
+        if (p % w == 0) qrank[p / w] = atomicAdd(&lh0[c], 1);
+    }
+    __syncthreads();
+    for (int c = tid; c < L; c += 1024) {
+        const int n = lh[c], n0 = lh0[c];
+        base_tab[(size_t)blockIdx.x * L + c] = n ? atomicAdd(&count[c], n) : 0;
+        base0_tab[(size_t)blockIdx.x * L + c] = n0 ? atomicAdd(&count0[c], n0) : 0;
+    }
+}
+
+// The same without LDS histograms (cluster counts too large for LDS): one global atomic per pair.
+// grid = ceil(npairs / 256), block = 256.  The block offsets are all zero.
+__global__ __launch_bounds__(256) void k_bucket_count_global(const int32_t* __restrict__ sel, int64_t npairs, int w,
+                                                              int32_t* __restrict__ count, int32_t* __restrict__ count0,
+                                                              int32_t* __restrict__ rank_in_bucket, int32_t* __restrict__ qrank) {
+    const int64_t p = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (p >= npairs) return;
+    const int c = sel[p];
+    rank_in_bucket[p] = atomicAdd(&count[c], 1);
+    if (p % w == 0) qrank[p / w] = atomicAdd(&count0[c], 1);
 }
 
 // ---- Counting sort, step 2: exclusive scans over the clusters (single block of 1024 threads). ----
@@ -165,22 +289,26 @@ __global__ __launch_bounds__(1024) void k_scan_buckets(const int32_t* __restrict
     if (tid == 0) { bucket_off[L] = carry_a; tile_off[L] = carry_b; unit_off[L] = carry_c; }
 }
 
-// ---- Counting sort, step 3: place every pair (slot = query * w + rank) into its cluster's bucket, at the rank
-// it drew in step 1 (the order inside a bucket is arbitrary; no result depends on it).  Also clears the pair's
-// best-score key for the scoring kernels, and places every query into the list ordered by nearest cluster.
-__global__ __launch_bounds__(256) void k_scatter_pairs(const int32_t* __restrict__ sel, int64_t npairs, int w,
+// ---- Counting sort, step 3: place every pair (slot = query * w + rank) into its cluster's bucket, at
+// bucket start + offset of its block + its rank inside the block (the order inside a bucket is arbitrary; no
+// result depends on it).  Also clears the pair's best-score key for the scoring kernels, and places every query
+// into the list ordered by nearest cluster.  base_tab == NULL: ranks are already bucket-wide.
+__global__ __launch_bounds__(256) void k_scatter_pairs(const int32_t* __restrict__ sel, int64_t npairs, int w, int L,
                                                         const int32_t* __restrict__ bucket_off, const int32_t* __restrict__ rank_in_bucket,
                                                         const int32_t* __restrict__ off0, const int32_t* __restrict__ qrank,
+                                                        const int32_t* __restrict__ base_tab, const int32_t* __restrict__ base0_tab,
                                                         int32_t* __restrict__ slot_of_pos, int32_t* __restrict__ pos_of_slot,
                                                         uint32_t* __restrict__ pmax, int32_t* __restrict__ qorder) {
     const int64_t p = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (p >= npairs) return;
     const int c = sel[p];
-    const int pos = bucket_off[c] + rank_in_bucket[p];
+    const int q = (int)(p / w);
+    const size_t tb = (size_t)(q / kBucketQueries) * L + c;
+    const int pos = bucket_off[c] + (base_tab ? base_tab[tb] : 0) + rank_in_bucket[p];
     slot_of_pos[pos] = (int32_t)p;
     pos_of_slot[p] = pos;
     pmax[p] = 0u;
-    if (p % w == 0) { const int q = (int)(p / w); qorder[off0[c] + qrank[q]] = q; }
+    if (p % w == 0) qorder[off0[c] + (base0_tab ? base0_tab[tb] : 0) + qrank[q]] = q;
 }
 
 __global__ void k_zero_i32(int32_t* __restrict__ p, int64_t n) {

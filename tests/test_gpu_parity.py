@@ -219,3 +219,33 @@ def test_mixed_batch_some_queries_fall_back(B, small_indexes):
                                       err_msg=f"k={k} w={w} m={m}")
         assert_topk_equal(g_ids, g_d, o_ids, o_d, f"k={k} w={w} m={m}")
     gix.close()
+
+
+@pytest.mark.parametrize("L", [1500, 4500])
+def test_many_clusters_routing_variants(B, L):
+    """Cluster counts that take the other routing kernels (keys in 64 registers per lane; block-wide select),
+    with duplicate centroids so that ties at the w-th place occur."""
+    rng = np.random.default_rng(L)
+    d, r, n, w = 32, 8, 3 * L, 40
+    corpus = rng.normal(size=(n, d)).astype(np.float32)
+    cent = rng.normal(size=(L, d)).astype(np.float32)
+    cent[L // 2:L // 2 + 300] = cent[:300]                     # exact ties between cluster pairs
+    sizes = rng.integers(0, 7, size=L)
+    sizes[-1] += n - sizes.sum()
+    assert sizes[-1] >= 0
+    off = np.zeros(L + 1, np.int64)
+    np.cumsum(sizes, out=off[1:])
+    ix = dict(metric=1, n=n, d=d, dp=d, r=r, L=L, centroids=cent, P=None,
+              A=rng.integers(-127, 128, size=(L, r, d)).astype(np.int8), B=rng.integers(-127, 128, size=(n, r)).astype(np.int8),
+              scale_A=rng.uniform(0.01, 0.1, L).astype(np.float32), scale_B=rng.uniform(0.01, 0.1, L).astype(np.float32),
+              cluster_offsets=off, corpus=corpus, ids=None)
+    q = rng.normal(size=(50, d)).astype(np.float32)
+    gix = B.Index(**ix)
+    oix = O.OracleIndex(ix)
+    o_ids, o_d, ost = O.search(oix, q, 10, w, 60, stages=True)
+    g_ids, g_d, gst = gix.search_stages(q, 10, w, 60)
+    np.testing.assert_array_equal(gst["sel"], ost["sel"])
+    np.testing.assert_array_equal(gst["z"], ost["z"])
+    np.testing.assert_array_equal(np.sort(gst["cand_rows"].astype(np.int64), axis=1), np.sort(ost["cand_rows"], axis=1))
+    assert_topk_equal(g_ids, g_d, o_ids, o_d, f"L={L}")
+    gix.close()
