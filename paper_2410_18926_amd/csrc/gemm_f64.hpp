@@ -10,15 +10,17 @@
 // Register layout of v_mfma_f64_16x16x4_f64 (measured on gfx950): A operand lane l holds A[l%16][l/16],
 // B operand lane l holds B[l/16][l%16], result register v of lane l holds D[4v + l/16][l%16].
 #pragma once
+#include <cmath>
+
 #include "common.hpp"
 
 namespace lorann {
 
 enum { EPI_PLAIN = 0, EPI_NEG = 1, EPI_L2 = 2 };
 
-constexpr int GM_BM = 64, GM_BN = 64, GM_KT = 16, GM_LD = GM_KT + 1;
+constexpr int GM_BN = 64, GM_KT = 16, GM_LD = GM_KT + 1;
 
-// One operand tile (64 rows x 16 k) is fetched by 256 threads as one float4 each.
+// One operand tile (rows x 16 k) is fetched as one float4 per thread.
 __device__ __forceinline__ float4 gemm_fetch(const float* __restrict__ base, int rows, int K, int row, int k, bool vec_ok) {
     float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
     if (row < rows) {
@@ -35,62 +37,70 @@ __device__ __forceinline__ float4 gemm_fetch(const float* __restrict__ base, int
     return v;
 }
 
-// grid = (ceil(N/64), ceil(M/64)), block = 256.  X [M][K], W [N][K] row-major, out [M][N].
-// nrm [N] (double) is used by EPI_L2 only: out = nrm[n] - 2 * acc.
-template <int EPI>
+// grid = (ceil(N/64), ceil(M/BM)), block = 256 (2 x 2 wavefronts, each BM/2 x 32 of the BM x 64 block tile).
+// BM = 64 or 32: the smaller tile is used when it fills the machine more evenly (see gemm_pick_bm).
+// X [M][K], W [N][K] row-major, out [M][N].  nrm [N] (double) is used by EPI_L2 only: out = nrm[n] - 2 * acc.
+template <int EPI, int BM>
 __global__ __launch_bounds__(256) void k_gemm_nt_f64(const float* __restrict__ X, const float* __restrict__ W,
                                                       float* __restrict__ out, const double* __restrict__ nrm,
                                                       int M, int N, int K) {
-    __shared__ float Xs[GM_BM * GM_LD];
+    constexpr int TI = BM / 32;          // 16-row MFMA tiles per wavefront along M
+    __shared__ float Xs[BM * GM_LD];
     __shared__ float Ws[GM_BN * GM_LD];
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int wm = wv >> 1, wn = wv & 1;
-    const int m0 = blockIdx.y * GM_BM, n0 = blockIdx.x * GM_BN;
+    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * GM_BN;
     const int lrow = tid >> 2, lk = (tid & 3) * 4;
     const bool vec_ok = (K % 4) == 0;
+    const bool x_loader = lrow < BM;
 
-    f64x4 acc[2][2];
+    f64x4 acc[TI][2];
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int a = 0; a < TI; ++a)
 #pragma unroll
         for (int b = 0; b < 2; ++b) acc[a][b] = (f64x4){0.0, 0.0, 0.0, 0.0};
 
-    float4 rx = gemm_fetch(X, M, K, m0 + lrow, lk, vec_ok);
+    float4 rx = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (x_loader) rx = gemm_fetch(X, M, K, m0 + lrow, lk, vec_ok);
     float4 rw = gemm_fetch(W, N, K, n0 + lrow, lk, vec_ok);
     const int i = lane & 15, g = lane >> 4;
 
     for (int k0 = 0; k0 < K; k0 += GM_KT) {
-        float* xs = Xs + lrow * GM_LD + lk;
+        if (x_loader) {
+            float* xs = Xs + lrow * GM_LD + lk;
+            xs[0] = rx.x; xs[1] = rx.y; xs[2] = rx.z; xs[3] = rx.w;
+        }
         float* ws = Ws + lrow * GM_LD + lk;
-        xs[0] = rx.x; xs[1] = rx.y; xs[2] = rx.z; xs[3] = rx.w;
         ws[0] = rw.x; ws[1] = rw.y; ws[2] = rw.z; ws[3] = rw.w;
         __syncthreads();
         if (k0 + GM_KT < K) {
-            rx = gemm_fetch(X, M, K, m0 + lrow, k0 + GM_KT + lk, vec_ok);
+            if (x_loader) rx = gemm_fetch(X, M, K, m0 + lrow, k0 + GM_KT + lk, vec_ok);
             rw = gemm_fetch(W, N, K, n0 + lrow, k0 + GM_KT + lk, vec_ok);
         }
 #pragma unroll
         for (int kk = 0; kk < GM_KT; kk += 4) {
-            const double a0 = (double)Xs[(wm * 32 + i) * GM_LD + kk + g];
-            const double a1 = (double)Xs[(wm * 32 + 16 + i) * GM_LD + kk + g];
+            double a[TI];
+#pragma unroll
+            for (int ti = 0; ti < TI; ++ti) a[ti] = (double)Xs[(wm * (BM / 2) + ti * 16 + i) * GM_LD + kk + g];
             const double b0 = (double)Ws[(wn * 32 + i) * GM_LD + kk + g];
             const double b1 = (double)Ws[(wn * 32 + 16 + i) * GM_LD + kk + g];
-            acc[0][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b0, acc[0][0], 0, 0, 0);
-            acc[0][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b1, acc[0][1], 0, 0, 0);
-            acc[1][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b0, acc[1][0], 0, 0, 0);
-            acc[1][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b1, acc[1][1], 0, 0, 0);
+#pragma unroll
+            for (int ti = 0; ti < TI; ++ti) {
+                acc[ti][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[ti], b0, acc[ti][0], 0, 0, 0);
+                acc[ti][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[ti], b1, acc[ti][1], 0, 0, 0);
+            }
         }
         __syncthreads();
     }
 
 #pragma unroll
-    for (int ti = 0; ti < 2; ++ti)
+    for (int ti = 0; ti < TI; ++ti)
 #pragma unroll
         for (int tj = 0; tj < 2; ++tj) {
             const int col = n0 + wn * 32 + tj * 16 + i;
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                const int row = m0 + wm * 32 + ti * 16 + 4 * v + g;
+                const int row = m0 + wm * (BM / 2) + ti * 16 + 4 * v + g;
                 if (row < M && col < N) {
                     const double s = acc[ti][tj][v];
                     float o;
@@ -101,6 +111,15 @@ __global__ __launch_bounds__(256) void k_gemm_nt_f64(const float* __restrict__ X
                 }
             }
         }
+}
+
+// Tile height that loads the 256 CUs more evenly: the workgroups of this kernel are bound by the matrix cores
+// of their CU, so the time follows the largest number of workgroups any CU receives.
+inline int gemm_pick_bm(long M, long N) {
+    const double t64 = (double)((M + 63) / 64) * (double)((N + 63) / 64) / 256.0;
+    const double t32 = (double)((M + 31) / 32) * (double)((N + 63) / 64) / 256.0;
+    const double e64 = t64 / std::ceil(t64), e32 = t32 / std::ceil(t32);
+    return e32 > e64 + 0.05 ? 32 : 64;
 }
 
 // out[row] = sum_i x[row][i]^2 accumulated in double; one wavefront per row.  OUT = float or double.

@@ -201,8 +201,10 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
     const float* qp = dQ;   // projected queries
     if (ix->Pt) {
         Prof p(ix, K_PROJECT);
-        dim3 grid((dp + GM_BN - 1) / GM_BN, (unsigned)((nq + GM_BM - 1) / GM_BM));
-        hipLaunchKernelGGL(k_gemm_nt_f64<EPI_PLAIN>, grid, dim3(256), 0, s, dQ, ix->Pt, ix->qproj.as<float>(), (const double*)nullptr, (int)nq, dp, d);
+        if (gemm_pick_bm(nq, dp) == 64)
+            hipLaunchKernelGGL((k_gemm_nt_f64<EPI_PLAIN, 64>), dim3((dp + 63) / 64, (unsigned)((nq + 63) / 64)), dim3(256), 0, s, dQ, ix->Pt, ix->qproj.as<float>(), (const double*)nullptr, (int)nq, dp, d);
+        else
+            hipLaunchKernelGGL((k_gemm_nt_f64<EPI_PLAIN, 32>), dim3((dp + 63) / 64, (unsigned)((nq + 31) / 32)), dim3(256), 0, s, dQ, ix->Pt, ix->qproj.as<float>(), (const double*)nullptr, (int)nq, dp, d);
         qp = ix->qproj.as<float>();
     }
     {
@@ -215,11 +217,16 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
     }
     {
         Prof p(ix, K_CENTROID);
-        dim3 grid((L + GM_BN - 1) / GM_BN, (unsigned)((nq + GM_BM - 1) / GM_BM));
-        if (ix->metric == LORANN_L2)
-            hipLaunchKernelGGL(k_gemm_nt_f64<EPI_L2>, grid, dim3(256), 0, s, qp, ix->centroids, ix->gscore.as<float>(), (const double*)ix->cent_sqnorm, (int)nq, L, dp);
-        else
-            hipLaunchKernelGGL(k_gemm_nt_f64<EPI_NEG>, grid, dim3(256), 0, s, qp, ix->centroids, ix->gscore.as<float>(), (const double*)nullptr, (int)nq, L, dp);
+        const bool big = gemm_pick_bm(nq, L) == 64;
+        const dim3 grid((L + 63) / 64, (unsigned)(big ? (nq + 63) / 64 : (nq + 31) / 32));
+        float* gs = ix->gscore.as<float>();
+        if (ix->metric == LORANN_L2) {
+            if (big) hipLaunchKernelGGL((k_gemm_nt_f64<EPI_L2, 64>), grid, dim3(256), 0, s, qp, ix->centroids, gs, (const double*)ix->cent_sqnorm, (int)nq, L, dp);
+            else hipLaunchKernelGGL((k_gemm_nt_f64<EPI_L2, 32>), grid, dim3(256), 0, s, qp, ix->centroids, gs, (const double*)ix->cent_sqnorm, (int)nq, L, dp);
+        } else {
+            if (big) hipLaunchKernelGGL((k_gemm_nt_f64<EPI_NEG, 64>), grid, dim3(256), 0, s, qp, ix->centroids, gs, (const double*)nullptr, (int)nq, L, dp);
+            else hipLaunchKernelGGL((k_gemm_nt_f64<EPI_NEG, 32>), grid, dim3(256), 0, s, qp, ix->centroids, gs, (const double*)nullptr, (int)nq, L, dp);
+        }
     }
     {
         Prof p(ix, K_SELECT_W);
@@ -301,9 +308,10 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
             qa.sel = ix->sel.as<int32_t>(); qa.pos_of_slot = ix->pos_of_slot.as<int32_t>(); qa.pmax = ix->pmax.as<uint32_t>();
             qa.Z = ix->Z.as<int8_t>(); qa.sigma = ix->sigma.as<float>(); qa.Bp = ix->Bp; qa.off = ix->off; qa.sqnorm = l2 ? ix->sqnorm : nullptr;
             qa.cand = ix->cand.as<int32_t>(); qa.tau = ix->tau.as<float>(); qa.n_kept = ix->n_kept.as<int32_t>();
-            qa.fb_list = ix->fb_list.as<int32_t>(); qa.fb_count = ix->count.as<int32_t>() + 2 * L; qa.w = w; qa.m = m;
-            if (ks == 1) hipLaunchKernelGGL(k_select_query<2>, dim3((unsigned)nq), dim3(256), 0, s, qa);
-            else hipLaunchKernelGGL(k_select_query<4>, dim3((unsigned)nq), dim3(256), 0, s, qa);
+            qa.fb_list = ix->fb_list.as<int32_t>(); qa.fb_count = ix->count.as<int32_t>() + 2 * L; qa.w = w; qa.m = m; qa.cap = select_query_cap(m);
+            const size_t qlds = (size_t)qa.cap * 8;
+            if (ks == 1) hipLaunchKernelGGL(k_select_query<2>, dim3((unsigned)nq), dim3(256), qlds, s, qa);
+            else hipLaunchKernelGGL(k_select_query<4>, dim3((unsigned)nq), dim3(256), qlds, s, qa);
         }
         {
             Prof p(ix, K_SELECT_M);

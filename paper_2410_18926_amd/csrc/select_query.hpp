@@ -63,8 +63,9 @@ __device__ __forceinline__ float key_to_float(uint32_t key) {   // inverse of fl
     return __uint_as_float((key & 0x80000000u) ? (key & 0x7fffffffu) : ~key);
 }
 
-constexpr int kQCap = 4096;       // (score, row) entries a query holds in LDS
-constexpr int kQChunk = 1024;     // points scored between capacity checks
+// (score, row) entries a query holds in LDS: 2048 (16 KiB, more blocks per CU) or 6144 for m > 1024.  A quarter
+// of the capacity is scored between capacity checks.
+inline int select_query_cap(int m) { return m <= 1024 ? 2048 : 6144; }
 
 struct QuerySelectArgs {
     const int32_t* sel;          // [nq][w] clusters of each query
@@ -81,14 +82,17 @@ struct QuerySelectArgs {
     int32_t* fb_list;            // out: queries that need the exact per-query kernel
     int32_t* fb_count;           //      and their number (0 on entry)
     int w, m;
+    int cap;                     // select_query_cap(m)
 };
 
-// grid = nq, block = 256.  RB = r_pad / 16.
+// grid = nq, block = 256, dynamic LDS = 8 * cap bytes.  RB = r_pad / 16.
 template <int RB>
 __global__ __launch_bounds__(256) void k_select_query(QuerySelectArgs a) {
     constexpr int ZW = RB * 4;
-    __shared__ uint32_t keys[kQCap];
-    __shared__ int32_t rows[kQCap];
+    extern __shared__ __align__(16) unsigned char qs_smem[];
+    uint32_t* keys = reinterpret_cast<uint32_t*>(qs_smem);
+    int32_t* rows = reinterpret_cast<int32_t*>(qs_smem + (size_t)a.cap * 4);
+    const int kQCap = a.cap, kQChunk = a.cap >> 2;
     __shared__ int zw[ZW];
     __shared__ int hist[256];
     __shared__ int wsum[4];

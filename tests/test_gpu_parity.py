@@ -221,18 +221,17 @@ def test_mixed_batch_some_queries_fall_back(B, small_indexes):
     gix.close()
 
 
-@pytest.mark.parametrize("L", [1500, 4500])
+@pytest.mark.parametrize("L", [1500, 4500, 9000])
 def test_many_clusters_routing_variants(B, L):
     """Cluster counts that take the other routing kernels (keys in 64 registers per lane; block-wide select),
     with duplicate centroids so that ties at the w-th place occur."""
     rng = np.random.default_rng(L)
-    d, r, n, w = 32, 8, 3 * L, 40
+    d, r, w = 32, 8, 40
+    sizes = rng.integers(0, 7, size=L)
+    n = int(sizes.sum())
     corpus = rng.normal(size=(n, d)).astype(np.float32)
     cent = rng.normal(size=(L, d)).astype(np.float32)
     cent[L // 2:L // 2 + 300] = cent[:300]                     # exact ties between cluster pairs
-    sizes = rng.integers(0, 7, size=L)
-    sizes[-1] += n - sizes.sum()
-    assert sizes[-1] >= 0
     off = np.zeros(L + 1, np.int64)
     np.cumsum(sizes, out=off[1:])
     ix = dict(metric=1, n=n, d=d, dp=d, r=r, L=L, centroids=cent, P=None,
