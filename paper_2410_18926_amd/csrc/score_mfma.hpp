@@ -42,18 +42,6 @@ __device__ __forceinline__ void wave_lds_sync() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-// Maximum over the 32 lanes of each lane half.
-__device__ __forceinline__ int half_max_i32(int v) {
-#pragma unroll
-    for (int o = 1; o < 32; o <<= 1) v = max(v, __shfl_xor(v, o, 64));
-    return v;
-}
-__device__ __forceinline__ float half_max_f32(float v) {
-#pragma unroll
-    for (int o = 1; o < 32; o <<= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
-    return v;
-}
-
 // grid = any (persistent: wavefronts stride over the work items), block = 256.
 // A work item = one cluster, up to 32*NZ of its pairs, up to chunk_tiles 32-point tiles of its codes; items of
 // bounded size keep the load balanced when cluster sizes and pair counts are skewed.
@@ -65,21 +53,25 @@ __global__ __launch_bounds__(256) void k_pair_max(ScoreArgs a) {
     constexpr int RP = KS * 32;
     constexpr int TB = 4;              // point tiles fetched per chunk
     constexpr int IMIN = (int)0x80000000;
-    __shared__ int s_red[4][NP];       // per-pair maxima of the item (int, or float bits for Euclidean)
+    constexpr int TRS = NZ * 16 + 1;   // padded row of the transpose buffer
+    __shared__ int s_tr[4][64 * TRS];
+    __shared__ int s_red[4][NP];       // per-pair maxima of the item (int, or order-preserving keys for Euclidean)
     __shared__ float s_sig[4][NP];     // Euclidean: 2 sigma of each pair
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     const int j = lane & 31, h = lane >> 5;
     const int n_items = a.unit_off[a.L];
     // no block-wide barrier below: the wavefronts of a block are independent
     for (int item = blockIdx.x * 4 + wv; item < n_items; item += gridDim.x * 4) {
-        const int c = find_bucket(a.unit_off, a.L, item);
+        const int c = find_bucket_wave(a.unit_off, a.L, item);
         const int64_t row_c = a.off[c];
         const int m_all = (int)(a.off[c + 1] - row_c);
-        const int n_pchunks = (m_all + 32 * a.chunk_tiles - 1) / (32 * a.chunk_tiles);
+        const int pbeg = a.bucket_off[c], pend = a.bucket_off[c + 1];
+        const int n_groups = (pend - pbeg + NP - 1) / NP;
         const int local = item - a.unit_off[c];
-        const int ug = local / n_pchunks, pk = local - ug * n_pchunks;
-        const int pb = a.bucket_off[c] + ug * NP;
-        const int pend = a.bucket_off[c + 1];
+        // consecutive items (the wavefronts of one block) share the point chunk and differ in the pair group,
+        // so the chunk's codes are fetched from L2 once per block
+        const int pk = local / n_groups, ug = local - pk * n_groups;
+        const int pb = pbeg + ug * NP;
         const int64_t row0 = row_c + (int64_t)pk * 32 * a.chunk_tiles;              // first row of this item's chunk
         const int m_c = min(32 * a.chunk_tiles, m_all - pk * 32 * a.chunk_tiles);   // rows in the chunk
 
@@ -166,17 +158,32 @@ __global__ __launch_bounds__(256) void k_pair_max(ScoreArgs a) {
             }
         }
 
-        // reduce over the 32 points held by the lanes of each half; the pair of (z, v, h) gets its maximum
+        // reduce over the 32 points held by the lanes of each half through an LDS transpose: every lane stores its
+        // NZ*16 running maxima as one padded row, then lane p gathers the column of pair p from the 32 lanes of
+        // the half that holds it (independent reads, one wait) instead of 5 dependent shuffles per register
         wave_lds_sync();
 #pragma unroll
         for (int z = 0; z < NZ; ++z)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                int r;
-                if (!L2) r = half_max_i32(mxi[z][v]);
-                else r = __float_as_int(half_max_f32(mxf[z][v]));
-                if (j == 0) s_red[wv][32 * z + tile_row(v, h)] = r;
+            for (int v = 0; v < 16; ++v)
+                s_tr[wv][lane * TRS + z * 16 + v] = L2 ? (int)float_key_asc(mxf[z][v]) : mxi[z][v];
+        wave_lds_sync();
+        for (int p = lane; p < NP; p += 64) {
+            const int z = p >> 5, i = p & 31;
+            const int hh = (i >> 2) & 1, v = 4 * (i >> 3) + (i & 3);        // inverse of tile_row
+            const int* col = &s_tr[wv][hh * 32 * TRS + z * 16 + v];
+            if (!L2) {
+                int r = IMIN;
+#pragma unroll
+                for (int jj = 0; jj < 32; ++jj) r = max(r, col[jj * TRS]);
+                s_red[wv][p] = r;
+            } else {
+                unsigned r = 0u;
+#pragma unroll
+                for (int jj = 0; jj < 32; ++jj) r = max(r, (unsigned)col[jj * TRS]);
+                s_red[wv][p] = (int)r;
             }
+        }
         wave_lds_sync();
         for (int p = lane; p < NP; p += 64) {
             const int gp = pb + p;
@@ -187,8 +194,8 @@ __global__ __launch_bounds__(256) void k_pair_max(ScoreArgs a) {
                     // sigma >= 0: the best score of the pair is the score of its largest integer score
                     if (y != IMIN) key = float_key_asc(__fmaf_rn((float)y, a.sigma[gp], -0.0f));
                 } else {
-                    const float f = __int_as_float(s_red[wv][p]);
-                    if (f > -INFINITY) key = float_key_asc(f);
+                    key = (uint32_t)s_red[wv][p];
+                    if (key == float_key_asc(-INFINITY)) key = 0u;      // no point of the chunk seen
                 }
                 if (key != 0u) atomicMax(&a.pmax[gp], key);      // the cluster's other point chunks contribute too
             }

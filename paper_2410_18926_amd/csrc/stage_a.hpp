@@ -24,6 +24,24 @@ __device__ __forceinline__ int find_bucket(const int32_t* __restrict__ off, int 
     return lo;
 }
 
+// The same search done by a whole wavefront for one (uniform) t: every round the 64 lanes probe 64 evenly
+// spaced entries of the current range, so the range shrinks 64-fold per dependent load instead of 2-fold.
+__device__ __forceinline__ int find_bucket_wave(const int32_t* __restrict__ off, int L, int t) {
+    const int lane = threadIdx.x & 63;
+    int lo = 0, hi = L;   // invariant: off[lo] <= t < off[hi]
+    while (hi - lo > 1) {
+        const int span = hi - lo;
+        const int step = (span + 63) >> 6;                 // >= 1
+        const int probe = lo + (lane + 1) * step;          // lo < probe; lanes beyond hi do not count
+        const bool le = probe < hi && off[probe] <= t;
+        const int n = __popcll(__ballot(le));              // off is non-decreasing: the first n probes are <= t
+        const int nlo = lo + n * step;
+        const int nhi = min(hi, nlo + step);
+        lo = nlo; hi = nhi;
+    }
+    return lo;
+}
+
 // grid = ceil(max_tiles / 4), block = 256 (one 16-pair tile per wavefront).
 // RT = r_pad / 16 result tiles (2 or 4).  A is [L][r][dp]; Z is [npairs][r_pad] in bucket order.
 template <int RT>
@@ -35,7 +53,7 @@ __global__ __launch_bounds__(256) void k_stage_a(const int8_t* __restrict__ q8, 
     const int lane = threadIdx.x & 63;
     const int tile = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (tile >= tile_off[L]) return;
-    const int c = find_bucket(tile_off, L, tile);
+    const int c = find_bucket_wave(tile_off, L, tile);
     const int base = bucket_off[c] + (tile - tile_off[c]) * 16;
     const int end = bucket_off[c + 1];
     const int i = lane & 15, g = lane >> 4;
