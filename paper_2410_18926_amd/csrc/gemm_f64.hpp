@@ -18,7 +18,7 @@ namespace lorann {
 
 enum { EPI_PLAIN = 0, EPI_NEG = 1, EPI_L2 = 2 };
 
-constexpr int GM_BN = 64, GM_KT = 16, GM_LD = GM_KT + 1;
+constexpr int GM_BN = 64, GM_KT = 32, GM_LD = GM_KT + 1;
 
 // One operand tile (rows x 16 k) is fetched as one float4 per thread.
 __device__ __forceinline__ float4 gemm_fetch(const float* __restrict__ base, int rows, int K, int row, int k, bool vec_ok) {
@@ -60,22 +60,24 @@ __global__ __launch_bounds__(256) void k_gemm_nt_f64(const float* __restrict__ X
 #pragma unroll
         for (int b = 0; b < 2; ++b) acc[a][b] = (f64x4){0.0, 0.0, 0.0, 0.0};
 
-    float4 rx = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (x_loader) rx = gemm_fetch(X, M, K, m0 + lrow, lk, vec_ok);
-    float4 rw = gemm_fetch(W, N, K, n0 + lrow, lk, vec_ok);
+    float4 rx = make_float4(0.f, 0.f, 0.f, 0.f), rx2 = rx;
+    if (x_loader) { rx = gemm_fetch(X, M, K, m0 + lrow, lk, vec_ok); rx2 = gemm_fetch(X, M, K, m0 + lrow, lk + 16, vec_ok); }
+    float4 rw = gemm_fetch(W, N, K, n0 + lrow, lk, vec_ok), rw2 = gemm_fetch(W, N, K, n0 + lrow, lk + 16, vec_ok);
     const int i = lane & 15, g = lane >> 4;
 
     for (int k0 = 0; k0 < K; k0 += GM_KT) {
         if (x_loader) {
             float* xs = Xs + lrow * GM_LD + lk;
             xs[0] = rx.x; xs[1] = rx.y; xs[2] = rx.z; xs[3] = rx.w;
+            xs[16] = rx2.x; xs[17] = rx2.y; xs[18] = rx2.z; xs[19] = rx2.w;
         }
         float* ws = Ws + lrow * GM_LD + lk;
         ws[0] = rw.x; ws[1] = rw.y; ws[2] = rw.z; ws[3] = rw.w;
+        ws[16] = rw2.x; ws[17] = rw2.y; ws[18] = rw2.z; ws[19] = rw2.w;
         __syncthreads();
         if (k0 + GM_KT < K) {
-            if (x_loader) rx = gemm_fetch(X, M, K, m0 + lrow, k0 + GM_KT + lk, vec_ok);
-            rw = gemm_fetch(W, N, K, n0 + lrow, k0 + GM_KT + lk, vec_ok);
+            if (x_loader) { rx = gemm_fetch(X, M, K, m0 + lrow, k0 + GM_KT + lk, vec_ok); rx2 = gemm_fetch(X, M, K, m0 + lrow, k0 + GM_KT + lk + 16, vec_ok); }
+            rw = gemm_fetch(W, N, K, n0 + lrow, k0 + GM_KT + lk, vec_ok); rw2 = gemm_fetch(W, N, K, n0 + lrow, k0 + GM_KT + lk + 16, vec_ok);
         }
 #pragma unroll
         for (int kk = 0; kk < GM_KT; kk += 4) {
