@@ -17,6 +17,7 @@
 #include "common.hpp"
 #include "gemm_f64.hpp"
 #include "rerank.hpp"
+#include "rerank_group.hpp"
 #include "route.hpp"
 #include "score_mfma.hpp"
 #include "select_exact.hpp"
@@ -74,10 +75,10 @@ struct DevBuf {
     template <typename T> T* as() const { return reinterpret_cast<T*>(p); }
 };
 
-enum KernelId { K_PROJECT, K_QUANTIZE, K_CENTROID, K_SELECT_W, K_BUCKET_COUNT, K_SCAN, K_SCATTER, K_STAGE_A, K_PAIR_MAX, K_SELECT_QUERY, K_SELECT_M, K_RERANK, K_ZERO, K_COUNT };
+enum KernelId { K_PROJECT, K_QUANTIZE, K_CENTROID, K_SELECT_W, K_BUCKET_COUNT, K_SCAN, K_SCATTER, K_STAGE_A, K_PAIR_MAX, K_SELECT_QUERY, K_SELECT_M, K_ORDER, K_UNION, K_RERANK, K_TOPK, K_ZERO, K_COUNT };
 const char* const kKernelNames[K_COUNT] = {"project_f64", "quantize_rows", "centroid_dissim_f64", "select_clusters",
                                             "bucket_count", "scan_buckets", "scatter_pairs", "stage_a_i8", "pair_max_i8", "select_query", "score_select_exact",
-                                            "rerank", "zero_counters"};
+                                            "order_queries", "group_union", "rerank", "topk", "zero_counters"};
 
 struct EventPair { hipEvent_t a, b; int kid; };
 
@@ -99,8 +100,8 @@ struct lorann_index {
     int64_t* ids = nullptr;         // [n] or NULL
     float* sqnorm = nullptr;        // [n] (Euclidean)
     // workspace (device), sized for `chunk` queries
-    DevBuf qproj, q8, dx, gscore, sel, count, rank_in_bucket, qrank, qorder, off0, base_tab, bucket_off, tile_off, unit_off, slot_of_pos, pos_of_slot, Z, sigma, cand;
-    DevBuf tau, n_kept, fb_list, pmax;
+    DevBuf qproj, q8, dx, gscore, sel, count, rank_in_bucket, qrank, qorder, qorder2, off0, base_tab, bucket_off, tile_off, unit_off, slot_of_pos, pos_of_slot, Z, sigma, cand;
+    DevBuf tau, n_kept, fb_list, pmax, qkey, u_row, u_mask, u_pos, u_count, rdist, rcid, rccount;
     int32_t force_exact = 0;        // 1: score + select with the per-query kernel only (verification)
     DevBuf stage_q, stage_ids, stage_dists;   // staging when the caller passes host memory
     // profiling
@@ -116,9 +117,9 @@ namespace {
 void free_all(lorann_index* ix) {
     void* ptrs[] = {ix->centroids, ix->cent_sqnorm, ix->Pt, ix->A, ix->Bp, ix->sA, ix->sB, ix->off, ix->corpus, ix->ids, ix->sqnorm};
     for (void* p : ptrs) if (p) (void)hipFree(p);
-    DevBuf* bufs[] = {&ix->qproj, &ix->q8, &ix->dx, &ix->gscore, &ix->sel, &ix->count, &ix->rank_in_bucket, &ix->qrank, &ix->qorder, &ix->off0, &ix->base_tab, &ix->bucket_off, &ix->tile_off,
+    DevBuf* bufs[] = {&ix->qproj, &ix->q8, &ix->dx, &ix->gscore, &ix->sel, &ix->count, &ix->rank_in_bucket, &ix->qrank, &ix->qorder, &ix->qorder2, &ix->off0, &ix->base_tab, &ix->bucket_off, &ix->tile_off,
                       &ix->unit_off, &ix->slot_of_pos, &ix->pos_of_slot, &ix->Z, &ix->sigma, &ix->cand, &ix->tau,
-                      &ix->n_kept, &ix->fb_list, &ix->pmax, &ix->stage_q, &ix->stage_ids, &ix->stage_dists};
+                      &ix->n_kept, &ix->fb_list, &ix->pmax, &ix->qkey, &ix->u_row, &ix->u_mask, &ix->u_pos, &ix->u_count, &ix->rdist, &ix->rcid, &ix->rccount, &ix->stage_q, &ix->stage_ids, &ix->stage_dists};
     for (DevBuf* b : bufs) b->release();
     for (auto& e : ix->ev_used) { (void)hipEventDestroy(e.a); (void)hipEventDestroy(e.b); }
     for (auto& e : ix->ev_free) { (void)hipEventDestroy(e.a); (void)hipEventDestroy(e.b); }
@@ -187,6 +188,7 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
     if ((rc = ix->rank_in_bucket.reserve((size_t)npairs * 4))) return rc;
     if ((rc = ix->qrank.reserve((size_t)nq * 4))) return rc;
     if ((rc = ix->qorder.reserve((size_t)nq * 4))) return rc;
+    if ((rc = ix->qorder2.reserve((size_t)nq * 4))) return rc;
     if ((rc = ix->off0.reserve((size_t)L * 4))) return rc;
     if ((rc = ix->pmax.reserve((size_t)npairs * 4))) return rc;
     if ((rc = ix->bucket_off.reserve((size_t)(L + 1) * 4))) return rc;
@@ -288,6 +290,7 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
         if ((rc = ix->tau.reserve((size_t)nq * 4))) return rc;
         if ((rc = ix->n_kept.reserve((size_t)nq * 4))) return rc;
         if ((rc = ix->fb_list.reserve((size_t)nq * 4))) return rc;
+        if ((rc = ix->qkey.reserve((size_t)nq * 4))) return rc;
         const bool l2 = ix->metric == LORANN_L2;
         const int ks = r_pad / 32;
         {
@@ -307,7 +310,7 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
             QuerySelectArgs qa;
             qa.sel = ix->sel.as<int32_t>(); qa.pos_of_slot = ix->pos_of_slot.as<int32_t>(); qa.pmax = ix->pmax.as<uint32_t>();
             qa.Z = ix->Z.as<int8_t>(); qa.sigma = ix->sigma.as<float>(); qa.Bp = ix->Bp; qa.off = ix->off; qa.sqnorm = l2 ? ix->sqnorm : nullptr;
-            qa.cand = ix->cand.as<int32_t>(); qa.tau = ix->tau.as<float>(); qa.n_kept = ix->n_kept.as<int32_t>();
+            qa.cand = ix->cand.as<int32_t>(); qa.tau = ix->tau.as<float>(); qa.n_kept = ix->n_kept.as<int32_t>(); qa.qkey = ix->qkey.as<int32_t>();
             qa.fb_list = ix->fb_list.as<int32_t>(); qa.fb_count = ix->count.as<int32_t>() + 2 * L; qa.w = w; qa.m = m; qa.cap = select_query_cap(m);
             const size_t qlds = (size_t)qa.cap * 8;
             if (ks == 1) hipLaunchKernelGGL(k_select_query<2>, dim3((unsigned)nq), dim3(256), qlds, s, qa);
@@ -321,9 +324,52 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
             else hipLaunchKernelGGL(k_select_exact<4>, dim3(grid), dim3(256), 0, s, sa_, (int)nq);
         }
     }
-    {
+    const int mp2 = std::max(256, next_pow2(m));
+    if (m <= 512 && !ix->force_exact && (size_t)kGroupQ * d * 4 <= 48 * 1024) {
+        // grouped re-rank: neighbours in the visiting order share candidate rows, each distinct row is gathered once
+        {
+            Prof p(ix, K_ORDER);
+            hipLaunchKernelGGL(k_order_queries, dim3((unsigned)L), dim3(64), 0, s, ix->qorder.as<int32_t>(), ix->off0.as<int32_t>(), L, (int)nq,
+                               ix->qkey.as<int32_t>(), ix->qorder2.as<int32_t>());
+        }
+        const int64_t ngroups = (nq + kGroupQ - 1) / kGroupQ;
+        const size_t gm = (size_t)kGroupQ * m;
+        if ((rc = ix->u_row.reserve(ngroups * gm * 4))) return rc;
+        if ((rc = ix->u_mask.reserve(ngroups * gm))) return rc;
+        if ((rc = ix->u_pos.reserve(ngroups * gm * kGroupQ * 2))) return rc;
+        if ((rc = ix->u_count.reserve((size_t)ngroups * 4))) return rc;
+        if ((rc = ix->rdist.reserve((size_t)nq * m * 4))) return rc;
+        if ((rc = ix->rcid.reserve((size_t)nq * m * 8))) return rc;
+        if ((rc = ix->rccount.reserve((size_t)nq * 4))) return rc;
+        GroupArgs ga;
+        ga.Q = dQ; ga.corpus = ix->corpus; ga.ids = ix->ids; ga.cand = ix->cand.as<int32_t>(); ga.qorder = ix->qorder2.as<int32_t>();
+        ga.u_row = ix->u_row.as<int32_t>(); ga.u_mask = ix->u_mask.as<uint8_t>(); ga.u_pos = ix->u_pos.as<uint16_t>(); ga.u_count = ix->u_count.as<int32_t>();
+        ga.dist = ix->rdist.as<float>(); ga.cid = ix->rcid.as<int64_t>(); ga.ccount = ix->rccount.as<int32_t>();
+        ga.out_ids = d_ids; ga.out_dists = d_dists; ga.nq = (int)nq; ga.d = d; ga.m = m; ga.k = k;
+        ga.ht = rerank_group_ht(m);
+        // enough gather blocks to keep every CU evenly busy: about 2 MiB of rows per block at most
+        ga.slices = (int)std::min<int64_t>(16, std::max<int64_t>(1, ((int64_t)gm * d * 4 / 2) / (2 << 20) + 1));
+        while ((int64_t)ga.slices * ngroups < 4096 && ga.slices < 16) ++ga.slices;
+        {
+            Prof p(ix, K_UNION);
+            hipLaunchKernelGGL(k_group_union, dim3((unsigned)ngroups), dim3(256), (size_t)ga.ht * 5, s, ga);
+        }
+        {
+            Prof p(ix, K_RERANK);
+            const dim3 grid((unsigned)(ngroups * ga.slices));
+            const size_t lds = (size_t)kGroupQ * d * 4;
+            if (ix->metric == LORANN_IP) hipLaunchKernelGGL(k_group_gather<0>, grid, dim3(256), lds, s, ga);
+            else if (ix->metric == LORANN_L2) hipLaunchKernelGGL(k_group_gather<1>, grid, dim3(256), lds, s, ga);
+            else hipLaunchKernelGGL(k_group_gather<2>, grid, dim3(256), lds, s, ga);
+        }
+        {
+            Prof p(ix, K_TOPK);
+            if (k <= 64 && m <= 256) hipLaunchKernelGGL(k_topk_wave<4>, dim3((unsigned)((nq + 3) / 4)), dim3(256), 0, s, ga);
+            else if (k <= 64) hipLaunchKernelGGL(k_topk_wave<8>, dim3((unsigned)((nq + 3) / 4)), dim3(256), 0, s, ga);
+            else hipLaunchKernelGGL(k_topk, dim3((unsigned)nq), dim3(256), (size_t)mp2 * 12, s, ga, mp2);
+        }
+    } else {
         Prof p(ix, K_RERANK);
-        const int mp2 = std::max(256, next_pow2(m));
         const size_t lds = (size_t)d * 4 + (size_t)mp2 * 12;
         const int32_t* cand = ix->cand.as<int32_t>();
         const dim3 rgrid((unsigned)(8 * ((nq + 7) / 8)));
@@ -395,7 +441,8 @@ int search_impl(lorann_index* ix, const float* queries, int64_t nq, int32_t k, i
     if (!queries || !out_ids || !out_dists) return fail(LORANN_E_INVAL, "queries / out_ids / out_dists must not be NULL");
     {
         const int mp2 = std::max(256, next_pow2(m));
-        if ((size_t)ix->d * 4 + (size_t)mp2 * 12 > 64 * 1024)
+        const size_t need = (size_t)ix->d * 4 + (size_t)mp2 * 12;      // the one-query-per-block re-rank must fit
+        if (need > 64 * 1024)
             return fail(LORANN_E_UNSUPPORTED, "d = %d with m = %d needs more than 64 KiB of LDS in the re-rank", ix->d, m);
     }
     // batches are processed in chunks that keep nq * w and nq * L within 32-bit indexing and a bounded workspace

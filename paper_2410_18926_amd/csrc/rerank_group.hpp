@@ -1,0 +1,333 @@
+// Exact re-rank with shared row gathers (Sec. 2.2 last step; Sec. 4.1: the original d-dimensional query).
+//
+// The re-rank is a row gather from HBM and dominates the bytes of the whole search.  Queries of one batch that
+// fall into the same region of the corpus share many candidates, so
+//   k_order_queries : puts the queries in an order in which such queries are neighbours (by nearest cluster,
+//                     then by smallest candidate row);
+//   k_group_union   : for every group of G consecutive queries forms the union of their candidate rows in an
+//                     LDS hash table and writes it out as a list of (row, which queries want it, where each of
+//                     them keeps the distance);
+//   k_group_gather  : streams the distinct rows - every row is gathered ONCE per group (16-byte loads per lane,
+//                     a row is contiguous, several rows in flight per wavefront) and scored against each query
+//                     that asked for it; work is cut into many small blocks so the machine stays evenly loaded;
+//   k_topk          : per query, the k smallest (distance, id), ties toward the lower id.
+// Distances are accumulated exactly as in the one-query-per-block kernel (same per-lane order, same shuffle
+// tree), so both paths return identical bits.
+#pragma once
+#include <algorithm>
+
+#include "common.hpp"
+#include "rerank.hpp"
+
+namespace lorann {
+
+constexpr int kGroupQ = 8;        // queries per group (one mask byte per distinct row)
+
+// Order the queries inside each nearest-cluster segment of `qorder` by `qkey` (their smallest candidate row), so
+// that queries with overlapping candidate sets become neighbours.  grid = L, block = 64 (one wavefront per
+// cluster).  Segments longer than 1024 queries are copied unchanged (the order is only a locality hint).
+__global__ __launch_bounds__(64) void k_order_queries(const int32_t* __restrict__ qorder, const int32_t* __restrict__ off0,
+                                                      int L, int nq, const int32_t* __restrict__ qkey,
+                                                      int32_t* __restrict__ qorder2) {
+    __shared__ int skey[1024], sq[1024];
+    const int c = blockIdx.x, lane = threadIdx.x;
+    const int beg = off0[c], end = c + 1 < L ? off0[c + 1] : nq;
+    const int len = end - beg;
+    if (len <= 0) return;
+    if (len > 1024) {
+        for (int e = lane; e < len; e += 64) qorder2[beg + e] = qorder[beg + e];
+        return;
+    }
+    for (int e = lane; e < len; e += 64) { const int q = qorder[beg + e]; sq[e] = q; skey[e] = qkey[q]; }
+    __syncthreads();
+    for (int e = lane; e < len; e += 64) {
+        const int k = skey[e], q = sq[e];
+        int rank = 0;
+        for (int u = 0; u < len; ++u) rank += (skey[u] < k || (skey[u] == k && sq[u] < q)) ? 1 : 0;
+        qorder2[beg + rank] = q;
+    }
+}
+
+struct GroupArgs {
+    const float* Q;              // [nq][d]
+    const float* corpus;         // [n][d]
+    const int64_t* ids;          // [n] or NULL
+    const int32_t* cand;         // [nq][m]
+    const int32_t* qorder;       // [nq] visiting order
+    int32_t* u_row;              // [ngroups][G*m]    distinct candidate rows of each group
+    uint8_t* u_mask;             // [ngroups][G*m]    bit g: query g of the group wants the row
+    uint16_t* u_pos;             // [ngroups][G*m][G] where query g keeps the distance of that row
+    int32_t* u_count;            // [ngroups]         number of distinct rows
+    float* dist;                 // [nq][m]  exact dissimilarities, in the query's own slot order
+    int64_t* cid;                // [nq][m]  id of the row in each slot
+    int32_t* ccount;             // [nq]     slots in use
+    int64_t* out_ids;            // [nq][k]
+    float* out_dists;            // [nq][k]
+    int nq, d, m, k;
+    int ht;                      // hash table slots (rerank_group_ht)
+    int slices;                  // gather blocks per group
+};
+
+inline int rerank_group_ht(int m) {      // hash table slots: power of two, load factor <= 0.8
+    int ht = 16;
+    while (ht * 4 < kGroupQ * m * 5) ht <<= 1;
+    return ht;
+}
+
+// grid = ngroups, block = 256, dynamic LDS = ht * 5 bytes.
+__global__ __launch_bounds__(256) void k_group_union(GroupArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int ht = a.ht, m = a.m;
+    int32_t* tkey = reinterpret_cast<int32_t*>(smem);              // [ht]
+    uint32_t* tmask = reinterpret_cast<uint32_t*>(tkey + ht);      // [ht/4], one byte per slot
+    __shared__ int s_q[kGroupQ], s_rcount[kGroupQ], s_nuniq;
+    const int tid = threadIdx.x;
+    const int grp = blockIdx.x;
+    const int g0 = grp * kGroupQ;
+    const int ng = min(kGroupQ, a.nq - g0);
+    if (tid < kGroupQ) { s_q[tid] = tid < ng ? a.qorder[g0 + tid] : -1; s_rcount[tid] = 0; }
+    if (tid == 0) s_nuniq = 0;
+    for (int s = tid; s < ht; s += 256) tkey[s] = -1;
+    for (int s = tid; s < ht / 4; s += 256) tmask[s] = 0u;
+    __syncthreads();
+    // open addressing, key = row, one mask byte per slot (bit g: query g wants the row)
+    for (int t = tid; t < ng * m; t += 256) {
+        const int g = t / m, c = t - g * m;
+        const int row = a.cand[(size_t)s_q[g] * m + c];
+        if (row < 0) continue;
+        uint32_t h = ((uint32_t)row * 2654435761u) >> 7;
+        for (;;) {
+            h &= (uint32_t)(ht - 1);
+            const int old = atomicCAS(&tkey[h], -1, row);
+            if (old == -1 || old == row) { atomicOr(&tmask[h >> 2], (1u << g) << (8 * (h & 3))); break; }
+            ++h;
+        }
+    }
+    __syncthreads();
+    const size_t gbase = (size_t)grp * kGroupQ * m;
+    for (int s = tid; s < ht; s += 256) {
+        const int row = tkey[s];
+        if (row == -1) continue;
+        const uint32_t mk = (tmask[s >> 2] >> (8 * (s & 3))) & 0xffu;
+        const int at = atomicAdd(&s_nuniq, 1);
+        a.u_row[gbase + at] = row;
+        a.u_mask[gbase + at] = (uint8_t)mk;
+        const int64_t id = a.ids ? a.ids[row] : (int64_t)row;
+        for (int g = 0; g < ng; ++g) {
+            if (!((mk >> g) & 1u)) continue;
+            const int pos = atomicAdd(&s_rcount[g], 1);
+            a.u_pos[(gbase + at) * kGroupQ + g] = (uint16_t)pos;
+            a.cid[(size_t)s_q[g] * m + pos] = id;
+        }
+    }
+    __syncthreads();
+    if (tid == 0) a.u_count[grp] = s_nuniq;
+    if (tid < ng) a.ccount[s_q[tid]] = s_rcount[tid];
+}
+
+// grid = ngroups * slices, block = 256, dynamic LDS = G * d * 4 bytes.  METRIC: 0 inner product, 1 squared
+// Euclidean, 2 cosine.
+template <int METRIC>
+__global__ __launch_bounds__(256) void k_group_gather(GroupArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    float* qs = reinterpret_cast<float*>(smem);                    // [G][d]
+    __shared__ int s_q[kGroupQ];
+    __shared__ float s_qnorm[kGroupQ];
+    const int d = a.d, m = a.m;
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int grp = blockIdx.x / a.slices, sl = blockIdx.x - grp * a.slices;
+    const int g0 = grp * kGroupQ;
+    const int ng = min(kGroupQ, a.nq - g0);
+    const int nuniq = a.u_count[grp];
+    const int per = (nuniq + a.slices - 1) / a.slices;
+    const int ubeg = sl * per, uend = min(nuniq, ubeg + per);
+    if (ubeg >= uend) return;
+    if (tid < kGroupQ) s_q[tid] = tid < ng ? a.qorder[g0 + tid] : -1;
+    __syncthreads();
+    for (int g = 0; g < ng; ++g) {
+        const float* qrow = a.Q + (size_t)s_q[g] * d;
+        for (int i = tid; i < d; i += 256) qs[(size_t)g * d + i] = qrow[i];
+    }
+    __syncthreads();
+    if (METRIC == 2) {
+        if (tid < 64) {
+            for (int g = 0; g < ng; ++g) {
+                float acc = 0.0f;
+                for (int i = lane; i < d; i += 64) acc = fmaf(qs[(size_t)g * d + i], qs[(size_t)g * d + i], acc);
+                acc = wave_sum_f32(acc);
+                if (lane == 0) s_qnorm[g] = sqrtf(acc);
+            }
+        }
+        __syncthreads();
+    }
+    const size_t gbase = (size_t)grp * kGroupQ * m;
+    const int d4 = (d % 4 == 0) ? d / 4 : 0;      // vector path needs 16-byte aligned rows
+    auto emit = [&](int g, int pos, float acc) {  // lane 0 of the wavefront records one (query, row) distance
+        float dist;
+        if (METRIC == 1) dist = acc;
+        else if (METRIC == 0) dist = -acc;
+        else dist = s_qnorm[g] > 0.0f ? 1.0f - acc / s_qnorm[g] : 1.0f;
+        a.dist[(size_t)s_q[g] * m + pos] = dist;
+    };
+    if (d4 && d4 <= 256) {
+        // rows of up to 1024 floats live in registers (4 float4 per lane); RB rows are fetched before any is used
+        constexpr int RB = 4;
+        for (int u0 = ubeg + wv * RB; u0 < uend; u0 += 4 * RB) {
+            float4 x[RB][4];
+            int row[RB], ps[RB];
+            uint32_t mk[RB];
+#pragma unroll
+            for (int r = 0; r < RB; ++r) {
+                const int u = u0 + r;
+                row[r] = u < uend ? a.u_row[gbase + u] : -1;
+                mk[r] = u < uend ? a.u_mask[gbase + u] : 0u;
+                // lane l keeps the slot of query l % 8 for this row (fetched now, together with the row itself)
+                ps[r] = u < uend ? a.u_pos[(gbase + u) * kGroupQ + (lane & (kGroupQ - 1))] : 0;
+            }
+#pragma unroll
+            for (int r = 0; r < RB; ++r) {
+                const float4* p4 = reinterpret_cast<const float4*>(a.corpus + (size_t)(row[r] < 0 ? 0 : row[r]) * d);
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    x[r][v] = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (row[r] >= 0 && lane + 64 * v < d4) x[r][v] = p4[lane + 64 * v];
+                }
+            }
+#pragma unroll
+            for (int r = 0; r < RB; ++r) {
+                for (int g = 0; g < ng; ++g) {
+                    if (!((mk[r] >> g) & 1u)) continue;                    // uniform
+                    const float4* q4 = reinterpret_cast<const float4*>(qs + (size_t)g * d);
+                    float acc = 0.0f;
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        if (lane + 64 * v < d4) {
+                            const float4 y = q4[lane + 64 * v];
+                            if (METRIC == 1) {
+                                const float a0 = y.x - x[r][v].x, a1 = y.y - x[r][v].y, a2 = y.z - x[r][v].z, a3 = y.w - x[r][v].w;
+                                acc = fmaf(a0, a0, acc); acc = fmaf(a1, a1, acc); acc = fmaf(a2, a2, acc); acc = fmaf(a3, a3, acc);
+                            } else {
+                                acc = fmaf(x[r][v].x, y.x, acc); acc = fmaf(x[r][v].y, y.y, acc); acc = fmaf(x[r][v].z, y.z, acc); acc = fmaf(x[r][v].w, y.w, acc);
+                            }
+                        }
+                    }
+                    acc = wave_sum_f32(acc);
+                    const int pos = __shfl(ps[r], g, 64);
+                    if (lane == 0) emit(g, pos, acc);
+                }
+            }
+        }
+    } else {
+        for (int u = ubeg + wv; u < uend; u += 4) {
+            const int row = a.u_row[gbase + u];
+            const uint32_t mk = a.u_mask[gbase + u];
+            const float* p = a.corpus + (size_t)row * d;
+            for (int g = 0; g < ng; ++g) {
+                if (!((mk >> g) & 1u)) continue;
+                const float* qg = qs + (size_t)g * d;
+                float acc = 0.0f;
+                if (d4) {
+                    const float4* p4 = reinterpret_cast<const float4*>(p);
+                    const float4* q4 = reinterpret_cast<const float4*>(qg);
+                    for (int i = lane; i < d4; i += 64) {
+                        const float4 x = p4[i], y = q4[i];
+                        if (METRIC == 1) {
+                            const float a0 = y.x - x.x, a1 = y.y - x.y, a2 = y.z - x.z, a3 = y.w - x.w;
+                            acc = fmaf(a0, a0, acc); acc = fmaf(a1, a1, acc); acc = fmaf(a2, a2, acc); acc = fmaf(a3, a3, acc);
+                        } else {
+                            acc = fmaf(x.x, y.x, acc); acc = fmaf(x.y, y.y, acc); acc = fmaf(x.z, y.z, acc); acc = fmaf(x.w, y.w, acc);
+                        }
+                    }
+                } else {
+                    for (int i = lane; i < d; i += 64) {
+                        if (METRIC == 1) { const float t = qg[i] - p[i]; acc = fmaf(t, t, acc); }
+                        else acc = fmaf(p[i], qg[i], acc);
+                    }
+                }
+                acc = wave_sum_f32(acc);
+                if (lane == 0) emit(g, a.u_pos[(gbase + u) * kGroupQ + g], acc);
+            }
+        }
+    }
+}
+
+// The k smallest (distance, id) of each query, one WAVEFRONT per query, candidates in registers (EPL per lane,
+// m <= 64 * EPL): k rounds of "take the wavefront-wide minimum and retire it".  For k much smaller than m this is
+// far cheaper than sorting.  grid = ceil(nq / 4), block = 256.
+template <int EPL>
+__global__ __launch_bounds__(256) void k_topk_wave(GroupArgs a) {
+    const int lane = threadIdx.x & 63;
+    const int64_t q = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (q >= a.nq) return;
+    const int cnt = a.ccount[q];
+    float dv[EPL];
+    int64_t iv[EPL];
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) {
+        const int t = 64 * e + lane;
+        dv[e] = INFINITY; iv[e] = kPadId;
+        if (t < cnt) { dv[e] = a.dist[(size_t)q * a.m + t]; iv[e] = a.cid[(size_t)q * a.m + t]; }
+    }
+    for (int r = 0; r < a.k; ++r) {
+        float bd = dv[0];
+        int64_t bi = iv[0];
+#pragma unroll
+        for (int e = 1; e < EPL; ++e)
+            if (rr_less(dv[e], iv[e], bd, bi)) { bd = dv[e]; bi = iv[e]; }
+        float wd = bd;
+        int64_t wi = bi;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            const float od = __shfl_xor(wd, o, 64);
+            const int64_t oi = __shfl_xor(wi, o, 64);
+            if (rr_less(od, oi, wd, wi)) { wd = od; wi = oi; }
+        }
+        // ids are distinct, so exactly one lane owns the winner (padding entries may repeat: nothing to retire)
+        if (wi != kPadId && bi == wi && bd == wd) {
+#pragma unroll
+            for (int e = 0; e < EPL; ++e)
+                if (iv[e] == wi && dv[e] == wd) { dv[e] = INFINITY; iv[e] = kPadId; }
+        }
+        if (lane == 0) {
+            a.out_ids[(size_t)q * a.k + r] = wi == kPadId ? -1 : wi;
+            a.out_dists[(size_t)q * a.k + r] = wi == kPadId ? INFINITY : wd;
+        }
+    }
+}
+
+// The k smallest (distance, id) of each query: bitonic sort in LDS.  grid = nq, block = 256,
+// dynamic LDS = mp2 * 12 bytes (mp2 = power of two >= m, >= 256).
+__global__ __launch_bounds__(256) void k_topk(GroupArgs a, int mp2) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    int64_t* sid = reinterpret_cast<int64_t*>(smem);
+    float* sdist = reinterpret_cast<float*>(sid + mp2);
+    const int tid = threadIdx.x;
+    const int64_t q = blockIdx.x;
+    const int cnt = a.ccount[q];
+    for (int t = tid; t < mp2; t += 256) {
+        if (t < cnt) { sdist[t] = a.dist[(size_t)q * a.m + t]; sid[t] = a.cid[(size_t)q * a.m + t]; }
+        else { sdist[t] = INFINITY; sid[t] = kPadId; }
+    }
+    __syncthreads();
+    for (int size = 2; size <= mp2; size <<= 1) {
+        for (int stride = size >> 1; stride > 0; stride >>= 1) {
+            for (int t = tid; t < (mp2 >> 1); t += 256) {
+                const int lo = 2 * t - (t & (stride - 1));
+                const int hi = lo + stride;
+                const bool up = (lo & size) == 0;
+                const float dl = sdist[lo], dh = sdist[hi];
+                const int64_t il = sid[lo], ih = sid[hi];
+                const bool swap = up ? rr_less(dh, ih, dl, il) : rr_less(dl, il, dh, ih);
+                if (swap) { sdist[lo] = dh; sdist[hi] = dl; sid[lo] = ih; sid[hi] = il; }
+            }
+            __syncthreads();
+        }
+    }
+    for (int t = tid; t < a.k; t += 256) {
+        const int64_t id = sid[t];
+        a.out_ids[(size_t)q * a.k + t] = id == kPadId ? -1 : id;
+        a.out_dists[(size_t)q * a.k + t] = id == kPadId ? INFINITY : sdist[t];
+    }
+}
+
+}  // namespace lorann

@@ -67,6 +67,17 @@ __device__ __forceinline__ float key_to_float(uint32_t key) {   // inverse of fl
 // of the capacity is scored between capacity checks.
 inline int select_query_cap(int m) { return m <= 1024 ? 2048 : 6144; }
 
+// Block-wide minimum of `v` written to *dst (scratch: one int of LDS, clobbered).  Contains barriers.
+__device__ __forceinline__ void block_min_to(int32_t* dst, int v, int* scratch) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = min(v, __shfl_xor(v, o, 64));
+    if (threadIdx.x == 0) *scratch = 0x7fffffff;
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) atomicMin(scratch, v);
+    __syncthreads();
+    if (threadIdx.x == 0) *dst = *scratch;
+}
+
 struct QuerySelectArgs {
     const int32_t* sel;          // [nq][w] clusters of each query
     const int32_t* pos_of_slot;  // [nq*w]
@@ -79,6 +90,7 @@ struct QuerySelectArgs {
     int32_t* cand;               // out [nq][m]: candidate rows, unordered, -1 padded
     float* tau;                  // out [nq]: score of the m-th candidate (-inf if fewer than m points were scored)
     int32_t* n_kept;             // out [nq]: scores held in LDS when the walk ended (-1: handed to the exact kernel)
+    int32_t* qkey;               // out [nq]: smallest candidate row (locality hint for the order of the re-rank)
     int32_t* fb_list;            // out: queries that need the exact per-query kernel
     int32_t* fb_count;           //      and their number (0 on entry)
     int w, m;
@@ -183,12 +195,17 @@ __global__ __launch_bounds__(256) void k_select_query(QuerySelectArgs a) {
 
     int32_t* out = a.cand + (size_t)q * m;
     if (overflow) {
-        if (tid == 0) { a.fb_list[atomicAdd(a.fb_count, 1)] = q; a.n_kept[q] = -1; a.tau[q] = key_to_float(T); }
+        if (tid == 0) {
+            a.fb_list[atomicAdd(a.fb_count, 1)] = q; a.n_kept[q] = -1; a.tau[q] = key_to_float(T);
+            a.qkey[q] = (int32_t)a.off[a.sel[(size_t)q * w + order[0]]];     // first row of its most promising cluster
+        }
         return;
     }
     if (tid == 0) { a.n_kept[q] = count; a.tau[q] = count >= m ? key_to_float(T) : -INFINITY; s_out = 0; s_ties = 0; }
     if (count <= m) {       // every kept score is a candidate (count < m: all scored points)
-        for (int i = tid; i < m; i += 256) out[i] = i < count ? rows[i] : -1;
+        int mn = 0x7fffffff;
+        for (int i = tid; i < m; i += 256) { const int r = i < count ? rows[i] : -1; out[i] = r; if (r >= 0) mn = min(mn, r); }
+        block_min_to(a.qkey + q, mn, &s_ties);
         return;
     }
     // count > m: T is the m-th largest key (compact() ran after the last arrivals); ties at T go to the lower rows
@@ -206,11 +223,14 @@ __global__ __launch_bounds__(256) void k_select_query(QuerySelectArgs a) {
     int dummy;
     const uint32_t RT = block_mth_largest(count, need_ties, hist, sh, dummy,
                                           [&](int i, uint32_t& key) { key = ~(uint32_t)rows[i]; return keys[i] == T; });
+    int mn = 0x7fffffff;
     for (int i = tid; i < count; i += 256) {
         const uint32_t key = keys[i];
-        if (key > T) out[atomicAdd(&s_out, 1)] = rows[i];
-        else if ((~(uint32_t)rows[i]) >= RT) out[n_above + atomicAdd(&s_ties, 1)] = rows[i];
+        if (key > T) { out[atomicAdd(&s_out, 1)] = rows[i]; mn = min(mn, rows[i]); }
+        else if ((~(uint32_t)rows[i]) >= RT) { out[n_above + atomicAdd(&s_ties, 1)] = rows[i]; mn = min(mn, rows[i]); }
     }
+    __syncthreads();
+    block_min_to(a.qkey + q, mn, &s_out);
 }
 
 }  // namespace lorann
