@@ -138,8 +138,9 @@ int lorann_search_stages(lorann_index *ix, const float *queries, int64_t nq, int
 
 /*
  * Per-kernel timing of the searches of one index, taken with HIP events on the index's stream.
- * lorann_profile_enable(ix, 1) starts recording (and clears the totals), 0 stops.  lorann_profile_get
- * writes up to `cap` records and returns how many kernels exist (or a negative error code).
+ * lorann_profile_enable(ix, 1) starts recording every kernel (and clears the totals), 2 records only the
+ * re-rank gather kernel (two events per batch: negligible overhead inside a timed run), 0 stops.
+ * lorann_profile_get writes up to `cap` records and returns how many kernels exist (or a negative error code).
  */
 typedef struct lorann_kernel_time {
     char name[48];      /* kernel name */

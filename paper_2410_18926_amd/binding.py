@@ -183,8 +183,9 @@ class Index:
     def set_exact_selection(self, on: bool):
         _check(lib().lorann_set_exact_selection(self._h, 1 if on else 0))
 
-    def profile_enable(self, on: bool = True):
-        _check(lib().lorann_profile_enable(self._h, 1 if on else 0))
+    def profile_enable(self, on=True):
+        """True / 1: every kernel; 2: only the re-rank gather kernel; False / 0: off."""
+        _check(lib().lorann_profile_enable(self._h, int(on)))
 
     def profile_fallback_queries(self) -> int:
         return int(lib().lorann_profile_fallback_queries(self._h))

@@ -106,6 +106,7 @@ struct lorann_index {
     DevBuf stage_q, stage_ids, stage_dists;   // staging when the caller passes host memory
     // profiling
     bool prof_on = false;
+    int prof_only = -1;             // >= 0: record only this kernel (keeps the event overhead out of a timed run)
     std::vector<EventPair> ev_used, ev_free;
     double prof_ms[K_COUNT] = {0};
     int64_t prof_launches[K_COUNT] = {0};
@@ -145,7 +146,7 @@ struct Prof {
     lorann_index* ix;
     int idx = -1;
     Prof(lorann_index* ix_, int kid) : ix(ix_) {
-        if (!ix->prof_on) return;
+        if (!ix->prof_on || (ix->prof_only >= 0 && ix->prof_only != kid)) return;
         EventPair ep;
         if (!ix->ev_free.empty()) { ep = ix->ev_free.back(); ix->ev_free.pop_back(); }
         else if (hipEventCreate(&ep.a) != hipSuccess || hipEventCreate(&ep.b) != hipSuccess) return;
@@ -613,6 +614,7 @@ int lorann_profile_enable(lorann_index* ix, int32_t on) {
     HIP_TRY(hipStreamSynchronize(ix->stream));
     prof_collect(ix);
     ix->prof_on = on != 0;
+    ix->prof_only = on == 2 ? (int)K_RERANK : -1;
     if (on) { for (int i = 0; i < K_COUNT; ++i) { ix->prof_ms[i] = 0.0; ix->prof_launches[i] = 0; } ix->prof_fallback_queries = 0; }
     return LORANN_OK;
 }

@@ -172,18 +172,25 @@ __global__ __launch_bounds__(256) void k_group_gather(GroupArgs a) {
     if (d4 && d4 <= 256) {
         // rows of up to 1024 floats live in registers (4 float4 per lane); RB rows are fetched before any is used
         constexpr int RB = 4;
+        int nrow[RB], nps[RB];
+        uint32_t nmk[RB];
+        auto fetch_meta = [&](int u0) {           // (row, mask, slots) of the next RB rows, one iteration ahead
+#pragma unroll
+            for (int r = 0; r < RB; ++r) {
+                const int u = u0 + r;
+                nrow[r] = u < uend ? a.u_row[gbase + u] : -1;
+                nmk[r] = u < uend ? a.u_mask[gbase + u] : 0u;
+                // lane l keeps the slot of query l % 8 for this row
+                nps[r] = u < uend ? a.u_pos[(gbase + u) * kGroupQ + (lane & (kGroupQ - 1))] : 0;
+            }
+        };
+        fetch_meta(ubeg + wv * RB);
         for (int u0 = ubeg + wv * RB; u0 < uend; u0 += 4 * RB) {
             float4 x[RB][4];
             int row[RB], ps[RB];
             uint32_t mk[RB];
 #pragma unroll
-            for (int r = 0; r < RB; ++r) {
-                const int u = u0 + r;
-                row[r] = u < uend ? a.u_row[gbase + u] : -1;
-                mk[r] = u < uend ? a.u_mask[gbase + u] : 0u;
-                // lane l keeps the slot of query l % 8 for this row (fetched now, together with the row itself)
-                ps[r] = u < uend ? a.u_pos[(gbase + u) * kGroupQ + (lane & (kGroupQ - 1))] : 0;
-            }
+            for (int r = 0; r < RB; ++r) { row[r] = nrow[r]; mk[r] = nmk[r]; ps[r] = nps[r]; }
 #pragma unroll
             for (int r = 0; r < RB; ++r) {
                 const float4* p4 = reinterpret_cast<const float4*>(a.corpus + (size_t)(row[r] < 0 ? 0 : row[r]) * d);
@@ -193,6 +200,7 @@ __global__ __launch_bounds__(256) void k_group_gather(GroupArgs a) {
                     if (row[r] >= 0 && lane + 64 * v < d4) x[r][v] = p4[lane + 64 * v];
                 }
             }
+            fetch_meta(u0 + 4 * RB);
 #pragma unroll
             for (int r = 0; r < RB; ++r) {
                 for (int g = 0; g < ng; ++g) {
