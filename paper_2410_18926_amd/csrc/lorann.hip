@@ -359,9 +359,9 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
             Prof p(ix, K_RERANK);
             const dim3 grid((unsigned)(ngroups * ga.slices));
             const size_t lds = (size_t)kGroupQ * d * 4;
-            if (ix->metric == LORANN_IP) hipLaunchKernelGGL(k_group_gather<0>, grid, dim3(256), lds, s, ga);
-            else if (ix->metric == LORANN_L2) hipLaunchKernelGGL(k_group_gather<1>, grid, dim3(256), lds, s, ga);
-            else hipLaunchKernelGGL(k_group_gather<2>, grid, dim3(256), lds, s, ga);
+            if (ix->metric == LORANN_IP) hipLaunchKernelGGL(k_group_gather<0>, grid, dim3(kGatherThreads), lds, s, ga);
+            else if (ix->metric == LORANN_L2) hipLaunchKernelGGL(k_group_gather<1>, grid, dim3(kGatherThreads), lds, s, ga);
+            else hipLaunchKernelGGL(k_group_gather<2>, grid, dim3(kGatherThreads), lds, s, ga);
         }
         {
             Prof p(ix, K_TOPK);

@@ -125,10 +125,12 @@ __global__ __launch_bounds__(256) void k_group_union(GroupArgs a) {
     if (tid < ng) a.ccount[s_q[tid]] = s_rcount[tid];
 }
 
-// grid = ngroups * slices, block = 256, dynamic LDS = G * d * 4 bytes.  METRIC: 0 inner product, 1 squared
+constexpr int kGatherThreads = 512, kGatherWaves = kGatherThreads / 64;
+
+// grid = ngroups * slices, block = kGatherThreads, dynamic LDS = G * d * 4 bytes.  METRIC: 0 inner product, 1 squared
 // Euclidean, 2 cosine.
 template <int METRIC>
-__global__ __launch_bounds__(256) void k_group_gather(GroupArgs a) {
+__global__ __launch_bounds__(kGatherThreads) void k_group_gather(GroupArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     float* qs = reinterpret_cast<float*>(smem);                    // [G][d]
     __shared__ int s_q[kGroupQ];
@@ -146,7 +148,7 @@ __global__ __launch_bounds__(256) void k_group_gather(GroupArgs a) {
     __syncthreads();
     for (int g = 0; g < ng; ++g) {
         const float* qrow = a.Q + (size_t)s_q[g] * d;
-        for (int i = tid; i < d; i += 256) qs[(size_t)g * d + i] = qrow[i];
+        for (int i = tid; i < d; i += kGatherThreads) qs[(size_t)g * d + i] = qrow[i];
     }
     __syncthreads();
     if (METRIC == 2) {
@@ -171,7 +173,7 @@ __global__ __launch_bounds__(256) void k_group_gather(GroupArgs a) {
     };
     if (d4 && d4 <= 256) {
         // rows of up to 1024 floats live in registers (4 float4 per lane); RB rows are fetched before any is used
-        constexpr int RB = 4;
+        constexpr int RB = 2;
         int nrow[RB], nps[RB];
         uint32_t nmk[RB];
         auto fetch_meta = [&](int u0) {           // (row, mask, slots) of the next RB rows, one iteration ahead
@@ -185,7 +187,7 @@ __global__ __launch_bounds__(256) void k_group_gather(GroupArgs a) {
             }
         };
         fetch_meta(ubeg + wv * RB);
-        for (int u0 = ubeg + wv * RB; u0 < uend; u0 += 4 * RB) {
+        for (int u0 = ubeg + wv * RB; u0 < uend; u0 += kGatherWaves * RB) {
             float4 x[RB][4];
             int row[RB], ps[RB];
             uint32_t mk[RB];
@@ -200,7 +202,7 @@ __global__ __launch_bounds__(256) void k_group_gather(GroupArgs a) {
                     if (row[r] >= 0 && lane + 64 * v < d4) x[r][v] = p4[lane + 64 * v];
                 }
             }
-            fetch_meta(u0 + 4 * RB);
+            fetch_meta(u0 + kGatherWaves * RB);
 #pragma unroll
             for (int r = 0; r < RB; ++r) {
                 for (int g = 0; g < ng; ++g) {
@@ -226,7 +228,7 @@ __global__ __launch_bounds__(256) void k_group_gather(GroupArgs a) {
             }
         }
     } else {
-        for (int u = ubeg + wv; u < uend; u += 4) {
+        for (int u = ubeg + wv; u < uend; u += kGatherWaves) {
             const int row = a.u_row[gbase + u];
             const uint32_t mk = a.u_mask[gbase + u];
             const float* p = a.corpus + (size_t)row * d;
