@@ -75,10 +75,10 @@ struct DevBuf {
     template <typename T> T* as() const { return reinterpret_cast<T*>(p); }
 };
 
-enum KernelId { K_PROJECT, K_QUANTIZE, K_CENTROID, K_SELECT_W, K_BUCKET_COUNT, K_SCAN, K_SCATTER, K_STAGE_A, K_PAIR_MAX, K_SELECT_QUERY, K_SELECT_M, K_ORDER, K_UNION, K_RERANK, K_TOPK, K_ZERO, K_COUNT };
+enum KernelId { K_PROJECT, K_QUANTIZE, K_CENTROID, K_SELECT_W, K_BUCKET_COUNT, K_SCAN, K_SCATTER, K_STAGE_A, K_PAIR_MAX, K_SELECT_QUERY, K_SELECT_M, K_ORDER, K_UNION, K_RERANK, K_TOPK, K_COUNT };
 const char* const kKernelNames[K_COUNT] = {"project_f64", "quantize_rows", "centroid_dissim_f64", "select_clusters",
                                             "bucket_count", "scan_buckets", "scatter_pairs", "stage_a_i8", "pair_max_i8", "select_query", "score_select_exact",
-                                            "order_queries", "group_union", "rerank", "topk", "zero_counters"};
+                                            "order_queries", "group_union", "rerank", "topk"};
 
 struct EventPair { hipEvent_t a, b; int kid; };
 
@@ -211,12 +211,9 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
         qp = ix->qproj.as<float>();
     }
     {
-        Prof p(ix, K_ZERO);
-        hipLaunchKernelGGL(k_zero_i32, dim3((2 * L + 256) / 256), dim3(256), 0, s, ix->count.as<int32_t>(), (int64_t)2 * L + 1);
-    }
-    {
         Prof p(ix, K_QUANTIZE);
-        hipLaunchKernelGGL(k_quantize_rows, dim3((unsigned)((nq + 3) / 4)), dim3(256), 0, s, qp, ix->q8.as<int8_t>(), ix->dx.as<float>(), (int)nq, dp);
+        hipLaunchKernelGGL(k_quantize_rows, dim3((unsigned)((nq + 3) / 4)), dim3(256), 0, s, qp, ix->q8.as<int8_t>(), ix->dx.as<float>(), (int)nq, dp,
+                           ix->count.as<int32_t>(), 2 * L + 1);
     }
     {
         Prof p(ix, K_CENTROID);
@@ -312,10 +309,11 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
             qa.sel = ix->sel.as<int32_t>(); qa.pos_of_slot = ix->pos_of_slot.as<int32_t>(); qa.pmax = ix->pmax.as<uint32_t>();
             qa.Z = ix->Z.as<int8_t>(); qa.sigma = ix->sigma.as<float>(); qa.Bp = ix->Bp; qa.off = ix->off; qa.sqnorm = l2 ? ix->sqnorm : nullptr;
             qa.cand = ix->cand.as<int32_t>(); qa.tau = ix->tau.as<float>(); qa.n_kept = ix->n_kept.as<int32_t>(); qa.qkey = ix->qkey.as<int32_t>();
-            qa.fb_list = ix->fb_list.as<int32_t>(); qa.fb_count = ix->count.as<int32_t>() + 2 * L; qa.w = w; qa.m = m; qa.cap = select_query_cap(m);
+            qa.fb_list = ix->fb_list.as<int32_t>(); qa.fb_count = ix->count.as<int32_t>() + 2 * L; qa.qorder = ix->qorder.as<int32_t>(); qa.nq = (int)nq; qa.w = w; qa.m = m; qa.cap = select_query_cap(m);
             const size_t qlds = (size_t)qa.cap * 8;
-            if (ks == 1) hipLaunchKernelGGL(k_select_query<2>, dim3((unsigned)nq), dim3(256), qlds, s, qa);
-            else hipLaunchKernelGGL(k_select_query<4>, dim3((unsigned)nq), dim3(256), qlds, s, qa);
+            const dim3 qgrid((unsigned)(8 * ((nq + 7) / 8)));
+            if (ks == 1) hipLaunchKernelGGL(k_select_query<2>, qgrid, dim3(256), qlds, s, qa);
+            else hipLaunchKernelGGL(k_select_query<4>, qgrid, dim3(256), qlds, s, qa);
         }
         {
             Prof p(ix, K_SELECT_M);

@@ -9,9 +9,11 @@ namespace lorann {
 // ---- Sec. 3.3: x_i8 = round(c_x x), c_x = 127 / |x|_inf; step size Delta_x = |x|_inf / 127. ----
 // One wavefront per query row; block = 256 (4 rows).  Round-half-to-even, codes clamped to [-127, 127];
 // a zero row gives zero codes and step 0.  The quotients are formed in double and rounded once, which equals
-// IEEE float division.
+// IEEE float division.  The first blocks also clear the `nzero` counters of the counting sorts that follow.
 __global__ __launch_bounds__(256) void k_quantize_rows(const float* __restrict__ qp, int8_t* __restrict__ q8,
-                                                        float* __restrict__ dx, int nq, int dp) {
+                                                        float* __restrict__ dx, int nq, int dp,
+                                                        int32_t* __restrict__ zero, int nzero) {
+    for (int i = blockIdx.x * 256 + threadIdx.x; i < nzero; i += gridDim.x * 256) zero[i] = 0;
     const int lane = threadIdx.x & 63;
     const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (row >= nq) return;

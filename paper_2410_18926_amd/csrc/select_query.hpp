@@ -93,11 +93,14 @@ struct QuerySelectArgs {
     int32_t* qkey;               // out [nq]: smallest candidate row (locality hint for the order of the re-rank)
     int32_t* fb_list;            // out: queries that need the exact per-query kernel
     int32_t* fb_count;           //      and their number (0 on entry)
-    int w, m;
+    const int32_t* qorder;       // [nq] queries grouped by nearest cluster (visiting order)
+    int nq, w, m;
     int cap;                     // select_query_cap(m)
 };
 
-// grid = nq, block = 256, dynamic LDS = 8 * cap bytes.  RB = r_pad / 16.
+// grid = 8 * ceil(nq / 8), block = 256, dynamic LDS = 8 * cap bytes.  RB = r_pad / 16.
+// Queries are visited grouped by nearest cluster, consecutive ones on the same XCD (workgroups are dealt
+// round-robin over the 8 XCDs): queries that score the same cluster run together and share its codes in L2.
 template <int RB>
 __global__ __launch_bounds__(256) void k_select_query(QuerySelectArgs a) {
     constexpr int ZW = RB * 4;
@@ -113,7 +116,10 @@ __global__ __launch_bounds__(256) void k_select_query(QuerySelectArgs a) {
     __shared__ int ppos[256], order[256];
     __shared__ int s_count, s_out, s_ties;
     const int tid = threadIdx.x;
-    const int q = blockIdx.x;
+    const int per_xcd = (a.nq + 7) >> 3;
+    const int si = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
+    if (si >= a.nq) return;
+    const int q = a.qorder[si];
     const int w = a.w, m = a.m;
     const bool l2 = a.sqnorm != nullptr;
     if (tid == 0) s_count = 0;
