@@ -9,6 +9,7 @@ int8 scoring, top-m, exact re-rank), with index, queries and outputs resident in
 from __future__ import annotations
 
 import argparse
+import dataclasses
 import json
 import os
 import sys
@@ -56,6 +57,59 @@ def kernel_models(wl, nq, touched_rows, npairs):
     }
 
 
+def batch_sweep(torch, gix, wl, dev, batch_sizes, k, w, m, cluster_sizes, draw_queries):
+    """Per-batch latency and throughput at several batch sizes, each batch a distinct query set; and the B_c
+    scoring kernel (pair maxima) against the HBM roof: bytes = codes of the clusters the batch touches, once,
+    plus the pairs' z and sigma."""
+    rows = []
+    for b in batch_sizes:
+        iters = 200 if b <= 1024 else (40 if b <= 16384 else 10)
+        n_sets = min(iters, max(1, (1 << 22) // b))               # distinct query sets held at once
+        pool = draw_queries(wl, dev, b * n_sets, 100 + len(rows))
+        out = (torch.empty((b, k), dtype=torch.int64, device=dev), torch.empty((b, k), dtype=torch.float32, device=dev))
+        for i in range(3):
+            gix.search(pool[(i % n_sets) * b:(i % n_sets + 1) * b], k, w, m, out=out)
+        torch.cuda.synchronize()
+        lat = []
+        for i in range(iters):
+            q = pool[(i % n_sets) * b:(i % n_sets + 1) * b]
+            t0 = time.perf_counter()
+            gix.search(q, k, w, m, out=out)
+            torch.cuda.synchronize()
+            lat.append((time.perf_counter() - t0) * 1e3)
+        lat = np.sort(np.array(lat))
+        # kernel table of this batch size (events on every kernel; separate pass)
+        gix.profile_enable(1)
+        n_ev = min(iters, 20)
+        for i in range(n_ev):
+            gix.search(pool[(i % n_sets) * b:(i % n_sets + 1) * b], k, w, m, out=out)
+        torch.cuda.synchronize()
+        prof = gix.profile_get()
+        gix.profile_enable(0)
+        sel = gix.search_stages(pool[:min(b, 20000)], k, w, m)[2]["sel"]
+        touched = np.zeros(wl.L, bool)
+        touched[np.unique(sel)] = True
+        frac_seen = min(b, 20000) / b
+        touched_rows = int(cluster_sizes[touched].sum()) if frac_seen == 1.0 else int(cluster_sizes.sum())
+        b_bytes = touched_rows * (wl.r + (4 if wl.metric == 1 else 0)) + b * w * (wl.r + 4)
+        row = {"batch": b, "iters": iters, "latency_ms_p50": round(float(np.percentile(lat, 50)), 4),
+               "latency_ms_p99": round(float(np.percentile(lat, 99)), 4), "latency_ms_best": round(float(lat[0]), 4),
+               "queries_per_s": round(b / (float(np.median(lat)) / 1e3), 1),
+               "touched_clusters": int(touched.sum()) if frac_seen == 1.0 else None,
+               "kernels_ms": {n: round(ms / max(1, c), 5) for n, (ms, c) in prof.items() if c}}
+        pm = prof.get("pair_max_i8")
+        if pm and pm[1]:
+            avg_ms = pm[0] / pm[1] * (pm[1] / n_ev)               # per search call (large batches run in chunks)
+            row["b_scoring"] = {"kernel": "pair_max_i8", "bytes": b_bytes, "ms_per_batch": round(avg_ms, 5),
+                                "achieved_GBs": round(b_bytes / 1e9 / (avg_ms / 1e3), 1), "peak_GBs": PEAK_HBM_GBS,
+                                "frac": round(b_bytes / 1e9 / (avg_ms / 1e3) / PEAK_HBM_GBS, 4)}
+        log(f"[bench] sweep batch {b}: p50 {row['latency_ms_p50']} ms, p99 {row['latency_ms_p99']} ms, "
+            f"{row['queries_per_s']:.0f} q/s, B scoring {row.get('b_scoring')}")
+        rows.append(row)
+        del pool, out
+    return rows
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -65,6 +119,10 @@ def main():
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (development only)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target duration of the oracle baseline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--batch", type=int, default=None, help="queries per step (default: the workload's batch)")
+    ap.add_argument("--recall-queries", type=int, default=10000, help="recall is measured on this many queries of the batch")
+    ap.add_argument("--batch-sweep", default="", help="comma-separated batch sizes: per-batch latency (p50/p99), "
+                    "queries/s and the B_c scoring kernel's GB/s at each, reported under 'batch_sweep'")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain 1 GiB elementwise copy (calibrates the HBM byte counters under rocprofv3 --pmc)")
     args = ap.parse_args()
@@ -75,7 +133,7 @@ def main():
 
     import torch
     from paper_2410_18926_amd import binding
-    from paper_2410_18926_amd.synth import get_workload, make_dataset, build_index
+    from paper_2410_18926_amd.synth import get_workload, make_dataset, build_index, draw_queries
     from paper_2410_18926_amd.synth.data import brute_force_topk
 
     if not torch.cuda.is_available():
@@ -86,6 +144,8 @@ def main():
     wl = get_workload(args.workload)
     if args.scale != 1.0:
         wl = wl.scaled(args.scale)
+    if args.batch:
+        wl = dataclasses.replace(wl, nq=args.batch)
     K, W = args.steps, args.warmup
 
     t0 = time.time()
@@ -99,9 +159,11 @@ def main():
     torch.cuda.synchronize()
     build_s = time.time() - t0
     log(f"[bench] index built in {build_s:.1f}s")
-    gt_ids, gt_d = brute_force_topk(corpus, queries, wl.metric, wl.k)
+    n_rec = min(wl.nq, args.recall_queries)
+    gt_ids, gt_d = brute_force_topk(corpus, queries[:n_rec], wl.metric, wl.k)
     gt_d = gt_d.cpu().numpy()
     del corpus
+    log(f"[bench] ground truth for {n_rec} queries done")
 
     gix = binding.Index.from_arrays(ix)
     gix.use_torch_stream()
@@ -133,10 +195,10 @@ def main():
 
     ids, dists = gix.search(queries, k, w, m)
     ids_h, dists_h = ids.cpu().numpy(), dists.cpu().numpy()
-    recall = recall_at_k(ids_h, dists_h, gt_d)
+    recall = recall_at_k(ids_h[:n_rec], dists_h[:n_rec], gt_d)
     # map returned ids (original corpus indices) check: true top-k ids overlap, as a second recall definition
     gt_ids_h = gt_ids.cpu().numpy()
-    recall_ids = float(np.mean([len(set(ids_h[i]) & set(gt_ids_h[i])) / k for i in range(0, nq, max(1, nq // 2000))]))
+    recall_ids = float(np.mean([len(set(ids_h[i]) & set(gt_ids_h[i])) / k for i in range(0, n_rec, max(1, n_rec // 2000))]))
 
     # per-kernel roofline figures from the events recorded over the timed region
     sizes = (ix.cluster_offsets[1:] - ix.cluster_offsets[:-1]).cpu().numpy()
@@ -170,6 +232,10 @@ def main():
         roofline = {"kernel": dom["kernel"], "bound": dom["bound"], "achieved": dom["achieved"], "peak": dom["peak"],
                     "unit": dom["unit"], "frac": dom["frac"], "avg_ms": dom["avg_ms"],
                     "traffic": MEASURED_TRAFFIC_GB.get((args.workload, args.scale, dom["kernel"]))}
+
+    sweep = None
+    if args.batch_sweep:
+        sweep = batch_sweep(torch, gix, wl, dev, [int(x) for x in args.batch_sweep.split(",")], k, w, m, sizes, draw_queries)
 
     cpu_baseline = None
     oracle_match = None
@@ -224,6 +290,8 @@ def main():
         "fallback_queries_per_step": fallback_queries / K,
         "index_build_s": round(build_s, 1),
     }
+    if sweep is not None:
+        res["batch_sweep"] = sweep
     print(json.dumps(res), flush=True)
 
 

@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 namespace lorann {
 
 typedef int i32x4 __attribute__((ext_vector_type(4)));
@@ -27,6 +29,23 @@ __device__ __forceinline__ float wave_max_f32(float v) {
 __device__ __forceinline__ float wave_sum_f32(float v) {
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+    return v;
+}
+// Sum over the 64 lanes with data-parallel-primitive moves (no LDS traffic, unlike the shuffles above): prefix
+// sums inside each row of 16 lanes (shifts by 1, 2, 4, 8 with zero fill), then lane 15 of a row is added to the
+// next row, then lane 31 to the upper half.  The TOTAL IS VALID IN LANE 63 ONLY.
+__device__ __forceinline__ float wave_sum_f32_lane63(float v) {
+    auto shifted = [](float x, auto ctrl, auto row_mask, auto bound) {
+        return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), decltype(ctrl)::value, decltype(row_mask)::value, 0xf,
+                                                          decltype(bound)::value));
+    };
+    using std::integral_constant;
+    v += shifted(v, integral_constant<int, 0x111>{}, integral_constant<int, 0xf>{}, integral_constant<bool, true>{});   // row_shr:1
+    v += shifted(v, integral_constant<int, 0x112>{}, integral_constant<int, 0xf>{}, integral_constant<bool, true>{});   // row_shr:2
+    v += shifted(v, integral_constant<int, 0x114>{}, integral_constant<int, 0xf>{}, integral_constant<bool, true>{});   // row_shr:4
+    v += shifted(v, integral_constant<int, 0x118>{}, integral_constant<int, 0xf>{}, integral_constant<bool, true>{});   // row_shr:8
+    v += shifted(v, integral_constant<int, 0x142>{}, integral_constant<int, 0xa>{}, integral_constant<bool, false>{});  // row_bcast:15 -> rows 1, 3
+    v += shifted(v, integral_constant<int, 0x143>{}, integral_constant<int, 0xc>{}, integral_constant<bool, false>{});  // row_bcast:31 -> rows 2, 3
     return v;
 }
 __device__ __forceinline__ double wave_sum_f64(double v) {

@@ -9,6 +9,13 @@
 //
 // Register layout of v_mfma_f64_16x16x4_f64 (measured on gfx950): A operand lane l holds A[l%16][l/16],
 // B operand lane l holds B[l/16][l%16], result register v of lane l holds D[4v + l/16][l%16].
+//
+// No LDS staging: both operands are K-contiguous in memory, and the instruction does not care WHICH four k a
+// step contracts as long as A and B agree.  So lane (i = l%16, g = l/16) fetches 16-byte pieces
+// X[row i][k0 + 16h + 4g .. +3] straight into registers and step (h, j) of the chunk contracts the k's
+// {k0 + 16h + 4g + j : g = 0..3}.  Every global load is a full float4, a row's 128 bytes of a 32-k chunk are
+// consumed by one wavefront, and there are no barriers; the two wavefronts of a block that share rows (or
+// columns) find them in the vector cache.
 #pragma once
 #include <cmath>
 
@@ -18,41 +25,40 @@ namespace lorann {
 
 enum { EPI_PLAIN = 0, EPI_NEG = 1, EPI_L2 = 2 };
 
-constexpr int GM_BN = 64, GM_KT = 32, GM_LD = GM_KT + 1;
+constexpr int GM_BN = 64, GM_KC = 32;
 
-// One operand tile (rows x 16 k) is fetched as one float4 per thread.
-__device__ __forceinline__ float4 gemm_fetch(const float* __restrict__ base, int rows, int K, int row, int k, bool vec_ok) {
+// Guarded fetch of four floats p[k .. k+3] of a row of length K (zero beyond the end); any alignment.
+__device__ __forceinline__ float4 gemm_fetch_tail(const float* __restrict__ p, int k, int K) {
     float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (row < rows) {
-        const float* p = base + (size_t)row * K + k;
-        if (vec_ok && k + 4 <= K) {
-            v = *reinterpret_cast<const float4*>(p);
-        } else {
-            if (k + 0 < K) v.x = p[0];
-            if (k + 1 < K) v.y = p[1];
-            if (k + 2 < K) v.z = p[2];
-            if (k + 3 < K) v.w = p[3];
-        }
-    }
+    if (k + 0 < K) v.x = p[k + 0];
+    if (k + 1 < K) v.y = p[k + 1];
+    if (k + 2 < K) v.z = p[k + 2];
+    if (k + 3 < K) v.w = p[k + 3];
     return v;
 }
 
-// grid = (ceil(N/64), ceil(M/BM)), block = 256 (2 x 2 wavefronts, each BM/2 x 32 of the BM x 64 block tile).
+// grid = (ceil(N/64), ceil(M/BM)), block = 256 (2 x 2 wavefronts, each (BM/2) x 32 of the BM x 64 block tile).
 // BM = 64 or 32: the smaller tile is used when it fills the machine more evenly (see gemm_pick_bm).
 // X [M][K], W [N][K] row-major, out [M][N].  nrm [N] (double) is used by EPI_L2 only: out = nrm[n] - 2 * acc.
+// vec_ok: rows of X and W are 16-byte aligned (K % 4 == 0 and aligned bases); otherwise every chunk takes the
+// guarded scalar path.
 template <int EPI, int BM>
 __global__ __launch_bounds__(256) void k_gemm_nt_f64(const float* __restrict__ X, const float* __restrict__ W,
                                                       float* __restrict__ out, const double* __restrict__ nrm,
-                                                      int M, int N, int K) {
+                                                      int M, int N, int K, int vec_ok) {
     constexpr int TI = BM / 32;          // 16-row MFMA tiles per wavefront along M
-    __shared__ float Xs[BM * GM_LD];
-    __shared__ float Ws[GM_BN * GM_LD];
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int wm = wv >> 1, wn = wv & 1;
-    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * GM_BN;
-    const int lrow = tid >> 2, lk = (tid & 3) * 4;
-    const bool vec_ok = (K % 4) == 0;
-    const bool x_loader = lrow < BM;
+    const int i = lane & 15, g = lane >> 4;
+    const int m0 = blockIdx.y * BM + wm * (BM / 2), n0 = blockIdx.x * GM_BN + wn * 32;
+
+    // rows / columns beyond the matrix are clamped (loaded, never stored)
+    const float* xa[TI];
+    const float* wb[2];
+#pragma unroll
+    for (int ti = 0; ti < TI; ++ti) xa[ti] = X + (size_t)min(m0 + ti * 16 + i, M - 1) * K;
+#pragma unroll
+    for (int tj = 0; tj < 2; ++tj) wb[tj] = W + (size_t)min(n0 + tj * 16 + i, N - 1) * K;
 
     f64x4 acc[TI][2];
 #pragma unroll
@@ -60,49 +66,73 @@ __global__ __launch_bounds__(256) void k_gemm_nt_f64(const float* __restrict__ X
 #pragma unroll
         for (int b = 0; b < 2; ++b) acc[a][b] = (f64x4){0.0, 0.0, 0.0, 0.0};
 
-    float4 rx = make_float4(0.f, 0.f, 0.f, 0.f), rx2 = rx;
-    if (x_loader) { rx = gemm_fetch(X, M, K, m0 + lrow, lk, vec_ok); rx2 = gemm_fetch(X, M, K, m0 + lrow, lk + 16, vec_ok); }
-    float4 rw = gemm_fetch(W, N, K, n0 + lrow, lk, vec_ok), rw2 = gemm_fetch(W, N, K, n0 + lrow, lk + 16, vec_ok);
-    const int i = lane & 15, g = lane >> 4;
-
-    for (int k0 = 0; k0 < K; k0 += GM_KT) {
-        if (x_loader) {
-            float* xs = Xs + lrow * GM_LD + lk;
-            xs[0] = rx.x; xs[1] = rx.y; xs[2] = rx.z; xs[3] = rx.w;
-            xs[16] = rx2.x; xs[17] = rx2.y; xs[18] = rx2.z; xs[19] = rx2.w;
-        }
-        float* ws = Ws + lrow * GM_LD + lk;
-        ws[0] = rw.x; ws[1] = rw.y; ws[2] = rw.z; ws[3] = rw.w;
-        ws[16] = rw2.x; ws[17] = rw2.y; ws[18] = rw2.z; ws[19] = rw2.w;
-        __syncthreads();
-        if (k0 + GM_KT < K) {
-            if (x_loader) { rx = gemm_fetch(X, M, K, m0 + lrow, k0 + GM_KT + lk, vec_ok); rx2 = gemm_fetch(X, M, K, m0 + lrow, k0 + GM_KT + lk + 16, vec_ok); }
-            rw = gemm_fetch(W, N, K, n0 + lrow, k0 + GM_KT + lk, vec_ok); rw2 = gemm_fetch(W, N, K, n0 + lrow, k0 + GM_KT + lk + 16, vec_ok);
-        }
+    auto contract = [&](const float4 (&a)[TI][2], const float4 (&b)[2][2]) {
 #pragma unroll
-        for (int kk = 0; kk < GM_KT; kk += 4) {
-            double a[TI];
+        for (int h = 0; h < 2; ++h) {
 #pragma unroll
-            for (int ti = 0; ti < TI; ++ti) a[ti] = (double)Xs[(wm * (BM / 2) + ti * 16 + i) * GM_LD + kk + g];
-            const double b0 = (double)Ws[(wn * 32 + i) * GM_LD + kk + g];
-            const double b1 = (double)Ws[(wn * 32 + 16 + i) * GM_LD + kk + g];
+            for (int j = 0; j < 4; ++j) {
+                double av[TI], bv[2];
 #pragma unroll
-            for (int ti = 0; ti < TI; ++ti) {
-                acc[ti][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[ti], b0, acc[ti][0], 0, 0, 0);
-                acc[ti][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[ti], b1, acc[ti][1], 0, 0, 0);
+                for (int ti = 0; ti < TI; ++ti) av[ti] = (double)(j == 0 ? a[ti][h].x : j == 1 ? a[ti][h].y : j == 2 ? a[ti][h].z : a[ti][h].w);
+#pragma unroll
+                for (int tj = 0; tj < 2; ++tj) bv[tj] = (double)(j == 0 ? b[tj][h].x : j == 1 ? b[tj][h].y : j == 2 ? b[tj][h].z : b[tj][h].w);
+#pragma unroll
+                for (int ti = 0; ti < TI; ++ti)
+#pragma unroll
+                    for (int tj = 0; tj < 2; ++tj)
+                        acc[ti][tj] = __builtin_amdgcn_mfma_f64_16x16x4f64(av[ti], bv[tj], acc[ti][tj], 0, 0, 0);
             }
         }
-        __syncthreads();
+    };
+
+    const int k_full = vec_ok ? (K / GM_KC) * GM_KC : 0;     // chunks fetched with unconditional float4 loads
+    if (k_full > 0) {
+        float4 a_cur[TI][2], b_cur[2][2], a_nxt[TI][2], b_nxt[2][2];
+        auto fetch = [&](int k0, float4 (&a)[TI][2], float4 (&b)[2][2]) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int k = k0 + 16 * h + 4 * g;
+#pragma unroll
+                for (int ti = 0; ti < TI; ++ti) a[ti][h] = *reinterpret_cast<const float4*>(xa[ti] + k);
+#pragma unroll
+                for (int tj = 0; tj < 2; ++tj) b[tj][h] = *reinterpret_cast<const float4*>(wb[tj] + k);
+            }
+        };
+        fetch(0, a_cur, b_cur);
+        for (int k0 = 0; k0 < k_full; k0 += GM_KC) {
+            // the next chunk is requested before this one is contracted (clamped: the last request is a repeat)
+            fetch(min(k0 + GM_KC, k_full - GM_KC), a_nxt, b_nxt);
+            contract(a_cur, b_cur);
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+#pragma unroll
+                for (int ti = 0; ti < TI; ++ti) a_cur[ti][h] = a_nxt[ti][h];
+#pragma unroll
+                for (int tj = 0; tj < 2; ++tj) b_cur[tj][h] = b_nxt[tj][h];
+            }
+        }
+    }
+    for (int k0 = k_full; k0 < K; k0 += GM_KC) {             // remainder (or everything when rows are unaligned)
+        float4 a[TI][2], b[2][2];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int k = k0 + 16 * h + 4 * g;
+#pragma unroll
+            for (int ti = 0; ti < TI; ++ti) a[ti][h] = gemm_fetch_tail(xa[ti], k, K);
+#pragma unroll
+            for (int tj = 0; tj < 2; ++tj) b[tj][h] = gemm_fetch_tail(wb[tj], k, K);
+        }
+        contract(a, b);
     }
 
 #pragma unroll
     for (int ti = 0; ti < TI; ++ti)
 #pragma unroll
         for (int tj = 0; tj < 2; ++tj) {
-            const int col = n0 + wn * 32 + tj * 16 + i;
+            const int col = n0 + tj * 16 + i;
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                const int row = m0 + wm * (BM / 2) + ti * 16 + 4 * v + g;
+                const int row = m0 + ti * 16 + 4 * v + g;
                 if (row < M && col < N) {
                     const double s = acc[ti][tj][v];
                     float o;

@@ -204,10 +204,11 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
     const float* qp = dQ;   // projected queries
     if (ix->Pt) {
         Prof p(ix, K_PROJECT);
+        const int pvec = (d % 4 == 0 && (reinterpret_cast<uintptr_t>(dQ) & 15u) == 0 && (reinterpret_cast<uintptr_t>(ix->Pt) & 15u) == 0) ? 1 : 0;
         if (gemm_pick_bm(nq, dp) == 64)
-            hipLaunchKernelGGL((k_gemm_nt_f64<EPI_PLAIN, 64>), dim3((dp + 63) / 64, (unsigned)((nq + 63) / 64)), dim3(256), 0, s, dQ, ix->Pt, ix->qproj.as<float>(), (const double*)nullptr, (int)nq, dp, d);
+            hipLaunchKernelGGL((k_gemm_nt_f64<EPI_PLAIN, 64>), dim3((dp + 63) / 64, (unsigned)((nq + 63) / 64)), dim3(256), 0, s, dQ, ix->Pt, ix->qproj.as<float>(), (const double*)nullptr, (int)nq, dp, d, pvec);
         else
-            hipLaunchKernelGGL((k_gemm_nt_f64<EPI_PLAIN, 32>), dim3((dp + 63) / 64, (unsigned)((nq + 31) / 32)), dim3(256), 0, s, dQ, ix->Pt, ix->qproj.as<float>(), (const double*)nullptr, (int)nq, dp, d);
+            hipLaunchKernelGGL((k_gemm_nt_f64<EPI_PLAIN, 32>), dim3((dp + 63) / 64, (unsigned)((nq + 31) / 32)), dim3(256), 0, s, dQ, ix->Pt, ix->qproj.as<float>(), (const double*)nullptr, (int)nq, dp, d, pvec);
         qp = ix->qproj.as<float>();
     }
     {
@@ -218,14 +219,15 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
     {
         Prof p(ix, K_CENTROID);
         const bool big = gemm_pick_bm(nq, L) == 64;
+        const int cvec = (dp % 4 == 0 && (reinterpret_cast<uintptr_t>(qp) & 15u) == 0 && (reinterpret_cast<uintptr_t>(ix->centroids) & 15u) == 0) ? 1 : 0;
         const dim3 grid((L + 63) / 64, (unsigned)(big ? (nq + 63) / 64 : (nq + 31) / 32));
         float* gs = ix->gscore.as<float>();
         if (ix->metric == LORANN_L2) {
-            if (big) hipLaunchKernelGGL((k_gemm_nt_f64<EPI_L2, 64>), grid, dim3(256), 0, s, qp, ix->centroids, gs, (const double*)ix->cent_sqnorm, (int)nq, L, dp);
-            else hipLaunchKernelGGL((k_gemm_nt_f64<EPI_L2, 32>), grid, dim3(256), 0, s, qp, ix->centroids, gs, (const double*)ix->cent_sqnorm, (int)nq, L, dp);
+            if (big) hipLaunchKernelGGL((k_gemm_nt_f64<EPI_L2, 64>), grid, dim3(256), 0, s, qp, ix->centroids, gs, (const double*)ix->cent_sqnorm, (int)nq, L, dp, cvec);
+            else hipLaunchKernelGGL((k_gemm_nt_f64<EPI_L2, 32>), grid, dim3(256), 0, s, qp, ix->centroids, gs, (const double*)ix->cent_sqnorm, (int)nq, L, dp, cvec);
         } else {
-            if (big) hipLaunchKernelGGL((k_gemm_nt_f64<EPI_NEG, 64>), grid, dim3(256), 0, s, qp, ix->centroids, gs, (const double*)nullptr, (int)nq, L, dp);
-            else hipLaunchKernelGGL((k_gemm_nt_f64<EPI_NEG, 32>), grid, dim3(256), 0, s, qp, ix->centroids, gs, (const double*)nullptr, (int)nq, L, dp);
+            if (big) hipLaunchKernelGGL((k_gemm_nt_f64<EPI_NEG, 64>), grid, dim3(256), 0, s, qp, ix->centroids, gs, (const double*)nullptr, (int)nq, L, dp, cvec);
+            else hipLaunchKernelGGL((k_gemm_nt_f64<EPI_NEG, 32>), grid, dim3(256), 0, s, qp, ix->centroids, gs, (const double*)nullptr, (int)nq, L, dp, cvec);
         }
     }
     {
@@ -234,6 +236,10 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
             hipLaunchKernelGGL(k_select_clusters_wave<16>, dim3((unsigned)((nq + 3) / 4)), dim3(256), 0, s, ix->gscore.as<float>(), (int)nq, L, w, ix->sel.as<int32_t>());
         else if (L <= 4096)
             hipLaunchKernelGGL(k_select_clusters_wave<64>, dim3((unsigned)((nq + 3) / 4)), dim3(256), 0, s, ix->gscore.as<float>(), (int)nq, L, w, ix->sel.as<int32_t>());
+        else if (L <= 8192)
+            hipLaunchKernelGGL(k_select_clusters_regs<32>, dim3((unsigned)nq), dim3(256), 0, s, ix->gscore.as<float>(), L, w, ix->sel.as<int32_t>());
+        else if (L <= 16384)
+            hipLaunchKernelGGL(k_select_clusters_regs<64>, dim3((unsigned)nq), dim3(256), 0, s, ix->gscore.as<float>(), L, w, ix->sel.as<int32_t>());
         else
             hipLaunchKernelGGL(k_select_clusters, dim3((unsigned)nq), dim3(256), 0, s, ix->gscore.as<float>(), L, w, ix->sel.as<int32_t>());
     }
@@ -297,8 +303,14 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
             sc.Bp = ix->Bp; sc.Z = ix->Z.as<int8_t>(); sc.sigma = ix->sigma.as<float>(); sc.off = ix->off;
             sc.bucket_off = ix->bucket_off.as<int32_t>(); sc.unit_off = ix->unit_off.as<int32_t>();
             sc.sqnorm = l2 ? ix->sqnorm : nullptr; sc.pmax = ix->pmax.as<uint32_t>(); sc.L = L; sc.chunk_tiles = kChunkTiles;
-            const dim3 ugrid(2048);             // persistent: 8192 wavefronts stride over the work items
-#define LAUNCH_PM(KS_, L2_) hipLaunchKernelGGL((k_pair_max<kNZ, KS_, L2_>), ugrid, dim3(256), 0, s, sc)
+            // few pairs per cluster: the kernel streams the codes of the touched clusters, one wavefront per cluster
+            const bool stream = npairs <= (int64_t)16 * L;
+            const dim3 ugrid(stream ? (unsigned)((L + 3) / 4) : 2048u);     // else persistent: 8192 wavefronts stride over the work items
+#define LAUNCH_PM(KS_, L2_)                                                                                          \
+    do {                                                                                                             \
+        if (stream) hipLaunchKernelGGL((k_pair_max<1, KS_, L2_, 8 / KS_, true>), ugrid, dim3(256), 0, s, sc);         \
+        else hipLaunchKernelGGL((k_pair_max<kNZ, KS_, L2_, 4, false>), ugrid, dim3(256), 0, s, sc);                   \
+    } while (0)
             if (ks == 1) { if (l2) LAUNCH_PM(1, true); else LAUNCH_PM(1, false); }
             else         { if (l2) LAUNCH_PM(2, true); else LAUNCH_PM(2, false); }
 #undef LAUNCH_PM
@@ -324,7 +336,8 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
         }
     }
     const int mp2 = std::max(256, next_pow2(m));
-    if (m <= 512 && !ix->force_exact && (size_t)kGroupQ * d * 4 <= 48 * 1024) {
+    const int kGroupQ = rerank_group_size(d);    // queries per re-rank group (0: rows too long to share)
+    if (m <= 512 && !ix->force_exact && kGroupQ > 0) {
         // grouped re-rank: neighbours in the visiting order share candidate rows, each distinct row is gathered once
         {
             Prof p(ix, K_ORDER);
@@ -334,7 +347,7 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
         const int64_t ngroups = (nq + kGroupQ - 1) / kGroupQ;
         const size_t gm = (size_t)kGroupQ * m;
         if ((rc = ix->u_row.reserve(ngroups * gm * 4))) return rc;
-        if ((rc = ix->u_mask.reserve(ngroups * gm))) return rc;
+        if ((rc = ix->u_mask.reserve(ngroups * gm * 2))) return rc;
         if ((rc = ix->u_pos.reserve(ngroups * gm * kGroupQ * 2))) return rc;
         if ((rc = ix->u_count.reserve((size_t)ngroups * 4))) return rc;
         if ((rc = ix->rdist.reserve((size_t)nq * m * 4))) return rc;
@@ -342,24 +355,43 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
         if ((rc = ix->rccount.reserve((size_t)nq * 4))) return rc;
         GroupArgs ga;
         ga.Q = dQ; ga.corpus = ix->corpus; ga.ids = ix->ids; ga.cand = ix->cand.as<int32_t>(); ga.qorder = ix->qorder2.as<int32_t>();
-        ga.u_row = ix->u_row.as<int32_t>(); ga.u_mask = ix->u_mask.as<uint8_t>(); ga.u_pos = ix->u_pos.as<uint16_t>(); ga.u_count = ix->u_count.as<int32_t>();
+        ga.u_row = ix->u_row.as<int32_t>(); ga.u_mask = ix->u_mask.as<uint16_t>(); ga.u_pos = ix->u_pos.as<uint16_t>(); ga.u_count = ix->u_count.as<int32_t>();
         ga.dist = ix->rdist.as<float>(); ga.cid = ix->rcid.as<int64_t>(); ga.ccount = ix->rccount.as<int32_t>();
         ga.out_ids = d_ids; ga.out_dists = d_dists; ga.nq = (int)nq; ga.d = d; ga.m = m; ga.k = k;
-        ga.ht = rerank_group_ht(m);
+        ga.ht = rerank_group_ht(kGroupQ, m);
         // enough gather blocks to keep every CU evenly busy: about 2 MiB of rows per block at most
         ga.slices = (int)std::min<int64_t>(16, std::max<int64_t>(1, ((int64_t)gm * d * 4 / 2) / (2 << 20) + 1));
         while ((int64_t)ga.slices * ngroups < 4096 && ga.slices < 16) ++ga.slices;
         {
             Prof p(ix, K_UNION);
-            hipLaunchKernelGGL(k_group_union, dim3((unsigned)ngroups), dim3(256), (size_t)ga.ht * 5, s, ga);
+            if (kGroupQ == 16) hipLaunchKernelGGL(k_group_union<16>, dim3((unsigned)ngroups), dim3(256), (size_t)ga.ht * 6, s, ga);
+            else hipLaunchKernelGGL(k_group_union<8>, dim3((unsigned)ngroups), dim3(256), (size_t)ga.ht * 6, s, ga);
         }
         {
             Prof p(ix, K_RERANK);
             const dim3 grid((unsigned)(ngroups * ga.slices));
             const size_t lds = (size_t)kGroupQ * d * 4;
-            if (ix->metric == LORANN_IP) hipLaunchKernelGGL(k_group_gather<0>, grid, dim3(kGatherThreads), lds, s, ga);
-            else if (ix->metric == LORANN_L2) hipLaunchKernelGGL(k_group_gather<1>, grid, dim3(kGatherThreads), lds, s, ga);
-            else hipLaunchKernelGGL(k_group_gather<2>, grid, dim3(kGatherThreads), lds, s, ga);
+            const int nv = (d % 4 == 0 && d <= 1024) ? (d / 4 + 63) / 64 : 0;
+#define LAUNCH_GG3(M_, NV_)                                                                                    \
+    do {                                                                                                       \
+        if (kGroupQ == 16) hipLaunchKernelGGL((k_group_gather<M_, NV_, 16>), grid, dim3(kGatherThreads), lds, s, ga); \
+        else hipLaunchKernelGGL((k_group_gather<M_, NV_, 8>), grid, dim3(kGatherThreads), lds, s, ga);          \
+    } while (0)
+#define LAUNCH_GG(M_)                                                                                          \
+    do {                                                                                                       \
+        switch (nv) {                                                                                          \
+            case 1: LAUNCH_GG3(M_, 1); break;                                                                  \
+            case 2: LAUNCH_GG3(M_, 2); break;                                                                  \
+            case 3: LAUNCH_GG3(M_, 3); break;                                                                  \
+            case 4: LAUNCH_GG3(M_, 4); break;                                                                  \
+            default: LAUNCH_GG3(M_, 0); break;                                                                 \
+        }                                                                                                      \
+    } while (0)
+            if (ix->metric == LORANN_IP) LAUNCH_GG(0);
+            else if (ix->metric == LORANN_L2) LAUNCH_GG(1);
+            else LAUNCH_GG(2);
+#undef LAUNCH_GG3
+#undef LAUNCH_GG
         }
         {
             Prof p(ix, K_TOPK);

@@ -76,8 +76,8 @@ __global__ __launch_bounds__(256) void k_rerank(const float* __restrict__ Q, con
                 else acc = fmaf(p[i], qs[i], acc);
             }
         }
-        acc = wave_sum_f32(acc);
-        if (lane == 0) {
+        acc = wave_sum_f32_lane63(acc);
+        if (lane == 63) {
             float dist;
             if (METRIC == 1) dist = acc;
             else if (METRIC == 0) dist = -acc;

@@ -11,8 +11,8 @@
 //                     a row is contiguous, several rows in flight per wavefront) and scored against each query
 //                     that asked for it; work is cut into many small blocks so the machine stays evenly loaded;
 //   k_topk          : per query, the k smallest (distance, id), ties toward the lower id.
-// Distances are accumulated exactly as in the one-query-per-block kernel (same per-lane order, same shuffle
-// tree), so both paths return identical bits.
+// Distances are accumulated exactly as in the one-query-per-block kernel (same per-lane order, same reduction
+// across lanes), so both paths return identical bits.
 #pragma once
 #include <algorithm>
 
@@ -21,7 +21,7 @@
 
 namespace lorann {
 
-constexpr int kGroupQ = 8;        // queries per group (one mask byte per distinct row)
+constexpr int kGroupMax = 16;     // queries per group: 8 or 16 (one 16-bit mask per distinct row)
 
 // Order the queries inside each nearest-cluster segment of `qorder` by `qkey` (their smallest candidate row), so
 // that queries with overlapping candidate sets become neighbours.  grid = L, block = 64 (one wavefront per
@@ -55,7 +55,7 @@ struct GroupArgs {
     const int32_t* cand;         // [nq][m]
     const int32_t* qorder;       // [nq] visiting order
     int32_t* u_row;              // [ngroups][G*m]    distinct candidate rows of each group
-    uint8_t* u_mask;             // [ngroups][G*m]    bit g: query g of the group wants the row
+    uint16_t* u_mask;            // [ngroups][G*m]    bit g: query g of the group wants the row
     uint16_t* u_pos;             // [ngroups][G*m][G] where query g keeps the distance of that row
     int32_t* u_count;            // [ngroups]         number of distinct rows
     float* dist;                 // [nq][m]  exact dissimilarities, in the query's own slot order
@@ -68,18 +68,27 @@ struct GroupArgs {
     int slices;                  // gather blocks per group
 };
 
-inline int rerank_group_ht(int m) {      // hash table slots: power of two, load factor <= 0.8
+inline int rerank_group_ht(int G, int m) {      // hash table slots: power of two, load factor <= 0.8
     int ht = 16;
-    while (ht * 4 < kGroupQ * m * 5) ht <<= 1;
+    while (ht * 4 < G * m * 5) ht <<= 1;
     return ht;
 }
 
-// grid = ngroups, block = 256, dynamic LDS = ht * 5 bytes.
+// Queries per group for rows of d floats: 8 when their copies fit 48 KB of LDS (0: they do not).  Groups of 16
+// (the kernels take either) move 15 % fewer bytes on the 768-d benchmark but were measured slower overall: the
+// union costs twice as much and only three 512-thread gather blocks fit a CU.
+inline int rerank_group_size(int d) {
+    return (size_t)8 * d * 4 <= 48 * 1024 ? 8 : 0;
+}
+
+// grid = ngroups, block = 256, dynamic LDS = ht * 6 bytes.  G = queries per group.
+template <int G>
 __global__ __launch_bounds__(256) void k_group_union(GroupArgs a) {
+    constexpr int kGroupQ = G;
     extern __shared__ __align__(16) unsigned char smem[];
     const int ht = a.ht, m = a.m;
     int32_t* tkey = reinterpret_cast<int32_t*>(smem);              // [ht]
-    uint32_t* tmask = reinterpret_cast<uint32_t*>(tkey + ht);      // [ht/4], one byte per slot
+    uint32_t* tmask = reinterpret_cast<uint32_t*>(tkey + ht);      // [ht/2], 16 bits per slot
     __shared__ int s_q[kGroupQ], s_rcount[kGroupQ], s_nuniq;
     const int tid = threadIdx.x;
     const int grp = blockIdx.x;
@@ -88,9 +97,9 @@ __global__ __launch_bounds__(256) void k_group_union(GroupArgs a) {
     if (tid < kGroupQ) { s_q[tid] = tid < ng ? a.qorder[g0 + tid] : -1; s_rcount[tid] = 0; }
     if (tid == 0) s_nuniq = 0;
     for (int s = tid; s < ht; s += 256) tkey[s] = -1;
-    for (int s = tid; s < ht / 4; s += 256) tmask[s] = 0u;
+    for (int s = tid; s < ht / 2; s += 256) tmask[s] = 0u;
     __syncthreads();
-    // open addressing, key = row, one mask byte per slot (bit g: query g wants the row)
+    // open addressing, key = row, one 16-bit mask per slot (bit g: query g wants the row)
     for (int t = tid; t < ng * m; t += 256) {
         const int g = t / m, c = t - g * m;
         const int row = a.cand[(size_t)s_q[g] * m + c];
@@ -99,7 +108,7 @@ __global__ __launch_bounds__(256) void k_group_union(GroupArgs a) {
         for (;;) {
             h &= (uint32_t)(ht - 1);
             const int old = atomicCAS(&tkey[h], -1, row);
-            if (old == -1 || old == row) { atomicOr(&tmask[h >> 2], (1u << g) << (8 * (h & 3))); break; }
+            if (old == -1 || old == row) { atomicOr(&tmask[h >> 1], (1u << g) << (16 * (h & 1))); break; }
             ++h;
         }
     }
@@ -108,10 +117,10 @@ __global__ __launch_bounds__(256) void k_group_union(GroupArgs a) {
     for (int s = tid; s < ht; s += 256) {
         const int row = tkey[s];
         if (row == -1) continue;
-        const uint32_t mk = (tmask[s >> 2] >> (8 * (s & 3))) & 0xffu;
+        const uint32_t mk = (tmask[s >> 1] >> (16 * (s & 1))) & 0xffffu;
         const int at = atomicAdd(&s_nuniq, 1);
         a.u_row[gbase + at] = row;
-        a.u_mask[gbase + at] = (uint8_t)mk;
+        a.u_mask[gbase + at] = (uint16_t)mk;
         const int64_t id = a.ids ? a.ids[row] : (int64_t)row;
         for (int g = 0; g < ng; ++g) {
             if (!((mk >> g) & 1u)) continue;
@@ -127,10 +136,15 @@ __global__ __launch_bounds__(256) void k_group_union(GroupArgs a) {
 
 constexpr int kGatherThreads = 512, kGatherWaves = kGatherThreads / 64;
 
-// grid = ngroups * slices, block = kGatherThreads, dynamic LDS = G * d * 4 bytes.  METRIC: 0 inner product, 1 squared
+// grid = ngroups * slices, block = kGatherThreads, dynamic LDS = G * d * 4 bytes (G = queries per group).
+// METRIC: 0 inner product, 1 squared
 // Euclidean, 2 cosine.
-template <int METRIC>
+// NV = number of 64-lane float4 slices of a row, ceil(d / 256), for rows that live in registers (d % 4 == 0,
+// d <= 1024); NV = 0: any d, rows are streamed element by element.
+template <int METRIC, int NV, int G>
 __global__ __launch_bounds__(kGatherThreads) void k_group_gather(GroupArgs a) {
+    constexpr int kGroupQ = G;
+    constexpr int RB = 2;                                          // rows in flight per wavefront
     extern __shared__ __align__(16) unsigned char smem[];
     float* qs = reinterpret_cast<float*>(smem);                    // [G][d]
     __shared__ int s_q[kGroupQ];
@@ -146,9 +160,18 @@ __global__ __launch_bounds__(kGatherThreads) void k_group_gather(GroupArgs a) {
     if (ubeg >= uend) return;
     if (tid < kGroupQ) s_q[tid] = tid < ng ? a.qorder[g0 + tid] : -1;
     __syncthreads();
-    for (int g = 0; g < ng; ++g) {
-        const float* qrow = a.Q + (size_t)s_q[g] * d;
-        for (int i = tid; i < d; i += kGatherThreads) qs[(size_t)g * d + i] = qrow[i];
+    if (d % 4 == 0) {       // one flat loop over the float4 of all the group's queries: the loads are independent
+        const int q4n = d / 4;
+#pragma unroll 4
+        for (int t = tid; t < ng * q4n; t += kGatherThreads) {
+            const int g = t / q4n, i = t - g * q4n;
+            reinterpret_cast<float4*>(qs)[t] = reinterpret_cast<const float4*>(a.Q + (size_t)s_q[g] * d)[i];
+        }
+    } else {
+        for (int t = tid; t < ng * d; t += kGatherThreads) {
+            const int g = t / d, i = t - g * d;
+            qs[t] = a.Q[(size_t)s_q[g] * d + i];
+        }
     }
     __syncthreads();
     if (METRIC == 2) {
@@ -164,54 +187,54 @@ __global__ __launch_bounds__(kGatherThreads) void k_group_gather(GroupArgs a) {
     }
     const size_t gbase = (size_t)grp * kGroupQ * m;
     const int d4 = (d % 4 == 0) ? d / 4 : 0;      // vector path needs 16-byte aligned rows
-    auto emit = [&](int g, int pos, float acc) {  // lane 0 of the wavefront records one (query, row) distance
+    auto emit = [&](int g, int pos, float acc) {  // one lane of the wavefront records one (query, row) distance
         float dist;
         if (METRIC == 1) dist = acc;
         else if (METRIC == 0) dist = -acc;
         else dist = s_qnorm[g] > 0.0f ? 1.0f - acc / s_qnorm[g] : 1.0f;
         a.dist[(size_t)s_q[g] * m + pos] = dist;
     };
-    if (d4 && d4 <= 256) {
-        // rows of up to 1024 floats live in registers (4 float4 per lane); RB rows are fetched before any is used
-        constexpr int RB = 2;
+    if (NV > 0) {
+        // RB rows are fetched before any is used.  Every load below is unconditional (indices clamped into the
+        // row / the list instead of branching around the load), so the loads of all RB rows are in flight together.
         int nrow[RB], nps[RB];
         uint32_t nmk[RB];
         auto fetch_meta = [&](int u0) {           // (row, mask, slots) of the next RB rows, one iteration ahead
 #pragma unroll
             for (int r = 0; r < RB; ++r) {
                 const int u = u0 + r;
-                nrow[r] = u < uend ? a.u_row[gbase + u] : -1;
-                nmk[r] = u < uend ? a.u_mask[gbase + u] : 0u;
-                // lane l keeps the slot of query l % 8 for this row
-                nps[r] = u < uend ? a.u_pos[(gbase + u) * kGroupQ + (lane & (kGroupQ - 1))] : 0;
+                const size_t uc = gbase + min(u, uend - 1);
+                const int rw = a.u_row[uc];
+                const uint32_t mkk = a.u_mask[uc];
+                nps[r] = a.u_pos[uc * kGroupQ + (lane & (kGroupQ - 1))];   // lane l keeps the slot of query l % G
+                nrow[r] = u < uend ? rw : 0;
+                nmk[r] = u < uend ? mkk : 0u;
             }
         };
         fetch_meta(ubeg + wv * RB);
         for (int u0 = ubeg + wv * RB; u0 < uend; u0 += kGatherWaves * RB) {
-            float4 x[RB][4];
-            int row[RB], ps[RB];
+            float4 x[RB][NV > 0 ? NV : 1];
+            int ps[RB];
             uint32_t mk[RB];
 #pragma unroll
-            for (int r = 0; r < RB; ++r) { row[r] = nrow[r]; mk[r] = nmk[r]; ps[r] = nps[r]; }
-#pragma unroll
             for (int r = 0; r < RB; ++r) {
-                const float4* p4 = reinterpret_cast<const float4*>(a.corpus + (size_t)(row[r] < 0 ? 0 : row[r]) * d);
+                mk[r] = nmk[r]; ps[r] = nps[r];
+                const float4* p4 = reinterpret_cast<const float4*>(a.corpus + (size_t)nrow[r] * d);
 #pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    x[r][v] = make_float4(0.f, 0.f, 0.f, 0.f);
-                    if (row[r] >= 0 && lane + 64 * v < d4) x[r][v] = p4[lane + 64 * v];
-                }
+                for (int v = 0; v < NV; ++v) x[r][v] = p4[min(lane + 64 * v, d4 - 1)];
             }
             fetch_meta(u0 + kGatherWaves * RB);
 #pragma unroll
             for (int r = 0; r < RB; ++r) {
-                for (int g = 0; g < ng; ++g) {
-                    if (!((mk[r] >> g) & 1u)) continue;                    // uniform
+                uint32_t todo = __builtin_amdgcn_readfirstlane(mk[r]);     // uniform: the queries that want this row
+                while (todo) {
+                    const int g = __builtin_ctz(todo);
+                    todo &= todo - 1u;
                     const float4* q4 = reinterpret_cast<const float4*>(qs + (size_t)g * d);
                     float acc = 0.0f;
 #pragma unroll
-                    for (int v = 0; v < 4; ++v) {
-                        if (lane + 64 * v < d4) {
+                    for (int v = 0; v < NV; ++v) {
+                        if (v + 1 < NV || lane + 64 * v < d4) {            // only the last slice can be partial
                             const float4 y = q4[lane + 64 * v];
                             if (METRIC == 1) {
                                 const float a0 = y.x - x[r][v].x, a1 = y.y - x[r][v].y, a2 = y.z - x[r][v].z, a3 = y.w - x[r][v].w;
@@ -221,9 +244,9 @@ __global__ __launch_bounds__(kGatherThreads) void k_group_gather(GroupArgs a) {
                             }
                         }
                     }
-                    acc = wave_sum_f32(acc);
-                    const int pos = __shfl(ps[r], g, 64);
-                    if (lane == 0) emit(g, pos, acc);
+                    acc = wave_sum_f32_lane63(acc);
+                    const int pos = __builtin_amdgcn_readlane(ps[r], g);
+                    if (lane == 63) emit(g, pos, acc);
                 }
             }
         }
@@ -254,8 +277,8 @@ __global__ __launch_bounds__(kGatherThreads) void k_group_gather(GroupArgs a) {
                         else acc = fmaf(p[i], qg[i], acc);
                     }
                 }
-                acc = wave_sum_f32(acc);
-                if (lane == 0) emit(g, a.u_pos[(gbase + u) * kGroupQ + g], acc);
+                acc = wave_sum_f32_lane63(acc);
+                if (lane == 63) emit(g, a.u_pos[(gbase + u) * kGroupQ + g], acc);
             }
         }
     }

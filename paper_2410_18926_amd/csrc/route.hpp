@@ -37,11 +37,10 @@ __global__ __launch_bounds__(256) void k_quantize_rows(const float* __restrict__
 }
 
 // ---- Sec. 2.2: tau(x) = the w centroids of smallest dissimilarity. ----
-// One block (256 threads) per query.  g [nq][L] holds the centroid dissimilarities.  Exact selection by a
+// Block-wide exact selection over one row of dissimilarities (256 threads; every thread of the block calls it).
 // 4-pass radix select on order-preserving keys, ties at the threshold resolved toward the lower cluster id;
-// the result is written ordered (dissimilarity ascending, cluster id ascending).
-__global__ __launch_bounds__(256) void k_select_clusters(const float* __restrict__ g, int L, int w,
-                                                          int32_t* __restrict__ sel) {
+// the result is written ordered (dissimilarity ascending, cluster id ascending).  Reads the row five times.
+__device__ __forceinline__ void select_clusters_radix(const float* __restrict__ row, int L, int w, int32_t* __restrict__ out) {
     __shared__ int hist[256];
     __shared__ int wsum[4];
     __shared__ uint32_t s_prefix;
@@ -50,8 +49,8 @@ __global__ __launch_bounds__(256) void k_select_clusters(const float* __restrict
     __shared__ int seli[256];
     __shared__ int s_nless;
     const int tid = threadIdx.x;
-    const float* row = g + (size_t)blockIdx.x * L;
 
+    __syncthreads();
     if (tid == 0) { s_prefix = 0u; s_need = w; s_nless = 0; }
     uint32_t mask = 0u;
     for (int shift = 24; shift >= 0; shift -= 8) {
@@ -110,7 +109,85 @@ __global__ __launch_bounds__(256) void k_select_clusters(const float* __restrict
             const int iu = seli[u];
             rank += (ku < k || (ku == k && iu < id)) ? 1 : 0;
         }
-        sel[(size_t)blockIdx.x * w + rank] = id;
+        out[rank] = id;
+    }
+}
+
+// One block (256 threads) per query, any L.  g [nq][L] holds the centroid dissimilarities.
+__global__ __launch_bounds__(256) void k_select_clusters(const float* __restrict__ g, int L, int w,
+                                                          int32_t* __restrict__ sel) {
+    select_clusters_radix(g + (size_t)blockIdx.x * L, L, w, sel + (size_t)blockIdx.x * w);
+}
+
+// One block per query with the row read ONCE into registers (KPT keys per thread, 256 * KPT >= L, L >= 256, w <= 256).
+// The w-th smallest of the 256 per-thread minima bounds the w-th smallest key from above (w distinct keys do
+// not exceed it), so only the keys up to that bound - a few more than w when the row is in no special order -
+// are collected into LDS and ranked exactly by (key, cluster id).  A row whose keys up to the bound do not fit
+// (long runs of equal keys, adversarial order) is selected by the radix routine instead.
+template <int KPT>
+__global__ __launch_bounds__(256) void k_select_clusters_regs(const float* __restrict__ g, int L, int w,
+                                                               int32_t* __restrict__ sel) {
+    constexpr int CAP = 2048;
+    // (key, position) packed into one 64-bit word: a single unsigned compare orders by key, then position
+    __shared__ __align__(16) unsigned long long tmin[256];
+    __shared__ __align__(16) unsigned long long cand[CAP + 2];
+    __shared__ int s_cnt;
+    __shared__ uint32_t s_bound;
+    const int tid = threadIdx.x;
+    const float* row = g + (size_t)blockIdx.x * L;
+    int32_t* out = sel + (size_t)blockIdx.x * w;
+    uint32_t key[KPT];
+    uint32_t mn = 0xFFFFFFFFu;
+#pragma unroll
+    for (int i = 0; i < KPT; ++i) key[i] = __float_as_uint(row[min(i * 256 + tid, L - 1)]);   // independent loads, all in flight
+#pragma unroll
+    for (int i = 0; i < KPT; ++i) {
+        key[i] = i * 256 + tid < L ? float_key_asc(__uint_as_float(key[i])) : 0xFFFFFFFFu;
+        mn = min(mn, key[i]);
+    }
+    const unsigned long long mine = ((unsigned long long)mn << 32) | (unsigned)tid;
+    tmin[tid] = mine;
+    if (tid == 0) s_cnt = 0;
+    __syncthreads();
+    int rank = 0;
+    {
+        const ulonglong2* t2 = reinterpret_cast<const ulonglong2*>(tmin);
+#pragma unroll 16
+        for (int u = 0; u < 128; ++u) {
+            const ulonglong2 t = t2[u];
+            rank += (t.x < mine ? 1 : 0) + (t.y < mine ? 1 : 0);
+        }
+    }
+    if (rank == w - 1) s_bound = mn;
+    __syncthreads();
+    const uint32_t bound = s_bound;
+#pragma unroll
+    for (int i = 0; i < KPT; ++i) {
+        const int l = i * 256 + tid;
+        if (l < L && key[i] <= bound) {
+            const int p = atomicAdd(&s_cnt, 1);
+            if (p < CAP) cand[p] = ((unsigned long long)key[i] << 32) | (unsigned)l;
+        }
+    }
+    __syncthreads();
+    const int c = s_cnt;
+    if (c > CAP) {          // uniform over the block
+        select_clusters_radix(row, L, w, out);
+        return;
+    }
+    if (tid < 2) cand[c + tid] = ~0ull;      // pad to a whole 16-byte read
+    __syncthreads();
+    const ulonglong2* c2 = reinterpret_cast<const ulonglong2*>(cand);
+    const int c_pairs = (c + 1) >> 1;
+    for (int e = tid; e < c; e += 256) {
+        const unsigned long long me = cand[e];
+        int r = 0;
+#pragma unroll 8
+        for (int u = 0; u < c_pairs; ++u) {
+            const ulonglong2 t = c2[u];
+            r += (t.x < me ? 1 : 0) + (t.y < me ? 1 : 0);
+        }
+        if (r < w) out[r] = (int)(unsigned)(me & 0xFFFFFFFFull);
     }
 }
 
@@ -130,10 +207,10 @@ __global__ __launch_bounds__(256) void k_select_clusters_wave(const float* __res
     const float* row = g + (size_t)q * L;
     uint32_t key[KPL];                         // element l = 64 * i + lane
 #pragma unroll
-    for (int i = 0; i < KPL; ++i) {
-        const int l = 64 * i + lane;
-        key[i] = l < L ? float_key_asc(row[l]) : 0xFFFFFFFFu;     // padding sorts last (and is never selected: w <= L)
-    }
+    for (int i = 0; i < KPL; ++i) key[i] = __float_as_uint(row[min(64 * i + lane, L - 1)]);   // independent loads, all in flight
+#pragma unroll
+    for (int i = 0; i < KPL; ++i)       // padding sorts last (and is never selected: w <= L)
+        key[i] = 64 * i + lane < L ? float_key_asc(__uint_as_float(key[i])) : 0xFFFFFFFFu;
     uint32_t prefix = 0u, mask = 0u;
     int need = w;
     for (int shift = 24; shift >= 0; shift -= 8) {
@@ -254,41 +331,61 @@ __global__ __launch_bounds__(1024) void k_scan_buckets(const int32_t* __restrict
                                                         const int64_t* __restrict__ off, int L, int unit_pairs, int chunk_points,
                                                         int32_t* __restrict__ bucket_off, int32_t* __restrict__ tile_off,
                                                         int32_t* __restrict__ unit_off, int32_t* __restrict__ off0) {
-    __shared__ int sa[1024], sb[1024], sc[1024], sd[1024];
-    __shared__ int carry_a, carry_b, carry_c, carry_d;
-    const int tid = threadIdx.x;
-    if (tid == 0) { carry_a = 0; carry_b = 0; carry_c = 0; carry_d = 0; }
-    __syncthreads();
-    for (int c0 = 0; c0 < L; c0 += 1024) {
-        const int c = c0 + tid;
-        const int a = c < L ? count[c] : 0;
-        const int b = (a + 15) >> 4;
-        int u = 0;
-        if (c < L) {
-            const int m_c = (int)(off[c + 1] - off[c]);
-            u = ((a + unit_pairs - 1) / unit_pairs) * ((m_c + chunk_points - 1) / chunk_points);
+    // rounds of 1024 * PER clusters: every thread owns a run of PER consecutive clusters, loaded with independent
+    // loads; the run totals are scanned over the block once per round (shuffles inside a wavefront, LDS across
+    // the 16 wavefronts), and a carry links the rounds
+    constexpr int PER = 8;
+    __shared__ int wtot[4][16];
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int per = min(PER, (L + 1023) / 1024);
+    int carry[4] = {0, 0, 0, 0};
+    for (int base = 0; base < L; base += 1024 * per) {
+        const int c_beg = base + tid * per;
+        int va[PER], vu[PER], v0[PER];
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {       // unconditional (clamped) loads: all in flight together
+            const int c = min(c_beg + i, L - 1);
+            va[i] = count[c];
+            v0[i] = count0[c];
+            vu[i] = (int)(off[c + 1] - off[c]);
         }
-        const int d0 = c < L ? count0[c] : 0;
-        sa[tid] = a; sb[tid] = b; sc[tid] = u; sd[tid] = d0;
+#pragma unroll
+        for (int i = 0; i < PER; ++i)
+            if (!(i < per && c_beg + i < L)) { va[i] = 0; vu[i] = 0; v0[i] = 0; }
+        int v[4] = {0, 0, 0, 0};
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            vu[i] = ((va[i] + unit_pairs - 1) / unit_pairs) * ((vu[i] + chunk_points - 1) / chunk_points);
+            v[0] += va[i]; v[1] += (va[i] + 15) >> 4; v[2] += vu[i]; v[3] += v0[i];
+        }
+        int incl[4];
+#pragma unroll
+        for (int f = 0; f < 4; ++f) {
+            int x = v[f];
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) { const int t = __shfl_up(x, o, 64); if (lane >= o) x += t; }
+            incl[f] = x;
+            if (lane == 63) wtot[f][wv] = x;
+        }
         __syncthreads();
-        for (int o = 1; o < 1024; o <<= 1) {
-            int ta = 0, tb = 0, tc = 0, td = 0;
-            if (tid >= o) { ta = sa[tid - o]; tb = sb[tid - o]; tc = sc[tid - o]; td = sd[tid - o]; }
-            __syncthreads();
-            sa[tid] += ta; sb[tid] += tb; sc[tid] += tc; sd[tid] += td;
-            __syncthreads();
+        int run[4];
+#pragma unroll
+        for (int f = 0; f < 4; ++f) {
+            int before = 0, tot = 0;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) { const int t = wtot[f][i]; if (i < wv) before += t; tot += t; }
+            run[f] = carry[f] + before + incl[f] - v[f];
+            carry[f] += tot;
         }
-        if (c < L) {
-            bucket_off[c] = carry_a + sa[tid] - a;
-            tile_off[c] = carry_b + sb[tid] - b;
-            unit_off[c] = carry_c + sc[tid] - u;
-            off0[c] = carry_d + sd[tid] - d0;
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const int c = c_beg + i;
+            if (i < per && c < L) { bucket_off[c] = run[0]; tile_off[c] = run[1]; unit_off[c] = run[2]; off0[c] = run[3]; }
+            run[0] += va[i]; run[1] += (va[i] + 15) >> 4; run[2] += vu[i]; run[3] += v0[i];
         }
-        __syncthreads();
-        if (tid == 1023) { carry_a += sa[1023]; carry_b += sb[1023]; carry_c += sc[1023]; carry_d += sd[1023]; }
         __syncthreads();
     }
-    if (tid == 0) { bucket_off[L] = carry_a; tile_off[L] = carry_b; unit_off[L] = carry_c; }
+    if (tid == 0) { bucket_off[L] = carry[0]; tile_off[L] = carry[1]; unit_off[L] = carry[2]; }
 }
 
 // ---- Counting sort, step 3: place every pair (slot = query * w + rank) into its cluster's bucket, at

@@ -47,11 +47,14 @@ __device__ __forceinline__ void wave_lds_sync() {
 // bounded size keep the load balanced when cluster sizes and pair counts are skewed.
 // NZ pair tiles per item, KS = r_pad / 32 k-steps, L2 = Euclidean score epilogue (per-point bias, float domain;
 // inner product and cosine compare the integer maximum, sigma >= 0 being constant per pair).
-template <int NZ, int KS, bool L2>
+// TB = point tiles fetched ahead (double buffered in registers).
+// STREAM = false: items as above.  STREAM = true (few pairs per cluster: the kernel is a pure stream of the
+// codes from HBM): one wavefront per cluster takes all of its points, no search for the item's cluster, deeper
+// fetch-ahead; clusters without pairs cost nothing.
+template <int NZ, int KS, bool L2, int TB, bool STREAM>
 __global__ __launch_bounds__(256) void k_pair_max(ScoreArgs a) {
     constexpr int NP = 32 * NZ;        // pairs per item
     constexpr int RP = KS * 32;
-    constexpr int TB = 4;              // point tiles fetched per chunk
     constexpr int IMIN = (int)0x80000000;
     constexpr int TRS = NZ * 16 + 1;   // padded row of the transpose buffer
     __shared__ int s_tr[4][64 * TRS];
@@ -59,22 +62,10 @@ __global__ __launch_bounds__(256) void k_pair_max(ScoreArgs a) {
     __shared__ float s_sig[4][NP];     // Euclidean: 2 sigma of each pair
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     const int j = lane & 31, h = lane >> 5;
-    const int n_items = a.unit_off[a.L];
     // no block-wide barrier below: the wavefronts of a block are independent
-    for (int item = blockIdx.x * 4 + wv; item < n_items; item += gridDim.x * 4) {
-        const int c = find_bucket_wave(a.unit_off, a.L, item);
-        const int64_t row_c = a.off[c];
-        const int m_all = (int)(a.off[c + 1] - row_c);
-        const int pbeg = a.bucket_off[c], pend = a.bucket_off[c + 1];
-        const int n_groups = (pend - pbeg + NP - 1) / NP;
-        const int local = item - a.unit_off[c];
-        // consecutive items (the wavefronts of one block) share the point chunk and differ in the pair group,
-        // so the chunk's codes are fetched from L2 once per block
-        const int pk = local / n_groups, ug = local - pk * n_groups;
-        const int pb = pbeg + ug * NP;
-        const int64_t row0 = row_c + (int64_t)pk * 32 * a.chunk_tiles;              // first row of this item's chunk
-        const int m_c = min(32 * a.chunk_tiles, m_all - pk * 32 * a.chunk_tiles);   // rows in the chunk
 
+    // pairs [pb, min(pb + NP, pend)) against rows [row0, row0 + m_c)
+    auto process = [&](int pb, int pend, int64_t row0, int m_c) {
         i32x4 zreg[NZ][KS];
 #pragma unroll
         for (int z = 0; z < NZ; ++z) {
@@ -199,6 +190,31 @@ __global__ __launch_bounds__(256) void k_pair_max(ScoreArgs a) {
                 }
                 if (key != 0u) atomicMax(&a.pmax[gp], key);      // the cluster's other point chunks contribute too
             }
+        }
+    };
+
+    if (STREAM) {
+        for (int c = blockIdx.x * 4 + wv; c < a.L; c += gridDim.x * 4) {
+            const int pbeg = a.bucket_off[c], pend = a.bucket_off[c + 1];
+            if (pbeg == pend) continue;
+            const int64_t row_c = a.off[c];
+            const int m_all = (int)(a.off[c + 1] - row_c);
+            for (int pb = pbeg; pb < pend; pb += NP) process(pb, pend, row_c, m_all);
+        }
+    } else {
+        const int n_items = a.unit_off[a.L];
+        for (int item = blockIdx.x * 4 + wv; item < n_items; item += gridDim.x * 4) {
+            const int c = find_bucket_wave(a.unit_off, a.L, item);
+            const int64_t row_c = a.off[c];
+            const int m_all = (int)(a.off[c + 1] - row_c);
+            const int pbeg = a.bucket_off[c], pend = a.bucket_off[c + 1];
+            const int n_groups = (pend - pbeg + NP - 1) / NP;
+            const int local = item - a.unit_off[c];
+            // consecutive items (the wavefronts of one block) share the point chunk and differ in the pair group,
+            // so the chunk's codes are fetched from L2 once per block
+            const int pk = local / n_groups, ug = local - pk * n_groups;
+            process(pbeg + ug * NP, pend, row_c + (int64_t)pk * 32 * a.chunk_tiles,
+                    min(32 * a.chunk_tiles, m_all - pk * 32 * a.chunk_tiles));
         }
     }
 }

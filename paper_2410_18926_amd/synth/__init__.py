@@ -5,7 +5,7 @@ scoring, candidate selection, re-ranking): that lives twice, independently, in t
 CPU oracle, and neither of those imports the other.  Both consume the arrays made here.
 """
 from .workloads import Workload, WORKLOADS, get_workload
-from .data import make_dataset
+from .data import make_dataset, draw_queries
 from .index_builder import build_index, IndexArrays
 
-__all__ = ["Workload", "WORKLOADS", "get_workload", "make_dataset", "build_index", "IndexArrays"]
+__all__ = ["Workload", "WORKLOADS", "get_workload", "make_dataset", "draw_queries", "build_index", "IndexArrays"]

@@ -91,7 +91,14 @@ def make_dataset(wl: Workload, device: str | torch.device = "cpu", nq: int | Non
     return corpus, queries, extra
 
 
-def brute_force_topk(corpus: torch.Tensor, queries: torch.Tensor, metric: int, k: int, chunk: int = 2048):
+def draw_queries(wl: Workload, device: str | torch.device, count: int, batch_index: int) -> torch.Tensor:
+    """`count` held-out queries of workload `wl` from the stream of query batch `batch_index` (0 = the batch
+    make_dataset returns, 1.. = its extra batches; any larger index is a further independent stream)."""
+    device = torch.device(device)
+    return _Mixture(wl, device).draw(count, _STREAM_QUERIES + batch_index)
+
+
+def brute_force_topk(corpus: torch.Tensor, queries: torch.Tensor, metric: int, k: int, chunk: int | None = None):
     """Ground-truth neighbours by exhaustive fp32 scoring (used for recall only, never timed).
 
     Returns (ids [nq, k] int64, dists [nq, k] fp32) with the paper's dissimilarities: squared L2,
@@ -99,6 +106,8 @@ def brute_force_topk(corpus: torch.Tensor, queries: torch.Tensor, metric: int, k
     """
     from .workloads import IP, L2, COS
     nq = queries.shape[0]
+    if chunk is None:       # keep the [chunk, n] score block near 2^31 elements (8 GiB) whatever the corpus size
+        chunk = int(max(16, min(2048, (1 << 31) // max(1, corpus.shape[0]))))
     ids = torch.empty(nq, k, dtype=torch.int64, device=queries.device)
     dists = torch.empty(nq, k, dtype=torch.float32, device=queries.device)
     cn = (corpus * corpus).sum(1) if metric == L2 else None

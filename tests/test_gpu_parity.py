@@ -221,17 +221,21 @@ def test_mixed_batch_some_queries_fall_back(B, small_indexes):
     gix.close()
 
 
-@pytest.mark.parametrize("L", [1500, 4500, 9000])
-def test_many_clusters_routing_variants(B, L):
-    """Cluster counts that take the other routing kernels (keys in 64 registers per lane; block-wide select),
-    with duplicate centroids so that ties at the w-th place occur."""
-    rng = np.random.default_rng(L)
+@pytest.mark.parametrize("L,plateau", [(1500, 0), (4500, 0), (9000, 0), (9000, 3000), (16384, 0), (20000, 0)])
+def test_many_clusters_routing_variants(B, L, plateau):
+    """Cluster counts that take the other routing kernels (keys in 64 registers per lane; the row in the
+    registers of a block; block-wide radix select), with duplicate centroids so that ties at the w-th place
+    occur.  `plateau` > 0: that many identical centroids nearest to every query, more equal keys than the
+    register kernel's candidate list holds, so it has to hand the row to the radix routine."""
+    rng = np.random.default_rng(L + plateau)
     d, r, w = 32, 8, 40
     sizes = rng.integers(0, 7, size=L)
     n = int(sizes.sum())
     corpus = rng.normal(size=(n, d)).astype(np.float32)
     cent = rng.normal(size=(L, d)).astype(np.float32)
     cent[L // 2:L // 2 + 300] = cent[:300]                     # exact ties between cluster pairs
+    if plateau:
+        cent[1000:1000 + plateau] = 0.05 * rng.normal(size=d).astype(np.float32)
     off = np.zeros(L + 1, np.int64)
     np.cumsum(sizes, out=off[1:])
     ix = dict(metric=1, n=n, d=d, dp=d, r=r, L=L, centroids=cent, P=None,
@@ -239,12 +243,16 @@ def test_many_clusters_routing_variants(B, L):
               scale_A=rng.uniform(0.01, 0.1, L).astype(np.float32), scale_B=rng.uniform(0.01, 0.1, L).astype(np.float32),
               cluster_offsets=off, corpus=corpus, ids=None)
     q = rng.normal(size=(50, d)).astype(np.float32)
+    if plateau:
+        q *= 0.05                                              # short queries: the centroids near the origin win
     gix = B.Index(**ix)
     oix = O.OracleIndex(ix)
     o_ids, o_d, ost = O.search(oix, q, 10, w, 60, stages=True)
+    if plateau:
+        assert np.isin(ost["sel"], np.arange(1000, 1000 + plateau)).all()
     g_ids, g_d, gst = gix.search_stages(q, 10, w, 60)
     np.testing.assert_array_equal(gst["sel"], ost["sel"])
     np.testing.assert_array_equal(gst["z"], ost["z"])
     np.testing.assert_array_equal(np.sort(gst["cand_rows"].astype(np.int64), axis=1), np.sort(ost["cand_rows"], axis=1))
-    assert_topk_equal(g_ids, g_d, o_ids, o_d, f"L={L}")
+    assert_topk_equal(g_ids, g_d, o_ids, o_d, f"L={L} plateau={plateau}")
     gix.close()
