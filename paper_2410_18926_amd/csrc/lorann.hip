@@ -260,7 +260,7 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
     }
     {
         Prof p(ix, K_SCAN);
-        hipLaunchKernelGGL(k_scan_buckets, dim3(1), dim3(1024), 0, s, ix->count.as<int32_t>(), ix->count.as<int32_t>() + L, ix->off, L, kUnitPairs, 32 * kChunkTiles, ix->bucket_off.as<int32_t>(),
+        hipLaunchKernelGGL(k_scan_buckets, dim3((unsigned)((L + 1023) / 1024)), dim3(1024), 0, s, ix->count.as<int32_t>(), ix->count.as<int32_t>() + L, ix->off, L, kUnitPairs, 32 * kChunkTiles, ix->bucket_off.as<int32_t>(),
                            ix->tile_off.as<int32_t>(), ix->unit_off.as<int32_t>(), ix->off0.as<int32_t>());
     }
     {
@@ -305,11 +305,10 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
             sc.sqnorm = l2 ? ix->sqnorm : nullptr; sc.pmax = ix->pmax.as<uint32_t>(); sc.L = L; sc.chunk_tiles = kChunkTiles;
             // few pairs per cluster: the kernel streams the codes of the touched clusters, one wavefront per cluster
             const bool stream = npairs <= (int64_t)16 * L;
-            const dim3 ugrid(stream ? (unsigned)((L + 3) / 4) : 2048u);     // else persistent: 8192 wavefronts stride over the work items
 #define LAUNCH_PM(KS_, L2_)                                                                                          \
     do {                                                                                                             \
-        if (stream) hipLaunchKernelGGL((k_pair_max<1, KS_, L2_, 8 / KS_, true>), ugrid, dim3(256), 0, s, sc);         \
-        else hipLaunchKernelGGL((k_pair_max<kNZ, KS_, L2_, 4, false>), ugrid, dim3(256), 0, s, sc);                   \
+        if (stream) hipLaunchKernelGGL((k_pair_max<1, KS_, L2_, 8 / KS_, true, 4>), dim3((unsigned)((L + 3) / 4)), dim3(256), 0, s, sc); \
+        else hipLaunchKernelGGL((k_pair_max<kNZ, KS_, L2_, 4, false, 4>), dim3(2048), dim3(256), 0, s, sc);   /* persistent: 8192 wavefronts stride over the work items */ \
     } while (0)
             if (ks == 1) { if (l2) LAUNCH_PM(1, true); else LAUNCH_PM(1, false); }
             else         { if (l2) LAUNCH_PM(2, true); else LAUNCH_PM(2, false); }
@@ -324,8 +323,13 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
             qa.fb_list = ix->fb_list.as<int32_t>(); qa.fb_count = ix->count.as<int32_t>() + 2 * L; qa.qorder = ix->qorder.as<int32_t>(); qa.nq = (int)nq; qa.w = w; qa.m = m; qa.cap = select_query_cap(m);
             const size_t qlds = (size_t)qa.cap * 8;
             const dim3 qgrid((unsigned)(8 * ((nq + 7) / 8)));
-            if (ks == 1) hipLaunchKernelGGL(k_select_query<2>, qgrid, dim3(256), qlds, s, qa);
-            else hipLaunchKernelGGL(k_select_query<4>, qgrid, dim3(256), qlds, s, qa);
+            if (qa.cap == 2048) {
+                if (ks == 1) hipLaunchKernelGGL((k_select_query<2, 2>), qgrid, dim3(256), qlds, s, qa);
+                else hipLaunchKernelGGL((k_select_query<4, 2>), qgrid, dim3(256), qlds, s, qa);
+            } else {
+                if (ks == 1) hipLaunchKernelGGL((k_select_query<2, 6>), qgrid, dim3(256), qlds, s, qa);
+                else hipLaunchKernelGGL((k_select_query<4, 6>), qgrid, dim3(256), qlds, s, qa);
+            }
         }
         {
             Prof p(ix, K_SELECT_M);
@@ -576,8 +580,10 @@ int lorann_load_index(lorann_index** out, int32_t metric, int64_t n, int32_t d, 
         {   // codes padded to r_pad bytes per point so that every point is one or two aligned 32-byte operands
             int8_t* Braw = nullptr;
             if ((e = dev_copy(&Braw, B, (size_t)n * r))) return e;
-            hipError_t he = hipMalloc((void**)&ix->Bp, (size_t)n * ix->r_pad);
+            // 32 zero rows follow the last point: the scoring kernel requests whole 32-point tiles
+            hipError_t he = hipMalloc((void**)&ix->Bp, (size_t)(n + 32) * ix->r_pad);
             if (he != hipSuccess) { (void)hipFree(Braw); return fail(LORANN_E_NOMEM, "hipMalloc of padded codes failed"); }
+            (void)hipMemset(ix->Bp + (size_t)n * ix->r_pad, 0, (size_t)32 * ix->r_pad);
             const int64_t tot = n * ix->r_pad;
             hipLaunchKernelGGL(k_pad_codes, dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, 0, Braw, ix->Bp, n, r, ix->r_pad);
             he = hipDeviceSynchronize();

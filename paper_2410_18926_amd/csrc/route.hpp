@@ -321,71 +321,66 @@ __global__ __launch_bounds__(256) void k_bucket_count_global(const int32_t* __re
     if (p % w == 0) qrank[p / w] = atomicAdd(&count0[c], 1);
 }
 
-// ---- Counting sort, step 2: exclusive scans over the clusters (single block of 1024 threads). ----
+// ---- Counting sort, step 2: exclusive scans over the clusters. ----
 // bucket_off[c]  = number of pairs routed to clusters < c                  (bucket_off[L] = number of pairs)
 // tile_off[c]    = number of 16-pair tiles of clusters < c                 (tile_off[L]   = number of tiles)
 // unit_off[c]    = number of scoring work items of clusters < c            (unit_off[L]   = number of items);
 //                  a cluster with a pairs and m_c points has ceil(a / unit_pairs) * ceil(m_c / chunk_points) items
 // off0[c]        = number of queries whose nearest cluster is < c
+// grid = ceil(L / 1024), block = 1024: block b scans clusters [1024 b, 1024 b + 1024) and first adds up, on its
+// own, everything that precedes them (at most L - 1024 independent loads spread over its threads), so the blocks
+// need no communication and none of them waits for another.
 __global__ __launch_bounds__(1024) void k_scan_buckets(const int32_t* __restrict__ count, const int32_t* __restrict__ count0,
                                                         const int64_t* __restrict__ off, int L, int unit_pairs, int chunk_points,
                                                         int32_t* __restrict__ bucket_off, int32_t* __restrict__ tile_off,
                                                         int32_t* __restrict__ unit_off, int32_t* __restrict__ off0) {
-    // rounds of 1024 * PER clusters: every thread owns a run of PER consecutive clusters, loaded with independent
-    // loads; the run totals are scanned over the block once per round (shuffles inside a wavefront, LDS across
-    // the 16 wavefronts), and a carry links the rounds
-    constexpr int PER = 8;
-    __shared__ int wtot[4][16];
+    __shared__ int wtot[4][16], wpre[4][16];
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    const int per = min(PER, (L + 1023) / 1024);
-    int carry[4] = {0, 0, 0, 0};
-    for (int base = 0; base < L; base += 1024 * per) {
-        const int c_beg = base + tid * per;
-        int va[PER], vu[PER], v0[PER];
+    const int c0 = blockIdx.x * 1024;
+    auto fields = [&](int c, int (&f)[4]) {         // c < L
+        const int a = count[c];
+        const int m_c = (int)(off[c + 1] - off[c]);
+        f[0] = a; f[1] = (a + 15) >> 4;
+        f[2] = ((a + unit_pairs - 1) / unit_pairs) * ((m_c + chunk_points - 1) / chunk_points);
+        f[3] = count0[c];
+    };
+    int pre[4] = {0, 0, 0, 0};                      // this thread's share of the clusters before c0
+#pragma unroll 4
+    for (int c = tid; c < c0; c += 1024) {
+        int f[4];
+        fields(c, f);
 #pragma unroll
-        for (int i = 0; i < PER; ++i) {       // unconditional (clamped) loads: all in flight together
-            const int c = min(c_beg + i, L - 1);
-            va[i] = count[c];
-            v0[i] = count0[c];
-            vu[i] = (int)(off[c + 1] - off[c]);
-        }
-#pragma unroll
-        for (int i = 0; i < PER; ++i)
-            if (!(i < per && c_beg + i < L)) { va[i] = 0; vu[i] = 0; v0[i] = 0; }
-        int v[4] = {0, 0, 0, 0};
-#pragma unroll
-        for (int i = 0; i < PER; ++i) {
-            vu[i] = ((va[i] + unit_pairs - 1) / unit_pairs) * ((vu[i] + chunk_points - 1) / chunk_points);
-            v[0] += va[i]; v[1] += (va[i] + 15) >> 4; v[2] += vu[i]; v[3] += v0[i];
-        }
-        int incl[4];
-#pragma unroll
-        for (int f = 0; f < 4; ++f) {
-            int x = v[f];
-#pragma unroll
-            for (int o = 1; o < 64; o <<= 1) { const int t = __shfl_up(x, o, 64); if (lane >= o) x += t; }
-            incl[f] = x;
-            if (lane == 63) wtot[f][wv] = x;
-        }
-        __syncthreads();
-        int run[4];
-#pragma unroll
-        for (int f = 0; f < 4; ++f) {
-            int before = 0, tot = 0;
-#pragma unroll
-            for (int i = 0; i < 16; ++i) { const int t = wtot[f][i]; if (i < wv) before += t; tot += t; }
-            run[f] = carry[f] + before + incl[f] - v[f];
-            carry[f] += tot;
-        }
-#pragma unroll
-        for (int i = 0; i < PER; ++i) {
-            const int c = c_beg + i;
-            if (i < per && c < L) { bucket_off[c] = run[0]; tile_off[c] = run[1]; unit_off[c] = run[2]; off0[c] = run[3]; }
-            run[0] += va[i]; run[1] += (va[i] + 15) >> 4; run[2] += vu[i]; run[3] += v0[i];
-        }
-        __syncthreads();
+        for (int k = 0; k < 4; ++k) pre[k] += f[k];
     }
-    if (tid == 0) { bucket_off[L] = carry[0]; tile_off[L] = carry[1]; unit_off[L] = carry[2]; }
+    const int c = c0 + tid;
+    int v[4] = {0, 0, 0, 0};
+    if (c < L) fields(c, v);
+    int incl[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        int x = v[k], y = pre[k];
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int t = __shfl_up(x, o, 64);
+            if (lane >= o) x += t;
+            y += __shfl_xor(y, o, 64);
+        }
+        incl[k] = x;
+        if (lane == 63) wtot[k][wv] = x;
+        if (lane == 0) wpre[k][wv] = y;
+    }
+    __syncthreads();
+    int total[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        int before = 0, tot = 0;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) { const int t = wtot[k][i]; if (i < wv) before += t; tot += t + wpre[k][i]; before += wpre[k][i]; }
+        incl[k] += before - v[k];                   // exclusive, including everything before this block
+        total[k] = tot;
+    }
+    if (c < L) { bucket_off[c] = incl[0]; tile_off[c] = incl[1]; unit_off[c] = incl[2]; off0[c] = incl[3]; }
+    if (blockIdx.x == gridDim.x - 1 && tid == 0) { bucket_off[L] = total[0]; tile_off[L] = total[1]; unit_off[L] = total[2]; }
 }
 
 // ---- Counting sort, step 3: place every pair (slot = query * w + rank) into its cluster's bucket, at

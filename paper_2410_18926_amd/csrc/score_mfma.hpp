@@ -42,7 +42,7 @@ __device__ __forceinline__ void wave_lds_sync() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-// grid = any (persistent: wavefronts stride over the work items), block = 256.
+// grid = any (persistent: wavefronts stride over the work items), block = 64 * WPB (independent wavefronts).
 // A work item = one cluster, up to 32*NZ of its pairs, up to chunk_tiles 32-point tiles of its codes; items of
 // bounded size keep the load balanced when cluster sizes and pair counts are skewed.
 // NZ pair tiles per item, KS = r_pad / 32 k-steps, L2 = Euclidean score epilogue (per-point bias, float domain;
@@ -51,15 +51,15 @@ __device__ __forceinline__ void wave_lds_sync() {
 // STREAM = false: items as above.  STREAM = true (few pairs per cluster: the kernel is a pure stream of the
 // codes from HBM): one wavefront per cluster takes all of its points, no search for the item's cluster, deeper
 // fetch-ahead; clusters without pairs cost nothing.
-template <int NZ, int KS, bool L2, int TB, bool STREAM>
-__global__ __launch_bounds__(256) void k_pair_max(ScoreArgs a) {
+template <int NZ, int KS, bool L2, int TB, bool STREAM, int WPB>
+__global__ __launch_bounds__(64 * WPB) void k_pair_max(ScoreArgs a) {
     constexpr int NP = 32 * NZ;        // pairs per item
     constexpr int RP = KS * 32;
     constexpr int IMIN = (int)0x80000000;
     constexpr int TRS = NZ * 16 + 1;   // padded row of the transpose buffer
-    __shared__ int s_tr[4][64 * TRS];
-    __shared__ int s_red[4][NP];       // per-pair maxima of the item (int, or order-preserving keys for Euclidean)
-    __shared__ float s_sig[4][NP];     // Euclidean: 2 sigma of each pair
+    __shared__ int s_tr[WPB][64 * TRS];
+    __shared__ int s_red[WPB][NP];       // per-pair maxima of the item (int, or order-preserving keys for Euclidean)
+    __shared__ float s_sig[WPB][NP];     // Euclidean: 2 sigma of each pair
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     const int j = lane & 31, h = lane >> 5;
     // no block-wide barrier below: the wavefronts of a block are independent
@@ -95,34 +95,32 @@ __global__ __launch_bounds__(256) void k_pair_max(ScoreArgs a) {
 
         const int ntiles = (m_c + 31) >> 5;
         const int nchunks = (ntiles + TB - 1) / TB;
-        auto fetch_chunk = [&](int t0, i32x4 (*dst)[KS]) {
+        // Whole tiles are requested under a uniform guard with addresses that are affine in the tile number: the
+        // lanes of the cluster's last tile that lie past its end read the rows that follow (the allocation is
+        // padded by 32 rows) and are masked out of the maxima below.
+        const int8_t* bbase = a.Bp + (size_t)(row0 + j) * RP + 16 * h;
+        auto fetch_chunk = [&](int t0, i32x4 (*dst)[KS], float* nb) {
 #pragma unroll
             for (int u = 0; u < TB; ++u) {
-                const int pt = 32 * (t0 + u) + j;
+                if (t0 + u < ntiles) {                   // uniform
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-                    dst[u][ks] = (i32x4){0, 0, 0, 0};
-                    if (pt < m_c) dst[u][ks] = load16(a.Bp + (size_t)(row0 + pt) * RP + 32 * ks + 16 * h);
+                    for (int ks = 0; ks < KS; ++ks) dst[u][ks] = load16(bbase + (size_t)(t0 + u) * (32 * RP) + 32 * ks);
+                    if (L2) nb[u] = a.sqnorm[row0 + min(32 * (t0 + u) + j, m_c - 1)];
+                } else {
+#pragma unroll
+                    for (int ks = 0; ks < KS; ++ks) dst[u][ks] = (i32x4){0, 0, 0, 0};
+                    if (L2) nb[u] = 0.0f;
                 }
             }
         };
-        i32x4 bnext[TB][KS];
-        if (nchunks > 0) fetch_chunk(0, bnext);
-        for (int c0 = 0; c0 < nchunks; ++c0) {
-            i32x4 breg[TB][KS];
-#pragma unroll
-            for (int u = 0; u < TB; ++u)
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) breg[u][ks] = bnext[u][ks];
-            if (c0 + 1 < nchunks) fetch_chunk((c0 + 1) * TB, bnext);
+        auto score_chunk = [&](int c0, i32x4 (*breg)[KS], const float* nb) {
 #pragma unroll
             for (int u = 0; u < TB; ++u) {
                 const int t = c0 * TB + u;
                 if (t < ntiles) {                        // uniform
                     const int pt = 32 * t + j;           // this lane's point of the tile
                     const bool pt_ok = pt < m_c;         // false only in the last tile of the cluster
-                    float bias = 0.0f;
-                    if (L2 && pt_ok) bias = a.sqnorm[row0 + pt];
+                    const float bias = L2 ? nb[u] : 0.0f;
 #pragma unroll
                     for (int z = 0; z < NZ; ++z) {
                         i32x16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
@@ -146,6 +144,23 @@ __global__ __launch_bounds__(256) void k_pair_max(ScoreArgs a) {
                     }
                 }
                 __builtin_amdgcn_sched_barrier(0);       // keep the tiles sequential: bounds live accumulators
+            }
+        };
+        {
+            i32x4 bnext[TB][KS];
+            float nbnext[TB];
+            if (nchunks > 0) fetch_chunk(0, bnext, nbnext);
+            for (int c0 = 0; c0 < nchunks; ++c0) {
+                i32x4 breg[TB][KS];
+                float nb[TB];
+#pragma unroll
+                for (int u = 0; u < TB; ++u) {
+                    nb[u] = nbnext[u];
+#pragma unroll
+                    for (int ks = 0; ks < KS; ++ks) breg[u][ks] = bnext[u][ks];
+                }
+                if (c0 + 1 < nchunks) fetch_chunk((c0 + 1) * TB, bnext, nbnext);
+                score_chunk(c0, breg, nb);
             }
         }
 
@@ -194,7 +209,8 @@ __global__ __launch_bounds__(256) void k_pair_max(ScoreArgs a) {
     };
 
     if (STREAM) {
-        for (int c = blockIdx.x * 4 + wv; c < a.L; c += gridDim.x * 4) {
+        // the cluster number is uniform over the wavefront: say so, and its offsets come through scalar loads
+        for (int c = blockIdx.x * WPB + __builtin_amdgcn_readfirstlane(wv); c < a.L; c += gridDim.x * WPB) {
             const int pbeg = a.bucket_off[c], pend = a.bucket_off[c + 1];
             if (pbeg == pend) continue;
             const int64_t row_c = a.off[c];
@@ -203,8 +219,8 @@ __global__ __launch_bounds__(256) void k_pair_max(ScoreArgs a) {
         }
     } else {
         const int n_items = a.unit_off[a.L];
-        for (int item = blockIdx.x * 4 + wv; item < n_items; item += gridDim.x * 4) {
-            const int c = find_bucket_wave(a.unit_off, a.L, item);
+        for (int item = blockIdx.x * WPB + wv; item < n_items; item += gridDim.x * WPB) {
+            const int c = __builtin_amdgcn_readfirstlane(find_bucket_wave(a.unit_off, a.L, item));   // uniform: scalar loads below
             const int64_t row_c = a.off[c];
             const int m_all = (int)(a.off[c + 1] - row_c);
             const int pbeg = a.bucket_off[c], pend = a.bucket_off[c + 1];

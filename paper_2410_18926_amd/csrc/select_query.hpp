@@ -101,7 +101,8 @@ struct QuerySelectArgs {
 // grid = 8 * ceil(nq / 8), block = 256, dynamic LDS = 8 * cap bytes.  RB = r_pad / 16.
 // Queries are visited grouped by nearest cluster, consecutive ones on the same XCD (workgroups are dealt
 // round-robin over the 8 XCDs): queries that score the same cluster run together and share its codes in L2.
-template <int RB>
+// PT = points a thread scores between two capacity checks = cap / 1024.
+template <int RB, int PT>
 __global__ __launch_bounds__(256) void k_select_query(QuerySelectArgs a) {
     constexpr int ZW = RB * 4;
     extern __shared__ __align__(16) unsigned char qs_smem[];
@@ -119,7 +120,7 @@ __global__ __launch_bounds__(256) void k_select_query(QuerySelectArgs a) {
     const int per_xcd = (a.nq + 7) >> 3;
     const int si = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
     if (si >= a.nq) return;
-    const int q = a.qorder[si];
+    const int q = __builtin_amdgcn_readfirstlane(a.qorder[si]);     // uniform over the block: scalar loads below
     const int w = a.w, m = a.m;
     const bool l2 = a.sqnorm != nullptr;
     if (tid == 0) s_count = 0;
@@ -165,32 +166,61 @@ __global__ __launch_bounds__(256) void k_select_query(QuerySelectArgs a) {
         __syncthreads();
     };
 
+    // The codes of the PT points a thread scores between two capacity checks are requested together, with
+    // clamped addresses instead of branches, so that the loads overlap.
     for (int o = 0; o < w && !overflow; ++o) {
-        const int jp = order[o];
+        const int jp = __builtin_amdgcn_readfirstlane(order[o]);
         if (pk[jp] == 0u || pk[jp] < T) break;           // sorted: no later cluster can reach T either
         const int c = a.sel[(size_t)q * w + jp];
         const int64_t r0 = a.off[c];
         const int m_c = (int)(a.off[c + 1] - r0);
-        const int pos = ppos[jp];
-        __syncthreads();
-        if (tid < ZW) zw[tid] = reinterpret_cast<const int*>(a.Z)[(size_t)pos * ZW + tid];
-        __syncthreads();
+        const int pos = __builtin_amdgcn_readfirstlane(ppos[jp]);
+        // requests that do not depend on each other go out together: the pair's z and sigma, the first codes
+        const int zv = reinterpret_cast<const int*>(a.Z)[(size_t)pos * ZW + (tid < ZW ? tid : 0)];
         const float s = a.sigma[pos];
+        i32x4 code[PT][RB];
+        float bias[PT];
+        auto fetch_codes = [&](int p0) {
+#pragma unroll
+            for (int e = 0; e < PT; ++e) {
+                {
+                    const int64_t row = r0 + min(p0 + e * 256 + tid, m_c - 1);
+                    const i32x4* bp = reinterpret_cast<const i32x4*>(a.Bp + (size_t)row * (RB * 16));
+#pragma unroll
+                    for (int u = 0; u < RB; ++u) code[e][u] = bp[u];
+                    bias[e] = l2 ? a.sqnorm[row] : 0.0f;
+                }
+            }
+        };
+        if (m_c > 0) fetch_codes(0);
+        __syncthreads();
+        if (tid < ZW) zw[tid] = zv;
+        __syncthreads();
         const float sp = l2 ? 2.0f * s : s;
         for (int p0 = 0; p0 < m_c; p0 += kQChunk) {
             if (count > kQCap - kQChunk) {
                 compact();
                 if (count > kQCap - kQChunk) { overflow = true; break; }   // too many scores tie with the threshold
             }
-            const int pe = min(m_c, p0 + kQChunk);
-            for (int t = p0 + tid; t < pe; t += 256) {
-                const int y = point_score<RB>(a.Bp + (size_t)(r0 + t) * (RB * 16), zw);
-                const float bias = l2 ? a.sqnorm[r0 + t] : 0.0f;
-                const uint32_t key = float_key_asc(__fmaf_rn((float)y, sp, -bias));
-                if (key >= T) {
-                    const int at = atomicAdd(&s_count, 1);
-                    keys[at] = key;
-                    rows[at] = (int32_t)(r0 + t);
+            if (p0 > 0) fetch_codes(p0);
+#pragma unroll
+            for (int e = 0; e < PT; ++e) {
+                {
+                    const int t = p0 + e * 256 + tid;
+                    int y = 0;
+#pragma unroll
+                    for (int u = 0; u < RB; ++u) {
+                        y = dot4_i8(code[e][u][0], zw[4 * u + 0], y);
+                        y = dot4_i8(code[e][u][1], zw[4 * u + 1], y);
+                        y = dot4_i8(code[e][u][2], zw[4 * u + 2], y);
+                        y = dot4_i8(code[e][u][3], zw[4 * u + 3], y);
+                    }
+                    const uint32_t key = float_key_asc(__fmaf_rn((float)y, sp, -bias[e]));
+                    if (t < m_c && key >= T) {
+                        const int at = atomicAdd(&s_count, 1);
+                        keys[at] = key;
+                        rows[at] = (int32_t)(r0 + t);
+                    }
                 }
             }
             __syncthreads();

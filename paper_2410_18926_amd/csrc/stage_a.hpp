@@ -53,7 +53,7 @@ __global__ __launch_bounds__(256) void k_stage_a(const int8_t* __restrict__ q8, 
     const int lane = threadIdx.x & 63;
     const int tile = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (tile >= tile_off[L]) return;
-    const int c = find_bucket_wave(tile_off, L, tile);
+    const int c = __builtin_amdgcn_readfirstlane(find_bucket_wave(tile_off, L, tile));   // uniform: scalar loads below
     const int base = bucket_off[c] + (tile - tile_off[c]) * 16;
     const int end = bucket_off[c + 1];
     const int i = lane & 15, g = lane >> 4;
@@ -67,18 +67,31 @@ __global__ __launch_bounds__(256) void k_stage_a(const int8_t* __restrict__ q8, 
 #pragma unroll
     for (int t = 0; t < RT; ++t) acc[t] = (i32x4){0, 0, 0, 0};
 
+    // The operands of SB k-steps are requested together, with clamped addresses instead of branches around the
+    // loads (so that they overlap), and what lies outside the matrices is zeroed in registers afterwards.
+    constexpr int SB = 4;
     const int steps = (dp + 63) >> 6;                    // uniform trip count: the MFMA runs with all lanes on
-    for (int s = 0; s < steps; ++s) {
-        const int k0 = 64 * s + 16 * g;
-        const bool k_ok = k0 < dp;                       // d' is a multiple of 16: a 16-byte group is all in or all out
-        i32x4 a = (i32x4){0, 0, 0, 0};
-        if (row_ok && k_ok) a = load16(qrow + k0);
+    for (int s0 = 0; s0 < steps; s0 += SB) {
+        i32x4 av[SB], bv[SB][RT];
 #pragma unroll
-        for (int t = 0; t < RT; ++t) {
-            const int j = t * 16 + i;
-            i32x4 b = (i32x4){0, 0, 0, 0};
-            if (j < r && k_ok) b = load16(Ac + (size_t)j * dp + k0);
-            acc[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b, acc[t], 0, 0, 0);
+        for (int u = 0; u < SB; ++u) {
+            const int kc = min(64 * (s0 + u) + 16 * g, dp - 16);
+            av[u] = load16(qrow + kc);
+#pragma unroll
+            for (int t = 0; t < RT; ++t) bv[u][t] = load16(Ac + (size_t)min(t * 16 + i, r - 1) * dp + kc);
+        }
+#pragma unroll
+        for (int u = 0; u < SB; ++u) {
+            if (s0 + u < steps) {                        // uniform
+                // d' is a multiple of 16: a 16-byte group is all in or all out
+                const bool a_ok = row_ok && 64 * (s0 + u) + 16 * g < dp;
+                const i32x4 a = a_ok ? av[u] : (i32x4){0, 0, 0, 0};
+#pragma unroll
+                for (int t = 0; t < RT; ++t) {
+                    const i32x4 b = t * 16 + i < r ? bv[u][t] : (i32x4){0, 0, 0, 0};
+                    acc[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b, acc[t], 0, 0, 0);
+                }
+            }
         }
     }
 
