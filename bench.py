@@ -119,6 +119,9 @@ def main():
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (development only)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target duration of the oracle baseline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--random-index", action="store_true",
+                    help="skip the index fit: random factors and codes of the workload's shapes (kernel timing and "
+                         "profiling only; recall is not reported)")
     ap.add_argument("--batch", type=int, default=None, help="queries per step (default: the workload's batch)")
     ap.add_argument("--recall-queries", type=int, default=10000, help="recall is measured on this many queries of the batch")
     ap.add_argument("--batch-sweep", default="", help="comma-separated batch sizes: per-batch latency (p50/p99), "
@@ -133,7 +136,7 @@ def main():
 
     import torch
     from paper_2410_18926_amd import binding
-    from paper_2410_18926_amd.synth import get_workload, make_dataset, build_index, draw_queries
+    from paper_2410_18926_amd.synth import get_workload, make_dataset, build_index, random_index, draw_queries
     from paper_2410_18926_amd.synth.data import brute_force_topk
 
     if not torch.cuda.is_available():
@@ -155,11 +158,14 @@ def main():
     torch.cuda.synchronize()
     log(f"[bench] data {wl.name}: corpus {tuple(corpus.shape)}, {nb} batches of {wl.nq} queries in {time.time() - t0:.1f}s")
     t0 = time.time()
-    ix = build_index(corpus, wl, progress=lambda s: log(f"[bench]   index: {s}"))
+    if args.random_index:
+        ix = random_index(corpus, wl)
+    else:
+        ix = build_index(corpus, wl, progress=lambda s: log(f"[bench]   index: {s}"))
     torch.cuda.synchronize()
     build_s = time.time() - t0
     log(f"[bench] index built in {build_s:.1f}s")
-    n_rec = min(wl.nq, args.recall_queries)
+    n_rec = min(wl.nq, args.recall_queries if not args.random_index else 16)
     gt_ids, gt_d = brute_force_topk(corpus, queries[:n_rec], wl.metric, wl.k)
     gt_d = gt_d.cpu().numpy()
     del corpus
@@ -215,8 +221,9 @@ def main():
         avg_ms = ms / launches
         ent = {"kernel": name, "avg_ms": round(avg_ms, 5), "launches_per_step": launches / K}
         if name in models:
+            # the models give the work of one STEP (a batch larger than 32768 queries runs in several launches)
             bound, amount, peak, unit = models[name]
-            ach = amount / (avg_ms / 1e3)
+            ach = amount / (ms / K / 1e3)
             ent.update({"bound": bound, "achieved": round(ach, 3), "peak": peak, "unit": unit, "frac": round(ach / peak, 4)})
         kernels.append(ent)
     kernels.sort(key=lambda e: -e["avg_ms"])
@@ -227,7 +234,7 @@ def main():
         ms, launches = prof_dom.get(dom["kernel"], (0.0, 0))
         if launches:
             bound, amount, peak, unit = models[dom["kernel"]]
-            ach = amount / (ms / launches / 1e3)
+            ach = amount / (ms / K / 1e3)
             dom = dict(dom, avg_ms=round(ms / launches, 5), achieved=round(ach, 3), frac=round(ach / peak, 4))
         roofline = {"kernel": dom["kernel"], "bound": dom["bound"], "achieved": dom["achieved"], "peak": dom["peak"],
                     "unit": dom["unit"], "frac": dom["frac"], "avg_ms": dom["avg_ms"],
@@ -283,7 +290,9 @@ def main():
                                f"{metric_names[wl.metric]}, L={wl.L} clusters, d'={wl.dp}, r={wl.r} int8, batch {nq}, "
                                f"w={w}, m={m}, k={k}",
                    "n": wl.n, "d": wl.d, "batch": nq, "L": wl.L, "dp": wl.dp, "r": wl.r, "w": w, "m": m, "k": k},
-        "recall_at_10": round(recall, 4), "recall_at_10_by_id": round(recall_ids, 4),
+        "recall_at_10": None if args.random_index else round(recall, 4),
+        "recall_at_10_by_id": None if args.random_index else round(recall_ids, 4),
+        "index": "random factors and codes (timing only)" if args.random_index else "fitted",
         "roofline": roofline, "cpu_baseline": cpu_baseline,
         "kernels": kernels, "oracle_match": oracle_match,
         "ms_per_step_with_events_on_every_kernel": round(elapsed_allev / K * 1e3, 4),

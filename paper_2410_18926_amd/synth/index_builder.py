@@ -236,3 +236,32 @@ def build_index(corpus: torch.Tensor, wl: Workload, *, exact_svd: bool = False, 
     return IndexArrays(metric=metric, n=n, d=d, dp=dp, r=r, L=L, centroids=centroids.contiguous(), P=P,
                        A=A_q, B=B_q, scale_A=sA.to(dev), scale_B=sB.to(dev), cluster_offsets=offsets,
                        corpus=corpus_sorted, ids=order.to(torch.int64).contiguous(), A_f32=A_f, B_f32=B_f)
+
+
+def random_index(corpus: torch.Tensor, wl: Workload) -> IndexArrays:
+    """Index arrays of the right shapes with RANDOM content (unit random centroids, uniform random int8 factors
+    and codes, clusters of 0.65..1.35 times the mean size cut from the corpus in its given order).
+
+    Search results on it mean nothing.  It exists to time and profile kernels whose cost does not depend on the
+    values (the streaming of the codes, the row gather) at shapes whose real index takes minutes to fit.
+    """
+    dev = corpus.device
+    n, d = corpus.shape
+    dp, r, L = wl.dp, wl.r, wl.L
+    g = _gen(dev, 1000 * wl.config_id + 77)
+    cent = torch.randn(L, dp, generator=g, device=dev)
+    cent = cent / cent.norm(dim=1, keepdim=True)
+    sizes = 0.65 + 0.7 * torch.rand(L, generator=g, device=dev, dtype=torch.float64)
+    sizes = torch.floor(sizes * (n / sizes.sum())).long()
+    sizes[0] += n - sizes.sum()
+    offsets = torch.zeros(L + 1, dtype=torch.int64, device=dev)
+    offsets[1:] = torch.cumsum(sizes, 0)
+    P = None
+    if dp != d:
+        P = _random_rotation(d, 1000 * wl.config_id + 78, "cpu")[:, :dp].to(torch.float32).to(dev).contiguous()
+    A = torch.randint(-127, 128, (L, r, dp), generator=g, device=dev, dtype=torch.int8)
+    B = torch.randint(-127, 128, (n, r), generator=g, device=dev, dtype=torch.int8)
+    s = torch.full((L,), 1e-3, device=dev)
+    return IndexArrays(metric=wl.metric, n=n, d=d, dp=dp, r=r, L=L, centroids=cent, P=P, A=A, B=B, scale_A=s,
+                       scale_B=s.clone(), cluster_offsets=offsets, corpus=corpus,
+                       ids=torch.arange(n, dtype=torch.int64, device=dev))
