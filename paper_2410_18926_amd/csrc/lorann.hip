@@ -20,6 +20,7 @@
 #include "rerank_group.hpp"
 #include "route.hpp"
 #include "score_mfma.hpp"
+#include "screen.hpp"
 #include "select_exact.hpp"
 #include "select_query.hpp"
 #include "stage_a.hpp"
@@ -75,8 +76,8 @@ struct DevBuf {
     template <typename T> T* as() const { return reinterpret_cast<T*>(p); }
 };
 
-enum KernelId { K_PROJECT, K_QUANTIZE, K_CENTROID, K_SELECT_W, K_BUCKET_COUNT, K_SCAN, K_SCATTER, K_STAGE_A, K_PAIR_MAX, K_SELECT_QUERY, K_SELECT_M, K_ORDER, K_UNION, K_RERANK, K_TOPK, K_COUNT };
-const char* const kKernelNames[K_COUNT] = {"project_f64", "quantize_rows", "centroid_dissim_f64", "select_clusters",
+enum KernelId { K_PROJECT, K_QUANTIZE, K_CENTROID, K_CENTROID_BF16, K_SELECT_W, K_BUCKET_COUNT, K_SCAN, K_SCATTER, K_STAGE_A, K_PAIR_MAX, K_SELECT_QUERY, K_SELECT_M, K_ORDER, K_UNION, K_RERANK, K_TOPK, K_COUNT };
+const char* const kKernelNames[K_COUNT] = {"project_f64", "quantize_rows", "centroid_dissim_f64", "centroid_screen_bf16", "select_clusters",
                                             "bucket_count", "scan_buckets", "scatter_pairs", "stage_a_i8", "pair_max_i8", "select_query", "score_select_exact",
                                             "order_queries", "group_union", "rerank", "topk"};
 
@@ -91,6 +92,10 @@ struct lorann_index {
     // index data (device)
     float* centroids = nullptr;     // [L][dp]
     double* cent_sqnorm = nullptr;  // [L] (Euclidean)
+    float* cent_nrm_f32 = nullptr;  // [L] (Euclidean) the same norms rounded to float, for the approximate scores
+    __bf16* cent_bf16 = nullptr;    // [L][dp] centroids rounded to bfloat16
+    float mu_max = 0.0f;            // >= max_l |mu_l|_2 (rounded up)
+    float nrm_max = 0.0f;           // >= max_l |mu_l|_2^2 (Euclidean)
     float* Pt = nullptr;            // [dp][d] transposed projection, or NULL
     int8_t* A = nullptr;            // [L][r][dp]
     int8_t* Bp = nullptr;           // [n][r_pad] codes padded with zeros to r_pad bytes
@@ -100,7 +105,7 @@ struct lorann_index {
     int64_t* ids = nullptr;         // [n] or NULL
     float* sqnorm = nullptr;        // [n] (Euclidean)
     // workspace (device), sized for `chunk` queries
-    DevBuf qproj, q8, dx, gscore, sel, count, rank_in_bucket, qrank, qorder, qorder2, off0, base_tab, bucket_off, tile_off, unit_off, slot_of_pos, pos_of_slot, Z, sigma, cand;
+    DevBuf qproj, qbf, q8, dx, gscore, sel, count, rank_in_bucket, qrank, qorder, qorder2, off0, base_tab, bucket_off, tile_off, unit_off, slot_of_pos, pos_of_slot, Z, sigma, cand;
     DevBuf tau, n_kept, fb_list, pmax, qkey, u_row, u_mask, u_pos, u_count, rdist, rcid, rccount;
     int32_t force_exact = 0;        // 1: score + select with the per-query kernel only (verification)
     DevBuf stage_q, stage_ids, stage_dists;   // staging when the caller passes host memory
@@ -116,9 +121,9 @@ struct lorann_index {
 namespace {
 
 void free_all(lorann_index* ix) {
-    void* ptrs[] = {ix->centroids, ix->cent_sqnorm, ix->Pt, ix->A, ix->Bp, ix->sA, ix->sB, ix->off, ix->corpus, ix->ids, ix->sqnorm};
+    void* ptrs[] = {ix->centroids, ix->cent_sqnorm, ix->cent_nrm_f32, ix->cent_bf16, ix->Pt, ix->A, ix->Bp, ix->sA, ix->sB, ix->off, ix->corpus, ix->ids, ix->sqnorm};
     for (void* p : ptrs) if (p) (void)hipFree(p);
-    DevBuf* bufs[] = {&ix->qproj, &ix->q8, &ix->dx, &ix->gscore, &ix->sel, &ix->count, &ix->rank_in_bucket, &ix->qrank, &ix->qorder, &ix->qorder2, &ix->off0, &ix->base_tab, &ix->bucket_off, &ix->tile_off,
+    DevBuf* bufs[] = {&ix->qproj, &ix->qbf, &ix->q8, &ix->dx, &ix->gscore, &ix->sel, &ix->count, &ix->rank_in_bucket, &ix->qrank, &ix->qorder, &ix->qorder2, &ix->off0, &ix->base_tab, &ix->bucket_off, &ix->tile_off,
                       &ix->unit_off, &ix->slot_of_pos, &ix->pos_of_slot, &ix->Z, &ix->sigma, &ix->cand, &ix->tau,
                       &ix->n_kept, &ix->fb_list, &ix->pmax, &ix->qkey, &ix->u_row, &ix->u_mask, &ix->u_pos, &ix->u_count, &ix->rdist, &ix->rcid, &ix->rccount, &ix->stage_q, &ix->stage_ids, &ix->stage_dists};
     for (DevBuf* b : bufs) b->release();
@@ -211,11 +216,36 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
             hipLaunchKernelGGL((k_gemm_nt_f64<EPI_PLAIN, 32>), dim3((dp + 63) / 64, (unsigned)((nq + 31) / 32)), dim3(256), 0, s, dQ, ix->Pt, ix->qproj.as<float>(), (const double*)nullptr, (int)nq, dp, d, pvec);
         qp = ix->qproj.as<float>();
     }
+    // Routing by screening (approximate scores on the bf16 matrix cores, exact evaluation of a short list) unless
+    // verification asks for the plain route or the row of values does not fit the registers of a block.
+    const bool screen = !ix->force_exact && L <= 16384;
+    if (screen && (rc = ix->qbf.reserve((size_t)nq * dp * 2))) return rc;
     {
         Prof p(ix, K_QUANTIZE);
         hipLaunchKernelGGL(k_quantize_rows, dim3((unsigned)((nq + 3) / 4)), dim3(256), 0, s, qp, ix->q8.as<int8_t>(), ix->dx.as<float>(), (int)nq, dp,
-                           ix->count.as<int32_t>(), 2 * L + 1);
+                           ix->count.as<int32_t>(), 2 * L + 1, screen ? ix->qbf.as<__bf16>() : (__bf16*)nullptr);
     }
+    if (screen) {
+        {
+            Prof p(ix, K_CENTROID_BF16);
+            const dim3 grid((unsigned)((L + 127) / 128), (unsigned)((nq + 127) / 128));
+            if (ix->metric == LORANN_L2)
+                hipLaunchKernelGGL(k_centroid_bf16<true>, grid, dim3(256), 0, s, ix->qbf.as<__bf16>(), ix->cent_bf16, ix->gscore.as<float>(), ix->cent_nrm_f32, (int)nq, L, dp);
+            else
+                hipLaunchKernelGGL(k_centroid_bf16<false>, grid, dim3(256), 0, s, ix->qbf.as<__bf16>(), ix->cent_bf16, ix->gscore.as<float>(), (const float*)nullptr, (int)nq, L, dp);
+        }
+        {
+            Prof p(ix, K_SELECT_W);
+            ScreenArgs sa;
+            sa.ghat = ix->gscore.as<float>(); sa.qp = qp; sa.centroids = ix->centroids;
+            sa.cent_sqnorm = ix->metric == LORANN_L2 ? ix->cent_sqnorm : nullptr; sa.sel = ix->sel.as<int32_t>();
+            sa.L = L; sa.dp = dp; sa.w = w; sa.mu_max = ix->mu_max; sa.nrm_max = ix->metric == LORANN_L2 ? ix->nrm_max : 0.0f;
+            const size_t lds = (size_t)dp * 4;
+            if (L <= 1024) hipLaunchKernelGGL(k_select_clusters_screen_wave<16>, dim3((unsigned)((nq + 3) / 4)), dim3(256), 4 * lds, s, sa, (int)nq);
+            else if (L <= 4096) hipLaunchKernelGGL(k_select_clusters_screen<16>, dim3((unsigned)nq), dim3(256), lds, s, sa);
+            else hipLaunchKernelGGL(k_select_clusters_screen<64>, dim3((unsigned)nq), dim3(256), lds, s, sa);
+        }
+    } else {
     {
         Prof p(ix, K_CENTROID);
         const bool big = gemm_pick_bm(nq, L) == 64;
@@ -242,6 +272,7 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
             hipLaunchKernelGGL(k_select_clusters_regs<64>, dim3((unsigned)nq), dim3(256), 0, s, ix->gscore.as<float>(), L, w, ix->sel.as<int32_t>());
         else
             hipLaunchKernelGGL(k_select_clusters, dim3((unsigned)nq), dim3(256), 0, s, ix->gscore.as<float>(), L, w, ix->sel.as<int32_t>());
+    }
     }
     const bool lds_hist = (size_t)L * 8 <= 64 * 1024;
     const int nbb = (int)((nq + kBucketQueries - 1) / kBucketQueries);
@@ -601,11 +632,34 @@ int lorann_load_index(lorann_index** out, int32_t metric, int64_t n, int32_t d, 
             (void)hipFree(Praw);
             if (he != hipSuccess) return fail(LORANN_E_DEVICE, "transposing the projection failed: %s", hipGetErrorString(he));
         }
-        if (metric == LORANN_L2) {   // Sec. 3.1: the norms |c_j|^2 (and |mu_l|^2 for routing) are precomputed
+        {   // centroid norms: |mu_l|^2 enters the Euclidean routing (Sec. 3.1); the largest norm enters the error
+            // bound of the approximate centroid scores
+            double* nrm = nullptr;
+            HIP_TRY(hipMalloc((void**)&nrm, (size_t)L * 8));
+            hipLaunchKernelGGL(k_row_sqnorm<double>, dim3((unsigned)((L + 3) / 4)), dim3(256), 0, 0, ix->centroids, nrm, (int64_t)L, dp);
+            std::vector<double> h((size_t)L);
+            hipError_t he = hipMemcpy(h.data(), nrm, (size_t)L * 8, hipMemcpyDeviceToHost);
+            if (he != hipSuccess) { (void)hipFree(nrm); return fail(LORANN_E_DEVICE, "centroid norms failed: %s", hipGetErrorString(he)); }
+            double mx = 0.0;
+            for (double v : h) mx = std::max(mx, v);          // a NaN norm is ignored here; such rows are garbage anyway
+            ix->mu_max = std::nextafter((float)(std::sqrt(mx) * (1.0 + 1e-6)), INFINITY);
+            ix->nrm_max = std::nextafter((float)(mx * (1.0 + 1e-6)), INFINITY);
+            if (metric == LORANN_L2) {
+                ix->cent_sqnorm = nrm;
+                std::vector<float> hf((size_t)L);
+                for (size_t i = 0; i < hf.size(); ++i) hf[i] = (float)h[i];
+                if ((e = dev_copy(&ix->cent_nrm_f32, hf.data(), (size_t)L))) return e;
+            } else {
+                (void)hipFree(nrm);
+            }
+            HIP_TRY(hipMalloc((void**)&ix->cent_bf16, (size_t)L * dp * 2));
+            const int64_t tot = (int64_t)L * dp;
+            hipLaunchKernelGGL(k_to_bf16, dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, 0, ix->centroids, ix->cent_bf16, tot);
+            HIP_TRY(hipDeviceSynchronize());
+        }
+        if (metric == LORANN_L2) {   // Sec. 3.1: the norms |c_j|^2 of the corpus rows are precomputed
             HIP_TRY(hipMalloc((void**)&ix->sqnorm, (size_t)n * 4));
-            HIP_TRY(hipMalloc((void**)&ix->cent_sqnorm, (size_t)L * 8));
             hipLaunchKernelGGL(k_row_sqnorm<float>, dim3((unsigned)((n + 3) / 4)), dim3(256), 0, 0, ix->corpus, ix->sqnorm, n, d);
-            hipLaunchKernelGGL(k_row_sqnorm<double>, dim3((unsigned)((L + 3) / 4)), dim3(256), 0, 0, ix->centroids, ix->cent_sqnorm, (int64_t)L, dp);
             HIP_TRY(hipDeviceSynchronize());
         }
         return LORANN_OK;

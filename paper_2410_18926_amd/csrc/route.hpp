@@ -10,16 +10,21 @@ namespace lorann {
 // One wavefront per query row; block = 256 (4 rows).  Round-half-to-even, codes clamped to [-127, 127];
 // a zero row gives zero codes and step 0.  The quotients are formed in double and rounded once, which equals
 // IEEE float division.  The first blocks also clear the `nzero` counters of the counting sorts that follow.
+// qb (optional): the row rounded to bfloat16, for the approximate centroid scores.
 __global__ __launch_bounds__(256) void k_quantize_rows(const float* __restrict__ qp, int8_t* __restrict__ q8,
                                                         float* __restrict__ dx, int nq, int dp,
-                                                        int32_t* __restrict__ zero, int nzero) {
+                                                        int32_t* __restrict__ zero, int nzero, __bf16* __restrict__ qb) {
     for (int i = blockIdx.x * 256 + threadIdx.x; i < nzero; i += gridDim.x * 256) zero[i] = 0;
     const int lane = threadIdx.x & 63;
     const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (row >= nq) return;
     const float* p = qp + (size_t)row * dp;
     float a = 0.0f;
-    for (int i = lane; i < dp; i += 64) a = fmaxf(a, fabsf(p[i]));
+    for (int i = lane; i < dp; i += 64) {
+        const float x = p[i];
+        a = fmaxf(a, fabsf(x));
+        if (qb) qb[(size_t)row * dp + i] = (__bf16)x;
+    }
     a = wave_max_f32(a);
     int8_t* o = q8 + (size_t)row * dp;
     if (!(a > 0.0f)) {
@@ -191,39 +196,27 @@ __global__ __launch_bounds__(256) void k_select_clusters_regs(const float* __res
     }
 }
 
-// Same selection, one WAVEFRONT per query with the L keys held in registers (KPL keys per lane, L <= 64 * KPL):
-// no re-reading of the scores and no block barriers.  4-pass radix select with a wavefront-private LDS
-// histogram; ties at the threshold go to the lower cluster id; ordered output.
-// grid = ceil(nq / 4), block = 256 (4 queries per block).
+// The same selection done by ONE WAVEFRONT over keys it holds in registers (KPL keys per lane, element
+// l = 64 * i + lane, L <= 64 * KPL, padding = 0xFFFFFFFF): 4-pass radix select with a wavefront-private LDS
+// histogram (`hist`, 256 ints); ties at the threshold go to the lower cluster id; the w selected are written to
+// `out` ordered by (key, cluster id).  `selk`, `seli`: 256 entries of wavefront-private LDS each.  No block
+// barrier inside.
 template <int KPL>
-__global__ __launch_bounds__(256) void k_select_clusters_wave(const float* __restrict__ g, int nq, int L, int w,
-                                                               int32_t* __restrict__ sel) {
-    __shared__ int hist[4][256];
-    __shared__ uint32_t selk[4][256];
-    __shared__ int seli[4][256];
-    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-    const int q = blockIdx.x * 4 + wv;
-    if (q >= nq) return;                       // wavefronts are independent: no block barrier below
-    const float* row = g + (size_t)q * L;
-    uint32_t key[KPL];                         // element l = 64 * i + lane
-#pragma unroll
-    for (int i = 0; i < KPL; ++i) key[i] = __float_as_uint(row[min(64 * i + lane, L - 1)]);   // independent loads, all in flight
-#pragma unroll
-    for (int i = 0; i < KPL; ++i)       // padding sorts last (and is never selected: w <= L)
-        key[i] = 64 * i + lane < L ? float_key_asc(__uint_as_float(key[i])) : 0xFFFFFFFFu;
+__device__ __forceinline__ uint32_t wave_wth_smallest_key(const uint32_t (&key)[KPL], int L, int w, int* hist, int& need_out) {
+    const int lane = threadIdx.x & 63;
     uint32_t prefix = 0u, mask = 0u;
     int need = w;
     for (int shift = 24; shift >= 0; shift -= 8) {
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront"); __builtin_amdgcn_wave_barrier();
 #pragma unroll
-        for (int b = 0; b < 4; ++b) hist[wv][lane + 64 * b] = 0;
+        for (int b = 0; b < 4; ++b) hist[lane + 64 * b] = 0;
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront"); __builtin_amdgcn_wave_barrier();
 #pragma unroll
         for (int i = 0; i < KPL; ++i)
-            if (64 * i + lane < L && (key[i] & mask) == prefix) atomicAdd(&hist[wv][(key[i] >> shift) & 255u], 1);
+            if (64 * i + lane < L && (key[i] & mask) == prefix) atomicAdd(&hist[(key[i] >> shift) & 255u], 1);
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront"); __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        const int h0 = hist[wv][4 * lane], h1 = hist[wv][4 * lane + 1], h2 = hist[wv][4 * lane + 2], h3 = hist[wv][4 * lane + 3];
+        const int h0 = hist[4 * lane], h1 = hist[4 * lane + 1], h2 = hist[4 * lane + 2], h3 = hist[4 * lane + 3];
         const int mine = h0 + h1 + h2 + h3;
         int incl = mine;
 #pragma unroll
@@ -242,8 +235,17 @@ __global__ __launch_bounds__(256) void k_select_clusters_wave(const float* __res
         need -= cum;
         mask |= 255u << shift;
     }
-    // prefix = key of the w-th smallest; `need` of the keys equal to it are taken, lowest cluster id first
-    const uint32_t T = prefix;
+    need_out = need;       // how many of the keys equal to the result belong to the w smallest
+    return prefix;
+}
+
+template <int KPL>
+__device__ __forceinline__ void wave_select_from_keys(const uint32_t (&key)[KPL], int L, int w, int32_t* __restrict__ out,
+                                                      int* hist, uint32_t* selk, int* seli) {
+    const int lane = threadIdx.x & 63;
+    int need;
+    const uint32_t T = wave_wth_smallest_key<KPL>(key, L, w, hist, need);
+    // `need` of the keys equal to T are taken, lowest cluster id first
     int n_out = 0, ties_left = need;
 #pragma unroll
     for (int i = 0; i < KPL; ++i) {
@@ -253,10 +255,10 @@ __global__ __launch_bounds__(256) void k_select_clusters_wave(const float* __res
         const bool tie = in && key[i] == T;
         const unsigned long long ml = __ballot(less), mt = __ballot(tie);
         const unsigned long long below = (1ull << lane) - 1ull;
-        if (less) { const int p = n_out + __popcll(ml & below); selk[wv][p] = key[i]; seli[wv][p] = l; }
+        if (less) { const int p = n_out + __popcll(ml & below); selk[p] = key[i]; seli[p] = l; }
         n_out += __popcll(ml);
         const int trank = __popcll(mt & below);
-        if (tie && trank < ties_left) { const int p = n_out + trank; selk[wv][p] = key[i]; seli[wv][p] = l; }
+        if (tie && trank < ties_left) { const int p = n_out + trank; selk[p] = key[i]; seli[p] = l; }
         const int took = min(ties_left, __popcll(mt));
         n_out += took;
         ties_left -= took;
@@ -264,16 +266,37 @@ __global__ __launch_bounds__(256) void k_select_clusters_wave(const float* __res
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront"); __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     for (int t = lane; t < w; t += 64) {       // order the w selected by (key, id): rank by counting
-        const uint32_t k = selk[wv][t];
-        const int id = seli[wv][t];
+        const uint32_t k = selk[t];
+        const int id = seli[t];
         int rank = 0;
         for (int u = 0; u < w; ++u) {
-            const uint32_t ku = selk[wv][u];
-            const int iu = seli[wv][u];
+            const uint32_t ku = selk[u];
+            const int iu = seli[u];
             rank += (ku < k || (ku == k && iu < id)) ? 1 : 0;
         }
-        sel[(size_t)q * w + rank] = id;
+        out[rank] = id;
     }
+}
+
+// One WAVEFRONT per query with the row of dissimilarities read once into registers: no re-reading of the scores
+// and no block barriers.  grid = ceil(nq / 4), block = 256 (4 queries per block).
+template <int KPL>
+__global__ __launch_bounds__(256) void k_select_clusters_wave(const float* __restrict__ g, int nq, int L, int w,
+                                                               int32_t* __restrict__ sel) {
+    __shared__ int hist[4][256];
+    __shared__ uint32_t selk[4][256];
+    __shared__ int seli[4][256];
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int q = blockIdx.x * 4 + wv;
+    if (q >= nq) return;                       // wavefronts are independent: no block barrier below
+    const float* row = g + (size_t)q * L;
+    uint32_t key[KPL];                         // element l = 64 * i + lane
+#pragma unroll
+    for (int i = 0; i < KPL; ++i) key[i] = __float_as_uint(row[min(64 * i + lane, L - 1)]);   // independent loads, all in flight
+#pragma unroll
+    for (int i = 0; i < KPL; ++i)       // padding sorts last (and is never selected: w <= L)
+        key[i] = 64 * i + lane < L ? float_key_asc(__uint_as_float(key[i])) : 0xFFFFFFFFu;
+    wave_select_from_keys<KPL>(key, L, w, sel + (size_t)q * w, hist[wv], selk[wv], seli[wv]);
 }
 
 // ---- Counting sort, step 1: count the pairs of every cluster. ----

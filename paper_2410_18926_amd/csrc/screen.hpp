@@ -1,0 +1,445 @@
+// Routing (Sec. 2.2; in the d'-dimensional space, Sec. 4.1) by screening: the w clusters of smallest
+// dissimilarity are found WITHOUT evaluating all L dissimilarities in double.
+//
+//   1. k_centroid_bf16: all L dissimilarities approximately - operands rounded to bfloat16, products on the
+//      bf16 matrix cores (v_mfma_f32_32x32x16_bf16), float accumulation.
+//   2. k_select_clusters_screen: a rigorous bound eps on |approximate - exact| turns the approximate values into
+//      a short list that provably contains the exact w best (everything not above the w-th smallest approximate
+//      value + 2 eps); only the list is evaluated exactly - double accumulation, one rounding to float, as the
+//      definition says - and ranked by (value, cluster id).
+//
+// The result is identical to ranking all L exact values; the double-precision work drops from L to about w
+// dot products per query.  A list that does not fit (huge norms, long runs of near-equal values) makes the
+// block evaluate every cluster exactly instead, so correctness never rests on the bound being tight.
+//
+// Error bound.  Rounding to bfloat16 (nearest even, same exponent range as float) changes a number by at most
+// 2^-9 relative, a product of two rounded numbers by at most (2^-8 + 2^-18) relative; the products are exact in
+// float; K float additions add at most ~K 2^-24 relative to the sum of magnitudes.  With Cauchy-Schwarz,
+// |ip_approx - ip| <= kScreenRel * |q|_2 * |mu|_2 with kScreenRel = 0.0042 >= 2^-8 + 2^-18 + 2 * 1024 * 2^-24
+// (d' <= 1024).  The final float operations of both sides are covered by a relative slack of 2^-20.
+//
+// Register layout of v_mfma_f32_32x32x16_bf16 (measured on gfx950): both operands give lane l eight consecutive
+// k (k-half l/32) of row / column l%32; result register v of lane l holds D[8*(v/4) + 4*(l/32) + v%4][l%32].
+#pragma once
+#include "common.hpp"
+#include "route.hpp"
+
+namespace lorann {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr float kScreenRel = 0.0042f;
+
+// o[i] = bfloat16(x[i]), round to nearest even.
+__global__ void k_to_bf16(const float* __restrict__ x, __bf16* __restrict__ o, int64_t n) {
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t < n) o[t] = (__bf16)x[t];
+}
+
+// out[q][l] = - <Q[q], C[l]>  (L2 = false)   or   nrm[l] - 2 <Q[q], C[l]>  (L2 = true), approximately.
+// Q [M][K], C [N][K] bfloat16 row-major (K % 16 == 0, 16-byte aligned rows), out [M][N] float, nrm [N] float.
+// grid = (ceil(N/128), ceil(M/128)), block = 256: 2 x 2 wavefronts, each a 64 x 64 tile as 2 x 2 MFMA tiles.
+// Operands go from memory straight into the registers of the lanes that feed them to the matrix core (rows
+// beyond the matrices are clamped, never stored); the two wavefronts that share rows meet in the vector cache.
+template <bool L2>
+__global__ __launch_bounds__(256) void k_centroid_bf16(const __bf16* __restrict__ Q, const __bf16* __restrict__ C,
+                                                        float* __restrict__ out, const float* __restrict__ nrm,
+                                                        int M, int N, int K) {
+    constexpr int SB = 4;                 // k-steps (of 16) requested together
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int i = lane & 31, h = lane >> 5;
+    const int m0 = blockIdx.y * 128 + (wv >> 1) * 64, n0 = blockIdx.x * 128 + (wv & 1) * 64;
+    const __bf16* qa[2];
+    const __bf16* cb[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+        qa[t] = Q + (size_t)min(m0 + 32 * t + i, M - 1) * K + 8 * h;
+        cb[t] = C + (size_t)min(n0 + 32 * t + i, N - 1) * K + 8 * h;
+    }
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.0f;
+
+    const int steps = K >> 4;
+    auto fetch = [&](int s0, bf16x8 (&a)[SB][2], bf16x8 (&b)[SB][2]) {
+#pragma unroll
+        for (int u = 0; u < SB; ++u) {
+            const int k = 16 * min(s0 + u, steps - 1);        // clamped: a repeat beyond the end, not used
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                a[u][t] = *reinterpret_cast<const bf16x8*>(qa[t] + k);
+                b[u][t] = *reinterpret_cast<const bf16x8*>(cb[t] + k);
+            }
+        }
+    };
+    bf16x8 a_cur[SB][2], b_cur[SB][2], a_nxt[SB][2], b_nxt[SB][2];
+    fetch(0, a_cur, b_cur);
+    for (int s0 = 0; s0 < steps; s0 += SB) {
+        fetch(s0 + SB, a_nxt, b_nxt);
+#pragma unroll
+        for (int u = 0; u < SB; ++u) {
+            if (s0 + u < steps) {                             // uniform
+#pragma unroll
+                for (int ta = 0; ta < 2; ++ta)
+#pragma unroll
+                    for (int tb = 0; tb < 2; ++tb)
+                        acc[ta][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cur[u][ta], b_cur[u][tb], acc[ta][tb], 0, 0, 0);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < SB; ++u)
+#pragma unroll
+            for (int t = 0; t < 2; ++t) { a_cur[u][t] = a_nxt[u][t]; b_cur[u][t] = b_nxt[u][t]; }
+    }
+#pragma unroll
+    for (int ta = 0; ta < 2; ++ta)
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb) {
+            const int col = n0 + 32 * tb + i;
+            const float nb = (L2 && col < N) ? nrm[col] : 0.0f;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = m0 + 32 * ta + 8 * (v >> 2) + 4 * h + (v & 3);
+                if (row < M && col < N) out[(size_t)row * N + col] = L2 ? nb - 2.0f * acc[ta][tb][v] : -acc[ta][tb][v];
+            }
+        }
+}
+
+// Sum of a double over each row of 16 lanes (data-parallel-primitive shifts with zero fill); the total is valid
+// in the LAST lane of the row only.
+__device__ __forceinline__ double row16_sum_f64_last(double x) {
+    auto shr = [](double v, auto ctrl) {
+        const long long b = __double_as_longlong(v);
+        const int lo = __builtin_amdgcn_update_dpp(0, (int)(b & 0xffffffffll), decltype(ctrl)::value, 0xf, 0xf, true);
+        const int hi = __builtin_amdgcn_update_dpp(0, (int)(b >> 32), decltype(ctrl)::value, 0xf, 0xf, true);
+        return __longlong_as_double(((long long)hi << 32) | (unsigned int)lo);
+    };
+    x += shr(x, std::integral_constant<int, 0x111>{});
+    x += shr(x, std::integral_constant<int, 0x112>{});
+    x += shr(x, std::integral_constant<int, 0x114>{});
+    x += shr(x, std::integral_constant<int, 0x118>{});
+    return x;
+}
+
+struct ScreenArgs {
+    float* ghat;                 // [nq][L] approximate dissimilarities (a row is overwritten with exact values
+                                 //         when its list does not fit)
+    const float* qp;             // [nq][dp] projected queries (float)
+    const float* centroids;      // [L][dp]
+    const double* cent_sqnorm;   // [L] (Euclidean) or NULL
+    int32_t* sel;                // out [nq][w], ordered (dissimilarity ascending, cluster id ascending)
+    int L, dp, w;
+    float mu_max;                // >= max_l |mu_l|_2
+    float nrm_max;               // >= max_l |mu_l|_2^2 (Euclidean; else 0)
+};
+
+// One block (256 threads) per query; KPT approximate values per thread in registers (256 * KPT >= L).
+// dynamic LDS = dp * 4 bytes (the query).
+template <int KPT>
+__global__ __launch_bounds__(256) void k_select_clusters_screen(ScreenArgs a) {
+    constexpr int CAP = 2048;
+    extern __shared__ __align__(16) unsigned char scr_smem[];
+    float* qs = reinterpret_cast<float*>(scr_smem);                  // [dp]
+    __shared__ __align__(16) unsigned long long tmin[256];
+    __shared__ __align__(16) unsigned long long cand[CAP + 2];     // (key, cluster) of the first, then the final list
+    __shared__ int clist[CAP];                                       // clusters evaluated exactly
+    __shared__ float s_part[4];
+    __shared__ int s_cnt, s_cnt2;
+    __shared__ uint32_t s_bound, s_gw;
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int L = a.L, dp = a.dp, w = a.w;
+    const bool l2 = a.cent_sqnorm != nullptr;
+    float* row = a.ghat + (size_t)blockIdx.x * L;
+    const float* qrow = a.qp + (size_t)blockIdx.x * dp;
+    int32_t* out = a.sel + (size_t)blockIdx.x * w;
+
+    // the query, its norm (rounded up), the approximate values
+    float v[KPT];
+#pragma unroll
+    for (int i = 0; i < KPT; ++i) v[i] = row[min(i * 256 + tid, L - 1)];
+    float nn = 0.0f;
+    for (int i = tid; i < dp; i += 256) { const float x = qrow[i]; qs[i] = x; nn = fmaf(x, x, nn); }
+    nn = wave_sum_f32(nn);
+    if (lane == 0) s_part[wv] = nn;
+    if (tid == 0) { s_cnt = 0; s_cnt2 = 0; }
+    uint32_t mn = 0xFFFFFFFFu;
+#pragma unroll
+    for (int i = 0; i < KPT; ++i) {
+        if (i * 256 + tid < L) mn = min(mn, float_key_asc(v[i]));
+    }
+    const unsigned long long mine = ((unsigned long long)mn << 32) | (unsigned)tid;
+    tmin[tid] = mine;
+    __syncthreads();
+    const float qn = sqrtf((s_part[0] + s_part[1]) + (s_part[2] + s_part[3])) * 1.00001f;
+    // |approximate - exact| <= eps for every cluster (see the header); Euclidean: g = nrm - 2 ip, nrm rounded to float
+    float eps = kScreenRel * qn * a.mu_max;
+    if (l2) eps = 2.0f * eps + 2.4e-7f * (a.nrm_max + 2.0f * qn * a.mu_max);
+    eps += 1e-30f;
+    // w-th smallest of the 256 per-thread minima: an upper bound of the w-th smallest approximate value
+    int rank = 0;
+    {
+        const ulonglong2* t2 = reinterpret_cast<const ulonglong2*>(tmin);
+#pragma unroll 16
+        for (int u = 0; u < 128; ++u) {
+            const ulonglong2 t = t2[u];
+            rank += (t.x < mine ? 1 : 0) + (t.y < mine ? 1 : 0);
+        }
+    }
+    if (rank == w - 1) s_bound = mn;
+    __syncthreads();
+    auto widen = [&](float t) {                           // t + 2 eps, rounded up generously
+        const float s = t + 2.0f * eps;
+        return s + 1e-6f * (fabsf(s) + eps);
+    };
+    const float tf1 = widen(key_to_float(s_bound));
+    // first list: everything that may lie below (w-th smallest approximate value) + 2 eps
+#pragma unroll
+    for (int i = 0; i < KPT; ++i) {
+        const int l = i * 256 + tid;
+        if (l < L && !(v[i] > tf1)) {
+            const int p = atomicAdd(&s_cnt, 1);
+            if (p < CAP) cand[p] = ((unsigned long long)float_key_asc(v[i]) << 32) | (unsigned)l;
+        }
+    }
+    __syncthreads();
+    const int c1 = s_cnt;
+    bool all_exact = c1 > CAP;                            // uniform
+    int c2 = 0;
+    if (!all_exact) {
+        // the w-th smallest approximate value itself (it is in the list), then the final list
+        if (tid < 2) cand[c1 + tid] = ~0ull;
+        __syncthreads();
+        const ulonglong2* cc = reinterpret_cast<const ulonglong2*>(cand);
+        const int c_pairs = (c1 + 1) >> 1;
+        for (int e = tid; e < c1; e += 256) {
+            const unsigned long long me = cand[e];
+            int r = 0;
+#pragma unroll 8
+            for (int u = 0; u < c_pairs; ++u) {
+                const ulonglong2 t = cc[u];
+                r += (t.x < me ? 1 : 0) + (t.y < me ? 1 : 0);
+            }
+            if (r == w - 1) s_gw = (uint32_t)(me >> 32);
+        }
+        __syncthreads();
+        const float tf2 = widen(key_to_float(s_gw));
+        for (int e = tid; e < c1; e += 256) {
+            const unsigned long long me = cand[e];
+            if (!(key_to_float((uint32_t)(me >> 32)) > tf2)) clist[atomicAdd(&s_cnt2, 1)] = (int)(unsigned)(me & 0xFFFFFFFFull);
+        }
+        __syncthreads();
+        c2 = s_cnt2;
+    }
+    // exact values: 16 lanes per cluster, double accumulation, one rounding to float
+    const int grp = tid >> 4, l16 = tid & 15;
+    const int n_exact = all_exact ? L : c2;
+    const int d4 = dp >> 2;                               // d' is a multiple of 16
+    __syncthreads();
+    for (int e = grp; e < n_exact; e += 16) {
+        const int l = all_exact ? e : clist[e];
+        const float4* mu = reinterpret_cast<const float4*>(a.centroids + (size_t)l * dp);
+        const float4* q4 = reinterpret_cast<const float4*>(qs);
+        double acc = 0.0;
+        for (int i4 = l16; i4 < d4; i4 += 16) {
+            const float4 m = mu[i4], x = q4[i4];
+            acc += (double)x.x * (double)m.x;
+            acc += (double)x.y * (double)m.y;
+            acc += (double)x.z * (double)m.z;
+            acc += (double)x.w * (double)m.w;
+        }
+        acc = row16_sum_f64_last(acc);
+        if (l16 == 15) {
+            const float g = l2 ? (float)(a.cent_sqnorm[l] - 2.0 * acc) : (float)(-acc);
+            if (all_exact) row[l] = g;
+            else cand[e] = ((unsigned long long)float_key_asc(g) << 32) | (unsigned)l;
+        }
+    }
+    __syncthreads();
+    if (all_exact) {                                      // uniform: rank the whole (now exact) row
+        // the row was rewritten through global memory by other threads of this block: complete the writes, meet,
+        // and drop what the vector cache still holds of the old row
+        __threadfence();
+        __syncthreads();
+        __threadfence();
+        select_clusters_radix(row, L, w, out);
+        return;
+    }
+    if (tid < 2) cand[c2 + tid] = ~0ull;
+    __syncthreads();
+    const ulonglong2* cc = reinterpret_cast<const ulonglong2*>(cand);
+    const int c_pairs = (c2 + 1) >> 1;
+    for (int e = tid; e < c2; e += 256) {
+        const unsigned long long me = cand[e];
+        int r = 0;
+#pragma unroll 8
+        for (int u = 0; u < c_pairs; ++u) {
+            const ulonglong2 t = cc[u];
+            r += (t.x < me ? 1 : 0) + (t.y < me ? 1 : 0);
+        }
+        if (r < w) out[r] = (int)(unsigned)(me & 0xFFFFFFFFull);
+    }
+}
+
+// The same screening by ONE WAVEFRONT per query (row of approximate values in registers, KPL per lane,
+// L <= 64 * KPL): no block barriers, four queries per block.  grid = ceil(nq / 4), block = 256,
+// dynamic LDS = 4 * dp * 4 bytes (the four queries).
+// Per wavefront: radix select of the w-th smallest approximate value; the values up to it + 2 eps form the list
+// (at most kScreenWaveCap clusters; a longer list makes the wavefront evaluate all L clusters exactly); 16 lanes
+// evaluate one listed cluster exactly, four clusters at a time and two rounds in flight; the list is ranked by
+// (exact value, cluster id).
+constexpr int kScreenWaveCap = 256;
+template <int KPL>
+__global__ __launch_bounds__(256) void k_select_clusters_screen_wave(ScreenArgs a, int nq) {
+    extern __shared__ __align__(16) unsigned char scrw_smem[];
+    __shared__ int hist[4][256];
+    // per wavefront: [cand (kScreenWaveCap + 2) x 8 B | clist kScreenWaveCap x 4 B]; when everything is evaluated
+    // exactly the same bytes hold the L exact values (L <= 64 * KPL floats) instead
+    constexpr int kListBytes = (kScreenWaveCap + 2) * 8 + kScreenWaveCap * 4;
+    constexpr int kRowBytes = 64 * KPL * 4;
+    constexpr int kUnion = kListBytes > kRowBytes ? kListBytes : kRowBytes;
+    __shared__ __align__(16) unsigned char wbuf[4][kUnion];
+    __shared__ uint32_t selk[4][256];
+    __shared__ int seli[4][256];
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int q = blockIdx.x * 4 + wv;
+    if (q >= nq) return;                       // wavefronts are independent: no block barrier below
+    const int L = a.L, dp = a.dp, w = a.w;
+    const bool l2 = a.cent_sqnorm != nullptr;
+    float* qs = reinterpret_cast<float*>(scrw_smem) + (size_t)wv * dp;
+    unsigned long long* cand = reinterpret_cast<unsigned long long*>(wbuf[wv]);
+    int* clist = reinterpret_cast<int*>(wbuf[wv] + (kScreenWaveCap + 2) * 8);
+    float* gex = reinterpret_cast<float*>(wbuf[wv]);
+    float* row = a.ghat + (size_t)q * L;
+    const float* qrow = a.qp + (size_t)q * dp;
+    int32_t* out = a.sel + (size_t)q * w;
+    const int d4 = dp >> 2;                    // d' is a multiple of 16
+
+    float v[KPL];
+#pragma unroll
+    for (int i = 0; i < KPL; ++i) v[i] = row[min(64 * i + lane, L - 1)];
+    float nn = 0.0f;
+    for (int i4 = lane; i4 < d4; i4 += 64) {
+        const float4 x = reinterpret_cast<const float4*>(qrow)[i4];
+        reinterpret_cast<float4*>(qs)[i4] = x;
+        nn = fmaf(x.x, x.x, nn); nn = fmaf(x.y, x.y, nn); nn = fmaf(x.z, x.z, nn); nn = fmaf(x.w, x.w, nn);
+    }
+    nn = wave_sum_f32(nn);
+    const float qn = sqrtf(nn) * 1.00001f;
+    float eps = kScreenRel * qn * a.mu_max;
+    if (l2) eps = 2.0f * eps + 2.4e-7f * (a.nrm_max + 2.0f * qn * a.mu_max);
+    eps += 1e-30f;
+    uint32_t key[KPL];
+#pragma unroll
+    for (int i = 0; i < KPL; ++i) key[i] = 64 * i + lane < L ? float_key_asc(v[i]) : 0xFFFFFFFFu;
+    int need_unused;
+    const uint32_t gw = wave_wth_smallest_key<KPL>(key, L, w, hist[wv], need_unused);
+    const float s2 = key_to_float(gw) + 2.0f * eps;
+    const float tf2 = s2 + 1e-6f * (fabsf(s2) + eps);
+    // the list: clusters whose approximate value does not exceed tf2
+    int c2 = 0;
+#pragma unroll
+    for (int i = 0; i < KPL; ++i) {
+        const int l = 64 * i + lane;
+        const bool in = l < L && !(v[i] > tf2);
+        const unsigned long long mk = __ballot(in);
+        const int p = c2 + __popcll(mk & ((1ull << lane) - 1ull));
+        if (in && p < kScreenWaveCap) clist[p] = l;
+        c2 += __popcll(mk);
+    }
+    const bool all_exact = c2 > kScreenWaveCap;            // uniform over the wavefront
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront"); __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+    // exact values: 16 lanes per cluster, 4 clusters at a time, 2 rounds (8 clusters) requested together
+    const int grp = lane >> 4, l16 = lane & 15;
+    const int n_exact = all_exact ? L : c2;
+    const float4* q4 = reinterpret_cast<const float4*>(qs);
+    auto exact_of = [&](int l, const float4* mu) {       // full rows of 16 lanes execute this together
+        double acc = 0.0;
+        for (int i4 = l16; i4 < d4; i4 += 16) {
+            const float4 m = mu[i4], x = q4[i4];
+            acc += (double)x.x * (double)m.x;
+            acc += (double)x.y * (double)m.y;
+            acc += (double)x.z * (double)m.z;
+            acc += (double)x.w * (double)m.w;
+        }
+        acc = row16_sum_f64_last(acc);
+        return l2 ? (float)(a.cent_sqnorm[l] - 2.0 * acc) : (float)(-acc);
+    };
+    if (d4 <= 64) {
+        // d' <= 256: a lane holds its share of a centroid in 4 float4; two rounds are in flight
+        for (int e0 = 0; e0 < n_exact; e0 += 8) {
+            int le[2];
+            float4 m[2][4];
+#pragma unroll
+            for (int r = 0; r < 2; ++r) {
+                const int e = min(e0 + 4 * r + grp, n_exact - 1);
+                le[r] = all_exact ? e : clist[e];
+                const float4* mu = reinterpret_cast<const float4*>(a.centroids + (size_t)le[r] * dp);
+#pragma unroll
+                for (int u = 0; u < 4; ++u) m[r][u] = mu[min(l16 + 16 * u, d4 - 1)];
+            }
+#pragma unroll
+            for (int r = 0; r < 2; ++r) {
+                double acc = 0.0;
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    if (l16 + 16 * u < d4) {
+                        const float4 x = q4[l16 + 16 * u];
+                        acc += (double)x.x * (double)m[r][u].x;
+                        acc += (double)x.y * (double)m[r][u].y;
+                        acc += (double)x.z * (double)m[r][u].z;
+                        acc += (double)x.w * (double)m[r][u].w;
+                    }
+                }
+                acc = row16_sum_f64_last(acc);
+                const int e = e0 + 4 * r + grp;
+                if (l16 == 15 && e < n_exact) {
+                    const float g = l2 ? (float)(a.cent_sqnorm[le[r]] - 2.0 * acc) : (float)(-acc);
+                    if (all_exact) gex[le[r]] = g;
+                    else cand[e] = ((unsigned long long)float_key_asc(g) << 32) | (unsigned)le[r];
+                }
+            }
+        }
+    } else {
+        for (int e0 = 0; e0 < n_exact; e0 += 4) {
+            const int e = min(e0 + grp, n_exact - 1);
+            const int l = all_exact ? e : clist[e];
+            const float g = exact_of(l, reinterpret_cast<const float4*>(a.centroids + (size_t)l * dp));
+            if (l16 == 15 && e0 + grp < n_exact) {
+                if (all_exact) gex[l] = g;
+                else cand[e] = ((unsigned long long)float_key_asc(g) << 32) | (unsigned)l;
+            }
+        }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront"); __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    if (all_exact) {                                       // rank the whole exact row
+#pragma unroll
+        for (int i = 0; i < KPL; ++i) key[i] = 64 * i + lane < L ? float_key_asc(gex[64 * i + lane]) : 0xFFFFFFFFu;
+        wave_select_from_keys<KPL>(key, L, w, out, hist[wv], selk[wv], seli[wv]);
+        return;
+    }
+    if (lane < 2) cand[c2 + lane] = ~0ull;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront"); __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const ulonglong2* cc = reinterpret_cast<const ulonglong2*>(cand);
+    const int c_pairs = (c2 + 1) >> 1;
+    for (int e = lane; e < c2; e += 64) {
+        const unsigned long long me = cand[e];
+        int r = 0;
+#pragma unroll 8
+        for (int u = 0; u < c_pairs; ++u) {
+            const ulonglong2 t = cc[u];
+            r += (t.x < me ? 1 : 0) + (t.y < me ? 1 : 0);
+        }
+        if (r < w) out[r] = (int)(unsigned)(me & 0xFFFFFFFFull);
+    }
+}
+
+}  // namespace lorann

@@ -59,9 +59,6 @@ __device__ __forceinline__ uint32_t block_mth_largest(int n, int m, int* hist, u
     return T;
 }
 
-__device__ __forceinline__ float key_to_float(uint32_t key) {   // inverse of float_key_asc
-    return __uint_as_float((key & 0x80000000u) ? (key & 0x7fffffffu) : ~key);
-}
 
 // (score, row) entries a query holds in LDS: 2048 (16 KiB, more blocks per CU) or 6144 for m > 1024.  A quarter
 // of the capacity is scored between capacity checks.

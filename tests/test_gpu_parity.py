@@ -256,3 +256,41 @@ def test_many_clusters_routing_variants(B, L, plateau):
     np.testing.assert_array_equal(np.sort(gst["cand_rows"].astype(np.int64), axis=1), np.sort(ost["cand_rows"], axis=1))
     assert_topk_equal(g_ids, g_d, o_ids, o_d, f"L={L} plateau={plateau}")
     gix.close()
+
+
+def test_full_size_benchmark_configuration_sampled_parity(B):
+    """The benchmark configuration at its full size (1M x 768, batch 10000, w=32, m=200, k=10) in the launch
+    configuration bench.py times - device-resident inputs, one whole batch per call, hence the cluster-batched
+    scoring, the per-query walk and the grouped re-rank - against the oracle on a sample of the batch: the
+    oracle handles a query on its own, so any subset can be checked one by one.  Integer stages and candidate
+    sets bit-exact, distances and ids to the usual bars."""
+    from paper_2410_18926_amd.synth import get_workload, make_dataset, build_index
+    wl = get_workload("embed-ip")
+    dev = torch.device("cuda:0")
+    corpus, queries = make_dataset(wl, dev)
+    ix = build_index(corpus, wl)
+    del corpus
+    gix = B.Index.from_arrays(ix)
+    k, w, m = wl.k, wl.w, wl.m
+    g_ids, g_d, gst = gix.search_stages(queries, k, w, m)
+    p_ids, p_d = gix.search(queries, k, w, m)                      # the entry point the benchmark calls
+    np.testing.assert_array_equal(p_ids.cpu().numpy(), g_ids)
+    np.testing.assert_array_equal(p_d.cpu().numpy(), g_d)
+    gix.close()
+
+    sample = np.random.default_rng(7).choice(wl.nq, size=192, replace=False)
+    sample.sort()
+    a = ix.numpy()
+    del ix
+    torch.cuda.empty_cache()
+    oix = O.OracleIndex(a)
+    qh = queries.cpu().numpy()[sample]
+    o_ids, o_d, ost = O.search(oix, qh, k, w, m, stages=True)
+    np.testing.assert_array_equal(gst["qproj"][sample], ost["qproj"], err_msg="projected queries")
+    np.testing.assert_array_equal(gst["q8"][sample], ost["q8"], err_msg="query codes")
+    np.testing.assert_array_equal(gst["sel"][sample], ost["sel"], err_msg="selected clusters")
+    np.testing.assert_array_equal(gst["z"][sample], ost["z"], err_msg="re-quantized vectors")
+    np.testing.assert_array_equal(gst["sigma"][sample], ost["sigma"], err_msg="pair scales")
+    np.testing.assert_array_equal(np.sort(gst["cand_rows"][sample].astype(np.int64), axis=1), np.sort(ost["cand_rows"], axis=1),
+                                  err_msg="candidate sets")
+    assert_topk_equal(g_ids[sample], g_d[sample], o_ids, o_d, "embed-ip full size")
