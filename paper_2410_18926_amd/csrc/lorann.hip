@@ -228,11 +228,14 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
     if (screen) {
         {
             Prof p(ix, K_CENTROID_BF16);
-            const dim3 grid((unsigned)((L + 127) / 128), (unsigned)((nq + 127) / 128));
-            if (ix->metric == LORANN_L2)
-                hipLaunchKernelGGL(k_centroid_bf16<true>, grid, dim3(256), 0, s, ix->qbf.as<__bf16>(), ix->cent_bf16, ix->gscore.as<float>(), ix->cent_nrm_f32, (int)nq, L, dp);
-            else
-                hipLaunchKernelGGL(k_centroid_bf16<false>, grid, dim3(256), 0, s, ix->qbf.as<__bf16>(), ix->cent_bf16, ix->gscore.as<float>(), (const float*)nullptr, (int)nq, L, dp);
+            const int64_t blocks2 = (int64_t)((L + 127) / 128) * ((nq + 127) / 128);
+            const int ti = blocks2 >= 256 ? 2 : 1;          // tiny problems: twice the blocks of half the height
+            const dim3 grid((unsigned)((L + 127) / 128), (unsigned)((nq + 64 * ti - 1) / (64 * ti)));
+            const float* nrm = ix->metric == LORANN_L2 ? ix->cent_nrm_f32 : nullptr;
+#define LAUNCH_CB(L2_, TI_) hipLaunchKernelGGL((k_centroid_bf16<L2_, TI_>), grid, dim3(256), 0, s, ix->qbf.as<__bf16>(), ix->cent_bf16, ix->gscore.as<float>(), nrm, (int)nq, L, dp)
+            if (ix->metric == LORANN_L2) { if (ti == 2) LAUNCH_CB(true, 2); else LAUNCH_CB(true, 1); }
+            else { if (ti == 2) LAUNCH_CB(false, 2); else LAUNCH_CB(false, 1); }
+#undef LAUNCH_CB
         }
         {
             Prof p(ix, K_SELECT_W);

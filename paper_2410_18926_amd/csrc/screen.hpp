@@ -39,45 +39,44 @@ __global__ void k_to_bf16(const float* __restrict__ x, __bf16* __restrict__ o, i
 
 // out[q][l] = - <Q[q], C[l]>  (L2 = false)   or   nrm[l] - 2 <Q[q], C[l]>  (L2 = true), approximately.
 // Q [M][K], C [N][K] bfloat16 row-major (K % 16 == 0, 16-byte aligned rows), out [M][N] float, nrm [N] float.
-// grid = (ceil(N/128), ceil(M/128)), block = 256: 2 x 2 wavefronts, each a 64 x 64 tile as 2 x 2 MFMA tiles.
+// grid = (ceil(N/128), ceil(M/(64 TI))), block = 256: 2 x 2 wavefronts, each a (32 TI) x 64 tile as TI x 2 MFMA
+// tiles (TI = 2 moves fewer operand bytes; TI = 1 gives twice the blocks when the problem is small).
 // Operands go from memory straight into the registers of the lanes that feed them to the matrix core (rows
 // beyond the matrices are clamped, never stored); the two wavefronts that share rows meet in the vector cache.
-template <bool L2>
+template <bool L2, int TI>
 __global__ __launch_bounds__(256) void k_centroid_bf16(const __bf16* __restrict__ Q, const __bf16* __restrict__ C,
                                                         float* __restrict__ out, const float* __restrict__ nrm,
                                                         int M, int N, int K) {
     constexpr int SB = 4;                 // k-steps (of 16) requested together
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     const int i = lane & 31, h = lane >> 5;
-    const int m0 = blockIdx.y * 128 + (wv >> 1) * 64, n0 = blockIdx.x * 128 + (wv & 1) * 64;
-    const __bf16* qa[2];
+    const int m0 = blockIdx.y * (64 * TI) + (wv >> 1) * (32 * TI), n0 = blockIdx.x * 128 + (wv & 1) * 64;
+    const __bf16* qa[TI];
     const __bf16* cb[2];
 #pragma unroll
-    for (int t = 0; t < 2; ++t) {
-        qa[t] = Q + (size_t)min(m0 + 32 * t + i, M - 1) * K + 8 * h;
-        cb[t] = C + (size_t)min(n0 + 32 * t + i, N - 1) * K + 8 * h;
-    }
-    f32x16 acc[2][2];
+    for (int t = 0; t < TI; ++t) qa[t] = Q + (size_t)min(m0 + 32 * t + i, M - 1) * K + 8 * h;
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int t = 0; t < 2; ++t) cb[t] = C + (size_t)min(n0 + 32 * t + i, N - 1) * K + 8 * h;
+    f32x16 acc[TI][2];
+#pragma unroll
+    for (int a = 0; a < TI; ++a)
 #pragma unroll
         for (int b = 0; b < 2; ++b)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.0f;
 
     const int steps = K >> 4;
-    auto fetch = [&](int s0, bf16x8 (&a)[SB][2], bf16x8 (&b)[SB][2]) {
+    auto fetch = [&](int s0, bf16x8 (&a)[SB][TI], bf16x8 (&b)[SB][2]) {
 #pragma unroll
         for (int u = 0; u < SB; ++u) {
             const int k = 16 * min(s0 + u, steps - 1);        // clamped: a repeat beyond the end, not used
 #pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                a[u][t] = *reinterpret_cast<const bf16x8*>(qa[t] + k);
-                b[u][t] = *reinterpret_cast<const bf16x8*>(cb[t] + k);
-            }
+            for (int t = 0; t < TI; ++t) a[u][t] = *reinterpret_cast<const bf16x8*>(qa[t] + k);
+#pragma unroll
+            for (int t = 0; t < 2; ++t) b[u][t] = *reinterpret_cast<const bf16x8*>(cb[t] + k);
         }
     };
-    bf16x8 a_cur[SB][2], b_cur[SB][2], a_nxt[SB][2], b_nxt[SB][2];
+    bf16x8 a_cur[SB][TI], b_cur[SB][2], a_nxt[SB][TI], b_nxt[SB][2];
     fetch(0, a_cur, b_cur);
     for (int s0 = 0; s0 < steps; s0 += SB) {
         fetch(s0 + SB, a_nxt, b_nxt);
@@ -85,19 +84,22 @@ __global__ __launch_bounds__(256) void k_centroid_bf16(const __bf16* __restrict_
         for (int u = 0; u < SB; ++u) {
             if (s0 + u < steps) {                             // uniform
 #pragma unroll
-                for (int ta = 0; ta < 2; ++ta)
+                for (int ta = 0; ta < TI; ++ta)
 #pragma unroll
                     for (int tb = 0; tb < 2; ++tb)
                         acc[ta][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cur[u][ta], b_cur[u][tb], acc[ta][tb], 0, 0, 0);
             }
         }
 #pragma unroll
-        for (int u = 0; u < SB; ++u)
+        for (int u = 0; u < SB; ++u) {
 #pragma unroll
-            for (int t = 0; t < 2; ++t) { a_cur[u][t] = a_nxt[u][t]; b_cur[u][t] = b_nxt[u][t]; }
+            for (int t = 0; t < TI; ++t) a_cur[u][t] = a_nxt[u][t];
+#pragma unroll
+            for (int t = 0; t < 2; ++t) b_cur[u][t] = b_nxt[u][t];
+        }
     }
 #pragma unroll
-    for (int ta = 0; ta < 2; ++ta)
+    for (int ta = 0; ta < TI; ++ta)
 #pragma unroll
         for (int tb = 0; tb < 2; ++tb) {
             const int col = n0 + 32 * tb + i;
@@ -336,20 +338,99 @@ __global__ __launch_bounds__(256) void k_select_clusters_screen_wave(ScreenArgs 
     uint32_t key[KPL];
 #pragma unroll
     for (int i = 0; i < KPL; ++i) key[i] = 64 * i + lane < L ? float_key_asc(v[i]) : 0xFFFFFFFFu;
-    int need_unused;
-    const uint32_t gw = wave_wth_smallest_key<KPL>(key, L, w, hist[wv], need_unused);
-    const float s2 = key_to_float(gw) + 2.0f * eps;
-    const float tf2 = s2 + 1e-6f * (fabsf(s2) + eps);
-    // the list: clusters whose approximate value does not exceed tf2
+    auto widen = [&](float t) {                           // t + 2 eps, rounded up generously
+        const float s = t + 2.0f * eps;
+        return s + 1e-6f * (fabsf(s) + eps);
+    };
+    auto lds_sync = [&]() {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront"); __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    };
+    const unsigned long long below = (1ull << lane) - 1ull;
     int c2 = 0;
+    bool listed = false;
+    if (w <= 64) {
+        // The w-th smallest of the 64 per-lane minima bounds the w-th smallest value from above, so the values up
+        // to that bound + 2 eps contain the w smallest AND the whole list; the w-th smallest itself is found by
+        // counting inside this first list (a few more than w entries when the row is in no special order).
+        uint32_t mn = 0xFFFFFFFFu;
 #pragma unroll
-    for (int i = 0; i < KPL; ++i) {
-        const int l = 64 * i + lane;
-        const bool in = l < L && !(v[i] > tf2);
-        const unsigned long long mk = __ballot(in);
-        const int p = c2 + __popcll(mk & ((1ull << lane) - 1ull));
-        if (in && p < kScreenWaveCap) clist[p] = l;
-        c2 += __popcll(mk);
+        for (int i = 0; i < KPL; ++i) mn = min(mn, key[i]);
+        const unsigned long long mine = ((unsigned long long)mn << 32) | (unsigned)lane;
+        cand[lane] = mine;
+        lds_sync();
+        int rank = 0;
+        {
+            const ulonglong2* t2 = reinterpret_cast<const ulonglong2*>(cand);
+#pragma unroll 8
+            for (int u = 0; u < 32; ++u) {
+                const ulonglong2 t = t2[u];
+                rank += (t.x < mine ? 1 : 0) + (t.y < mine ? 1 : 0);
+            }
+        }
+        const int src = __ffsll((unsigned long long)__ballot(rank == w - 1)) - 1;     // exactly one lane
+        const float tf1 = widen(key_to_float((uint32_t)__shfl((int)mn, src, 64)));
+        lds_sync();
+        int c1 = 0;
+#pragma unroll
+        for (int i = 0; i < KPL; ++i) {
+            const int l = 64 * i + lane;
+            const bool in = l < L && !(v[i] > tf1);
+            const unsigned long long mk = __ballot(in);
+            const int p = c1 + __popcll(mk & below);
+            if (in && p < kScreenWaveCap) cand[p] = ((unsigned long long)key[i] << 32) | (unsigned)l;
+            c1 += __popcll(mk);
+        }
+        if (c1 <= kScreenWaveCap) {                        // uniform
+            if (lane < 2) cand[c1 + lane] = ~0ull;
+            lds_sync();
+            const ulonglong2* cc = reinterpret_cast<const ulonglong2*>(cand);
+            const int c_pairs = (c1 + 1) >> 1;
+            uint32_t gw_mine = 0u;
+            bool found = false;
+            unsigned long long mine_e[kScreenWaveCap / 64];
+#pragma unroll
+            for (int j = 0; j < kScreenWaveCap / 64; ++j) {
+                const int e = lane + 64 * j;
+                mine_e[j] = e < c1 ? cand[e] : ~0ull;
+                int r = 0;
+                if (e < c1) {
+                    for (int u = 0; u < c_pairs; ++u) {
+                        const ulonglong2 t = cc[u];
+                        r += (t.x < mine_e[j] ? 1 : 0) + (t.y < mine_e[j] ? 1 : 0);
+                    }
+                    if (r == w - 1) { found = true; gw_mine = (uint32_t)(mine_e[j] >> 32); }
+                }
+            }
+            const int src2 = __ffsll((unsigned long long)__ballot(found)) - 1;
+            const float tf2 = widen(key_to_float((uint32_t)__shfl((int)gw_mine, src2, 64)));
+#pragma unroll
+            for (int j = 0; j < kScreenWaveCap / 64; ++j) {
+                const int e = lane + 64 * j;
+                const bool in = e < c1 && !(key_to_float((uint32_t)(mine_e[j] >> 32)) > tf2);
+                const unsigned long long mk = __ballot(in);
+                if (in) clist[c2 + __popcll(mk & below)] = (int)(unsigned)(mine_e[j] & 0xFFFFFFFFull);
+                c2 += __popcll(mk);
+            }
+            listed = true;
+        }
+    }
+    if (!listed) {
+        // radix select of the w-th smallest approximate value, then the list
+        int need_unused;
+        lds_sync();
+        const uint32_t gw = wave_wth_smallest_key<KPL>(key, L, w, hist[wv], need_unused);
+        const float tf2 = widen(key_to_float(gw));
+        c2 = 0;
+#pragma unroll
+        for (int i = 0; i < KPL; ++i) {
+            const int l = 64 * i + lane;
+            const bool in = l < L && !(v[i] > tf2);
+            const unsigned long long mk = __ballot(in);
+            const int p = c2 + __popcll(mk & below);
+            if (in && p < kScreenWaveCap) clist[p] = l;
+            c2 += __popcll(mk);
+        }
     }
     const bool all_exact = c2 > kScreenWaveCap;            // uniform over the wavefront
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront"); __builtin_amdgcn_wave_barrier();

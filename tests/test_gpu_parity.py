@@ -294,3 +294,59 @@ def test_full_size_benchmark_configuration_sampled_parity(B):
     np.testing.assert_array_equal(np.sort(gst["cand_rows"][sample].astype(np.int64), axis=1), np.sort(ost["cand_rows"], axis=1),
                                   err_msg="candidate sets")
     assert_topk_equal(g_ids[sample], g_d[sample], o_ids, o_d, "embed-ip full size")
+
+
+@pytest.mark.parametrize("L,w,metric,case", [
+    (700, 32, 0, "near_ties"), (700, 32, 1, "near_ties"), (700, 32, 2, "plateau"), (512, 100, 0, "plain"),
+    (512, 100, 1, "near_ties"), (900, 40, 0, "outlier"), (900, 40, 1, "outlier"), (64, 64, 0, "plain"),
+    (3000, 48, 0, "near_ties"), (3000, 48, 1, "outlier"), (12000, 64, 0, "near_ties"), (12000, 200, 2, "plain"),
+])
+def test_routing_by_screening_adversarial(B, L, w, metric, case):
+    """Routing finds the w nearest centroids from bfloat16 scores plus an error bound and evaluates only a short
+    list exactly.  These inputs stress the list: hundreds of centroids within 1e-6 of each other around the
+    w-th place (near_ties), several hundred identical ones (plateau: the list overflows and every cluster is
+    evaluated exactly), one centroid of huge norm (outlier: the bound becomes useless), w above the lane count.
+    The selected clusters must equal the oracle's, in order, whatever route is taken."""
+    rng = np.random.default_rng(1000 * L + w + metric)
+    d, r = 32, 8
+    sizes = rng.integers(1, 5, size=L)
+    n = int(sizes.sum())
+    corpus = rng.normal(size=(n, d)).astype(np.float32)
+    cent = rng.normal(size=(L, d)).astype(np.float32)
+    cent /= np.linalg.norm(cent, axis=1, keepdims=True)
+    q = rng.normal(size=(40, d)).astype(np.float32)
+    q /= np.linalg.norm(q, axis=1, keepdims=True)
+    if case == "near_ties":
+        # 300 centroids that differ from one direction by ~1e-6: their scores crowd around the w-th place
+        base = q[0] / np.linalg.norm(q[0])
+        idx = rng.choice(L, size=min(300, L // 2), replace=False)
+        cent[idx] = (base[None, :] * (1.0 + 1e-6 * rng.normal(size=(idx.size, 1))) + 1e-6 * rng.normal(size=(idx.size, d))).astype(np.float32)
+        q[1:20] = (base[None, :] + 0.05 * rng.normal(size=(19, d))).astype(np.float32)
+    elif case == "plateau":
+        idx = rng.choice(L, size=400, replace=False)
+        cent[idx] = q[0]
+        q[1:20] = (q[0][None, :] + 0.01 * rng.normal(size=(19, d))).astype(np.float32)
+    elif case == "outlier":
+        cent[L // 3] *= 3.0e4
+        cent[L // 3 + 1] *= -2.0e4
+    if metric == 2:
+        corpus /= np.linalg.norm(corpus, axis=1, keepdims=True)
+    off = np.zeros(L + 1, np.int64)
+    np.cumsum(sizes, out=off[1:])
+    ix = dict(metric=metric, n=n, d=d, dp=d, r=r, L=L, centroids=cent, P=None,
+              A=rng.integers(-127, 128, size=(L, r, d)).astype(np.int8), B=rng.integers(-127, 128, size=(n, r)).astype(np.int8),
+              scale_A=rng.uniform(0.01, 0.1, L).astype(np.float32), scale_B=rng.uniform(0.01, 0.1, L).astype(np.float32),
+              cluster_offsets=off, corpus=corpus, ids=None)
+    gix = B.Index(**ix)
+    oix = O.OracleIndex(ix)
+    m = 50
+    o_ids, o_d, ost = O.search(oix, q, 10, w, m, stages=True)
+    g_ids, g_d, gst = gix.search_stages(q, 10, w, m)
+    np.testing.assert_array_equal(gst["sel"], ost["sel"], err_msg=f"selected clusters ({case})")
+    np.testing.assert_array_equal(gst["z"], ost["z"])
+    assert_topk_equal(g_ids, g_d, o_ids, o_d, f"L={L} w={w} metric={metric} {case}")
+    # the plain route (all L dissimilarities in double) agrees as well
+    gix.set_exact_selection(True)
+    e_ids, e_d, est = gix.search_stages(q, 10, w, m)
+    np.testing.assert_array_equal(est["sel"], ost["sel"], err_msg=f"selected clusters, plain route ({case})")
+    gix.close()

@@ -1,0 +1,64 @@
+"""The error bound behind routing by screening (CPU check of the mathematics; the GPU kernels rely on it).
+
+Approximate centroid scores come from operands rounded to bfloat16 with float accumulation; the library keeps
+every cluster whose approximate value is within 2 eps of the w-th smallest, eps = 0.0042 |q| |mu| (doubled plus
+a float-rounding term for the Euclidean form).  Here the inequality |approximate - exact| <= eps is checked on
+seeded inputs of several scales, including ones built to be bad for bfloat16 (all mantissas just below a
+rounding boundary), with bfloat16 emulated by torch on the CPU.
+"""
+import numpy as np
+import torch
+
+K_SCREEN_REL = 0.0042      # must equal kScreenRel in csrc/screen.hpp
+
+
+def _bf16(x):
+    return torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy()
+
+
+def test_constant_matches_the_kernel_source():
+    import pathlib, re
+    src = (pathlib.Path(__file__).resolve().parents[1] / "paper_2410_18926_amd" / "csrc" / "screen.hpp").read_text()
+    assert float(re.search(r"kScreenRel\s*=\s*([0-9.]+)f", src).group(1)) == K_SCREEN_REL
+
+
+def test_bf16_inner_product_error_is_within_the_bound():
+    rng = np.random.default_rng(5)
+    for dp in (16, 64, 256, 1024):
+        for scale_q, scale_c in ((1.0, 1.0), (1e-3, 40.0), (300.0, 1e-2)):
+            q = (scale_q * rng.normal(size=(64, dp))).astype(np.float32)
+            c = (scale_c * rng.normal(size=(200, dp))).astype(np.float32)
+            # worst case for round-to-nearest: mantissas just below the midpoint between two bfloat16 values
+            bad = (np.float32(1.0) + np.float32(2.0 ** -9) * np.float32(0.999)) * np.sign(rng.normal(size=(8, dp))).astype(np.float32)
+            q[:8] = scale_q * bad
+            c[:8] = scale_c * np.abs(bad)
+            exact = q.astype(np.float64) @ c.astype(np.float64).T
+            approx = (_bf16(q) @ _bf16(c).T).astype(np.float64)           # float accumulation
+            bound = K_SCREEN_REL * np.linalg.norm(q.astype(np.float64), axis=1)[:, None] * np.linalg.norm(c.astype(np.float64), axis=1)[None, :]
+            assert np.all(np.abs(approx - exact) <= bound), (dp, scale_q, scale_c, float(np.max(np.abs(approx - exact) / bound)))
+            # Euclidean form: |mu|^2 - 2 ip with the norm rounded to float
+            nrm = (c.astype(np.float64) ** 2).sum(1)
+            g = nrm[None, :] - 2.0 * exact
+            g_hat = (nrm.astype(np.float32)[None, :] - np.float32(2.0) * approx.astype(np.float32)).astype(np.float64)
+            qn, mu_max, nrm_max = np.linalg.norm(q.astype(np.float64), axis=1), np.sqrt(nrm.max()), nrm.max()
+            eps = 2.0 * K_SCREEN_REL * qn * mu_max + 2.4e-7 * (nrm_max + 2.0 * qn * mu_max)
+            assert np.all(np.abs(g_hat - g) <= eps[:, None])
+
+
+def test_the_list_contains_the_exact_w_best():
+    """The selection rule itself, in numpy: everything within 2 eps of the w-th smallest approximate value."""
+    rng = np.random.default_rng(6)
+    dp, L, w = 64, 2000, 48
+    c = rng.normal(size=(L, dp)).astype(np.float32)
+    c /= np.linalg.norm(c, axis=1, keepdims=True)
+    c[100:400] = c[100] * (1.0 + 1e-6 * rng.normal(size=(300, 1))).astype(np.float32)     # a crowd of near-equal scores
+    q = (c[100][None, :] + 0.05 * rng.normal(size=(32, dp))).astype(np.float32)
+    exact = (-(q.astype(np.float64) @ c.astype(np.float64).T)).astype(np.float32)
+    approx = -(_bf16(q) @ _bf16(c).T)
+    eps = K_SCREEN_REL * np.linalg.norm(q, axis=1) * np.linalg.norm(c, axis=1).max() * 1.00001
+    for i in range(q.shape[0]):
+        best = np.argsort(exact[i], kind="stable")[:w]
+        gw = np.sort(approx[i])[w - 1]
+        listed = approx[i] <= gw + 2.0 * eps[i]
+        assert listed[best].all()
+        assert listed.sum() >= w
