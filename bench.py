@@ -18,6 +18,7 @@ import time
 import numpy as np
 
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
+PEAK_BF16_MFMA_TFLOPS = 2500.0 # dense bf16 MFMA
 PEAK_FP64_MFMA_TFLOPS = 78.6
 PEAK_INT8_MFMA_TOPS = 5000.0
 PEAK_VALU_LANE_TOPS = 256 * 64 * 2.4e9 / 1e12   # 256 CUs x 64 lanes x 2.4 GHz = 39.3 T lane-ops/s
@@ -46,6 +47,8 @@ def kernel_models(wl, nq, touched_rows, npairs):
     return {
         "project_f64": ("mfma", 2.0 * nq * d * dp / 1e12, PEAK_FP64_MFMA_TFLOPS, "TFLOP/s"),
         "centroid_dissim_f64": ("mfma", 2.0 * nq * dp * L / 1e12, PEAK_FP64_MFMA_TFLOPS, "TFLOP/s"),
+        # approximate scores on the bf16 matrix cores; in practice bound by writing the nq x L float matrix
+        "centroid_screen_bf16": ("mfma", 2.0 * nq * dp * L / 1e12, PEAK_BF16_MFMA_TFLOPS, "TFLOP/s"),
         "quantize_rows": ("hbm", nq * dp * 5 / 1e9, PEAK_HBM_GBS, "GB/s"),
         "select_clusters": ("hbm", nq * L * 4 / 1e9, PEAK_HBM_GBS, "GB/s"),
         "scatter_pairs": ("hbm", npairs * 12 / 1e9, PEAK_HBM_GBS, "GB/s"),

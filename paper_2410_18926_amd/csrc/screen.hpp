@@ -242,23 +242,61 @@ __global__ __launch_bounds__(256) void k_select_clusters_screen(ScreenArgs a) {
     const int n_exact = all_exact ? L : c2;
     const int d4 = dp >> 2;                               // d' is a multiple of 16
     __syncthreads();
-    for (int e = grp; e < n_exact; e += 16) {
-        const int l = all_exact ? e : clist[e];
-        const float4* mu = reinterpret_cast<const float4*>(a.centroids + (size_t)l * dp);
-        const float4* q4 = reinterpret_cast<const float4*>(qs);
-        double acc = 0.0;
-        for (int i4 = l16; i4 < d4; i4 += 16) {
-            const float4 m = mu[i4], x = q4[i4];
-            acc += (double)x.x * (double)m.x;
-            acc += (double)x.y * (double)m.y;
-            acc += (double)x.z * (double)m.z;
-            acc += (double)x.w * (double)m.w;
+    const float4* q4 = reinterpret_cast<const float4*>(qs);
+    if (d4 <= 64) {
+        // d' <= 256: a lane holds its share of a centroid in 4 float4; two clusters per group are in flight
+        for (int e0 = 0; e0 < n_exact; e0 += 32) {
+            int le[2];
+            float4 m[2][4];
+#pragma unroll
+            for (int r = 0; r < 2; ++r) {
+                const int e = min(e0 + 16 * r + grp, n_exact - 1);
+                le[r] = all_exact ? e : clist[e];
+                const float4* mu = reinterpret_cast<const float4*>(a.centroids + (size_t)le[r] * dp);
+#pragma unroll
+                for (int u = 0; u < 4; ++u) m[r][u] = mu[min(l16 + 16 * u, d4 - 1)];
+            }
+#pragma unroll
+            for (int r = 0; r < 2; ++r) {
+                double acc = 0.0;
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    if (l16 + 16 * u < d4) {
+                        const float4 x = q4[l16 + 16 * u];
+                        acc += (double)x.x * (double)m[r][u].x;
+                        acc += (double)x.y * (double)m[r][u].y;
+                        acc += (double)x.z * (double)m[r][u].z;
+                        acc += (double)x.w * (double)m[r][u].w;
+                    }
+                }
+                acc = row16_sum_f64_last(acc);
+                const int e = e0 + 16 * r + grp;
+                if (l16 == 15 && e < n_exact) {
+                    const float g = l2 ? (float)(a.cent_sqnorm[le[r]] - 2.0 * acc) : (float)(-acc);
+                    if (all_exact) row[le[r]] = g;
+                    else cand[e] = ((unsigned long long)float_key_asc(g) << 32) | (unsigned)le[r];
+                }
+            }
         }
-        acc = row16_sum_f64_last(acc);
-        if (l16 == 15) {
-            const float g = l2 ? (float)(a.cent_sqnorm[l] - 2.0 * acc) : (float)(-acc);
-            if (all_exact) row[l] = g;
-            else cand[e] = ((unsigned long long)float_key_asc(g) << 32) | (unsigned)l;
+    } else {
+        for (int e0 = 0; e0 < n_exact; e0 += 16) {
+            const int e = min(e0 + grp, n_exact - 1);
+            const int l = all_exact ? e : clist[e];
+            const float4* mu = reinterpret_cast<const float4*>(a.centroids + (size_t)l * dp);
+            double acc = 0.0;
+            for (int i4 = l16; i4 < d4; i4 += 16) {
+                const float4 m = mu[i4], x = q4[i4];
+                acc += (double)x.x * (double)m.x;
+                acc += (double)x.y * (double)m.y;
+                acc += (double)x.z * (double)m.z;
+                acc += (double)x.w * (double)m.w;
+            }
+            acc = row16_sum_f64_last(acc);
+            if (l16 == 15 && e0 + grp < n_exact) {
+                const float g = l2 ? (float)(a.cent_sqnorm[l] - 2.0 * acc) : (float)(-acc);
+                if (all_exact) row[l] = g;
+                else cand[e] = ((unsigned long long)float_key_asc(g) << 32) | (unsigned)l;
+            }
         }
     }
     __syncthreads();
