@@ -350,3 +350,71 @@ def test_routing_by_screening_adversarial(B, L, w, metric, case):
     e_ids, e_d, est = gix.search_stages(q, 10, w, m)
     np.testing.assert_array_equal(est["sel"], ost["sel"], err_msg=f"selected clusters, plain route ({case})")
     gix.close()
+
+
+def _random_index(rng, n, d, L, r, metric, dp=None, with_ids=True):
+    dp = dp or d
+    cuts = np.sort(rng.choice(np.arange(1, n), size=L - 1, replace=False))
+    off = np.concatenate([[0], cuts, [n]]).astype(np.int64)
+    corpus = rng.normal(size=(n, d)).astype(np.float32)
+    if metric == 2:
+        corpus /= np.linalg.norm(corpus, axis=1, keepdims=True)
+    P = None if dp == d else np.linalg.qr(rng.normal(size=(d, d)))[0][:, :dp].astype(np.float32)
+    return dict(metric=metric, n=n, d=d, dp=dp, r=r, L=L, centroids=rng.normal(size=(L, dp)).astype(np.float32), P=P,
+                A=rng.integers(-127, 128, size=(L, r, dp)).astype(np.int8), B=rng.integers(-127, 128, size=(n, r)).astype(np.int8),
+                scale_A=rng.uniform(0.01, 0.1, L).astype(np.float32), scale_B=rng.uniform(0.01, 0.1, L).astype(np.float32),
+                cluster_offsets=off, corpus=corpus, ids=rng.permutation(n).astype(np.int64) if with_ids else None)
+
+
+@pytest.mark.parametrize("metric", [0, 1, 2])
+def test_parameter_extremes(B, metric):
+    """Parameters at and across the internal switch points: k at 64 / 65 (wavefront vs block top-k), m at 256 / 300 /
+    512 / 513 / 1025 / 4096 (top-k register budget, grouped vs one-query re-rank, the two capacities of the
+    per-query walk), w = 256 of 300 clusters."""
+    rng = np.random.default_rng(70 + metric)
+    ix = _random_index(rng, n=6000, d=48, L=300, r=16, metric=metric, dp=32)
+    q = rng.normal(size=(37, 48)).astype(np.float32)
+    gix = B.Index(**ix)
+    oix = O.OracleIndex(ix)
+    for (k, w, m) in [(64, 20, 256), (65, 20, 300), (100, 30, 512), (10, 30, 513), (200, 40, 1025), (10, 256, 4096), (1, 256, 200)]:
+        o_ids, o_d, ost = O.search(oix, q, k, w, m, stages=True)
+        g_ids, g_d, gst = gix.search_stages(q, k, w, m)
+        np.testing.assert_array_equal(gst["sel"], ost["sel"], err_msg=f"k={k} w={w} m={m}")
+        np.testing.assert_array_equal(np.sort(gst["cand_rows"].astype(np.int64), axis=1), np.sort(ost["cand_rows"], axis=1),
+                                      err_msg=f"candidate sets k={k} w={w} m={m}")
+        assert_topk_equal(g_ids, g_d, o_ids, o_d, f"metric={metric} k={k} w={w} m={m}")
+    gix.close()
+
+
+@pytest.mark.parametrize("d", [1028, 1100, 2000])
+def test_long_rows(B, d):
+    """Rows longer than the register-resident re-rank handles (d > 1024: streamed rows) and longer than a group of
+    queries fits in LDS (d = 2000: one query per block)."""
+    rng = np.random.default_rng(d)
+    ix = _random_index(rng, n=1500, d=d, L=12, r=8, metric=1, dp=64)
+    q = rng.normal(size=(21, d)).astype(np.float32)
+    gix = B.Index(**ix)
+    oix = O.OracleIndex(ix)
+    o_ids, o_d = O.search(oix, q, 10, 5, 120)
+    g_ids, g_d = gix.search(q, 10, 5, 120)
+    assert_topk_equal(g_ids, g_d, o_ids, o_d, f"d={d}")
+    gix.close()
+
+
+def test_batch_larger_than_one_launch(B):
+    """A batch of 70 000 queries runs as three launches of at most 32 768; every query must come out as if alone."""
+    rng = np.random.default_rng(33)
+    ix = _random_index(rng, n=3000, d=16, L=40, r=8, metric=0, with_ids=False)
+    q = rng.normal(size=(70000, 16)).astype(np.float32)
+    gix = B.Index(**ix)
+    oix = O.OracleIndex(ix)
+    g_ids, g_d = gix.search(torch.from_numpy(q).cuda(), 5, 4, 30)
+    g_ids, g_d = g_ids.cpu().numpy(), g_d.cpu().numpy()
+    pick = np.concatenate([np.arange(0, 64), np.arange(32768 - 32, 32768 + 32), np.arange(65536 - 32, 65536 + 32), np.arange(70000 - 64, 70000)])
+    o_ids, o_d = O.search(oix, q[pick], 5, 4, 30)
+    assert_topk_equal(g_ids[pick], g_d[pick], o_ids, o_d, "chunked batch")
+    # and the whole batch equals the same queries searched in small pieces
+    h_ids, h_d = gix.search(torch.from_numpy(q[40000:41000]).cuda(), 5, 4, 30)
+    np.testing.assert_array_equal(h_ids.cpu().numpy(), g_ids[40000:41000])
+    np.testing.assert_array_equal(h_d.cpu().numpy(), g_d[40000:41000])
+    gix.close()
