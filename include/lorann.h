@@ -106,8 +106,10 @@ const char *lorann_last_error(void);
 int lorann_set_stream(lorann_index *ix, void *hip_stream);
 
 /* Candidate selection normally runs batched by cluster (each cluster's codes are read once per batch) and
- * hands the rare queries it cannot finish to an exact per-query kernel.  on != 0 makes every query take the
- * per-query kernel (same results, much slower); used to verify one path against the other. */
+ * hands the rare queries it cannot finish to an exact per-query kernel; cluster selection (Sec. 2.2) normally
+ * evaluates approximate centroid scores for all clusters and exact ones for a provably sufficient short list.
+ * on != 0 makes every query take the per-query kernel, evaluates every centroid score exactly and re-ranks one
+ * query at a time (same results, much slower); used to verify one path against the other. */
 int lorann_set_exact_selection(lorann_index *ix, int32_t on);
 
 /*
