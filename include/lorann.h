@@ -77,6 +77,18 @@ int lorann_load_index(lorann_index **out, int32_t metric, int64_t n, int32_t d, 
                       const float *corpus, const int64_t *ids);
 
 /*
+ * lorann_load_index_file - the same from a serialized index (the file the CPU reference implementation reads
+ * too; the harness writes it).  Little-endian; every array starts at a multiple of 64 bytes:
+ *   offset 0  char[8] "LRNIDX01";  8 int32 metric;  12 int32 d;  16 int32 dp;  20 int32 r;  24 int32 L;
+ *   28 int32 flags (bit 0: P present, bit 1: ids present);  32 int64 n;  zero padding up to 64;
+ *   then cluster_offsets, ids (if present), centroids, P (if present), A, B, scale_A, scale_B, corpus, with
+ *   the element types and layouts of lorann_load_index.
+ * `path` is a host string.  Errors: LORANN_E_INVAL for a missing, foreign or truncated file, otherwise those
+ * of lorann_load_index.
+ */
+int lorann_load_index_file(lorann_index **out, const char *path);
+
+/*
  * lorann_search - the query phase (Sec. 2.2 template with the score computation of Sec. 3.2-3.3, 4.1):
  * project each query, route it to its w nearest centroids, estimate the scores of all points of those
  * clusters with the 8-bit reduced-rank model, keep the m best (the paper's t), re-rank them with the exact

@@ -25,6 +25,7 @@
  */
 #include <math.h>
 #include <stdint.h>
+#include <stdio.h>
 #include <stdlib.h>
 #include <string.h>
 
@@ -330,4 +331,74 @@ void oracle_rrr_predict_f64(const double *x, int32_t s, int32_t r, const double 
         y[c] = acc;
     }
     free(t);
+}
+
+
+/* ------------------------------------------------------------------------------------------------------------
+ * The serialized index file (written by the harness, read here and - by code of its own - by the library).
+ * Little-endian.  Header of 64 bytes: "LRNIDX01", int32 metric, d, dp, r, L, flags (bit 0: P present, bit 1:
+ * ids present), int64 n at offset 32.  Then, each at the next multiple of 64 bytes: cluster_offsets
+ * int64[L+1], ids int64[n] (if present), centroids float[L][dp], P float[d][dp] (if present), A int8[L][r][dp],
+ * B int8[n][r], scale_A float[L], scale_B float[L], corpus float[n][d].
+ * oracle_load_file returns a heap-allocated index that owns its arrays (NULL on any error);
+ * oracle_free_loaded releases it.
+ * ------------------------------------------------------------------------------------------------------------ */
+static void *read_array(FILE *f, long long *pos, size_t bytes)
+{
+    long long at = (*pos + 63) / 64 * 64;
+    void *buf = malloc(bytes ? bytes : 1);
+    if (!buf) return NULL;
+    if (fseeko(f, (off_t)at, SEEK_SET) != 0 || fread(buf, 1, bytes, f) != bytes) { free(buf); return NULL; }
+    *pos = at + (long long)bytes;
+    return buf;
+}
+
+void oracle_free_loaded(oracle_index *ix)
+{
+    if (!ix) return;
+    free((void *)ix->centroids); free((void *)ix->P); free((void *)ix->A); free((void *)ix->B);
+    free((void *)ix->scale_A); free((void *)ix->scale_B); free((void *)ix->offsets); free((void *)ix->corpus);
+    free((void *)ix->ids); free((void *)ix->sqnorms);
+    free(ix);
+}
+
+oracle_index *oracle_load_file(const char *path)
+{
+    FILE *f = fopen(path, "rb");
+    if (!f) return NULL;
+    unsigned char head[64];
+    oracle_index *ix = NULL;
+    if (fread(head, 1, 64, f) == 64 && memcmp(head, "LRNIDX01", 8) == 0) {
+        int32_t hv[6];
+        int64_t n;
+        memcpy(hv, head + 8, sizeof hv);
+        memcpy(&n, head + 32, sizeof n);
+        ix = (oracle_index *)calloc(1, sizeof *ix);
+        if (ix && n >= 1 && hv[1] >= 1 && hv[2] >= 1 && hv[3] >= 1 && hv[4] >= 1) {
+            const int flags = hv[5];
+            long long pos = 64;
+            int ok = 1;
+            ix->metric = hv[0]; ix->d = hv[1]; ix->dp = hv[2]; ix->r = hv[3]; ix->L = hv[4]; ix->n = n;
+            ok = ok && (ix->offsets = (const int64_t *)read_array(f, &pos, ((size_t)ix->L + 1) * 8)) != NULL;
+            if (flags & 2) ok = ok && (ix->ids = (const int64_t *)read_array(f, &pos, (size_t)n * 8)) != NULL;
+            ok = ok && (ix->centroids = (const float *)read_array(f, &pos, (size_t)ix->L * ix->dp * 4)) != NULL;
+            if (flags & 1) ok = ok && (ix->P = (const float *)read_array(f, &pos, (size_t)ix->d * ix->dp * 4)) != NULL;
+            ok = ok && (ix->A = (const int8_t *)read_array(f, &pos, (size_t)ix->L * ix->r * ix->dp)) != NULL;
+            ok = ok && (ix->B = (const int8_t *)read_array(f, &pos, (size_t)n * ix->r)) != NULL;
+            ok = ok && (ix->scale_A = (const float *)read_array(f, &pos, (size_t)ix->L * 4)) != NULL;
+            ok = ok && (ix->scale_B = (const float *)read_array(f, &pos, (size_t)ix->L * 4)) != NULL;
+            ok = ok && (ix->corpus = (const float *)read_array(f, &pos, (size_t)n * ix->d * 4)) != NULL;
+            if (ok && !(flags & 1) && ix->dp != ix->d) ok = 0;          /* no projection means identity */
+            if (ok && (ix->offsets[0] != 0 || ix->offsets[ix->L] != n)) ok = 0;
+            if (ok && ix->metric == ORACLE_L2) {
+                float *sq = (float *)malloc((size_t)n * sizeof(float));
+                if (sq) { oracle_corpus_sqnorms(ix->corpus, n, ix->d, sq); ix->sqnorms = sq; } else ok = 0;
+            }
+            if (!ok) { oracle_free_loaded(ix); ix = NULL; }
+        } else {
+            free(ix); ix = NULL;
+        }
+    }
+    fclose(f);
+    return ix;
 }

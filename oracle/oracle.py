@@ -39,6 +39,10 @@ def lib():
         _lib.oracle_score.restype = C.c_float
         _lib.oracle_score.argtypes = [C.c_int32, C.c_float, C.c_int32, C.c_float]
         _lib.oracle_exact_dissim.restype = C.c_float
+        _lib.oracle_load_file.restype = C.POINTER(_Index)
+        _lib.oracle_load_file.argtypes = [C.c_char_p]
+        _lib.oracle_free_loaded.restype = None
+        _lib.oracle_free_loaded.argtypes = [C.POINTER(_Index)]
     return _lib
 
 
@@ -75,6 +79,46 @@ class OracleIndex:
         self.c = _Index(self.metric, self.n, self.d, self.dp, self.r, self.L, _p(self.centroids), _p(self.P),
                         _p(self.A), _p(self.B), _p(self.scale_A), _p(self.scale_B), _p(self.offsets),
                         _p(self.corpus), _p(self.ids), _p(self.sqnorms))
+
+
+def _from_file(path) -> "OracleIndex":
+    """The oracle's own reader of the serialized index file (the C routine parses it; numpy only views its arrays)."""
+    p = lib().oracle_load_file(str(path).encode())
+    if not p:
+        raise ValueError(f"oracle: cannot load index file {path}")
+    c = p.contents
+    self = OracleIndex.__new__(OracleIndex)
+    self._loaded = p
+    self.metric, self.n, self.d, self.dp, self.r, self.L = c.metric, c.n, c.d, c.dp, c.r, c.L
+
+    def view(ptr, ctype, shape):
+        if not ptr:
+            return None
+        return np.ctypeslib.as_array(C.cast(ptr, C.POINTER(ctype)), shape=shape)
+
+    self.centroids = view(c.centroids, C.c_float, (c.L, c.dp))
+    self.P = view(c.P, C.c_float, (c.d, c.dp))
+    self.A = view(c.A, C.c_int8, (c.L, c.r, c.dp))
+    self.B = view(c.B, C.c_int8, (c.n, c.r))
+    self.scale_A = view(c.scale_A, C.c_float, (c.L,))
+    self.scale_B = view(c.scale_B, C.c_float, (c.L,))
+    self.offsets = view(c.offsets, C.c_int64, (c.L + 1,))
+    self.corpus = view(c.corpus, C.c_float, (c.n, c.d))
+    self.ids = view(c.ids, C.c_int64, (c.n,))
+    self.sqnorms = view(c.sqnorms, C.c_float, (c.n,))
+    self.c = c
+    return self
+
+
+def _release(self):
+    p = getattr(self, "_loaded", None)
+    if p:
+        self._loaded = None
+        lib().oracle_free_loaded(p)
+
+
+OracleIndex.from_file = staticmethod(_from_file)
+OracleIndex.__del__ = _release
 
 
 def default_threads() -> int:

@@ -21,7 +21,7 @@ LIB_PATH = pathlib.Path(__file__).resolve().parent / "liblorann.so"
 LORANN_IP, LORANN_L2, LORANN_COS = 0, 1, 2
 LORANN_OK, LORANN_E_INVAL, LORANN_E_NOMEM, LORANN_E_DEVICE, LORANN_E_UNSUPPORTED = 0, -1, -2, -3, -4
 
-EXPORTS = ["lorann_load_index", "lorann_search", "lorann_free_index", "lorann_last_error", "lorann_set_stream",
+EXPORTS = ["lorann_load_index", "lorann_load_index_file", "lorann_search", "lorann_free_index", "lorann_last_error", "lorann_set_stream",
            "lorann_search_stages", "lorann_profile_enable", "lorann_profile_get", "lorann_set_exact_selection",
            "lorann_profile_fallback_queries"]
 
@@ -57,6 +57,8 @@ def lib() -> C.CDLL:
         L.lorann_search.argtypes = [vp, vp, i64, i32, i32, i32, vp, vp]
         L.lorann_search_stages.restype = C.c_int
         L.lorann_search_stages.argtypes = [vp, vp, i64, i32, i32, i32, vp, vp, C.POINTER(_Stages)]
+        L.lorann_load_index_file.restype = C.c_int
+        L.lorann_load_index_file.argtypes = [C.POINTER(C.c_void_p), C.c_char_p]
         L.lorann_free_index.restype = None
         L.lorann_free_index.argtypes = [vp]
         L.lorann_last_error.restype = C.c_char_p
@@ -119,6 +121,17 @@ class Index:
                                              ("metric", "n", "d", "dp", "r", "L", "centroids", "P", "A", "B", "scale_A",
                                               "scale_B", "cluster_offsets", "corpus", "ids")}
         return cls(**d)
+
+    @classmethod
+    def from_file(cls, path) -> "Index":
+        """lorann_load_index_file: load a serialized index (see synth.index_file for the writer)."""
+        self = cls.__new__(cls)
+        self._h = C.c_void_p()
+        _check(lib().lorann_load_index_file(C.byref(self._h), str(path).encode()))
+        from .synth.index_file import read_header
+        h = read_header(path)
+        self.metric, self.n, self.d, self.dp, self.r, self.L = (int(h[k]) for k in ("metric", "n", "d", "dp", "r", "L"))
+        return self
 
     def close(self):
         if getattr(self, "_h", None) is not None and self._h.value:

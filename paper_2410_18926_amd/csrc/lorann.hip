@@ -673,6 +673,52 @@ int lorann_load_index(lorann_index** out, int32_t metric, int64_t n, int32_t d, 
     return LORANN_OK;
 }
 
+// The serialized index: a 64-byte header ("LRNIDX01", metric, d, d', r, L, flags, n) and the arrays of
+// lorann_load_index, each at a multiple of 64 bytes.  The file is read into host memory and handed to
+// lorann_load_index, which validates it like any other caller's arrays.
+int lorann_load_index_file(lorann_index** out, const char* path) {
+    if (!out || !path) return fail(LORANN_E_INVAL, "lorann_load_index_file: NULL argument");
+    FILE* f = fopen(path, "rb");
+    if (!f) return fail(LORANN_E_INVAL, "cannot open index file '%s'", path);
+    struct Closer { FILE* f; ~Closer() { fclose(f); } } closer{f};
+    unsigned char head[64];
+    if (fread(head, 1, sizeof head, f) != sizeof head || memcmp(head, "LRNIDX01", 8) != 0)
+        return fail(LORANN_E_INVAL, "'%s' is not a LRNIDX01 index file", path);
+    int32_t hv[6];
+    int64_t n;
+    memcpy(hv, head + 8, sizeof hv);
+    memcpy(&n, head + 32, sizeof n);
+    const int32_t metric = hv[0], d = hv[1], dp = hv[2], r = hv[3], L = hv[4], flags = hv[5];
+    if (n < 1 || d < 1 || dp < 1 || r < 1 || L < 1 || n >= (int64_t(1) << 31) || (flags & ~3))
+        return fail(LORANN_E_INVAL, "index file '%s': bad header", path);
+    int64_t pos = 64;
+    auto read_section = [&](std::vector<unsigned char>& buf, size_t bytes) -> bool {
+        const int64_t at = (pos + 63) / 64 * 64;
+        if (fseeko(f, (off_t)at, SEEK_SET) != 0) return false;
+        try { buf.resize(bytes); } catch (...) { return false; }
+        size_t got = 0;
+        while (got < bytes) {
+            const size_t k = fread(buf.data() + got, 1, std::min<size_t>(bytes - got, (size_t)1 << 28), f);
+            if (k == 0) return false;
+            got += k;
+        }
+        pos = at + (int64_t)bytes;
+        return true;
+    };
+    std::vector<unsigned char> off, ids, cent, P, A, B, sA, sB, corpus;
+    const bool ok = read_section(off, ((size_t)L + 1) * 8) && (!(flags & 2) || read_section(ids, (size_t)n * 8)) &&
+                    read_section(cent, (size_t)L * dp * 4) && (!(flags & 1) || read_section(P, (size_t)d * dp * 4)) &&
+                    read_section(A, (size_t)L * r * dp) && read_section(B, (size_t)n * r) && read_section(sA, (size_t)L * 4) &&
+                    read_section(sB, (size_t)L * 4) && read_section(corpus, (size_t)n * d * 4);
+    if (!ok) return fail(LORANN_E_INVAL, "index file '%s' is truncated (or host memory ran out reading it)", path);
+    return lorann_load_index(out, metric, n, d, dp, r, L, reinterpret_cast<const float*>(cent.data()),
+                             (flags & 1) ? reinterpret_cast<const float*>(P.data()) : nullptr,
+                             reinterpret_cast<const int8_t*>(A.data()), reinterpret_cast<const int8_t*>(B.data()),
+                             reinterpret_cast<const float*>(sA.data()), reinterpret_cast<const float*>(sB.data()),
+                             reinterpret_cast<const int64_t*>(off.data()), reinterpret_cast<const float*>(corpus.data()),
+                             (flags & 2) ? reinterpret_cast<const int64_t*>(ids.data()) : nullptr);
+}
+
 void lorann_free_index(lorann_index* ix) {
     if (!ix) return;
     (void)hipStreamSynchronize(ix->stream);

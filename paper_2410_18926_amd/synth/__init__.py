@@ -7,5 +7,6 @@ CPU oracle, and neither of those imports the other.  Both consume the arrays mad
 from .workloads import Workload, WORKLOADS, get_workload
 from .data import make_dataset, draw_queries
 from .index_builder import build_index, random_index, IndexArrays
+from .index_file import save_index, read_index
 
-__all__ = ["Workload", "WORKLOADS", "get_workload", "make_dataset", "draw_queries", "build_index", "random_index", "IndexArrays"]
+__all__ = ["Workload", "WORKLOADS", "get_workload", "make_dataset", "draw_queries", "build_index", "random_index", "save_index", "read_index", "IndexArrays"]
