@@ -47,7 +47,7 @@ template <bool L2, int TI>
 __global__ __launch_bounds__(256) void k_centroid_bf16(const __bf16* __restrict__ Q, const __bf16* __restrict__ C,
                                                         float* __restrict__ out, const float* __restrict__ nrm,
                                                         int M, int N, int K) {
-    constexpr int SB = 4;                 // k-steps (of 16) requested together
+    constexpr int SB = 1;                 // k-steps (of 16) requested ahead
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     const int i = lane & 31, h = lane >> 5;
     const int m0 = blockIdx.y * (64 * TI) + (wv >> 1) * (32 * TI), n0 = blockIdx.x * 128 + (wv & 1) * 64;
