@@ -52,6 +52,21 @@ __device__ __forceinline__ float wave_sum_f32_lane63(float v) {
     v += shifted(v, integral_constant<int, 0x143>{}, integral_constant<int, 0xc>{}, integral_constant<bool, false>{});  // row_bcast:31 -> rows 2, 3
     return v;
 }
+// Minimum of an unsigned over the 64 lanes, same scheme (lanes without a source keep 0xFFFFFFFF, the identity);
+// the result is returned to every lane through a scalar read of lane 63.
+__device__ __forceinline__ uint32_t wave_min_u32(uint32_t v) {
+    auto shifted = [](uint32_t x, auto ctrl, auto row_mask) {
+        return (uint32_t)__builtin_amdgcn_update_dpp((int)0xFFFFFFFFu, (int)x, decltype(ctrl)::value, decltype(row_mask)::value, 0xf, false);
+    };
+    using std::integral_constant;
+    v = min(v, shifted(v, integral_constant<int, 0x111>{}, integral_constant<int, 0xf>{}));   // row_shr:1
+    v = min(v, shifted(v, integral_constant<int, 0x112>{}, integral_constant<int, 0xf>{}));   // row_shr:2
+    v = min(v, shifted(v, integral_constant<int, 0x114>{}, integral_constant<int, 0xf>{}));   // row_shr:4
+    v = min(v, shifted(v, integral_constant<int, 0x118>{}, integral_constant<int, 0xf>{}));   // row_shr:8
+    v = min(v, shifted(v, integral_constant<int, 0x142>{}, integral_constant<int, 0xa>{}));   // row_bcast:15 -> rows 1, 3
+    v = min(v, shifted(v, integral_constant<int, 0x143>{}, integral_constant<int, 0xc>{}));   // row_bcast:31 -> rows 2, 3
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
+}
 __device__ __forceinline__ double wave_sum_f64(double v) {
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);

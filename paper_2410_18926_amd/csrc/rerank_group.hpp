@@ -286,44 +286,57 @@ __global__ __launch_bounds__(kGatherThreads) void k_group_gather(GroupArgs a) {
 
 // The k smallest (distance, id) of each query, one WAVEFRONT per query, candidates in registers (EPL per lane,
 // m <= 64 * EPL): k rounds of "take the wavefront-wide minimum and retire it".  For k much smaller than m this is
-// far cheaper than sorting.  grid = ceil(nq / 4), block = 256.
+// far cheaper than sorting.  A round is one minimum over order-preserving distance keys (data-parallel moves, no
+// LDS traffic) and a ballot; only when several lanes hold that distance are their ids compared.
+// grid = ceil(nq / 4), block = 256.
 template <int EPL>
 __global__ __launch_bounds__(256) void k_topk_wave(GroupArgs a) {
     const int lane = threadIdx.x & 63;
     const int64_t q = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (q >= a.nq) return;
     const int cnt = a.ccount[q];
-    float dv[EPL];
+    uint32_t kv[EPL];                       // order-preserving key of the distance; 0xFFFFFFFF = retired / padding
     int64_t iv[EPL];
 #pragma unroll
+    for (int e = 0; e < EPL; ++e) {         // clamped addresses: the loads go out together
+        const int t = min(64 * e + lane, max(cnt - 1, 0));
+        kv[e] = __float_as_uint(a.dist[(size_t)q * a.m + t]);
+        iv[e] = a.cid[(size_t)q * a.m + t];
+    }
+#pragma unroll
     for (int e = 0; e < EPL; ++e) {
-        const int t = 64 * e + lane;
-        dv[e] = INFINITY; iv[e] = kPadId;
-        if (t < cnt) { dv[e] = a.dist[(size_t)q * a.m + t]; iv[e] = a.cid[(size_t)q * a.m + t]; }
+        const bool in = 64 * e + lane < cnt;
+        // a NaN distance would map to a key above +inf's: clamp to +inf's key so that 0xFFFFFFFF stays reserved
+        kv[e] = in ? min(float_key_asc(__uint_as_float(kv[e])), float_key_asc(INFINITY)) : 0xFFFFFFFFu;
+        iv[e] = in ? iv[e] : kPadId;
     }
     for (int r = 0; r < a.k; ++r) {
-        float bd = dv[0];
+        uint32_t bk = kv[0];
         int64_t bi = iv[0];
 #pragma unroll
         for (int e = 1; e < EPL; ++e)
-            if (rr_less(dv[e], iv[e], bd, bi)) { bd = dv[e]; bi = iv[e]; }
-        float wd = bd;
-        int64_t wi = bi;
+            if (kv[e] < bk || (kv[e] == bk && iv[e] < bi)) { bk = kv[e]; bi = iv[e]; }
+        const uint32_t wk = wave_min_u32(bk);
+        int64_t wi = kPadId;
+        if (wk != 0xFFFFFFFFu) {                                           // uniform
+            const unsigned long long holders = __ballot(bk == wk);
+            int src = __ffsll((unsigned long long)holders) - 1;
+            if (holders & (holders - 1ull)) {                              // several lanes tie on the distance: lowest id
+                int64_t mi = bk == wk ? bi : kPadId;
 #pragma unroll
-        for (int o = 32; o > 0; o >>= 1) {
-            const float od = __shfl_xor(wd, o, 64);
-            const int64_t oi = __shfl_xor(wi, o, 64);
-            if (rr_less(od, oi, wd, wi)) { wd = od; wi = oi; }
-        }
-        // ids are distinct, so exactly one lane owns the winner (padding entries may repeat: nothing to retire)
-        if (wi != kPadId && bi == wi && bd == wd) {
+                for (int o = 32; o > 0; o >>= 1) { const int64_t oi = __shfl_xor(mi, o, 64); mi = oi < mi ? oi : mi; }
+                src = __ffsll((unsigned long long)__ballot(bk == wk && bi == mi)) - 1;
+            }
+            wi = __shfl(bi, src, 64);
+            if (lane == src) {
 #pragma unroll
-            for (int e = 0; e < EPL; ++e)
-                if (iv[e] == wi && dv[e] == wd) { dv[e] = INFINITY; iv[e] = kPadId; }
+                for (int e = 0; e < EPL; ++e)
+                    if (iv[e] == wi && kv[e] == wk) { kv[e] = 0xFFFFFFFFu; iv[e] = kPadId; }
+            }
         }
         if (lane == 0) {
             a.out_ids[(size_t)q * a.k + r] = wi == kPadId ? -1 : wi;
-            a.out_dists[(size_t)q * a.k + r] = wi == kPadId ? INFINITY : wd;
+            a.out_dists[(size_t)q * a.k + r] = wi == kPadId ? INFINITY : key_to_float(wk);
         }
     }
 }
