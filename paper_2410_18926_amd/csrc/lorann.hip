@@ -402,8 +402,8 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
         while ((int64_t)ga.slices * ngroups < 4096 && ga.slices < 16) ++ga.slices;
         {
             Prof p(ix, K_UNION);
-            if (kGroupQ == 16) hipLaunchKernelGGL(k_group_union<16>, dim3((unsigned)ngroups), dim3(256), (size_t)ga.ht * 6, s, ga);
-            else hipLaunchKernelGGL(k_group_union<8>, dim3((unsigned)ngroups), dim3(256), (size_t)ga.ht * 6, s, ga);
+            if (kGroupQ == 16) hipLaunchKernelGGL(k_group_union<16>, dim3((unsigned)ngroups), dim3(kUnionThreads), (size_t)ga.ht * 6, s, ga);
+            else hipLaunchKernelGGL(k_group_union<8>, dim3((unsigned)ngroups), dim3(kUnionThreads), (size_t)ga.ht * 6, s, ga);
         }
         {
             Prof p(ix, K_RERANK);

@@ -81,9 +81,11 @@ inline int rerank_group_size(int d) {
     return (size_t)8 * d * 4 <= 48 * 1024 ? 8 : 0;
 }
 
-// grid = ngroups, block = 256, dynamic LDS = ht * 6 bytes.  G = queries per group.
+// grid = ngroups, block = kUnionThreads, dynamic LDS = ht * 6 bytes.  G = queries per group.  All groups are
+// resident at once, so the kernel lasts as long as one block: many threads per block keep that short.
+constexpr int kUnionThreads = 1024;
 template <int G>
-__global__ __launch_bounds__(256) void k_group_union(GroupArgs a) {
+__global__ __launch_bounds__(kUnionThreads) void k_group_union(GroupArgs a) {
     constexpr int kGroupQ = G;
     extern __shared__ __align__(16) unsigned char smem[];
     const int ht = a.ht, m = a.m;
@@ -96,37 +98,59 @@ __global__ __launch_bounds__(256) void k_group_union(GroupArgs a) {
     const int ng = min(kGroupQ, a.nq - g0);
     if (tid < kGroupQ) { s_q[tid] = tid < ng ? a.qorder[g0 + tid] : -1; s_rcount[tid] = 0; }
     if (tid == 0) s_nuniq = 0;
-    for (int s = tid; s < ht; s += 256) tkey[s] = -1;
-    for (int s = tid; s < ht / 2; s += 256) tmask[s] = 0u;
+    for (int s = tid; s < ht; s += kUnionThreads) tkey[s] = -1;
+    for (int s = tid; s < ht / 2; s += kUnionThreads) tmask[s] = 0u;
     __syncthreads();
     // open addressing, key = row, one 16-bit mask per slot (bit g: query g wants the row)
-    for (int t = tid; t < ng * m; t += 256) {
-        const int g = t / m, c = t - g * m;
-        const int row = a.cand[(size_t)s_q[g] * m + c];
-        if (row < 0) continue;
-        uint32_t h = ((uint32_t)row * 2654435761u) >> 7;
-        for (;;) {
-            h &= (uint32_t)(ht - 1);
-            const int old = atomicCAS(&tkey[h], -1, row);
-            if (old == -1 || old == row) { atomicOr(&tmask[h >> 1], (1u << g) << (16 * (h & 1))); break; }
-            ++h;
+    for (int t0 = 0; t0 < ng * m; t0 += kUnionThreads * 8) {
+        int rows[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {            // eight candidates per thread requested together (clamped addresses)
+            const int t = min(t0 + kUnionThreads * u + tid, ng * m - 1);
+            const int g = t / m;
+            rows[u] = a.cand[(size_t)s_q[g] * m + (t - g * m)];
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int t = t0 + kUnionThreads * u + tid;
+            const int row = rows[u];
+            if (t >= ng * m || row < 0) continue;
+            const int g = t / m;
+            uint32_t h = ((uint32_t)row * 2654435761u) >> 7;
+            for (;;) {
+                h &= (uint32_t)(ht - 1);
+                const int old = atomicCAS(&tkey[h], -1, row);
+                if (old == -1 || old == row) { atomicOr(&tmask[h >> 1], (1u << g) << (16 * (h & 1))); break; }
+                ++h;
+            }
         }
     }
     __syncthreads();
     const size_t gbase = (size_t)grp * kGroupQ * m;
-    for (int s = tid; s < ht; s += 256) {
-        const int row = tkey[s];
-        if (row == -1) continue;
-        const uint32_t mk = (tmask[s >> 1] >> (16 * (s & 1))) & 0xffffu;
-        const int at = atomicAdd(&s_nuniq, 1);
-        a.u_row[gbase + at] = row;
-        a.u_mask[gbase + at] = (uint16_t)mk;
-        const int64_t id = a.ids ? a.ids[row] : (int64_t)row;
-        for (int g = 0; g < ng; ++g) {
-            if (!((mk >> g) & 1u)) continue;
-            const int pos = atomicAdd(&s_rcount[g], 1);
-            a.u_pos[(gbase + at) * kGroupQ + g] = (uint16_t)pos;
-            a.cid[(size_t)s_q[g] * m + pos] = id;
+    for (int s0 = 0; s0 < ht; s0 += kUnionThreads * 8) {
+        int rowv[8];
+        int64_t idv[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {            // the ids of eight table slots per thread requested together
+            const int s = s0 + kUnionThreads * u + tid;
+            rowv[u] = s < ht ? tkey[s] : -1;
+            idv[u] = a.ids ? a.ids[max(rowv[u], 0)] : (int64_t)rowv[u];
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int s = s0 + kUnionThreads * u + tid;
+            const int row = rowv[u];
+            if (row == -1) continue;
+            const uint32_t mk = (tmask[s >> 1] >> (16 * (s & 1))) & 0xffffu;
+            const int at = atomicAdd(&s_nuniq, 1);
+            a.u_row[gbase + at] = row;
+            a.u_mask[gbase + at] = (uint16_t)mk;
+            for (int g = 0; g < ng; ++g) {
+                if (!((mk >> g) & 1u)) continue;
+                const int pos = atomicAdd(&s_rcount[g], 1);
+                a.u_pos[(gbase + at) * kGroupQ + g] = (uint16_t)pos;
+                a.cid[(size_t)s_q[g] * m + pos] = idv[u];
+            }
         }
     }
     __syncthreads();
