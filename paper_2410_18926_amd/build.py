@@ -13,6 +13,9 @@ FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC",
     # packed fp32 instructions are kept off: some of their forms have produced wrong results on the test machines
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # matrix-core results go to ordinary vector registers: the epilogues read every result register once, and
+    # from the accumulation registers each read costs an extra move
+    "-mllvm", "-amdgpu-mfma-vgpr-form=1",
     "-Wall", "-Wno-unused-function",
 ]
 

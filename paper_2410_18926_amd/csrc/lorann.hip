@@ -176,7 +176,7 @@ int next_pow2(int v) { int p = 1; while (p < v) p <<= 1; return p; }
 
 constexpr int kNZ = 2;                 // 32-pair tiles per scoring unit
 constexpr int kUnitPairs = 32 * kNZ;
-constexpr int kChunkTiles = 32;       // 32-point tiles per scoring work item
+constexpr int kChunkTiles = 16;       // 32-point tiles per scoring work item
 
 // One batch of at most `chunk` queries, device pointers only.
 int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, int m, int64_t* d_ids, float* d_dists,
