@@ -305,14 +305,14 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
     }
     {
         Prof p(ix, K_STAGE_A);
-        const int64_t max_tiles = npairs / 16 + L + 1;      // sum_c ceil(count_c / 16) <= npairs / 16 + L
-        dim3 grid((unsigned)((max_tiles + 3) / 4));
-        if (r_pad == 32)
-            hipLaunchKernelGGL(k_stage_a<2>, grid, dim3(256), 0, s, ix->q8.as<int8_t>(), ix->dx.as<float>(), ix->A, ix->sA, ix->sB, ix->bucket_off.as<int32_t>(),
-                               ix->tile_off.as<int32_t>(), ix->slot_of_pos.as<int32_t>(), L, dp, ix->r, w, ix->Z.as<int8_t>(), ix->sigma.as<float>());
-        else
-            hipLaunchKernelGGL(k_stage_a<4>, grid, dim3(256), 0, s, ix->q8.as<int8_t>(), ix->dx.as<float>(), ix->A, ix->sA, ix->sB, ix->bucket_off.as<int32_t>(),
-                               ix->tile_off.as<int32_t>(), ix->slot_of_pos.as<int32_t>(), L, dp, ix->r, w, ix->Z.as<int8_t>(), ix->sigma.as<float>());
+        // about five tiles of 16 pairs per wavefront on average; skewed clusters just loop longer
+        const int64_t avg_tiles = npairs / 16 / L + 1;
+        const dim3 grid((unsigned)L, (unsigned)std::max<int64_t>(1, std::min<int64_t>(32, (avg_tiles + 19) / 20)));
+#define LAUNCH_SA(RT_, RES_) hipLaunchKernelGGL((k_stage_a<RT_, RES_>), grid, dim3(256), 0, s, ix->q8.as<int8_t>(), ix->dx.as<float>(), ix->A, ix->sA, ix->sB, \
+                                               ix->bucket_off.as<int32_t>(), ix->slot_of_pos.as<int32_t>(), L, dp, ix->r, w, ix->Z.as<int8_t>(), ix->sigma.as<float>())
+        if (r_pad == 32) { if (dp <= 256) LAUNCH_SA(2, true); else LAUNCH_SA(2, false); }
+        else { if (dp <= 256) LAUNCH_SA(4, true); else LAUNCH_SA(4, false); }
+#undef LAUNCH_SA
     }
     // Scores + candidate selection.  Batched path: pair maxima (MFMA) -> per-query walk over the few clusters whose maximum reaches the running m-th best score; the exact per-query kernel finishes what the batched path cannot.
     SelectArgs sa_;

@@ -42,55 +42,74 @@ __device__ __forceinline__ int find_bucket_wave(const int32_t* __restrict__ off,
     return lo;
 }
 
-// grid = ceil(max_tiles / 4), block = 256 (one 16-pair tile per wavefront).
-// RT = r_pad / 16 result tiles (2 or 4).  A is [L][r][dp]; Z is [npairs][r_pad] in bucket order.
-template <int RT>
+// grid = (L, slices), block = 256.  Block (c, y) serves cluster c: its wavefronts take the cluster's 16-pair tiles
+// 4 y + wv, 4 y + wv + 4 slices, ...  (no search for the cluster of a tile; clusters without pairs cost one scalar
+// load).  A_c stays in registers across the tiles of a wavefront when d' <= 256.
+// RT = r_pad / 16 result tiles (2 or 4); RES: d' <= 256, A_c resident.  A is [L][r][dp]; Z is [npairs][r_pad] in
+// bucket order.
+template <int RT, bool RES>
 __global__ __launch_bounds__(256) void k_stage_a(const int8_t* __restrict__ q8, const float* __restrict__ dx,
                                                   const int8_t* __restrict__ A, const float* __restrict__ sA,
                                                   const float* __restrict__ sB, const int32_t* __restrict__ bucket_off,
-                                                  const int32_t* __restrict__ tile_off, const int32_t* __restrict__ slot_of_pos,
+                                                  const int32_t* __restrict__ slot_of_pos,
                                                   int L, int dp, int r, int w, int8_t* __restrict__ Z, float* __restrict__ sigma) {
     const int lane = threadIdx.x & 63;
-    const int tile = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (tile >= tile_off[L]) return;
-    const int c = __builtin_amdgcn_readfirstlane(find_bucket_wave(tile_off, L, tile));   // uniform: scalar loads below
-    const int base = bucket_off[c] + (tile - tile_off[c]) * 16;
-    const int end = bucket_off[c + 1];
+    const int c = blockIdx.x;
+    const int pbeg = bucket_off[c], end = bucket_off[c + 1];
+    const int ntiles = (end - pbeg + 15) >> 4;
+    const int first = blockIdx.y * 4 + __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    if (first >= ntiles) return;                       // wavefronts are independent: no block barrier below
     const int i = lane & 15, g = lane >> 4;
-
-    const bool row_ok = base + i < end;
-    const int8_t* qrow = q8;
-    if (row_ok) qrow = q8 + (size_t)(slot_of_pos[base + i] / w) * dp;
     const int8_t* Ac = A + (size_t)c * r * dp;
-
-    i32x4 acc[RT];
-#pragma unroll
-    for (int t = 0; t < RT; ++t) acc[t] = (i32x4){0, 0, 0, 0};
-
-    // The operands of SB k-steps are requested together, with clamped addresses instead of branches around the
-    // loads (so that they overlap), and what lies outside the matrices is zeroed in registers afterwards.
-    constexpr int SB = 4;
+    constexpr int SB = 4;                                // k-steps whose operands are requested together
     const int steps = (dp + 63) >> 6;                    // uniform trip count: the MFMA runs with all lanes on
-    for (int s0 = 0; s0 < steps; s0 += SB) {
-        i32x4 av[SB], bv[SB][RT];
+    constexpr bool a_resident = RES;                     // requires steps <= SB
+    const i32x4 zero4 = (i32x4){0, 0, 0, 0};
+
+    // Operands are requested with clamped addresses instead of branches around the loads (so that they overlap)
+    // and what lies outside the matrices is zeroed in registers afterwards.
+    auto fetch_a = [&](int s0, i32x4 (&bv)[SB][RT]) {
 #pragma unroll
         for (int u = 0; u < SB; ++u) {
             const int kc = min(64 * (s0 + u) + 16 * g, dp - 16);
-            av[u] = load16(qrow + kc);
 #pragma unroll
             for (int t = 0; t < RT; ++t) bv[u][t] = load16(Ac + (size_t)min(t * 16 + i, r - 1) * dp + kc);
         }
+#pragma unroll
+        for (int u = 0; u < SB; ++u)
+#pragma unroll
+            for (int t = 0; t < RT; ++t)
+                if (!(t * 16 + i < r)) bv[u][t] = zero4;
+    };
+    i32x4 bres[RES ? SB : 1][RT];
+    if constexpr (RES) fetch_a(0, bres);
+
+    int slot_next = slot_of_pos[min(pbeg + first * 16 + i, end - 1)];
+    for (int tile = first; tile < ntiles; tile += 4 * gridDim.y) {
+    const int base = pbeg + tile * 16;
+    const bool row_ok = base + i < end;
+    const int8_t* qrow = q8 + (size_t)(slot_next / w) * dp;
+    // the next tile's pair numbers are requested now, its query rows when this tile is done
+    slot_next = slot_of_pos[min(base + 16 * 4 * (int)gridDim.y + i, end - 1)];
+
+    i32x4 acc[RT];
+#pragma unroll
+    for (int t = 0; t < RT; ++t) acc[t] = zero4;
+
+    for (int s0 = 0; s0 < steps; s0 += SB) {
+        i32x4 av[SB], bload[RES ? 1 : SB][RT];
+#pragma unroll
+        for (int u = 0; u < SB; ++u) av[u] = load16(qrow + min(64 * (s0 + u) + 16 * g, dp - 16));
+        if constexpr (!RES) fetch_a(s0, bload);
 #pragma unroll
         for (int u = 0; u < SB; ++u) {
             if (s0 + u < steps) {                        // uniform
                 // d' is a multiple of 16: a 16-byte group is all in or all out
                 const bool a_ok = row_ok && 64 * (s0 + u) + 16 * g < dp;
-                const i32x4 a = a_ok ? av[u] : (i32x4){0, 0, 0, 0};
+                const i32x4 a = a_ok ? av[u] : zero4;
 #pragma unroll
-                for (int t = 0; t < RT; ++t) {
-                    const i32x4 b = t * 16 + i < r ? bv[u][t] : (i32x4){0, 0, 0, 0};
-                    acc[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b, acc[t], 0, 0, 0);
-                }
+                for (int t = 0; t < RT; ++t)
+                    acc[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, RES ? bres[RES ? u : 0][t] : bload[RES ? 0 : u][t], acc[t], 0, 0, 0);
             }
         }
     }
@@ -126,6 +145,7 @@ __global__ __launch_bounds__(256) void k_stage_a(const int8_t* __restrict__ q8, 
             }
         }
     }
+    }   // tiles of this wavefront
 }
 
 }  // namespace lorann
