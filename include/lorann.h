@@ -107,6 +107,17 @@ int lorann_load_index_file(lorann_index **out, const char *path);
 int lorann_search(lorann_index *ix, const float *queries, int64_t nq, int32_t k, int32_t w, int32_t m,
                   int64_t *out_ids, float *out_dists);
 
+/*
+ * lorann_search_async - lorann_search without the wait: the work is enqueued on the index's stream and the call
+ * returns; out_ids / out_dists are complete once that stream has been synchronised (by the caller, or by any later
+ * synchronous call on this index).  queries, out_ids and out_dists must be device pointers and must stay valid
+ * until then.  Calls on one index execute in the order they were made (they share its workspace through the
+ * stream), so a serving loop can enqueue the next batch while the GPU finishes the current one.
+ * Errors: those of lorann_search, plus LORANN_E_INVAL for a host pointer.
+ */
+int lorann_search_async(lorann_index *ix, const float *queries, int64_t nq, int32_t k, int32_t w, int32_t m,
+                        int64_t *out_ids, float *out_dists);
+
 /* Release an index and its workspace.  NULL is ignored. */
 void lorann_free_index(lorann_index *ix);
 

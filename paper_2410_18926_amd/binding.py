@@ -21,7 +21,7 @@ LIB_PATH = pathlib.Path(__file__).resolve().parent / "liblorann.so"
 LORANN_IP, LORANN_L2, LORANN_COS = 0, 1, 2
 LORANN_OK, LORANN_E_INVAL, LORANN_E_NOMEM, LORANN_E_DEVICE, LORANN_E_UNSUPPORTED = 0, -1, -2, -3, -4
 
-EXPORTS = ["lorann_load_index", "lorann_load_index_file", "lorann_search", "lorann_free_index", "lorann_last_error", "lorann_set_stream",
+EXPORTS = ["lorann_load_index", "lorann_load_index_file", "lorann_search", "lorann_search_async", "lorann_free_index", "lorann_last_error", "lorann_set_stream",
            "lorann_search_stages", "lorann_profile_enable", "lorann_profile_get", "lorann_set_exact_selection",
            "lorann_profile_fallback_queries"]
 
@@ -55,6 +55,8 @@ def lib() -> C.CDLL:
         L.lorann_load_index.argtypes = [C.POINTER(vp), i32, i64, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.lorann_search.restype = C.c_int
         L.lorann_search.argtypes = [vp, vp, i64, i32, i32, i32, vp, vp]
+        L.lorann_search_async.restype = C.c_int
+        L.lorann_search_async.argtypes = [vp, vp, i64, i32, i32, i32, vp, vp]
         L.lorann_search_stages.restype = C.c_int
         L.lorann_search_stages.argtypes = [vp, vp, i64, i32, i32, i32, vp, vp, C.POINTER(_Stages)]
         L.lorann_load_index_file.restype = C.c_int
@@ -159,8 +161,10 @@ class Index:
         ids, dists = np.empty((nq, k), np.int64), np.empty((nq, k), np.float32)
         return ids, dists, ids.ctypes.data, dists.ctypes.data
 
-    def search(self, queries, k: int, w: int, m: int, out=None):
-        """lorann_search: returns (ids [nq,k] int64, dists [nq,k] float32) of the same kind as `queries`."""
+    def search(self, queries, k: int, w: int, m: int, out=None, asynchronous: bool = False):
+        """lorann_search: returns (ids [nq,k] int64, dists [nq,k] float32) of the same kind as `queries`.
+        asynchronous=True (device tensors only) calls lorann_search_async: the results are complete once the
+        index's stream has been synchronised."""
         qk, qptr = _prep(queries, np.float32, torch.float32 if torch else None)
         nq = int(qk.shape[0])
         if qk.ndim != 2 or int(qk.shape[1]) != self.d:
@@ -170,7 +174,7 @@ class Index:
         else:
             ids, dists = out
             ip, dptr = (ids.data_ptr(), dists.data_ptr()) if _is_torch(ids) else (ids.ctypes.data, dists.ctypes.data)
-        _check(lib().lorann_search(self._h, qptr, nq, k, w, m, ip, dptr))
+        _check((lib().lorann_search_async if asynchronous else lib().lorann_search)(self._h, qptr, nq, k, w, m, ip, dptr))
         return ids, dists
 
     def search_stages(self, queries, k: int, w: int, m: int, y_off=None):

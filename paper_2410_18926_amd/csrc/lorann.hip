@@ -109,6 +109,8 @@ struct lorann_index {
     DevBuf tau, n_kept, fb_list, pmax, qkey, u_row, u_mask, u_pos, u_count, rdist, rcid, rccount;
     int32_t force_exact = 0;        // 1: score + select with the per-query kernel only (verification)
     DevBuf stage_q, stage_ids, stage_dists;   // staging when the caller passes host memory
+    DevBuf fb_total;                // while profiling asynchronous searches: device-side sum of the fallback counts
+    bool fb_total_live = false;
     // profiling
     bool prof_on = false;
     int prof_only = -1;             // >= 0: record only this kernel (keeps the event overhead out of a timed run)
@@ -125,7 +127,7 @@ void free_all(lorann_index* ix) {
     for (void* p : ptrs) if (p) (void)hipFree(p);
     DevBuf* bufs[] = {&ix->qproj, &ix->qbf, &ix->q8, &ix->dx, &ix->gscore, &ix->sel, &ix->count, &ix->rank_in_bucket, &ix->qrank, &ix->qorder, &ix->qorder2, &ix->off0, &ix->base_tab, &ix->bucket_off, &ix->tile_off,
                       &ix->unit_off, &ix->slot_of_pos, &ix->pos_of_slot, &ix->Z, &ix->sigma, &ix->cand, &ix->tau,
-                      &ix->n_kept, &ix->fb_list, &ix->pmax, &ix->qkey, &ix->u_row, &ix->u_mask, &ix->u_pos, &ix->u_count, &ix->rdist, &ix->rcid, &ix->rccount, &ix->stage_q, &ix->stage_ids, &ix->stage_dists};
+                      &ix->n_kept, &ix->fb_list, &ix->pmax, &ix->qkey, &ix->u_row, &ix->u_mask, &ix->u_pos, &ix->u_count, &ix->rdist, &ix->rcid, &ix->rccount, &ix->stage_q, &ix->stage_ids, &ix->stage_dists, &ix->fb_total};
     for (DevBuf* b : bufs) b->release();
     for (auto& e : ix->ev_used) { (void)hipEventDestroy(e.a); (void)hipEventDestroy(e.b); }
     for (auto& e : ix->ev_free) { (void)hipEventDestroy(e.a); (void)hipEventDestroy(e.b); }
@@ -170,6 +172,20 @@ void prof_collect(lorann_index* ix) {   // the stream has been synchronised
         ix->ev_free.push_back(e);
     }
     ix->ev_used.clear();
+}
+
+// Brings the profile totals up to date with everything enqueued so far (asynchronous searches leave their events
+// and their fallback counts pending).
+int prof_settle(lorann_index* ix) {
+    HIP_TRY(hipStreamSynchronize(ix->stream));
+    prof_collect(ix);
+    if (ix->fb_total_live) {
+        int32_t fb = 0;
+        HIP_TRY(hipMemcpy(&fb, ix->fb_total.p, 4, hipMemcpyDeviceToHost));
+        ix->prof_fallback_queries += fb;
+        ix->fb_total_live = false;
+    }
+    return LORANN_OK;
 }
 
 int next_pow2(int v) { int p = 1; while (p < v) p <<= 1; return p; }
@@ -498,8 +514,12 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
     return LORANN_OK;
 }
 
+__global__ void k_add_counter(const int32_t* __restrict__ src, int32_t* __restrict__ dst) {
+    if (blockIdx.x == 0 && threadIdx.x == 0) *dst += *src;
+}
+
 int search_impl(lorann_index* ix, const float* queries, int64_t nq, int32_t k, int32_t w, int32_t m, int64_t* out_ids,
-                float* out_dists, const lorann_stages* st) {
+                float* out_dists, const lorann_stages* st, bool async = false) {
     if (!ix) return fail(LORANN_E_INVAL, "index is NULL");
     if (nq < 0) return fail(LORANN_E_INVAL, "nq = %lld is negative", (long long)nq);
     if (k < 1 || m < 1 || k > m) return fail(LORANN_E_INVAL, "need 1 <= k <= m (k = %d, m = %d)", k, m);
@@ -515,10 +535,13 @@ int search_impl(lorann_index* ix, const float* queries, int64_t nq, int32_t k, i
             return fail(LORANN_E_UNSUPPORTED, "d = %d with m = %d needs more than 64 KiB of LDS in the re-rank", ix->d, m);
     }
     // batches are processed in chunks that keep nq * w and nq * L within 32-bit indexing and a bounded workspace
+    int rc0 = LORANN_OK;
     int64_t chunk = 32768;
     while (chunk > 1 && (chunk * w > (1ll << 30) || chunk * (int64_t)ix->L > (1ll << 31))) chunk >>= 1;
 
     const bool q_dev = is_device_ptr(queries), i_dev = is_device_ptr(out_ids), d_dev = is_device_ptr(out_dists);
+    if (async && !(q_dev && i_dev && d_dev)) return fail(LORANN_E_INVAL, "lorann_search_async needs device pointers");
+    if (async && ix->prof_on && (rc0 = ix->fb_total.reserve(4))) return rc0;
     for (int64_t q0 = 0; q0 < nq; q0 += chunk) {
         const int64_t cn = std::min(chunk, nq - q0);
         const float* dQ = queries + (size_t)q0 * ix->d;
@@ -535,6 +558,15 @@ int search_impl(lorann_index* ix, const float* queries, int64_t nq, int32_t k, i
         if ((rc = search_chunk(ix, dQ, cn, k, w, m, dI, dD, st, q0))) return rc;
         if (!i_dev) HIP_TRY(hipMemcpyAsync(out_ids + (size_t)q0 * k, dI, (size_t)cn * k * 8, hipMemcpyDeviceToHost, ix->stream));
         if (!d_dev) HIP_TRY(hipMemcpyAsync(out_dists + (size_t)q0 * k, dD, (size_t)cn * k * 4, hipMemcpyDeviceToHost, ix->stream));
+        if (async) {
+            // nothing waits here: the results are complete once the stream is; while profiling, the batch's count
+            // of queries finished by the per-query kernel is added up on the device
+            if (ix->prof_on && !ix->force_exact) {
+                if (!ix->fb_total_live) { HIP_TRY(hipMemsetAsync(ix->fb_total.p, 0, 4, ix->stream)); ix->fb_total_live = true; }
+                hipLaunchKernelGGL(k_add_counter, dim3(1), dim3(64), 0, ix->stream, ix->count.as<int32_t>() + 2 * ix->L, ix->fb_total.as<int32_t>());
+            }
+            continue;
+        }
         HIP_TRY(hipStreamSynchronize(ix->stream));
         if (ix->prof_on) {
             prof_collect(ix);
@@ -737,6 +769,11 @@ int lorann_search(lorann_index* ix, const float* queries, int64_t nq, int32_t k,
     return search_impl(ix, queries, nq, k, w, m, out_ids, out_dists, nullptr);
 }
 
+int lorann_search_async(lorann_index* ix, const float* queries, int64_t nq, int32_t k, int32_t w, int32_t m, int64_t* out_ids,
+                        float* out_dists) {
+    return search_impl(ix, queries, nq, k, w, m, out_ids, out_dists, nullptr, true);
+}
+
 int lorann_search_stages(lorann_index* ix, const float* queries, int64_t nq, int32_t k, int32_t w, int32_t m,
                          int64_t* out_ids, float* out_dists, const lorann_stages* st) {
     return search_impl(ix, queries, nq, k, w, m, out_ids, out_dists, st);
@@ -750,8 +787,7 @@ int lorann_set_exact_selection(lorann_index* ix, int32_t on) {
 
 int lorann_profile_enable(lorann_index* ix, int32_t on) {
     if (!ix) return fail(LORANN_E_INVAL, "index is NULL");
-    HIP_TRY(hipStreamSynchronize(ix->stream));
-    prof_collect(ix);
+    { const int rc = prof_settle(ix); if (rc) return rc; }
     ix->prof_on = on != 0;
     ix->prof_only = on == 2 ? (int)K_RERANK : -1;
     if (on) { for (int i = 0; i < K_COUNT; ++i) { ix->prof_ms[i] = 0.0; ix->prof_launches[i] = 0; } ix->prof_fallback_queries = 0; }
@@ -759,12 +795,15 @@ int lorann_profile_enable(lorann_index* ix, int32_t on) {
 }
 
 int64_t lorann_profile_fallback_queries(lorann_index* ix) {
-    return ix ? ix->prof_fallback_queries : -1;
+    if (!ix) return -1;
+    if (prof_settle(ix) != LORANN_OK) return -1;
+    return ix->prof_fallback_queries;
 }
 
 int lorann_profile_get(lorann_index* ix, lorann_kernel_time* out, int32_t cap) {
     if (!ix) return fail(LORANN_E_INVAL, "index is NULL");
     if (cap > 0 && !out) return fail(LORANN_E_INVAL, "out is NULL");
+    { const int rc = prof_settle(ix); if (rc) return rc; }
     for (int i = 0; i < K_COUNT && i < cap; ++i) {
         memset(out[i].name, 0, sizeof out[i].name);
         strncpy(out[i].name, kKernelNames[i], sizeof out[i].name - 1);

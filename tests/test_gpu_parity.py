@@ -418,3 +418,30 @@ def test_batch_larger_than_one_launch(B):
     np.testing.assert_array_equal(h_ids.cpu().numpy(), g_ids[40000:41000])
     np.testing.assert_array_equal(h_d.cpu().numpy(), g_d[40000:41000])
     gix.close()
+
+
+def test_asynchronous_searches_match_synchronous_ones(B, small_indexes):
+    """lorann_search_async enqueues and returns: several calls in a row on different buffers, synchronised once,
+    must give what the synchronous entry point gives; host pointers are refused."""
+    wl, ix, corpus, queries = small_indexes["ip_P"]
+    gix = B.Index.from_arrays(ix.to("cuda"))
+    gix.use_torch_stream()
+    k, w, m = wl.k, wl.w, wl.m
+    dev = torch.device("cuda:0")
+    rng = np.random.default_rng(12)
+    sets = [torch.from_numpy(queries[rng.choice(queries.shape[0], size=n, replace=True)]).to(dev) for n in (33, 200, 7, 129)]
+    outs = [(torch.empty((q.shape[0], k), dtype=torch.int64, device=dev), torch.empty((q.shape[0], k), dtype=torch.float32, device=dev)) for q in sets]
+    gix.profile_enable(True)
+    for q, o in zip(sets, outs):
+        gix.search(q, k, w, m, out=o, asynchronous=True)
+    torch.cuda.synchronize()
+    prof = gix.profile_get()
+    assert prof["rerank"][1] == len(sets)                 # the pending events of all four calls were collected
+    gix.profile_enable(False)
+    for q, o in zip(sets, outs):
+        s_ids, s_d = gix.search(q, k, w, m)
+        np.testing.assert_array_equal(o[0].cpu().numpy(), s_ids.cpu().numpy())
+        np.testing.assert_array_equal(o[1].cpu().numpy(), s_d.cpu().numpy())
+    with pytest.raises(B.LorannError):
+        gix.search(queries[:4], k, w, m, asynchronous=True)
+    gix.close()
