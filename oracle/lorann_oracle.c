@@ -202,8 +202,12 @@ float oracle_exact_dissim(const float *q, const float *c, int32_t d, int32_t met
 }
 
 /* ---- The whole query phase for one query (steps 1-7). ---- */
+/* rerank = 0 is the variant without the final re-ranking step (Sec. 7.1 memory usage, App. D.3: the original
+ * vectors are then not needed): the k points of highest estimated score are the answer (ties at the boundary
+ * toward the lower corpus row, as in step 6), reported with dissimilarity = -score and ordered like every other
+ * result (dissimilarity ascending, id ascending); m plays no role. */
 static void search_one(const oracle_index *ix, const float *q, int32_t k, int32_t w, int32_t m,
-                       int64_t *out_ids, float *out_dists, const oracle_dump *dump, int64_t qi)
+                       int64_t *out_ids, float *out_dists, const oracle_dump *dump, int64_t qi, int rerank)
 {
     const int32_t d = ix->d, dp = ix->dp, r = ix->r, L = ix->L;
     float *qp = (float *)malloc(sizeof(float) * (size_t)dp);
@@ -250,11 +254,12 @@ static void search_one(const oracle_index *ix, const float *q, int32_t k, int32_
     }
     /* step 6: the m highest estimated scores, order (score descending, row ascending) */
     qsort(sc, (size_t)total, sizeof(keyidx), cmp_key_desc);
+    if (!rerank) m = k;
     int64_t nc = total < m ? total : m;
     keyidx *fin = (keyidx *)malloc(sizeof(keyidx) * (size_t)(nc > 0 ? nc : 1));
     for (int64_t t = 0; t < nc; ++t) {                                     /* step 7: exact re-rank */
         int64_t row = sc[t].idx;
-        fin[t].key = oracle_exact_dissim(q, ix->corpus + (size_t)row * d, d, ix->metric);
+        fin[t].key = rerank ? oracle_exact_dissim(q, ix->corpus + (size_t)row * d, d, ix->metric) : -sc[t].key;
         fin[t].idx = ix->ids ? ix->ids[row] : row;
     }
     qsort(fin, (size_t)nc, sizeof(keyidx), cmp_key_asc);
@@ -287,7 +292,22 @@ int oracle_search(const oracle_index *ix, const float *Q, int64_t nq, int32_t k,
 #pragma omp parallel for schedule(dynamic, 4) num_threads(threads > 0 ? threads : 1)
 #endif
     for (int64_t qi = 0; qi < nq; ++qi)
-        search_one(ix, Q + (size_t)qi * ix->d, k, w, m, out_ids + (size_t)qi * k, out_dists + (size_t)qi * k, dump, qi);
+        search_one(ix, Q + (size_t)qi * ix->d, k, w, m, out_ids + (size_t)qi * k, out_dists + (size_t)qi * k, dump, qi, 1);
+    return 0;
+}
+
+/* The same without the final re-ranking step (see search_one); ix->corpus is only read for the row norms of
+ * the Euclidean score when ix->sqnorms is NULL. */
+int oracle_search_no_rerank(const oracle_index *ix, const float *Q, int64_t nq, int32_t k, int32_t w,
+                            int64_t *out_ids, float *out_dists, int32_t threads)
+{
+    if (!ix || !Q || nq < 0 || k < 1 || w < 1 || w > ix->L || !out_ids || !out_dists) return -1;
+    if (!ix->P && ix->dp != ix->d) return -1;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(dynamic, 4) num_threads(threads > 0 ? threads : 1)
+#endif
+    for (int64_t qi = 0; qi < nq; ++qi)
+        search_one(ix, Q + (size_t)qi * ix->d, k, w, k, out_ids + (size_t)qi * k, out_dists + (size_t)qi * k, NULL, qi, 0);
     return 0;
 }
 

@@ -35,6 +35,7 @@ def lib():
         _lib = C.CDLL(str(path))
         _lib.oracle_search.restype = C.c_int
         _lib.oracle_exact_knn.restype = C.c_int
+        _lib.oracle_search_no_rerank.restype = C.c_int
         _lib.oracle_row_sqnorm.restype = C.c_float
         _lib.oracle_score.restype = C.c_float
         _lib.oracle_score.argtypes = [C.c_int32, C.c_float, C.c_int32, C.c_float]
@@ -76,9 +77,13 @@ class OracleIndex:
         if self.metric == 1:
             self.sqnorms = np.empty(self.n, np.float32)
             lib().oracle_corpus_sqnorms(_p(self.corpus), C.c_int64(self.n), C.c_int32(self.d), _p(self.sqnorms))
+        # optional: the rows the re-rank reads, when they are not the corpus the index was built from
+        self.rerank_corpus = _c(ix.get("rerank_corpus"), np.float32)
+        assert self.rerank_corpus is None or self.rerank_corpus.shape == self.corpus.shape
         self.c = _Index(self.metric, self.n, self.d, self.dp, self.r, self.L, _p(self.centroids), _p(self.P),
                         _p(self.A), _p(self.B), _p(self.scale_A), _p(self.scale_B), _p(self.offsets),
-                        _p(self.corpus), _p(self.ids), _p(self.sqnorms))
+                        _p(self.corpus if self.rerank_corpus is None else self.rerank_corpus), _p(self.ids),
+                        _p(self.sqnorms))
 
 
 def _from_file(path) -> "OracleIndex":
@@ -147,6 +152,30 @@ def search(oix: OracleIndex, Q, k: int, w: int, m: int, stages: bool = False, th
     if rc != 0:
         raise ValueError("oracle_search: invalid arguments")
     return (ids, dists, st) if stages else (ids, dists)
+
+
+def search_no_rerank(oix: OracleIndex, Q, k: int, w: int, threads: int | None = None):
+    """The query phase without the final re-ranking step: the k highest estimated scores, dists = -score."""
+    Q = _c(Q, np.float32)
+    nq = Q.shape[0]
+    assert Q.ndim == 2 and Q.shape[1] == oix.d
+    ids = np.empty((nq, k), np.int64)
+    dists = np.empty((nq, k), np.float32)
+    rc = lib().oracle_search_no_rerank(C.byref(oix.c), _p(Q), C.c_int64(nq), C.c_int32(k), C.c_int32(w), _p(ids),
+                                       _p(dists), C.c_int32(threads or default_threads()))
+    if rc != 0:
+        raise ValueError("oracle_search_no_rerank: invalid arguments")
+    return ids, dists
+
+
+def with_half_precision_corpus(ix: dict) -> dict:
+    """The index whose re-rank reads a 16-bit floating-point copy of the corpus (Sec. 4.3: 16-bit floating point
+    on the GPU): every corpus value rounded to IEEE binary16 (numpy's conversion: round to nearest, ties to even)
+    and widened back exactly.  Everything else is unchanged; in particular the row norms inside the Euclidean
+    score (Sec. 3.1) stay those of the original rows, they belong to the index."""
+    out = dict(ix)
+    out["rerank_corpus"] = np.asarray(ix["corpus"], np.float32).astype(np.float16).astype(np.float32)
+    return out
 
 
 def exact_knn(corpus, Q, metric: int, k: int, ids=None, threads: int | None = None):

@@ -354,6 +354,91 @@ def test_candidate_set_and_rerank_follow_the_template(small_indexes):
             np.testing.assert_allclose(dists[qi, :len(e_ids)], e_d, rtol=1e-6, atol=1e-7)
 
 
+def test_no_rerank_variant_returns_the_best_estimated_scores(small_indexes):
+    """Sec. 7.1 (memory usage) / App. D.3: without the final re-ranking step the answer is the k points of highest
+    estimated score.  Recomputed in numpy from the stage outputs (integer products, one rounding per score)."""
+    for name, (wl, ix, corpus, queries) in small_indexes.items():
+        a = ix.numpy()
+        oix = O.OracleIndex(a)
+        _, _, st = O.search(oix, queries, wl.k, wl.w, wl.m, stages=True)
+        ids, dists = O.search_no_rerank(oix, queries, wl.k, wl.w)
+        off = a["cluster_offsets"]
+        for qi in range(0, len(queries), 3):
+            rows, scores = [], []
+            for j in range(wl.w):
+                c = int(st["sel"][qi, j])
+                o0, o1 = int(off[c]), int(off[c + 1])
+                Y = a["B"][o0:o1].astype(np.int64) @ st["z"][qi, j].astype(np.int64)
+                sg = np.float32(st["sigma"][qi, j])
+                if wl.metric == L2:
+                    nrm = (a["corpus"][o0:o1].astype(np.float64) ** 2).sum(1).astype(np.float32)
+                    s = (Y.astype(np.float64) * float(np.float32(2) * sg) - nrm.astype(np.float64)).astype(np.float32)
+                else:
+                    s = (Y.astype(np.float64) * float(sg)).astype(np.float32)
+                rows.append(np.arange(o0, o1))
+                scores.append(s)
+            rows, scores = np.concatenate(rows), np.concatenate(scores)
+            best = np.lexsort((rows, -scores.astype(np.float64)))[:wl.k]       # boundary ties: lower row
+            e_ids, e_d = a["ids"][rows[best]], -scores[best]
+            order = np.lexsort((e_ids, e_d))                                     # reported order: (dissimilarity, id)
+            np.testing.assert_array_equal(ids[qi], e_ids[order], err_msg=name)
+            np.testing.assert_array_equal(dists[qi], e_d[order], err_msg=name)
+
+
+def test_no_rerank_variant_with_exact_factors_is_exact_search():
+    """With integer data that the 8-bit codes represent exactly (A_c = 127 I, rows and queries integer vectors whose
+    largest entry is 127) every estimated score is a known multiple of the true inner product, so the variant without
+    re-ranking must return the exact nearest neighbours by inner product: brute force with Python integers."""
+    g = np.random.default_rng(5)
+    d, L, per = 16, 4, 30
+    n = L * per
+    rows = g.integers(-127, 128, size=(n, d)).astype(np.int64)
+    A = np.zeros((L, d, d), np.int8)
+    A[:, np.arange(d), np.arange(d)] = 127
+    ix = dict(metric=IP, n=n, d=d, dp=d, r=d, L=L, centroids=g.normal(size=(L, d)).astype(np.float32), P=None, A=A,
+              B=rows.astype(np.int8), scale_A=np.full(L, 1 / 127, np.float32), scale_B=np.ones(L, np.float32),
+              cluster_offsets=np.arange(L + 1, dtype=np.int64) * per, corpus=rows.astype(np.float32), ids=None)
+    Q = g.integers(-126, 127, size=(20, d)).astype(np.int64)
+    Q[:, 0] = 127                                  # absmax 127: the query codes are the query itself
+    ids, dists = O.search_no_rerank(O.OracleIndex(ix), Q.astype(np.float32), 7, L)
+    for qi in range(len(Q)):
+        ip = [int(sum(int(a) * int(b) for a, b in zip(rows[j], Q[qi]))) for j in range(n)]
+        # every R_j equals 127 q_j, so max|R| = 127 * 127, z = q and sigma = 1: the score is the inner product itself
+        order = sorted(range(n), key=lambda j: (-ip[j], j))[:7]
+        assert ids[qi].tolist() == order, qi
+        np.testing.assert_allclose(dists[qi], [-ip[j] for j in order], rtol=2e-7)
+
+
+def test_half_precision_rerank_rows():
+    """Sec. 4.3 (16-bit floating point on the GPU): the re-rank over a binary16 copy of the corpus is the plain
+    re-rank over the rounded rows.  Pins of the rounding (nearest, ties to even, gradual underflow) on hand-computed
+    values, and of the search against brute force over the rounded rows."""
+    x = np.array([1 + 2.0 ** -11, 1 + 3 * 2.0 ** -11, 1 + 2.0 ** -11 + 2.0 ** -20, 65504.0, 2.0 ** -24, 2.0 ** -25,
+                  3 * 2.0 ** -25, -0.1], np.float32)
+    want = np.array([1.0, 1 + 2.0 ** -9, 1 + 2.0 ** -10, 65504.0, 2.0 ** -24, 0.0, 2.0 ** -23, -0.0999755859375],
+                    np.float32)
+    got = O.with_half_precision_corpus(dict(corpus=x.reshape(1, -1)))["rerank_corpus"].ravel()
+    np.testing.assert_array_equal(got, want)
+
+
+def test_half_precision_rerank_search(small_indexes):
+    for name, (wl, ix, corpus, queries) in small_indexes.items():
+        a = O.with_half_precision_corpus(ix.numpy())
+        rounded = a["rerank_corpus"]
+        assert np.abs(rounded - a["corpus"]).max() <= 2.0 ** -11 * np.abs(a["corpus"]).max()
+        oix = O.OracleIndex(a)
+        ids, dists = O.search(oix, queries[:15], wl.k, wl.L, wl.n)          # everything probed and kept: exact k-NN
+        for qi in range(15):
+            e_ids, e_d = _numpy_knn(rounded, queries[qi], wl.metric, wl.k, a["ids"])
+            np.testing.assert_allclose(dists[qi], e_d, rtol=1e-5, atol=1e-6, err_msg=name)
+            assert np.array_equal(ids[qi], e_ids) or np.allclose(dists[qi], e_d, rtol=1e-6), name
+        # the candidate sets do not depend on the re-rank rows (the Euclidean score keeps the original norms)
+        _, _, st_h = O.search(oix, queries, wl.k, wl.w, wl.m, stages=True)
+        _, _, st_f = O.search(O.OracleIndex(ix.numpy()), queries, wl.k, wl.w, wl.m, stages=True)
+        np.testing.assert_array_equal(st_h["cand_rows"], st_f["cand_rows"])
+        np.testing.assert_array_equal(st_h["cand_scores"], st_f["cand_scores"])
+
+
 def test_fewer_candidates_than_k_pads():
     """Fewer scored points than k: remaining slots hold id -1 and distance +inf."""
     d, L = 8, 3
