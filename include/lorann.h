@@ -136,6 +136,25 @@ int lorann_set_stream(lorann_index *ix, void *hip_stream);
 int lorann_set_exact_selection(lorann_index *ix, int32_t on);
 
 /*
+ * lorann_set_rerank - choose what the last step of later searches reads (Sec. 2.2 re-ranking; default F32).
+ *   LORANN_RERANK_F32   the float corpus given at load time;
+ *   LORANN_RERANK_F16   a half-precision (IEEE binary16, round to nearest even) copy of it, half the bytes of the
+ *                       step that dominates the search (Sec. 4.3: 16-bit floating point on the GPU).  Each stored
+ *                       value is widened exactly and the arithmetic stays in float, so the result is the plain
+ *                       re-rank over the rounded rows; candidates are unaffected.  The copy (2*n*d bytes) is made by
+ *                       the first call that selects this mode and lives as long as the index.  LORANN_E_UNSUPPORTED
+ *                       if a corpus value is not finite or exceeds 65504 in magnitude (mode unchanged).
+ *   LORANN_RERANK_NONE  no re-ranking step (Sec. 7.1 memory usage, App. D.3): the k points of highest estimated
+ *                       score are returned (ties at the boundary toward the lower corpus row), nearest first by
+ *                       out_dists = -score (for LORANN_L2 the score is 2<q', x'> - |x|^2 as estimated, i.e. the
+ *                       |q|^2 term is left out), ties toward the lower id.  The search's m argument is then taken
+ *                       to be k, also for the layouts of lorann_search_stages.
+ * Errors: LORANN_E_INVAL for an unknown mode, LORANN_E_NOMEM / LORANN_E_DEVICE from the runtime.
+ */
+enum { LORANN_RERANK_F32 = 0, LORANN_RERANK_F16 = 1, LORANN_RERANK_NONE = 2 };
+int lorann_set_rerank(lorann_index *ix, int32_t mode);
+
+/*
  * Intermediate results of one search, for verification against a reference implementation.  Every pointer
  * may be NULL (skipped) and may be a host or device pointer.  Layouts, with slot = query * w + rank:
  */

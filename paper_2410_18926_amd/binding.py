@@ -23,7 +23,8 @@ LORANN_OK, LORANN_E_INVAL, LORANN_E_NOMEM, LORANN_E_DEVICE, LORANN_E_UNSUPPORTED
 
 EXPORTS = ["lorann_load_index", "lorann_load_index_file", "lorann_search", "lorann_search_async", "lorann_free_index", "lorann_last_error", "lorann_set_stream",
            "lorann_search_stages", "lorann_profile_enable", "lorann_profile_get", "lorann_set_exact_selection",
-           "lorann_profile_fallback_queries"]
+           "lorann_profile_fallback_queries", "lorann_set_rerank"]
+RERANK_F32, RERANK_F16, RERANK_NONE = 0, 1, 2
 
 
 class LorannError(RuntimeError):
@@ -68,6 +69,8 @@ def lib() -> C.CDLL:
         L.lorann_set_stream.argtypes = [vp, vp]
         L.lorann_set_exact_selection.restype = C.c_int
         L.lorann_set_exact_selection.argtypes = [vp, i32]
+        L.lorann_set_rerank.restype = C.c_int
+        L.lorann_set_rerank.argtypes = [vp, i32]
         L.lorann_profile_enable.restype = C.c_int
         L.lorann_profile_enable.argtypes = [vp, i32]
         L.lorann_profile_fallback_queries.restype = C.c_int64
@@ -199,6 +202,10 @@ class Index:
 
     def set_exact_selection(self, on: bool):
         _check(lib().lorann_set_exact_selection(self._h, 1 if on else 0))
+
+    def set_rerank(self, mode: int):
+        """RERANK_F32 (default), RERANK_F16 (half-precision copy of the corpus) or RERANK_NONE (no re-ranking step)."""
+        _check(lib().lorann_set_rerank(self._h, int(mode)))
 
     def profile_enable(self, on=True):
         """True / 1: every kernel; 2: only the re-rank gather kernel; False / 0: off."""

@@ -76,10 +76,10 @@ struct DevBuf {
     template <typename T> T* as() const { return reinterpret_cast<T*>(p); }
 };
 
-enum KernelId { K_PROJECT, K_QUANTIZE, K_CENTROID, K_CENTROID_BF16, K_SELECT_W, K_BUCKET_COUNT, K_SCAN, K_SCATTER, K_STAGE_A, K_PAIR_MAX, K_SELECT_QUERY, K_SELECT_M, K_ORDER, K_UNION, K_RERANK, K_TOPK, K_COUNT };
+enum KernelId { K_PROJECT, K_QUANTIZE, K_CENTROID, K_CENTROID_BF16, K_SELECT_W, K_BUCKET_COUNT, K_SCAN, K_SCATTER, K_STAGE_A, K_PAIR_MAX, K_SELECT_QUERY, K_SELECT_M, K_ORDER, K_UNION, K_RERANK, K_TOPK, K_CAND_SCORES, K_COUNT };
 const char* const kKernelNames[K_COUNT] = {"project_f64", "quantize_rows", "centroid_dissim_f64", "centroid_screen_bf16", "select_clusters",
                                             "bucket_count", "scan_buckets", "scatter_pairs", "stage_a_i8", "pair_max_i8", "select_query", "score_select_exact",
-                                            "order_queries", "group_union", "rerank", "topk"};
+                                            "order_queries", "group_union", "rerank", "topk", "candidate_scores"};
 
 struct EventPair { hipEvent_t a, b; int kid; };
 
@@ -102,6 +102,8 @@ struct lorann_index {
     float *sA = nullptr, *sB = nullptr;
     int64_t* off = nullptr;         // [L+1]
     float* corpus = nullptr;        // [n][d]
+    _Float16* corpus_h = nullptr;   // [n][d] binary16 copy, made when the half-precision re-rank is first selected
+    int32_t rerank_mode = LORANN_RERANK_F32;
     int64_t* ids = nullptr;         // [n] or NULL
     float* sqnorm = nullptr;        // [n] (Euclidean)
     // workspace (device), sized for `chunk` queries
@@ -123,7 +125,7 @@ struct lorann_index {
 namespace {
 
 void free_all(lorann_index* ix) {
-    void* ptrs[] = {ix->centroids, ix->cent_sqnorm, ix->cent_nrm_f32, ix->cent_bf16, ix->Pt, ix->A, ix->Bp, ix->sA, ix->sB, ix->off, ix->corpus, ix->ids, ix->sqnorm};
+    void* ptrs[] = {ix->centroids, ix->cent_sqnorm, ix->cent_nrm_f32, ix->cent_bf16, ix->Pt, ix->A, ix->Bp, ix->sA, ix->sB, ix->off, ix->corpus, ix->corpus_h, ix->ids, ix->sqnorm};
     for (void* p : ptrs) if (p) (void)hipFree(p);
     DevBuf* bufs[] = {&ix->qproj, &ix->qbf, &ix->q8, &ix->dx, &ix->gscore, &ix->sel, &ix->count, &ix->rank_in_bucket, &ix->qrank, &ix->qorder, &ix->qorder2, &ix->off0, &ix->base_tab, &ix->bucket_off, &ix->tile_off,
                       &ix->unit_off, &ix->slot_of_pos, &ix->pos_of_slot, &ix->Z, &ix->sigma, &ix->cand, &ix->tau,
@@ -391,7 +393,28 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
     }
     const int mp2 = std::max(256, next_pow2(m));
     const int kGroupQ = rerank_group_size(d);    // queries per re-rank group (0: rows too long to share)
-    if (m <= 512 && !ix->force_exact && kGroupQ > 0) {
+    const bool half_rows = ix->rerank_mode == LORANN_RERANK_F16;
+    if (ix->rerank_mode == LORANN_RERANK_NONE) {
+        // no re-ranking step: the candidates (m == k here) are the answer, ordered by their estimated scores
+        if ((rc = ix->rdist.reserve((size_t)nq * m * 4))) return rc;
+        if ((rc = ix->rcid.reserve((size_t)nq * m * 8))) return rc;
+        if ((rc = ix->rccount.reserve((size_t)nq * 4))) return rc;
+        sa_.qlist = nullptr; sa_.qcount = nullptr;
+        {
+            Prof p(ix, K_CAND_SCORES);
+            const dim3 grid((unsigned)((nq + 3) / 4));
+            if (r_pad == 32) hipLaunchKernelGGL(k_candidate_scores<2>, grid, dim3(256), 0, s, sa_, (int)nq, ix->ids, ix->rdist.as<float>(), ix->rcid.as<int64_t>(), ix->rccount.as<int32_t>());
+            else hipLaunchKernelGGL(k_candidate_scores<4>, grid, dim3(256), 0, s, sa_, (int)nq, ix->ids, ix->rdist.as<float>(), ix->rcid.as<int64_t>(), ix->rccount.as<int32_t>());
+        }
+        GroupArgs ga{};
+        ga.dist = ix->rdist.as<float>(); ga.cid = ix->rcid.as<int64_t>(); ga.ccount = ix->rccount.as<int32_t>();
+        ga.out_ids = d_ids; ga.out_dists = d_dists; ga.nq = (int)nq; ga.d = d; ga.m = m; ga.k = k;
+        {
+            Prof p(ix, K_TOPK);
+            if (k <= 64) hipLaunchKernelGGL(k_topk_wave<4>, dim3((unsigned)((nq + 3) / 4)), dim3(256), 0, s, ga);
+            else hipLaunchKernelGGL(k_topk, dim3((unsigned)nq), dim3(256), (size_t)mp2 * 12, s, ga, mp2);
+        }
+    } else if (m <= 512 && !ix->force_exact && kGroupQ > 0) {
         // grouped re-rank: neighbours in the visiting order share candidate rows, each distinct row is gathered once
         {
             Prof p(ix, K_ORDER);
@@ -408,7 +431,7 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
         if ((rc = ix->rcid.reserve((size_t)nq * m * 8))) return rc;
         if ((rc = ix->rccount.reserve((size_t)nq * 4))) return rc;
         GroupArgs ga;
-        ga.Q = dQ; ga.corpus = ix->corpus; ga.ids = ix->ids; ga.cand = ix->cand.as<int32_t>(); ga.qorder = ix->qorder2.as<int32_t>();
+        ga.Q = dQ; ga.corpus = half_rows ? (const void*)ix->corpus_h : (const void*)ix->corpus; ga.ids = ix->ids; ga.cand = ix->cand.as<int32_t>(); ga.qorder = ix->qorder2.as<int32_t>();
         ga.u_row = ix->u_row.as<int32_t>(); ga.u_mask = ix->u_mask.as<uint16_t>(); ga.u_pos = ix->u_pos.as<uint16_t>(); ga.u_count = ix->u_count.as<int32_t>();
         ga.dist = ix->rdist.as<float>(); ga.cid = ix->rcid.as<int64_t>(); ga.ccount = ix->rccount.as<int32_t>();
         ga.out_ids = d_ids; ga.out_dists = d_dists; ga.nq = (int)nq; ga.d = d; ga.m = m; ga.k = k;
@@ -418,8 +441,7 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
         while ((int64_t)ga.slices * ngroups < 4096 && ga.slices < 16) ++ga.slices;
         {
             Prof p(ix, K_UNION);
-            if (kGroupQ == 16) hipLaunchKernelGGL(k_group_union<16>, dim3((unsigned)ngroups), dim3(kUnionThreads), (size_t)ga.ht * 6, s, ga);
-            else hipLaunchKernelGGL(k_group_union<8>, dim3((unsigned)ngroups), dim3(kUnionThreads), (size_t)ga.ht * 6, s, ga);
+            hipLaunchKernelGGL(k_group_union<8>, dim3((unsigned)ngroups), dim3(kUnionThreads), (size_t)ga.ht * 6, s, ga);
         }
         {
             Prof p(ix, K_RERANK);
@@ -428,8 +450,8 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
             const int nv = (d % 4 == 0 && d <= 1024) ? (d / 4 + 63) / 64 : 0;
 #define LAUNCH_GG3(M_, NV_)                                                                                    \
     do {                                                                                                       \
-        if (kGroupQ == 16) hipLaunchKernelGGL((k_group_gather<M_, NV_, 16>), grid, dim3(kGatherThreads), lds, s, ga); \
-        else hipLaunchKernelGGL((k_group_gather<M_, NV_, 8>), grid, dim3(kGatherThreads), lds, s, ga);          \
+        if (half_rows) hipLaunchKernelGGL((k_group_gather<M_, NV_, 8, _Float16>), grid, dim3(kGatherThreads), lds, s, ga); \
+        else hipLaunchKernelGGL((k_group_gather<M_, NV_, 8, float>), grid, dim3(kGatherThreads), lds, s, ga);   \
     } while (0)
 #define LAUNCH_GG(M_)                                                                                          \
     do {                                                                                                       \
@@ -458,12 +480,15 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
         const size_t lds = (size_t)d * 4 + (size_t)mp2 * 12;
         const int32_t* cand = ix->cand.as<int32_t>();
         const dim3 rgrid((unsigned)(8 * ((nq + 7) / 8)));
-        if (ix->metric == LORANN_IP)
-            hipLaunchKernelGGL(k_rerank<0>, rgrid, dim3(256), lds, s, dQ, ix->corpus, ix->ids, cand, ix->qorder.as<int32_t>(), (int)nq, d, m, mp2, k, d_ids, d_dists);
-        else if (ix->metric == LORANN_L2)
-            hipLaunchKernelGGL(k_rerank<1>, rgrid, dim3(256), lds, s, dQ, ix->corpus, ix->ids, cand, ix->qorder.as<int32_t>(), (int)nq, d, m, mp2, k, d_ids, d_dists);
-        else
-            hipLaunchKernelGGL(k_rerank<2>, rgrid, dim3(256), lds, s, dQ, ix->corpus, ix->ids, cand, ix->qorder.as<int32_t>(), (int)nq, d, m, mp2, k, d_ids, d_dists);
+#define LAUNCH_RR(M_)                                                                                          \
+    do {                                                                                                       \
+        if (half_rows) hipLaunchKernelGGL((k_rerank<M_, _Float16>), rgrid, dim3(256), lds, s, dQ, (const _Float16*)ix->corpus_h, ix->ids, cand, ix->qorder.as<int32_t>(), (int)nq, d, m, mp2, k, d_ids, d_dists); \
+        else hipLaunchKernelGGL((k_rerank<M_, float>), rgrid, dim3(256), lds, s, dQ, (const float*)ix->corpus, ix->ids, cand, ix->qorder.as<int32_t>(), (int)nq, d, m, mp2, k, d_ids, d_dists); \
+    } while (0)
+        if (ix->metric == LORANN_IP) LAUNCH_RR(0);
+        else if (ix->metric == LORANN_L2) LAUNCH_RR(1);
+        else LAUNCH_RR(2);
+#undef LAUNCH_RR
     }
     HIP_TRY(hipGetLastError());
 
@@ -522,6 +547,7 @@ int search_impl(lorann_index* ix, const float* queries, int64_t nq, int32_t k, i
                 float* out_dists, const lorann_stages* st, bool async = false) {
     if (!ix) return fail(LORANN_E_INVAL, "index is NULL");
     if (nq < 0) return fail(LORANN_E_INVAL, "nq = %lld is negative", (long long)nq);
+    if (ix->rerank_mode == LORANN_RERANK_NONE && k >= 1 && m >= k) m = k;    // the candidates are the answer
     if (k < 1 || m < 1 || k > m) return fail(LORANN_E_INVAL, "need 1 <= k <= m (k = %d, m = %d)", k, m);
     if (w < 1 || w > ix->L) return fail(LORANN_E_INVAL, "need 1 <= w <= L (w = %d, L = %d)", w, ix->L);
     if (w > LORANN_MAX_W) return fail(LORANN_E_UNSUPPORTED, "w = %d exceeds LORANN_MAX_W = %d", w, LORANN_MAX_W);
@@ -777,6 +803,34 @@ int lorann_search_async(lorann_index* ix, const float* queries, int64_t nq, int3
 int lorann_search_stages(lorann_index* ix, const float* queries, int64_t nq, int32_t k, int32_t w, int32_t m,
                          int64_t* out_ids, float* out_dists, const lorann_stages* st) {
     return search_impl(ix, queries, nq, k, w, m, out_ids, out_dists, st);
+}
+
+int lorann_set_rerank(lorann_index* ix, int32_t mode) {
+    if (!ix) return fail(LORANN_E_INVAL, "index is NULL");
+    if (mode != LORANN_RERANK_F32 && mode != LORANN_RERANK_F16 && mode != LORANN_RERANK_NONE) return fail(LORANN_E_INVAL, "unknown re-rank mode %d", mode);
+    if (mode == LORANN_RERANK_F16 && !ix->corpus_h) {
+        HIP_TRY(hipStreamSynchronize(ix->stream));
+        const size_t count = (size_t)ix->n * ix->d;
+        _Float16* h = nullptr;
+        uint32_t* mx = nullptr;
+        HIP_TRY(hipMalloc((void**)&h, count * 2));
+        hipError_t e = hipMalloc((void**)&mx, 4);
+        if (e == hipSuccess) e = hipMemset(mx, 0, 4);
+        uint32_t bits = 0;
+        if (e == hipSuccess) {
+            const unsigned grid = (unsigned)std::min<size_t>((count + 255) / 256, 16384);
+            hipLaunchKernelGGL(k_corpus_to_half, dim3(grid), dim3(256), 0, nullptr, ix->corpus, h, count, mx);
+            e = hipGetLastError();
+        }
+        if (e == hipSuccess) e = hipMemcpy(&bits, mx, 4, hipMemcpyDeviceToHost);
+        if (mx) (void)hipFree(mx);
+        if (e != hipSuccess) { (void)hipFree(h); (void)hipGetLastError(); return fail(e == hipErrorOutOfMemory ? LORANN_E_NOMEM : LORANN_E_DEVICE, "building the half-precision corpus failed: %s", hipGetErrorString(e)); }
+        float mxf; memcpy(&mxf, &bits, 4);
+        if (!(mxf <= 65504.0f)) { (void)hipFree(h); return fail(LORANN_E_UNSUPPORTED, "the corpus holds values beyond the binary16 range (largest magnitude %g)", (double)mxf); }
+        ix->corpus_h = h;
+    }
+    ix->rerank_mode = mode;
+    return LORANN_OK;
 }
 
 int lorann_set_exact_selection(lorann_index* ix, int32_t on) {

@@ -4,12 +4,40 @@
 //
 // HBM-bound row gather: one block per query, each wavefront streams whole corpus rows with 16-byte loads per
 // lane (a row of d floats is contiguous), reduces with shuffles, and the block sorts the m distances in LDS.
+//
+// The rows are read either from the float corpus or from a half-precision (IEEE binary16) copy of it (Sec. 4.3:
+// 16-bit floating point on the GPU); a half is widened exactly and all arithmetic stays in float, element for
+// element in the same order, so the two modes differ only by the rounding of the stored rows.
 #pragma once
 #include "common.hpp"
 
 namespace lorann {
 
 constexpr int64_t kPadId = 0x7fffffffffffffffLL;
+
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+template <typename T> struct Row4 { using type = float4; };          // four consecutive row elements as stored
+template <> struct Row4<_Float16> { using type = f16x4; };
+__device__ __forceinline__ float4 widen4(const float4& v) { return v; }
+__device__ __forceinline__ float4 widen4(const f16x4& v) { return make_float4((float)v[0], (float)v[1], (float)v[2], (float)v[3]); }
+__device__ __forceinline__ float widen1(float v) { return v; }
+__device__ __forceinline__ float widen1(_Float16 v) { return (float)v; }
+
+// The half-precision copy of the corpus: round to nearest even.  *max_abs_bits receives the largest |x| seen (as
+// float bits; a NaN compares above everything) so that the host can refuse rows binary16 cannot hold.
+// grid-stride over count elements, block = 256.
+__global__ __launch_bounds__(256) void k_corpus_to_half(const float* __restrict__ src, _Float16* __restrict__ dst, size_t count,
+                                                         uint32_t* __restrict__ max_abs_bits) {
+    uint32_t mx = 0u;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < count; i += (size_t)gridDim.x * 256) {
+        const float v = src[i];
+        mx = max(mx, __float_as_uint(v) & 0x7fffffffu);
+        dst[i] = (_Float16)v;
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) mx = max(mx, (uint32_t)__shfl_xor((int)mx, o, 64));
+    if ((threadIdx.x & 63) == 0) atomicMax(max_abs_bits, mx);
+}
 
 __device__ __forceinline__ bool rr_less(float da, int64_t ia, float db, int64_t ib) {
     return da < db || (da == db && ia < ib);
@@ -20,8 +48,8 @@ __device__ __forceinline__ bool rr_less(float da, int64_t ia, float db, int64_t 
 // Queries are taken in the order of `qorder` (grouped by nearest cluster: queries that share candidates run at
 // the same time, so a corpus row gathered for one of them is still in cache for the others), and consecutive
 // entries of that order go to the same XCD (workgroups are dealt round-robin over the 8 XCDs, each with its own L2).
-template <int METRIC>
-__global__ __launch_bounds__(256) void k_rerank(const float* __restrict__ Q, const float* __restrict__ corpus,
+template <int METRIC, typename T>
+__global__ __launch_bounds__(256) void k_rerank(const float* __restrict__ Q, const T* __restrict__ corpus,
                                                  const int64_t* __restrict__ ids, const int32_t* __restrict__ cand,
                                                  const int32_t* __restrict__ qorder, int nq,
                                                  int d, int m, int mp2, int k, int64_t* __restrict__ out_ids,
@@ -51,18 +79,19 @@ __global__ __launch_bounds__(256) void k_rerank(const float* __restrict__ Q, con
         __syncthreads();
     }
     const int32_t* crow = cand + (size_t)q * m;
-    const int d4 = (d % 4 == 0) ? d / 4 : 0;      // vector path needs 16-byte aligned rows
+    const int d4 = (d % 4 == 0) ? d / 4 : 0;      // vector path needs rows aligned to four elements
+    using V = typename Row4<T>::type;
 
     for (int c = wv; c < m; c += 4) {
         const int row = crow[c];
         if (row < 0) continue;                    // uniform per wavefront
-        const float* p = corpus + (size_t)row * d;
+        const T* p = corpus + (size_t)row * d;
         float acc = 0.0f;
         if (d4) {
-            const float4* p4 = reinterpret_cast<const float4*>(p);
+            const V* p4 = reinterpret_cast<const V*>(p);
             const float4* q4 = reinterpret_cast<const float4*>(qs);
             for (int i = lane; i < d4; i += 64) {
-                const float4 x = p4[i], y = q4[i];
+                const float4 x = widen4(p4[i]), y = q4[i];
                 if (METRIC == 1) {
                     const float a0 = y.x - x.x, a1 = y.y - x.y, a2 = y.z - x.z, a3 = y.w - x.w;
                     acc = fmaf(a0, a0, acc); acc = fmaf(a1, a1, acc); acc = fmaf(a2, a2, acc); acc = fmaf(a3, a3, acc);
@@ -72,8 +101,9 @@ __global__ __launch_bounds__(256) void k_rerank(const float* __restrict__ Q, con
             }
         } else {
             for (int i = lane; i < d; i += 64) {
-                if (METRIC == 1) { const float t = qs[i] - p[i]; acc = fmaf(t, t, acc); }
-                else acc = fmaf(p[i], qs[i], acc);
+                const float x = widen1(p[i]);
+                if (METRIC == 1) { const float t = qs[i] - x; acc = fmaf(t, t, acc); }
+                else acc = fmaf(x, qs[i], acc);
             }
         }
         acc = wave_sum_f32_lane63(acc);

@@ -50,7 +50,7 @@ __global__ __launch_bounds__(64) void k_order_queries(const int32_t* __restrict_
 
 struct GroupArgs {
     const float* Q;              // [nq][d]
-    const float* corpus;         // [n][d]
+    const void* corpus;          // [n][d] float, or its binary16 copy (the gather kernel's row type says which)
     const int64_t* ids;          // [n] or NULL
     const int32_t* cand;         // [nq][m]
     const int32_t* qorder;       // [nq] visiting order
@@ -163,12 +163,16 @@ constexpr int kGatherThreads = 512, kGatherWaves = kGatherThreads / 64;
 // grid = ngroups * slices, block = kGatherThreads, dynamic LDS = G * d * 4 bytes (G = queries per group).
 // METRIC: 0 inner product, 1 squared
 // Euclidean, 2 cosine.
-// NV = number of 64-lane float4 slices of a row, ceil(d / 256), for rows that live in registers (d % 4 == 0,
-// d <= 1024); NV = 0: any d, rows are streamed element by element.
-template <int METRIC, int NV, int G>
+// NV = number of 64-lane slices of four elements of a row, ceil(d / 256), for rows that live in registers
+// (d % 4 == 0, d <= 1024); NV = 0: any d, rows are streamed element by element.
+// T = element type of the stored rows: float (16-byte loads per lane) or _Float16 (8-byte loads, twice the rows in
+// flight); a lane owns the same four elements of a slice in both, so the arithmetic is the same.
+template <int METRIC, int NV, int G, typename T>
 __global__ __launch_bounds__(kGatherThreads) void k_group_gather(GroupArgs a) {
     constexpr int kGroupQ = G;
-    constexpr int RB = 2;                                          // rows in flight per wavefront
+    constexpr int RB = sizeof(T) == 2 ? 4 : 2;                     // rows in flight per wavefront
+    using V = typename Row4<T>::type;
+    const T* const corpus = static_cast<const T*>(a.corpus);
     extern __shared__ __align__(16) unsigned char smem[];
     float* qs = reinterpret_cast<float*>(smem);                    // [G][d]
     __shared__ int s_q[kGroupQ];
@@ -237,13 +241,13 @@ __global__ __launch_bounds__(kGatherThreads) void k_group_gather(GroupArgs a) {
         };
         fetch_meta(ubeg + wv * RB);
         for (int u0 = ubeg + wv * RB; u0 < uend; u0 += kGatherWaves * RB) {
-            float4 x[RB][NV > 0 ? NV : 1];
+            V x[RB][NV > 0 ? NV : 1];
             int ps[RB];
             uint32_t mk[RB];
 #pragma unroll
             for (int r = 0; r < RB; ++r) {
                 mk[r] = nmk[r]; ps[r] = nps[r];
-                const float4* p4 = reinterpret_cast<const float4*>(a.corpus + (size_t)nrow[r] * d);
+                const V* p4 = reinterpret_cast<const V*>(corpus + (size_t)nrow[r] * d);
 #pragma unroll
                 for (int v = 0; v < NV; ++v) x[r][v] = p4[min(lane + 64 * v, d4 - 1)];
             }
@@ -259,12 +263,12 @@ __global__ __launch_bounds__(kGatherThreads) void k_group_gather(GroupArgs a) {
 #pragma unroll
                     for (int v = 0; v < NV; ++v) {
                         if (v + 1 < NV || lane + 64 * v < d4) {            // only the last slice can be partial
-                            const float4 y = q4[lane + 64 * v];
+                            const float4 y = q4[lane + 64 * v], xv = widen4(x[r][v]);
                             if (METRIC == 1) {
-                                const float a0 = y.x - x[r][v].x, a1 = y.y - x[r][v].y, a2 = y.z - x[r][v].z, a3 = y.w - x[r][v].w;
+                                const float a0 = y.x - xv.x, a1 = y.y - xv.y, a2 = y.z - xv.z, a3 = y.w - xv.w;
                                 acc = fmaf(a0, a0, acc); acc = fmaf(a1, a1, acc); acc = fmaf(a2, a2, acc); acc = fmaf(a3, a3, acc);
                             } else {
-                                acc = fmaf(x[r][v].x, y.x, acc); acc = fmaf(x[r][v].y, y.y, acc); acc = fmaf(x[r][v].z, y.z, acc); acc = fmaf(x[r][v].w, y.w, acc);
+                                acc = fmaf(xv.x, y.x, acc); acc = fmaf(xv.y, y.y, acc); acc = fmaf(xv.z, y.z, acc); acc = fmaf(xv.w, y.w, acc);
                             }
                         }
                     }
@@ -278,16 +282,16 @@ __global__ __launch_bounds__(kGatherThreads) void k_group_gather(GroupArgs a) {
         for (int u = ubeg + wv; u < uend; u += kGatherWaves) {
             const int row = a.u_row[gbase + u];
             const uint32_t mk = a.u_mask[gbase + u];
-            const float* p = a.corpus + (size_t)row * d;
+            const T* p = corpus + (size_t)row * d;
             for (int g = 0; g < ng; ++g) {
                 if (!((mk >> g) & 1u)) continue;
                 const float* qg = qs + (size_t)g * d;
                 float acc = 0.0f;
                 if (d4) {
-                    const float4* p4 = reinterpret_cast<const float4*>(p);
+                    const V* p4 = reinterpret_cast<const V*>(p);
                     const float4* q4 = reinterpret_cast<const float4*>(qg);
                     for (int i = lane; i < d4; i += 64) {
-                        const float4 x = p4[i], y = q4[i];
+                        const float4 x = widen4(p4[i]), y = q4[i];
                         if (METRIC == 1) {
                             const float a0 = y.x - x.x, a1 = y.y - x.y, a2 = y.z - x.z, a3 = y.w - x.w;
                             acc = fmaf(a0, a0, acc); acc = fmaf(a1, a1, acc); acc = fmaf(a2, a2, acc); acc = fmaf(a3, a3, acc);
@@ -297,8 +301,9 @@ __global__ __launch_bounds__(kGatherThreads) void k_group_gather(GroupArgs a) {
                     }
                 } else {
                     for (int i = lane; i < d; i += 64) {
-                        if (METRIC == 1) { const float t = qg[i] - p[i]; acc = fmaf(t, t, acc); }
-                        else acc = fmaf(p[i], qg[i], acc);
+                        const float x = widen1(p[i]);
+                        if (METRIC == 1) { const float t = qg[i] - x; acc = fmaf(t, t, acc); }
+                        else acc = fmaf(x, qg[i], acc);
                     }
                 }
                 acc = wave_sum_f32_lane63(acc);

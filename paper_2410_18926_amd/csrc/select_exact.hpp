@@ -177,6 +177,47 @@ __global__ __launch_bounds__(256) void k_select_exact(SelectArgs a, int nq) {
     }
 }
 
+// Search without the final re-ranking step (Sec. 7.1 memory usage, App. D.3): the candidates ARE the answer and their
+// estimated scores are what is reported.  For every candidate row of a.cand ([nq][m], valid entries first) this
+// recomputes the score exactly as the selection did - same integer product, same single fused multiply-add - and
+// writes dissimilarity = -score and the row's id into the arrays the top-k kernels order.
+// grid = ceil(nq / 4), block = 256 (one wavefront per query).
+template <int RB>
+__global__ __launch_bounds__(256) void k_candidate_scores(SelectArgs a, int nq, const int64_t* __restrict__ ids,
+                                                           float* __restrict__ dist, int64_t* __restrict__ cid,
+                                                           int32_t* __restrict__ ccount) {
+    constexpr int ZW = RB * 4;
+    const int lane = threadIdx.x & 63;
+    const int64_t q = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (q >= nq) return;
+    const int w = a.w, m = a.m;
+    const bool l2 = a.sqnorm != nullptr;
+    int cnt = 0;
+    for (int t0 = 0; t0 < m; t0 += 64) {
+        const int t = t0 + lane;
+        const int row = t < m ? a.cand[(size_t)q * m + t] : -1;
+        if (row >= 0) {
+            int j = 0;                                  // the selected cluster that owns the row
+            for (int u = 0; u < w; ++u) {
+                const int c = a.sel[(size_t)q * w + u];
+                if (a.off[c] <= row && row < a.off[c + 1]) j = u;
+            }
+            const int pos = a.pos_of_slot[(size_t)q * w + j];
+            int zw[ZW];
+#pragma unroll
+            for (int i = 0; i < ZW; ++i) zw[i] = reinterpret_cast<const int*>(a.Z)[(size_t)pos * ZW + i];
+            const int y = point_score<RB>(a.Bp + (size_t)row * (RB * 16), zw);
+            const float sg = a.sigma[pos];
+            const float bias = l2 ? a.sqnorm[row] : 0.0f;
+            const float sc = __fmaf_rn((float)y, l2 ? 2.0f * sg : sg, -bias);
+            dist[(size_t)q * m + t] = -sc;
+            cid[(size_t)q * m + t] = ids ? ids[row] : (int64_t)row;
+        }
+        cnt += __popcll(__ballot(row >= 0));
+    }
+    if (lane == 0) ccount[q] = cnt;
+}
+
 // Integer scores of every point of every pair, for verification: y[y_off[slot] + t] = z_slot^T code(row0 + t).
 // grid = npairs (one block per slot), block = 256.
 template <int RB>

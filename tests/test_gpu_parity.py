@@ -445,3 +445,113 @@ def test_asynchronous_searches_match_synchronous_ones(B, small_indexes):
     with pytest.raises(B.LorannError):
         gix.search(queries[:4], k, w, m, asynchronous=True)
     gix.close()
+
+
+def test_half_precision_rerank_small_workloads(B, small_indexes):
+    """Re-rank over the binary16 copy of the corpus (Sec. 4.3): the library's rounding and float arithmetic against
+    the oracle's plain re-rank over numpy-rounded rows; candidates are those of the float mode; switching back
+    restores the float results."""
+    for name, (wl, ix, corpus, queries) in small_indexes.items():
+        a = ix.numpy()
+        o_ids, o_d, ost = O.search(O.OracleIndex(O.with_half_precision_corpus(a)), queries, wl.k, wl.w, wl.m, stages=True)
+        gix = B.Index.from_arrays(ix.to("cuda"))
+        f_ids, f_d = gix.search(queries, wl.k, wl.w, wl.m)
+        gix.set_rerank(B.RERANK_F16)
+        g_ids, g_d, gst = gix.search_stages(queries, wl.k, wl.w, wl.m)
+        np.testing.assert_array_equal(np.sort(gst["cand_rows"].astype(np.int64), axis=1), np.sort(ost["cand_rows"], axis=1), err_msg=name)
+        assert_topk_equal(g_ids, g_d, o_ids, o_d, f"{name} half-precision rows")
+        gix.set_exact_selection(True)                       # the one-query-per-block re-rank reads the same copy
+        e_ids, e_d = gix.search(queries, wl.k, wl.w, wl.m)
+        gix.set_exact_selection(False)
+        np.testing.assert_array_equal(e_ids, g_ids)
+        np.testing.assert_array_equal(e_d, g_d)
+        gix.set_rerank(B.RERANK_F32)
+        b_ids, b_d = gix.search(queries, wl.k, wl.w, wl.m)
+        np.testing.assert_array_equal(b_ids, f_ids)
+        np.testing.assert_array_equal(b_d, f_d)
+        gix.close()
+
+
+@pytest.mark.parametrize("d,metric", [(768, 0), (1024, 1), (200, 2), (50, 1), (1100, 0), (2000, 1)])
+def test_half_precision_rerank_row_lengths(B, d, metric):
+    """Every row-length path of the gather (one to four register slices, rows not a multiple of four elements,
+    streamed rows, one query per block), values spread over binary16's normal and subnormal ranges."""
+    rng = np.random.default_rng(1000 + d)
+    ix = _random_index(rng, n=2500, d=d, L=16, r=8, metric=metric, dp=64 if d >= 64 else 32)
+    if metric != 2:
+        ix["corpus"] = (ix["corpus"] * np.exp(rng.normal(size=(2500, 1)) * 2).astype(np.float32)).astype(np.float32)
+        ix["corpus"][::97, ::5] *= np.float32(1e-6)        # binary16 subnormals and zeros
+    q = rng.normal(size=(45, d)).astype(np.float32)
+    gix = B.Index(**ix)
+    gix.set_rerank(B.RERANK_F16)
+    o_ids, o_d = O.search(O.OracleIndex(O.with_half_precision_corpus(ix)), q, 10, 6, 150)
+    g_ids, g_d = gix.search(q, 10, 6, 150)
+    assert_topk_equal(g_ids, g_d, o_ids, o_d, f"d={d} metric={metric} half-precision rows")
+    gix.close()
+
+
+def test_half_precision_rerank_refuses_values_out_of_range(B):
+    rng = np.random.default_rng(77)
+    ix = _random_index(rng, n=600, d=32, L=6, r=8, metric=0)
+    q = rng.normal(size=(9, 32)).astype(np.float32)
+    for bad in (7.0e4, -1.0e9, np.inf, np.nan):
+        broken = dict(ix)
+        broken["corpus"] = ix["corpus"].copy()
+        broken["corpus"][311, 7] = bad
+        gix = B.Index(**broken)
+        with pytest.raises(B.LorannError) as ei:
+            gix.set_rerank(B.RERANK_F16)
+        assert ei.value.code == B.LORANN_E_UNSUPPORTED
+        if np.isfinite(bad):                                # the mode is unchanged: float rows are still what is read
+            o_ids, o_d = O.search(O.OracleIndex(broken), q, 5, 3, 40)
+            g_ids, g_d = gix.search(q, 5, 3, 40)
+            assert_topk_equal(g_ids, g_d, o_ids, o_d, f"after refusing {bad}")
+        gix.close()
+    edge = dict(ix)
+    edge["corpus"] = ix["corpus"].copy()
+    edge["corpus"][5, 5] = 65504.0                          # the largest binary16 value is fine
+    gix = B.Index(**edge)
+    gix.set_rerank(B.RERANK_F16)
+    with pytest.raises(B.LorannError):
+        gix.set_rerank(7)
+    gix.close()
+
+
+def test_search_without_rerank_small_workloads(B, small_indexes):
+    """No re-ranking step (Sec. 7.1 memory usage, App. D.3): ids and -score bit-identical to the oracle's, from the
+    batched selection and from the per-query kernel, with m ignored."""
+    for name, (wl, ix, corpus, queries) in small_indexes.items():
+        a = ix.numpy()
+        oix = O.OracleIndex(a)
+        gix = B.Index.from_arrays(ix.to("cuda"))
+        gix.set_rerank(B.RERANK_NONE)
+        for k in (1, wl.k, 64, 70):
+            o_ids, o_d = O.search_no_rerank(oix, queries, k, wl.w)
+            g_ids, g_d = gix.search(queries, k, wl.w, max(k, wl.m))
+            np.testing.assert_array_equal(g_ids, o_ids, err_msg=f"{name} k={k}")
+            np.testing.assert_array_equal(g_d, o_d, err_msg=f"{name} k={k}")
+            gix.set_exact_selection(True)
+            e_ids, e_d = gix.search(queries, k, wl.w, max(k, wl.m))
+            gix.set_exact_selection(False)
+            np.testing.assert_array_equal(e_ids, o_ids, err_msg=f"{name} k={k} per-query kernel")
+            np.testing.assert_array_equal(e_d, o_d, err_msg=f"{name} k={k} per-query kernel")
+        gix.close()
+
+
+def test_search_without_rerank_ties_and_short_lists(B):
+    """Many equal scores (tiny codes): boundary ties go to the lower row, reported ties to the lower id; fewer scored
+    points than k pads with -1 / +inf."""
+    rng = np.random.default_rng(8)
+    ix = _random_index(rng, n=900, d=32, L=30, r=8, metric=0)
+    ix["B"] = rng.integers(-1, 2, size=ix["B"].shape).astype(np.int8)
+    ix["cluster_offsets"] = np.concatenate([[0, 0, 3, 3, 5], np.linspace(40, 900, 26).astype(np.int64)])
+    q = rng.normal(size=(60, 32)).astype(np.float32)
+    gix = B.Index(**ix)
+    gix.set_rerank(B.RERANK_NONE)
+    oix = O.OracleIndex(ix)
+    for k, w in [(10, 5), (100, 2), (40, 30), (300, 1)]:
+        o_ids, o_d = O.search_no_rerank(oix, q, k, w)
+        g_ids, g_d = gix.search(q, k, w, k)
+        np.testing.assert_array_equal(g_ids, o_ids, err_msg=f"k={k} w={w}")
+        np.testing.assert_array_equal(g_d, o_d, err_msg=f"k={k} w={w}")
+    gix.close()
