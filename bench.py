@@ -129,6 +129,9 @@ def main():
     ap.add_argument("--recall-queries", type=int, default=10000, help="recall is measured on this many queries of the batch")
     ap.add_argument("--batch-sweep", default="", help="comma-separated batch sizes: per-batch latency (p50/p99), "
                     "queries/s and the B_c scoring kernel's GB/s at each, reported under 'batch_sweep'")
+    ap.add_argument("--rerank", choices=["f32", "f16", "none"], default="f32",
+                    help="what the last step reads: the float corpus (the headline configuration), its half-precision "
+                         "copy, or nothing (no re-ranking step)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain 1 GiB elementwise copy (calibrates the HBM byte counters under rocprofv3 --pmc)")
     args = ap.parse_args()
@@ -176,6 +179,8 @@ def main():
 
     gix = binding.Index.from_arrays(ix)
     gix.use_torch_stream()
+    rerank_modes = {"f32": binding.RERANK_F32, "f16": binding.RERANK_F16, "none": binding.RERANK_NONE}
+    gix.set_rerank(rerank_modes[args.rerank])
     nq, k, w, m = wl.nq, wl.k, min(wl.w, wl.L), wl.m
     out = (torch.empty((nq, k), dtype=torch.int64, device=dev), torch.empty((nq, k), dtype=torch.float32, device=dev))
 
@@ -211,6 +216,8 @@ def main():
     # map returned ids (original corpus indices) check: true top-k ids overlap, as a second recall definition
     gt_ids_h = gt_ids.cpu().numpy()
     recall_ids = float(np.mean([len(set(ids_h[i]) & set(gt_ids_h[i])) / k for i in range(0, n_rec, max(1, n_rec // 2000))]))
+    if args.rerank != "f32":
+        recall = recall_ids          # the returned distances are not the exact ones: count by id only
 
     # per-kernel roofline figures from the events recorded over the timed region
     sizes = (ix.cluster_offsets[1:] - ix.cluster_offsets[:-1]).cpu().numpy()
@@ -220,6 +227,9 @@ def main():
     touched[np.unique(sel_all)] = True
     touched_rows = int(sizes[touched].sum())
     models = kernel_models(wl, nq, touched_rows, nq * w)
+    if args.rerank == "f16":
+        bound, amount, peak, unit = models["rerank"]
+        models["rerank"] = (bound, amount / 2, peak, unit)           # two bytes per gathered element
     kernels = []
     for name, (ms, launches) in prof.items():
         if launches == 0:
@@ -244,7 +254,30 @@ def main():
             dom = dict(dom, avg_ms=round(ms / launches, 5), achieved=round(ach, 3), frac=round(ach / peak, 4))
         roofline = {"kernel": dom["kernel"], "bound": dom["bound"], "achieved": dom["achieved"], "peak": dom["peak"],
                     "unit": dom["unit"], "frac": dom["frac"], "avg_ms": dom["avg_ms"],
-                    "traffic": MEASURED_TRAFFIC_GB.get((args.workload, args.scale, dom["kernel"]))}
+                    "traffic": MEASURED_TRAFFIC_GB.get((args.workload, args.scale, dom["kernel"])) if args.rerank == "f32" else None}
+
+    # The other two modes of the last step, timed the same way (fewer steps), with recall by id against the true
+    # neighbours: context for the headline figure, which is always the mode selected by --rerank.
+    other_modes = {}
+    for name, mode in rerank_modes.items():
+        if name == args.rerank:
+            continue
+        gix.set_rerank(mode)
+        for s in range(2):
+            gix.search(batches[s % nb], k, w, m, out=out)
+        torch.cuda.synchronize()
+        Km = max(1, min(K, 10))
+        t0 = time.perf_counter()
+        for s in range(Km):
+            gix.search(batches[s % nb], k, w, m, out=out, asynchronous=True)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        mi = gix.search(queries[:n_rec], k, w, m)[0].cpu().numpy()
+        rec = float(np.mean([len(set(mi[i]) & set(gt_ids_h[i])) / k for i in range(n_rec)]))
+        other_modes[name] = {"queries_per_s": round(nq * Km / dt, 1), "ms_per_step": round(dt / Km * 1e3, 4), "steps": Km,
+                             "recall_at_10_by_id": None if args.random_index else round(rec, 4)}
+        log(f"[bench] rerank mode {name}: {other_modes[name]}")
+    gix.set_rerank(rerank_modes[args.rerank])
 
     sweep = None
     if args.batch_sweep:
@@ -256,17 +289,21 @@ def main():
         from oracle import oracle as O
         t0 = time.time()
         a = ix.numpy()
+        if args.rerank == "f16":
+            a = O.with_half_precision_corpus(a)
         oix = O.OracleIndex(a)
+        o_search = (lambda q: O.search_no_rerank(oix, q, k, w, threads=threads)) if args.rerank == "none" else \
+                   (lambda q: O.search(oix, q, k, w, m, threads=threads))
         qh = queries.cpu().numpy()
         threads = O.default_threads()
-        O.search(oix, qh[:threads * 2], k, w, m, threads=threads)            # warm pass
+        o_search(qh[:threads * 2])            # warm pass
         t1 = time.perf_counter()
         n_cal = min(nq, threads * 8)
-        O.search(oix, qh[:n_cal], k, w, m, threads=threads)
+        o_search(qh[:n_cal])
         rate = n_cal / (time.perf_counter() - t1)
         n_s = int(max(n_cal, min(nq, rate * args.cpu_seconds)))
         t1 = time.perf_counter()
-        o_ids, o_d = O.search(oix, qh[:n_s], k, w, m, threads=threads)
+        o_ids, o_d = o_search(qh[:n_s])
         dt = time.perf_counter() - t1
         cpu_baseline = {"value": round(n_s / dt, 1), "unit": "queries/s", "cores": threads, "kind": "oracle",
                         "sample": f"first {n_s} of the {nq} queries of the timed batch shape, same index, one pass of {dt:.1f}s"}
@@ -295,7 +332,8 @@ def main():
         "config": {"workload": f"{wl.name}: corpus {wl.n}x{wl.d} fp32, {wl.G}-component anisotropic Gaussian mixture, "
                                f"{metric_names[wl.metric]}, L={wl.L} clusters, d'={wl.dp}, r={wl.r} int8, batch {nq}, "
                                f"w={w}, m={m}, k={k}",
-                   "n": wl.n, "d": wl.d, "batch": nq, "L": wl.L, "dp": wl.dp, "r": wl.r, "w": w, "m": m, "k": k},
+                   "n": wl.n, "d": wl.d, "batch": nq, "L": wl.L, "dp": wl.dp, "r": wl.r, "w": w, "m": m, "k": k,
+                   "rerank": {"f32": "float corpus", "f16": "half-precision copy of the corpus", "none": "no re-ranking step"}[args.rerank]},
         "recall_at_10": None if args.random_index else round(recall, 4),
         "recall_at_10_by_id": None if args.random_index else round(recall_ids, 4),
         "index": "random factors and codes (timing only)" if args.random_index else "fitted",
@@ -304,6 +342,7 @@ def main():
         "ms_per_step_with_events_on_every_kernel": round(elapsed_allev / K * 1e3, 4),
         "fallback_queries_per_step": fallback_queries / K,
         "index_build_s": round(build_s, 1),
+        "other_rerank_modes": other_modes,
     }
     if sweep is not None:
         res["batch_sweep"] = sweep
