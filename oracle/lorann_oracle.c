@@ -45,6 +45,10 @@ typedef struct {
     const float *corpus;           /* [n][d] rows in cluster order */
     const int64_t *ids;            /* [n] or NULL */
     const float *sqnorms;          /* [n] squared row norms from oracle_corpus_sqnorms (Euclidean), or NULL */
+    /* Sec. 3.3 as printed: absmax quantization of EACH COLUMN of A_c and B_c.  Both NULL: one step size per
+     * cluster (scale_A, scale_B above).  Both set: scale_A / scale_B are ignored. */
+    const float *col_scale_A;      /* [L][r]  step size of column j of A_c */
+    const float *pt_scale_B;       /* [n]     step size of the column of B_c that belongs to a corpus row */
 } oracle_index;
 
 /* Optional per-stage outputs of oracle_search; any pointer may be NULL. */
@@ -152,6 +156,36 @@ void oracle_stage_a(const int8_t *q8, int32_t dp, int32_t r, const int8_t *A_c /
     *sigma = (float)((double)M / 127.0 * (double)dx * (double)dA * (double)dB);
 }
 
+/* Step 4 with one step size per column of A_c (Sec. 3.3 as printed): the float approximation of r = x^T A is
+ * rho_j = R_j * (Delta_x * DeltaA_cj) - the paper's s (.) r_i32 with s_j = 1 / (c_x c_Aj) - and it is re-quantized
+ * like any vector: z = rint(rho * 127 / |rho|_inf), step size sigma = |rho|_inf / 127.  Every operation is one
+ * IEEE float operation in the order written. */
+void oracle_stage_a_columns(const int8_t *q8, int32_t dp, int32_t r, const int8_t *A_c /* [r][dp] */, float dx,
+                            const float *dA /* [r] */, int32_t *R, int8_t *z, float *sigma)
+{
+    float *rho = (float *)malloc(sizeof(float) * (size_t)r);
+    for (int32_t j = 0; j < r; ++j) {
+        int32_t acc = 0;
+        const int8_t *col = A_c + (size_t)j * dp;
+        for (int32_t i = 0; i < dp; ++i) acc += (int32_t)q8[i] * (int32_t)col[i];
+        R[j] = acc;
+        volatile float sj = dx * dA[j];            /* volatile: no contraction of the two multiplications */
+        rho[j] = (float)acc * sj;
+    }
+    oracle_quantize_query(rho, r, z, sigma);
+    free(rho);
+}
+
+/* Estimated score with one step size per column of B_c (i.e. per corpus point): the multiplier of the integer
+ * score is sigma' * DeltaB_t rounded to float (sigma' = sigma, or 2 sigma for Euclidean), then ONE fused
+ * multiply-add as in oracle_score. */
+float oracle_score_columns(int32_t Y, float sigma, float dB_t, int32_t metric, float sqnorm)
+{
+    if (metric == ORACLE_L2) { volatile float mult = (2.0f * sigma) * dB_t; return fmaf((float)Y, mult, -sqnorm); }
+    volatile float mult = sigma * dB_t;
+    return fmaf((float)Y, mult, -0.0f);
+}
+
 /* ---- Step 5 (Sec. 3.2 prediction y = (x^T A) B in its 8-bit form, Sec. 3.1 Euclidean reduction). ---- */
 /* int32 accumulators of one pair: Y_j = sum_t z_t B[row_j][t]. */
 void oracle_pair_accumulators(const int8_t *z, int32_t r, const int8_t *B_c /* [m_c][r] */, int64_t m_c, int32_t *Y)
@@ -236,7 +270,9 @@ static void search_one(const oracle_index *ix, const float *q, int32_t k, int32_
     for (int32_t j = 0; j < w; ++j) {                                      /* steps 4-5 per selected cluster */
         const int32_t c = sel[j];
         const int64_t off = ix->offsets[c], mc = ix->offsets[c + 1] - off;
-        oracle_stage_a(q8, dp, r, ix->A + (size_t)c * r * dp, dx, ix->scale_A[c], ix->scale_B[c], R, z, &sigma);
+        const int columns = ix->col_scale_A && ix->pt_scale_B;
+        if (columns) oracle_stage_a_columns(q8, dp, r, ix->A + (size_t)c * r * dp, dx, ix->col_scale_A + (size_t)c * r, R, z, &sigma);
+        else oracle_stage_a(q8, dp, r, ix->A + (size_t)c * r * dp, dx, ix->scale_A[c], ix->scale_B[c], R, z, &sigma);
         if (dump) {
             if (dump->R) memcpy(dump->R + ((size_t)qi * w + j) * r, R, sizeof(int32_t) * (size_t)r);
             if (dump->z) memcpy(dump->z + ((size_t)qi * w + j) * r, z, (size_t)r);
@@ -247,7 +283,8 @@ static void search_one(const oracle_index *ix, const float *q, int32_t k, int32_
             float sq = 0.0f;   /* Sec. 3.1: the norms |c_j|^2 "can be precomputed" */
             if (ix->metric == ORACLE_L2)
                 sq = ix->sqnorms ? ix->sqnorms[off + t] : oracle_row_sqnorm(ix->corpus + (size_t)(off + t) * d, d);
-            sc[pos].key = oracle_score(Y[t], sigma, ix->metric, sq);
+            sc[pos].key = columns ? oracle_score_columns(Y[t], sigma, ix->pt_scale_B[off + t], ix->metric, sq)
+                                  : oracle_score(Y[t], sigma, ix->metric, sq);
             sc[pos].idx = off + t;
             ++pos;
         }

@@ -20,7 +20,8 @@ class _Index(C.Structure):
     _fields_ = [("metric", C.c_int32), ("n", C.c_int64), ("d", C.c_int32), ("dp", C.c_int32), ("r", C.c_int32),
                 ("L", C.c_int32), ("centroids", C.c_void_p), ("P", C.c_void_p), ("A", C.c_void_p),
                 ("B", C.c_void_p), ("scale_A", C.c_void_p), ("scale_B", C.c_void_p), ("offsets", C.c_void_p),
-                ("corpus", C.c_void_p), ("ids", C.c_void_p), ("sqnorms", C.c_void_p)]
+                ("corpus", C.c_void_p), ("ids", C.c_void_p), ("sqnorms", C.c_void_p),
+                ("col_scale_A", C.c_void_p), ("pt_scale_B", C.c_void_p)]
 
 
 class _Dump(C.Structure):
@@ -40,6 +41,8 @@ def lib():
         _lib.oracle_score.restype = C.c_float
         _lib.oracle_score.argtypes = [C.c_int32, C.c_float, C.c_int32, C.c_float]
         _lib.oracle_exact_dissim.restype = C.c_float
+        _lib.oracle_score_columns.restype = C.c_float
+        _lib.oracle_score_columns.argtypes = [C.c_int32, C.c_float, C.c_float, C.c_int32, C.c_float]
         _lib.oracle_load_file.restype = C.POINTER(_Index)
         _lib.oracle_load_file.argtypes = [C.c_char_p]
         _lib.oracle_free_loaded.restype = None
@@ -80,10 +83,16 @@ class OracleIndex:
         # optional: the rows the re-rank reads, when they are not the corpus the index was built from
         self.rerank_corpus = _c(ix.get("rerank_corpus"), np.float32)
         assert self.rerank_corpus is None or self.rerank_corpus.shape == self.corpus.shape
+        # optional: one step size per column of A_c and of B_c (Sec. 3.3 as printed) instead of one per cluster
+        self.scale_A_columns = _c(ix.get("scale_A_columns"), np.float32)
+        self.scale_B_points = _c(ix.get("scale_B_points"), np.float32)
+        assert (self.scale_A_columns is None) == (self.scale_B_points is None)
+        if self.scale_A_columns is not None:
+            assert self.scale_A_columns.shape == (self.L, self.r) and self.scale_B_points.shape == (self.n,)
         self.c = _Index(self.metric, self.n, self.d, self.dp, self.r, self.L, _p(self.centroids), _p(self.P),
                         _p(self.A), _p(self.B), _p(self.scale_A), _p(self.scale_B), _p(self.offsets),
                         _p(self.corpus if self.rerank_corpus is None else self.rerank_corpus), _p(self.ids),
-                        _p(self.sqnorms))
+                        _p(self.sqnorms), _p(self.scale_A_columns), _p(self.scale_B_points))
 
 
 def _from_file(path) -> "OracleIndex":
@@ -235,6 +244,23 @@ def stage_a(q8, A_c, dx, dA, dB):
     lib().oracle_stage_a(_p(q8), C.c_int32(dp), C.c_int32(r), _p(A_c), C.c_float(dx), C.c_float(dA), C.c_float(dB),
                          _p(R), _p(z), C.byref(sg))
     return R, z, np.float32(sg.value)
+
+
+def stage_a_columns(q8, A_c, dx, dA_cols):
+    """Step 4 with one step size per column of A_c.  Returns (R int32 [r], z int8 [r], sigma f32)."""
+    q8, A_c, dA_cols = _c(q8, np.int8), _c(A_c, np.int8), _c(dA_cols, np.float32)
+    r, dp = A_c.shape
+    assert dA_cols.shape == (r,)
+    R = np.empty(r, np.int32)
+    z = np.empty(r, np.int8)
+    sg = C.c_float(0)
+    lib().oracle_stage_a_columns(_p(q8), C.c_int32(dp), C.c_int32(r), _p(A_c), C.c_float(dx), _p(dA_cols), _p(R), _p(z),
+                                 C.byref(sg))
+    return R, z, np.float32(sg.value)
+
+
+def score_columns(Y: int, sigma: float, dB_t: float, metric: int, sqnorm: float = 0.0) -> np.float32:
+    return np.float32(lib().oracle_score_columns(int(Y), float(sigma), float(dB_t), int(metric), float(sqnorm)))
 
 
 def pair_accumulators(z, B_c):

@@ -23,7 +23,7 @@ LORANN_OK, LORANN_E_INVAL, LORANN_E_NOMEM, LORANN_E_DEVICE, LORANN_E_UNSUPPORTED
 
 EXPORTS = ["lorann_load_index", "lorann_load_index_file", "lorann_search", "lorann_search_async", "lorann_free_index", "lorann_last_error", "lorann_set_stream",
            "lorann_search_stages", "lorann_profile_enable", "lorann_profile_get", "lorann_set_exact_selection",
-           "lorann_profile_fallback_queries", "lorann_set_rerank"]
+           "lorann_profile_fallback_queries", "lorann_set_rerank", "lorann_set_column_scales"]
 RERANK_F32, RERANK_F16, RERANK_NONE = 0, 1, 2
 
 
@@ -69,6 +69,8 @@ def lib() -> C.CDLL:
         L.lorann_set_stream.argtypes = [vp, vp]
         L.lorann_set_exact_selection.restype = C.c_int
         L.lorann_set_exact_selection.argtypes = [vp, i32]
+        L.lorann_set_column_scales.restype = C.c_int
+        L.lorann_set_column_scales.argtypes = [vp, vp, vp]
         L.lorann_set_rerank.restype = C.c_int
         L.lorann_set_rerank.argtypes = [vp, i32]
         L.lorann_profile_enable.restype = C.c_int
@@ -104,7 +106,8 @@ def _prep(a, dtype_np, dtype_t):
 class Index:
     """A loaded index (owns device memory inside the library)."""
 
-    def __init__(self, metric, n, d, dp, r, L, centroids, P, A, B, scale_A, scale_B, cluster_offsets, corpus, ids=None, **_):
+    def __init__(self, metric, n, d, dp, r, L, centroids, P, A, B, scale_A, scale_B, cluster_offsets, corpus, ids=None,
+                 scale_A_columns=None, scale_B_points=None, **_):
         self._h = C.c_void_p()
         self.metric, self.n, self.d, self.dp, self.r, self.L = int(metric), int(n), int(d), int(dp), int(r), int(L)
         T = torch
@@ -118,6 +121,8 @@ class Index:
         ptrs = [p for _, p in keep]
         _check(lib().lorann_load_index(C.byref(self._h), self.metric, self.n, self.d, self.dp, self.r, self.L, *ptrs))
         del keep
+        if scale_A_columns is not None or scale_B_points is not None:
+            self.set_column_scales(scale_A_columns, scale_B_points)
 
     @classmethod
     def from_arrays(cls, ix) -> "Index":
@@ -125,6 +130,9 @@ class Index:
         d = ix if isinstance(ix, dict) else {f: getattr(ix, f) for f in
                                              ("metric", "n", "d", "dp", "r", "L", "centroids", "P", "A", "B", "scale_A",
                                               "scale_B", "cluster_offsets", "corpus", "ids")}
+        if not isinstance(ix, dict):
+            d["scale_A_columns"] = getattr(ix, "scale_A_columns", None)
+            d["scale_B_points"] = getattr(ix, "scale_B_points", None)
         return cls(**d)
 
     @classmethod
@@ -202,6 +210,14 @@ class Index:
 
     def set_exact_selection(self, on: bool):
         _check(lib().lorann_set_exact_selection(self._h, 1 if on else 0))
+
+    def set_column_scales(self, scale_A_columns, scale_B_points):
+        """One step size per column of A_c ([L, r]) and per corpus row ([n]) instead of one per cluster; None, None
+        goes back to the per-cluster step sizes given at load time."""
+        T = torch
+        ka, pa = _prep(scale_A_columns, np.float32, T.float32 if T else None)
+        kb, pb = _prep(scale_B_points, np.float32, T.float32 if T else None)
+        _check(lib().lorann_set_column_scales(self._h, pa, pb))
 
     def set_rerank(self, mode: int):
         """RERANK_F32 (default), RERANK_F16 (half-precision copy of the corpus) or RERANK_NONE (no re-ranking step)."""

@@ -42,6 +42,8 @@ class IndexArrays:
     cluster_offsets: torch.Tensor  # [L + 1] int64
     corpus: torch.Tensor           # [n, d] f32, rows in cluster order
     ids: torch.Tensor              # [n] int64: original index of each row
+    scale_A_columns: torch.Tensor | None = None   # [L, r] f32: one step size per column of A_c (Sec. 3.3 as printed);
+    scale_B_points: torch.Tensor | None = None    # [n] f32: one per column of B_c, i.e. per corpus row; both or neither
     A_f32: torch.Tensor | None = None   # [L, r, dp] unquantized factors (kept on request, for tests)
     B_f32: torch.Tensor | None = None   # [n, r]
 
@@ -132,12 +134,25 @@ def _absmax_int8(x: torch.Tensor):
     return codes, float(delta)
 
 
+def _absmax_int8_rows(x: torch.Tensor):
+    """Absmax quantization with one scalar per row of x [rows, len]: (codes int8, Delta [rows] = max|row| / 127)."""
+    a = x.abs().amax(dim=1).to(torch.float32)
+    delta = a / 127.0
+    safe = torch.where(delta > 0, delta, torch.ones_like(delta))
+    codes = torch.round(x.to(torch.float32) / safe[:, None]).clamp_(-127, 127).to(torch.int8)
+    codes[delta == 0] = 0
+    return codes, delta
+
+
 def build_index(corpus: torch.Tensor, wl: Workload, *, exact_svd: bool = False, rotate: bool = True,
                 keep_float: bool = False, fit_dtype: torch.dtype = torch.float64,
-                train: torch.Tensor | None = None, progress=None) -> IndexArrays:
+                train: torch.Tensor | None = None, progress=None, column_scales: bool = False) -> IndexArrays:
     """Build the index arrays for `corpus` [n, d] under workload `wl` on corpus.device.
 
     `train` overrides the RRR training set (default: a seeded sample of min(n, wl.n_train) corpus rows).
+    `column_scales`: quantize every column of A_c and of B_c with its own step size (Sec. 3.3 as printed) instead
+    of one step size per cluster and matrix; the codes differ, and scale_A / scale_B then only hold the largest of
+    the column step sizes (the search ignores them once the column scales are set).
     """
     dev = corpus.device
     n, d = corpus.shape
@@ -197,6 +212,8 @@ def build_index(corpus: torch.Tensor, wl: Workload, *, exact_svd: bool = False, 
     B_q = torch.zeros(n, r, dtype=torch.int8, device=dev)
     sA = torch.zeros(L, dtype=torch.float32)
     sB = torch.zeros(L, dtype=torch.float32)
+    sA_cols = torch.zeros(L, r, dtype=torch.float32, device=dev) if column_scales else None
+    sB_pts = torch.zeros(n, dtype=torch.float32, device=dev) if column_scales else None
     A_f = torch.zeros(L, r, dp, dtype=torch.float32, device=dev) if keep_float else None
     B_f = torch.zeros(n, r, dtype=torch.float32, device=dev) if keep_float else None
     Pd = None if P is None else P.to(fit_dtype)
@@ -226,8 +243,13 @@ def build_index(corpus: torch.Tensor, wl: Workload, *, exact_svd: bool = False, 
         Bf = torch.zeros(m_l, r, dtype=torch.float32, device=dev)
         Af[:rr] = A.T.to(torch.float32)
         Bf[:, :rr] = V.to(torch.float32)
-        A_q[l], sA[l] = _absmax_int8(Af)
-        B_q[c0:c1], sB[l] = _absmax_int8(Bf)
+        if column_scales:
+            A_q[l], sA_cols[l] = _absmax_int8_rows(Af)          # rows of A_c^T are the columns of A_c
+            B_q[c0:c1], sB_pts[c0:c1] = _absmax_int8_rows(Bf)    # rows of B_c^T are the columns of B_c
+            sA[l], sB[l] = float(sA_cols[l].max()), float(sB_pts[c0:c1].max())
+        else:
+            A_q[l], sA[l] = _absmax_int8(Af)
+            B_q[c0:c1], sB[l] = _absmax_int8(Bf)
         if keep_float:
             A_f[l], B_f[c0:c1] = Af, Bf
         if (l + 1) % 128 == 0:
@@ -235,7 +257,8 @@ def build_index(corpus: torch.Tensor, wl: Workload, *, exact_svd: bool = False, 
 
     return IndexArrays(metric=metric, n=n, d=d, dp=dp, r=r, L=L, centroids=centroids.contiguous(), P=P,
                        A=A_q, B=B_q, scale_A=sA.to(dev), scale_B=sB.to(dev), cluster_offsets=offsets,
-                       corpus=corpus_sorted, ids=order.to(torch.int64).contiguous(), A_f32=A_f, B_f32=B_f)
+                       corpus=corpus_sorted, ids=order.to(torch.int64).contiguous(), scale_A_columns=sA_cols,
+                       scale_B_points=sB_pts, A_f32=A_f, B_f32=B_f)
 
 
 def random_index(corpus: torch.Tensor, wl: Workload) -> IndexArrays:

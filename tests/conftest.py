@@ -37,3 +37,15 @@ def small_indexes(small_workloads):
         ix = build_index(corpus, wl, keep_float=True)
         out[name] = (wl, ix, corpus.numpy(), queries.numpy())
     return out
+
+
+@pytest.fixture(scope="session")
+def small_indexes_columns(small_workloads):
+    """The same workloads quantized with one step size per column of A_c and of B_c (Sec. 3.3 as printed)."""
+    from paper_2410_18926_amd.synth import make_dataset, build_index
+    out = {}
+    for name, wl in small_workloads.items():
+        corpus, queries = make_dataset(wl)
+        ix = build_index(corpus, wl, keep_float=True, column_scales=True)
+        out[name] = (wl, ix, corpus.numpy(), queries.numpy())
+    return out

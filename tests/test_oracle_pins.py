@@ -216,6 +216,135 @@ def test_quantized_scores_approximate_true_inner_products(small_indexes):
     assert np.mean(cors) > 0.8
 
 
+# ------------------------------------------------------------------ Sec. 3.3 as printed: one step size per column
+def test_column_scales_stage_a_hand_example():
+    """r_f32 = s (.) r_i32 with s_j = Delta_x * DeltaA_j, then absmax re-quantization (Sec. 3.3).  Numbers chosen so
+    that every float operation is exact: |rho|_inf = 127 / 16, hence z = rint(16 rho) with two exact ties."""
+    q8 = np.array([127, -64, 10, 0], np.int8)
+    A_c = np.array([[64, 0, 0, 0],            # column 0 of A_c: R_0 = 127 * 64 = 8128
+                    [0, -10, 0, 5],           # column 1:        R_1 = 640
+                    [1, 2, 0, 0],             # column 2:        R_2 = 127 - 128 = -1
+                    [0, 1, 0, 9]], np.int8)   # column 3:        R_3 = -64
+    dx = 2.0 ** -7
+    dA = np.array([2.0 ** -3, 2.0 ** -5, 2.0 ** -1, 2.0 ** -4], np.float32)
+    R, z, sigma = O.stage_a_columns(q8, A_c, dx, dA)
+    assert R.tolist() == [8128, 640, -1, -64]
+    # rho = R * 2^-7 * dA = [127/16, 640/4096, -1/256, -64/2048]; 16 rho = [127, 2.5, -1/16, -0.5]
+    assert z.tolist() == [127, 2, 0, 0]       # 2.5 -> 2 and -0.5 -> -0 (ties to even)
+    assert sigma == np.float32(2.0 ** -4)
+    R, z, sigma = O.stage_a_columns(np.zeros(4, np.int8), A_c, dx, dA)
+    assert z.tolist() == [0, 0, 0, 0] and sigma == 0.0
+    # the column step sizes are applied per column, not per row of the stored A_c^T: swap two and the codes move
+    R, z, _ = O.stage_a_columns(q8, A_c, dx, dA[[1, 0, 2, 3]])
+    assert z.tolist() == [127, 40, 0, -2]     # rho = [127/64, 640/1024, -1/256, -64/2048]; 64 rho = [127, 40, -1/4, -2]
+
+
+def test_column_scales_requantization_is_correctly_rounded():
+    """Random pairs: z_j is the integer nearest to 127 rho_j / |rho|_inf (rho from exact integer R and the float
+    step sizes, evaluated with rationals), up to the float rounding of the two multiplications."""
+    g = np.random.default_rng(11)
+    for _ in range(50):
+        dp, r = 24, 8
+        q8 = g.integers(-127, 128, dp).astype(np.int8)
+        A_c = g.integers(-127, 128, (r, dp)).astype(np.int8)
+        dx = np.float32(g.uniform(1e-3, 1e-1))
+        dA = g.uniform(1e-3, 1.0, r).astype(np.float32)
+        R, z, sigma = O.stage_a_columns(q8, A_c, dx, dA)
+        assert R.tolist() == [int(sum(int(a) * int(b) for a, b in zip(q8, A_c[j]))) for j in range(r)]
+        rho = [Fraction(int(R[j])) * Fraction(float(dx)) * Fraction(float(dA[j])) for j in range(r)]
+        M = max(abs(v) for v in rho)
+        assert abs(Fraction(float(sigma)) - M / 127) <= M / 127 * Fraction(1, 2 ** 21)
+        for j in range(r):
+            assert abs(Fraction(int(z[j])) - 127 * rho[j] / M) <= Fraction(1, 2) + Fraction(1, 10 ** 4)
+        assert max(abs(int(v)) for v in z) == 127
+
+
+def test_column_scales_score_is_scale_product_then_one_fma():
+    assert O.score_columns(1000, 0.375, 0.0625, IP) == np.float32(23.4375)
+    assert O.score_columns(1000, 0.375, 0.0625, COS) == np.float32(23.4375)
+    assert O.score_columns(1000, 0.375, 0.0625, L2, 5.5) == np.float32(41.375)
+    g = np.random.default_rng(12)
+    for _ in range(200):
+        Y = int(g.integers(-500000, 500000))
+        sg, dB, nrm = np.float32(g.uniform(1e-4, 1)), np.float32(g.uniform(1e-4, 1)), np.float32(g.uniform(0, 50))
+        mult = np.float32(np.float32(2) * sg) * dB                              # one rounding
+        exact = Fraction(Y) * Fraction(float(mult)) - Fraction(float(nrm))      # then one for the multiply-add
+        got = O.score_columns(Y, sg, dB, L2, nrm)
+        lo, hi = np.nextafter(got, np.float32(-np.inf)), np.nextafter(got, np.float32(np.inf))
+        assert abs(Fraction(float(got)) - exact) <= min(abs(Fraction(float(lo)) - exact), abs(Fraction(float(hi)) - exact))
+
+
+def test_column_scales_exact_case_equals_brute_force():
+    """Factors that the codes represent exactly, with a different power-of-two step size for every column of every
+    A_c and for every corpus row: the estimated scores are then the exact inner products <A_c^T q, x_t>, so the search
+    without re-ranking must order the points as brute force over rationals does.  A step size taken from the wrong
+    column, cluster or row breaks the order."""
+    g = np.random.default_rng(13)
+    d, L, per = 16, 5, 24
+    n = L * per
+    f = g.integers(0, 3, size=(L, d))                          # real A_c = diag(2^f_cj)
+    f[:, 0] = 2
+    e = g.integers(-6, 7, size=n)                              # real row t = 2^e_t * b_t
+    b = g.integers(-127, 128, size=(n, d)).astype(np.int64)
+    b[:, 1] = 127                                              # every row's absmax code is 127
+    A = np.zeros((L, d, d), np.int8)
+    A[:, np.arange(d), np.arange(d)] = 64
+    ix = dict(metric=IP, n=n, d=d, dp=d, r=d, L=L, centroids=g.normal(size=(L, d)).astype(np.float32), P=None, A=A,
+              B=b.astype(np.int8), scale_A=np.ones(L, np.float32), scale_B=np.ones(L, np.float32),
+              scale_A_columns=(2.0 ** f / 64).astype(np.float32), scale_B_points=(2.0 ** e).astype(np.float32),
+              cluster_offsets=np.arange(L + 1, dtype=np.int64) * per,
+              corpus=(b * 2.0 ** e[:, None]).astype(np.float32), ids=None)
+    # queries: q_j 2^f_cj / 4 must be an integer for every cluster, and the largest |q_j 2^f_cj| is 127 * 4 (at j = 0)
+    Q = (g.integers(-31, 32, size=(12, d)) * 4).astype(np.int64)
+    Q[:, 0] = 127
+    ids, dists = O.search_no_rerank(O.OracleIndex(ix), Q.astype(np.float32), 9, L)
+    for qi in range(len(Q)):
+        sc = []
+        for t in range(n):
+            c = t // per
+            sc.append(sum(Fraction(int(Q[qi, j])) * 2 ** int(f[c, j]) * int(b[t, j]) for j in range(d)) * Fraction(2) ** int(e[t]))
+        order = sorted(range(n), key=lambda t: (-sc[t], t))[:9]
+        assert ids[qi].tolist() == order, qi
+        assert [Fraction(float(v)) for v in dists[qi]] == [-sc[t] for t in order]
+
+
+def test_column_scales_track_float_model_and_beat_cluster_scales(small_indexes, small_indexes_columns):
+    """The bound of test_quantized_scores_track_float_model_within_quantization_bound, with the de-quantized factors
+    and the half steps of the column-wise scheme; and the reason the paper quantizes column-wise: on the same fitted
+    factors the estimated scores are closer to the unquantized model than with one step size per cluster."""
+    for name, (wl, ix, corpus, queries) in small_indexes_columns.items():
+        a = ix.numpy()
+        oix = O.OracleIndex(a)
+        _, _, st = O.search(oix, queries, wl.k, wl.w, wl.m, stages=True)
+        a1 = small_indexes[name][1].numpy()
+        _, _, st1 = O.search(O.OracleIndex(a1), queries, wl.k, wl.w, wl.m, stages=True)
+        np.testing.assert_array_equal(st["sel"], st1["sel"])         # routing does not depend on the factors
+        err_cols, err_clus = [], []
+        for qi in range(0, len(queries), 7):
+            for j in range(wl.w):
+                c = int(st["sel"][qi, j])
+                o0, o1 = int(a["cluster_offsets"][c]), int(a["cluster_offsets"][c + 1])
+                if o1 == o0:
+                    continue
+                dx = float(st["dx"][qi])
+                A_real = (a["scale_A_columns"][c].astype(np.float64)[:, None] * a["A"][c].astype(np.float64)).T   # [dp][r]
+                B_real = (a["scale_B_points"][o0:o1].astype(np.float64)[:, None] * a["B"][o0:o1].astype(np.float64)).T
+                qp = st["qproj"][qi].astype(np.float64)
+                y_ref = (qp @ A_real) @ B_real
+                sg = float(st["sigma"][qi, j])
+                err_r = 0.5 * dx * np.abs(A_real).sum(0) + 0.5 * sg
+                bound = err_r @ np.abs(B_real)
+                Y = O.pair_accumulators(st["z"][qi, j], a["B"][o0:o1]).astype(np.float64)
+                s_hat = sg * a["scale_B_points"][o0:o1].astype(np.float64) * Y
+                assert np.all(np.abs(s_hat - y_ref) <= bound * (1 + 1e-4) + 1e-5 * np.abs(y_ref).max()), name
+                # both schemes against the UNQUANTIZED fitted model
+                y_float = (qp @ a["A_f32"][c].astype(np.float64).T) @ a["B_f32"][o0:o1].astype(np.float64).T
+                Y1 = O.pair_accumulators(st1["z"][qi, j], a1["B"][o0:o1]).astype(np.float64)
+                err_cols.append(np.abs(s_hat - y_float).mean())
+                err_clus.append(np.abs(float(st1["sigma"][qi, j]) * Y1 - y_float).mean())
+        assert np.mean(err_cols) < np.mean(err_clus), (name, np.mean(err_cols), np.mean(err_clus))
+
+
 # ------------------------------------------------------------------ Sec. 2.2 / 3.1 / 4.1: routing, selection, re-rank
 def test_projection_is_matrix_product():
     """Sec. 4.1: x' = W_s^T x."""
