@@ -136,6 +136,21 @@ int lorann_set_stream(lorann_index *ix, void *hip_stream);
 int lorann_set_exact_selection(lorann_index *ix, int32_t on);
 
 /*
+ * lorann_set_column_scales - column-wise quantization, as Sec. 3.3 prints it: absmax quantization applied to EACH
+ * COLUMN of A_c and of B_c, instead of the one step size per cluster and matrix that lorann_load_index takes.
+ *   scale_A_columns  [L][r] float: real A_c[i][j] ~= scale_A_columns[c][j] * A[c][j][i]
+ *   scale_B_points   [n] float: real code of corpus row t ~= scale_B_points[t] * B[t][:] (a column of B_c)
+ * The codes given at load time must have been produced with these step sizes; scale_A / scale_B are then ignored.
+ * The arithmetic of the first product's re-quantization changes with it (the step sizes no longer cancel):
+ *   rho_j = R_j * (Delta_x * scale_A_columns[c][j]);  z = rint(rho * (127 / |rho|_inf)), clamped to +-127;
+ *   sigma = |rho|_inf / 127;  score of point t = fma(Y_t, sigma' * scale_B_points[t], -bias_t)  with sigma' = sigma
+ *   (2 sigma for LORANN_L2) - each operation one IEEE float operation in the order written.
+ * NULL, NULL returns to the per-cluster step sizes.  The arrays are copied (host or device pointers).
+ * Errors: LORANN_E_INVAL for one NULL of two or a negative / non-finite step size (index unchanged).
+ */
+int lorann_set_column_scales(lorann_index *ix, const float *scale_A_columns, const float *scale_B_points);
+
+/*
  * lorann_set_rerank - choose what the last step of later searches reads (Sec. 2.2 re-ranking; default F32).
  *   LORANN_RERANK_F32   the float corpus given at load time;
  *   LORANN_RERANK_F16   a half-precision (IEEE binary16, round to nearest even) copy of it, half the bytes of the

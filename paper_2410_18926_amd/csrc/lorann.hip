@@ -100,6 +100,8 @@ struct lorann_index {
     int8_t* A = nullptr;            // [L][r][dp]
     int8_t* Bp = nullptr;           // [n][r_pad] codes padded with zeros to r_pad bytes
     float *sA = nullptr, *sB = nullptr;
+    float* sA_cols = nullptr;       // [L][r] column-wise quantization: step size of every column of A_c (else NULL)
+    float* sB_pts = nullptr;        // [n]    ... and of every point's code
     int64_t* off = nullptr;         // [L+1]
     float* corpus = nullptr;        // [n][d]
     _Float16* corpus_h = nullptr;   // [n][d] binary16 copy, made when the half-precision re-rank is first selected
@@ -125,7 +127,7 @@ struct lorann_index {
 namespace {
 
 void free_all(lorann_index* ix) {
-    void* ptrs[] = {ix->centroids, ix->cent_sqnorm, ix->cent_nrm_f32, ix->cent_bf16, ix->Pt, ix->A, ix->Bp, ix->sA, ix->sB, ix->off, ix->corpus, ix->corpus_h, ix->ids, ix->sqnorm};
+    void* ptrs[] = {ix->centroids, ix->cent_sqnorm, ix->cent_nrm_f32, ix->cent_bf16, ix->Pt, ix->A, ix->Bp, ix->sA, ix->sB, ix->sA_cols, ix->sB_pts, ix->off, ix->corpus, ix->corpus_h, ix->ids, ix->sqnorm};
     for (void* p : ptrs) if (p) (void)hipFree(p);
     DevBuf* bufs[] = {&ix->qproj, &ix->qbf, &ix->q8, &ix->dx, &ix->gscore, &ix->sel, &ix->count, &ix->rank_in_bucket, &ix->qrank, &ix->qorder, &ix->qorder2, &ix->off0, &ix->base_tab, &ix->bucket_off, &ix->tile_off,
                       &ix->unit_off, &ix->slot_of_pos, &ix->pos_of_slot, &ix->Z, &ix->sigma, &ix->cand, &ix->tau,
@@ -326,8 +328,13 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
         // about five tiles of 16 pairs per wavefront on average; skewed clusters just loop longer
         const int64_t avg_tiles = npairs / 16 / L + 1;
         const dim3 grid((unsigned)L, (unsigned)std::max<int64_t>(1, std::min<int64_t>(32, (avg_tiles + 19) / 20)));
-#define LAUNCH_SA(RT_, RES_) hipLaunchKernelGGL((k_stage_a<RT_, RES_>), grid, dim3(256), 0, s, ix->q8.as<int8_t>(), ix->dx.as<float>(), ix->A, ix->sA, ix->sB, \
-                                               ix->bucket_off.as<int32_t>(), ix->slot_of_pos.as<int32_t>(), L, dp, ix->r, w, ix->Z.as<int8_t>(), ix->sigma.as<float>())
+#define LAUNCH_SA(RT_, RES_)                                                                                   \
+    do {                                                                                                       \
+        if (ix->sA_cols) hipLaunchKernelGGL((k_stage_a<RT_, RES_, true>), grid, dim3(256), 0, s, ix->q8.as<int8_t>(), ix->dx.as<float>(), ix->A, ix->sA_cols, ix->sB, \
+                                            ix->bucket_off.as<int32_t>(), ix->slot_of_pos.as<int32_t>(), L, dp, ix->r, w, ix->Z.as<int8_t>(), ix->sigma.as<float>()); \
+        else hipLaunchKernelGGL((k_stage_a<RT_, RES_, false>), grid, dim3(256), 0, s, ix->q8.as<int8_t>(), ix->dx.as<float>(), ix->A, ix->sA, ix->sB, \
+                                ix->bucket_off.as<int32_t>(), ix->slot_of_pos.as<int32_t>(), L, dp, ix->r, w, ix->Z.as<int8_t>(), ix->sigma.as<float>()); \
+    } while (0)
         if (r_pad == 32) { if (dp <= 256) LAUNCH_SA(2, true); else LAUNCH_SA(2, false); }
         else { if (dp <= 256) LAUNCH_SA(4, true); else LAUNCH_SA(4, false); }
 #undef LAUNCH_SA
@@ -336,7 +343,7 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
     SelectArgs sa_;
     sa_.qlist = nullptr; sa_.qcount = nullptr; sa_.sel = ix->sel.as<int32_t>(); sa_.pos_of_slot = ix->pos_of_slot.as<int32_t>();
     sa_.Z = ix->Z.as<int8_t>(); sa_.sigma = ix->sigma.as<float>(); sa_.Bp = ix->Bp; sa_.off = ix->off;
-    sa_.sqnorm = ix->metric == LORANN_L2 ? ix->sqnorm : nullptr; sa_.cand = ix->cand.as<int32_t>(); sa_.w = w; sa_.m = m;
+    sa_.sqnorm = ix->metric == LORANN_L2 ? ix->sqnorm : nullptr; sa_.pt_scale = ix->sB_pts; sa_.cand = ix->cand.as<int32_t>(); sa_.w = w; sa_.m = m;
     if (ix->force_exact) {
         Prof p(ix, K_SELECT_M);
         const unsigned grid = (unsigned)std::min<int64_t>(nq, 65536);
@@ -354,12 +361,15 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
             ScoreArgs sc;
             sc.Bp = ix->Bp; sc.Z = ix->Z.as<int8_t>(); sc.sigma = ix->sigma.as<float>(); sc.off = ix->off;
             sc.bucket_off = ix->bucket_off.as<int32_t>(); sc.unit_off = ix->unit_off.as<int32_t>();
-            sc.sqnorm = l2 ? ix->sqnorm : nullptr; sc.pmax = ix->pmax.as<uint32_t>(); sc.L = L; sc.chunk_tiles = kChunkTiles;
+            sc.sqnorm = l2 ? ix->sqnorm : nullptr; sc.pt_scale = ix->sB_pts; sc.pmax = ix->pmax.as<uint32_t>(); sc.L = L; sc.chunk_tiles = kChunkTiles;
             // few pairs per cluster: the kernel streams the codes of the touched clusters, one wavefront per cluster
             const bool stream = npairs <= (int64_t)16 * L;
 #define LAUNCH_PM(KS_, L2_)                                                                                          \
     do {                                                                                                             \
-        if (stream) hipLaunchKernelGGL((k_pair_max<1, KS_, L2_, 8 / KS_, true, 4>), dim3((unsigned)((L + 3) / 4)), dim3(256), 0, s, sc); \
+        if (ix->sB_pts) {                                                                                            \
+            if (stream) hipLaunchKernelGGL((k_pair_max<1, KS_, L2_, 8 / KS_, true, 4, true>), dim3((unsigned)((L + 3) / 4)), dim3(256), 0, s, sc); \
+            else hipLaunchKernelGGL((k_pair_max<kNZ, KS_, L2_, 4, false, 4, true>), dim3(2048), dim3(256), 0, s, sc); \
+        } else if (stream) hipLaunchKernelGGL((k_pair_max<1, KS_, L2_, 8 / KS_, true, 4>), dim3((unsigned)((L + 3) / 4)), dim3(256), 0, s, sc); \
         else hipLaunchKernelGGL((k_pair_max<kNZ, KS_, L2_, 4, false, 4>), dim3(2048), dim3(256), 0, s, sc);   /* persistent: 8192 wavefronts stride over the work items */ \
     } while (0)
             if (ks == 1) { if (l2) LAUNCH_PM(1, true); else LAUNCH_PM(1, false); }
@@ -370,7 +380,7 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
             Prof p(ix, K_SELECT_QUERY);
             QuerySelectArgs qa;
             qa.sel = ix->sel.as<int32_t>(); qa.pos_of_slot = ix->pos_of_slot.as<int32_t>(); qa.pmax = ix->pmax.as<uint32_t>();
-            qa.Z = ix->Z.as<int8_t>(); qa.sigma = ix->sigma.as<float>(); qa.Bp = ix->Bp; qa.off = ix->off; qa.sqnorm = l2 ? ix->sqnorm : nullptr;
+            qa.Z = ix->Z.as<int8_t>(); qa.sigma = ix->sigma.as<float>(); qa.Bp = ix->Bp; qa.off = ix->off; qa.sqnorm = l2 ? ix->sqnorm : nullptr; qa.pt_scale = ix->sB_pts;
             qa.cand = ix->cand.as<int32_t>(); qa.tau = ix->tau.as<float>(); qa.n_kept = ix->n_kept.as<int32_t>(); qa.qkey = ix->qkey.as<int32_t>();
             qa.fb_list = ix->fb_list.as<int32_t>(); qa.fb_count = ix->count.as<int32_t>() + 2 * L; qa.qorder = ix->qorder.as<int32_t>(); qa.nq = (int)nq; qa.w = w; qa.m = m; qa.cap = select_query_cap(m);
             const size_t qlds = (size_t)qa.cap * 8;
@@ -803,6 +813,31 @@ int lorann_search_async(lorann_index* ix, const float* queries, int64_t nq, int3
 int lorann_search_stages(lorann_index* ix, const float* queries, int64_t nq, int32_t k, int32_t w, int32_t m,
                          int64_t* out_ids, float* out_dists, const lorann_stages* st) {
     return search_impl(ix, queries, nq, k, w, m, out_ids, out_dists, st);
+}
+
+int lorann_set_column_scales(lorann_index* ix, const float* scale_A_columns, const float* scale_B_points) {
+    if (!ix) return fail(LORANN_E_INVAL, "index is NULL");
+    if ((scale_A_columns == nullptr) != (scale_B_points == nullptr)) return fail(LORANN_E_INVAL, "give both arrays of step sizes, or NULL for both");
+    float *na = nullptr, *nb = nullptr;
+    if (scale_A_columns) {
+        const size_t cnt[2] = {(size_t)ix->L * ix->r, (size_t)ix->n};
+        const float* src[2] = {scale_A_columns, scale_B_points};
+        for (int t = 0; t < 2; ++t) {      // step sizes are non-negative and finite, as at load time
+            std::vector<float> h(cnt[t]);
+            hipError_t e = hipMemcpy(h.data(), src[t], cnt[t] * 4, hipMemcpyDefault);
+            if (e != hipSuccess) { (void)hipGetLastError(); return fail(LORANN_E_DEVICE, "reading the step sizes failed: %s", hipGetErrorString(e)); }
+            for (size_t i = 0; i < cnt[t]; ++i)
+                if (!(h[i] >= 0.0f) || h[i] > 3.0e38f) return fail(LORANN_E_INVAL, "scale_%s[%zu] must be finite and >= 0", t ? "B_points" : "A_columns", i);
+        }
+        int rc;
+        if ((rc = dev_copy(&na, scale_A_columns, cnt[0]))) return rc;
+        if ((rc = dev_copy(&nb, scale_B_points, cnt[1]))) { (void)hipFree(na); return rc; }
+    }
+    HIP_TRY(hipStreamSynchronize(ix->stream));        // no search may still be reading the old arrays
+    if (ix->sA_cols) (void)hipFree(ix->sA_cols);
+    if (ix->sB_pts) (void)hipFree(ix->sB_pts);
+    ix->sA_cols = na; ix->sB_pts = nb;
+    return LORANN_OK;
 }
 
 int lorann_set_rerank(lorann_index* ix, int32_t mode) {

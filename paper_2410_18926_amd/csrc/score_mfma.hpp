@@ -27,6 +27,7 @@ struct ScoreArgs {
     const int32_t* bucket_off;   // [L+1] pairs of each cluster
     const int32_t* unit_off;     // [L+1] work items (pair group x point chunk) of each cluster
     const float* sqnorm;         // [n] (Euclidean) or NULL
+    const float* pt_scale;       // [n] step size of each point's code (column-wise quantization) or NULL
     uint32_t* pmax;              // out: [npairs] order-preserving key of the pair's best score (0 on entry)
     int L;
     int chunk_tiles;             // 32-point tiles per work item
@@ -46,13 +47,15 @@ __device__ __forceinline__ void wave_lds_sync() {
 // A work item = one cluster, up to 32*NZ of its pairs, up to chunk_tiles 32-point tiles of its codes; items of
 // bounded size keep the load balanced when cluster sizes and pair counts are skewed.
 // NZ pair tiles per item, KS = r_pad / 32 k-steps, L2 = Euclidean score epilogue (per-point bias, float domain;
-// inner product and cosine compare the integer maximum, sigma >= 0 being constant per pair).
+// inner product and cosine compare the integer maximum, sigma >= 0 being constant per pair).  COLS = column-wise
+// quantization: every point has its own step size, so the maximum is taken over float scores for every metric.
 // TB = point tiles fetched ahead (double buffered in registers).
 // STREAM = false: items as above.  STREAM = true (few pairs per cluster: the kernel is a pure stream of the
 // codes from HBM): one wavefront per cluster takes all of its points, no search for the item's cluster, deeper
 // fetch-ahead; clusters without pairs cost nothing.
-template <int NZ, int KS, bool L2, int TB, bool STREAM, int WPB>
+template <int NZ, int KS, bool L2, int TB, bool STREAM, int WPB, bool COLS = false>
 __global__ __launch_bounds__(64 * WPB) void k_pair_max(ScoreArgs a) {
+    constexpr bool FLT = L2 || COLS;   // float-domain epilogue
     constexpr int NP = 32 * NZ;        // pairs per item
     constexpr int RP = KS * 32;
     constexpr int IMIN = (int)0x80000000;
@@ -76,10 +79,10 @@ __global__ __launch_bounds__(64 * WPB) void k_pair_max(ScoreArgs a) {
                 if (gp < pend) zreg[z][ks] = load16(a.Z + (size_t)gp * RP + 32 * ks + 16 * h);
             }
         }
-        float sgv[NZ][16];             // Euclidean only: scale of the pair that register v belongs to
-        if (L2) {
+        float sgv[NZ][16];             // float epilogue only: scale of the pair that register v belongs to
+        if (FLT) {
             wave_lds_sync();
-            for (int p = lane; p < NP; p += 64) s_sig[wv][p] = (pb + p < pend) ? 2.0f * a.sigma[pb + p] : 0.0f;
+            for (int p = lane; p < NP; p += 64) s_sig[wv][p] = (pb + p < pend) ? (L2 ? 2.0f : 1.0f) * a.sigma[pb + p] : 0.0f;
             wave_lds_sync();
 #pragma unroll
             for (int z = 0; z < NZ; ++z)
@@ -99,21 +102,23 @@ __global__ __launch_bounds__(64 * WPB) void k_pair_max(ScoreArgs a) {
         // lanes of the cluster's last tile that lie past its end read the rows that follow (the allocation is
         // padded by 32 rows) and are masked out of the maxima below.
         const int8_t* bbase = a.Bp + (size_t)(row0 + j) * RP + 16 * h;
-        auto fetch_chunk = [&](int t0, i32x4 (*dst)[KS], float* nb) {
+        auto fetch_chunk = [&](int t0, i32x4 (*dst)[KS], float* nb, float* ns) {
 #pragma unroll
             for (int u = 0; u < TB; ++u) {
                 if (t0 + u < ntiles) {                   // uniform
 #pragma unroll
                     for (int ks = 0; ks < KS; ++ks) dst[u][ks] = load16(bbase + (size_t)(t0 + u) * (32 * RP) + 32 * ks);
                     if (L2) nb[u] = a.sqnorm[row0 + min(32 * (t0 + u) + j, m_c - 1)];
+                    if (COLS) ns[u] = a.pt_scale[row0 + min(32 * (t0 + u) + j, m_c - 1)];
                 } else {
 #pragma unroll
                     for (int ks = 0; ks < KS; ++ks) dst[u][ks] = (i32x4){0, 0, 0, 0};
                     if (L2) nb[u] = 0.0f;
+                    if (COLS) ns[u] = 0.0f;
                 }
             }
         };
-        auto score_chunk = [&](int c0, i32x4 (*breg)[KS], const float* nb) {
+        auto score_chunk = [&](int c0, i32x4 (*breg)[KS], const float* nb, const float* ns) {
 #pragma unroll
             for (int u = 0; u < TB; ++u) {
                 const int t = c0 * TB + u;
@@ -126,7 +131,7 @@ __global__ __launch_bounds__(64 * WPB) void k_pair_max(ScoreArgs a) {
                         i32x16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
                         for (int ks = 0; ks < KS; ++ks) acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(zreg[z][ks], breg[u][ks], acc, 0, 0, 0);
-                        if (!L2) {
+                        if (!FLT) {
                             if (32 * t + 32 <= m_c) {    // uniform: full tile
 #pragma unroll
                                 for (int v = 0; v < 16; ++v) mxi[z][v] = max(mxi[z][v], acc[v]);
@@ -137,7 +142,8 @@ __global__ __launch_bounds__(64 * WPB) void k_pair_max(ScoreArgs a) {
                         } else {
 #pragma unroll
                             for (int v = 0; v < 16; ++v) {
-                                const float sc = __fmaf_rn((float)acc[v], sgv[z][v], -bias);
+                                const float mult = COLS ? __fmul_rn(sgv[z][v], ns[u]) : sgv[z][v];
+                                const float sc = __fmaf_rn((float)acc[v], mult, -bias);
                                 mxf[z][v] = fmaxf(mxf[z][v], pt_ok ? sc : -INFINITY);
                             }
                         }
@@ -148,19 +154,19 @@ __global__ __launch_bounds__(64 * WPB) void k_pair_max(ScoreArgs a) {
         };
         {
             i32x4 bnext[TB][KS];
-            float nbnext[TB];
-            if (nchunks > 0) fetch_chunk(0, bnext, nbnext);
+            float nbnext[TB], nsnext[TB];
+            if (nchunks > 0) fetch_chunk(0, bnext, nbnext, nsnext);
             for (int c0 = 0; c0 < nchunks; ++c0) {
                 i32x4 breg[TB][KS];
-                float nb[TB];
+                float nb[TB], ns[TB];
 #pragma unroll
                 for (int u = 0; u < TB; ++u) {
-                    nb[u] = nbnext[u];
+                    nb[u] = nbnext[u]; ns[u] = nsnext[u];
 #pragma unroll
                     for (int ks = 0; ks < KS; ++ks) breg[u][ks] = bnext[u][ks];
                 }
-                if (c0 + 1 < nchunks) fetch_chunk((c0 + 1) * TB, bnext, nbnext);
-                score_chunk(c0, breg, nb);
+                if (c0 + 1 < nchunks) fetch_chunk((c0 + 1) * TB, bnext, nbnext, nsnext);
+                score_chunk(c0, breg, nb, ns);
             }
         }
 
@@ -172,13 +178,13 @@ __global__ __launch_bounds__(64 * WPB) void k_pair_max(ScoreArgs a) {
         for (int z = 0; z < NZ; ++z)
 #pragma unroll
             for (int v = 0; v < 16; ++v)
-                s_tr[wv][lane * TRS + z * 16 + v] = L2 ? (int)float_key_asc(mxf[z][v]) : mxi[z][v];
+                s_tr[wv][lane * TRS + z * 16 + v] = FLT ? (int)float_key_asc(mxf[z][v]) : mxi[z][v];
         wave_lds_sync();
         for (int p = lane; p < NP; p += 64) {
             const int z = p >> 5, i = p & 31;
             const int hh = (i >> 2) & 1, v = 4 * (i >> 3) + (i & 3);        // inverse of tile_row
             const int* col = &s_tr[wv][hh * 32 * TRS + z * 16 + v];
-            if (!L2) {
+            if (!FLT) {
                 int r = IMIN;
 #pragma unroll
                 for (int jj = 0; jj < 32; ++jj) r = max(r, col[jj * TRS]);
@@ -195,7 +201,7 @@ __global__ __launch_bounds__(64 * WPB) void k_pair_max(ScoreArgs a) {
             const int gp = pb + p;
             if (gp < pend) {
                 uint32_t key = 0u;       // 0 = no point seen (below the key of every float)
-                if (!L2) {
+                if (!FLT) {
                     const int y = s_red[wv][p];
                     // sigma >= 0: the best score of the pair is the score of its largest integer score
                     if (y != IMIN) key = float_key_asc(__fmaf_rn((float)y, a.sigma[gp], -0.0f));

@@ -43,6 +43,7 @@ struct SelectArgs {
     const int8_t* Bp;            // [n][r_pad]
     const int64_t* off;          // [L+1]
     const float* sqnorm;         // [n] (Euclidean) or NULL
+    const float* pt_scale;       // [n] step size of each point's code (column-wise quantization) or NULL
     int32_t* cand;               // [nq][m] out: candidate rows, -1 padded
     int w, m;
 };
@@ -109,7 +110,8 @@ __device__ __forceinline__ void select_exact_query(const SelectArgs& a, const in
         const int64_t row = prow0[j] + t;
         const int y = point_score<RB>(a.Bp + (size_t)row * (RB * 16), zs + j * ZW);
         const float bias = l2 ? a.sqnorm[row] : 0.0f;
-        return float_key_asc(__fmaf_rn((float)y, psig[j], -bias));
+        const float mult = a.pt_scale ? __fmul_rn(psig[j], a.pt_scale[row]) : psig[j];
+        return float_key_asc(__fmaf_rn((float)y, mult, -bias));
     };
 
     uint32_t mask = 0u;
@@ -209,7 +211,8 @@ __global__ __launch_bounds__(256) void k_candidate_scores(SelectArgs a, int nq, 
             const int y = point_score<RB>(a.Bp + (size_t)row * (RB * 16), zw);
             const float sg = a.sigma[pos];
             const float bias = l2 ? a.sqnorm[row] : 0.0f;
-            const float sc = __fmaf_rn((float)y, l2 ? 2.0f * sg : sg, -bias);
+            const float sp = l2 ? 2.0f * sg : sg;
+            const float sc = __fmaf_rn((float)y, a.pt_scale ? __fmul_rn(sp, a.pt_scale[row]) : sp, -bias);
             dist[(size_t)q * m + t] = -sc;
             cid[(size_t)q * m + t] = ids ? ids[row] : (int64_t)row;
         }

@@ -84,6 +84,7 @@ struct QuerySelectArgs {
     const int8_t* Bp;            // [n][r_pad]
     const int64_t* off;          // [L+1]
     const float* sqnorm;         // [n] (Euclidean) or NULL
+    const float* pt_scale;       // [n] step size of each point's code (column-wise quantization) or NULL
     int32_t* cand;               // out [nq][m]: candidate rows, unordered, -1 padded
     float* tau;                  // out [nq]: score of the m-th candidate (-inf if fewer than m points were scored)
     int32_t* n_kept;             // out [nq]: scores held in LDS when the walk ended (-1: handed to the exact kernel)
@@ -119,7 +120,7 @@ __global__ __launch_bounds__(256) void k_select_query(QuerySelectArgs a) {
     if (si >= a.nq) return;
     const int q = __builtin_amdgcn_readfirstlane(a.qorder[si]);     // uniform over the block: scalar loads below
     const int w = a.w, m = a.m;
-    const bool l2 = a.sqnorm != nullptr;
+    const bool l2 = a.sqnorm != nullptr, cols = a.pt_scale != nullptr;
     if (tid == 0) s_count = 0;
     if (tid < w) {
         const int pos = a.pos_of_slot[(size_t)q * w + tid];
@@ -176,7 +177,7 @@ __global__ __launch_bounds__(256) void k_select_query(QuerySelectArgs a) {
         const int zv = reinterpret_cast<const int*>(a.Z)[(size_t)pos * ZW + (tid < ZW ? tid : 0)];
         const float s = a.sigma[pos];
         i32x4 code[PT][RB];
-        float bias[PT];
+        float bias[PT], psc[PT];
         auto fetch_codes = [&](int p0) {
 #pragma unroll
             for (int e = 0; e < PT; ++e) {
@@ -186,6 +187,7 @@ __global__ __launch_bounds__(256) void k_select_query(QuerySelectArgs a) {
 #pragma unroll
                     for (int u = 0; u < RB; ++u) code[e][u] = bp[u];
                     bias[e] = l2 ? a.sqnorm[row] : 0.0f;
+                    psc[e] = cols ? a.pt_scale[row] : 1.0f;     // times 1 is exact: one code path for both schemes
                 }
             }
         };
@@ -212,7 +214,7 @@ __global__ __launch_bounds__(256) void k_select_query(QuerySelectArgs a) {
                         y = dot4_i8(code[e][u][2], zw[4 * u + 2], y);
                         y = dot4_i8(code[e][u][3], zw[4 * u + 3], y);
                     }
-                    const uint32_t key = float_key_asc(__fmaf_rn((float)y, sp, -bias[e]));
+                    const uint32_t key = float_key_asc(__fmaf_rn((float)y, __fmul_rn(sp, psc[e]), -bias[e]));
                     if (t < m_c && key >= T) {
                         const int at = atomicAdd(&s_count, 1);
                         keys[at] = key;

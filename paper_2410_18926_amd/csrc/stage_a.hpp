@@ -47,7 +47,10 @@ __device__ __forceinline__ int find_bucket_wave(const int32_t* __restrict__ off,
 // load).  A_c stays in registers across the tiles of a wavefront when d' <= 256.
 // RT = r_pad / 16 result tiles (2 or 4); RES: d' <= 256, A_c resident.  A is [L][r][dp]; Z is [npairs][r_pad] in
 // bucket order.
-template <int RT, bool RES>
+// COLS: column-wise quantization (Sec. 3.3 as printed) - sA is [L][r], one step size per column of A_c; the float
+// approximation rho_j = R_j * (Delta_x * DeltaA_cj) is re-quantized like a query: z = rint(rho * 127 / |rho|_inf),
+// sigma = |rho|_inf / 127 (every operation a single IEEE float operation); sB is not used.
+template <int RT, bool RES, bool COLS = false>
 __global__ __launch_bounds__(256) void k_stage_a(const int8_t* __restrict__ q8, const float* __restrict__ dx,
                                                   const int8_t* __restrict__ A, const float* __restrict__ sA,
                                                   const float* __restrict__ sB, const int32_t* __restrict__ bucket_off,
@@ -115,6 +118,36 @@ __global__ __launch_bounds__(256) void k_stage_a(const int8_t* __restrict__ q8, 
     }
 
     // acc[t][v] = R[pair 4g+v][column 16t+i].  Row maximum over the r columns: over t here, over i by shuffles.
+    if constexpr (COLS) {
+        float dA[RT];
+#pragma unroll
+        for (int t = 0; t < RT; ++t) dA[t] = sA[(size_t)c * r + min(t * 16 + i, r - 1)];
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int pos = base + 4 * g + v;
+            const float dxq = dx[slot_of_pos[min(pos, end - 1)] / w];
+            float rho[RT], mx = 0.0f;
+#pragma unroll
+            for (int t = 0; t < RT; ++t) {
+                rho[t] = t * 16 + i < r ? __fmul_rn((float)acc[t][v], __fmul_rn(dxq, dA[t])) : 0.0f;
+                mx = fmaxf(mx, fabsf(rho[t]));
+            }
+#pragma unroll
+            for (int o = 1; o < 16; o <<= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+            if (pos < end) {
+                const bool any = mx > 0.0f;
+                const float cx = any ? (float)(127.0 / (double)mx) : 0.0f;
+#pragma unroll
+                for (int t = 0; t < RT; ++t) {
+                    int zc = (int)rintf(__fmul_rn(rho[t], cx));
+                    zc = max(-127, min(127, zc));
+                    Z[(size_t)pos * (RT * 16) + t * 16 + i] = (int8_t)(any ? zc : 0);
+                }
+                if (i == 0) sigma[pos] = any ? (float)((double)mx / 127.0) : 0.0f;
+            }
+        }
+        continue;
+    }
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
         uint32_t mx = 0;

@@ -555,3 +555,75 @@ def test_search_without_rerank_ties_and_short_lists(B):
         np.testing.assert_array_equal(g_ids, o_ids, err_msg=f"k={k} w={w}")
         np.testing.assert_array_equal(g_d, o_d, err_msg=f"k={k} w={w}")
     gix.close()
+
+
+def test_column_scales_small_workloads_stagewise(B, small_indexes_columns):
+    """Column-wise quantization (Sec. 3.3 as printed: one step size per column of A_c and of B_c): every stage
+    bit-exact against the oracle - float re-quantization of the first product included - on the four small
+    configurations, through the batched path and the per-query kernel."""
+    for name, (wl, ix, corpus, queries) in small_indexes_columns.items():
+        _stagewise(B, wl, ix, queries)
+
+
+@pytest.mark.parametrize("r,dp,metric,dense", [(8, 16, 0, False), (24, 48, 1, False), (32, 256, 0, True), (48, 64, 2, False),
+                                               (64, 128, 1, True), (16, 1024, 0, False)])
+def test_column_scales_rank_dimension_metric_variants(B, r, dp, metric, dense):
+    """Random factors with widely spread step sizes (four decades across columns and across points), ranks that pad
+    on the matrix cores, both regimes of the pair-maxima kernel (dense: many pairs per cluster; else few), zero step
+    sizes (a dead column, a dead point).  Candidates bit-exact; also the search without re-ranking."""
+    rng = np.random.default_rng(500 + r + metric)
+    n, L, nq = (4000, 6, 300) if dense else (3000, 40, 45)
+    ix = _random_index(rng, n=n, d=dp, L=L, r=r, metric=metric)
+    ix["scale_A_columns"] = (10.0 ** rng.uniform(-4, 0, size=(L, r))).astype(np.float32)
+    ix["scale_B_points"] = (10.0 ** rng.uniform(-4, 0, size=n)).astype(np.float32)
+    ix["scale_A_columns"][1, 3] = 0.0
+    ix["scale_B_points"][17] = 0.0
+    ix["scale_A_columns"][2, :] = 0.0                         # a cluster whose intermediate vector is all zero
+    q = rng.normal(size=(nq, dp)).astype(np.float32)
+    w, m, k = min(L, 5), 60, 10
+    oix = O.OracleIndex(ix)
+    o_ids, o_d, ost = O.search(oix, q, k, w, m, stages=True)
+    gix = B.Index(**ix)
+    g_ids, g_d, gst = gix.search_stages(q, k, w, m)
+    np.testing.assert_array_equal(gst["z"], ost["z"], err_msg="re-quantized vectors")
+    np.testing.assert_array_equal(gst["sigma"], ost["sigma"], err_msg="pair step sizes")
+    np.testing.assert_array_equal(np.sort(gst["cand_rows"].astype(np.int64), axis=1), np.sort(ost["cand_rows"], axis=1), err_msg="candidates")
+    assert_topk_equal(g_ids, g_d, o_ids, o_d, "column scales")
+    gix.set_exact_selection(True)
+    e_ids, e_d, est = gix.search_stages(q, k, w, m)
+    gix.set_exact_selection(False)
+    np.testing.assert_array_equal(np.sort(est["cand_rows"].astype(np.int64), axis=1), np.sort(ost["cand_rows"], axis=1), err_msg="candidates (per-query kernel)")
+    gix.set_rerank(B.RERANK_NONE)
+    n_ids, n_d = gix.search(q, k, w, k)
+    r_ids, r_d = O.search_no_rerank(oix, q, k, w)
+    np.testing.assert_array_equal(n_ids, r_ids)
+    np.testing.assert_array_equal(n_d, r_d)
+    gix.close()
+
+
+def test_column_scales_can_be_set_and_removed(B, small_indexes, small_indexes_columns):
+    """lorann_set_column_scales on a loaded index, back to per-cluster step sizes with NULLs, and its refusals."""
+    wl, ixc, corpus, queries = small_indexes_columns["ip_P"]
+    a = ixc.numpy()
+    plain = {k: v for k, v in a.items() if k not in ("scale_A_columns", "scale_B_points")}
+    gix = B.Index(**plain)
+    p_ids, p_d = gix.search(queries, wl.k, wl.w, wl.m)                      # the codes read with the per-cluster step sizes
+    o_ids, o_d = O.search(O.OracleIndex(plain), queries, wl.k, wl.w, wl.m)
+    assert_topk_equal(p_ids, p_d, o_ids, o_d, "per-cluster reading")
+    gix.set_column_scales(a["scale_A_columns"], torch.from_numpy(a["scale_B_points"]).cuda())   # host and device pointers
+    c_ids, c_d, cst = gix.search_stages(queries, wl.k, wl.w, wl.m)
+    oc_ids, oc_d, ost = O.search(O.OracleIndex(a), queries, wl.k, wl.w, wl.m, stages=True)
+    np.testing.assert_array_equal(cst["z"], ost["z"])
+    assert_topk_equal(c_ids, c_d, oc_ids, oc_d, "column-wise reading")
+    for bad_a, bad_b in [(a["scale_A_columns"], None), (None, a["scale_B_points"]),
+                         (-a["scale_A_columns"] - 1, a["scale_B_points"]), (a["scale_A_columns"], a["scale_B_points"] * np.float32(np.nan))]:
+        with pytest.raises(B.LorannError) as ei:
+            gix.set_column_scales(bad_a, bad_b)
+        assert ei.value.code == B.LORANN_E_INVAL
+    k_ids, k_d = gix.search(queries, wl.k, wl.w, wl.m)                      # a refused call changes nothing
+    np.testing.assert_array_equal(k_ids, c_ids)
+    gix.set_column_scales(None, None)
+    b_ids, b_d = gix.search(queries, wl.k, wl.w, wl.m)
+    np.testing.assert_array_equal(b_ids, p_ids)
+    np.testing.assert_array_equal(b_d, p_d)
+    gix.close()
