@@ -135,6 +135,9 @@ def main():
     ap.add_argument("--column-scales", action="store_true",
                     help="quantize every column of A_c and B_c with its own step size (Sec. 3.3 as printed) instead of "
                          "one step size per cluster (the configured format of the headline run)")
+    ap.add_argument("--lanes", type=int, default=4,
+                    help="batches in flight: the timed steps are enqueued round-robin on this many lanes of the index "
+                         "(lorann_search_lane), each with its own workspace and stream; 1 = one batch at a time")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain 1 GiB elementwise copy (calibrates the HBM byte counters under rocprofv3 --pmc)")
     args = ap.parse_args()
@@ -186,23 +189,54 @@ def main():
     gix.set_rerank(rerank_modes[args.rerank])
     nq, k, w, m = wl.nq, wl.k, min(wl.w, wl.L), wl.m
     out = (torch.empty((nq, k), dtype=torch.int64, device=dev), torch.empty((nq, k), dtype=torch.float32, device=dev))
+    n_lanes = max(1, min(args.lanes, binding.LANES))
+    outs = [out] + [(torch.empty_like(out[0]), torch.empty_like(out[1])) for _ in range(n_lanes - 1)]
 
-    for s in range(W):
-        gix.search(batches[s % nb], k, w, m, out=out)
+    def run_steps(n_steps, first):
+        """Enqueue n_steps steps round-robin over the lanes and join the lanes onto the index's stream; no host wait."""
+        for s in range(n_steps):
+            gix.search(batches[(first + s) % nb], k, w, m, out=outs[s % n_lanes], lane=s % n_lanes)
+        for l in range(n_lanes):
+            gix.lane_join(l)
+
+    run_steps(max(W, n_lanes), 0)          # warm-up (every lane sizes its workspace)
     torch.cuda.synchronize()
     # Timed region: K steps.  HIP events bracket the dominant kernel (the re-rank gather) only, so that timing
     # the kernels does not slow the step being timed.
-    # The steps are enqueued without a host wait in between (lorann_search_async), as a serving loop would: the
+    # The steps are enqueued without a host wait in between, round-robin on the index's lanes (lorann_search_lane),
+    # as a serving loop would: up to n_lanes batches are in flight, each one passing through the whole path; the
     # timed region ends with the device synchronisation below.
+    gix.profile_enable(2)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run_steps(K, W)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    prof_dom = gix.profile_get()
+    fallback_queries = gix.profile_fallback_queries()
+    # for context: the same loop with the gathers of different lanes allowed to overlap (each launch then takes
+    # longer, so the kernel's own figures above are not taken from it)
+    overlapped = None
+    if n_lanes > 1:
+        gix.profile_enable(0)
+        gix.set_gather_turns(False)
+        run_steps(n_lanes, 0)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        run_steps(K, W)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        gix.set_gather_turns(True)
+        overlapped = {"queries_per_s": round(nq * K / dt, 1), "ms_per_step": round(dt / K * 1e3, 4)}
+    # for context: the same K steps one batch at a time (one lane)
     gix.profile_enable(2)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for s in range(K):
         gix.search(batches[(W + s) % nb], k, w, m, out=out, asynchronous=True)
     torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    prof_dom = gix.profile_get()
-    fallback_queries = gix.profile_fallback_queries()
+    elapsed_one_lane = time.perf_counter() - t0
+    prof_one = gix.profile_get()
     # The same loop again with events around every kernel, for the per-kernel table.
     gix.profile_enable(1)
     t0 = time.perf_counter()
@@ -297,22 +331,23 @@ def main():
         oix = O.OracleIndex(a)
         o_search = (lambda q: O.search_no_rerank(oix, q, k, w, threads=threads)) if args.rerank == "none" else \
                    (lambda q: O.search(oix, q, k, w, m, threads=threads))
-        qh = queries.cpu().numpy()
+        qh = torch.cat(batches, 0).cpu().numpy()      # the timed batches, in order (the first is the recall batch)
         threads = O.default_threads()
         o_search(qh[:threads * 2])            # warm pass
         t1 = time.perf_counter()
         n_cal = min(nq, threads * 8)
         o_search(qh[:n_cal])
         rate = n_cal / (time.perf_counter() - t1)
-        n_s = int(max(n_cal, min(nq, rate * args.cpu_seconds)))
+        n_s = int(max(n_cal, min(qh.shape[0], rate * args.cpu_seconds)))
         t1 = time.perf_counter()
         o_ids, o_d = o_search(qh[:n_s])
         dt = time.perf_counter() - t1
         cpu_baseline = {"value": round(n_s / dt, 1), "unit": "queries/s", "cores": threads, "kind": "oracle",
-                        "sample": f"first {n_s} of the {nq} queries of the timed batch shape, same index, one pass of {dt:.1f}s"}
-        oracle_match = {"queries": n_s, "id_lists_identical": float(np.mean(np.all(o_ids == ids_h[:n_s], axis=1))),
-                        "ids_equal": float(np.mean(o_ids == ids_h[:n_s])),
-                        "max_rel_dist_err": float(np.max(np.abs(o_d - dists_h[:n_s]) / np.maximum(np.abs(o_d), 1e-3)))}
+                        "sample": f"first {n_s} of the {qh.shape[0]} queries of the {nb} timed batches, same index, one pass of {dt:.1f}s"}
+        n_m = min(n_s, nq)                 # the GPU results held on the host are those of the first batch
+        oracle_match = {"queries": n_m, "id_lists_identical": float(np.mean(np.all(o_ids[:n_m] == ids_h[:n_m], axis=1))),
+                        "ids_equal": float(np.mean(o_ids[:n_m] == ids_h[:n_m])),
+                        "max_rel_dist_err": float(np.max(np.abs(o_d[:n_m] - dists_h[:n_m]) / np.maximum(np.abs(o_d[:n_m]), 1e-3)))}
         log(f"[bench] oracle baseline done in {time.time() - t0:.1f}s")
 
     if args.copy_probe:
@@ -343,6 +378,10 @@ def main():
         "index": "random factors and codes (timing only)" if args.random_index else "fitted",
         "roofline": roofline, "cpu_baseline": cpu_baseline,
         "kernels": kernels, "oracle_match": oracle_match,
+        "batches_in_flight": n_lanes,
+        "with_overlapping_gathers": overlapped,
+        "ms_per_step_one_batch_at_a_time": round(elapsed_one_lane / K * 1e3, 4),
+        "rerank_avg_ms_one_batch_at_a_time": round(prof_one["rerank"][0] / max(1, prof_one["rerank"][1]), 5) if "rerank" in prof_one else None,
         "ms_per_step_with_events_on_every_kernel": round(elapsed_allev / K * 1e3, 4),
         "fallback_queries_per_step": fallback_queries / K,
         "index_build_s": round(build_s, 1),

@@ -13,7 +13,8 @@
  *     memory it owns; search inputs/outputs are only used during the call.
  *   - Return value: LORANN_OK (0) or a negative error code; on error the outputs are untouched and
  *     lorann_last_error() describes the problem (thread-local string, valid until the next failing call).
- *   - One search at a time per index (the workspace belongs to the index).  Distinct indexes are independent.
+ *   - One search at a time per lane of an index (each lane owns a workspace; the plain entry points use lane 0).
+ *     Calls on one index must come from one host thread at a time.  Distinct indexes are independent.
  *   - Work is enqueued on the index's stream (default: the null stream, see lorann_set_stream) and
  *     lorann_search returns after the results are complete (it synchronises that stream).
  */
@@ -46,6 +47,7 @@ enum {
 #define LORANN_MAX_M 4096        /* candidates re-ranked per query */
 #define LORANN_MAX_R 64          /* RRR rank (multiple of 8) */
 #define LORANN_MAX_DP 1024       /* reduced dimension d' (multiple of 16) */
+#define LORANN_LANES 4           /* searches of one index that can be in flight at once (lorann_search_lane) */
 
 /*
  * lorann_load_index - copy an index to the GPU (Sec. 2.2 partition, Sec. 3.2-3.3 quantized factors,
@@ -118,7 +120,31 @@ int lorann_search(lorann_index *ix, const float *queries, int64_t nq, int32_t k,
 int lorann_search_async(lorann_index *ix, const float *queries, int64_t nq, int32_t k, int32_t w, int32_t m,
                         int64_t *out_ids, float *out_dists);
 
-/* Release an index and its workspace.  NULL is ignored. */
+/*
+ * lorann_search_lane - lorann_search_async on lane `lane` (0 <= lane < LORANN_LANES) of the index.  Every lane owns a
+ * workspace; lane 0 runs on the index's stream (lorann_search_lane(ix, 0, ...) IS lorann_search_async), each other lane
+ * on a stream the library creates for it (default priority).  Searches enqueued on different lanes run concurrently
+ * on the GPU: the re-rank of one batch is bound by HBM, the stages before it mostly are not, so two or three batches
+ * in flight raise the throughput of a serving loop.  Ordering: a lane starts a search only after everything enqueued
+ * on the index's stream at the time of the call (where the caller produced the queries) has finished, and runs its own
+ * searches in the order they were enqueued.  Results are complete on the index's stream after lorann_lane_join.
+ * The index's data is shared and read-only; lorann_set_rerank, lorann_set_column_scales, lorann_profile_* and
+ * lorann_free_index wait for all lanes first.  Errors: those of lorann_search_async, LORANN_E_INVAL for a bad lane.
+ */
+int lorann_search_lane(lorann_index *ix, int32_t lane, const float *queries, int64_t nq, int32_t k, int32_t w, int32_t m,
+                       int64_t *out_ids, float *out_dists);
+
+/* Make the index's stream wait (on the device; the host does not block) for everything enqueued so far on `lane`.
+ * After it, work enqueued on the index's stream - or a synchronisation of that stream - sees the lane's results. */
+int lorann_lane_join(lorann_index *ix, int32_t lane);
+
+/* The re-rank gather of one batch alone saturates HBM, so by default the gathers of different lanes take turns (each
+ * waits, on the device, for the previous lane's gather) while all other stages of the lanes overlap freely; every
+ * gather then runs at its full rate.  on = 0 lets gathers overlap as well: each launch takes longer, the throughput of
+ * a loop over several lanes was measured a few percent higher.  Waits for all lanes first. */
+int lorann_set_gather_turns(lorann_index *ix, int32_t on);
+
+/* Release an index and its workspaces.  NULL is ignored. */
 void lorann_free_index(lorann_index *ix);
 
 /* Message of the last failing call on this thread ("" if none). */

@@ -23,7 +23,8 @@ LORANN_OK, LORANN_E_INVAL, LORANN_E_NOMEM, LORANN_E_DEVICE, LORANN_E_UNSUPPORTED
 
 EXPORTS = ["lorann_load_index", "lorann_load_index_file", "lorann_search", "lorann_search_async", "lorann_free_index", "lorann_last_error", "lorann_set_stream",
            "lorann_search_stages", "lorann_profile_enable", "lorann_profile_get", "lorann_set_exact_selection",
-           "lorann_profile_fallback_queries", "lorann_set_rerank", "lorann_set_column_scales"]
+           "lorann_profile_fallback_queries", "lorann_set_rerank", "lorann_set_column_scales", "lorann_search_lane", "lorann_lane_join", "lorann_set_gather_turns"]
+LANES = 4
 RERANK_F32, RERANK_F16, RERANK_NONE = 0, 1, 2
 
 
@@ -71,6 +72,12 @@ def lib() -> C.CDLL:
         L.lorann_set_exact_selection.argtypes = [vp, i32]
         L.lorann_set_column_scales.restype = C.c_int
         L.lorann_set_column_scales.argtypes = [vp, vp, vp]
+        L.lorann_search_lane.restype = C.c_int
+        L.lorann_search_lane.argtypes = [vp, i32, vp, i64, i32, i32, i32, vp, vp]
+        L.lorann_set_gather_turns.restype = C.c_int
+        L.lorann_set_gather_turns.argtypes = [vp, i32]
+        L.lorann_lane_join.restype = C.c_int
+        L.lorann_lane_join.argtypes = [vp, i32]
         L.lorann_set_rerank.restype = C.c_int
         L.lorann_set_rerank.argtypes = [vp, i32]
         L.lorann_profile_enable.restype = C.c_int
@@ -172,10 +179,11 @@ class Index:
         ids, dists = np.empty((nq, k), np.int64), np.empty((nq, k), np.float32)
         return ids, dists, ids.ctypes.data, dists.ctypes.data
 
-    def search(self, queries, k: int, w: int, m: int, out=None, asynchronous: bool = False):
+    def search(self, queries, k: int, w: int, m: int, out=None, asynchronous: bool = False, lane: int | None = None):
         """lorann_search: returns (ids [nq,k] int64, dists [nq,k] float32) of the same kind as `queries`.
         asynchronous=True (device tensors only) calls lorann_search_async: the results are complete once the
-        index's stream has been synchronised."""
+        index's stream has been synchronised.  lane=i calls lorann_search_lane (enqueue only, on lane i of the
+        index); the results are complete on the index's stream after lane_join(i)."""
         qk, qptr = _prep(queries, np.float32, torch.float32 if torch else None)
         nq = int(qk.shape[0])
         if qk.ndim != 2 or int(qk.shape[1]) != self.d:
@@ -185,8 +193,17 @@ class Index:
         else:
             ids, dists = out
             ip, dptr = (ids.data_ptr(), dists.data_ptr()) if _is_torch(ids) else (ids.ctypes.data, dists.ctypes.data)
-        _check((lib().lorann_search_async if asynchronous else lib().lorann_search)(self._h, qptr, nq, k, w, m, ip, dptr))
+        if lane is not None:
+            _check(lib().lorann_search_lane(self._h, int(lane), qptr, nq, k, w, m, ip, dptr))
+        else:
+            _check((lib().lorann_search_async if asynchronous else lib().lorann_search)(self._h, qptr, nq, k, w, m, ip, dptr))
         return ids, dists
+
+    def set_gather_turns(self, on: bool):
+        _check(lib().lorann_set_gather_turns(self._h, 1 if on else 0))
+
+    def lane_join(self, lane: int):
+        _check(lib().lorann_lane_join(self._h, int(lane)))
 
     def search_stages(self, queries, k: int, w: int, m: int, y_off=None):
         """lorann_search_stages with host outputs: (ids, dists, dict of numpy arrays)."""

@@ -76,6 +76,25 @@ struct DevBuf {
     template <typename T> T* as() const { return reinterpret_cast<T*>(p); }
 };
 
+// Device buffers of one search in flight, sized for one chunk of queries, grown on demand.
+struct Workspace {
+    DevBuf qproj, qbf, q8, dx, gscore, sel, count, rank_in_bucket, qrank, qorder, qorder2, off0, base_tab, bucket_off, tile_off, unit_off, slot_of_pos, pos_of_slot, Z, sigma, cand;
+    DevBuf tau, n_kept, fb_list, pmax, qkey, u_row, u_mask, u_pos, u_count, rdist, rcid, rccount;
+    hipStream_t stream = nullptr;          // lanes >= 1: created on first use, default priority
+    hipEvent_t fork = nullptr, join = nullptr;
+    hipEvent_t gather_done = nullptr;      // recorded after this lane's latest re-rank gather
+    void release() {
+        DevBuf* bufs[] = {&qproj, &qbf, &q8, &dx, &gscore, &sel, &count, &rank_in_bucket, &qrank, &qorder, &qorder2, &off0, &base_tab, &bucket_off, &tile_off,
+                          &unit_off, &slot_of_pos, &pos_of_slot, &Z, &sigma, &cand, &tau, &n_kept, &fb_list, &pmax, &qkey, &u_row, &u_mask, &u_pos, &u_count, &rdist, &rcid, &rccount};
+        for (DevBuf* b : bufs) b->release();
+        if (fork) (void)hipEventDestroy(fork);
+        if (gather_done) (void)hipEventDestroy(gather_done);
+        if (join) (void)hipEventDestroy(join);
+        if (stream) (void)hipStreamDestroy(stream);
+        fork = join = gather_done = nullptr; stream = nullptr;
+    }
+};
+
 enum KernelId { K_PROJECT, K_QUANTIZE, K_CENTROID, K_CENTROID_BF16, K_SELECT_W, K_BUCKET_COUNT, K_SCAN, K_SCATTER, K_STAGE_A, K_PAIR_MAX, K_SELECT_QUERY, K_SELECT_M, K_ORDER, K_UNION, K_RERANK, K_TOPK, K_CAND_SCORES, K_COUNT };
 const char* const kKernelNames[K_COUNT] = {"project_f64", "quantize_rows", "centroid_dissim_f64", "centroid_screen_bf16", "select_clusters",
                                             "bucket_count", "scan_buckets", "scatter_pairs", "stage_a_i8", "pair_max_i8", "select_query", "score_select_exact",
@@ -108,9 +127,11 @@ struct lorann_index {
     int32_t rerank_mode = LORANN_RERANK_F32;
     int64_t* ids = nullptr;         // [n] or NULL
     float* sqnorm = nullptr;        // [n] (Euclidean)
-    // workspace (device), sized for `chunk` queries
-    DevBuf qproj, qbf, q8, dx, gscore, sel, count, rank_in_bucket, qrank, qorder, qorder2, off0, base_tab, bucket_off, tile_off, unit_off, slot_of_pos, pos_of_slot, Z, sigma, cand;
-    DevBuf tau, n_kept, fb_list, pmax, qkey, u_row, u_mask, u_pos, u_count, rdist, rcid, rccount;
+    // One workspace per lane.  Lane 0 runs on `stream` (lorann_search, lorann_search_async, lorann_search_stages);
+    // the other lanes run on streams of their own, so that batches on different lanes overlap on the GPU.
+    Workspace ws[LORANN_LANES];
+    hipEvent_t last_gather = nullptr;   // gather_done of the lane that enqueued the latest gather (owned by that lane)
+    int32_t gather_turns = 1;       // the re-rank gathers of different lanes run one after the other
     int32_t force_exact = 0;        // 1: score + select with the per-query kernel only (verification)
     DevBuf stage_q, stage_ids, stage_dists;   // staging when the caller passes host memory
     DevBuf fb_total;                // while profiling asynchronous searches: device-side sum of the fallback counts
@@ -129,9 +150,8 @@ namespace {
 void free_all(lorann_index* ix) {
     void* ptrs[] = {ix->centroids, ix->cent_sqnorm, ix->cent_nrm_f32, ix->cent_bf16, ix->Pt, ix->A, ix->Bp, ix->sA, ix->sB, ix->sA_cols, ix->sB_pts, ix->off, ix->corpus, ix->corpus_h, ix->ids, ix->sqnorm};
     for (void* p : ptrs) if (p) (void)hipFree(p);
-    DevBuf* bufs[] = {&ix->qproj, &ix->qbf, &ix->q8, &ix->dx, &ix->gscore, &ix->sel, &ix->count, &ix->rank_in_bucket, &ix->qrank, &ix->qorder, &ix->qorder2, &ix->off0, &ix->base_tab, &ix->bucket_off, &ix->tile_off,
-                      &ix->unit_off, &ix->slot_of_pos, &ix->pos_of_slot, &ix->Z, &ix->sigma, &ix->cand, &ix->tau,
-                      &ix->n_kept, &ix->fb_list, &ix->pmax, &ix->qkey, &ix->u_row, &ix->u_mask, &ix->u_pos, &ix->u_count, &ix->rdist, &ix->rcid, &ix->rccount, &ix->stage_q, &ix->stage_ids, &ix->stage_dists, &ix->fb_total};
+    for (Workspace& w : ix->ws) w.release();
+    DevBuf* bufs[] = {&ix->stage_q, &ix->stage_ids, &ix->stage_dists, &ix->fb_total};
     for (DevBuf* b : bufs) b->release();
     for (auto& e : ix->ev_used) { (void)hipEventDestroy(e.a); (void)hipEventDestroy(e.b); }
     for (auto& e : ix->ev_free) { (void)hipEventDestroy(e.a); (void)hipEventDestroy(e.b); }
@@ -155,8 +175,9 @@ __global__ void k_pad_codes(const int8_t* __restrict__ B, int8_t* __restrict__ B
 
 struct Prof {
     lorann_index* ix;
+    hipStream_t st;
     int idx = -1;
-    Prof(lorann_index* ix_, int kid) : ix(ix_) {
+    Prof(lorann_index* ix_, int kid, hipStream_t st_) : ix(ix_), st(st_) {
         if (!ix->prof_on || (ix->prof_only >= 0 && ix->prof_only != kid)) return;
         EventPair ep;
         if (!ix->ev_free.empty()) { ep = ix->ev_free.back(); ix->ev_free.pop_back(); }
@@ -164,9 +185,9 @@ struct Prof {
         ep.kid = kid;
         ix->ev_used.push_back(ep);
         idx = (int)ix->ev_used.size() - 1;
-        (void)hipEventRecord(ep.a, ix->stream);
+        (void)hipEventRecord(ep.a, st);
     }
-    ~Prof() { if (idx >= 0) (void)hipEventRecord(ix->ev_used[idx].b, ix->stream); }
+    ~Prof() { if (idx >= 0) (void)hipEventRecord(ix->ev_used[idx].b, st); }
 };
 
 void prof_collect(lorann_index* ix) {   // the stream has been synchronised
@@ -180,8 +201,10 @@ void prof_collect(lorann_index* ix) {   // the stream has been synchronised
 
 // Brings the profile totals up to date with everything enqueued so far (asynchronous searches leave their events
 // and their fallback counts pending).
+int sync_all(lorann_index* ix);
+
 int prof_settle(lorann_index* ix) {
-    HIP_TRY(hipStreamSynchronize(ix->stream));
+    { const int rc = sync_all(ix); if (rc) return rc; }
     prof_collect(ix);
     if (ix->fb_total_live) {
         int32_t fb = 0;
@@ -199,69 +222,68 @@ constexpr int kUnitPairs = 32 * kNZ;
 constexpr int kChunkTiles = 16;       // 32-point tiles per scoring work item
 
 // One batch of at most `chunk` queries, device pointers only.
-int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, int m, int64_t* d_ids, float* d_dists,
-                 const lorann_stages* st, int64_t q_base) {
+int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ, int64_t nq, int k, int w, int m, int64_t* d_ids,
+                 float* d_dists, const lorann_stages* st, int64_t q_base) {
     const int L = ix->L, dp = ix->dp, d = ix->d, r_pad = ix->r_pad;
     const int64_t npairs = nq * w;
-    hipStream_t s = ix->stream;
     int rc;
-    if ((rc = ix->qproj.reserve((size_t)nq * dp * 4))) return rc;
-    if ((rc = ix->q8.reserve((size_t)nq * dp))) return rc;
-    if ((rc = ix->dx.reserve((size_t)nq * 4))) return rc;
-    if ((rc = ix->gscore.reserve((size_t)nq * L * 4))) return rc;
-    if ((rc = ix->sel.reserve((size_t)npairs * 4))) return rc;
-    if ((rc = ix->count.reserve((size_t)(2 * L + 1) * 4))) return rc;   // [L] pair counters, [L] nearest-cluster counters, fallback-list counter
-    if ((rc = ix->rank_in_bucket.reserve((size_t)npairs * 4))) return rc;
-    if ((rc = ix->qrank.reserve((size_t)nq * 4))) return rc;
-    if ((rc = ix->qorder.reserve((size_t)nq * 4))) return rc;
-    if ((rc = ix->qorder2.reserve((size_t)nq * 4))) return rc;
-    if ((rc = ix->off0.reserve((size_t)L * 4))) return rc;
-    if ((rc = ix->pmax.reserve((size_t)npairs * 4))) return rc;
-    if ((rc = ix->bucket_off.reserve((size_t)(L + 1) * 4))) return rc;
-    if ((rc = ix->tile_off.reserve((size_t)(L + 1) * 4))) return rc;
-    if ((rc = ix->unit_off.reserve((size_t)(L + 1) * 4))) return rc;
-    if ((rc = ix->slot_of_pos.reserve((size_t)npairs * 4))) return rc;
-    if ((rc = ix->pos_of_slot.reserve((size_t)npairs * 4))) return rc;
-    if ((rc = ix->Z.reserve((size_t)npairs * r_pad))) return rc;
-    if ((rc = ix->sigma.reserve((size_t)npairs * 4))) return rc;
-    if ((rc = ix->cand.reserve((size_t)nq * m * 4))) return rc;
+    if ((rc = ws.qproj.reserve((size_t)nq * dp * 4))) return rc;
+    if ((rc = ws.q8.reserve((size_t)nq * dp))) return rc;
+    if ((rc = ws.dx.reserve((size_t)nq * 4))) return rc;
+    if ((rc = ws.gscore.reserve((size_t)nq * L * 4))) return rc;
+    if ((rc = ws.sel.reserve((size_t)npairs * 4))) return rc;
+    if ((rc = ws.count.reserve((size_t)(2 * L + 1) * 4))) return rc;   // [L] pair counters, [L] nearest-cluster counters, fallback-list counter
+    if ((rc = ws.rank_in_bucket.reserve((size_t)npairs * 4))) return rc;
+    if ((rc = ws.qrank.reserve((size_t)nq * 4))) return rc;
+    if ((rc = ws.qorder.reserve((size_t)nq * 4))) return rc;
+    if ((rc = ws.qorder2.reserve((size_t)nq * 4))) return rc;
+    if ((rc = ws.off0.reserve((size_t)L * 4))) return rc;
+    if ((rc = ws.pmax.reserve((size_t)npairs * 4))) return rc;
+    if ((rc = ws.bucket_off.reserve((size_t)(L + 1) * 4))) return rc;
+    if ((rc = ws.tile_off.reserve((size_t)(L + 1) * 4))) return rc;
+    if ((rc = ws.unit_off.reserve((size_t)(L + 1) * 4))) return rc;
+    if ((rc = ws.slot_of_pos.reserve((size_t)npairs * 4))) return rc;
+    if ((rc = ws.pos_of_slot.reserve((size_t)npairs * 4))) return rc;
+    if ((rc = ws.Z.reserve((size_t)npairs * r_pad))) return rc;
+    if ((rc = ws.sigma.reserve((size_t)npairs * 4))) return rc;
+    if ((rc = ws.cand.reserve((size_t)nq * m * 4))) return rc;
 
     const float* qp = dQ;   // projected queries
     if (ix->Pt) {
-        Prof p(ix, K_PROJECT);
+        Prof p(ix, K_PROJECT, s);
         const int pvec = (d % 4 == 0 && (reinterpret_cast<uintptr_t>(dQ) & 15u) == 0 && (reinterpret_cast<uintptr_t>(ix->Pt) & 15u) == 0) ? 1 : 0;
         if (gemm_pick_bm(nq, dp) == 64)
-            hipLaunchKernelGGL((k_gemm_nt_f64<EPI_PLAIN, 64>), dim3((dp + 63) / 64, (unsigned)((nq + 63) / 64)), dim3(256), 0, s, dQ, ix->Pt, ix->qproj.as<float>(), (const double*)nullptr, (int)nq, dp, d, pvec);
+            hipLaunchKernelGGL((k_gemm_nt_f64<EPI_PLAIN, 64>), dim3((dp + 63) / 64, (unsigned)((nq + 63) / 64)), dim3(256), 0, s, dQ, ix->Pt, ws.qproj.as<float>(), (const double*)nullptr, (int)nq, dp, d, pvec);
         else
-            hipLaunchKernelGGL((k_gemm_nt_f64<EPI_PLAIN, 32>), dim3((dp + 63) / 64, (unsigned)((nq + 31) / 32)), dim3(256), 0, s, dQ, ix->Pt, ix->qproj.as<float>(), (const double*)nullptr, (int)nq, dp, d, pvec);
-        qp = ix->qproj.as<float>();
+            hipLaunchKernelGGL((k_gemm_nt_f64<EPI_PLAIN, 32>), dim3((dp + 63) / 64, (unsigned)((nq + 31) / 32)), dim3(256), 0, s, dQ, ix->Pt, ws.qproj.as<float>(), (const double*)nullptr, (int)nq, dp, d, pvec);
+        qp = ws.qproj.as<float>();
     }
     // Routing by screening (approximate scores on the bf16 matrix cores, exact evaluation of a short list) unless
     // verification asks for the plain route or the row of values does not fit the registers of a block.
     const bool screen = !ix->force_exact && L <= 16384;
-    if (screen && (rc = ix->qbf.reserve((size_t)nq * dp * 2))) return rc;
+    if (screen && (rc = ws.qbf.reserve((size_t)nq * dp * 2))) return rc;
     {
-        Prof p(ix, K_QUANTIZE);
-        hipLaunchKernelGGL(k_quantize_rows, dim3((unsigned)((nq + 3) / 4)), dim3(256), 0, s, qp, ix->q8.as<int8_t>(), ix->dx.as<float>(), (int)nq, dp,
-                           ix->count.as<int32_t>(), 2 * L + 1, screen ? ix->qbf.as<__bf16>() : (__bf16*)nullptr);
+        Prof p(ix, K_QUANTIZE, s);
+        hipLaunchKernelGGL(k_quantize_rows, dim3((unsigned)((nq + 3) / 4)), dim3(256), 0, s, qp, ws.q8.as<int8_t>(), ws.dx.as<float>(), (int)nq, dp,
+                           ws.count.as<int32_t>(), 2 * L + 1, screen ? ws.qbf.as<__bf16>() : (__bf16*)nullptr);
     }
     if (screen) {
         {
-            Prof p(ix, K_CENTROID_BF16);
+            Prof p(ix, K_CENTROID_BF16, s);
             const int64_t blocks2 = (int64_t)((L + 127) / 128) * ((nq + 127) / 128);
             const int ti = blocks2 >= 256 ? 2 : 1;          // tiny problems: twice the blocks of half the height
             const dim3 grid((unsigned)((L + 127) / 128), (unsigned)((nq + 64 * ti - 1) / (64 * ti)));
             const float* nrm = ix->metric == LORANN_L2 ? ix->cent_nrm_f32 : nullptr;
-#define LAUNCH_CB(L2_, TI_) hipLaunchKernelGGL((k_centroid_bf16<L2_, TI_>), grid, dim3(256), 0, s, ix->qbf.as<__bf16>(), ix->cent_bf16, ix->gscore.as<float>(), nrm, (int)nq, L, dp)
+#define LAUNCH_CB(L2_, TI_) hipLaunchKernelGGL((k_centroid_bf16<L2_, TI_>), grid, dim3(256), 0, s, ws.qbf.as<__bf16>(), ix->cent_bf16, ws.gscore.as<float>(), nrm, (int)nq, L, dp)
             if (ix->metric == LORANN_L2) { if (ti == 2) LAUNCH_CB(true, 2); else LAUNCH_CB(true, 1); }
             else { if (ti == 2) LAUNCH_CB(false, 2); else LAUNCH_CB(false, 1); }
 #undef LAUNCH_CB
         }
         {
-            Prof p(ix, K_SELECT_W);
+            Prof p(ix, K_SELECT_W, s);
             ScreenArgs sa;
-            sa.ghat = ix->gscore.as<float>(); sa.qp = qp; sa.centroids = ix->centroids;
-            sa.cent_sqnorm = ix->metric == LORANN_L2 ? ix->cent_sqnorm : nullptr; sa.sel = ix->sel.as<int32_t>();
+            sa.ghat = ws.gscore.as<float>(); sa.qp = qp; sa.centroids = ix->centroids;
+            sa.cent_sqnorm = ix->metric == LORANN_L2 ? ix->cent_sqnorm : nullptr; sa.sel = ws.sel.as<int32_t>();
             sa.L = L; sa.dp = dp; sa.w = w; sa.mu_max = ix->mu_max; sa.nrm_max = ix->metric == LORANN_L2 ? ix->nrm_max : 0.0f;
             const size_t lds = (size_t)dp * 4;
             if (L <= 1024) hipLaunchKernelGGL(k_select_clusters_screen_wave<16>, dim3((unsigned)((nq + 3) / 4)), dim3(256), 4 * lds, s, sa, (int)nq);
@@ -270,11 +292,11 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
         }
     } else {
     {
-        Prof p(ix, K_CENTROID);
+        Prof p(ix, K_CENTROID, s);
         const bool big = gemm_pick_bm(nq, L) == 64;
         const int cvec = (dp % 4 == 0 && (reinterpret_cast<uintptr_t>(qp) & 15u) == 0 && (reinterpret_cast<uintptr_t>(ix->centroids) & 15u) == 0) ? 1 : 0;
         const dim3 grid((L + 63) / 64, (unsigned)(big ? (nq + 63) / 64 : (nq + 31) / 32));
-        float* gs = ix->gscore.as<float>();
+        float* gs = ws.gscore.as<float>();
         if (ix->metric == LORANN_L2) {
             if (big) hipLaunchKernelGGL((k_gemm_nt_f64<EPI_L2, 64>), grid, dim3(256), 0, s, qp, ix->centroids, gs, (const double*)ix->cent_sqnorm, (int)nq, L, dp, cvec);
             else hipLaunchKernelGGL((k_gemm_nt_f64<EPI_L2, 32>), grid, dim3(256), 0, s, qp, ix->centroids, gs, (const double*)ix->cent_sqnorm, (int)nq, L, dp, cvec);
@@ -284,56 +306,56 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
         }
     }
     {
-        Prof p(ix, K_SELECT_W);
+        Prof p(ix, K_SELECT_W, s);
         if (L <= 1024)
-            hipLaunchKernelGGL(k_select_clusters_wave<16>, dim3((unsigned)((nq + 3) / 4)), dim3(256), 0, s, ix->gscore.as<float>(), (int)nq, L, w, ix->sel.as<int32_t>());
+            hipLaunchKernelGGL(k_select_clusters_wave<16>, dim3((unsigned)((nq + 3) / 4)), dim3(256), 0, s, ws.gscore.as<float>(), (int)nq, L, w, ws.sel.as<int32_t>());
         else if (L <= 4096)
-            hipLaunchKernelGGL(k_select_clusters_wave<64>, dim3((unsigned)((nq + 3) / 4)), dim3(256), 0, s, ix->gscore.as<float>(), (int)nq, L, w, ix->sel.as<int32_t>());
+            hipLaunchKernelGGL(k_select_clusters_wave<64>, dim3((unsigned)((nq + 3) / 4)), dim3(256), 0, s, ws.gscore.as<float>(), (int)nq, L, w, ws.sel.as<int32_t>());
         else if (L <= 8192)
-            hipLaunchKernelGGL(k_select_clusters_regs<32>, dim3((unsigned)nq), dim3(256), 0, s, ix->gscore.as<float>(), L, w, ix->sel.as<int32_t>());
+            hipLaunchKernelGGL(k_select_clusters_regs<32>, dim3((unsigned)nq), dim3(256), 0, s, ws.gscore.as<float>(), L, w, ws.sel.as<int32_t>());
         else if (L <= 16384)
-            hipLaunchKernelGGL(k_select_clusters_regs<64>, dim3((unsigned)nq), dim3(256), 0, s, ix->gscore.as<float>(), L, w, ix->sel.as<int32_t>());
+            hipLaunchKernelGGL(k_select_clusters_regs<64>, dim3((unsigned)nq), dim3(256), 0, s, ws.gscore.as<float>(), L, w, ws.sel.as<int32_t>());
         else
-            hipLaunchKernelGGL(k_select_clusters, dim3((unsigned)nq), dim3(256), 0, s, ix->gscore.as<float>(), L, w, ix->sel.as<int32_t>());
+            hipLaunchKernelGGL(k_select_clusters, dim3((unsigned)nq), dim3(256), 0, s, ws.gscore.as<float>(), L, w, ws.sel.as<int32_t>());
     }
     }
     const bool lds_hist = (size_t)L * 8 <= 64 * 1024;
     const int nbb = (int)((nq + kBucketQueries - 1) / kBucketQueries);
-    if (lds_hist && (rc = ix->base_tab.reserve((size_t)2 * nbb * L * 4))) return rc;
-    int32_t* base_tab = lds_hist ? ix->base_tab.as<int32_t>() : nullptr;
+    if (lds_hist && (rc = ws.base_tab.reserve((size_t)2 * nbb * L * 4))) return rc;
+    int32_t* base_tab = lds_hist ? ws.base_tab.as<int32_t>() : nullptr;
     int32_t* base0_tab = lds_hist ? base_tab + (size_t)nbb * L : nullptr;
     {
-        Prof p(ix, K_BUCKET_COUNT);
-        int32_t* cnt = ix->count.as<int32_t>();
+        Prof p(ix, K_BUCKET_COUNT, s);
+        int32_t* cnt = ws.count.as<int32_t>();
         if (lds_hist)
-            hipLaunchKernelGGL(k_bucket_count, dim3((unsigned)nbb), dim3(1024), (size_t)L * 8, s, ix->sel.as<int32_t>(), (int)nq, w, L, cnt, cnt + L,
-                               ix->rank_in_bucket.as<int32_t>(), ix->qrank.as<int32_t>(), base_tab, base0_tab);
+            hipLaunchKernelGGL(k_bucket_count, dim3((unsigned)nbb), dim3(1024), (size_t)L * 8, s, ws.sel.as<int32_t>(), (int)nq, w, L, cnt, cnt + L,
+                               ws.rank_in_bucket.as<int32_t>(), ws.qrank.as<int32_t>(), base_tab, base0_tab);
         else
-            hipLaunchKernelGGL(k_bucket_count_global, dim3((unsigned)((npairs + 255) / 256)), dim3(256), 0, s, ix->sel.as<int32_t>(), npairs, w, cnt, cnt + L,
-                               ix->rank_in_bucket.as<int32_t>(), ix->qrank.as<int32_t>());
+            hipLaunchKernelGGL(k_bucket_count_global, dim3((unsigned)((npairs + 255) / 256)), dim3(256), 0, s, ws.sel.as<int32_t>(), npairs, w, cnt, cnt + L,
+                               ws.rank_in_bucket.as<int32_t>(), ws.qrank.as<int32_t>());
     }
     {
-        Prof p(ix, K_SCAN);
-        hipLaunchKernelGGL(k_scan_buckets, dim3((unsigned)((L + 1023) / 1024)), dim3(1024), 0, s, ix->count.as<int32_t>(), ix->count.as<int32_t>() + L, ix->off, L, kUnitPairs, 32 * kChunkTiles, ix->bucket_off.as<int32_t>(),
-                           ix->tile_off.as<int32_t>(), ix->unit_off.as<int32_t>(), ix->off0.as<int32_t>());
+        Prof p(ix, K_SCAN, s);
+        hipLaunchKernelGGL(k_scan_buckets, dim3((unsigned)((L + 1023) / 1024)), dim3(1024), 0, s, ws.count.as<int32_t>(), ws.count.as<int32_t>() + L, ix->off, L, kUnitPairs, 32 * kChunkTiles, ws.bucket_off.as<int32_t>(),
+                           ws.tile_off.as<int32_t>(), ws.unit_off.as<int32_t>(), ws.off0.as<int32_t>());
     }
     {
-        Prof p(ix, K_SCATTER);
-        hipLaunchKernelGGL(k_scatter_pairs, dim3((unsigned)((npairs + 255) / 256)), dim3(256), 0, s, ix->sel.as<int32_t>(), npairs, w, L, ix->bucket_off.as<int32_t>(),
-                           ix->rank_in_bucket.as<int32_t>(), ix->off0.as<int32_t>(), ix->qrank.as<int32_t>(), base_tab, base0_tab, ix->slot_of_pos.as<int32_t>(),
-                           ix->pos_of_slot.as<int32_t>(), ix->pmax.as<uint32_t>(), ix->qorder.as<int32_t>());
+        Prof p(ix, K_SCATTER, s);
+        hipLaunchKernelGGL(k_scatter_pairs, dim3((unsigned)((npairs + 255) / 256)), dim3(256), 0, s, ws.sel.as<int32_t>(), npairs, w, L, ws.bucket_off.as<int32_t>(),
+                           ws.rank_in_bucket.as<int32_t>(), ws.off0.as<int32_t>(), ws.qrank.as<int32_t>(), base_tab, base0_tab, ws.slot_of_pos.as<int32_t>(),
+                           ws.pos_of_slot.as<int32_t>(), ws.pmax.as<uint32_t>(), ws.qorder.as<int32_t>());
     }
     {
-        Prof p(ix, K_STAGE_A);
+        Prof p(ix, K_STAGE_A, s);
         // about five tiles of 16 pairs per wavefront on average; skewed clusters just loop longer
         const int64_t avg_tiles = npairs / 16 / L + 1;
         const dim3 grid((unsigned)L, (unsigned)std::max<int64_t>(1, std::min<int64_t>(32, (avg_tiles + 19) / 20)));
 #define LAUNCH_SA(RT_, RES_)                                                                                   \
     do {                                                                                                       \
-        if (ix->sA_cols) hipLaunchKernelGGL((k_stage_a<RT_, RES_, true>), grid, dim3(256), 0, s, ix->q8.as<int8_t>(), ix->dx.as<float>(), ix->A, ix->sA_cols, ix->sB, \
-                                            ix->bucket_off.as<int32_t>(), ix->slot_of_pos.as<int32_t>(), L, dp, ix->r, w, ix->Z.as<int8_t>(), ix->sigma.as<float>()); \
-        else hipLaunchKernelGGL((k_stage_a<RT_, RES_, false>), grid, dim3(256), 0, s, ix->q8.as<int8_t>(), ix->dx.as<float>(), ix->A, ix->sA, ix->sB, \
-                                ix->bucket_off.as<int32_t>(), ix->slot_of_pos.as<int32_t>(), L, dp, ix->r, w, ix->Z.as<int8_t>(), ix->sigma.as<float>()); \
+        if (ix->sA_cols) hipLaunchKernelGGL((k_stage_a<RT_, RES_, true>), grid, dim3(256), 0, s, ws.q8.as<int8_t>(), ws.dx.as<float>(), ix->A, ix->sA_cols, ix->sB, \
+                                            ws.bucket_off.as<int32_t>(), ws.slot_of_pos.as<int32_t>(), L, dp, ix->r, w, ws.Z.as<int8_t>(), ws.sigma.as<float>()); \
+        else hipLaunchKernelGGL((k_stage_a<RT_, RES_, false>), grid, dim3(256), 0, s, ws.q8.as<int8_t>(), ws.dx.as<float>(), ix->A, ix->sA, ix->sB, \
+                                ws.bucket_off.as<int32_t>(), ws.slot_of_pos.as<int32_t>(), L, dp, ix->r, w, ws.Z.as<int8_t>(), ws.sigma.as<float>()); \
     } while (0)
         if (r_pad == 32) { if (dp <= 256) LAUNCH_SA(2, true); else LAUNCH_SA(2, false); }
         else { if (dp <= 256) LAUNCH_SA(4, true); else LAUNCH_SA(4, false); }
@@ -341,27 +363,27 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
     }
     // Scores + candidate selection.  Batched path: pair maxima (MFMA) -> per-query walk over the few clusters whose maximum reaches the running m-th best score; the exact per-query kernel finishes what the batched path cannot.
     SelectArgs sa_;
-    sa_.qlist = nullptr; sa_.qcount = nullptr; sa_.sel = ix->sel.as<int32_t>(); sa_.pos_of_slot = ix->pos_of_slot.as<int32_t>();
-    sa_.Z = ix->Z.as<int8_t>(); sa_.sigma = ix->sigma.as<float>(); sa_.Bp = ix->Bp; sa_.off = ix->off;
-    sa_.sqnorm = ix->metric == LORANN_L2 ? ix->sqnorm : nullptr; sa_.pt_scale = ix->sB_pts; sa_.cand = ix->cand.as<int32_t>(); sa_.w = w; sa_.m = m;
+    sa_.qlist = nullptr; sa_.qcount = nullptr; sa_.sel = ws.sel.as<int32_t>(); sa_.pos_of_slot = ws.pos_of_slot.as<int32_t>();
+    sa_.Z = ws.Z.as<int8_t>(); sa_.sigma = ws.sigma.as<float>(); sa_.Bp = ix->Bp; sa_.off = ix->off;
+    sa_.sqnorm = ix->metric == LORANN_L2 ? ix->sqnorm : nullptr; sa_.pt_scale = ix->sB_pts; sa_.cand = ws.cand.as<int32_t>(); sa_.w = w; sa_.m = m;
     if (ix->force_exact) {
-        Prof p(ix, K_SELECT_M);
+        Prof p(ix, K_SELECT_M, s);
         const unsigned grid = (unsigned)std::min<int64_t>(nq, 65536);
         if (r_pad == 32) hipLaunchKernelGGL(k_select_exact<2>, dim3(grid), dim3(256), 0, s, sa_, (int)nq);
         else hipLaunchKernelGGL(k_select_exact<4>, dim3(grid), dim3(256), 0, s, sa_, (int)nq);
     } else {
-        if ((rc = ix->tau.reserve((size_t)nq * 4))) return rc;
-        if ((rc = ix->n_kept.reserve((size_t)nq * 4))) return rc;
-        if ((rc = ix->fb_list.reserve((size_t)nq * 4))) return rc;
-        if ((rc = ix->qkey.reserve((size_t)nq * 4))) return rc;
+        if ((rc = ws.tau.reserve((size_t)nq * 4))) return rc;
+        if ((rc = ws.n_kept.reserve((size_t)nq * 4))) return rc;
+        if ((rc = ws.fb_list.reserve((size_t)nq * 4))) return rc;
+        if ((rc = ws.qkey.reserve((size_t)nq * 4))) return rc;
         const bool l2 = ix->metric == LORANN_L2;
         const int ks = r_pad / 32;
         {
-            Prof p(ix, K_PAIR_MAX);
+            Prof p(ix, K_PAIR_MAX, s);
             ScoreArgs sc;
-            sc.Bp = ix->Bp; sc.Z = ix->Z.as<int8_t>(); sc.sigma = ix->sigma.as<float>(); sc.off = ix->off;
-            sc.bucket_off = ix->bucket_off.as<int32_t>(); sc.unit_off = ix->unit_off.as<int32_t>();
-            sc.sqnorm = l2 ? ix->sqnorm : nullptr; sc.pt_scale = ix->sB_pts; sc.pmax = ix->pmax.as<uint32_t>(); sc.L = L; sc.chunk_tiles = kChunkTiles;
+            sc.Bp = ix->Bp; sc.Z = ws.Z.as<int8_t>(); sc.sigma = ws.sigma.as<float>(); sc.off = ix->off;
+            sc.bucket_off = ws.bucket_off.as<int32_t>(); sc.unit_off = ws.unit_off.as<int32_t>();
+            sc.sqnorm = l2 ? ix->sqnorm : nullptr; sc.pt_scale = ix->sB_pts; sc.pmax = ws.pmax.as<uint32_t>(); sc.L = L; sc.chunk_tiles = kChunkTiles;
             // few pairs per cluster: the kernel streams the codes of the touched clusters, one wavefront per cluster
             const bool stream = npairs <= (int64_t)16 * L;
 #define LAUNCH_PM(KS_, L2_)                                                                                          \
@@ -377,12 +399,12 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
 #undef LAUNCH_PM
         }
         {
-            Prof p(ix, K_SELECT_QUERY);
+            Prof p(ix, K_SELECT_QUERY, s);
             QuerySelectArgs qa;
-            qa.sel = ix->sel.as<int32_t>(); qa.pos_of_slot = ix->pos_of_slot.as<int32_t>(); qa.pmax = ix->pmax.as<uint32_t>();
-            qa.Z = ix->Z.as<int8_t>(); qa.sigma = ix->sigma.as<float>(); qa.Bp = ix->Bp; qa.off = ix->off; qa.sqnorm = l2 ? ix->sqnorm : nullptr; qa.pt_scale = ix->sB_pts;
-            qa.cand = ix->cand.as<int32_t>(); qa.tau = ix->tau.as<float>(); qa.n_kept = ix->n_kept.as<int32_t>(); qa.qkey = ix->qkey.as<int32_t>();
-            qa.fb_list = ix->fb_list.as<int32_t>(); qa.fb_count = ix->count.as<int32_t>() + 2 * L; qa.qorder = ix->qorder.as<int32_t>(); qa.nq = (int)nq; qa.w = w; qa.m = m; qa.cap = select_query_cap(m);
+            qa.sel = ws.sel.as<int32_t>(); qa.pos_of_slot = ws.pos_of_slot.as<int32_t>(); qa.pmax = ws.pmax.as<uint32_t>();
+            qa.Z = ws.Z.as<int8_t>(); qa.sigma = ws.sigma.as<float>(); qa.Bp = ix->Bp; qa.off = ix->off; qa.sqnorm = l2 ? ix->sqnorm : nullptr; qa.pt_scale = ix->sB_pts;
+            qa.cand = ws.cand.as<int32_t>(); qa.tau = ws.tau.as<float>(); qa.n_kept = ws.n_kept.as<int32_t>(); qa.qkey = ws.qkey.as<int32_t>();
+            qa.fb_list = ws.fb_list.as<int32_t>(); qa.fb_count = ws.count.as<int32_t>() + 2 * L; qa.qorder = ws.qorder.as<int32_t>(); qa.nq = (int)nq; qa.w = w; qa.m = m; qa.cap = select_query_cap(m);
             const size_t qlds = (size_t)qa.cap * 8;
             const dim3 qgrid((unsigned)(8 * ((nq + 7) / 8)));
             if (qa.cap == 2048) {
@@ -394,8 +416,8 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
             }
         }
         {
-            Prof p(ix, K_SELECT_M);
-            sa_.qlist = ix->fb_list.as<int32_t>(); sa_.qcount = ix->count.as<int32_t>() + 2 * L;
+            Prof p(ix, K_SELECT_M, s);
+            sa_.qlist = ws.fb_list.as<int32_t>(); sa_.qcount = ws.count.as<int32_t>() + 2 * L;
             const unsigned grid = (unsigned)std::min<int64_t>(nq, 1024);
             if (r_pad == 32) hipLaunchKernelGGL(k_select_exact<2>, dim3(grid), dim3(256), 0, s, sa_, (int)nq);
             else hipLaunchKernelGGL(k_select_exact<4>, dim3(grid), dim3(256), 0, s, sa_, (int)nq);
@@ -406,55 +428,59 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
     const bool half_rows = ix->rerank_mode == LORANN_RERANK_F16;
     if (ix->rerank_mode == LORANN_RERANK_NONE) {
         // no re-ranking step: the candidates (m == k here) are the answer, ordered by their estimated scores
-        if ((rc = ix->rdist.reserve((size_t)nq * m * 4))) return rc;
-        if ((rc = ix->rcid.reserve((size_t)nq * m * 8))) return rc;
-        if ((rc = ix->rccount.reserve((size_t)nq * 4))) return rc;
+        if ((rc = ws.rdist.reserve((size_t)nq * m * 4))) return rc;
+        if ((rc = ws.rcid.reserve((size_t)nq * m * 8))) return rc;
+        if ((rc = ws.rccount.reserve((size_t)nq * 4))) return rc;
         sa_.qlist = nullptr; sa_.qcount = nullptr;
         {
-            Prof p(ix, K_CAND_SCORES);
+            Prof p(ix, K_CAND_SCORES, s);
             const dim3 grid((unsigned)((nq + 3) / 4));
-            if (r_pad == 32) hipLaunchKernelGGL(k_candidate_scores<2>, grid, dim3(256), 0, s, sa_, (int)nq, ix->ids, ix->rdist.as<float>(), ix->rcid.as<int64_t>(), ix->rccount.as<int32_t>());
-            else hipLaunchKernelGGL(k_candidate_scores<4>, grid, dim3(256), 0, s, sa_, (int)nq, ix->ids, ix->rdist.as<float>(), ix->rcid.as<int64_t>(), ix->rccount.as<int32_t>());
+            if (r_pad == 32) hipLaunchKernelGGL(k_candidate_scores<2>, grid, dim3(256), 0, s, sa_, (int)nq, ix->ids, ws.rdist.as<float>(), ws.rcid.as<int64_t>(), ws.rccount.as<int32_t>());
+            else hipLaunchKernelGGL(k_candidate_scores<4>, grid, dim3(256), 0, s, sa_, (int)nq, ix->ids, ws.rdist.as<float>(), ws.rcid.as<int64_t>(), ws.rccount.as<int32_t>());
         }
         GroupArgs ga{};
-        ga.dist = ix->rdist.as<float>(); ga.cid = ix->rcid.as<int64_t>(); ga.ccount = ix->rccount.as<int32_t>();
+        ga.dist = ws.rdist.as<float>(); ga.cid = ws.rcid.as<int64_t>(); ga.ccount = ws.rccount.as<int32_t>();
         ga.out_ids = d_ids; ga.out_dists = d_dists; ga.nq = (int)nq; ga.d = d; ga.m = m; ga.k = k;
         {
-            Prof p(ix, K_TOPK);
+            Prof p(ix, K_TOPK, s);
             if (k <= 64) hipLaunchKernelGGL(k_topk_wave<4>, dim3((unsigned)((nq + 3) / 4)), dim3(256), 0, s, ga);
             else hipLaunchKernelGGL(k_topk, dim3((unsigned)nq), dim3(256), (size_t)mp2 * 12, s, ga, mp2);
         }
     } else if (m <= 512 && !ix->force_exact && kGroupQ > 0) {
         // grouped re-rank: neighbours in the visiting order share candidate rows, each distinct row is gathered once
         {
-            Prof p(ix, K_ORDER);
-            hipLaunchKernelGGL(k_order_queries, dim3((unsigned)L), dim3(64), 0, s, ix->qorder.as<int32_t>(), ix->off0.as<int32_t>(), L, (int)nq,
-                               ix->qkey.as<int32_t>(), ix->qorder2.as<int32_t>());
+            Prof p(ix, K_ORDER, s);
+            hipLaunchKernelGGL(k_order_queries, dim3((unsigned)L), dim3(64), 0, s, ws.qorder.as<int32_t>(), ws.off0.as<int32_t>(), L, (int)nq,
+                               ws.qkey.as<int32_t>(), ws.qorder2.as<int32_t>());
         }
         const int64_t ngroups = (nq + kGroupQ - 1) / kGroupQ;
         const size_t gm = (size_t)kGroupQ * m;
-        if ((rc = ix->u_row.reserve(ngroups * gm * 4))) return rc;
-        if ((rc = ix->u_mask.reserve(ngroups * gm * 2))) return rc;
-        if ((rc = ix->u_pos.reserve(ngroups * gm * kGroupQ * 2))) return rc;
-        if ((rc = ix->u_count.reserve((size_t)ngroups * 4))) return rc;
-        if ((rc = ix->rdist.reserve((size_t)nq * m * 4))) return rc;
-        if ((rc = ix->rcid.reserve((size_t)nq * m * 8))) return rc;
-        if ((rc = ix->rccount.reserve((size_t)nq * 4))) return rc;
+        if ((rc = ws.u_row.reserve(ngroups * gm * 4))) return rc;
+        if ((rc = ws.u_mask.reserve(ngroups * gm * 2))) return rc;
+        if ((rc = ws.u_pos.reserve(ngroups * gm * kGroupQ * 2))) return rc;
+        if ((rc = ws.u_count.reserve((size_t)ngroups * 4))) return rc;
+        if ((rc = ws.rdist.reserve((size_t)nq * m * 4))) return rc;
+        if ((rc = ws.rcid.reserve((size_t)nq * m * 8))) return rc;
+        if ((rc = ws.rccount.reserve((size_t)nq * 4))) return rc;
         GroupArgs ga;
-        ga.Q = dQ; ga.corpus = half_rows ? (const void*)ix->corpus_h : (const void*)ix->corpus; ga.ids = ix->ids; ga.cand = ix->cand.as<int32_t>(); ga.qorder = ix->qorder2.as<int32_t>();
-        ga.u_row = ix->u_row.as<int32_t>(); ga.u_mask = ix->u_mask.as<uint16_t>(); ga.u_pos = ix->u_pos.as<uint16_t>(); ga.u_count = ix->u_count.as<int32_t>();
-        ga.dist = ix->rdist.as<float>(); ga.cid = ix->rcid.as<int64_t>(); ga.ccount = ix->rccount.as<int32_t>();
+        ga.Q = dQ; ga.corpus = half_rows ? (const void*)ix->corpus_h : (const void*)ix->corpus; ga.ids = ix->ids; ga.cand = ws.cand.as<int32_t>(); ga.qorder = ws.qorder2.as<int32_t>();
+        ga.u_row = ws.u_row.as<int32_t>(); ga.u_mask = ws.u_mask.as<uint16_t>(); ga.u_pos = ws.u_pos.as<uint16_t>(); ga.u_count = ws.u_count.as<int32_t>();
+        ga.dist = ws.rdist.as<float>(); ga.cid = ws.rcid.as<int64_t>(); ga.ccount = ws.rccount.as<int32_t>();
         ga.out_ids = d_ids; ga.out_dists = d_dists; ga.nq = (int)nq; ga.d = d; ga.m = m; ga.k = k;
         ga.ht = rerank_group_ht(kGroupQ, m);
         // enough gather blocks to keep every CU evenly busy: about 2 MiB of rows per block at most
         ga.slices = (int)std::min<int64_t>(16, std::max<int64_t>(1, ((int64_t)gm * d * 4 / 2) / (2 << 20) + 1));
         while ((int64_t)ga.slices * ngroups < 4096 && ga.slices < 16) ++ga.slices;
         {
-            Prof p(ix, K_UNION);
+            Prof p(ix, K_UNION, s);
             hipLaunchKernelGGL(k_group_union<8>, dim3((unsigned)ngroups), dim3(kUnionThreads), (size_t)ga.ht * 6, s, ga);
         }
+        // The gathers of different lanes take turns: each alone saturates HBM, so two at once only stretch each other,
+        // while the other stages of the other lanes still run beside a gather.
+        const bool turns = ix->gather_turns != 0;
+        if (turns && ix->last_gather && ix->last_gather != ws.gather_done) HIP_TRY(hipStreamWaitEvent(s, ix->last_gather, 0));
         {
-            Prof p(ix, K_RERANK);
+            Prof p(ix, K_RERANK, s);
             const dim3 grid((unsigned)(ngroups * ga.slices));
             const size_t lds = (size_t)kGroupQ * d * 4;
             const int nv = (d % 4 == 0 && d <= 1024) ? (d / 4 + 63) / 64 : 0;
@@ -479,21 +505,26 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
 #undef LAUNCH_GG3
 #undef LAUNCH_GG
         }
+        if (turns) {
+            if (!ws.gather_done) HIP_TRY(hipEventCreateWithFlags(&ws.gather_done, hipEventDisableTiming));
+            HIP_TRY(hipEventRecord(ws.gather_done, s));
+            ix->last_gather = ws.gather_done;
+        }
         {
-            Prof p(ix, K_TOPK);
+            Prof p(ix, K_TOPK, s);
             if (k <= 64 && m <= 256) hipLaunchKernelGGL(k_topk_wave<4>, dim3((unsigned)((nq + 3) / 4)), dim3(256), 0, s, ga);
             else if (k <= 64) hipLaunchKernelGGL(k_topk_wave<8>, dim3((unsigned)((nq + 3) / 4)), dim3(256), 0, s, ga);
             else hipLaunchKernelGGL(k_topk, dim3((unsigned)nq), dim3(256), (size_t)mp2 * 12, s, ga, mp2);
         }
     } else {
-        Prof p(ix, K_RERANK);
+        Prof p(ix, K_RERANK, s);
         const size_t lds = (size_t)d * 4 + (size_t)mp2 * 12;
-        const int32_t* cand = ix->cand.as<int32_t>();
+        const int32_t* cand = ws.cand.as<int32_t>();
         const dim3 rgrid((unsigned)(8 * ((nq + 7) / 8)));
 #define LAUNCH_RR(M_)                                                                                          \
     do {                                                                                                       \
-        if (half_rows) hipLaunchKernelGGL((k_rerank<M_, _Float16>), rgrid, dim3(256), lds, s, dQ, (const _Float16*)ix->corpus_h, ix->ids, cand, ix->qorder.as<int32_t>(), (int)nq, d, m, mp2, k, d_ids, d_dists); \
-        else hipLaunchKernelGGL((k_rerank<M_, float>), rgrid, dim3(256), lds, s, dQ, (const float*)ix->corpus, ix->ids, cand, ix->qorder.as<int32_t>(), (int)nq, d, m, mp2, k, d_ids, d_dists); \
+        if (half_rows) hipLaunchKernelGGL((k_rerank<M_, _Float16>), rgrid, dim3(256), lds, s, dQ, (const _Float16*)ix->corpus_h, ix->ids, cand, ws.qorder.as<int32_t>(), (int)nq, d, m, mp2, k, d_ids, d_dists); \
+        else hipLaunchKernelGGL((k_rerank<M_, float>), rgrid, dim3(256), lds, s, dQ, (const float*)ix->corpus, ix->ids, cand, ws.qorder.as<int32_t>(), (int)nq, d, m, mp2, k, d_ids, d_dists); \
     } while (0)
         if (ix->metric == LORANN_IP) LAUNCH_RR(0);
         else if (ix->metric == LORANN_L2) LAUNCH_RR(1);
@@ -505,19 +536,19 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
     if (st) {   // export intermediate results (verification only; not part of the timed path)
         HIP_TRY(hipStreamSynchronize(s));
         if (st->qproj) HIP_TRY(hipMemcpy(st->qproj + (size_t)q_base * dp, qp, (size_t)nq * dp * 4, hipMemcpyDefault));
-        if (st->q8) HIP_TRY(hipMemcpy(st->q8 + (size_t)q_base * dp, ix->q8.p, (size_t)nq * dp, hipMemcpyDefault));
-        if (st->dx) HIP_TRY(hipMemcpy(st->dx + q_base, ix->dx.p, (size_t)nq * 4, hipMemcpyDefault));
-        if (st->sel) HIP_TRY(hipMemcpy(st->sel + (size_t)q_base * w, ix->sel.p, (size_t)npairs * 4, hipMemcpyDefault));
-        if (st->cand_rows) HIP_TRY(hipMemcpy(st->cand_rows + (size_t)q_base * m, ix->cand.p, (size_t)nq * m * 4, hipMemcpyDefault));
-        if (st->tau && !ix->force_exact) HIP_TRY(hipMemcpy(st->tau + q_base, ix->tau.p, (size_t)nq * 4, hipMemcpyDefault));
-        if (st->n_survivors && !ix->force_exact) HIP_TRY(hipMemcpy(st->n_survivors + q_base, ix->n_kept.p, (size_t)nq * 4, hipMemcpyDefault));
+        if (st->q8) HIP_TRY(hipMemcpy(st->q8 + (size_t)q_base * dp, ws.q8.p, (size_t)nq * dp, hipMemcpyDefault));
+        if (st->dx) HIP_TRY(hipMemcpy(st->dx + q_base, ws.dx.p, (size_t)nq * 4, hipMemcpyDefault));
+        if (st->sel) HIP_TRY(hipMemcpy(st->sel + (size_t)q_base * w, ws.sel.p, (size_t)npairs * 4, hipMemcpyDefault));
+        if (st->cand_rows) HIP_TRY(hipMemcpy(st->cand_rows + (size_t)q_base * m, ws.cand.p, (size_t)nq * m * 4, hipMemcpyDefault));
+        if (st->tau && !ix->force_exact) HIP_TRY(hipMemcpy(st->tau + q_base, ws.tau.p, (size_t)nq * 4, hipMemcpyDefault));
+        if (st->n_survivors && !ix->force_exact) HIP_TRY(hipMemcpy(st->n_survivors + q_base, ws.n_kept.p, (size_t)nq * 4, hipMemcpyDefault));
         if (st->z || st->sigma) {   // bucket order -> slot order on the host
             std::vector<int32_t> pos(npairs);
             std::vector<int8_t> Zh((size_t)npairs * r_pad);
             std::vector<float> sg(npairs);
-            HIP_TRY(hipMemcpy(pos.data(), ix->pos_of_slot.p, (size_t)npairs * 4, hipMemcpyDeviceToHost));
-            HIP_TRY(hipMemcpy(Zh.data(), ix->Z.p, (size_t)npairs * r_pad, hipMemcpyDeviceToHost));
-            HIP_TRY(hipMemcpy(sg.data(), ix->sigma.p, (size_t)npairs * 4, hipMemcpyDeviceToHost));
+            HIP_TRY(hipMemcpy(pos.data(), ws.pos_of_slot.p, (size_t)npairs * 4, hipMemcpyDeviceToHost));
+            HIP_TRY(hipMemcpy(Zh.data(), ws.Z.p, (size_t)npairs * r_pad, hipMemcpyDeviceToHost));
+            HIP_TRY(hipMemcpy(sg.data(), ws.sigma.p, (size_t)npairs * 4, hipMemcpyDeviceToHost));
             std::vector<int8_t> zo((size_t)npairs * ix->r);
             std::vector<float> so(npairs);
             for (int64_t p = 0; p < npairs; ++p) {
@@ -538,8 +569,8 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
             hipError_t e = hipMalloc((void**)&d_y, std::max<size_t>((size_t)(y1 - y0), 1) * 4);
             if (e != hipSuccess) { (void)hipFree(d_yo); return fail(LORANN_E_NOMEM, "hipMalloc for the score dump failed"); }
             (void)hipMemcpy(d_yo, yo.data(), (size_t)(npairs + 1) * 8, hipMemcpyHostToDevice);
-            if (r_pad == 32) hipLaunchKernelGGL(k_dump_pair_scores<2>, dim3((unsigned)npairs), dim3(256), 0, s, ix->sel.as<int32_t>(), ix->pos_of_slot.as<int32_t>(), ix->Z.as<int8_t>(), ix->Bp, ix->off, d_yo, d_y);
-            else hipLaunchKernelGGL(k_dump_pair_scores<4>, dim3((unsigned)npairs), dim3(256), 0, s, ix->sel.as<int32_t>(), ix->pos_of_slot.as<int32_t>(), ix->Z.as<int8_t>(), ix->Bp, ix->off, d_yo, d_y);
+            if (r_pad == 32) hipLaunchKernelGGL(k_dump_pair_scores<2>, dim3((unsigned)npairs), dim3(256), 0, s, ws.sel.as<int32_t>(), ws.pos_of_slot.as<int32_t>(), ws.Z.as<int8_t>(), ix->Bp, ix->off, d_yo, d_y);
+            else hipLaunchKernelGGL(k_dump_pair_scores<4>, dim3((unsigned)npairs), dim3(256), 0, s, ws.sel.as<int32_t>(), ws.pos_of_slot.as<int32_t>(), ws.Z.as<int8_t>(), ix->Bp, ix->off, d_yo, d_y);
             e = hipStreamSynchronize(s);
             if (e == hipSuccess) e = hipMemcpy(st->y + y0, d_y, (size_t)(y1 - y0) * 4, hipMemcpyDefault);
             (void)hipFree(d_yo); (void)hipFree(d_y);
@@ -550,12 +581,35 @@ int search_chunk(lorann_index* ix, const float* dQ, int64_t nq, int k, int w, in
 }
 
 __global__ void k_add_counter(const int32_t* __restrict__ src, int32_t* __restrict__ dst) {
-    if (blockIdx.x == 0 && threadIdx.x == 0) *dst += *src;
+    if (blockIdx.x == 0 && threadIdx.x == 0) atomicAdd(dst, *src);     // lanes add concurrently
+}
+
+// The stream a lane runs on; lanes >= 1 get theirs (and the two events that tie them to the index's stream) on
+// first use.
+int lane_stream(lorann_index* ix, int lane, hipStream_t* out) {
+    if (lane == 0) { *out = ix->stream; return LORANN_OK; }
+    Workspace& ws = ix->ws[lane];
+    if (!ws.stream) {
+        HIP_TRY(hipStreamCreateWithFlags(&ws.stream, hipStreamNonBlocking));
+        HIP_TRY(hipEventCreateWithFlags(&ws.fork, hipEventDisableTiming));
+        HIP_TRY(hipEventCreateWithFlags(&ws.join, hipEventDisableTiming));
+    }
+    *out = ws.stream;
+    return LORANN_OK;
+}
+
+// Host wait for everything enqueued on the index's stream and on every lane.
+int sync_all(lorann_index* ix) {
+    HIP_TRY(hipStreamSynchronize(ix->stream));
+    for (int l = 1; l < LORANN_LANES; ++l)
+        if (ix->ws[l].stream) HIP_TRY(hipStreamSynchronize(ix->ws[l].stream));
+    return LORANN_OK;
 }
 
 int search_impl(lorann_index* ix, const float* queries, int64_t nq, int32_t k, int32_t w, int32_t m, int64_t* out_ids,
-                float* out_dists, const lorann_stages* st, bool async = false) {
+                float* out_dists, const lorann_stages* st, bool async = false, int lane = 0) {
     if (!ix) return fail(LORANN_E_INVAL, "index is NULL");
+    if (lane < 0 || lane >= LORANN_LANES) return fail(LORANN_E_INVAL, "lane = %d is outside 0..%d", lane, LORANN_LANES - 1);
     if (nq < 0) return fail(LORANN_E_INVAL, "nq = %lld is negative", (long long)nq);
     if (ix->rerank_mode == LORANN_RERANK_NONE && k >= 1 && m >= k) m = k;    // the candidates are the answer
     if (k < 1 || m < 1 || k > m) return fail(LORANN_E_INVAL, "need 1 <= k <= m (k = %d, m = %d)", k, m);
@@ -576,8 +630,15 @@ int search_impl(lorann_index* ix, const float* queries, int64_t nq, int32_t k, i
     while (chunk > 1 && (chunk * w > (1ll << 30) || chunk * (int64_t)ix->L > (1ll << 31))) chunk >>= 1;
 
     const bool q_dev = is_device_ptr(queries), i_dev = is_device_ptr(out_ids), d_dev = is_device_ptr(out_dists);
-    if (async && !(q_dev && i_dev && d_dev)) return fail(LORANN_E_INVAL, "lorann_search_async needs device pointers");
+    if (async && !(q_dev && i_dev && d_dev)) return fail(LORANN_E_INVAL, "lorann_search_async / lorann_search_lane need device pointers");
     if (async && ix->prof_on && (rc0 = ix->fb_total.reserve(4))) return rc0;
+    Workspace& ws = ix->ws[lane];
+    hipStream_t stream = nullptr;
+    if ((rc0 = lane_stream(ix, lane, &stream))) return rc0;
+    if (lane > 0) {     // the lane starts after what the index's stream holds now (the caller's queries)
+        HIP_TRY(hipEventRecord(ws.fork, ix->stream));
+        HIP_TRY(hipStreamWaitEvent(stream, ws.fork, 0));
+    }
     for (int64_t q0 = 0; q0 < nq; q0 += chunk) {
         const int64_t cn = std::min(chunk, nq - q0);
         const float* dQ = queries + (size_t)q0 * ix->d;
@@ -586,29 +647,38 @@ int search_impl(lorann_index* ix, const float* queries, int64_t nq, int32_t k, i
         int rc;
         if (!q_dev) {
             if ((rc = ix->stage_q.reserve((size_t)cn * ix->d * 4))) return rc;
-            HIP_TRY(hipMemcpyAsync(ix->stage_q.p, dQ, (size_t)cn * ix->d * 4, hipMemcpyHostToDevice, ix->stream));
+            HIP_TRY(hipMemcpyAsync(ix->stage_q.p, dQ, (size_t)cn * ix->d * 4, hipMemcpyHostToDevice, stream));
             dQ = ix->stage_q.as<float>();
         }
         if (!i_dev) { if ((rc = ix->stage_ids.reserve((size_t)cn * k * 8))) return rc; dI = ix->stage_ids.as<int64_t>(); }
         if (!d_dev) { if ((rc = ix->stage_dists.reserve((size_t)cn * k * 4))) return rc; dD = ix->stage_dists.as<float>(); }
-        if ((rc = search_chunk(ix, dQ, cn, k, w, m, dI, dD, st, q0))) return rc;
-        if (!i_dev) HIP_TRY(hipMemcpyAsync(out_ids + (size_t)q0 * k, dI, (size_t)cn * k * 8, hipMemcpyDeviceToHost, ix->stream));
-        if (!d_dev) HIP_TRY(hipMemcpyAsync(out_dists + (size_t)q0 * k, dD, (size_t)cn * k * 4, hipMemcpyDeviceToHost, ix->stream));
+        if ((rc = search_chunk(ix, ws, stream, dQ, cn, k, w, m, dI, dD, st, q0))) return rc;
+        if (!i_dev) HIP_TRY(hipMemcpyAsync(out_ids + (size_t)q0 * k, dI, (size_t)cn * k * 8, hipMemcpyDeviceToHost, stream));
+        if (!d_dev) HIP_TRY(hipMemcpyAsync(out_dists + (size_t)q0 * k, dD, (size_t)cn * k * 4, hipMemcpyDeviceToHost, stream));
         if (async) {
             // nothing waits here: the results are complete once the stream is; while profiling, the batch's count
             // of queries finished by the per-query kernel is added up on the device
             if (ix->prof_on && !ix->force_exact) {
-                if (!ix->fb_total_live) { HIP_TRY(hipMemsetAsync(ix->fb_total.p, 0, 4, ix->stream)); ix->fb_total_live = true; }
-                hipLaunchKernelGGL(k_add_counter, dim3(1), dim3(64), 0, ix->stream, ix->count.as<int32_t>() + 2 * ix->L, ix->fb_total.as<int32_t>());
+                if (!ix->fb_total_live) {      // first use since the totals were read: clear it before any lane adds
+                    int rcs = sync_all(ix);
+                    if (rcs) return rcs;
+                    HIP_TRY(hipMemset(ix->fb_total.p, 0, 4));
+                    ix->fb_total_live = true;
+                }
+                hipLaunchKernelGGL(k_add_counter, dim3(1), dim3(64), 0, stream, ws.count.as<int32_t>() + 2 * ix->L, ix->fb_total.as<int32_t>());
             }
             continue;
         }
-        HIP_TRY(hipStreamSynchronize(ix->stream));
+        HIP_TRY(hipStreamSynchronize(stream));
         if (ix->prof_on) {
+            {   // events of asynchronous searches on other lanes may still be pending
+                int rcs = sync_all(ix);
+                if (rcs) return rcs;
+            }
             prof_collect(ix);
             if (!ix->force_exact) {
                 int32_t fb = 0;
-                HIP_TRY(hipMemcpy(&fb, ix->count.as<int32_t>() + 2 * ix->L, 4, hipMemcpyDeviceToHost));
+                HIP_TRY(hipMemcpy(&fb, ws.count.as<int32_t>() + 2 * ix->L, 4, hipMemcpyDeviceToHost));
                 ix->prof_fallback_queries += fb;
             }
         }
@@ -789,7 +859,7 @@ int lorann_load_index_file(lorann_index** out, const char* path) {
 
 void lorann_free_index(lorann_index* ix) {
     if (!ix) return;
-    (void)hipStreamSynchronize(ix->stream);
+    (void)sync_all(ix);
     free_all(ix);
 }
 
@@ -808,6 +878,29 @@ int lorann_search(lorann_index* ix, const float* queries, int64_t nq, int32_t k,
 int lorann_search_async(lorann_index* ix, const float* queries, int64_t nq, int32_t k, int32_t w, int32_t m, int64_t* out_ids,
                         float* out_dists) {
     return search_impl(ix, queries, nq, k, w, m, out_ids, out_dists, nullptr, true);
+}
+
+int lorann_search_lane(lorann_index* ix, int32_t lane, const float* queries, int64_t nq, int32_t k, int32_t w, int32_t m,
+                       int64_t* out_ids, float* out_dists) {
+    return search_impl(ix, queries, nq, k, w, m, out_ids, out_dists, nullptr, true, lane);
+}
+
+int lorann_lane_join(lorann_index* ix, int32_t lane) {
+    if (!ix) return fail(LORANN_E_INVAL, "index is NULL");
+    if (lane < 0 || lane >= LORANN_LANES) return fail(LORANN_E_INVAL, "lane = %d is outside 0..%d", lane, LORANN_LANES - 1);
+    Workspace& ws = ix->ws[lane];
+    if (lane == 0 || !ws.stream) return LORANN_OK;       // lane 0 is the index's stream itself; an unused lane holds nothing
+    HIP_TRY(hipEventRecord(ws.join, ws.stream));
+    HIP_TRY(hipStreamWaitEvent(ix->stream, ws.join, 0));
+    return LORANN_OK;
+}
+
+int lorann_set_gather_turns(lorann_index* ix, int32_t on) {
+    if (!ix) return fail(LORANN_E_INVAL, "index is NULL");
+    { const int rc = sync_all(ix); if (rc) return rc; }
+    ix->gather_turns = on != 0;
+    ix->last_gather = nullptr;
+    return LORANN_OK;
 }
 
 int lorann_search_stages(lorann_index* ix, const float* queries, int64_t nq, int32_t k, int32_t w, int32_t m,
@@ -833,7 +926,7 @@ int lorann_set_column_scales(lorann_index* ix, const float* scale_A_columns, con
         if ((rc = dev_copy(&na, scale_A_columns, cnt[0]))) return rc;
         if ((rc = dev_copy(&nb, scale_B_points, cnt[1]))) { (void)hipFree(na); return rc; }
     }
-    HIP_TRY(hipStreamSynchronize(ix->stream));        // no search may still be reading the old arrays
+    { const int rc = sync_all(ix); if (rc) return rc; }   // no search may still be reading the old arrays
     if (ix->sA_cols) (void)hipFree(ix->sA_cols);
     if (ix->sB_pts) (void)hipFree(ix->sB_pts);
     ix->sA_cols = na; ix->sB_pts = nb;
@@ -843,8 +936,8 @@ int lorann_set_column_scales(lorann_index* ix, const float* scale_A_columns, con
 int lorann_set_rerank(lorann_index* ix, int32_t mode) {
     if (!ix) return fail(LORANN_E_INVAL, "index is NULL");
     if (mode != LORANN_RERANK_F32 && mode != LORANN_RERANK_F16 && mode != LORANN_RERANK_NONE) return fail(LORANN_E_INVAL, "unknown re-rank mode %d", mode);
+    { const int rc = sync_all(ix); if (rc) return rc; }   // searches in flight keep the mode they were enqueued with
     if (mode == LORANN_RERANK_F16 && !ix->corpus_h) {
-        HIP_TRY(hipStreamSynchronize(ix->stream));
         const size_t count = (size_t)ix->n * ix->d;
         _Float16* h = nullptr;
         uint32_t* mx = nullptr;

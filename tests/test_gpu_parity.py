@@ -627,3 +627,64 @@ def test_column_scales_can_be_set_and_removed(B, small_indexes, small_indexes_co
     np.testing.assert_array_equal(b_ids, p_ids)
     np.testing.assert_array_equal(b_d, p_d)
     gix.close()
+
+
+def test_lanes_overlap_searches_with_identical_results(B, small_indexes):
+    """lorann_search_lane: batches of different sizes enqueued round-robin on all lanes (each lane reused several
+    times, so its workspace is recycled while other lanes are busy), joined onto the index's stream and synchronised
+    once: every batch must equal the synchronous search; the queries are produced on the index's stream right before
+    the call (the lane must wait for them); bad lanes and host pointers are refused."""
+    wl, ix, corpus, queries = small_indexes["l2_P_norms"]
+    gix = B.Index.from_arrays(ix.to("cuda"))
+    gix.use_torch_stream()
+    k, w, m = wl.k, wl.w, wl.m
+    dev = torch.device("cuda:0")
+    rng = np.random.default_rng(21)
+    sizes = [33, 200, 7, 129, 64, 1, 40, 180, 5, 77]
+    picks = [rng.choice(queries.shape[0], size=n, replace=True) for n in sizes]
+    host_q = [torch.from_numpy(queries[p]) for p in picks]
+    outs = [(torch.empty((n, k), dtype=torch.int64, device=dev), torch.empty((n, k), dtype=torch.float32, device=dev)) for n in sizes]
+    bufs = [torch.zeros((n, queries.shape[1]), dtype=torch.float32, device=dev) for n in sizes]
+    gix.profile_enable(True)
+    for i, (hq, o, b) in enumerate(zip(host_q, outs, bufs)):
+        b.copy_(hq.to(dev) * 0.5).mul_(2.0)              # produced by kernels on the index's stream just before the call
+        gix.search(b, k, w, m, out=o, lane=i % B.LANES)
+    for l in range(B.LANES):
+        gix.lane_join(l)
+    torch.cuda.synchronize()
+    assert gix.profile_get()["rerank"][1] == len(sizes)
+    gix.profile_enable(False)
+    for hq, o in zip(host_q, outs):
+        s_ids, s_d = gix.search(hq.to(dev), k, w, m)
+        np.testing.assert_array_equal(o[0].cpu().numpy(), s_ids.cpu().numpy())
+        np.testing.assert_array_equal(o[1].cpu().numpy(), s_d.cpu().numpy())
+    # the oracle agrees with what the lanes returned
+    o_ids, o_d = O.search(O.OracleIndex(ix.numpy()), queries[picks[1]], k, w, m)
+    assert_topk_equal(outs[1][0].cpu().numpy(), outs[1][1].cpu().numpy(), o_ids, o_d, "lane 1")
+    for bad in (-1, B.LANES):
+        with pytest.raises(B.LorannError):
+            gix.search(bufs[0], k, w, m, out=outs[0], lane=bad)
+        with pytest.raises(B.LorannError):
+            gix.lane_join(bad)
+    with pytest.raises(B.LorannError):
+        gix.search(queries[:4], k, w, m, lane=1)
+    # gathers of different lanes allowed to overlap: same results
+    gix.set_gather_turns(False)
+    for i, (b, o) in enumerate(zip(bufs, outs)):
+        o[0].zero_(); o[1].zero_()
+        gix.search(b, k, w, m, out=o, lane=(i + 1) % B.LANES)
+    for l in range(B.LANES):
+        gix.lane_join(l)
+    torch.cuda.synchronize()
+    gix.set_gather_turns(True)
+    for hq, o in zip(host_q, outs):
+        s_ids, s_d = gix.search(hq.to(dev), k, w, m)
+        np.testing.assert_array_equal(o[0].cpu().numpy(), s_ids.cpu().numpy())
+        np.testing.assert_array_equal(o[1].cpu().numpy(), s_d.cpu().numpy())
+    # mode changes wait for the lanes: enqueue, switch, and the earlier results are those of the earlier mode
+    gix.search(bufs[1], k, w, m, out=outs[1], lane=2)
+    gix.set_rerank(B.RERANK_NONE)
+    gix.set_rerank(B.RERANK_F32)
+    s_ids, s_d = gix.search(bufs[1], k, w, m)
+    np.testing.assert_array_equal(outs[1][0].cpu().numpy(), s_ids.cpu().numpy())
+    gix.close()
