@@ -138,6 +138,10 @@ def main():
     ap.add_argument("--lanes", type=int, default=4,
                     help="batches in flight: the timed steps are enqueued round-robin on this many lanes of the index "
                          "(lorann_search_lane), each with its own workspace and stream; 1 = one batch at a time")
+    ap.add_argument("--timed-only", action="store_true",
+                    help="run the warm-up, the timed steps and one result pass only - no context loops, no per-kernel "
+                         "event pass, no other modes - so that a profiler attached to the process sees the timed "
+                         "configuration and little else")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain 1 GiB elementwise copy (calibrates the HBM byte counters under rocprofv3 --pmc)")
     args = ap.parse_args()
@@ -217,7 +221,7 @@ def main():
     # for context: the same loop with the gathers of different lanes allowed to overlap (each launch then takes
     # longer, so the kernel's own figures above are not taken from it)
     overlapped = None
-    if n_lanes > 1:
+    if n_lanes > 1 and not args.timed_only:
         gix.profile_enable(0)
         gix.set_gather_turns(False)
         run_steps(n_lanes, 0)
@@ -228,23 +232,25 @@ def main():
         dt = time.perf_counter() - t0
         gix.set_gather_turns(True)
         overlapped = {"queries_per_s": round(nq * K / dt, 1), "ms_per_step": round(dt / K * 1e3, 4)}
-    # for context: the same K steps one batch at a time (one lane)
-    gix.profile_enable(2)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for s in range(K):
-        gix.search(batches[(W + s) % nb], k, w, m, out=out, asynchronous=True)
-    torch.cuda.synchronize()
-    elapsed_one_lane = time.perf_counter() - t0
-    prof_one = gix.profile_get()
-    # The same loop again with events around every kernel, for the per-kernel table.
-    gix.profile_enable(1)
-    t0 = time.perf_counter()
-    for s in range(K):
-        gix.search(batches[(W + s) % nb], k, w, m, out=out)
-    torch.cuda.synchronize()
-    elapsed_allev = time.perf_counter() - t0
-    prof = gix.profile_get()
+    elapsed_one_lane, elapsed_allev, prof_one, prof = float("nan"), float("nan"), {}, dict(prof_dom)
+    if not args.timed_only:
+        # for context: the same K steps one batch at a time (one lane)
+        gix.profile_enable(2)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for s in range(K):
+            gix.search(batches[(W + s) % nb], k, w, m, out=out, asynchronous=True)
+        torch.cuda.synchronize()
+        elapsed_one_lane = time.perf_counter() - t0
+        prof_one = gix.profile_get()
+        # The same loop again with events around every kernel, for the per-kernel table.
+        gix.profile_enable(1)
+        t0 = time.perf_counter()
+        for s in range(K):
+            gix.search(batches[(W + s) % nb], k, w, m, out=out)
+        torch.cuda.synchronize()
+        elapsed_allev = time.perf_counter() - t0
+        prof = gix.profile_get()
     gix.profile_enable(0)
 
     ids, dists = gix.search(queries, k, w, m)
@@ -259,9 +265,11 @@ def main():
     # per-kernel roofline figures from the events recorded over the timed region
     sizes = (ix.cluster_offsets[1:] - ix.cluster_offsets[:-1]).cpu().numpy()
     # clusters touched by the batch (their codes are what the scoring kernel has to read at least once)
-    sel_all = gix.search_stages(queries[:20000], k, w, m)[2]["sel"]
-    touched = np.zeros(wl.L, bool)
-    touched[np.unique(sel_all)] = True
+    touched = np.ones(wl.L, bool)
+    if not args.timed_only:
+        sel_all = gix.search_stages(queries[:20000], k, w, m)[2]["sel"]
+        touched[:] = False
+        touched[np.unique(sel_all)] = True
     touched_rows = int(sizes[touched].sum())
     models = kernel_models(wl, nq, touched_rows, nq * w, args.column_scales)
     if args.rerank == "f16":
@@ -297,16 +305,17 @@ def main():
     # neighbours: context for the headline figure, which is always the mode selected by --rerank.
     other_modes = {}
     for name, mode in rerank_modes.items():
-        if name == args.rerank:
+        if name == args.rerank or args.timed_only:
             continue
         gix.set_rerank(mode)
         for s in range(2):
             gix.search(batches[s % nb], k, w, m, out=out)
         torch.cuda.synchronize()
         Km = max(1, min(K, 10))
+        run_steps(n_lanes, 0)
+        torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for s in range(Km):
-            gix.search(batches[s % nb], k, w, m, out=out, asynchronous=True)
+        run_steps(Km, 0)
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
         mi = gix.search(queries[:n_rec], k, w, m)[0].cpu().numpy()
@@ -380,9 +389,9 @@ def main():
         "kernels": kernels, "oracle_match": oracle_match,
         "batches_in_flight": n_lanes,
         "with_overlapping_gathers": overlapped,
-        "ms_per_step_one_batch_at_a_time": round(elapsed_one_lane / K * 1e3, 4),
+        "ms_per_step_one_batch_at_a_time": None if args.timed_only else round(elapsed_one_lane / K * 1e3, 4),
         "rerank_avg_ms_one_batch_at_a_time": round(prof_one["rerank"][0] / max(1, prof_one["rerank"][1]), 5) if "rerank" in prof_one else None,
-        "ms_per_step_with_events_on_every_kernel": round(elapsed_allev / K * 1e3, 4),
+        "ms_per_step_with_events_on_every_kernel": None if args.timed_only else round(elapsed_allev / K * 1e3, 4),
         "fallback_queries_per_step": fallback_queries / K,
         "index_build_s": round(build_s, 1),
         "other_rerank_modes": other_modes,

@@ -223,7 +223,7 @@ constexpr int kChunkTiles = 16;       // 32-point tiles per scoring work item
 
 // One batch of at most `chunk` queries, device pointers only.
 int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ, int64_t nq, int k, int w, int m, int64_t* d_ids,
-                 float* d_dists, const lorann_stages* st, int64_t q_base) {
+                 float* d_dists, const lorann_stages* st, int64_t q_base, int32_t* fb_total) {
     const int L = ix->L, dp = ix->dp, d = ix->d, r_pad = ix->r_pad;
     const int64_t npairs = nq * w;
     int rc;
@@ -363,7 +363,7 @@ int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ
     }
     // Scores + candidate selection.  Batched path: pair maxima (MFMA) -> per-query walk over the few clusters whose maximum reaches the running m-th best score; the exact per-query kernel finishes what the batched path cannot.
     SelectArgs sa_;
-    sa_.qlist = nullptr; sa_.qcount = nullptr; sa_.sel = ws.sel.as<int32_t>(); sa_.pos_of_slot = ws.pos_of_slot.as<int32_t>();
+    sa_.qlist = nullptr; sa_.qcount = nullptr; sa_.fb_total = nullptr; sa_.sel = ws.sel.as<int32_t>(); sa_.pos_of_slot = ws.pos_of_slot.as<int32_t>();
     sa_.Z = ws.Z.as<int8_t>(); sa_.sigma = ws.sigma.as<float>(); sa_.Bp = ix->Bp; sa_.off = ix->off;
     sa_.sqnorm = ix->metric == LORANN_L2 ? ix->sqnorm : nullptr; sa_.pt_scale = ix->sB_pts; sa_.cand = ws.cand.as<int32_t>(); sa_.w = w; sa_.m = m;
     if (ix->force_exact) {
@@ -418,6 +418,7 @@ int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ
         {
             Prof p(ix, K_SELECT_M, s);
             sa_.qlist = ws.fb_list.as<int32_t>(); sa_.qcount = ws.count.as<int32_t>() + 2 * L;
+            sa_.fb_total = fb_total;      // asynchronous searches being profiled: the count is added up on the device
             const unsigned grid = (unsigned)std::min<int64_t>(nq, 1024);
             if (r_pad == 32) hipLaunchKernelGGL(k_select_exact<2>, dim3(grid), dim3(256), 0, s, sa_, (int)nq);
             else hipLaunchKernelGGL(k_select_exact<4>, dim3(grid), dim3(256), 0, s, sa_, (int)nq);
@@ -431,7 +432,7 @@ int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ
         if ((rc = ws.rdist.reserve((size_t)nq * m * 4))) return rc;
         if ((rc = ws.rcid.reserve((size_t)nq * m * 8))) return rc;
         if ((rc = ws.rccount.reserve((size_t)nq * 4))) return rc;
-        sa_.qlist = nullptr; sa_.qcount = nullptr;
+        sa_.qlist = nullptr; sa_.qcount = nullptr; sa_.fb_total = nullptr;
         {
             Prof p(ix, K_CAND_SCORES, s);
             const dim3 grid((unsigned)((nq + 3) / 4));
@@ -580,10 +581,6 @@ int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ
     return LORANN_OK;
 }
 
-__global__ void k_add_counter(const int32_t* __restrict__ src, int32_t* __restrict__ dst) {
-    if (blockIdx.x == 0 && threadIdx.x == 0) atomicAdd(dst, *src);     // lanes add concurrently
-}
-
 // The stream a lane runs on; lanes >= 1 get theirs (and the two events that tie them to the index's stream) on
 // first use.
 int lane_stream(lorann_index* ix, int lane, hipStream_t* out) {
@@ -652,23 +649,21 @@ int search_impl(lorann_index* ix, const float* queries, int64_t nq, int32_t k, i
         }
         if (!i_dev) { if ((rc = ix->stage_ids.reserve((size_t)cn * k * 8))) return rc; dI = ix->stage_ids.as<int64_t>(); }
         if (!d_dev) { if ((rc = ix->stage_dists.reserve((size_t)cn * k * 4))) return rc; dD = ix->stage_dists.as<float>(); }
-        if ((rc = search_chunk(ix, ws, stream, dQ, cn, k, w, m, dI, dD, st, q0))) return rc;
+        int32_t* fb_total = nullptr;
+        if (async && ix->prof_on && !ix->force_exact) {
+            // while asynchronous searches are profiled, the fallback kernel adds its list length to a device total
+            if (!ix->fb_total_live) {      // first use since the totals were read: clear it before any lane adds
+                int rcs = sync_all(ix);
+                if (rcs) return rcs;
+                HIP_TRY(hipMemset(ix->fb_total.p, 0, 4));
+                ix->fb_total_live = true;
+            }
+            fb_total = ix->fb_total.as<int32_t>();
+        }
+        if ((rc = search_chunk(ix, ws, stream, dQ, cn, k, w, m, dI, dD, st, q0, fb_total))) return rc;
         if (!i_dev) HIP_TRY(hipMemcpyAsync(out_ids + (size_t)q0 * k, dI, (size_t)cn * k * 8, hipMemcpyDeviceToHost, stream));
         if (!d_dev) HIP_TRY(hipMemcpyAsync(out_dists + (size_t)q0 * k, dD, (size_t)cn * k * 4, hipMemcpyDeviceToHost, stream));
-        if (async) {
-            // nothing waits here: the results are complete once the stream is; while profiling, the batch's count
-            // of queries finished by the per-query kernel is added up on the device
-            if (ix->prof_on && !ix->force_exact) {
-                if (!ix->fb_total_live) {      // first use since the totals were read: clear it before any lane adds
-                    int rcs = sync_all(ix);
-                    if (rcs) return rcs;
-                    HIP_TRY(hipMemset(ix->fb_total.p, 0, 4));
-                    ix->fb_total_live = true;
-                }
-                hipLaunchKernelGGL(k_add_counter, dim3(1), dim3(64), 0, stream, ws.count.as<int32_t>() + 2 * ix->L, ix->fb_total.as<int32_t>());
-            }
-            continue;
-        }
+        if (async) continue;      // nothing waits here: the results are complete once the stream is
         HIP_TRY(hipStreamSynchronize(stream));
         if (ix->prof_on) {
             {   // events of asynchronous searches on other lanes may still be pending

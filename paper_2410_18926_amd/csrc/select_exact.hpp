@@ -45,6 +45,7 @@ struct SelectArgs {
     const float* sqnorm;         // [n] (Euclidean) or NULL
     const float* pt_scale;       // [n] step size of each point's code (column-wise quantization) or NULL
     int32_t* cand;               // [nq][m] out: candidate rows, -1 padded
+    int32_t* fb_total;           // optional running total of the list lengths seen (profiling), or NULL
     int w, m;
 };
 
@@ -173,6 +174,7 @@ __device__ __forceinline__ void select_exact_query(const SelectArgs& a, const in
 template <int RB>
 __global__ __launch_bounds__(256) void k_select_exact(SelectArgs a, int nq) {
     const int total = a.qlist ? *a.qcount : nq;
+    if (a.fb_total && a.qlist && blockIdx.x == 0 && threadIdx.x == 0 && total > 0) atomicAdd(a.fb_total, total);
     for (int e = blockIdx.x; e < total; e += gridDim.x) {
         select_exact_query<RB>(a, a.qlist ? a.qlist[e] : e);
         __syncthreads();

@@ -202,6 +202,21 @@ def test_survivor_overflow_falls_back_to_exact_kernel(B):
         g_ids, g_d, gst = gix.search_stages(q, k, w, m)
         np.testing.assert_array_equal(np.sort(gst["cand_rows"].astype(np.int64), axis=1), np.sort(ost["cand_rows"], axis=1))
         assert_topk_equal(g_ids, g_d, o_ids, o_d, "overflow")
+    # the count of queries finished by the per-query kernel, from synchronous, asynchronous and lane searches
+    n_fb = int((gix.search_stages(q, 10, 3, 64)[2]["n_survivors"] == -1).sum())
+    assert n_fb > 0
+    gix.profile_enable(True)
+    gix.search(q, 10, 3, 64)
+    assert gix.profile_fallback_queries() == n_fb
+    qd = torch.from_numpy(q).cuda()
+    outs = [(torch.empty((40, 10), dtype=torch.int64, device="cuda"), torch.empty((40, 10), dtype=torch.float32, device="cuda")) for _ in range(3)]
+    gix.search(qd, 10, 3, 64, out=outs[0], lane=1)
+    gix.search(qd, 10, 3, 64, out=outs[1], lane=2)
+    gix.search(qd, 10, 3, 64, out=outs[2], asynchronous=True)
+    gix.lane_join(1); gix.lane_join(2)
+    torch.cuda.synchronize()
+    assert gix.profile_fallback_queries() == 4 * n_fb
+    gix.profile_enable(False)
     gix.close()
 
 
