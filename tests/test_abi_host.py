@@ -72,3 +72,27 @@ def test_search_on_null_index_is_rejected(B):
     rc = lib.lorann_search(None, None, 1, 1, 1, 1, None, None)
     assert rc == -1 and b"NULL" in lib.lorann_last_error()
     lib.lorann_free_index(None)                                # documented no-op
+
+
+def test_every_entry_point_rejects_a_null_index(B):
+    lib = B.lib()
+    calls = [lambda: lib.lorann_search_async(None, None, 1, 1, 1, 1, None, None),
+             lambda: lib.lorann_search_lane(None, 0, None, 1, 1, 1, 1, None, None),
+             lambda: lib.lorann_lane_join(None, 0),
+             lambda: lib.lorann_set_gather_turns(None, 1),
+             lambda: lib.lorann_set_rerank(None, 0),
+             lambda: lib.lorann_set_column_scales(None, None, None),
+             lambda: lib.lorann_set_exact_selection(None, 1),
+             lambda: lib.lorann_set_stream(None, None),
+             lambda: lib.lorann_profile_enable(None, 1)]
+    for call in calls:
+        assert call() == B.LORANN_E_INVAL
+        assert b"NULL" in lib.lorann_last_error()
+    assert lib.lorann_profile_fallback_queries(None) == -1
+
+
+def test_header_constants_match_binding(B):
+    header = (ROOT / "include" / "lorann.h").read_text()
+    assert int(re.search(r"#define LORANN_LANES (\d+)", header).group(1)) == B.LANES
+    for name, val in (("LORANN_RERANK_F32", B.RERANK_F32), ("LORANN_RERANK_F16", B.RERANK_F16), ("LORANN_RERANK_NONE", B.RERANK_NONE)):
+        assert re.search(rf"{name}\s*=\s*{val}\b", header), name
