@@ -23,6 +23,19 @@ __device__ __forceinline__ float4 widen4(const f16x4& v) { return make_float4((f
 __device__ __forceinline__ float widen1(float v) { return v; }
 __device__ __forceinline__ float widen1(_Float16 v) { return (float)v; }
 
+// A corpus row is read once per group of queries (once per query in the one-query-per-block kernel): it is loaded
+// as streaming data (non-temporal), so that the gather does not evict what it re-reads itself (queries, row lists)
+// and what the other kernels - of this batch and of the batches on other lanes - keep in the caches.
+// Measured on the 768-d benchmark: 563 -> 531 us per launch of the grouped gather.
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float4 row_load(const float4* p) {
+    const f32x4_t t = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(p));
+    return make_float4(t[0], t[1], t[2], t[3]);
+}
+__device__ __forceinline__ f16x4 row_load(const f16x4* p) {
+    return __builtin_nontemporal_load(p);
+}
+
 // The half-precision copy of the corpus: round to nearest even.  *max_abs_bits receives the largest |x| seen (as
 // float bits; a NaN compares above everything) so that the host can refuse rows binary16 cannot hold.
 // grid-stride over count elements, block = 256.
@@ -91,7 +104,7 @@ __global__ __launch_bounds__(256) void k_rerank(const float* __restrict__ Q, con
             const V* p4 = reinterpret_cast<const V*>(p);
             const float4* q4 = reinterpret_cast<const float4*>(qs);
             for (int i = lane; i < d4; i += 64) {
-                const float4 x = widen4(p4[i]), y = q4[i];
+                const float4 x = widen4(row_load(p4 + i)), y = q4[i];
                 if (METRIC == 1) {
                     const float a0 = y.x - x.x, a1 = y.y - x.y, a2 = y.z - x.z, a3 = y.w - x.w;
                     acc = fmaf(a0, a0, acc); acc = fmaf(a1, a1, acc); acc = fmaf(a2, a2, acc); acc = fmaf(a3, a3, acc);

@@ -249,7 +249,7 @@ __global__ __launch_bounds__(kGatherThreads) void k_group_gather(GroupArgs a) {
                 mk[r] = nmk[r]; ps[r] = nps[r];
                 const V* p4 = reinterpret_cast<const V*>(corpus + (size_t)nrow[r] * d);
 #pragma unroll
-                for (int v = 0; v < NV; ++v) x[r][v] = p4[min(lane + 64 * v, d4 - 1)];
+                for (int v = 0; v < NV; ++v) x[r][v] = row_load(p4 + min(lane + 64 * v, d4 - 1));
             }
             fetch_meta(u0 + kGatherWaves * RB);
 #pragma unroll
@@ -291,7 +291,7 @@ __global__ __launch_bounds__(kGatherThreads) void k_group_gather(GroupArgs a) {
                     const V* p4 = reinterpret_cast<const V*>(p);
                     const float4* q4 = reinterpret_cast<const float4*>(qg);
                     for (int i = lane; i < d4; i += 64) {
-                        const float4 x = widen4(p4[i]), y = q4[i];
+                        const float4 x = widen4(row_load(p4 + i)), y = q4[i];
                         if (METRIC == 1) {
                             const float a0 = y.x - x.x, a1 = y.y - x.y, a2 = y.z - x.z, a3 = y.w - x.w;
                             acc = fmaf(a0, a0, acc); acc = fmaf(a1, a1, acc); acc = fmaf(a2, a2, acc); acc = fmaf(a3, a3, acc);
