@@ -703,3 +703,45 @@ def test_lanes_overlap_searches_with_identical_results(B, small_indexes):
     s_ids, s_d = gix.search(bufs[1], k, w, m)
     np.testing.assert_array_equal(outs[1][0].cpu().numpy(), s_ids.cpu().numpy())
     gix.close()
+
+
+@pytest.mark.parametrize("L", [40, 1500, 5000])
+@pytest.mark.parametrize("metric", [0, 1])
+def test_routing_by_screening_worst_case_rounding(B, L, metric):
+    """bfloat16 keeps 8 significant bits, so 1 + 2^-8 rounds (ties to even) down to 1 and anything just above it up
+    to 1 + 2^-7: a relative error of 2^-8 per operand, 2^-7 per product.  Centroid A and the query agree on 512
+    coordinates where both round down, centroid B and the query on 511 coordinates where both round up: A is the
+    nearest centroid (inner product 516.008 against 515.016) but the bfloat16 scores say 512.0 against 519.016, a
+    gap of 7.0 = 0.0096 |q| |mu|.  The short list must still contain A (an error bound built on a unit roundoff
+    of 2^-9 drops it)."""
+    rng = np.random.default_rng(90 + L + metric)
+    d = 1024
+    lo, hi = np.float32(1 + 2.0 ** -8), np.float32(1 + 2.0 ** -8 + 2.0 ** -16)
+    cent = (0.01 * rng.normal(size=(L, d))).astype(np.float32)
+    ia, ib = 3, L - 5
+    cent[ia] = 0.0; cent[ia, :512] = lo
+    cent[ib] = 0.0; cent[ib, 512:1023] = hi
+    q = np.zeros((6, d), np.float32)
+    q[:, :512] = lo
+    q[:, 512:1023] = hi
+    q[1] *= np.float32(0.5)                           # powers of two keep the ties
+    q[2] *= np.float32(8.0)
+    q[3, 1023] = 0.25
+    q[4, :512] = hi; q[4, 512:1023] = lo              # mixed: the query rounds up where A rounds down and vice versa
+    q[5] = q[0]; q[5, 0] = 0.0
+    sizes = rng.integers(1, 4, size=L)
+    n = int(sizes.sum())
+    off = np.zeros(L + 1, np.int64)
+    np.cumsum(sizes, out=off[1:])
+    ix = dict(metric=metric, n=n, d=d, dp=d, r=8, L=L, centroids=cent, P=None,
+              A=rng.integers(-127, 128, size=(L, 8, d)).astype(np.int8), B=rng.integers(-127, 128, size=(n, 8)).astype(np.int8),
+              scale_A=np.full(L, 0.01, np.float32), scale_B=np.full(L, 0.01, np.float32), cluster_offsets=off,
+              corpus=rng.normal(size=(n, d)).astype(np.float32), ids=None)
+    gix = B.Index(**ix)
+    oix = O.OracleIndex(ix)
+    for w in (1, 2, 3):
+        ost = O.search(oix, q, 1, w, 4, stages=True)[2]
+        gst = gix.search_stages(q, 1, w, 4)[2]
+        np.testing.assert_array_equal(gst["sel"], ost["sel"], err_msg=f"w={w}")
+    assert O.search(oix, q[:1], 1, 1, 4, stages=True)[2]["sel"][0, 0] == ia       # A is the nearest centroid of the first query
+    gix.close()

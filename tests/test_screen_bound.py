@@ -1,15 +1,16 @@
 """The error bound behind routing by screening (CPU check of the mathematics; the GPU kernels rely on it).
 
 Approximate centroid scores come from operands rounded to bfloat16 with float accumulation; the library keeps
-every cluster whose approximate value is within 2 eps of the w-th smallest, eps = 0.0042 |q| |mu| (doubled plus
+every cluster whose approximate value is within 2 eps of the w-th smallest, eps = 0.0080 |q| |mu| (doubled plus
 a float-rounding term for the Euclidean form).  Here the inequality |approximate - exact| <= eps is checked on
-seeded inputs of several scales, including ones built to be bad for bfloat16 (all mantissas just below a
-rounding boundary), with bfloat16 emulated by torch on the CPU.
+seeded inputs of several scales, including the worst case of bfloat16 (8 significant bits: every element of both
+vectors sits on, or just beside, the midpoint 1 + 2^-8 between two neighbours, all errors of one sign), with
+bfloat16 emulated by torch on the CPU.
 """
 import numpy as np
 import torch
 
-K_SCREEN_REL = 0.0042      # must equal kScreenRel in csrc/screen.hpp
+K_SCREEN_REL = 0.0080      # must equal kScreenRel in csrc/screen.hpp
 
 
 def _bf16(x):
@@ -28,10 +29,19 @@ def test_bf16_inner_product_error_is_within_the_bound():
         for scale_q, scale_c in ((1.0, 1.0), (1e-3, 40.0), (300.0, 1e-2)):
             q = (scale_q * rng.normal(size=(64, dp))).astype(np.float32)
             c = (scale_c * rng.normal(size=(200, dp))).astype(np.float32)
-            # worst case for round-to-nearest: mantissas just below the midpoint between two bfloat16 values
-            bad = (np.float32(1.0) + np.float32(2.0 ** -9) * np.float32(0.999)) * np.sign(rng.normal(size=(8, dp))).astype(np.float32)
+            # worst case for round-to-nearest: mantissas on / just below the midpoint between two bfloat16 values
+            # (1 and 1 + 2^-7), rows 0-3 with every product positive so that all errors add up; rows 4-7 just
+            # above the midpoint (rounded up)
+            bad = (np.float32(1.0) + np.float32(2.0 ** -8) * np.float32(0.9999)) * np.sign(rng.normal(size=(8, dp))).astype(np.float32)
+            bad[:2] = np.float32(1.0) + np.float32(2.0 ** -8)              # exact ties: to even, i.e. down to 1
+            bad[2:4] = np.abs(bad[2:4])
+            bad[4:] = (np.float32(1.0) + np.float32(2.0 ** -8) * np.float32(1.0001)) * np.sign(bad[4:])
             q[:8] = scale_q * bad
             c[:8] = scale_c * np.abs(bad)
+            if scale_q == 1.0 and scale_c == 1.0:                          # scales that are powers of two keep the ties
+                worst = np.abs(_bf16(q[:2]).astype(np.float64) @ _bf16(c[:2]).T.astype(np.float64) - q[:2].astype(np.float64) @ c[:2].astype(np.float64).T)
+                rel = worst / (np.linalg.norm(q[:2].astype(np.float64), axis=1)[:, None] * np.linalg.norm(c[:2].astype(np.float64), axis=1)[None, :])
+                assert rel.max() > 0.0077, "the worst case is not exercised"   # 2^-7 + 2^-16 over (1 + 2^-8)^2
             exact = q.astype(np.float64) @ c.astype(np.float64).T
             approx = (_bf16(q) @ _bf16(c).T).astype(np.float64)           # float accumulation
             bound = K_SCREEN_REL * np.linalg.norm(q.astype(np.float64), axis=1)[:, None] * np.linalg.norm(c.astype(np.float64), axis=1)[None, :]
