@@ -167,6 +167,21 @@ __global__ __launch_bounds__(256) void k_row_sqnorm(const float* __restrict__ x,
     if (lane == 0) out[row] = (OUT)acc;
 }
 
+// out[row] = sum_i (x[row][i] - xb[row][i])^2 in double: the squared norm of the error of a bfloat16 copy of x.
+__global__ __launch_bounds__(256) void k_row_bf16_err(const float* __restrict__ x, const __bf16* __restrict__ xb, double* __restrict__ out,
+                                                      int64_t rows, int d) {
+    const int lane = threadIdx.x & 63;
+    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= rows) return;
+    double acc = 0.0;
+    for (int i = lane; i < d; i += 64) {
+        const double v = (double)x[(size_t)row * d + i] - (double)(float)xb[(size_t)row * d + i];
+        acc += v * v;
+    }
+    acc = wave_sum_f64(acc);
+    if (lane == 0) out[row] = acc;
+}
+
 // Pt[j][i] = P[i][j]  (P is [d][dp]).
 __global__ void k_transpose(const float* __restrict__ P, float* __restrict__ Pt, int d, int dp) {
     const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;

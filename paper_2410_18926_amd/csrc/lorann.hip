@@ -114,6 +114,7 @@ struct lorann_index {
     float* cent_nrm_f32 = nullptr;  // [L] (Euclidean) the same norms rounded to float, for the approximate scores
     __bf16* cent_bf16 = nullptr;    // [L][dp] centroids rounded to bfloat16
     float mu_max = 0.0f;            // >= max_l |mu_l|_2 (rounded up)
+    float dmu_max = 0.0f;           // >= max_l |mu_l - bfloat16(mu_l)|_2 (rounded up)
     float nrm_max = 0.0f;           // >= max_l |mu_l|_2^2 (Euclidean)
     float* Pt = nullptr;            // [dp][d] transposed projection, or NULL
     int8_t* A = nullptr;            // [L][r][dp]
@@ -284,7 +285,7 @@ int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ
             ScreenArgs sa;
             sa.ghat = ws.gscore.as<float>(); sa.qp = qp; sa.centroids = ix->centroids;
             sa.cent_sqnorm = ix->metric == LORANN_L2 ? ix->cent_sqnorm : nullptr; sa.sel = ws.sel.as<int32_t>();
-            sa.L = L; sa.dp = dp; sa.w = w; sa.mu_max = ix->mu_max; sa.nrm_max = ix->metric == LORANN_L2 ? ix->nrm_max : 0.0f;
+            sa.L = L; sa.dp = dp; sa.w = w; sa.mu_max = ix->mu_max; sa.dmu_max = ix->dmu_max; sa.nrm_max = ix->metric == LORANN_L2 ? ix->nrm_max : 0.0f;
             const size_t lds = (size_t)dp * 4;
             if (L <= 1024) hipLaunchKernelGGL(k_select_clusters_screen_wave<16>, dim3((unsigned)((nq + 3) / 4)), dim3(256), 4 * lds, s, sa, (int)nq);
             else if (L <= 4096) hipLaunchKernelGGL(k_select_clusters_screen<16>, dim3((unsigned)nq), dim3(256), lds, s, sa);
@@ -791,6 +792,16 @@ int lorann_load_index(lorann_index** out, int32_t metric, int64_t n, int32_t d, 
             HIP_TRY(hipMalloc((void**)&ix->cent_bf16, (size_t)L * dp * 2));
             const int64_t tot = (int64_t)L * dp;
             hipLaunchKernelGGL(k_to_bf16, dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, 0, ix->centroids, ix->cent_bf16, tot);
+            // the largest rounding error of a centroid enters the same bound
+            double* err = nullptr;
+            HIP_TRY(hipMalloc((void**)&err, (size_t)L * 8));
+            hipLaunchKernelGGL(k_row_bf16_err, dim3((unsigned)((L + 3) / 4)), dim3(256), 0, 0, ix->centroids, ix->cent_bf16, err, (int64_t)L, dp);
+            he = hipMemcpy(h.data(), err, (size_t)L * 8, hipMemcpyDeviceToHost);
+            (void)hipFree(err);
+            if (he != hipSuccess) return fail(LORANN_E_DEVICE, "centroid rounding errors failed: %s", hipGetErrorString(he));
+            double mxe = 0.0;
+            for (double v : h) mxe = std::max(mxe, v);
+            ix->dmu_max = std::nextafter((float)(std::sqrt(mxe) * (1.0 + 1e-6)), INFINITY);
             HIP_TRY(hipDeviceSynchronize());
         }
         if (metric == LORANN_L2) {   // Sec. 3.1: the norms |c_j|^2 of the corpus rows are precomputed

@@ -12,12 +12,16 @@
 // dot products per query.  A list that does not fit (huge norms, long runs of near-equal values) makes the
 // block evaluate every cluster exactly instead, so correctness never rests on the bound being tight.
 //
-// Error bound.  bfloat16 keeps 8 significant bits: rounding to it (nearest even, same exponent range as float)
-// changes a number by at most 2^-8 relative (reached just above a power of two: 1 + 2^-8 becomes 1), a product of
-// two rounded numbers by at most (2^-7 + 2^-16) relative; the products are exact in float; K float additions add
-// at most ~K 2^-23 relative to the sum of magnitudes even if the matrix core truncates.  With Cauchy-Schwarz,
-// |ip_approx - ip| <= kScreenRel * |q|_2 * |mu|_2 with kScreenRel = 0.0080 >= 2^-7 + 2^-16 + 1024 * 2^-23 = 0.00795
-// (d' <= 1024).  The final float operations of both sides are covered by a relative slack of 2^-20.
+// Error bound.  Write qb = q + dq and mub = mu + dmu for the operands rounded to bfloat16.  Then
+//   <qb, mub> - <q, mu> = <dq, mu> + <qb, dmu>     (an identity),  so by Cauchy-Schwarz
+//   |<qb, mub> - <q, mu>| <= |dq|_2 |mu|_2 + |qb|_2 |dmu|_2.
+// |dq|_2 and |qb|_2 are computed from the query's ACTUAL rounding errors (the selection kernels redo the rounding
+// of their query), |mu|_2 and |dmu|_2 enter through their maxima over the centroids, computed when the index is
+// loaded.  For operands with no special structure this is about 0.003 |q||mu|; in the worst case of bfloat16 (8
+// significant bits: 1 + 2^-8 becomes 1, a relative error of 2^-8 per operand) it grows to the 2^-7 |q||mu| it has
+// to be.  The products of rounded operands are exact in float; the K float additions of the matrix core add at
+// most K 2^-23 |qb|_2 |mub|_2 even if it truncates.  All norms are rounded up by a relative 1e-3, which covers
+// their own float arithmetic; the final float operations of both sides are covered by a relative slack of 2^-20.
 //
 // Register layout of v_mfma_f32_32x32x16_bf16 (measured on gfx950): both operands give lane l eight consecutive
 // k (k-half l/32) of row / column l%32; result register v of lane l holds D[8*(v/4) + 4*(l/32) + v%4][l%32].
@@ -30,7 +34,7 @@ namespace lorann {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-constexpr float kScreenRel = 0.0080f;
+constexpr float kScreenAcc = 1.1920929e-7f;      // 2^-23: float accumulation error per term of the matrix-core sum
 
 // o[i] = bfloat16(x[i]), round to nearest even.
 __global__ void k_to_bf16(const float* __restrict__ x, __bf16* __restrict__ o, int64_t n) {
@@ -138,8 +142,15 @@ struct ScreenArgs {
     int32_t* sel;                // out [nq][w], ordered (dissimilarity ascending, cluster id ascending)
     int L, dp, w;
     float mu_max;                // >= max_l |mu_l|_2
+    float dmu_max;               // >= max_l |mu_l - bfloat16(mu_l)|_2
     float nrm_max;               // >= max_l |mu_l|_2^2 (Euclidean; else 0)
 };
+
+// Bound on |<qb, mub> - <q, mu>| for every centroid (see the header): qe >= |dq|_2, qb >= |qb|_2.
+__device__ __forceinline__ float screen_eps_ip(float qe, float qb, float mu_max, float dmu_max, int dp) {
+    const float e = qe * mu_max + qb * dmu_max + (float)dp * kScreenAcc * qb * (mu_max + dmu_max);
+    return e * 1.001f;
+}
 
 // One block (256 threads) per query; KPT approximate values per thread in registers (256 * KPT >= L).
 // dynamic LDS = dp * 4 bytes (the query).
@@ -151,7 +162,7 @@ __global__ __launch_bounds__(256) void k_select_clusters_screen(ScreenArgs a) {
     __shared__ __align__(16) unsigned long long tmin[256];
     __shared__ __align__(16) unsigned long long cand[CAP + 2];     // (key, cluster) of the first, then the final list
     __shared__ int clist[CAP];                                       // clusters evaluated exactly
-    __shared__ float s_part[4];
+    __shared__ float s_part[12];
     __shared__ int s_cnt, s_cnt2;
     __shared__ uint32_t s_bound, s_gw;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
@@ -165,10 +176,15 @@ __global__ __launch_bounds__(256) void k_select_clusters_screen(ScreenArgs a) {
     float v[KPT];
 #pragma unroll
     for (int i = 0; i < KPT; ++i) v[i] = row[min(i * 256 + tid, L - 1)];
-    float nn = 0.0f;
-    for (int i = tid; i < dp; i += 256) { const float x = qrow[i]; qs[i] = x; nn = fmaf(x, x, nn); }
-    nn = wave_sum_f32(nn);
-    if (lane == 0) s_part[wv] = nn;
+    float nn = 0.0f, ne = 0.0f, nb = 0.0f;      // |q|^2, |dq|^2, |qb|^2
+    for (int i = tid; i < dp; i += 256) {
+        const float x = qrow[i];
+        qs[i] = x;
+        const float xb = (float)(__bf16)x, e = x - xb;            // the rounding the approximate scores used; e is exact
+        nn = fmaf(x, x, nn); ne = fmaf(e, e, ne); nb = fmaf(xb, xb, nb);
+    }
+    nn = wave_sum_f32(nn); ne = wave_sum_f32(ne); nb = wave_sum_f32(nb);
+    if (lane == 0) { s_part[wv] = nn; s_part[4 + wv] = ne; s_part[8 + wv] = nb; }
     if (tid == 0) { s_cnt = 0; s_cnt2 = 0; }
     uint32_t mn = 0xFFFFFFFFu;
 #pragma unroll
@@ -178,9 +194,11 @@ __global__ __launch_bounds__(256) void k_select_clusters_screen(ScreenArgs a) {
     const unsigned long long mine = ((unsigned long long)mn << 32) | (unsigned)tid;
     tmin[tid] = mine;
     __syncthreads();
-    const float qn = sqrtf((s_part[0] + s_part[1]) + (s_part[2] + s_part[3])) * 1.00001f;
+    const float qn = sqrtf((s_part[0] + s_part[1]) + (s_part[2] + s_part[3])) * 1.001f;
+    const float qe = sqrtf((s_part[4] + s_part[5]) + (s_part[6] + s_part[7])) * 1.001f;
+    const float qb = sqrtf((s_part[8] + s_part[9]) + (s_part[10] + s_part[11])) * 1.001f;
     // |approximate - exact| <= eps for every cluster (see the header); Euclidean: g = nrm - 2 ip, nrm rounded to float
-    float eps = kScreenRel * qn * a.mu_max;
+    float eps = screen_eps_ip(qe, qb, a.mu_max, a.dmu_max, dp);
     if (l2) eps = 2.0f * eps + 2.4e-7f * (a.nrm_max + 2.0f * qn * a.mu_max);
     eps += 1e-30f;
     // w-th smallest of the 256 per-thread minima: an upper bound of the w-th smallest approximate value
@@ -363,15 +381,20 @@ __global__ __launch_bounds__(256) void k_select_clusters_screen_wave(ScreenArgs 
     float v[KPL];
 #pragma unroll
     for (int i = 0; i < KPL; ++i) v[i] = row[min(64 * i + lane, L - 1)];
-    float nn = 0.0f;
+    float nn = 0.0f, ne = 0.0f, nb = 0.0f;      // |q|^2, |dq|^2, |qb|^2
     for (int i4 = lane; i4 < d4; i4 += 64) {
         const float4 x = reinterpret_cast<const float4*>(qrow)[i4];
         reinterpret_cast<float4*>(qs)[i4] = x;
-        nn = fmaf(x.x, x.x, nn); nn = fmaf(x.y, x.y, nn); nn = fmaf(x.z, x.z, nn); nn = fmaf(x.w, x.w, nn);
+        const float xs[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const float xb = (float)(__bf16)xs[t], e = xs[t] - xb;   // the rounding the approximate scores used; e is exact
+            nn = fmaf(xs[t], xs[t], nn); ne = fmaf(e, e, ne); nb = fmaf(xb, xb, nb);
+        }
     }
-    nn = wave_sum_f32(nn);
-    const float qn = sqrtf(nn) * 1.00001f;
-    float eps = kScreenRel * qn * a.mu_max;
+    nn = wave_sum_f32(nn); ne = wave_sum_f32(ne); nb = wave_sum_f32(nb);
+    const float qn = sqrtf(nn) * 1.001f, qe = sqrtf(ne) * 1.001f, qb = sqrtf(nb) * 1.001f;
+    float eps = screen_eps_ip(qe, qb, a.mu_max, a.dmu_max, dp);
     if (l2) eps = 2.0f * eps + 2.4e-7f * (a.nrm_max + 2.0f * qn * a.mu_max);
     eps += 1e-30f;
     uint32_t key[KPL];
