@@ -268,6 +268,8 @@ int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ
         hipLaunchKernelGGL(k_quantize_rows, dim3((unsigned)((nq + 3) / 4)), dim3(256), 0, s, qp, ws.q8.as<int8_t>(), ws.dx.as<float>(), (int)nq, dp,
                            ws.count.as<int32_t>(), 2 * L + 1, screen ? ws.qbf.as<__bf16>() : (__bf16*)nullptr);
     }
+    // an approximate-score matrix beyond the caches (256 MB) is streamed: written and read once, nothing of it is worth keeping
+    const bool big_matrix = screen && L > 4096 && (int64_t)nq * L * 4 > (int64_t(256) << 20);
     if (screen) {
         {
             Prof p(ix, K_CENTROID_BF16, s);
@@ -275,9 +277,10 @@ int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ
             const int ti = blocks2 >= 256 ? 2 : 1;          // tiny problems: twice the blocks of half the height
             const dim3 grid((unsigned)((L + 127) / 128), (unsigned)((nq + 64 * ti - 1) / (64 * ti)));
             const float* nrm = ix->metric == LORANN_L2 ? ix->cent_nrm_f32 : nullptr;
-#define LAUNCH_CB(L2_, TI_) hipLaunchKernelGGL((k_centroid_bf16<L2_, TI_>), grid, dim3(256), 0, s, ws.qbf.as<__bf16>(), ix->cent_bf16, ws.gscore.as<float>(), nrm, (int)nq, L, dp)
-            if (ix->metric == LORANN_L2) { if (ti == 2) LAUNCH_CB(true, 2); else LAUNCH_CB(true, 1); }
-            else { if (ti == 2) LAUNCH_CB(false, 2); else LAUNCH_CB(false, 1); }
+#define LAUNCH_CB(L2_, TI_, NT_) hipLaunchKernelGGL((k_centroid_bf16<L2_, TI_, NT_>), grid, dim3(256), 0, s, ws.qbf.as<__bf16>(), ix->cent_bf16, ws.gscore.as<float>(), nrm, (int)nq, L, dp)
+            if (big_matrix) { if (ix->metric == LORANN_L2) LAUNCH_CB(true, 2, true); else LAUNCH_CB(false, 2, true); }
+            else if (ix->metric == LORANN_L2) { if (ti == 2) LAUNCH_CB(true, 2, false); else LAUNCH_CB(true, 1, false); }
+            else { if (ti == 2) LAUNCH_CB(false, 2, false); else LAUNCH_CB(false, 1, false); }
 #undef LAUNCH_CB
         }
         {
@@ -289,6 +292,7 @@ int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ
             const size_t lds = (size_t)dp * 4;
             if (L <= 1024) hipLaunchKernelGGL(k_select_clusters_screen_wave<16>, dim3((unsigned)((nq + 3) / 4)), dim3(256), 4 * lds, s, sa, (int)nq);
             else if (L <= 4096) hipLaunchKernelGGL(k_select_clusters_screen<16>, dim3((unsigned)nq), dim3(256), lds, s, sa);
+            else if (big_matrix) hipLaunchKernelGGL((k_select_clusters_screen<64, true>), dim3((unsigned)nq), dim3(256), lds, s, sa);
             else hipLaunchKernelGGL(k_select_clusters_screen<64>, dim3((unsigned)nq), dim3(256), lds, s, sa);
         }
     } else {

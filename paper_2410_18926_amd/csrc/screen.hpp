@@ -48,7 +48,8 @@ __global__ void k_to_bf16(const float* __restrict__ x, __bf16* __restrict__ o, i
 // tiles (TI = 2 moves fewer operand bytes; TI = 1 gives twice the blocks when the problem is small).
 // Operands go from memory straight into the registers of the lanes that feed them to the matrix core (rows
 // beyond the matrices are clamped, never stored); the two wavefronts that share rows meet in the vector cache.
-template <bool L2, int TI>
+// NT: the matrix is far larger than the caches and read once by the selection: written with streaming stores.
+template <bool L2, int TI, bool NT = false>
 __global__ __launch_bounds__(256) void k_centroid_bf16(const __bf16* __restrict__ Q, const __bf16* __restrict__ C,
                                                         float* __restrict__ out, const float* __restrict__ nrm,
                                                         int M, int N, int K) {
@@ -112,7 +113,11 @@ __global__ __launch_bounds__(256) void k_centroid_bf16(const __bf16* __restrict_
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int row = m0 + 32 * ta + 8 * (v >> 2) + 4 * h + (v & 3);
-                if (row < M && col < N) out[(size_t)row * N + col] = L2 ? nb - 2.0f * acc[ta][tb][v] : -acc[ta][tb][v];
+                if (row < M && col < N) {
+                    const float g = L2 ? nb - 2.0f * acc[ta][tb][v] : -acc[ta][tb][v];
+                    if (NT) __builtin_nontemporal_store(g, &out[(size_t)row * N + col]);
+                    else out[(size_t)row * N + col] = g;
+                }
             }
         }
 }
@@ -154,7 +159,7 @@ __device__ __forceinline__ float screen_eps_ip(float qe, float qb, float mu_max,
 
 // One block (256 threads) per query; KPT approximate values per thread in registers (256 * KPT >= L).
 // dynamic LDS = dp * 4 bytes (the query).
-template <int KPT>
+template <int KPT, bool NT = false>
 __global__ __launch_bounds__(256) void k_select_clusters_screen(ScreenArgs a) {
     constexpr int CAP = 2048;
     extern __shared__ __align__(16) unsigned char scr_smem[];
@@ -175,7 +180,7 @@ __global__ __launch_bounds__(256) void k_select_clusters_screen(ScreenArgs a) {
     // the query, its norm (rounded up), the approximate values
     float v[KPT];
 #pragma unroll
-    for (int i = 0; i < KPT; ++i) v[i] = row[min(i * 256 + tid, L - 1)];
+    for (int i = 0; i < KPT; ++i) v[i] = NT ? __builtin_nontemporal_load(&row[min(i * 256 + tid, L - 1)]) : row[min(i * 256 + tid, L - 1)];
     float nn = 0.0f, ne = 0.0f, nb = 0.0f;      // |q|^2, |dq|^2, |qb|^2
     for (int i = tid; i < dp; i += 256) {
         const float x = qrow[i];
