@@ -745,3 +745,23 @@ def test_routing_by_screening_worst_case_rounding(B, L, metric):
         np.testing.assert_array_equal(gst["sel"], ost["sel"], err_msg=f"w={w}")
     assert O.search(oix, q[:1], 1, 1, 4, stages=True)[2]["sel"][0, 0] == ia       # A is the nearest centroid of the first query
     gix.close()
+
+
+def test_routing_with_a_score_matrix_beyond_the_caches(B):
+    """9000 queries x 8192 clusters: the approximate score matrix (295 MB) takes the streaming stores / loads; the
+    selected clusters of sampled queries must equal the oracle's."""
+    rng = np.random.default_rng(44)
+    L, d, nq = 8192, 32, 9000
+    n = 2 * L
+    ix = dict(metric=1, n=n, d=d, dp=d, r=8, L=L, centroids=rng.normal(size=(L, d)).astype(np.float32), P=None,
+              A=rng.integers(-127, 128, size=(L, 8, d)).astype(np.int8), B=rng.integers(-127, 128, size=(n, 8)).astype(np.int8),
+              scale_A=np.full(L, 0.01, np.float32), scale_B=np.full(L, 0.01, np.float32),
+              cluster_offsets=np.arange(L + 1, dtype=np.int64) * 2, corpus=rng.normal(size=(n, d)).astype(np.float32), ids=None)
+    q = rng.normal(size=(nq, d)).astype(np.float32)
+    gix = B.Index(**ix)
+    gst = gix.search_stages(q, 5, 24, 20)[2]
+    pick = np.concatenate([np.arange(0, 60), np.arange(4470, 4530), np.arange(nq - 60, nq)])
+    ost = O.search(O.OracleIndex(ix), q[pick], 5, 24, 20, stages=True)[2]
+    np.testing.assert_array_equal(gst["sel"][pick], ost["sel"])
+    np.testing.assert_array_equal(gst["z"][pick], ost["z"])
+    gix.close()
