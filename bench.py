@@ -25,7 +25,7 @@ PEAK_VALU_LANE_TOPS = 256 * 64 * 2.4e9 / 1e12   # 256 CUs x 64 lanes x 2.4 GHz =
 
 # HBM bytes per launch (GB) measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by the copy-kernel
 # calibration (profiles/hbm_traffic_embed-ip_pmc.txt).  Valid for the default workload only.
-MEASURED_TRAFFIC_GB = {("embed-ip", 1.0, "rerank"): 3.29}
+MEASURED_TRAFFIC_GB = {("embed-ip", 1.0, "rerank"): 3.26}
 
 
 def log(*a):
