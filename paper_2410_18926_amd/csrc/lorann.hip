@@ -367,6 +367,8 @@ int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ
 #undef LAUNCH_SA
     }
     // Scores + candidate selection.  Batched path: pair maxima (MFMA) -> per-query walk over the few clusters whose maximum reaches the running m-th best score; the exact per-query kernel finishes what the batched path cannot.
+    const int kGroupQ = rerank_group_size(d);    // queries per re-rank group (0: rows too long to share)
+    const bool grouped = ix->rerank_mode != LORANN_RERANK_NONE && m <= 512 && !ix->force_exact && kGroupQ > 0;
     SelectArgs sa_;
     sa_.qlist = nullptr; sa_.qcount = nullptr; sa_.fb_total = nullptr; sa_.sel = ws.sel.as<int32_t>(); sa_.pos_of_slot = ws.pos_of_slot.as<int32_t>();
     sa_.Z = ws.Z.as<int8_t>(); sa_.sigma = ws.sigma.as<float>(); sa_.Bp = ix->Bp; sa_.off = ix->off;
@@ -420,17 +422,16 @@ int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ
                 else hipLaunchKernelGGL((k_select_query<4, 6>), qgrid, dim3(256), qlds, s, qa);
             }
         }
-        {
+        sa_.qlist = ws.fb_list.as<int32_t>(); sa_.qcount = ws.count.as<int32_t>() + 2 * L;
+        sa_.fb_total = fb_total;      // asynchronous searches being profiled: the count is added up on the device
+        if (!grouped) {               // (the grouped re-rank finishes these queries in the launch that orders the queries)
             Prof p(ix, K_SELECT_M, s);
-            sa_.qlist = ws.fb_list.as<int32_t>(); sa_.qcount = ws.count.as<int32_t>() + 2 * L;
-            sa_.fb_total = fb_total;      // asynchronous searches being profiled: the count is added up on the device
             const unsigned grid = (unsigned)std::min<int64_t>(nq, 1024);
             if (r_pad == 32) hipLaunchKernelGGL(k_select_exact<2>, dim3(grid), dim3(256), 0, s, sa_, (int)nq);
             else hipLaunchKernelGGL(k_select_exact<4>, dim3(grid), dim3(256), 0, s, sa_, (int)nq);
         }
     }
     const int mp2 = std::max(256, next_pow2(m));
-    const int kGroupQ = rerank_group_size(d);    // queries per re-rank group (0: rows too long to share)
     const bool half_rows = ix->rerank_mode == LORANN_RERANK_F16;
     if (ix->rerank_mode == LORANN_RERANK_NONE) {
         // no re-ranking step: the candidates (m == k here) are the answer, ordered by their estimated scores
@@ -452,12 +453,14 @@ int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ
             if (k <= 64) hipLaunchKernelGGL(k_topk_wave<4>, dim3((unsigned)((nq + 3) / 4)), dim3(256), 0, s, ga);
             else hipLaunchKernelGGL(k_topk, dim3((unsigned)nq), dim3(256), (size_t)mp2 * 12, s, ga, mp2);
         }
-    } else if (m <= 512 && !ix->force_exact && kGroupQ > 0) {
+    } else if (grouped) {
         // grouped re-rank: neighbours in the visiting order share candidate rows, each distinct row is gathered once
         {
             Prof p(ix, K_ORDER, s);
-            hipLaunchKernelGGL(k_order_queries, dim3((unsigned)L), dim3(64), 0, s, ws.qorder.as<int32_t>(), ws.off0.as<int32_t>(), L, (int)nq,
-                               ws.qkey.as<int32_t>(), ws.qorder2.as<int32_t>());
+            const int fb_blocks = (int)std::min<int64_t>(nq, 1024);
+            const dim3 grid((unsigned)(fb_blocks + L));
+            if (r_pad == 32) hipLaunchKernelGGL(k_finish_and_order<2>, grid, dim3(256), 0, s, sa_, fb_blocks, ws.qorder.as<int32_t>(), ws.off0.as<int32_t>(), L, (int)nq, ws.qkey.as<int32_t>(), ws.qorder2.as<int32_t>());
+            else hipLaunchKernelGGL(k_finish_and_order<4>, grid, dim3(256), 0, s, sa_, fb_blocks, ws.qorder.as<int32_t>(), ws.off0.as<int32_t>(), L, (int)nq, ws.qkey.as<int32_t>(), ws.qorder2.as<int32_t>());
         }
         const int64_t ngroups = (nq + kGroupQ - 1) / kGroupQ;
         const size_t gm = (size_t)kGroupQ * m;

@@ -18,6 +18,7 @@
 
 #include "common.hpp"
 #include "rerank.hpp"
+#include "select_exact.hpp"
 
 namespace lorann {
 
@@ -26,25 +27,50 @@ constexpr int kGroupMax = 16;     // queries per group: 8 or 16 (one 16-bit mask
 // Order the queries inside each nearest-cluster segment of `qorder` by `qkey` (their smallest candidate row), so
 // that queries with overlapping candidate sets become neighbours.  grid = L, block = 64 (one wavefront per
 // cluster).  Segments longer than 1024 queries are copied unchanged (the order is only a locality hint).
-__global__ __launch_bounds__(64) void k_order_queries(const int32_t* __restrict__ qorder, const int32_t* __restrict__ off0,
-                                                      int L, int nq, const int32_t* __restrict__ qkey,
-                                                      int32_t* __restrict__ qorder2) {
+__device__ __forceinline__ void order_segment(int c, const int32_t* __restrict__ qorder, const int32_t* __restrict__ off0,
+                                              int L, int nq, const int32_t* __restrict__ qkey, int32_t* __restrict__ qorder2) {
     __shared__ int skey[1024], sq[1024];
-    const int c = blockIdx.x, lane = threadIdx.x;
+    const int tid = threadIdx.x, nt = blockDim.x;
     const int beg = off0[c], end = c + 1 < L ? off0[c + 1] : nq;
     const int len = end - beg;
-    if (len <= 0) return;
+    if (len <= 0) return;                              // uniform over the block
     if (len > 1024) {
-        for (int e = lane; e < len; e += 64) qorder2[beg + e] = qorder[beg + e];
+        for (int e = tid; e < len; e += nt) qorder2[beg + e] = qorder[beg + e];
         return;
     }
-    for (int e = lane; e < len; e += 64) { const int q = qorder[beg + e]; sq[e] = q; skey[e] = qkey[q]; }
+    for (int e = tid; e < len; e += nt) { const int q = qorder[beg + e]; sq[e] = q; skey[e] = qkey[q]; }
     __syncthreads();
-    for (int e = lane; e < len; e += 64) {
+    for (int e = tid; e < len; e += nt) {
         const int k = skey[e], q = sq[e];
         int rank = 0;
         for (int u = 0; u < len; ++u) rank += (skey[u] < k || (skey[u] == k && sq[u] < q)) ? 1 : 0;
         qorder2[beg + rank] = q;
+    }
+}
+
+__global__ __launch_bounds__(64) void k_order_queries(const int32_t* __restrict__ qorder, const int32_t* __restrict__ off0,
+                                                      int L, int nq, const int32_t* __restrict__ qkey,
+                                                      int32_t* __restrict__ qorder2) {
+    order_segment(blockIdx.x, qorder, off0, L, nq, qkey, qorder2);
+}
+
+// Two short, mutually independent steps of a batch in ONE launch (every launch is several microseconds of latency in
+// the chain of a batch, more when other batches keep the machine busy): blocks [0, fb_blocks) finish, with the exact
+// per-query kernel, the queries that the batched selection handed over (usually none); block fb_blocks + c orders the
+// queries of nearest-cluster segment c.  grid = fb_blocks + L, block = 256.
+template <int RB>
+__global__ __launch_bounds__(256) void k_finish_and_order(SelectArgs a, int fb_blocks, const int32_t* __restrict__ qorder,
+                                                          const int32_t* __restrict__ off0, int L, int nq,
+                                                          const int32_t* __restrict__ qkey, int32_t* __restrict__ qorder2) {
+    if ((int)blockIdx.x >= fb_blocks) {                // uniform over the block
+        order_segment((int)blockIdx.x - fb_blocks, qorder, off0, L, nq, qkey, qorder2);
+        return;
+    }
+    const int total = *a.qcount;
+    if (a.fb_total && blockIdx.x == 0 && threadIdx.x == 0 && total > 0) atomicAdd(a.fb_total, total);
+    for (int e = blockIdx.x; e < total; e += fb_blocks) {
+        select_exact_query<RB>(a, a.qlist[e]);
+        __syncthreads();
     }
 }
 
