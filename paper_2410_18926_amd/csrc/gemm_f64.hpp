@@ -45,7 +45,7 @@ __device__ __forceinline__ float4 gemm_fetch_tail(const float* __restrict__ p, i
 template <int EPI, int BM>
 __global__ __launch_bounds__(256) void k_gemm_nt_f64(const float* __restrict__ X, const float* __restrict__ W,
                                                       float* __restrict__ out, const double* __restrict__ nrm,
-                                                      int M, int N, int K, int vec_ok) {
+                                                      int M, int N, int K, int vec_ok, __bf16* __restrict__ out_bf = nullptr) {
     constexpr int TI = BM / 32;          // 16-row MFMA tiles per wavefront along M
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int wm = wv >> 1, wn = wv & 1;
@@ -140,6 +140,7 @@ __global__ __launch_bounds__(256) void k_gemm_nt_f64(const float* __restrict__ X
                     else if (EPI == EPI_NEG) o = (float)(-s);
                     else o = (float)(nrm[col] - 2.0 * s);
                     out[(size_t)row * N + col] = o;
+                    if (EPI == EPI_PLAIN && out_bf) out_bf[(size_t)row * N + col] = (__bf16)o;     // bfloat16 copy of the same matrix
                 }
             }
         }

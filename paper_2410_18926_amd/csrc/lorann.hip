@@ -250,20 +250,25 @@ int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ
     if ((rc = ws.cand.reserve((size_t)nq * m * 4))) return rc;
 
     const float* qp = dQ;   // projected queries
+    // Few clusters (one wavefront per query selects): the projection also writes the bfloat16 copy of q', the
+    // selection kernel also quantizes its query and clears the batch's counters - one pass over the queries less.
+    const bool fused_quant = !ix->force_exact && L <= 1024 && ix->Pt != nullptr;
+    if (fused_quant && (rc = ws.qbf.reserve((size_t)nq * dp * 2))) return rc;
+    __bf16* proj_bf = fused_quant ? ws.qbf.as<__bf16>() : nullptr;
     if (ix->Pt) {
         Prof p(ix, K_PROJECT, s);
         const int pvec = (d % 4 == 0 && (reinterpret_cast<uintptr_t>(dQ) & 15u) == 0 && (reinterpret_cast<uintptr_t>(ix->Pt) & 15u) == 0) ? 1 : 0;
         if (gemm_pick_bm(nq, dp) == 64)
-            hipLaunchKernelGGL((k_gemm_nt_f64<EPI_PLAIN, 64>), dim3((dp + 63) / 64, (unsigned)((nq + 63) / 64)), dim3(256), 0, s, dQ, ix->Pt, ws.qproj.as<float>(), (const double*)nullptr, (int)nq, dp, d, pvec);
+            hipLaunchKernelGGL((k_gemm_nt_f64<EPI_PLAIN, 64>), dim3((dp + 63) / 64, (unsigned)((nq + 63) / 64)), dim3(256), 0, s, dQ, ix->Pt, ws.qproj.as<float>(), (const double*)nullptr, (int)nq, dp, d, pvec, proj_bf);
         else
-            hipLaunchKernelGGL((k_gemm_nt_f64<EPI_PLAIN, 32>), dim3((dp + 63) / 64, (unsigned)((nq + 31) / 32)), dim3(256), 0, s, dQ, ix->Pt, ws.qproj.as<float>(), (const double*)nullptr, (int)nq, dp, d, pvec);
+            hipLaunchKernelGGL((k_gemm_nt_f64<EPI_PLAIN, 32>), dim3((dp + 63) / 64, (unsigned)((nq + 31) / 32)), dim3(256), 0, s, dQ, ix->Pt, ws.qproj.as<float>(), (const double*)nullptr, (int)nq, dp, d, pvec, proj_bf);
         qp = ws.qproj.as<float>();
     }
     // Routing by screening (approximate scores on the bf16 matrix cores, exact evaluation of a short list) unless
     // verification asks for the plain route or the row of values does not fit the registers of a block.
     const bool screen = !ix->force_exact && L <= 16384;
-    if (screen && (rc = ws.qbf.reserve((size_t)nq * dp * 2))) return rc;
-    {
+    if (screen && !fused_quant && (rc = ws.qbf.reserve((size_t)nq * dp * 2))) return rc;
+    if (!fused_quant) {
         Prof p(ix, K_QUANTIZE, s);
         hipLaunchKernelGGL(k_quantize_rows, dim3((unsigned)((nq + 3) / 4)), dim3(256), 0, s, qp, ws.q8.as<int8_t>(), ws.dx.as<float>(), (int)nq, dp,
                            ws.count.as<int32_t>(), 2 * L + 1, screen ? ws.qbf.as<__bf16>() : (__bf16*)nullptr);
@@ -289,6 +294,8 @@ int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ
             sa.ghat = ws.gscore.as<float>(); sa.qp = qp; sa.centroids = ix->centroids;
             sa.cent_sqnorm = ix->metric == LORANN_L2 ? ix->cent_sqnorm : nullptr; sa.sel = ws.sel.as<int32_t>();
             sa.L = L; sa.dp = dp; sa.w = w; sa.mu_max = ix->mu_max; sa.dmu_max = ix->dmu_max; sa.nrm_max = ix->metric == LORANN_L2 ? ix->nrm_max : 0.0f;
+            sa.q8 = fused_quant ? ws.q8.as<int8_t>() : nullptr; sa.dx = ws.dx.as<float>();
+            sa.zero = fused_quant ? ws.count.as<int32_t>() : nullptr; sa.nzero = 2 * L + 1;
             const size_t lds = (size_t)dp * 4;
             if (L <= 1024) hipLaunchKernelGGL(k_select_clusters_screen_wave<16>, dim3((unsigned)((nq + 3) / 4)), dim3(256), 4 * lds, s, sa, (int)nq);
             else if (L <= 4096) hipLaunchKernelGGL(k_select_clusters_screen<16>, dim3((unsigned)nq), dim3(256), lds, s, sa);

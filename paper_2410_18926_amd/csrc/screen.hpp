@@ -148,6 +148,12 @@ struct ScreenArgs {
     int L, dp, w;
     float mu_max;                // >= max_l |mu_l|_2
     float dmu_max;               // >= max_l |mu_l - bfloat16(mu_l)|_2
+    // optional (wavefront-per-query kernel): the absmax quantization of the query (Sec. 3.3) done here as well,
+    // and the batch's counters cleared, so that no separate pass over the queries is needed
+    int8_t* q8;                  // out [nq][dp] or NULL
+    float* dx;                   // out [nq]
+    int32_t* zero;               // [nzero] cleared by this launch, or NULL
+    int nzero;
     float nrm_max;               // >= max_l |mu_l|_2^2 (Euclidean; else 0)
 };
 
@@ -370,6 +376,7 @@ __global__ __launch_bounds__(256) void k_select_clusters_screen_wave(ScreenArgs 
     __shared__ uint32_t selk[4][256];
     __shared__ int seli[4][256];
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    if (a.zero) for (int i = blockIdx.x * 256 + threadIdx.x; i < a.nzero; i += gridDim.x * 256) a.zero[i] = 0;
     const int q = blockIdx.x * 4 + wv;
     if (q >= nq) return;                       // wavefronts are independent: no block barrier below
     const int L = a.L, dp = a.dp, w = a.w;
@@ -387,6 +394,7 @@ __global__ __launch_bounds__(256) void k_select_clusters_screen_wave(ScreenArgs 
 #pragma unroll
     for (int i = 0; i < KPL; ++i) v[i] = row[min(64 * i + lane, L - 1)];
     float nn = 0.0f, ne = 0.0f, nb = 0.0f;      // |q|^2, |dq|^2, |qb|^2
+    float amax = 0.0f;
     for (int i4 = lane; i4 < d4; i4 += 64) {
         const float4 x = reinterpret_cast<const float4*>(qrow)[i4];
         reinterpret_cast<float4*>(qs)[i4] = x;
@@ -395,7 +403,24 @@ __global__ __launch_bounds__(256) void k_select_clusters_screen_wave(ScreenArgs 
         for (int t = 0; t < 4; ++t) {
             const float xb = (float)(__bf16)xs[t], e = xs[t] - xb;   // the rounding the approximate scores used; e is exact
             nn = fmaf(xs[t], xs[t], nn); ne = fmaf(e, e, ne); nb = fmaf(xb, xb, nb);
+            amax = fmaxf(amax, fabsf(xs[t]));
         }
+    }
+    if (a.q8) {     // uniform: absmax codes of the query, exactly as k_quantize_rows computes them
+        amax = wave_max_f32(amax);
+        int8_t* o = a.q8 + (size_t)q * dp;
+        const bool any = amax > 0.0f;
+        const float cx = any ? (float)(127.0 / (double)amax) : 0.0f;
+        for (int i4 = lane; i4 < d4; i4 += 64) {
+            const float4 x = reinterpret_cast<const float4*>(qrow)[i4];      // this lane's own elements: still in its cache
+            const float xs[4] = {x.x, x.y, x.z, x.w};
+            char4 c;
+            int v0 = max(-127, min(127, (int)rintf(__fmul_rn(xs[0], cx)))), v1 = max(-127, min(127, (int)rintf(__fmul_rn(xs[1], cx))));
+            int v2 = max(-127, min(127, (int)rintf(__fmul_rn(xs[2], cx)))), v3 = max(-127, min(127, (int)rintf(__fmul_rn(xs[3], cx))));
+            c.x = (signed char)(any ? v0 : 0); c.y = (signed char)(any ? v1 : 0); c.z = (signed char)(any ? v2 : 0); c.w = (signed char)(any ? v3 : 0);
+            reinterpret_cast<char4*>(o)[i4] = c;
+        }
+        if (lane == 0) a.dx[q] = any ? (float)((double)amax / 127.0) : 0.0f;
     }
     nn = wave_sum_f32(nn); ne = wave_sum_f32(ne); nb = wave_sum_f32(nb);
     const float qn = sqrtf(nn) * 1.001f, qe = sqrtf(ne) * 1.001f, qb = sqrtf(nb) * 1.001f;
