@@ -346,16 +346,25 @@ int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ
             hipLaunchKernelGGL(k_bucket_count_global, dim3((unsigned)((npairs + 255) / 256)), dim3(256), 0, s, ws.sel.as<int32_t>(), npairs, w, cnt, cnt + L,
                                ws.rank_in_bucket.as<int32_t>(), ws.qrank.as<int32_t>());
     }
-    {
+    const bool fused_scan = L <= 1024;       // the scatter kernel scans the counters itself
+    if (!fused_scan) {
         Prof p(ix, K_SCAN, s);
         hipLaunchKernelGGL(k_scan_buckets, dim3((unsigned)((L + 1023) / 1024)), dim3(1024), 0, s, ws.count.as<int32_t>(), ws.count.as<int32_t>() + L, ix->off, L, kUnitPairs, 32 * kChunkTiles, ws.bucket_off.as<int32_t>(),
                            ws.tile_off.as<int32_t>(), ws.unit_off.as<int32_t>(), ws.off0.as<int32_t>());
     }
     {
         Prof p(ix, K_SCATTER, s);
-        hipLaunchKernelGGL(k_scatter_pairs, dim3((unsigned)((npairs + 255) / 256)), dim3(256), 0, s, ws.sel.as<int32_t>(), npairs, w, L, ws.bucket_off.as<int32_t>(),
-                           ws.rank_in_bucket.as<int32_t>(), ws.off0.as<int32_t>(), ws.qrank.as<int32_t>(), base_tab, base0_tab, ws.slot_of_pos.as<int32_t>(),
-                           ws.pos_of_slot.as<int32_t>(), ws.pmax.as<uint32_t>(), ws.qorder.as<int32_t>());
+        ScanArgs sc;
+        sc.count = ws.count.as<int32_t>(); sc.count0 = ws.count.as<int32_t>() + L; sc.off = ix->off; sc.unit_pairs = kUnitPairs; sc.chunk_points = 32 * kChunkTiles;
+        sc.tile_off = ws.tile_off.as<int32_t>(); sc.unit_off = ws.unit_off.as<int32_t>();
+        if (fused_scan)
+            hipLaunchKernelGGL(k_scatter_pairs<true>, dim3((unsigned)((npairs + 255) / 256)), dim3(256), 0, s, ws.sel.as<int32_t>(), npairs, w, L, ws.bucket_off.as<int32_t>(),
+                               ws.rank_in_bucket.as<int32_t>(), ws.off0.as<int32_t>(), ws.qrank.as<int32_t>(), base_tab, base0_tab, ws.slot_of_pos.as<int32_t>(),
+                               ws.pos_of_slot.as<int32_t>(), ws.pmax.as<uint32_t>(), ws.qorder.as<int32_t>(), sc);
+        else
+            hipLaunchKernelGGL(k_scatter_pairs<false>, dim3((unsigned)((npairs + 255) / 256)), dim3(256), 0, s, ws.sel.as<int32_t>(), npairs, w, L, ws.bucket_off.as<int32_t>(),
+                               ws.rank_in_bucket.as<int32_t>(), ws.off0.as<int32_t>(), ws.qrank.as<int32_t>(), base_tab, base0_tab, ws.slot_of_pos.as<int32_t>(),
+                               ws.pos_of_slot.as<int32_t>(), ws.pmax.as<uint32_t>(), ws.qorder.as<int32_t>(), sc);
     }
     {
         Prof p(ix, K_STAGE_A, s);

@@ -410,22 +410,81 @@ __global__ __launch_bounds__(1024) void k_scan_buckets(const int32_t* __restrict
 // bucket start + offset of its block + its rank inside the block (the order inside a bucket is arbitrary; no
 // result depends on it).  Also clears the pair's best-score key for the scoring kernels, and places every query
 // into the list ordered by nearest cluster.  base_tab == NULL: ranks are already bucket-wide.
+// SCAN (L <= 1024): step 2 is done here as well - every block scans the L counters on its own in LDS (16 KB of
+// cached reads per block is cheaper than one more kernel in the chain of a batch) and block 0 writes the four
+// offset arrays of k_scan_buckets for the kernels that follow; bucket_off / off0 are then outputs.
+struct ScanArgs {
+    const int32_t* count; const int32_t* count0; const int64_t* off;
+    int unit_pairs, chunk_points;
+    int32_t* tile_off; int32_t* unit_off;
+};
+template <bool SCAN>
 __global__ __launch_bounds__(256) void k_scatter_pairs(const int32_t* __restrict__ sel, int64_t npairs, int w, int L,
-                                                        const int32_t* __restrict__ bucket_off, const int32_t* __restrict__ rank_in_bucket,
-                                                        const int32_t* __restrict__ off0, const int32_t* __restrict__ qrank,
+                                                        int32_t* __restrict__ bucket_off, const int32_t* __restrict__ rank_in_bucket,
+                                                        int32_t* __restrict__ off0, const int32_t* __restrict__ qrank,
                                                         const int32_t* __restrict__ base_tab, const int32_t* __restrict__ base0_tab,
                                                         int32_t* __restrict__ slot_of_pos, int32_t* __restrict__ pos_of_slot,
-                                                        uint32_t* __restrict__ pmax, int32_t* __restrict__ qorder) {
+                                                        uint32_t* __restrict__ pmax, int32_t* __restrict__ qorder, ScanArgs sc) {
+    __shared__ int s_boff[SCAN ? 1024 : 1], s_off0[SCAN ? 1024 : 1];
+    __shared__ int wtot[4][4];
+    if (SCAN) {
+        const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+        int f[4][4], tot[4] = {0, 0, 0, 0};                   // thread t owns clusters 4t .. 4t+3
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int c = min(4 * tid + j, L - 1);
+            const bool in = 4 * tid + j < L;
+            const int a = sc.count[c];
+            const int m_c = (int)(sc.off[c + 1] - sc.off[c]);
+            f[j][0] = in ? a : 0;
+            f[j][1] = in ? (a + 15) >> 4 : 0;
+            f[j][2] = in ? ((a + sc.unit_pairs - 1) / sc.unit_pairs) * ((m_c + sc.chunk_points - 1) / sc.chunk_points) : 0;
+            f[j][3] = in ? sc.count0[c] : 0;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) tot[k] += f[j][k];
+        }
+        int incl[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            int x = tot[k];
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) { const int t = __shfl_up(x, o, 64); if (lane >= o) x += t; }
+            incl[k] = x;
+            if (lane == 63) wtot[k][wv] = x;
+        }
+        __syncthreads();
+        int run[4], total[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            int before = 0, all = 0;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { const int t = wtot[k][i]; if (i < wv) before += t; all += t; }
+            run[k] = incl[k] - tot[k] + before;                 // exclusive prefix of this thread's first cluster
+            total[k] = all;
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int c = 4 * tid + j;
+            if (c < L) {
+                s_boff[c] = run[0]; s_off0[c] = run[3];
+                if (blockIdx.x == 0) { bucket_off[c] = run[0]; sc.tile_off[c] = run[1]; sc.unit_off[c] = run[2]; off0[c] = run[3]; }
+            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k) run[k] += f[j][k];
+        }
+        if (blockIdx.x == 0 && tid == 0) { bucket_off[L] = total[0]; sc.tile_off[L] = total[1]; sc.unit_off[L] = total[2]; }
+        __syncthreads();
+    }
     const int64_t p = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (p >= npairs) return;
+    if (p >= npairs) return;                                   // no barrier below
     const int c = sel[p];
     const int q = (int)(p / w);
     const size_t tb = (size_t)(q / kBucketQueries) * L + c;
-    const int pos = bucket_off[c] + (base_tab ? base_tab[tb] : 0) + rank_in_bucket[p];
+    const int pos = (SCAN ? s_boff[c] : bucket_off[c]) + (base_tab ? base_tab[tb] : 0) + rank_in_bucket[p];
     slot_of_pos[pos] = (int32_t)p;
     pos_of_slot[p] = pos;
     pmax[p] = 0u;
-    if (p % w == 0) qorder[off0[c] + (base0_tab ? base0_tab[tb] : 0) + qrank[q]] = q;
+    if (p % w == 0) qorder[(SCAN ? s_off0[c] : off0[c]) + (base0_tab ? base0_tab[tb] : 0) + qrank[q]] = q;
 }
 
 __global__ void k_zero_i32(int32_t* __restrict__ p, int64_t n) {
