@@ -250,9 +250,9 @@ int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ
     if ((rc = ws.cand.reserve((size_t)nq * m * 4))) return rc;
 
     const float* qp = dQ;   // projected queries
-    // Few clusters (one wavefront per query selects): the projection also writes the bfloat16 copy of q', the
-    // selection kernel also quantizes its query and clears the batch's counters - one pass over the queries less.
-    const bool fused_quant = !ix->force_exact && L <= 1024 && ix->Pt != nullptr;
+    // With a projection and routing by screening: the projection also writes the bfloat16 copy of q', the selection
+    // kernel also quantizes its query and clears the batch's counters - one pass over the queries less.
+    const bool fused_quant = !ix->force_exact && L <= 16384 && ix->Pt != nullptr;
     if (fused_quant && (rc = ws.qbf.reserve((size_t)nq * dp * 2))) return rc;
     __bf16* proj_bf = fused_quant ? ws.qbf.as<__bf16>() : nullptr;
     if (ix->Pt) {

@@ -148,7 +148,7 @@ struct ScreenArgs {
     int L, dp, w;
     float mu_max;                // >= max_l |mu_l|_2
     float dmu_max;               // >= max_l |mu_l - bfloat16(mu_l)|_2
-    // optional (wavefront-per-query kernel): the absmax quantization of the query (Sec. 3.3) done here as well,
+    // optional: the absmax quantization of the query (Sec. 3.3) done here as well,
     // and the batch's counters cleared, so that no separate pass over the queries is needed
     int8_t* q8;                  // out [nq][dp] or NULL
     float* dx;                   // out [nq]
@@ -173,7 +173,7 @@ __global__ __launch_bounds__(256) void k_select_clusters_screen(ScreenArgs a) {
     __shared__ __align__(16) unsigned long long tmin[256];
     __shared__ __align__(16) unsigned long long cand[CAP + 2];     // (key, cluster) of the first, then the final list
     __shared__ int clist[CAP];                                       // clusters evaluated exactly
-    __shared__ float s_part[12];
+    __shared__ float s_part[16];
     __shared__ int s_cnt, s_cnt2;
     __shared__ uint32_t s_bound, s_gw;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
@@ -187,15 +187,18 @@ __global__ __launch_bounds__(256) void k_select_clusters_screen(ScreenArgs a) {
     float v[KPT];
 #pragma unroll
     for (int i = 0; i < KPT; ++i) v[i] = NT ? __builtin_nontemporal_load(&row[min(i * 256 + tid, L - 1)]) : row[min(i * 256 + tid, L - 1)];
+    if (a.zero) for (int i = blockIdx.x * 256 + tid; i < a.nzero; i += gridDim.x * 256) a.zero[i] = 0;
     float nn = 0.0f, ne = 0.0f, nb = 0.0f;      // |q|^2, |dq|^2, |qb|^2
+    float amax = 0.0f;
     for (int i = tid; i < dp; i += 256) {
         const float x = qrow[i];
         qs[i] = x;
         const float xb = (float)(__bf16)x, e = x - xb;            // the rounding the approximate scores used; e is exact
         nn = fmaf(x, x, nn); ne = fmaf(e, e, ne); nb = fmaf(xb, xb, nb);
+        amax = fmaxf(amax, fabsf(x));
     }
-    nn = wave_sum_f32(nn); ne = wave_sum_f32(ne); nb = wave_sum_f32(nb);
-    if (lane == 0) { s_part[wv] = nn; s_part[4 + wv] = ne; s_part[8 + wv] = nb; }
+    nn = wave_sum_f32(nn); ne = wave_sum_f32(ne); nb = wave_sum_f32(nb); amax = wave_max_f32(amax);
+    if (lane == 0) { s_part[wv] = nn; s_part[4 + wv] = ne; s_part[8 + wv] = nb; s_part[12 + wv] = amax; }
     if (tid == 0) { s_cnt = 0; s_cnt2 = 0; }
     uint32_t mn = 0xFFFFFFFFu;
 #pragma unroll
@@ -205,6 +208,17 @@ __global__ __launch_bounds__(256) void k_select_clusters_screen(ScreenArgs a) {
     const unsigned long long mine = ((unsigned long long)mn << 32) | (unsigned)tid;
     tmin[tid] = mine;
     __syncthreads();
+    if (a.q8) {     // uniform: absmax codes of the query, exactly as k_quantize_rows computes them
+        const float am = fmaxf(fmaxf(s_part[12], s_part[13]), fmaxf(s_part[14], s_part[15]));
+        const bool any = am > 0.0f;
+        const float cx = any ? (float)(127.0 / (double)am) : 0.0f;
+        int8_t* o = a.q8 + (size_t)blockIdx.x * dp;
+        for (int i = tid; i < dp; i += 256) {
+            const int c8 = max(-127, min(127, (int)rintf(__fmul_rn(qs[i], cx))));
+            o[i] = (int8_t)(any ? c8 : 0);
+        }
+        if (tid == 0) a.dx[blockIdx.x] = any ? (float)((double)am / 127.0) : 0.0f;
+    }
     const float qn = sqrtf((s_part[0] + s_part[1]) + (s_part[2] + s_part[3])) * 1.001f;
     const float qe = sqrtf((s_part[4] + s_part[5]) + (s_part[6] + s_part[7])) * 1.001f;
     const float qb = sqrtf((s_part[8] + s_part[9]) + (s_part[10] + s_part[11])) * 1.001f;

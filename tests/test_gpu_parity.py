@@ -765,3 +765,22 @@ def test_routing_with_a_score_matrix_beyond_the_caches(B):
     np.testing.assert_array_equal(gst["sel"][pick], ost["sel"])
     np.testing.assert_array_equal(gst["z"][pick], ost["z"])
     gix.close()
+
+
+@pytest.mark.parametrize("L,metric", [(900, 0), (3000, 1), (6000, 2), (16384, 0)])
+def test_query_codes_when_the_selection_kernel_quantizes(B, L, metric):
+    """With a projection and routing by screening the query is quantized inside the cluster-selection kernel (one
+    wavefront or one block per query) and the projection writes the bfloat16 copy: projected queries, codes, step
+    sizes and selected clusters bit-exact, an all-zero query included."""
+    rng = np.random.default_rng(3000 + L)
+    n = 2 * L + 17
+    ix = _random_index(rng, n=n, d=48, L=L, r=8, metric=metric, dp=32)
+    q = rng.normal(size=(70, 48)).astype(np.float32) * np.exp(rng.normal(size=(70, 1)) * 2).astype(np.float32)
+    q[5] = 0.0
+    gix = B.Index(**ix)
+    o_ids, o_d, ost = O.search(O.OracleIndex(ix), q, 5, 12, 30, stages=True)
+    g_ids, g_d, gst = gix.search_stages(q, 5, 12, 30)
+    for key in ("qproj", "q8", "dx", "sel", "z", "sigma"):
+        np.testing.assert_array_equal(gst[key], ost[key], err_msg=key)
+    assert_topk_equal(g_ids, g_d, o_ids, o_d, f"L={L}")
+    gix.close()
