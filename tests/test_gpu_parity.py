@@ -784,3 +784,65 @@ def test_query_codes_when_the_selection_kernel_quantizes(B, L, metric):
         np.testing.assert_array_equal(gst[key], ost[key], err_msg=key)
     assert_topk_equal(g_ids, g_d, o_ids, o_d, f"L={L}")
     gix.close()
+
+
+@pytest.mark.parametrize("seed", list(range(24)))
+def test_randomized_configurations(B, seed):
+    """Seeded random shapes and parameters - metric, d, d' (with and without projection), rank, cluster count and
+    sizes (empty clusters included), w, m, k, per-cluster or column-wise step sizes, re-rank mode, batch size - each
+    compared with the oracle: selected clusters, re-quantized vectors, pair scales and candidate sets bit-exact,
+    results to the usual bar."""
+    rng = np.random.default_rng(7000 + seed)
+    metric = int(rng.integers(0, 3))
+    dp = int(rng.choice([16, 32, 48, 64, 128, 256]))
+    d = dp if rng.random() < 0.3 else int(dp + rng.integers(1, 200))
+    r = int(rng.choice([8, 16, 24, 32, 40, 64]))
+    L = int(rng.choice([1, 2, 7, 33, 150, 700, 1300, 2500]))
+    n = int(max(L, rng.integers(L, 40 * L + 50)))
+    nq = int(rng.choice([1, 3, 17, 64, 130, 400]))
+    w = int(rng.integers(1, min(L, 40) + 1))
+    m = int(rng.choice([1, 5, 30, 100, 256, 300, 600]))
+    k = int(rng.integers(1, min(m, 80) + 1))
+    ix = _random_index(rng, n=max(n, 2), d=d, L=L, r=r, metric=metric, dp=dp) if L > 1 else None
+    if ix is None:      # a single cluster
+        n = max(n, 2)
+        corpus = rng.normal(size=(n, d)).astype(np.float32)
+        if metric == 2:
+            corpus /= np.linalg.norm(corpus, axis=1, keepdims=True)
+        P = None if dp == d else np.linalg.qr(rng.normal(size=(d, d)))[0][:, :dp].astype(np.float32)
+        ix = dict(metric=metric, n=n, d=d, dp=dp, r=r, L=1, centroids=rng.normal(size=(1, dp)).astype(np.float32), P=P,
+                  A=rng.integers(-127, 128, size=(1, r, dp)).astype(np.int8), B=rng.integers(-127, 128, size=(n, r)).astype(np.int8),
+                  scale_A=np.array([0.03], np.float32), scale_B=np.array([0.05], np.float32),
+                  cluster_offsets=np.array([0, n], np.int64), corpus=corpus, ids=None)
+    n = ix["n"]
+    if L > 3:           # some empty clusters
+        off = ix["cluster_offsets"].copy()
+        for c in rng.choice(np.arange(1, L), size=min(3, L - 1), replace=False):
+            off[c] = off[c - 1]
+        ix["cluster_offsets"] = np.maximum.accumulate(off)
+    if rng.random() < 0.4:
+        ix["scale_A_columns"] = (10.0 ** rng.uniform(-3, 0, size=(L, r))).astype(np.float32)
+        ix["scale_B_points"] = (10.0 ** rng.uniform(-3, 0, size=n)).astype(np.float32)
+    q = rng.normal(size=(nq, d)).astype(np.float32)
+    mode = int(rng.choice([B.RERANK_F32, B.RERANK_F32, B.RERANK_F16, B.RERANK_NONE]))
+    what = f"seed={seed} metric={metric} d={d} dp={dp} r={r} L={L} n={n} nq={nq} w={w} m={m} k={k} cols={'scale_A_columns' in ix} mode={mode}"
+    gix = B.Index(**ix)
+    gix.set_rerank(mode)
+    oracle_ix = O.with_half_precision_corpus(ix) if mode == B.RERANK_F16 else ix
+    oix = O.OracleIndex(oracle_ix)
+    if mode == B.RERANK_NONE:
+        o_ids, o_d = O.search_no_rerank(oix, q, k, w)
+        g_ids, g_d = gix.search(q, k, w, m)
+        np.testing.assert_array_equal(g_ids, o_ids, err_msg=what)
+        np.testing.assert_array_equal(g_d, o_d, err_msg=what)
+    else:
+        o_ids, o_d, ost = O.search(oix, q, k, w, m, stages=True)
+        g_ids, g_d, gst = gix.search_stages(q, k, w, m)
+        for key in ("q8", "dx", "sel", "z", "sigma"):
+            np.testing.assert_array_equal(gst[key], ost[key], err_msg=f"{key}: {what}")
+        np.testing.assert_array_equal(np.sort(gst["cand_rows"].astype(np.int64), axis=1), np.sort(ost["cand_rows"], axis=1), err_msg=what)
+        # k can reach most of the scored points here, so the results include inner products that cancel to almost
+        # nothing: their float rounding is measured against 5 % of |q| |x|, not against their own size
+        floor = 0.05 * float(np.linalg.norm(q, axis=1).max() * np.linalg.norm(ix["corpus"], axis=1).max()) if metric == 0 else 0.05
+        assert_topk_equal(g_ids, g_d, o_ids, o_d, what, floor=max(floor, 1e-3))
+    gix.close()
