@@ -155,6 +155,42 @@ inline int gemm_pick_bm(long M, long N) {
     return e32 > e64 + 0.05 ? 32 : 64;
 }
 
+// The projection of a small batch (M <= kSmallBatch): out[m][n] = sum_k X[m][k] * W[n][k], double accumulation, one
+// rounding to float, optional bfloat16 copy.  A matrix-core tile is mostly padding at this size and its K loop a
+// chain of dependent steps; here one wavefront owns one output column n for kSmallM queries, its lanes stride over k
+// (W row and X rows are read coalesced) and the sums meet in a wavefront reduction.
+// grid = (ceil(N / 4), ceil(M / kSmallM)), block = 256.
+constexpr int kSmallM = 16, kSmallBatch = 128;
+__global__ __launch_bounds__(256) void k_project_small(const float* __restrict__ X, const float* __restrict__ W, float* __restrict__ out,
+                                                       int M, int N, int K, __bf16* __restrict__ out_bf) {
+    const int lane = threadIdx.x & 63;
+    const int n = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (n >= N) return;                              // wavefronts are independent
+    const int m0 = blockIdx.y * kSmallM;
+    X += (size_t)m0 * K; out += (size_t)m0 * N; if (out_bf) out_bf += (size_t)m0 * N;
+    M = min(M - m0, kSmallM);
+    double acc[kSmallM];
+#pragma unroll
+    for (int m = 0; m < kSmallM; ++m) acc[m] = 0.0;
+    for (int k = lane; k < K; k += 64) {
+        const double wv = (double)W[(size_t)n * K + k];
+#pragma unroll
+        for (int m = 0; m < kSmallM; ++m) {
+            const float x = X[(size_t)min(m, M - 1) * K + k];      // rows beyond M repeat the last one (never stored)
+            acc[m] += (double)x * wv;
+        }
+    }
+#pragma unroll
+    for (int m = 0; m < kSmallM; ++m) {
+        const double s = wave_sum_f64(acc[m]);
+        if (lane == 0 && m < M) {
+            const float o = (float)s;
+            out[(size_t)m * N + n] = o;
+            if (out_bf) out_bf[(size_t)m * N + n] = (__bf16)o;
+        }
+    }
+}
+
 // out[row] = sum_i x[row][i]^2 accumulated in double; one wavefront per row.  OUT = float or double.
 template <typename OUT>
 __global__ __launch_bounds__(256) void k_row_sqnorm(const float* __restrict__ x, OUT* __restrict__ out, int64_t rows, int d) {

@@ -846,3 +846,20 @@ def test_randomized_configurations(B, seed):
         floor = 0.05 * float(np.linalg.norm(q, axis=1).max() * np.linalg.norm(ix["corpus"], axis=1).max()) if metric == 0 else 0.05
         assert_topk_equal(g_ids, g_d, o_ids, o_d, what, floor=max(floor, 1e-3))
     gix.close()
+
+
+@pytest.mark.parametrize("nq", [1, 2, 15, 16, 17, 40])
+def test_small_batches_take_the_small_projection(B, small_indexes, nq):
+    """Small batches are projected by the one-wavefront-per-output-column kernel, 16 queries per wavefront (the
+    workload has 40 queries; larger batches, on the matrix cores, are what every other test runs): projected queries,
+    codes and everything after them bit-exact."""
+    wl, ix, corpus, queries = small_indexes["cos_P"]
+    a = ix.numpy()
+    q = queries[:nq]
+    o_ids, o_d, ost = O.search(O.OracleIndex(a), q, wl.k, wl.w, wl.m, stages=True)
+    gix = B.Index.from_arrays(ix.to("cuda"))
+    g_ids, g_d, gst = gix.search_stages(q, wl.k, wl.w, wl.m)
+    for key in ("qproj", "q8", "dx", "sel", "z", "sigma"):
+        np.testing.assert_array_equal(gst[key], ost[key], err_msg=key)
+    assert_topk_equal(g_ids, g_d, o_ids, o_d, f"nq={nq}")
+    gix.close()
