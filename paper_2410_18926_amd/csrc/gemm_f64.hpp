@@ -160,7 +160,7 @@ inline int gemm_pick_bm(long M, long N) {
 // chain of dependent steps; here one wavefront owns one output column n for kSmallM queries, its lanes stride over k
 // (W row and X rows are read coalesced) and the sums meet in a wavefront reduction.
 // grid = (ceil(N / 4), ceil(M / kSmallM)), block = 256.
-constexpr int kSmallM = 16, kSmallBatch = 128;
+constexpr int kSmallM = 16, kSmallBatch = 512;
 __global__ __launch_bounds__(256) void k_project_small(const float* __restrict__ X, const float* __restrict__ W, float* __restrict__ out,
                                                        int M, int N, int K, __bf16* __restrict__ out_bf) {
     const int lane = threadIdx.x & 63;

@@ -850,9 +850,8 @@ def test_randomized_configurations(B, seed):
 
 @pytest.mark.parametrize("nq", [1, 2, 15, 16, 17, 40])
 def test_small_batches_take_the_small_projection(B, small_indexes, nq):
-    """Small batches are projected by the one-wavefront-per-output-column kernel, 16 queries per wavefront (the
-    workload has 40 queries; larger batches, on the matrix cores, are what every other test runs): projected queries,
-    codes and everything after them bit-exact."""
+    """Batches of up to 512 queries are projected by the one-wavefront-per-output-column kernel, 16 queries per
+    wavefront (the workload has 40 queries): projected queries, codes and everything after them bit-exact."""
     wl, ix, corpus, queries = small_indexes["cos_P"]
     a = ix.numpy()
     q = queries[:nq]
@@ -862,4 +861,21 @@ def test_small_batches_take_the_small_projection(B, small_indexes, nq):
     for key in ("qproj", "q8", "dx", "sel", "z", "sigma"):
         np.testing.assert_array_equal(gst[key], ost[key], err_msg=key)
     assert_topk_equal(g_ids, g_d, o_ids, o_d, f"nq={nq}")
+    gix.close()
+
+
+@pytest.mark.parametrize("nq,d,dp", [(513, 48, 32), (700, 50, 32), (2000, 200, 64), (1500, 333, 256)])
+def test_batches_beyond_the_small_projection_use_the_matrix_cores(B, nq, d, dp):
+    """More than 512 queries are projected on the fp64 matrix cores (rows that are and are not a multiple of four
+    floats, both tile heights): projected queries, codes, step sizes and selected clusters bit-exact."""
+    rng = np.random.default_rng(nq + d)
+    ix = _random_index(rng, n=900, d=d, L=20, r=8, metric=int(nq % 3), dp=dp)
+    q = rng.normal(size=(nq, d)).astype(np.float32)
+    gix = B.Index(**ix)
+    o_ids, o_d, ost = O.search(O.OracleIndex(ix), q, 5, 4, 30, stages=True)
+    g_ids, g_d, gst = gix.search_stages(q, 5, 4, 30)
+    for key in ("qproj", "q8", "dx", "sel", "z", "sigma"):
+        np.testing.assert_array_equal(gst[key], ost[key], err_msg=key)
+    floor = 0.05 * float(np.linalg.norm(q, axis=1).max() * np.linalg.norm(ix["corpus"], axis=1).max()) if ix["metric"] == 0 else 0.05
+    assert_topk_equal(g_ids, g_d, o_ids, o_d, f"nq={nq}", floor=max(floor, 1e-3))
     gix.close()
