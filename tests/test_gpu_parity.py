@@ -86,7 +86,7 @@ def test_small_workloads_host_pointers(B, small_indexes):
 
 
 def test_tiny_config_stagewise(B):
-    """BASELINE config 1 (20 000 x 128, 64 clusters, r = 32, w = 8, m = 100, Euclidean), all 1000 queries."""
+    """The smallest configured workload (20 000 x 128, 64 clusters, r = 32, w = 8, m = 100, Euclidean), all 1000 queries."""
     from paper_2410_18926_amd.synth import get_workload, make_dataset, build_index
     wl = get_workload("tiny")
     corpus, queries = make_dataset(wl)
