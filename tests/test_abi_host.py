@@ -96,3 +96,15 @@ def test_header_constants_match_binding(B):
     assert int(re.search(r"#define LORANN_LANES (\d+)", header).group(1)) == B.LANES
     for name, val in (("LORANN_RERANK_F32", B.RERANK_F32), ("LORANN_RERANK_F16", B.RERANK_F16), ("LORANN_RERANK_NONE", B.RERANK_NONE)):
         assert re.search(rf"{name}\s*=\s*{val}\b", header), name
+
+
+def test_bench_refuses_more_than_one_gpu_and_a_missing_gpu():
+    """bench.py measures one GPU: --gpus 2 exits with a message before anything is imported; without a GPU it says
+    that no CPU fallback exists (this test runs where there is none)."""
+    import subprocess, sys
+    r = subprocess.run([sys.executable, str(ROOT / "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 2 and "one GPU" in r.stderr and r.stdout.strip() == ""
+    import torch
+    if not torch.cuda.is_available():
+        r = subprocess.run([sys.executable, str(ROOT / "bench.py")], capture_output=True, text=True, timeout=300)
+        assert r.returncode == 2 and "needs the GPU" in r.stderr and r.stdout.strip() == ""
