@@ -372,7 +372,9 @@ int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ
         Prof p(ix, K_STAGE_A, s);
         // about five tiles of 16 pairs per wavefront on average; skewed clusters just loop longer
         const int64_t avg_tiles = npairs / 16 / L + 1;
-        const dim3 grid((unsigned)L, (unsigned)std::max<int64_t>(1, std::min<int64_t>(32, (avg_tiles + 19) / 20)));
+        // ... and with few clusters at least ~1024 blocks, so that a cluster that attracts many pairs is shared out
+        const int64_t by_load = (avg_tiles + 19) / 20, by_count = (1024 + L - 1) / L;
+        const dim3 grid((unsigned)L, (unsigned)std::max<int64_t>(1, std::min<int64_t>(32, std::max(by_load, by_count))));
 #define LAUNCH_SA(RT_, RES_)                                                                                   \
     do {                                                                                                       \
         if (ix->sA_cols) hipLaunchKernelGGL((k_stage_a<RT_, RES_, true>), grid, dim3(256), 0, s, ws.q8.as<int8_t>(), ws.dx.as<float>(), ix->A, ix->sA_cols, ix->sB, \
