@@ -124,6 +124,38 @@ __global__ __launch_bounds__(64 * WPB) void k_pair_max(ScoreArgs a) {
             }
         };
         auto score_chunk = [&](int c0, i32x4 (*breg)[KS], const float* nb, const float* ns) {
+            if constexpr (!FLT) {
+                // integer maxima: two tiles at a time, so that one three-operand maximum per result register takes
+                // in both tiles (the epilogue is bound by the vector ALU: one instruction per score otherwise)
+                static_assert(TB % 2 == 0, "tiles are taken in pairs");
+#pragma unroll
+                for (int u = 0; u < TB; u += 2) {
+                    const int t = c0 * TB + u;
+                    if (t < ntiles) {                        // uniform
+                        const bool has2 = t + 1 < ntiles;                              // uniform
+                        const bool full = has2 && 32 * t + 64 <= m_c;                  // uniform: both tiles complete
+                        const bool ok_a = 32 * t + j < m_c, ok_b = has2 && 32 * (t + 1) + j < m_c;
+#pragma unroll
+                        for (int z = 0; z < NZ; ++z) {
+                            i32x16 acc_a = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}, acc_b = acc_a;
+#pragma unroll
+                            for (int ks = 0; ks < KS; ++ks) {
+                                acc_a = __builtin_amdgcn_mfma_i32_32x32x32_i8(zreg[z][ks], breg[u][ks], acc_a, 0, 0, 0);
+                                acc_b = __builtin_amdgcn_mfma_i32_32x32x32_i8(zreg[z][ks], breg[u + 1][ks], acc_b, 0, 0, 0);
+                            }
+                            if (full) {
+#pragma unroll
+                                for (int v = 0; v < 16; ++v) mxi[z][v] = max(max(mxi[z][v], acc_a[v]), acc_b[v]);
+                            } else {
+#pragma unroll
+                                for (int v = 0; v < 16; ++v) mxi[z][v] = max(max(mxi[z][v], ok_a ? acc_a[v] : IMIN), ok_b ? acc_b[v] : IMIN);
+                            }
+                        }
+                    }
+                    __builtin_amdgcn_sched_barrier(0);       // keep the tile pairs sequential: bounds live accumulators
+                }
+                return;
+            }
 #pragma unroll
             for (int u = 0; u < TB; ++u) {
                 const int t = c0 * TB + u;
