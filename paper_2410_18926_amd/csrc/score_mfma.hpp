@@ -124,25 +124,26 @@ __global__ __launch_bounds__(64 * WPB) void k_pair_max(ScoreArgs a) {
             }
         };
         auto score_chunk = [&](int c0, i32x4 (*breg)[KS], const float* nb, const float* ns) {
-            if constexpr (!FLT) {
-                // integer maxima: two tiles at a time, so that one three-operand maximum per result register takes
-                // in both tiles (the epilogue is bound by the vector ALU: one instruction per score otherwise)
-                static_assert(TB % 2 == 0, "tiles are taken in pairs");
+            // Two tiles at a time, so that ONE three-operand maximum per result register takes in both tiles (the
+            // epilogue is bound by the vector ALU: integer maxima cost one instruction per score otherwise).
+            static_assert(TB % 2 == 0, "tiles are taken in pairs");
 #pragma unroll
-                for (int u = 0; u < TB; u += 2) {
-                    const int t = c0 * TB + u;
-                    if (t < ntiles) {                        // uniform
-                        const bool has2 = t + 1 < ntiles;                              // uniform
-                        const bool full = has2 && 32 * t + 64 <= m_c;                  // uniform: both tiles complete
-                        const bool ok_a = 32 * t + j < m_c, ok_b = has2 && 32 * (t + 1) + j < m_c;
+            for (int u = 0; u < TB; u += 2) {
+                const int t = c0 * TB + u;
+                if (t < ntiles) {                        // uniform
+                    const bool has2 = t + 1 < ntiles;                              // uniform
+                    const bool full = has2 && 32 * t + 64 <= m_c;                  // uniform: both tiles complete
+                    const bool ok_a = 32 * t + j < m_c, ok_b = has2 && 32 * (t + 1) + j < m_c;
+                    const float bias_a = L2 ? nb[u] : 0.0f, bias_b = L2 ? nb[u + 1] : 0.0f;
 #pragma unroll
-                        for (int z = 0; z < NZ; ++z) {
-                            i32x16 acc_a = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}, acc_b = acc_a;
+                    for (int z = 0; z < NZ; ++z) {
+                        i32x16 acc_a = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}, acc_b = acc_a;
 #pragma unroll
-                            for (int ks = 0; ks < KS; ++ks) {
-                                acc_a = __builtin_amdgcn_mfma_i32_32x32x32_i8(zreg[z][ks], breg[u][ks], acc_a, 0, 0, 0);
-                                acc_b = __builtin_amdgcn_mfma_i32_32x32x32_i8(zreg[z][ks], breg[u + 1][ks], acc_b, 0, 0, 0);
-                            }
+                        for (int ks = 0; ks < KS; ++ks) {
+                            acc_a = __builtin_amdgcn_mfma_i32_32x32x32_i8(zreg[z][ks], breg[u][ks], acc_a, 0, 0, 0);
+                            acc_b = __builtin_amdgcn_mfma_i32_32x32x32_i8(zreg[z][ks], breg[u + 1][ks], acc_b, 0, 0, 0);
+                        }
+                        if (!FLT) {
                             if (full) {
 #pragma unroll
                                 for (int v = 0; v < 16; ++v) mxi[z][v] = max(max(mxi[z][v], acc_a[v]), acc_b[v]);
@@ -150,43 +151,19 @@ __global__ __launch_bounds__(64 * WPB) void k_pair_max(ScoreArgs a) {
 #pragma unroll
                                 for (int v = 0; v < 16; ++v) mxi[z][v] = max(max(mxi[z][v], ok_a ? acc_a[v] : IMIN), ok_b ? acc_b[v] : IMIN);
                             }
-                        }
-                    }
-                    __builtin_amdgcn_sched_barrier(0);       // keep the tile pairs sequential: bounds live accumulators
-                }
-                return;
-            }
-#pragma unroll
-            for (int u = 0; u < TB; ++u) {
-                const int t = c0 * TB + u;
-                if (t < ntiles) {                        // uniform
-                    const int pt = 32 * t + j;           // this lane's point of the tile
-                    const bool pt_ok = pt < m_c;         // false only in the last tile of the cluster
-                    const float bias = L2 ? nb[u] : 0.0f;
-#pragma unroll
-                    for (int z = 0; z < NZ; ++z) {
-                        i32x16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll
-                        for (int ks = 0; ks < KS; ++ks) acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(zreg[z][ks], breg[u][ks], acc, 0, 0, 0);
-                        if (!FLT) {
-                            if (32 * t + 32 <= m_c) {    // uniform: full tile
-#pragma unroll
-                                for (int v = 0; v < 16; ++v) mxi[z][v] = max(mxi[z][v], acc[v]);
-                            } else {
-#pragma unroll
-                                for (int v = 0; v < 16; ++v) mxi[z][v] = max(mxi[z][v], pt_ok ? acc[v] : IMIN);
-                            }
                         } else {
 #pragma unroll
                             for (int v = 0; v < 16; ++v) {
-                                const float mult = COLS ? __fmul_rn(sgv[z][v], ns[u]) : sgv[z][v];
-                                const float sc = __fmaf_rn((float)acc[v], mult, -bias);
-                                mxf[z][v] = fmaxf(mxf[z][v], pt_ok ? sc : -INFINITY);
+                                const float mult_a = COLS ? __fmul_rn(sgv[z][v], ns[u]) : sgv[z][v];
+                                const float mult_b = COLS ? __fmul_rn(sgv[z][v], ns[u + 1]) : sgv[z][v];
+                                const float sc_a = __fmaf_rn((float)acc_a[v], mult_a, -bias_a);
+                                const float sc_b = __fmaf_rn((float)acc_b[v], mult_b, -bias_b);
+                                mxf[z][v] = fmaxf(fmaxf(mxf[z][v], ok_a ? sc_a : -INFINITY), ok_b ? sc_b : -INFINITY);
                             }
                         }
                     }
                 }
-                __builtin_amdgcn_sched_barrier(0);       // keep the tiles sequential: bounds live accumulators
+                __builtin_amdgcn_sched_barrier(0);       // keep the tile pairs sequential: bounds live accumulators
             }
         };
         {
