@@ -49,6 +49,11 @@ typedef struct {
      * cluster (scale_A, scale_B above).  Both set: scale_A / scale_B are ignored. */
     const float *col_scale_A;      /* [L][r]  step size of column j of A_c */
     const float *pt_scale_B;       /* [n]     step size of the column of B_c that belongs to a corpus row */
+    /* Sec. 4.2 mixed-precision decomposition: the first component of the projected query and the first row of
+     * every A_c and B_c are not quantized.  Both NULL: everything is quantized.  Both set (needs the column-wise
+     * step sizes above): the codes' first components (A[c][j][0], B[t][0]) are not read. */
+    const float *first_row_A;      /* [L][r]  A_c[0][j] in float */
+    const float *first_row_B;      /* [n]     B_c[0][t] in float, for the column that belongs to a corpus row */
 } oracle_index;
 
 /* Optional per-stage outputs of oracle_search; any pointer may be NULL. */
@@ -63,6 +68,7 @@ typedef struct {
     float *sigma;        /* [nq][w]       combined scale of each pair           */
     int64_t *cand_rows;  /* [nq][m]       candidate rows (score desc, row asc), -1 padded */
     float *cand_scores;  /* [nq][m]       their estimated scores (0 where padded) */
+    float *rho0;         /* [nq][w]       mixed precision: unquantized first component of each pair's r */
 } oracle_dump;
 
 /* ---- Step 1 (Sec. 4.1): q' = P^T q, double accumulation over i ascending, one rounding to float. ---- */
@@ -186,6 +192,46 @@ float oracle_score_columns(int32_t Y, float sigma, float dB_t, int32_t metric, f
     return fmaf((float)Y, mult, -0.0f);
 }
 
+/* ---- Mixed-precision decomposition (Sec. 4.2): x = (x_0, x_rest), r = (r_0, r_rest). ----
+ * Only x_rest and r_rest are quantized (absmax over the rest alone, code 0 in the first position, so that the
+ * integer products skip it whatever the matrices hold there); x_0 meets the float first row of A_c, r_0 the float
+ * first row of B_c.  Every operation is one IEEE float operation (fmaf = one rounding) in the order written. */
+void oracle_quantize_query_mixed(const float *qp, int32_t dp, int8_t *q8, float *dx)
+{
+    q8[0] = 0;
+    oracle_quantize_query(qp + 1, dp - 1, q8 + 1, dx);
+}
+
+/* r_j ~= rho_j = x_0 A_c[0][j] + R_j (Delta_x DeltaA_cj) with R_j over the quantized rest; rho_0 stays a float,
+ * (rho_1..) is re-quantized like a query. */
+void oracle_stage_a_mixed(const int8_t *q8, float x0, int32_t dp, int32_t r, const int8_t *A_c /* [r][dp] */, float dx,
+                          const float *dA /* [r] */, const float *A0 /* [r] first row of A_c */, int32_t *R, int8_t *z,
+                          float *sigma, float *rho0)
+{
+    float *rho = (float *)malloc(sizeof(float) * (size_t)r);
+    for (int32_t j = 0; j < r; ++j) {
+        int32_t acc = 0;
+        const int8_t *col = A_c + (size_t)j * dp;
+        for (int32_t i = 1; i < dp; ++i) acc += (int32_t)q8[i] * (int32_t)col[i];
+        R[j] = acc;
+        volatile float sj = dx * dA[j];
+        volatile float quantized_part = (float)acc * sj;
+        rho[j] = fmaf(x0, A0[j], quantized_part);
+    }
+    *rho0 = rho[0];
+    z[0] = 0;
+    if (r > 1) oracle_quantize_query(rho + 1, r - 1, z + 1, sigma); else *sigma = 0.0f;
+    free(rho);
+}
+
+/* Estimated score: the float rank-one term r_0 B_c[0][t] on top of the quantized rest (as oracle_score_columns);
+ * for Euclidean both parts carry the factor 2 of Sec. 3.1 (doubling is exact). */
+float oracle_score_mixed(int32_t Y, float sigma, float dB_t, float rho0, float B0_t, int32_t metric, float sqnorm)
+{
+    const float rest = oracle_score_columns(Y, sigma, dB_t, metric, sqnorm);
+    return fmaf(metric == ORACLE_L2 ? 2.0f * rho0 : rho0, B0_t, rest);
+}
+
 /* ---- Step 5 (Sec. 3.2 prediction y = (x^T A) B in its 8-bit form, Sec. 3.1 Euclidean reduction). ---- */
 /* int32 accumulators of one pair: Y_j = sum_t z_t B[row_j][t]. */
 void oracle_pair_accumulators(const int8_t *z, int32_t r, const int8_t *B_c /* [m_c][r] */, int64_t m_c, int32_t *Y)
@@ -251,12 +297,15 @@ static void search_one(const oracle_index *ix, const float *q, int32_t k, int32_
     int8_t *q8 = (int8_t *)malloc((size_t)dp);
     int32_t *R = (int32_t *)malloc(sizeof(int32_t) * (size_t)r);
     int8_t *z = (int8_t *)malloc((size_t)r);
-    float dx, sigma;
+    float dx, sigma, rho0 = 0.0f;
+    const int columns = ix->col_scale_A && ix->pt_scale_B;
+    const int mixed = columns && ix->first_row_A && ix->first_row_B;
 
     oracle_project(q, d, dp, ix->P, qp);                                   /* step 1 */
     oracle_centroid_dissim(qp, dp, ix->centroids, L, ix->metric, g);       /* step 2 */
     oracle_select_clusters(g, L, w, sel, sel_g);
-    oracle_quantize_query(qp, dp, q8, &dx);                                /* step 3 */
+    if (mixed) oracle_quantize_query_mixed(qp, dp, q8, &dx);               /* step 3 */
+    else oracle_quantize_query(qp, dp, q8, &dx);
 
     int64_t total = 0, max_mc = 0;
     for (int32_t j = 0; j < w; ++j) {
@@ -270,20 +319,23 @@ static void search_one(const oracle_index *ix, const float *q, int32_t k, int32_
     for (int32_t j = 0; j < w; ++j) {                                      /* steps 4-5 per selected cluster */
         const int32_t c = sel[j];
         const int64_t off = ix->offsets[c], mc = ix->offsets[c + 1] - off;
-        const int columns = ix->col_scale_A && ix->pt_scale_B;
-        if (columns) oracle_stage_a_columns(q8, dp, r, ix->A + (size_t)c * r * dp, dx, ix->col_scale_A + (size_t)c * r, R, z, &sigma);
+        if (mixed) oracle_stage_a_mixed(q8, qp[0], dp, r, ix->A + (size_t)c * r * dp, dx, ix->col_scale_A + (size_t)c * r,
+                                        ix->first_row_A + (size_t)c * r, R, z, &sigma, &rho0);
+        else if (columns) oracle_stage_a_columns(q8, dp, r, ix->A + (size_t)c * r * dp, dx, ix->col_scale_A + (size_t)c * r, R, z, &sigma);
         else oracle_stage_a(q8, dp, r, ix->A + (size_t)c * r * dp, dx, ix->scale_A[c], ix->scale_B[c], R, z, &sigma);
         if (dump) {
             if (dump->R) memcpy(dump->R + ((size_t)qi * w + j) * r, R, sizeof(int32_t) * (size_t)r);
             if (dump->z) memcpy(dump->z + ((size_t)qi * w + j) * r, z, (size_t)r);
             if (dump->sigma) dump->sigma[(size_t)qi * w + j] = sigma;
+            if (dump->rho0) dump->rho0[(size_t)qi * w + j] = rho0;
         }
         oracle_pair_accumulators(z, r, ix->B + (size_t)off * r, mc, Y);
         for (int64_t t = 0; t < mc; ++t) {
             float sq = 0.0f;   /* Sec. 3.1: the norms |c_j|^2 "can be precomputed" */
             if (ix->metric == ORACLE_L2)
                 sq = ix->sqnorms ? ix->sqnorms[off + t] : oracle_row_sqnorm(ix->corpus + (size_t)(off + t) * d, d);
-            sc[pos].key = columns ? oracle_score_columns(Y[t], sigma, ix->pt_scale_B[off + t], ix->metric, sq)
+            sc[pos].key = mixed ? oracle_score_mixed(Y[t], sigma, ix->pt_scale_B[off + t], rho0, ix->first_row_B[off + t], ix->metric, sq)
+                        : columns ? oracle_score_columns(Y[t], sigma, ix->pt_scale_B[off + t], ix->metric, sq)
                                   : oracle_score(Y[t], sigma, ix->metric, sq);
             sc[pos].idx = off + t;
             ++pos;

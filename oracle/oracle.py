@@ -21,12 +21,13 @@ class _Index(C.Structure):
                 ("L", C.c_int32), ("centroids", C.c_void_p), ("P", C.c_void_p), ("A", C.c_void_p),
                 ("B", C.c_void_p), ("scale_A", C.c_void_p), ("scale_B", C.c_void_p), ("offsets", C.c_void_p),
                 ("corpus", C.c_void_p), ("ids", C.c_void_p), ("sqnorms", C.c_void_p),
-                ("col_scale_A", C.c_void_p), ("pt_scale_B", C.c_void_p)]
+                ("col_scale_A", C.c_void_p), ("pt_scale_B", C.c_void_p),
+                ("first_row_A", C.c_void_p), ("first_row_B", C.c_void_p)]
 
 
 class _Dump(C.Structure):
     _fields_ = [(name, C.c_void_p) for name in
-                ("qproj", "q8", "dx", "sel", "sel_g", "R", "z", "sigma", "cand_rows", "cand_scores")]
+                ("qproj", "q8", "dx", "sel", "sel_g", "R", "z", "sigma", "cand_rows", "cand_scores", "rho0")]
 
 
 def lib():
@@ -43,6 +44,8 @@ def lib():
         _lib.oracle_exact_dissim.restype = C.c_float
         _lib.oracle_score_columns.restype = C.c_float
         _lib.oracle_score_columns.argtypes = [C.c_int32, C.c_float, C.c_float, C.c_int32, C.c_float]
+        _lib.oracle_score_mixed.restype = C.c_float
+        _lib.oracle_score_mixed.argtypes = [C.c_int32, C.c_float, C.c_float, C.c_float, C.c_float, C.c_int32, C.c_float]
         _lib.oracle_load_file.restype = C.POINTER(_Index)
         _lib.oracle_load_file.argtypes = [C.c_char_p]
         _lib.oracle_free_loaded.restype = None
@@ -89,10 +92,18 @@ class OracleIndex:
         assert (self.scale_A_columns is None) == (self.scale_B_points is None)
         if self.scale_A_columns is not None:
             assert self.scale_A_columns.shape == (self.L, self.r) and self.scale_B_points.shape == (self.n,)
+        # optional (with the column step sizes): unquantized first rows of A_c and B_c (Sec. 4.2 mixed precision)
+        self.first_row_A = _c(ix.get("first_row_A"), np.float32)
+        self.first_row_B = _c(ix.get("first_row_B"), np.float32)
+        assert (self.first_row_A is None) == (self.first_row_B is None)
+        if self.first_row_A is not None:
+            assert self.scale_A_columns is not None
+            assert self.first_row_A.shape == (self.L, self.r) and self.first_row_B.shape == (self.n,)
         self.c = _Index(self.metric, self.n, self.d, self.dp, self.r, self.L, _p(self.centroids), _p(self.P),
                         _p(self.A), _p(self.B), _p(self.scale_A), _p(self.scale_B), _p(self.offsets),
                         _p(self.corpus if self.rerank_corpus is None else self.rerank_corpus), _p(self.ids),
-                        _p(self.sqnorms), _p(self.scale_A_columns), _p(self.scale_B_points))
+                        _p(self.sqnorms), _p(self.scale_A_columns), _p(self.scale_B_points), _p(self.first_row_A),
+                        _p(self.first_row_B))
 
 
 def _from_file(path) -> "OracleIndex":
@@ -153,7 +164,7 @@ def search(oix: OracleIndex, Q, k: int, w: int, m: int, stages: bool = False, th
                   dx=np.zeros(nq, np.float32), sel=np.zeros((nq, w), np.int32), sel_g=np.zeros((nq, w), np.float32),
                   R=np.zeros((nq, w, oix.r), np.int32), z=np.zeros((nq, w, oix.r), np.int8),
                   sigma=np.zeros((nq, w), np.float32), cand_rows=np.zeros((nq, m), np.int64),
-                  cand_scores=np.zeros((nq, m), np.float32))
+                  cand_scores=np.zeros((nq, m), np.float32), rho0=np.zeros((nq, w), np.float32))
         dump = _Dump(*[_p(st[f[0]]) for f in _Dump._fields_])
     rc = lib().oracle_search(C.byref(oix.c), _p(Q), C.c_int64(nq), C.c_int32(k), C.c_int32(w), C.c_int32(m),
                              _p(ids), _p(dists), C.byref(dump) if dump is not None else None,
@@ -257,6 +268,33 @@ def stage_a_columns(q8, A_c, dx, dA_cols):
     lib().oracle_stage_a_columns(_p(q8), C.c_int32(dp), C.c_int32(r), _p(A_c), C.c_float(dx), _p(dA_cols), _p(R), _p(z),
                                  C.byref(sg))
     return R, z, np.float32(sg.value)
+
+
+def quantize_query_mixed(qp):
+    """Sec. 4.2: the first component stays out of the quantization (code 0 there)."""
+    qp = _c(qp, np.float32)
+    q8 = np.empty(qp.shape[0], np.int8)
+    dx = C.c_float(0)
+    lib().oracle_quantize_query_mixed(_p(qp), C.c_int32(qp.shape[0]), _p(q8), C.byref(dx))
+    return q8, np.float32(dx.value)
+
+
+def stage_a_mixed(q8, x0, A_c, dx, dA_cols, A0):
+    """Step 4 with the unquantized first component.  Returns (R int32 [r], z int8 [r], sigma f32, rho0 f32)."""
+    q8, A_c, dA_cols, A0 = _c(q8, np.int8), _c(A_c, np.int8), _c(dA_cols, np.float32), _c(A0, np.float32)
+    r, dp = A_c.shape
+    assert dA_cols.shape == (r,) and A0.shape == (r,)
+    R = np.empty(r, np.int32)
+    z = np.empty(r, np.int8)
+    sg, r0 = C.c_float(0), C.c_float(0)
+    lib().oracle_stage_a_mixed(_p(q8), C.c_float(x0), C.c_int32(dp), C.c_int32(r), _p(A_c), C.c_float(dx), _p(dA_cols),
+                               _p(A0), _p(R), _p(z), C.byref(sg), C.byref(r0))
+    return R, z, np.float32(sg.value), np.float32(r0.value)
+
+
+def score_mixed(Y: int, sigma: float, dB_t: float, rho0: float, B0_t: float, metric: int, sqnorm: float = 0.0) -> np.float32:
+    return np.float32(lib().oracle_score_mixed(int(Y), float(sigma), float(dB_t), float(rho0), float(B0_t), int(metric),
+                                               float(sqnorm)))
 
 
 def score_columns(Y: int, sigma: float, dB_t: float, metric: int, sqnorm: float = 0.0) -> np.float32:

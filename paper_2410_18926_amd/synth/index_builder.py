@@ -44,6 +44,8 @@ class IndexArrays:
     ids: torch.Tensor              # [n] int64: original index of each row
     scale_A_columns: torch.Tensor | None = None   # [L, r] f32: one step size per column of A_c (Sec. 3.3 as printed);
     scale_B_points: torch.Tensor | None = None    # [n] f32: one per column of B_c, i.e. per corpus row; both or neither
+    first_row_A: torch.Tensor | None = None       # [L, r] f32: A_c[0][j] unquantized (Sec. 4.2 mixed precision); with
+    first_row_B: torch.Tensor | None = None       # [n] f32: B_c[0][t] unquantized; both or neither, need the column scales
     A_f32: torch.Tensor | None = None   # [L, r, dp] unquantized factors (kept on request, for tests)
     B_f32: torch.Tensor | None = None   # [n, r]
 
@@ -146,14 +148,19 @@ def _absmax_int8_rows(x: torch.Tensor):
 
 def build_index(corpus: torch.Tensor, wl: Workload, *, exact_svd: bool = False, rotate: bool = True,
                 keep_float: bool = False, fit_dtype: torch.dtype = torch.float64,
-                train: torch.Tensor | None = None, progress=None, column_scales: bool = False) -> IndexArrays:
+                train: torch.Tensor | None = None, progress=None, column_scales: bool = False,
+                mixed_precision: bool = False) -> IndexArrays:
     """Build the index arrays for `corpus` [n, d] under workload `wl` on corpus.device.
 
     `train` overrides the RRR training set (default: a seeded sample of min(n, wl.n_train) corpus rows).
     `column_scales`: quantize every column of A_c and of B_c with its own step size (Sec. 3.3 as printed) instead
     of one step size per cluster and matrix; the codes differ, and scale_A / scale_B then only hold the largest of
     the column step sizes (the search ignores them once the column scales are set).
+    `mixed_precision` (Sec. 4.2; implies column_scales): the first row of every A_c and B_c is kept in float
+    (first_row_A, first_row_B), its codes are zero and the step sizes come from the other rows alone; the random
+    rotations then leave the first component (the principal axis, the leading singular direction) in place.
     """
+    column_scales = column_scales or mixed_precision
     dev = corpus.device
     n, d = corpus.shape
     dp, r, L, metric = wl.dp, wl.r, wl.L, wl.metric
@@ -175,7 +182,9 @@ def build_index(corpus: torch.Tensor, wl: Workload, *, exact_svd: bool = False, 
             gram += t.T @ t
         evals, evecs = torch.linalg.eigh(gram.cpu())
         W = evecs[:, torch.argsort(evals, descending=True)[:dp]]          # [d, dp] fp64
-        if rotate:
+        if rotate and mixed_precision:
+            W = torch.cat([W[:, :1], W[:, 1:] @ _random_rotation(dp - 1, base + 12, "cpu")], 1)
+        elif rotate:
             W = W @ _random_rotation(dp, base + 12, "cpu")
         P = W.to(torch.float32).to(dev).contiguous()
     say("projection done")
@@ -214,6 +223,8 @@ def build_index(corpus: torch.Tensor, wl: Workload, *, exact_svd: bool = False, 
     sB = torch.zeros(L, dtype=torch.float32)
     sA_cols = torch.zeros(L, r, dtype=torch.float32, device=dev) if column_scales else None
     sB_pts = torch.zeros(n, dtype=torch.float32, device=dev) if column_scales else None
+    A_first = torch.zeros(L, r, dtype=torch.float32, device=dev) if mixed_precision else None
+    B_first = torch.zeros(n, dtype=torch.float32, device=dev) if mixed_precision else None
     A_f = torch.zeros(L, r, dp, dtype=torch.float32, device=dev) if keep_float else None
     B_f = torch.zeros(n, r, dtype=torch.float32, device=dev) if keep_float else None
     Pd = None if P is None else P.to(fit_dtype)
@@ -231,7 +242,9 @@ def build_index(corpus: torch.Tensor, wl: Workload, *, exact_svd: bool = False, 
         Y = X @ C.T                                                        # [n_l, m_l]
         V = _top_right_singular(Y, r, exact_svd, base + 100 + l)           # [m_l, r']
         rr = V.shape[1]
-        if rotate and rr > 1:
+        if rotate and mixed_precision and rr > 2:
+            V = torch.cat([V[:, :1], V[:, 1:] @ _random_rotation(rr - 1, base + 14, dev).to(fit_dtype)], 1)
+        elif rotate and rr > 1 and not mixed_precision:
             V = V @ _random_rotation(rr, base + 14, dev).to(fit_dtype)
         YV = Y @ V                                                         # [n_l, r']
         # A = Xt^+ (Y V): least squares through the normal equations with a tiny ridge for rank safety
@@ -243,7 +256,12 @@ def build_index(corpus: torch.Tensor, wl: Workload, *, exact_svd: bool = False, 
         Bf = torch.zeros(m_l, r, dtype=torch.float32, device=dev)
         Af[:rr] = A.T.to(torch.float32)
         Bf[:, :rr] = V.to(torch.float32)
-        if column_scales:
+        if mixed_precision:
+            A_first[l], B_first[c0:c1] = Af[:, 0], Bf[:, 0]
+            A_q[l, :, 1:], sA_cols[l] = _absmax_int8_rows(Af[:, 1:])
+            B_q[c0:c1, 1:], sB_pts[c0:c1] = _absmax_int8_rows(Bf[:, 1:])
+            sA[l], sB[l] = float(sA_cols[l].max()), float(sB_pts[c0:c1].max())
+        elif column_scales:
             A_q[l], sA_cols[l] = _absmax_int8_rows(Af)          # rows of A_c^T are the columns of A_c
             B_q[c0:c1], sB_pts[c0:c1] = _absmax_int8_rows(Bf)    # rows of B_c^T are the columns of B_c
             sA[l], sB[l] = float(sA_cols[l].max()), float(sB_pts[c0:c1].max())
@@ -258,7 +276,7 @@ def build_index(corpus: torch.Tensor, wl: Workload, *, exact_svd: bool = False, 
     return IndexArrays(metric=metric, n=n, d=d, dp=dp, r=r, L=L, centroids=centroids.contiguous(), P=P,
                        A=A_q, B=B_q, scale_A=sA.to(dev), scale_B=sB.to(dev), cluster_offsets=offsets,
                        corpus=corpus_sorted, ids=order.to(torch.int64).contiguous(), scale_A_columns=sA_cols,
-                       scale_B_points=sB_pts, A_f32=A_f, B_f32=B_f)
+                       scale_B_points=sB_pts, first_row_A=A_first, first_row_B=B_first, A_f32=A_f, B_f32=B_f)
 
 
 def random_index(corpus: torch.Tensor, wl: Workload) -> IndexArrays:

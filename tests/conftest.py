@@ -49,3 +49,15 @@ def small_indexes_columns(small_workloads):
         ix = build_index(corpus, wl, keep_float=True, column_scales=True)
         out[name] = (wl, ix, corpus.numpy(), queries.numpy())
     return out
+
+
+@pytest.fixture(scope="session")
+def small_indexes_mixed(small_workloads):
+    """The same workloads with the first row of every A_c and B_c kept in float (Sec. 4.2 mixed precision)."""
+    from paper_2410_18926_amd.synth import make_dataset, build_index
+    out = {}
+    for name, wl in small_workloads.items():
+        corpus, queries = make_dataset(wl)
+        ix = build_index(corpus, wl, keep_float=True, mixed_precision=True)
+        out[name] = (wl, ix, corpus.numpy(), queries.numpy())
+    return out

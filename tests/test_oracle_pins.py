@@ -345,6 +345,147 @@ def test_column_scales_track_float_model_and_beat_cluster_scales(small_indexes, 
         assert np.mean(err_cols) < np.mean(err_clus), (name, np.mean(err_cols), np.mean(err_clus))
 
 
+# ------------------------------------------------------------------ Sec. 4.2: mixed-precision decomposition
+def test_mixed_precision_hand_example():
+    """The first component of the query and the first rows of A_c and B_c stay in float; only the rest is quantized.
+    Numbers chosen so that every float operation is exact."""
+    qp = np.array([1000.0, 63.5, -127.0, 0.0, 32.0], np.float32)      # the large first component must not set the step
+    q8, dx = O.quantize_query_mixed(qp)
+    assert q8.tolist() == [0, 64, -127, 0, 32] and dx == np.float32(1.0)      # 63.5 -> 64 (tie to even)
+    A_c = np.array([[99, 2, 0, 0, 0],         # column 0 of A_c (its first entry, 99, must not be read)
+                    [-5, 0, 1, 0, 1],         # column 1
+                    [7, 1, 1, 0, 0]], np.int8)   # column 2
+    dA = np.array([0.5, 0.25, 2.0], np.float32)
+    A0 = np.array([0.5, -0.125, 0.0], np.float32)                     # first row of A_c
+    R, z, sigma, rho0 = O.stage_a_mixed(q8, float(qp[0]), A_c, float(dx), dA, A0)
+    assert R.tolist() == [128, -95, -63]
+    # rho = x0 A0 + R dx dA = [500 + 64, -125 - 23.75, 0 - 126] = [564, -148.75, -126]
+    assert rho0 == np.float32(564.0)
+    assert sigma == np.float32(148.75 / 127)                          # the rest's absmax, not 564
+    assert z.tolist() == [0, -127, -108]                              # 126 * 127 / 148.75 = 107.58
+    # score: rho0 B0_t on top of the quantized rest, both doubled for Euclidean
+    assert O.score_mixed(100, 0.5, 0.25, 564.0, 0.5, IP) == np.float32(12.5 + 282.0)
+    assert O.score_mixed(100, 0.5, 0.25, 564.0, 0.5, L2, 3.0) == np.float32(25.0 - 3.0 + 564.0)
+    assert O.score_mixed(100, 0.5, 0.25, 0.0, 0.5, COS) == O.score_columns(100, 0.5, 0.25, COS)
+
+
+def test_mixed_precision_reduces_to_column_scales_without_first_component():
+    """A query whose first component is zero, against factors whose first rows are zero, is the column-wise scheme on
+    the remaining components: same codes, same step sizes, same results."""
+    g = np.random.default_rng(31)
+    d, L, per, r = 12, 4, 30, 6
+    n = L * per
+    A = g.integers(-127, 128, (L, r, d)).astype(np.int8)
+    B = g.integers(-127, 128, (n, r)).astype(np.int8)
+    A[:, 0, :] = 0; A[:, :, 0] = 0; B[:, 0] = 0       # column 0 of every A_c and the first rows carry nothing
+    base = dict(metric=L2, n=n, d=d, dp=d, r=r, L=L, centroids=g.normal(size=(L, d)).astype(np.float32), P=None, A=A, B=B,
+                scale_A=np.ones(L, np.float32), scale_B=np.ones(L, np.float32),
+                scale_A_columns=g.uniform(0.01, 1, (L, r)).astype(np.float32),
+                scale_B_points=g.uniform(0.01, 1, n).astype(np.float32),
+                cluster_offsets=np.arange(L + 1, dtype=np.int64) * per,
+                corpus=g.normal(size=(n, d)).astype(np.float32), ids=None)
+    mixed = dict(base, first_row_A=np.zeros((L, r), np.float32), first_row_B=np.zeros(n, np.float32))
+    Q = g.normal(size=(20, d)).astype(np.float32)
+    Q[:, 0] = 0.0
+    a = O.search(O.OracleIndex(base), Q, 5, 3, 20, stages=True)
+    b = O.search(O.OracleIndex(mixed), Q, 5, 3, 20, stages=True)
+    for key in ("q8", "dx", "z", "sigma", "cand_rows", "cand_scores"):
+        np.testing.assert_array_equal(a[2][key], b[2][key], err_msg=key)
+    np.testing.assert_array_equal(a[0], b[0])
+    assert not b[2]["rho0"].any()
+
+
+def test_mixed_precision_exact_case_equals_brute_force():
+    """Codes that represent the quantized parts exactly (power-of-two steps) plus small-integer float rows: the
+    estimated score is then exactly <q^T A_c, B_c[:, t]> over the full real factors, so the search without
+    re-ranking orders the points as brute force over rationals does.  Dropping a float term (x_0 A_c[0][j] for any j,
+    r_0 B_c[0][t]), or taking it from the wrong cluster or row, changes the order."""
+    g = np.random.default_rng(32)
+    d, L, per = 9, 4, 20
+    n = L * per
+    # real A_c (d x d, r = d): first row a0 in float, below it diag(2^f_cj) on components 1..d-1
+    f = g.integers(0, 3, size=(L, d))
+    f[:, 1] = 2
+    a0 = g.integers(-3, 4, size=(L, d)).astype(np.int64) * 4         # multiples of 4: 127 rho_j / |rho|_inf stays integral
+    a0[:, 0] = g.integers(-3, 4, size=L)                              # (r_0 is not quantized: any value)
+    a0[:, 1] = 0                                                      # rho_1 = 127 * 4 stays the largest of the rest
+    A = np.zeros((L, d, d), np.int8)
+    A[:, np.arange(1, d), np.arange(1, d)] = 64
+    e = g.integers(-3, 4, size=n)
+    b = g.integers(-127, 128, size=(n, d)).astype(np.int64)
+    b[:, 0] = 0
+    b[:, 2] = 127                                                     # every row's absmax code is 127
+    b0 = g.integers(-5, 6, size=n).astype(np.int64)                   # real first row of B_c
+    ix = dict(metric=IP, n=n, d=d, dp=d, r=d, L=L, centroids=g.normal(size=(L, d)).astype(np.float32), P=None, A=A,
+              B=b.astype(np.int8), scale_A=np.ones(L, np.float32), scale_B=np.ones(L, np.float32),
+              scale_A_columns=(2.0 ** f / 64).astype(np.float32), scale_B_points=(2.0 ** e).astype(np.float32),
+              first_row_A=a0.astype(np.float32), first_row_B=b0.astype(np.float32),
+              cluster_offsets=np.arange(L + 1, dtype=np.int64) * per,
+              corpus=g.normal(size=(n, d)).astype(np.float32), ids=None)
+    # queries: x_0 a small integer; the rest multiples of 4 with |x_0 a0_j + x_j 2^f_cj| <= 108 + 320 < 508 = rho_1
+    Q = (g.integers(-20, 21, size=(10, d)) * 4).astype(np.int64)
+    Q[:, 1] = 127
+    Q[:, 0] = g.integers(-9, 10, size=10)
+    ids, dists = O.search_no_rerank(O.OracleIndex(ix), Q.astype(np.float32), 7, L)
+    for qi in range(len(Q)):
+        sc = []
+        for t in range(n):
+            c = t // per
+            x0 = int(Q[qi, 0])
+            r = [Fraction(x0 * int(a0[c, 0]))] + [Fraction(x0 * int(a0[c, j]) + int(Q[qi, j]) * 2 ** int(f[c, j])) for j in range(1, d)]
+            sc.append(r[0] * int(b0[t]) + sum(r[j] * int(b[t, j]) for j in range(1, d)) * Fraction(2) ** int(e[t]))
+        order = sorted(range(n), key=lambda t: (-sc[t], t))[:7]
+        assert ids[qi].tolist() == order, qi
+        assert [Fraction(float(v)) for v in dists[qi]] == [-sc[t] for t in order]
+
+
+def test_mixed_precision_tracks_float_model_better_when_first_component_dominates(small_indexes_columns, small_indexes_mixed):
+    """The reason for the decomposition (Sec. 4.2): after the projection the first component of the query lies on
+    the principal axis and dominates the absmax step, so keeping it (and the matching rows) in float leaves finer
+    steps for the rest.  On the projected workloads the estimated scores are closer to the unquantized model than
+    with the column-wise scheme alone; on every workload they obey the propagated quantization bound."""
+    better = []
+    for name, (wl, ix, corpus, queries) in small_indexes_mixed.items():
+        a = ix.numpy()
+        _, _, st = O.search(O.OracleIndex(a), queries, wl.k, wl.w, wl.m, stages=True)
+        ac = small_indexes_columns[name][1].numpy()
+        _, _, sc = O.search(O.OracleIndex(ac), queries, wl.k, wl.w, wl.m, stages=True)
+        err_mixed, err_cols = [], []
+        for qi in range(0, len(queries), 7):
+            qp = st["qproj"][qi].astype(np.float64)
+            for j in range(wl.w):
+                c = int(st["sel"][qi, j])
+                o0, o1 = int(a["cluster_offsets"][c]), int(a["cluster_offsets"][c + 1])
+                if o1 == o0:
+                    continue
+                y_float = (qp @ a["A_f32"][c].astype(np.float64).T) @ a["B_f32"][o0:o1].astype(np.float64).T
+                sg, r0 = float(st["sigma"][qi, j]), float(st["rho0"][qi, j])
+                Y = O.pair_accumulators(st["z"][qi, j], a["B"][o0:o1]).astype(np.float64)
+                s_hat = r0 * a["first_row_B"][o0:o1].astype(np.float64) + sg * a["scale_B_points"][o0:o1].astype(np.float64) * Y
+                # bound: half a step per quantized query component through |A|, half a step of z through |B|
+                A_real = (a["scale_A_columns"][c].astype(np.float64)[:, None] * a["A"][c].astype(np.float64)).T   # [dp][r], row 0 zero
+                B_real = (a["scale_B_points"][o0:o1].astype(np.float64)[:, None] * a["B"][o0:o1].astype(np.float64)).T
+                y_ref = (qp[1:] @ A_real[1:] + qp[0] * a["first_row_A"][c].astype(np.float64))
+                y_ref = y_ref[0] * a["first_row_B"][o0:o1].astype(np.float64) + y_ref[1:] @ B_real[1:]
+                err_r = 0.5 * float(st["dx"][qi]) * np.abs(A_real[1:]).sum(0) + 0.5 * sg
+                err_r[0] = 0.5 * float(st["dx"][qi]) * np.abs(A_real[1:, 0]).sum()
+                bound = err_r[1:] @ np.abs(B_real[1:]) + err_r[0] * np.abs(a["first_row_B"][o0:o1].astype(np.float64))
+                assert np.all(np.abs(s_hat - y_ref) <= bound * (1 + 1e-4) + 1e-5 * np.abs(y_ref).max()), name
+                if wl.dp < wl.d and int(sc["sel"][qi, j]) == c:
+                    # (the two builds rotate differently, so each is compared with its own unquantized model)
+                    qpc = sc["qproj"][qi].astype(np.float64)
+                    y_float_c = (qpc @ ac["A_f32"][c].astype(np.float64).T) @ ac["B_f32"][o0:o1].astype(np.float64).T
+                    Yc = O.pair_accumulators(sc["z"][qi, j], ac["B"][o0:o1]).astype(np.float64)
+                    s_c = float(sc["sigma"][qi, j]) * ac["scale_B_points"][o0:o1].astype(np.float64) * Yc
+                    err_mixed.append(np.abs(s_hat - y_float).mean() / (np.abs(y_float).mean() + 1e-30))
+                    err_cols.append(np.abs(s_c - y_float_c).mean() / (np.abs(y_float_c).mean() + 1e-30))
+        if err_mixed:
+            better.append((name, float(np.mean(err_mixed)), float(np.mean(err_cols))))
+    assert better, "no projected workload among the small ones"
+    print(better)
+    assert all(m < c for _, m, c in better), better
+
+
 # ------------------------------------------------------------------ Sec. 2.2 / 3.1 / 4.1: routing, selection, re-rank
 def test_projection_is_matrix_product():
     """Sec. 4.1: x' = W_s^T x."""
