@@ -177,6 +177,25 @@ int lorann_set_exact_selection(lorann_index *ix, int32_t on);
 int lorann_set_column_scales(lorann_index *ix, const float *scale_A_columns, const float *scale_B_points);
 
 /*
+ * lorann_set_first_rows - mixed-precision decomposition (Sec. 4.2): the first component of the projected query and
+ * the first row of every A_c and B_c are not quantized.  Needs the column-wise step sizes (lorann_set_column_scales).
+ *   first_row_A  [L][r] float: A_c[0][j], the row that meets the query's first component q'_0
+ *   first_row_B  [n] float: B_c[0][t] for the column of B_c that belongs to corpus row t
+ * The codes' first components (A[c][j][0], B[t][0]) are then not read, and the step sizes must have been formed
+ * from the remaining components.  Arithmetic, each operation one IEEE float operation in the order written:
+ *   codes of q' from q'_1.. alone (absmax over them; code 0 in position 0), Delta_x likewise;
+ *   rho_j = fma(q'_0, first_row_A[c][j], R_j * (Delta_x * scale_A_columns[c][j]))  for every j;
+ *   rho_0 stays a float;  z_0 = 0, (z_1..) = rint(rho * (127 / |rho_1..|_inf)),  sigma = |rho_1..|_inf / 127;
+ *   score of point t = fma(rho_0', first_row_B[t], fma(Y_t, sigma' * scale_B_points[t], -bias_t))
+ *   with (rho_0', sigma') = (rho_0, sigma), doubled for LORANN_L2.
+ * NULL, NULL switches the decomposition off (so does lorann_set_column_scales(ix, NULL, NULL)).  The arrays are
+ * copied (host or device pointers).
+ * Errors: LORANN_E_INVAL for one NULL of two, a non-finite value, or when the index has no column-wise step sizes
+ * (index unchanged).
+ */
+int lorann_set_first_rows(lorann_index *ix, const float *first_row_A, const float *first_row_B);
+
+/*
  * lorann_set_rerank - choose what the last step of later searches reads (Sec. 2.2 re-ranking; default F32).
  *   LORANN_RERANK_F32   the float corpus given at load time;
  *   LORANN_RERANK_F16   a half-precision (IEEE binary16, round to nearest even) copy of it, half the bytes of the
@@ -214,6 +233,8 @@ typedef struct lorann_stages {
     const int64_t *y_off;  /* [nq*w + 1]    caller-chosen offsets into y (needs sel known beforehand)     */
     int32_t *y;            /* [y_off[nq*w]] int32 score accumulators of every point of every pair, in     */
                            /*               cluster row order: y[y_off[slot] + t] (Sec. 3.3, 4.2)         */
+    float *rho0;           /* [nq][w]       unquantized first component of each pair's intermediate vector */
+                           /*               (zeros unless lorann_set_first_rows is in force; Sec. 4.2)     */
 } lorann_stages;
 
 /* lorann_search that also exports the intermediate results named in `st`.  Same arguments and errors as

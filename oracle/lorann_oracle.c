@@ -208,7 +208,7 @@ void oracle_stage_a_mixed(const int8_t *q8, float x0, int32_t dp, int32_t r, con
                           const float *dA /* [r] */, const float *A0 /* [r] first row of A_c */, int32_t *R, int8_t *z,
                           float *sigma, float *rho0)
 {
-    float *rho = (float *)malloc(sizeof(float) * (size_t)r);
+    float *rho = (float *)calloc((size_t)(r > 0 ? r : 1), sizeof(float));
     for (int32_t j = 0; j < r; ++j) {
         int32_t acc = 0;
         const int8_t *col = A_c + (size_t)j * dp;

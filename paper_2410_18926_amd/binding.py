@@ -23,7 +23,7 @@ LORANN_OK, LORANN_E_INVAL, LORANN_E_NOMEM, LORANN_E_DEVICE, LORANN_E_UNSUPPORTED
 
 EXPORTS = ["lorann_load_index", "lorann_load_index_file", "lorann_search", "lorann_search_async", "lorann_free_index", "lorann_last_error", "lorann_set_stream",
            "lorann_search_stages", "lorann_profile_enable", "lorann_profile_get", "lorann_set_exact_selection",
-           "lorann_profile_fallback_queries", "lorann_set_rerank", "lorann_set_column_scales", "lorann_search_lane", "lorann_lane_join", "lorann_set_gather_turns"]
+           "lorann_profile_fallback_queries", "lorann_set_rerank", "lorann_set_column_scales", "lorann_set_first_rows", "lorann_search_lane", "lorann_lane_join", "lorann_set_gather_turns"]
 LANES = 4
 RERANK_F32, RERANK_F16, RERANK_NONE = 0, 1, 2
 
@@ -35,7 +35,7 @@ class LorannError(RuntimeError):
 
 
 class _Stages(C.Structure):
-    _fields_ = [(n, C.c_void_p) for n in ("qproj", "q8", "dx", "sel", "z", "sigma", "cand_rows", "tau", "n_survivors", "y_off", "y")]
+    _fields_ = [(n, C.c_void_p) for n in ("qproj", "q8", "dx", "sel", "z", "sigma", "cand_rows", "tau", "n_survivors", "y_off", "y", "rho0")]
 
 
 class _KernelTime(C.Structure):
@@ -72,6 +72,8 @@ def lib() -> C.CDLL:
         L.lorann_set_exact_selection.argtypes = [vp, i32]
         L.lorann_set_column_scales.restype = C.c_int
         L.lorann_set_column_scales.argtypes = [vp, vp, vp]
+        L.lorann_set_first_rows.restype = C.c_int
+        L.lorann_set_first_rows.argtypes = [vp, vp, vp]
         L.lorann_search_lane.restype = C.c_int
         L.lorann_search_lane.argtypes = [vp, i32, vp, i64, i32, i32, i32, vp, vp]
         L.lorann_set_gather_turns.restype = C.c_int
@@ -114,7 +116,7 @@ class Index:
     """A loaded index (owns device memory inside the library)."""
 
     def __init__(self, metric, n, d, dp, r, L, centroids, P, A, B, scale_A, scale_B, cluster_offsets, corpus, ids=None,
-                 scale_A_columns=None, scale_B_points=None, **_):
+                 scale_A_columns=None, scale_B_points=None, first_row_A=None, first_row_B=None, **_):
         self._h = C.c_void_p()
         self.metric, self.n, self.d, self.dp, self.r, self.L = int(metric), int(n), int(d), int(dp), int(r), int(L)
         T = torch
@@ -130,6 +132,8 @@ class Index:
         del keep
         if scale_A_columns is not None or scale_B_points is not None:
             self.set_column_scales(scale_A_columns, scale_B_points)
+        if first_row_A is not None or first_row_B is not None:
+            self.set_first_rows(first_row_A, first_row_B)
 
     @classmethod
     def from_arrays(cls, ix) -> "Index":
@@ -140,6 +144,8 @@ class Index:
         if not isinstance(ix, dict):
             d["scale_A_columns"] = getattr(ix, "scale_A_columns", None)
             d["scale_B_points"] = getattr(ix, "scale_B_points", None)
+            d["first_row_A"] = getattr(ix, "first_row_A", None)
+            d["first_row_B"] = getattr(ix, "first_row_B", None)
         return cls(**d)
 
     @classmethod
@@ -213,7 +219,7 @@ class Index:
         st = dict(qproj=np.zeros((nq, self.dp), np.float32), q8=np.zeros((nq, self.dp), np.int8),
                   dx=np.zeros(nq, np.float32), sel=np.zeros((nq, w), np.int32), z=np.zeros((nq, w, self.r), np.int8),
                   sigma=np.zeros((nq, w), np.float32), cand_rows=np.zeros((nq, m), np.int32),
-                  tau=np.zeros(nq, np.float32), n_survivors=np.zeros(nq, np.int32))
+                  tau=np.zeros(nq, np.float32), n_survivors=np.zeros(nq, np.int32), rho0=np.zeros((nq, w), np.float32))
         cs = _Stages()
         for name in st:
             setattr(cs, name, st[name].ctypes.data)
@@ -235,6 +241,14 @@ class Index:
         ka, pa = _prep(scale_A_columns, np.float32, T.float32 if T else None)
         kb, pb = _prep(scale_B_points, np.float32, T.float32 if T else None)
         _check(lib().lorann_set_column_scales(self._h, pa, pb))
+
+    def set_first_rows(self, first_row_A, first_row_B):
+        """Mixed-precision decomposition: the unquantized first row of every A_c ([L, r]) and B_c ([n], one value per
+        corpus row); needs the column step sizes.  None, None switches it off."""
+        T = torch
+        ka, pa = _prep(first_row_A, np.float32, T.float32 if T else None)
+        kb, pb = _prep(first_row_B, np.float32, T.float32 if T else None)
+        _check(lib().lorann_set_first_rows(self._h, pa, pb))
 
     def set_rerank(self, mode: int):
         """RERANK_F32 (default), RERANK_F16 (half-precision copy of the corpus) or RERANK_NONE (no re-ranking step)."""

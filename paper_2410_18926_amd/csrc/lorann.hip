@@ -78,14 +78,14 @@ struct DevBuf {
 
 // Device buffers of one search in flight, sized for one chunk of queries, grown on demand.
 struct Workspace {
-    DevBuf qproj, qbf, q8, dx, gscore, sel, count, rank_in_bucket, qrank, qorder, qorder2, off0, base_tab, bucket_off, tile_off, unit_off, slot_of_pos, pos_of_slot, Z, sigma, cand;
+    DevBuf qproj, qbf, q8, dx, gscore, sel, count, rank_in_bucket, qrank, qorder, qorder2, off0, base_tab, bucket_off, tile_off, unit_off, slot_of_pos, pos_of_slot, Z, sigma, rho0, cand;
     DevBuf tau, n_kept, fb_list, pmax, qkey, u_row, u_mask, u_pos, u_count, rdist, rcid, rccount;
     hipStream_t stream = nullptr;          // lanes >= 1: created on first use, default priority
     hipEvent_t fork = nullptr, join = nullptr;
     hipEvent_t gather_done = nullptr;      // recorded after this lane's latest re-rank gather
     void release() {
         DevBuf* bufs[] = {&qproj, &qbf, &q8, &dx, &gscore, &sel, &count, &rank_in_bucket, &qrank, &qorder, &qorder2, &off0, &base_tab, &bucket_off, &tile_off,
-                          &unit_off, &slot_of_pos, &pos_of_slot, &Z, &sigma, &cand, &tau, &n_kept, &fb_list, &pmax, &qkey, &u_row, &u_mask, &u_pos, &u_count, &rdist, &rcid, &rccount};
+                          &unit_off, &slot_of_pos, &pos_of_slot, &Z, &sigma, &rho0, &cand, &tau, &n_kept, &fb_list, &pmax, &qkey, &u_row, &u_mask, &u_pos, &u_count, &rdist, &rcid, &rccount};
         for (DevBuf* b : bufs) b->release();
         if (fork) (void)hipEventDestroy(fork);
         if (gather_done) (void)hipEventDestroy(gather_done);
@@ -122,6 +122,8 @@ struct lorann_index {
     float *sA = nullptr, *sB = nullptr;
     float* sA_cols = nullptr;       // [L][r] column-wise quantization: step size of every column of A_c (else NULL)
     float* sB_pts = nullptr;        // [n]    ... and of every point's code
+    float* A_first = nullptr;       // [L][r] mixed-precision decomposition: unquantized first row of every A_c (else NULL)
+    float* B_first = nullptr;       // [n]    ... and of every B_c (one value per point)
     int64_t* off = nullptr;         // [L+1]
     float* corpus = nullptr;        // [n][d]
     _Float16* corpus_h = nullptr;   // [n][d] binary16 copy, made when the half-precision re-rank is first selected
@@ -149,7 +151,7 @@ struct lorann_index {
 namespace {
 
 void free_all(lorann_index* ix) {
-    void* ptrs[] = {ix->centroids, ix->cent_sqnorm, ix->cent_nrm_f32, ix->cent_bf16, ix->Pt, ix->A, ix->Bp, ix->sA, ix->sB, ix->sA_cols, ix->sB_pts, ix->off, ix->corpus, ix->corpus_h, ix->ids, ix->sqnorm};
+    void* ptrs[] = {ix->centroids, ix->cent_sqnorm, ix->cent_nrm_f32, ix->cent_bf16, ix->Pt, ix->A, ix->Bp, ix->sA, ix->sB, ix->sA_cols, ix->sB_pts, ix->A_first, ix->B_first, ix->off, ix->corpus, ix->corpus_h, ix->ids, ix->sqnorm};
     for (void* p : ptrs) if (p) (void)hipFree(p);
     for (Workspace& w : ix->ws) w.release();
     DevBuf* bufs[] = {&ix->stage_q, &ix->stage_ids, &ix->stage_dists, &ix->fb_total};
@@ -247,12 +249,14 @@ int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ
     if ((rc = ws.pos_of_slot.reserve((size_t)npairs * 4))) return rc;
     if ((rc = ws.Z.reserve((size_t)npairs * r_pad))) return rc;
     if ((rc = ws.sigma.reserve((size_t)npairs * 4))) return rc;
+    const bool mixed = ix->A_first != nullptr;      // Sec. 4.2: first component of q' and of every r stay in float
+    if (mixed && (rc = ws.rho0.reserve((size_t)npairs * 4))) return rc;
     if ((rc = ws.cand.reserve((size_t)nq * m * 4))) return rc;
 
     const float* qp = dQ;   // projected queries
     // With a projection and routing by screening: the projection also writes the bfloat16 copy of q', the selection
     // kernel also quantizes its query and clears the batch's counters - one pass over the queries less.
-    const bool fused_quant = !ix->force_exact && L <= 16384 && ix->Pt != nullptr;
+    const bool fused_quant = !ix->force_exact && L <= 16384 && ix->Pt != nullptr && !mixed;
     if (fused_quant && (rc = ws.qbf.reserve((size_t)nq * dp * 2))) return rc;
     __bf16* proj_bf = fused_quant ? ws.qbf.as<__bf16>() : nullptr;
     if (ix->Pt) {
@@ -273,7 +277,7 @@ int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ
     if (!fused_quant) {
         Prof p(ix, K_QUANTIZE, s);
         hipLaunchKernelGGL(k_quantize_rows, dim3((unsigned)((nq + 3) / 4)), dim3(256), 0, s, qp, ws.q8.as<int8_t>(), ws.dx.as<float>(), (int)nq, dp,
-                           ws.count.as<int32_t>(), 2 * L + 1, screen ? ws.qbf.as<__bf16>() : (__bf16*)nullptr);
+                           ws.count.as<int32_t>(), 2 * L + 1, screen ? ws.qbf.as<__bf16>() : (__bf16*)nullptr, mixed ? 1 : 0);
     }
     // an approximate-score matrix beyond the caches (256 MB) is streamed: written and read once, nothing of it is worth keeping
     const bool big_matrix = screen && L > 4096 && (int64_t)nq * L * 4 > (int64_t(256) << 20);
@@ -378,9 +382,11 @@ int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ
 #define LAUNCH_SA(RT_, RES_)                                                                                   \
     do {                                                                                                       \
         if (ix->sA_cols) hipLaunchKernelGGL((k_stage_a<RT_, RES_, true>), grid, dim3(256), 0, s, ws.q8.as<int8_t>(), ws.dx.as<float>(), ix->A, ix->sA_cols, ix->sB, \
-                                            ws.bucket_off.as<int32_t>(), ws.slot_of_pos.as<int32_t>(), L, dp, ix->r, w, ws.Z.as<int8_t>(), ws.sigma.as<float>()); \
+                                            ws.bucket_off.as<int32_t>(), ws.slot_of_pos.as<int32_t>(), L, dp, ix->r, w, ws.Z.as<int8_t>(), ws.sigma.as<float>(), \
+                                            qp, (const float*)ix->A_first, mixed ? ws.rho0.as<float>() : (float*)nullptr); \
         else hipLaunchKernelGGL((k_stage_a<RT_, RES_, false>), grid, dim3(256), 0, s, ws.q8.as<int8_t>(), ws.dx.as<float>(), ix->A, ix->sA, ix->sB, \
-                                ws.bucket_off.as<int32_t>(), ws.slot_of_pos.as<int32_t>(), L, dp, ix->r, w, ws.Z.as<int8_t>(), ws.sigma.as<float>()); \
+                                ws.bucket_off.as<int32_t>(), ws.slot_of_pos.as<int32_t>(), L, dp, ix->r, w, ws.Z.as<int8_t>(), ws.sigma.as<float>(), \
+                                (const float*)nullptr, (const float*)nullptr, (float*)nullptr); \
     } while (0)
         if (r_pad == 32) { if (dp <= 256) LAUNCH_SA(2, true); else LAUNCH_SA(2, false); }
         else { if (dp <= 256) LAUNCH_SA(4, true); else LAUNCH_SA(4, false); }
@@ -392,7 +398,7 @@ int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ
     SelectArgs sa_;
     sa_.qlist = nullptr; sa_.qcount = nullptr; sa_.fb_total = nullptr; sa_.sel = ws.sel.as<int32_t>(); sa_.pos_of_slot = ws.pos_of_slot.as<int32_t>();
     sa_.Z = ws.Z.as<int8_t>(); sa_.sigma = ws.sigma.as<float>(); sa_.Bp = ix->Bp; sa_.off = ix->off;
-    sa_.sqnorm = ix->metric == LORANN_L2 ? ix->sqnorm : nullptr; sa_.pt_scale = ix->sB_pts; sa_.cand = ws.cand.as<int32_t>(); sa_.w = w; sa_.m = m;
+    sa_.sqnorm = ix->metric == LORANN_L2 ? ix->sqnorm : nullptr; sa_.pt_scale = ix->sB_pts; sa_.pt_first = ix->B_first; sa_.rho0 = mixed ? ws.rho0.as<float>() : nullptr; sa_.cand = ws.cand.as<int32_t>(); sa_.w = w; sa_.m = m;
     if (ix->force_exact) {
         Prof p(ix, K_SELECT_M, s);
         const unsigned grid = (unsigned)std::min<int64_t>(nq, 65536);
@@ -410,12 +416,15 @@ int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ
             ScoreArgs sc;
             sc.Bp = ix->Bp; sc.Z = ws.Z.as<int8_t>(); sc.sigma = ws.sigma.as<float>(); sc.off = ix->off;
             sc.bucket_off = ws.bucket_off.as<int32_t>(); sc.unit_off = ws.unit_off.as<int32_t>();
-            sc.sqnorm = l2 ? ix->sqnorm : nullptr; sc.pt_scale = ix->sB_pts; sc.pmax = ws.pmax.as<uint32_t>(); sc.L = L; sc.chunk_tiles = kChunkTiles;
+            sc.sqnorm = l2 ? ix->sqnorm : nullptr; sc.pt_scale = ix->sB_pts; sc.pt_first = ix->B_first; sc.rho0 = mixed ? ws.rho0.as<float>() : nullptr; sc.pmax = ws.pmax.as<uint32_t>(); sc.L = L; sc.chunk_tiles = kChunkTiles;
             // few pairs per cluster: the kernel streams the codes of the touched clusters, one wavefront per cluster
             const bool stream = npairs <= (int64_t)16 * L;
 #define LAUNCH_PM(KS_, L2_)                                                                                          \
     do {                                                                                                             \
-        if (ix->sB_pts) {                                                                                            \
+        if (mixed) {                                                                                                 \
+            if (stream) hipLaunchKernelGGL((k_pair_max<1, KS_, L2_, 8 / KS_, true, 4, true, true>), dim3((unsigned)((L + 3) / 4)), dim3(256), 0, s, sc); \
+            else hipLaunchKernelGGL((k_pair_max<kNZ, KS_, L2_, 4, false, 4, true, true>), dim3(2048), dim3(256), 0, s, sc); \
+        } else if (ix->sB_pts) {                                                                                     \
             if (stream) hipLaunchKernelGGL((k_pair_max<1, KS_, L2_, 8 / KS_, true, 4, true>), dim3((unsigned)((L + 3) / 4)), dim3(256), 0, s, sc); \
             else hipLaunchKernelGGL((k_pair_max<kNZ, KS_, L2_, 4, false, 4, true>), dim3(2048), dim3(256), 0, s, sc); \
         } else if (stream) hipLaunchKernelGGL((k_pair_max<1, KS_, L2_, 8 / KS_, true, 4>), dim3((unsigned)((L + 3) / 4)), dim3(256), 0, s, sc); \
@@ -429,7 +438,7 @@ int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ
             Prof p(ix, K_SELECT_QUERY, s);
             QuerySelectArgs qa;
             qa.sel = ws.sel.as<int32_t>(); qa.pos_of_slot = ws.pos_of_slot.as<int32_t>(); qa.pmax = ws.pmax.as<uint32_t>();
-            qa.Z = ws.Z.as<int8_t>(); qa.sigma = ws.sigma.as<float>(); qa.Bp = ix->Bp; qa.off = ix->off; qa.sqnorm = l2 ? ix->sqnorm : nullptr; qa.pt_scale = ix->sB_pts;
+            qa.Z = ws.Z.as<int8_t>(); qa.sigma = ws.sigma.as<float>(); qa.Bp = ix->Bp; qa.off = ix->off; qa.sqnorm = l2 ? ix->sqnorm : nullptr; qa.pt_scale = ix->sB_pts; qa.pt_first = ix->B_first; qa.rho0 = mixed ? ws.rho0.as<float>() : nullptr;
             qa.cand = ws.cand.as<int32_t>(); qa.tau = ws.tau.as<float>(); qa.n_kept = ws.n_kept.as<int32_t>(); qa.qkey = ws.qkey.as<int32_t>();
             qa.fb_list = ws.fb_list.as<int32_t>(); qa.fb_count = ws.count.as<int32_t>() + 2 * L; qa.qorder = ws.qorder.as<int32_t>(); qa.nq = (int)nq; qa.w = w; qa.m = m; qa.cap = select_query_cap(m);
             const size_t qlds = (size_t)qa.cap * 8;
@@ -571,19 +580,22 @@ int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ
         if (st->cand_rows) HIP_TRY(hipMemcpy(st->cand_rows + (size_t)q_base * m, ws.cand.p, (size_t)nq * m * 4, hipMemcpyDefault));
         if (st->tau && !ix->force_exact) HIP_TRY(hipMemcpy(st->tau + q_base, ws.tau.p, (size_t)nq * 4, hipMemcpyDefault));
         if (st->n_survivors && !ix->force_exact) HIP_TRY(hipMemcpy(st->n_survivors + q_base, ws.n_kept.p, (size_t)nq * 4, hipMemcpyDefault));
-        if (st->z || st->sigma) {   // bucket order -> slot order on the host
+        if (st->z || st->sigma || st->rho0) {   // bucket order -> slot order on the host
             std::vector<int32_t> pos(npairs);
             std::vector<int8_t> Zh((size_t)npairs * r_pad);
-            std::vector<float> sg(npairs);
+            std::vector<float> sg(npairs), r0(npairs, 0.0f);
+            if (mixed) HIP_TRY(hipMemcpy(r0.data(), ws.rho0.p, (size_t)npairs * 4, hipMemcpyDeviceToHost));
             HIP_TRY(hipMemcpy(pos.data(), ws.pos_of_slot.p, (size_t)npairs * 4, hipMemcpyDeviceToHost));
             HIP_TRY(hipMemcpy(Zh.data(), ws.Z.p, (size_t)npairs * r_pad, hipMemcpyDeviceToHost));
             HIP_TRY(hipMemcpy(sg.data(), ws.sigma.p, (size_t)npairs * 4, hipMemcpyDeviceToHost));
             std::vector<int8_t> zo((size_t)npairs * ix->r);
-            std::vector<float> so(npairs);
+            std::vector<float> so(npairs), ro(npairs);
             for (int64_t p = 0; p < npairs; ++p) {
                 memcpy(zo.data() + (size_t)p * ix->r, Zh.data() + (size_t)pos[p] * r_pad, (size_t)ix->r);
                 so[p] = sg[pos[p]];
+                ro[p] = r0[pos[p]];
             }
+            if (st->rho0) HIP_TRY(hipMemcpy(st->rho0 + (size_t)q_base * w, ro.data(), ro.size() * 4, hipMemcpyDefault));
             if (st->z) HIP_TRY(hipMemcpy(st->z + (size_t)q_base * w * ix->r, zo.data(), zo.size(), hipMemcpyDefault));
             if (st->sigma) HIP_TRY(hipMemcpy(st->sigma + (size_t)q_base * w, so.data(), so.size() * 4, hipMemcpyDefault));
         }
@@ -963,6 +975,37 @@ int lorann_set_column_scales(lorann_index* ix, const float* scale_A_columns, con
     if (ix->sA_cols) (void)hipFree(ix->sA_cols);
     if (ix->sB_pts) (void)hipFree(ix->sB_pts);
     ix->sA_cols = na; ix->sB_pts = nb;
+    if (!na) {      // the float first rows belong to the column-wise scheme: they go with it
+        if (ix->A_first) (void)hipFree(ix->A_first);
+        if (ix->B_first) (void)hipFree(ix->B_first);
+        ix->A_first = ix->B_first = nullptr;
+    }
+    return LORANN_OK;
+}
+
+int lorann_set_first_rows(lorann_index* ix, const float* first_row_A, const float* first_row_B) {
+    if (!ix) return fail(LORANN_E_INVAL, "index is NULL");
+    if ((first_row_A == nullptr) != (first_row_B == nullptr)) return fail(LORANN_E_INVAL, "give both first rows, or NULL for both");
+    if (first_row_A && !ix->sA_cols) return fail(LORANN_E_INVAL, "the mixed-precision decomposition needs the column-wise step sizes (lorann_set_column_scales first)");
+    float *na = nullptr, *nb = nullptr;
+    if (first_row_A) {
+        const size_t cnt[2] = {(size_t)ix->L * ix->r, (size_t)ix->n};
+        const float* src[2] = {first_row_A, first_row_B};
+        for (int t = 0; t < 2; ++t) {
+            std::vector<float> h(cnt[t]);
+            hipError_t e = hipMemcpy(h.data(), src[t], cnt[t] * 4, hipMemcpyDefault);
+            if (e != hipSuccess) { (void)hipGetLastError(); return fail(LORANN_E_DEVICE, "reading the first rows failed: %s", hipGetErrorString(e)); }
+            for (size_t i = 0; i < cnt[t]; ++i)
+                if (!(std::fabs(h[i]) <= 3.0e38f)) return fail(LORANN_E_INVAL, "first_row_%s[%zu] must be finite", t ? "B" : "A", i);
+        }
+        int rc;
+        if ((rc = dev_copy(&na, first_row_A, cnt[0]))) return rc;
+        if ((rc = dev_copy(&nb, first_row_B, cnt[1]))) { (void)hipFree(na); return rc; }
+    }
+    { const int rc = sync_all(ix); if (rc) return rc; }   // no search may still be reading the old arrays
+    if (ix->A_first) (void)hipFree(ix->A_first);
+    if (ix->B_first) (void)hipFree(ix->B_first);
+    ix->A_first = na; ix->B_first = nb;
     return LORANN_OK;
 }
 

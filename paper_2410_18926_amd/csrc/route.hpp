@@ -11,9 +11,12 @@ namespace lorann {
 // a zero row gives zero codes and step 0.  The quotients are formed in double and rounded once, which equals
 // IEEE float division.  The first blocks also clear the `nzero` counters of the counting sorts that follow.
 // qb (optional): the row rounded to bfloat16, for the approximate centroid scores.
+// first = 1 (Sec. 4.2 mixed-precision decomposition): component 0 is not quantized - it takes no part in the
+// maximum and its code is 0, so that the integer products that follow skip it; first = 0 otherwise.
 __global__ __launch_bounds__(256) void k_quantize_rows(const float* __restrict__ qp, int8_t* __restrict__ q8,
                                                         float* __restrict__ dx, int nq, int dp,
-                                                        int32_t* __restrict__ zero, int nzero, __bf16* __restrict__ qb) {
+                                                        int32_t* __restrict__ zero, int nzero, __bf16* __restrict__ qb,
+                                                        int first) {
     for (int i = blockIdx.x * 256 + threadIdx.x; i < nzero; i += gridDim.x * 256) zero[i] = 0;
     const int lane = threadIdx.x & 63;
     const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -22,7 +25,7 @@ __global__ __launch_bounds__(256) void k_quantize_rows(const float* __restrict__
     float a = 0.0f;
     for (int i = lane; i < dp; i += 64) {
         const float x = p[i];
-        a = fmaxf(a, fabsf(x));
+        if (i >= first) a = fmaxf(a, fabsf(x));
         if (qb) qb[(size_t)row * dp + i] = (__bf16)x;
     }
     a = wave_max_f32(a);
@@ -36,7 +39,7 @@ __global__ __launch_bounds__(256) void k_quantize_rows(const float* __restrict__
     for (int i = lane; i < dp; i += 64) {
         int v = (int)rintf(__fmul_rn(p[i], cx));
         v = max(-127, min(127, v));
-        o[i] = (int8_t)v;
+        o[i] = (int8_t)(i >= first ? v : 0);
     }
     if (lane == 0) dx[row] = (float)((double)a / 127.0);
 }

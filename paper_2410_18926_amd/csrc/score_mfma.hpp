@@ -28,6 +28,8 @@ struct ScoreArgs {
     const int32_t* unit_off;     // [L+1] work items (pair group x point chunk) of each cluster
     const float* sqnorm;         // [n] (Euclidean) or NULL
     const float* pt_scale;       // [n] step size of each point's code (column-wise quantization) or NULL
+    const float* pt_first;       // [n] unquantized first row of B_c (mixed-precision decomposition) or NULL
+    const float* rho0;           // [npairs] bucket order: unquantized first component of each pair's r, or NULL
     uint32_t* pmax;              // out: [npairs] order-preserving key of the pair's best score (0 on entry)
     int L;
     int chunk_tiles;             // 32-point tiles per work item
@@ -49,12 +51,15 @@ __device__ __forceinline__ void wave_lds_sync() {
 // NZ pair tiles per item, KS = r_pad / 32 k-steps, L2 = Euclidean score epilogue (per-point bias, float domain;
 // inner product and cosine compare the integer maximum, sigma >= 0 being constant per pair).  COLS = column-wise
 // quantization: every point has its own step size, so the maximum is taken over float scores for every metric.
+// MIX (with COLS; Sec. 4.2 mixed-precision decomposition): score = fma(rho0', pt_first[t], score of the quantized
+// rest), rho0' = rho0 of the pair (twice that for Euclidean).
 // TB = point tiles fetched ahead (double buffered in registers).
 // STREAM = false: items as above.  STREAM = true (few pairs per cluster: the kernel is a pure stream of the
 // codes from HBM): one wavefront per cluster takes all of its points, no search for the item's cluster, deeper
 // fetch-ahead; clusters without pairs cost nothing.
-template <int NZ, int KS, bool L2, int TB, bool STREAM, int WPB, bool COLS = false>
+template <int NZ, int KS, bool L2, int TB, bool STREAM, int WPB, bool COLS = false, bool MIX = false>
 __global__ __launch_bounds__(64 * WPB) void k_pair_max(ScoreArgs a) {
+    static_assert(!MIX || COLS, "the mixed-precision decomposition builds on the column-wise step sizes");
     constexpr bool FLT = L2 || COLS;   // float-domain epilogue
     constexpr int NP = 32 * NZ;        // pairs per item
     constexpr int RP = KS * 32;
@@ -63,6 +68,7 @@ __global__ __launch_bounds__(64 * WPB) void k_pair_max(ScoreArgs a) {
     __shared__ int s_tr[WPB][64 * TRS];
     __shared__ int s_red[WPB][NP];       // per-pair maxima of the item (int, or order-preserving keys for Euclidean)
     __shared__ float s_sig[WPB][NP];     // Euclidean: 2 sigma of each pair
+    __shared__ float s_r0[WPB][MIX ? NP : 1];
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     const int j = lane & 31, h = lane >> 5;
     // no block-wide barrier below: the wavefronts of a block are independent
@@ -80,14 +86,21 @@ __global__ __launch_bounds__(64 * WPB) void k_pair_max(ScoreArgs a) {
             }
         }
         float sgv[NZ][16];             // float epilogue only: scale of the pair that register v belongs to
+        float r0v[MIX ? NZ : 1][16];   // MIX: (doubled) first component of that pair's r
         if (FLT) {
             wave_lds_sync();
-            for (int p = lane; p < NP; p += 64) s_sig[wv][p] = (pb + p < pend) ? (L2 ? 2.0f : 1.0f) * a.sigma[pb + p] : 0.0f;
+            for (int p = lane; p < NP; p += 64) {
+                s_sig[wv][p] = (pb + p < pend) ? (L2 ? 2.0f : 1.0f) * a.sigma[pb + p] : 0.0f;
+                if (MIX) s_r0[wv][p] = (pb + p < pend) ? (L2 ? 2.0f : 1.0f) * a.rho0[pb + p] : 0.0f;
+            }
             wave_lds_sync();
 #pragma unroll
             for (int z = 0; z < NZ; ++z)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) sgv[z][v] = s_sig[wv][32 * z + tile_row(v, h)];
+                for (int v = 0; v < 16; ++v) {
+                    sgv[z][v] = s_sig[wv][32 * z + tile_row(v, h)];
+                    if (MIX) r0v[z][v] = s_r0[wv][32 * z + tile_row(v, h)];
+                }
         }
         int mxi[NZ][16];
         float mxf[NZ][16];
@@ -102,7 +115,7 @@ __global__ __launch_bounds__(64 * WPB) void k_pair_max(ScoreArgs a) {
         // lanes of the cluster's last tile that lie past its end read the rows that follow (the allocation is
         // padded by 32 rows) and are masked out of the maxima below.
         const int8_t* bbase = a.Bp + (size_t)(row0 + j) * RP + 16 * h;
-        auto fetch_chunk = [&](int t0, i32x4 (*dst)[KS], float* nb, float* ns) {
+        auto fetch_chunk = [&](int t0, i32x4 (*dst)[KS], float* nb, float* ns, float* nf) {
 #pragma unroll
             for (int u = 0; u < TB; ++u) {
                 if (t0 + u < ntiles) {                   // uniform
@@ -115,15 +128,17 @@ __global__ __launch_bounds__(64 * WPB) void k_pair_max(ScoreArgs a) {
                     }
                     if (L2) nb[u] = a.sqnorm[row0 + min(32 * (t0 + u) + j, m_c - 1)];
                     if (COLS) ns[u] = a.pt_scale[row0 + min(32 * (t0 + u) + j, m_c - 1)];
+                    if (MIX) nf[u] = a.pt_first[row0 + min(32 * (t0 + u) + j, m_c - 1)];
                 } else {
 #pragma unroll
                     for (int ks = 0; ks < KS; ++ks) dst[u][ks] = (i32x4){0, 0, 0, 0};
                     if (L2) nb[u] = 0.0f;
                     if (COLS) ns[u] = 0.0f;
+                    if (MIX) nf[u] = 0.0f;
                 }
             }
         };
-        auto score_chunk = [&](int c0, i32x4 (*breg)[KS], const float* nb, const float* ns) {
+        auto score_chunk = [&](int c0, i32x4 (*breg)[KS], const float* nb, const float* ns, const float* nf) {
             // Two tiles at a time, so that ONE three-operand maximum per result register takes in both tiles (the
             // epilogue is bound by the vector ALU: integer maxima cost one instruction per score otherwise).
             static_assert(TB % 2 == 0, "tiles are taken in pairs");
@@ -156,8 +171,12 @@ __global__ __launch_bounds__(64 * WPB) void k_pair_max(ScoreArgs a) {
                             for (int v = 0; v < 16; ++v) {
                                 const float mult_a = COLS ? __fmul_rn(sgv[z][v], ns[u]) : sgv[z][v];
                                 const float mult_b = COLS ? __fmul_rn(sgv[z][v], ns[u + 1]) : sgv[z][v];
-                                const float sc_a = __fmaf_rn((float)acc_a[v], mult_a, -bias_a);
-                                const float sc_b = __fmaf_rn((float)acc_b[v], mult_b, -bias_b);
+                                float sc_a = __fmaf_rn((float)acc_a[v], mult_a, -bias_a);
+                                float sc_b = __fmaf_rn((float)acc_b[v], mult_b, -bias_b);
+                                if (MIX) {
+                                    sc_a = __fmaf_rn(r0v[MIX ? z : 0][v], nf[u], sc_a);
+                                    sc_b = __fmaf_rn(r0v[MIX ? z : 0][v], nf[u + 1], sc_b);
+                                }
                                 mxf[z][v] = fmaxf(fmaxf(mxf[z][v], ok_a ? sc_a : -INFINITY), ok_b ? sc_b : -INFINITY);
                             }
                         }
@@ -168,19 +187,19 @@ __global__ __launch_bounds__(64 * WPB) void k_pair_max(ScoreArgs a) {
         };
         {
             i32x4 bnext[TB][KS];
-            float nbnext[TB], nsnext[TB];
-            if (nchunks > 0) fetch_chunk(0, bnext, nbnext, nsnext);
+            float nbnext[TB], nsnext[TB], nfnext[TB];
+            if (nchunks > 0) fetch_chunk(0, bnext, nbnext, nsnext, nfnext);
             for (int c0 = 0; c0 < nchunks; ++c0) {
                 i32x4 breg[TB][KS];
-                float nb[TB], ns[TB];
+                float nb[TB], ns[TB], nf[TB];
 #pragma unroll
                 for (int u = 0; u < TB; ++u) {
-                    nb[u] = nbnext[u]; ns[u] = nsnext[u];
+                    nb[u] = nbnext[u]; ns[u] = nsnext[u]; nf[u] = nfnext[u];
 #pragma unroll
                     for (int ks = 0; ks < KS; ++ks) breg[u][ks] = bnext[u][ks];
                 }
-                if (c0 + 1 < nchunks) fetch_chunk((c0 + 1) * TB, bnext, nbnext, nsnext);
-                score_chunk(c0, breg, nb, ns);
+                if (c0 + 1 < nchunks) fetch_chunk((c0 + 1) * TB, bnext, nbnext, nsnext, nfnext);
+                score_chunk(c0, breg, nb, ns, nf);
             }
         }
 

@@ -44,6 +44,8 @@ struct SelectArgs {
     const int64_t* off;          // [L+1]
     const float* sqnorm;         // [n] (Euclidean) or NULL
     const float* pt_scale;       // [n] step size of each point's code (column-wise quantization) or NULL
+    const float* pt_first;       // [n] unquantized first row of B_c (mixed-precision decomposition) or NULL
+    const float* rho0;           // [npairs] bucket order: unquantized first component of each pair's r, or NULL
     int32_t* cand;               // [nq][m] out: candidate rows, -1 padded
     int32_t* fb_total;           // optional running total of the list lengths seen (profiling), or NULL
     int w, m;
@@ -55,7 +57,7 @@ __device__ __forceinline__ void select_exact_query(const SelectArgs& a, const in
     constexpr int ZW = RB * 4;                    // 32-bit words per z vector
     __shared__ int pc[256], ppos[256], pcnt[256], pstart[257];
     __shared__ int64_t prow0[256];
-    __shared__ float psig[256];
+    __shared__ float psig[256], pr0[256];
     __shared__ int zs[256 * ZW];
     __shared__ int hist[256];
     __shared__ int wsum[4];
@@ -84,6 +86,8 @@ __device__ __forceinline__ void select_exact_query(const SelectArgs& a, const in
         pcnt[myrank] = (int)(a.off[myc + 1] - r0);
         const float s = a.sigma[mypos];
         psig[myrank] = l2 ? 2.0f * s : s;
+        const float r0f = a.rho0 ? a.rho0[mypos] : 0.0f;
+        pr0[myrank] = l2 ? 2.0f * r0f : r0f;
     }
     __syncthreads();
     if (tid == 0) {
@@ -112,7 +116,9 @@ __device__ __forceinline__ void select_exact_query(const SelectArgs& a, const in
         const int y = point_score<RB>(a.Bp + (size_t)row * (RB * 16), zs + j * ZW);
         const float bias = l2 ? a.sqnorm[row] : 0.0f;
         const float mult = a.pt_scale ? __fmul_rn(psig[j], a.pt_scale[row]) : psig[j];
-        return float_key_asc(__fmaf_rn((float)y, mult, -bias));
+        float sc = __fmaf_rn((float)y, mult, -bias);
+        if (a.pt_first) sc = __fmaf_rn(pr0[j], a.pt_first[row], sc);
+        return float_key_asc(sc);
     };
 
     uint32_t mask = 0u;
@@ -214,7 +220,8 @@ __global__ __launch_bounds__(256) void k_candidate_scores(SelectArgs a, int nq, 
             const float sg = a.sigma[pos];
             const float bias = l2 ? a.sqnorm[row] : 0.0f;
             const float sp = l2 ? 2.0f * sg : sg;
-            const float sc = __fmaf_rn((float)y, a.pt_scale ? __fmul_rn(sp, a.pt_scale[row]) : sp, -bias);
+            float sc = __fmaf_rn((float)y, a.pt_scale ? __fmul_rn(sp, a.pt_scale[row]) : sp, -bias);
+            if (a.pt_first) sc = __fmaf_rn(l2 ? 2.0f * a.rho0[pos] : a.rho0[pos], a.pt_first[row], sc);
             dist[(size_t)q * m + t] = -sc;
             cid[(size_t)q * m + t] = ids ? ids[row] : (int64_t)row;
         }

@@ -85,6 +85,8 @@ struct QuerySelectArgs {
     const int64_t* off;          // [L+1]
     const float* sqnorm;         // [n] (Euclidean) or NULL
     const float* pt_scale;       // [n] step size of each point's code (column-wise quantization) or NULL
+    const float* pt_first;       // [n] unquantized first row of B_c (mixed-precision decomposition) or NULL
+    const float* rho0;           // [npairs] bucket order: unquantized first component of each pair's r, or NULL
     int32_t* cand;               // out [nq][m]: candidate rows, unordered, -1 padded
     float* tau;                  // out [nq]: score of the m-th candidate (-inf if fewer than m points were scored)
     int32_t* n_kept;             // out [nq]: scores held in LDS when the walk ended (-1: handed to the exact kernel)
@@ -120,7 +122,7 @@ __global__ __launch_bounds__(256) void k_select_query(QuerySelectArgs a) {
     if (si >= a.nq) return;
     const int q = __builtin_amdgcn_readfirstlane(a.qorder[si]);     // uniform over the block: scalar loads below
     const int w = a.w, m = a.m;
-    const bool l2 = a.sqnorm != nullptr, cols = a.pt_scale != nullptr;
+    const bool l2 = a.sqnorm != nullptr, cols = a.pt_scale != nullptr, mixed = a.pt_first != nullptr;
     if (tid == 0) s_count = 0;
     if (tid < w) {
         const int pos = a.pos_of_slot[(size_t)q * w + tid];
@@ -176,8 +178,9 @@ __global__ __launch_bounds__(256) void k_select_query(QuerySelectArgs a) {
         // requests that do not depend on each other go out together: the pair's z and sigma, the first codes
         const int zv = reinterpret_cast<const int*>(a.Z)[(size_t)pos * ZW + (tid < ZW ? tid : 0)];
         const float s = a.sigma[pos];
+        const float rfirst = mixed ? a.rho0[pos] : 0.0f;
         i32x4 code[PT][RB];
-        float bias[PT], psc[PT];
+        float bias[PT], psc[PT], pf[PT];
         auto fetch_codes = [&](int p0) {
 #pragma unroll
             for (int e = 0; e < PT; ++e) {
@@ -188,6 +191,7 @@ __global__ __launch_bounds__(256) void k_select_query(QuerySelectArgs a) {
                     for (int u = 0; u < RB; ++u) code[e][u] = bp[u];
                     bias[e] = l2 ? a.sqnorm[row] : 0.0f;
                     psc[e] = cols ? a.pt_scale[row] : 1.0f;     // times 1 is exact: one code path for both schemes
+                    pf[e] = mixed ? a.pt_first[row] : 0.0f;
                 }
             }
         };
@@ -196,6 +200,7 @@ __global__ __launch_bounds__(256) void k_select_query(QuerySelectArgs a) {
         if (tid < ZW) zw[tid] = zv;
         __syncthreads();
         const float sp = l2 ? 2.0f * s : s;
+        const float r0p = l2 ? 2.0f * rfirst : rfirst;
         for (int p0 = 0; p0 < m_c; p0 += kQChunk) {
             if (count > kQCap - kQChunk) {
                 compact();
@@ -214,7 +219,9 @@ __global__ __launch_bounds__(256) void k_select_query(QuerySelectArgs a) {
                         y = dot4_i8(code[e][u][2], zw[4 * u + 2], y);
                         y = dot4_i8(code[e][u][3], zw[4 * u + 3], y);
                     }
-                    const uint32_t key = float_key_asc(__fmaf_rn((float)y, __fmul_rn(sp, psc[e]), -bias[e]));
+                    float sc = __fmaf_rn((float)y, __fmul_rn(sp, psc[e]), -bias[e]);
+                    if (mixed) sc = __fmaf_rn(r0p, pf[e], sc);      // uniform
+                    const uint32_t key = float_key_asc(sc);
                     if (t < m_c && key >= T) {
                         const int at = atomicAdd(&s_count, 1);
                         keys[at] = key;

@@ -50,12 +50,17 @@ __device__ __forceinline__ int find_bucket_wave(const int32_t* __restrict__ off,
 // COLS: column-wise quantization (Sec. 3.3 as printed) - sA is [L][r], one step size per column of A_c; the float
 // approximation rho_j = R_j * (Delta_x * DeltaA_cj) is re-quantized like a query: z = rint(rho * 127 / |rho|_inf),
 // sigma = |rho|_inf / 127 (every operation a single IEEE float operation); sB is not used.
+// COLS with A_first != NULL (Sec. 4.2 mixed-precision decomposition; the queries' codes then have 0 in component
+// 0): rho_j = fma(x_0, A_first[c][j], R_j * (Delta_x * DeltaA_cj)) with x_0 = qproj[query][0]; rho_0 goes to
+// rho0[pair] as it is, z_0 = 0, and the maximum and the codes come from rho_1.. alone.
 template <int RT, bool RES, bool COLS = false>
 __global__ __launch_bounds__(256) void k_stage_a(const int8_t* __restrict__ q8, const float* __restrict__ dx,
                                                   const int8_t* __restrict__ A, const float* __restrict__ sA,
                                                   const float* __restrict__ sB, const int32_t* __restrict__ bucket_off,
                                                   const int32_t* __restrict__ slot_of_pos,
-                                                  int L, int dp, int r, int w, int8_t* __restrict__ Z, float* __restrict__ sigma) {
+                                                  int L, int dp, int r, int w, int8_t* __restrict__ Z, float* __restrict__ sigma,
+                                                  const float* __restrict__ qproj = nullptr, const float* __restrict__ A_first = nullptr,
+                                                  float* __restrict__ rho0 = nullptr) {
     const int lane = threadIdx.x & 63;
     const int c = blockIdx.x;
     const int pbeg = bucket_off[c], end = bucket_off[c + 1];
@@ -119,17 +124,30 @@ __global__ __launch_bounds__(256) void k_stage_a(const int8_t* __restrict__ q8, 
 
     // acc[t][v] = R[pair 4g+v][column 16t+i].  Row maximum over the r columns: over t here, over i by shuffles.
     if constexpr (COLS) {
-        float dA[RT];
+        const bool mixed = A_first != nullptr;           // uniform
+        float dA[RT], a0[RT];
 #pragma unroll
-        for (int t = 0; t < RT; ++t) dA[t] = sA[(size_t)c * r + min(t * 16 + i, r - 1)];
+        for (int t = 0; t < RT; ++t) {
+            dA[t] = sA[(size_t)c * r + min(t * 16 + i, r - 1)];
+            a0[t] = mixed ? A_first[(size_t)c * r + min(t * 16 + i, r - 1)] : 0.0f;
+        }
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
             const int pos = base + 4 * g + v;
-            const float dxq = dx[slot_of_pos[min(pos, end - 1)] / w];
+            const int qv = slot_of_pos[min(pos, end - 1)] / w;
+            const float dxq = dx[qv];
+            const float x0 = mixed ? qproj[(size_t)qv * dp] : 0.0f;
             float rho[RT], mx = 0.0f;
 #pragma unroll
             for (int t = 0; t < RT; ++t) {
                 rho[t] = t * 16 + i < r ? __fmul_rn((float)acc[t][v], __fmul_rn(dxq, dA[t])) : 0.0f;
+                if (mixed) {
+                    if (t * 16 + i < r) rho[t] = __fmaf_rn(x0, a0[t], rho[t]);
+                    if (t == 0 && i == 0) {                  // the unquantized first component of r
+                        if (pos < end) rho0[pos] = rho[0];
+                        rho[0] = 0.0f;                       // out of the maximum; its code is rint(0) = 0
+                    }
+                }
                 mx = fmaxf(mx, fabsf(rho[t]));
             }
 #pragma unroll

@@ -39,6 +39,7 @@ def _stagewise(B, wl, ix, queries, k=None, w=None, m=None, device_inputs=True):
     np.testing.assert_array_equal(gst["sel"], ost["sel"], err_msg=f"{tag}: selected clusters")
     np.testing.assert_array_equal(gst["z"], ost["z"], err_msg=f"{tag}: re-quantized vectors")
     np.testing.assert_array_equal(gst["sigma"], ost["sigma"], err_msg=f"{tag}: pair scales")
+    np.testing.assert_array_equal(gst["rho0"], ost["rho0"], err_msg=f"{tag}: unquantized first components")
     # int32 score accumulators of every point of every selected cluster
     nq = queries.shape[0]
     y_ref = np.empty_like(gst["y"])
@@ -641,6 +642,101 @@ def test_column_scales_can_be_set_and_removed(B, small_indexes, small_indexes_co
     b_ids, b_d = gix.search(queries, wl.k, wl.w, wl.m)
     np.testing.assert_array_equal(b_ids, p_ids)
     np.testing.assert_array_equal(b_d, p_d)
+    gix.close()
+
+
+def test_mixed_precision_small_workloads_stagewise(B, small_indexes_mixed):
+    """Mixed-precision decomposition (Sec. 4.2: the first component of the projected query and the first rows of A_c
+    and B_c stay in float): every stage bit-exact against the oracle - the codes that skip the first component, the
+    float first component of every pair's intermediate vector, the candidates - on the four small configurations,
+    through the batched path and the per-query kernel."""
+    for name, (wl, ix, corpus, queries) in small_indexes_mixed.items():
+        assert ix.first_row_A is not None and float(ix.first_row_B.abs().max()) > 0
+        _stagewise(B, wl, ix, queries)
+
+
+@pytest.mark.parametrize("r,dp,metric,dense", [(8, 16, 0, False), (24, 48, 1, False), (32, 256, 0, True), (48, 64, 2, False),
+                                               (64, 128, 1, True), (16, 1024, 0, False), (8, 512, 2, True)])
+def test_mixed_precision_rank_dimension_metric_variants(B, r, dp, metric, dense):
+    """Random factors, float first rows whose size ranges from negligible to dominant against the quantized rest,
+    non-zero codes in the positions that must not be read, ranks that pad on the matrix cores, both regimes of the pair-maxima kernel.  Stages and candidates bit-exact; also the search
+    without re-ranking."""
+    rng = np.random.default_rng(900 + r + metric)
+    n, L, nq = (4000, 6, 300) if dense else (3000, 40, 45)
+    ix = _random_index(rng, n=n, d=dp, L=L, r=r, metric=metric)
+    ix["scale_A_columns"] = (10.0 ** rng.uniform(-3, 0, size=(L, r))).astype(np.float32)
+    ix["scale_B_points"] = (10.0 ** rng.uniform(-3, 0, size=n)).astype(np.float32)
+    ix["first_row_A"] = (rng.normal(size=(L, r)) * 10.0 ** rng.uniform(-2, 2, size=(L, 1))).astype(np.float32)
+    ix["first_row_B"] = (rng.normal(size=n) * 10.0 ** rng.uniform(-2, 2, size=n)).astype(np.float32)
+    ix["first_row_A"][1, :] = 0.0
+    ix["first_row_B"][5] = 0.0
+    q = rng.normal(size=(nq, dp)).astype(np.float32)
+    q[:, 0] *= 30.0                                              # the component that would otherwise set the step size
+    q[3, 1:] = 0.0                                               # nothing but the first component
+    q[4, 0] = 0.0
+    w, m, k = min(L, 5), 60, 10
+    oix = O.OracleIndex(ix)
+    o_ids, o_d, ost = O.search(oix, q, k, w, m, stages=True)
+    assert not ost["q8"][:, 0].any() and not ost["z"][:, :, 0].any()
+    gix = B.Index(**ix)
+    g_ids, g_d, gst = gix.search_stages(q, k, w, m)
+    np.testing.assert_array_equal(gst["q8"], ost["q8"], err_msg="query codes")
+    np.testing.assert_array_equal(gst["dx"], ost["dx"], err_msg="query step sizes")
+    np.testing.assert_array_equal(gst["rho0"], ost["rho0"], err_msg="unquantized first components")
+    np.testing.assert_array_equal(gst["z"], ost["z"], err_msg="re-quantized vectors")
+    np.testing.assert_array_equal(gst["sigma"], ost["sigma"], err_msg="pair step sizes")
+    np.testing.assert_array_equal(np.sort(gst["cand_rows"].astype(np.int64), axis=1), np.sort(ost["cand_rows"], axis=1), err_msg="candidates")
+    assert_topk_equal(g_ids, g_d, o_ids, o_d, "mixed precision")
+    gix.set_exact_selection(True)
+    e_ids, e_d, est = gix.search_stages(q, k, w, m)
+    gix.set_exact_selection(False)
+    np.testing.assert_array_equal(np.sort(est["cand_rows"].astype(np.int64), axis=1), np.sort(ost["cand_rows"], axis=1), err_msg="candidates (per-query kernel)")
+    gix.set_rerank(B.RERANK_NONE)
+    n_ids, n_d = gix.search(q, k, w, k)
+    r_ids, r_d = O.search_no_rerank(oix, q, k, w)
+    np.testing.assert_array_equal(n_ids, r_ids)
+    np.testing.assert_array_equal(n_d, r_d)
+    gix.close()
+
+
+def test_first_rows_can_be_set_and_removed(B, small_indexes_mixed):
+    """lorann_set_first_rows on a loaded index, off again with NULLs, dropped together with the column step sizes,
+    and its refusals (no column step sizes, one array of two, a non-finite value)."""
+    wl, ixm, corpus, queries = small_indexes_mixed["cos_P"]
+    a = ixm.numpy()
+    cols = {k: v for k, v in a.items() if k not in ("first_row_A", "first_row_B")}
+    plain = {k: v for k, v in cols.items() if k not in ("scale_A_columns", "scale_B_points")}
+    gix = B.Index(**plain)
+    with pytest.raises(B.LorannError) as ei:
+        gix.set_first_rows(a["first_row_A"], a["first_row_B"])              # needs the column-wise step sizes
+    assert ei.value.code == B.LORANN_E_INVAL
+    gix.set_column_scales(a["scale_A_columns"], a["scale_B_points"])
+    c_ids, c_d = gix.search(queries, wl.k, wl.w, wl.m)                      # the codes read without the float rows
+    oc_ids, oc_d = O.search(O.OracleIndex(cols), queries, wl.k, wl.w, wl.m)
+    assert_topk_equal(c_ids, c_d, oc_ids, oc_d, "column-wise reading")
+    gix.set_first_rows(torch.from_numpy(a["first_row_A"]).cuda(), a["first_row_B"])      # device and host pointers
+    m_ids, m_d, mst = gix.search_stages(queries, wl.k, wl.w, wl.m)
+    om_ids, om_d, ost = O.search(O.OracleIndex(a), queries, wl.k, wl.w, wl.m, stages=True)
+    np.testing.assert_array_equal(mst["rho0"], ost["rho0"])
+    np.testing.assert_array_equal(mst["z"], ost["z"])
+    assert_topk_equal(m_ids, m_d, om_ids, om_d, "mixed-precision reading")
+    bad = a["first_row_B"].copy(); bad[7] = np.inf
+    for fa, fb in [(a["first_row_A"], None), (None, a["first_row_B"]), (a["first_row_A"], bad)]:
+        with pytest.raises(B.LorannError) as ei:
+            gix.set_first_rows(fa, fb)
+        assert ei.value.code == B.LORANN_E_INVAL
+    k_ids, k_d = gix.search(queries, wl.k, wl.w, wl.m)                      # a refused call changes nothing
+    np.testing.assert_array_equal(k_ids, m_ids)
+    gix.set_first_rows(None, None)
+    b_ids, b_d = gix.search(queries, wl.k, wl.w, wl.m)
+    np.testing.assert_array_equal(b_ids, c_ids)
+    np.testing.assert_array_equal(b_d, c_d)
+    gix.set_first_rows(a["first_row_A"], a["first_row_B"])
+    gix.set_column_scales(None, None)                                       # takes the float rows with it
+    p_ids, p_d, pst = gix.search_stages(queries, wl.k, wl.w, wl.m)
+    o_ids, o_d = O.search(O.OracleIndex(plain), queries, wl.k, wl.w, wl.m)
+    assert not pst["rho0"].any()
+    assert_topk_equal(p_ids, p_d, o_ids, o_d, "per-cluster reading")
     gix.close()
 
 
