@@ -40,10 +40,10 @@ def recall_at_k(ids, dists, gt_dists):
     return float(ok.mean())
 
 
-def kernel_models(wl, nq, touched_rows, npairs, column_scales=False):
+def kernel_models(wl, nq, touched_rows, npairs, column_scales=False, mixed=False):
     """Algorithmic work of one launch of each kernel: (bound, amount, unit-peak)."""
     d, dp, r, L, m = wl.d, wl.dp, wl.r, wl.L, wl.m
-    b_bytes = touched_rows * (r + (4 if wl.metric == 1 else 0) + (4 if column_scales else 0)) + npairs * (r + 4)
+    b_bytes = touched_rows * (r + (4 if wl.metric == 1 else 0) + (4 if column_scales else 0) + (4 if mixed else 0)) + npairs * (r + 4 + (4 if mixed else 0))
     return {
         "project_f64": ("mfma", 2.0 * nq * d * dp / 1e12, PEAK_FP64_MFMA_TFLOPS, "TFLOP/s"),
         "centroid_dissim_f64": ("mfma", 2.0 * nq * dp * L / 1e12, PEAK_FP64_MFMA_TFLOPS, "TFLOP/s"),
@@ -135,6 +135,9 @@ def main():
     ap.add_argument("--column-scales", action="store_true",
                     help="quantize every column of A_c and B_c with its own step size (Sec. 3.3 as printed) instead of "
                          "one step size per cluster (the configured format of the headline run)")
+    ap.add_argument("--mixed-precision", action="store_true",
+                    help="mixed-precision decomposition (paper Sec. 4.2): the first component of the projected query and the "
+                         "first row of every A_c and B_c stay in float (implies --column-scales; a separate mode, not the headline)")
     ap.add_argument("--lanes", type=int, default=4,
                     help="batches in flight: the timed steps are enqueued round-robin on this many lanes of the index "
                          "(lorann_search_lane), each with its own workspace and stream; 1 = one batch at a time")
@@ -177,7 +180,8 @@ def main():
     if args.random_index:
         ix = random_index(corpus, wl)
     else:
-        ix = build_index(corpus, wl, progress=lambda s: log(f"[bench]   index: {s}"), column_scales=args.column_scales)
+        ix = build_index(corpus, wl, progress=lambda s: log(f"[bench]   index: {s}"), column_scales=args.column_scales or args.mixed_precision,
+                         mixed_precision=args.mixed_precision)
     torch.cuda.synchronize()
     build_s = time.time() - t0
     log(f"[bench] index built in {build_s:.1f}s")
@@ -271,7 +275,7 @@ def main():
         touched[:] = False
         touched[np.unique(sel_all)] = True
     touched_rows = int(sizes[touched].sum())
-    models = kernel_models(wl, nq, touched_rows, nq * w, args.column_scales)
+    models = kernel_models(wl, nq, touched_rows, nq * w, args.column_scales or args.mixed_precision, args.mixed_precision)
     if args.rerank == "f16":
         bound, amount, peak, unit = models["rerank"]
         models["rerank"] = (bound, amount / 2, peak, unit)           # two bytes per gathered element
@@ -380,7 +384,7 @@ def main():
                                f"{metric_names[wl.metric]}, L={wl.L} clusters, d'={wl.dp}, r={wl.r} int8, batch {nq}, "
                                f"w={w}, m={m}, k={k}",
                    "n": wl.n, "d": wl.d, "batch": nq, "L": wl.L, "dp": wl.dp, "r": wl.r, "w": w, "m": m, "k": k,
-                   "quantization": "one step size per column of A_c and of B_c" if args.column_scales else "one step size per cluster and matrix",
+                   "quantization": "float first component of q' and first row of A_c and B_c; one step size per column of the rest" if args.mixed_precision else "one step size per column of A_c and of B_c" if args.column_scales else "one step size per cluster and matrix",
                    "rerank": {"f32": "float corpus", "f16": "half-precision copy of the corpus", "none": "no re-ranking step"}[args.rerank]},
         "recall_at_10": None if args.random_index else round(recall, 4),
         "recall_at_10_by_id": None if args.random_index else round(recall_ids, 4),

@@ -82,6 +82,7 @@ def test_every_entry_point_rejects_a_null_index(B):
              lambda: lib.lorann_set_gather_turns(None, 1),
              lambda: lib.lorann_set_rerank(None, 0),
              lambda: lib.lorann_set_column_scales(None, None, None),
+             lambda: lib.lorann_set_first_rows(None, None, None),
              lambda: lib.lorann_set_exact_selection(None, 1),
              lambda: lib.lorann_set_stream(None, None),
              lambda: lib.lorann_profile_enable(None, 1)]
