@@ -159,29 +159,41 @@ inline int gemm_pick_bm(long M, long N) {
 // rounding to float, optional bfloat16 copy.  A matrix-core tile is mostly padding at this size and its K loop a
 // chain of dependent steps; here one wavefront owns one output column n for kSmallM queries, its lanes stride over k
 // (W row and X rows are read coalesced) and the sums meet in a wavefront reduction.
-// grid = (ceil(N / 4), ceil(M / kSmallM)), block = 256.
+// MT = queries per wavefront (1 or 16: a single query does not pay for sixteen).  Four k-steps are requested
+// together, so that a wavefront waits for memory K / 256 times instead of K / 64 times; a lane still adds its
+// products in ascending k.
+// grid = (ceil(N / 4), ceil(M / MT)), block = 256.
 constexpr int kSmallM = 16, kSmallBatch = 512;
+template <int MT>
 __global__ __launch_bounds__(256) void k_project_small(const float* __restrict__ X, const float* __restrict__ W, float* __restrict__ out,
                                                        int M, int N, int K, __bf16* __restrict__ out_bf) {
     const int lane = threadIdx.x & 63;
     const int n = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (n >= N) return;                              // wavefronts are independent
-    const int m0 = blockIdx.y * kSmallM;
+    const int m0 = blockIdx.y * MT;
     X += (size_t)m0 * K; out += (size_t)m0 * N; if (out_bf) out_bf += (size_t)m0 * N;
-    M = min(M - m0, kSmallM);
-    double acc[kSmallM];
+    M = min(M - m0, MT);
+    double acc[MT];
 #pragma unroll
-    for (int m = 0; m < kSmallM; ++m) acc[m] = 0.0;
-    for (int k = lane; k < K; k += 64) {
-        const double wv = (double)W[(size_t)n * K + k];
+    for (int m = 0; m < MT; ++m) acc[m] = 0.0;
+    constexpr int KU = MT == 1 ? 4 : 1;      // sixteen queries already keep sixteen loads in flight per step
+    for (int k0 = lane; k0 < K; k0 += 64 * KU) {
+        float wv[KU], x[KU][MT];
 #pragma unroll
-        for (int m = 0; m < kSmallM; ++m) {
-            const float x = X[(size_t)min(m, M - 1) * K + k];      // rows beyond M repeat the last one (never stored)
-            acc[m] += (double)x * wv;
+        for (int u = 0; u < KU; ++u) {
+            const int k = k0 + 64 * u;
+            const bool ok = k < K;
+            wv[u] = ok ? W[(size_t)n * K + k] : 0.0f;      // beyond K: + 0 * 0, which leaves the sum as it is
+#pragma unroll
+            for (int m = 0; m < MT; ++m) x[u][m] = ok ? X[(size_t)min(m, M - 1) * K + k] : 0.0f;   // rows beyond M repeat the last one (never stored)
         }
+#pragma unroll
+        for (int u = 0; u < KU; ++u)
+#pragma unroll
+            for (int m = 0; m < MT; ++m) acc[m] += (double)x[u][m] * (double)wv[u];
     }
 #pragma unroll
-    for (int m = 0; m < kSmallM; ++m) {
+    for (int m = 0; m < MT; ++m) {
         const double s = wave_sum_f64(acc[m]);
         if (lane == 0 && m < M) {
             const float o = (float)s;

@@ -262,8 +262,10 @@ int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ
     if (ix->Pt) {
         Prof p(ix, K_PROJECT, s);
         const int pvec = (d % 4 == 0 && (reinterpret_cast<uintptr_t>(dQ) & 15u) == 0 && (reinterpret_cast<uintptr_t>(ix->Pt) & 15u) == 0) ? 1 : 0;
-        if (nq <= kSmallBatch)
-            hipLaunchKernelGGL(k_project_small, dim3((unsigned)((dp + 3) / 4), (unsigned)((nq + kSmallM - 1) / kSmallM)), dim3(256), 0, s, dQ, ix->Pt, ws.qproj.as<float>(), (int)nq, dp, d, proj_bf);
+        if (nq <= 32)      // a handful of queries: one wavefront per (query, column)
+            hipLaunchKernelGGL(k_project_small<1>, dim3((unsigned)((dp + 3) / 4), (unsigned)nq), dim3(256), 0, s, dQ, ix->Pt, ws.qproj.as<float>(), (int)nq, dp, d, proj_bf);
+        else if (nq <= kSmallBatch)
+            hipLaunchKernelGGL(k_project_small<kSmallM>, dim3((unsigned)((dp + 3) / 4), (unsigned)((nq + kSmallM - 1) / kSmallM)), dim3(256), 0, s, dQ, ix->Pt, ws.qproj.as<float>(), (int)nq, dp, d, proj_bf);
         else if (gemm_pick_bm(nq, dp) == 64)
             hipLaunchKernelGGL((k_gemm_nt_f64<EPI_PLAIN, 64>), dim3((dp + 63) / 64, (unsigned)((nq + 63) / 64)), dim3(256), 0, s, dQ, ix->Pt, ws.qproj.as<float>(), (const double*)nullptr, (int)nq, dp, d, pvec, proj_bf);
         else

@@ -944,10 +944,11 @@ def test_randomized_configurations(B, seed):
     gix.close()
 
 
-@pytest.mark.parametrize("nq", [1, 2, 15, 16, 17, 40])
+@pytest.mark.parametrize("nq", [1, 2, 15, 16, 17, 32, 33, 40])
 def test_small_batches_take_the_small_projection(B, small_indexes, nq):
-    """Batches of up to 512 queries are projected by the one-wavefront-per-output-column kernel, 16 queries per
-    wavefront (the workload has 40 queries): projected queries, codes and everything after them bit-exact."""
+    """Batches of up to 512 queries are projected by the one-wavefront-per-output-column kernel - one query per
+    wavefront up to 32 queries, 16 per wavefront beyond (the workload has 40 queries): projected queries, codes and
+    everything after them bit-exact."""
     wl, ix, corpus, queries = small_indexes["cos_P"]
     a = ix.numpy()
     q = queries[:nq]
