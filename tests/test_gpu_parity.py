@@ -888,7 +888,16 @@ def test_randomized_configurations(B, seed):
     sizes (empty clusters included), w, m, k, per-cluster or column-wise step sizes, re-rank mode, batch size - each
     compared with the oracle: selected clusters, re-quantized vectors, pair scales and candidate sets bit-exact,
     results to the usual bar."""
-    rng = np.random.default_rng(7000 + seed)
+    _randomized(B, np.random.default_rng(7000 + seed), f"seed={seed}", mixed=False)
+
+
+@pytest.mark.parametrize("seed", list(range(12)))
+def test_randomized_configurations_mixed_precision(B, seed):
+    """The same random shapes with the mixed-precision decomposition switched on (float first rows of every size)."""
+    _randomized(B, np.random.default_rng(11000 + seed), f"mixed seed={seed}", mixed=True)
+
+
+def _randomized(B, rng, tag, mixed):
     metric = int(rng.integers(0, 3))
     dp = int(rng.choice([16, 32, 48, 64, 128, 256]))
     d = dp if rng.random() < 0.3 else int(dp + rng.integers(1, 200))
@@ -921,7 +930,13 @@ def test_randomized_configurations(B, seed):
         ix["scale_B_points"] = (10.0 ** rng.uniform(-3, 0, size=n)).astype(np.float32)
     q = rng.normal(size=(nq, d)).astype(np.float32)
     mode = int(rng.choice([B.RERANK_F32, B.RERANK_F32, B.RERANK_F16, B.RERANK_NONE]))
-    what = f"seed={seed} metric={metric} d={d} dp={dp} r={r} L={L} n={n} nq={nq} w={w} m={m} k={k} cols={'scale_A_columns' in ix} mode={mode}"
+    if mixed:
+        if "scale_A_columns" not in ix:
+            ix["scale_A_columns"] = (10.0 ** rng.uniform(-3, 0, size=(L, r))).astype(np.float32)
+            ix["scale_B_points"] = (10.0 ** rng.uniform(-3, 0, size=n)).astype(np.float32)
+        ix["first_row_A"] = (rng.normal(size=(L, r)) * 10.0 ** rng.uniform(-2, 1, size=(L, 1))).astype(np.float32)
+        ix["first_row_B"] = (rng.normal(size=n) * 10.0 ** rng.uniform(-2, 1, size=n)).astype(np.float32)
+    what = f"{tag} metric={metric} d={d} dp={dp} r={r} L={L} n={n} nq={nq} w={w} m={m} k={k} cols={'scale_A_columns' in ix} mode={mode}"
     gix = B.Index(**ix)
     gix.set_rerank(mode)
     oracle_ix = O.with_half_precision_corpus(ix) if mode == B.RERANK_F16 else ix
@@ -934,7 +949,7 @@ def test_randomized_configurations(B, seed):
     else:
         o_ids, o_d, ost = O.search(oix, q, k, w, m, stages=True)
         g_ids, g_d, gst = gix.search_stages(q, k, w, m)
-        for key in ("q8", "dx", "sel", "z", "sigma"):
+        for key in ("q8", "dx", "sel", "z", "sigma", "rho0"):
             np.testing.assert_array_equal(gst[key], ost[key], err_msg=f"{key}: {what}")
         np.testing.assert_array_equal(np.sort(gst["cand_rows"].astype(np.int64), axis=1), np.sort(ost["cand_rows"], axis=1), err_msg=what)
         # k can reach most of the scored points here, so the results include inner products that cancel to almost
