@@ -37,20 +37,17 @@ __device__ __forceinline__ float4 gemm_fetch_tail(const float* __restrict__ p, i
     return v;
 }
 
-// grid = (ceil(N/64), ceil(M/BM)), block = 256 (2 x 2 wavefronts, each (BM/2) x 32 of the BM x 64 block tile).
-// BM = 64 or 32: the smaller tile is used when it fills the machine more evenly (see gemm_pick_bm).
+// One wavefront's tile: rows [m0, m0 + 16 TI), columns [n0, n0 + 32).
 // X [M][K], W [N][K] row-major, out [M][N].  nrm [N] (double) is used by EPI_L2 only: out = nrm[n] - 2 * acc.
 // vec_ok: rows of X and W are 16-byte aligned (K % 4 == 0 and aligned bases); otherwise every chunk takes the
 // guarded scalar path.
-template <int EPI, int BM>
-__global__ __launch_bounds__(256) void k_gemm_nt_f64(const float* __restrict__ X, const float* __restrict__ W,
-                                                      float* __restrict__ out, const double* __restrict__ nrm,
-                                                      int M, int N, int K, int vec_ok, __bf16* __restrict__ out_bf = nullptr) {
-    constexpr int TI = BM / 32;          // 16-row MFMA tiles per wavefront along M
-    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    const int wm = wv >> 1, wn = wv & 1;
+template <int EPI, int TI>
+__device__ __forceinline__ void gemm_wave_tile(const float* __restrict__ X, const float* __restrict__ W,
+                                               float* __restrict__ out, const double* __restrict__ nrm,
+                                               int M, int N, int K, int vec_ok, __bf16* __restrict__ out_bf,
+                                               const int m0, const int n0) {
+    const int lane = threadIdx.x & 63;
     const int i = lane & 15, g = lane >> 4;
-    const int m0 = blockIdx.y * BM + wm * (BM / 2), n0 = blockIdx.x * GM_BN + wn * 32;
 
     // rows / columns beyond the matrix are clamped (loaded, never stored)
     const float* xa[TI];
@@ -87,7 +84,9 @@ __global__ __launch_bounds__(256) void k_gemm_nt_f64(const float* __restrict__ X
 
     const int k_full = vec_ok ? (K / GM_KC) * GM_KC : 0;     // chunks fetched with unconditional float4 loads
     if (k_full > 0) {
-        float4 a_cur[TI][2], b_cur[2][2], a_nxt[TI][2], b_nxt[2][2];
+        // Three register stages: the chunk contracted now, and the next two already requested (one chunk of matrix-core
+        // work is shorter than a trip to the L2 under load, so one chunk of lead leaves the matrix cores waiting).
+        float4 a_st[3][TI][2], b_st[3][2][2];
         auto fetch = [&](int k0, float4 (&a)[TI][2], float4 (&b)[2][2]) {
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
@@ -98,17 +97,18 @@ __global__ __launch_bounds__(256) void k_gemm_nt_f64(const float* __restrict__ X
                 for (int tj = 0; tj < 2; ++tj) b[tj][h] = *reinterpret_cast<const float4*>(wb[tj] + k);
             }
         };
-        fetch(0, a_cur, b_cur);
-        for (int k0 = 0; k0 < k_full; k0 += GM_KC) {
-            // the next chunk is requested before this one is contracted (clamped: the last request is a repeat)
-            fetch(min(k0 + GM_KC, k_full - GM_KC), a_nxt, b_nxt);
-            contract(a_cur, b_cur);
+        const int k_last = k_full - GM_KC;
+        fetch(0, a_st[0], b_st[0]);
+        fetch(min(GM_KC, k_last), a_st[1], b_st[1]);
+        for (int k0 = 0; k0 < k_full; k0 += 3 * GM_KC) {
 #pragma unroll
-            for (int h = 0; h < 2; ++h) {
-#pragma unroll
-                for (int ti = 0; ti < TI; ++ti) a_cur[ti][h] = a_nxt[ti][h];
-#pragma unroll
-                for (int tj = 0; tj < 2; ++tj) b_cur[tj][h] = b_nxt[tj][h];
+            for (int st = 0; st < 3; ++st) {
+                const int kc = k0 + st * GM_KC;
+                if (kc < k_full) {                                   // uniform
+                    // (clamped: the last requests are repeats that are never contracted)
+                    fetch(min(kc + 2 * GM_KC, k_last), a_st[(st + 2) % 3], b_st[(st + 2) % 3]);
+                    contract(a_st[st], b_st[st]);
+                }
             }
         }
     }
@@ -146,13 +146,26 @@ __global__ __launch_bounds__(256) void k_gemm_nt_f64(const float* __restrict__ X
         }
 }
 
-// Tile height that loads the 256 CUs more evenly: the workgroups of this kernel are bound by the matrix cores
-// of their CU, so the time follows the largest number of workgroups any CU receives.
+// grid = (ceil(N/64), ceil(M/BM)), block = 256 (2 x 2 wavefronts, each (BM/2) x 32 of the BM x 64 block tile).
+// BM = 64 or 32: the smaller tile is used when it fills the machine more evenly (see gemm_pick_bm).
+template <int EPI, int BM>
+__global__ __launch_bounds__(256) void k_gemm_nt_f64(const float* __restrict__ X, const float* __restrict__ W,
+                                                      float* __restrict__ out, const double* __restrict__ nrm,
+                                                      int M, int N, int K, int vec_ok, __bf16* __restrict__ out_bf = nullptr) {
+    const int wv = threadIdx.x >> 6;
+    const int wm = wv >> 1, wn = wv & 1;
+    gemm_wave_tile<EPI, BM / 32>(X, W, out, nrm, M, N, K, vec_ok, out_bf, blockIdx.y * BM + wm * (BM / 2), blockIdx.x * GM_BN + wn * 32);
+}
+
+// Tile height: the workgroups of this kernel are bound by the matrix cores of their CU, so the time follows the
+// largest number of workgroups any CU receives, times the work of one, over the rate the tile shape reaches (measured:
+// the 64-row tile, with four accumulators per wavefront and half the operand traffic, keeps the fp64 matrix cores
+// 72 % busy, the 32-row tile 50 %).  The smaller tile wins only where it fills the machine much more evenly.
 inline int gemm_pick_bm(long M, long N) {
     const double t64 = (double)((M + 63) / 64) * (double)((N + 63) / 64) / 256.0;
     const double t32 = (double)((M + 31) / 32) * (double)((N + 63) / 64) / 256.0;
-    const double e64 = t64 / std::ceil(t64), e32 = t32 / std::ceil(t32);
-    return e32 > e64 + 0.05 ? 32 : 64;
+    const double time64 = std::ceil(t64) * 1.0 / 0.72, time32 = std::ceil(t32) * 0.5 / 0.50;
+    return time32 < time64 ? 32 : 64;
 }
 
 // The projection of a small batch (M <= kSmallBatch): out[m][n] = sum_k X[m][k] * W[n][k], double accumulation, one
