@@ -274,8 +274,10 @@ def test_many_clusters_routing_variants(B, L, plateau):
     gix.close()
 
 
-def test_full_size_benchmark_configuration_sampled_parity(B):
-    """The benchmark configuration at its full size (1M x 768, batch 10000, w=32, m=200, k=10) in the launch
+@pytest.mark.parametrize("scheme", ["cluster", "mixed"])
+def test_full_size_benchmark_configuration_sampled_parity(B, scheme):
+    """(scheme: the configured step sizes per cluster, or the mixed-precision decomposition on column-wise step sizes.)
+    The benchmark configuration at its full size (1M x 768, batch 10000, w=32, m=200, k=10) in the launch
     configuration bench.py times - device-resident inputs, one whole batch per call, hence the cluster-batched
     scoring, the per-query walk and the grouped re-rank - against the oracle on a sample of the batch: the
     oracle handles a query on its own, so any subset can be checked one by one.  Integer stages and candidate
@@ -284,7 +286,7 @@ def test_full_size_benchmark_configuration_sampled_parity(B):
     wl = get_workload("embed-ip")
     dev = torch.device("cuda:0")
     corpus, queries = make_dataset(wl, dev)
-    ix = build_index(corpus, wl)
+    ix = build_index(corpus, wl, mixed_precision=(scheme == "mixed"))
     del corpus
     gix = B.Index.from_arrays(ix)
     k, w, m = wl.k, wl.w, wl.m
@@ -307,9 +309,11 @@ def test_full_size_benchmark_configuration_sampled_parity(B):
     np.testing.assert_array_equal(gst["sel"][sample], ost["sel"], err_msg="selected clusters")
     np.testing.assert_array_equal(gst["z"][sample], ost["z"], err_msg="re-quantized vectors")
     np.testing.assert_array_equal(gst["sigma"][sample], ost["sigma"], err_msg="pair scales")
+    np.testing.assert_array_equal(gst["rho0"][sample], ost["rho0"], err_msg="unquantized first components")
+    assert (np.abs(ost["rho0"]).max() > 0) == (scheme == "mixed")
     np.testing.assert_array_equal(np.sort(gst["cand_rows"][sample].astype(np.int64), axis=1), np.sort(ost["cand_rows"], axis=1),
                                   err_msg="candidate sets")
-    assert_topk_equal(g_ids[sample], g_d[sample], o_ids, o_d, "embed-ip full size")
+    assert_topk_equal(g_ids[sample], g_d[sample], o_ids, o_d, f"embed-ip full size, {scheme}")
 
 
 @pytest.mark.parametrize("L,w,metric,case", [
