@@ -223,6 +223,9 @@ int next_pow2(int v) { int p = 1; while (p < v) p <<= 1; return p; }
 constexpr int kNZ = 2;                 // 32-pair tiles per scoring unit
 constexpr int kUnitPairs = 32 * kNZ;
 constexpr int kChunkTiles = 16;       // 32-point tiles per scoring work item
+constexpr int ilog2_exact(int v) { return v == 1 ? 0 : 1 + ilog2_exact(v / 2); }
+constexpr int kUnitShift = ilog2_exact(kUnitPairs), kChunkShift = ilog2_exact(32 * kChunkTiles);
+static_assert((1 << kUnitShift) == kUnitPairs && (1 << kChunkShift) == 32 * kChunkTiles, "work items are powers of two");
 
 // One batch of at most `chunk` queries, device pointers only.
 int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ, int64_t nq, int k, int w, int m, int64_t* d_ids,
@@ -357,13 +360,13 @@ int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ
     const bool fused_scan = L <= 1024;       // the scatter kernel scans the counters itself
     if (!fused_scan) {
         Prof p(ix, K_SCAN, s);
-        hipLaunchKernelGGL(k_scan_buckets, dim3((unsigned)((L + 1023) / 1024)), dim3(1024), 0, s, ws.count.as<int32_t>(), ws.count.as<int32_t>() + L, ix->off, L, kUnitPairs, 32 * kChunkTiles, ws.bucket_off.as<int32_t>(),
+        hipLaunchKernelGGL(k_scan_buckets, dim3((unsigned)((L + 1023) / 1024)), dim3(1024), 0, s, ws.count.as<int32_t>(), ws.count.as<int32_t>() + L, ix->off, L, kUnitShift, kChunkShift, ws.bucket_off.as<int32_t>(),
                            ws.tile_off.as<int32_t>(), ws.unit_off.as<int32_t>(), ws.off0.as<int32_t>());
     }
     {
         Prof p(ix, K_SCATTER, s);
         ScanArgs sc;
-        sc.count = ws.count.as<int32_t>(); sc.count0 = ws.count.as<int32_t>() + L; sc.off = ix->off; sc.unit_pairs = kUnitPairs; sc.chunk_points = 32 * kChunkTiles;
+        sc.count = ws.count.as<int32_t>(); sc.count0 = ws.count.as<int32_t>() + L; sc.off = ix->off; sc.unit_shift = kUnitShift; sc.chunk_shift = kChunkShift;
         sc.tile_off = ws.tile_off.as<int32_t>(); sc.unit_off = ws.unit_off.as<int32_t>();
         if (fused_scan)
             hipLaunchKernelGGL(k_scatter_pairs<true>, dim3((unsigned)((npairs + 255) / 256)), dim3(256), 0, s, ws.sel.as<int32_t>(), npairs, w, L, ws.bucket_off.as<int32_t>(),

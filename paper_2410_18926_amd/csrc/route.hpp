@@ -352,12 +352,13 @@ __global__ __launch_bounds__(256) void k_bucket_count_global(const int32_t* __re
 // tile_off[c]    = number of 16-pair tiles of clusters < c                 (tile_off[L]   = number of tiles)
 // unit_off[c]    = number of scoring work items of clusters < c            (unit_off[L]   = number of items);
 //                  a cluster with a pairs and m_c points has ceil(a / unit_pairs) * ceil(m_c / chunk_points) items
+//                  (both powers of two, given as shifts: two integer divisions per cluster are most of this kernel otherwise)
 // off0[c]        = number of queries whose nearest cluster is < c
 // grid = ceil(L / 1024), block = 1024: block b scans clusters [1024 b, 1024 b + 1024) and first adds up, on its
 // own, everything that precedes them (at most L - 1024 independent loads spread over its threads), so the blocks
 // need no communication and none of them waits for another.
 __global__ __launch_bounds__(1024) void k_scan_buckets(const int32_t* __restrict__ count, const int32_t* __restrict__ count0,
-                                                        const int64_t* __restrict__ off, int L, int unit_pairs, int chunk_points,
+                                                        const int64_t* __restrict__ off, int L, int unit_shift, int chunk_shift,
                                                         int32_t* __restrict__ bucket_off, int32_t* __restrict__ tile_off,
                                                         int32_t* __restrict__ unit_off, int32_t* __restrict__ off0) {
     __shared__ int wtot[4][16], wpre[4][16];
@@ -367,11 +368,11 @@ __global__ __launch_bounds__(1024) void k_scan_buckets(const int32_t* __restrict
         const int a = count[c];
         const int m_c = (int)(off[c + 1] - off[c]);
         f[0] = a; f[1] = (a + 15) >> 4;
-        f[2] = ((a + unit_pairs - 1) / unit_pairs) * ((m_c + chunk_points - 1) / chunk_points);
+        f[2] = ((a + (1 << unit_shift) - 1) >> unit_shift) * ((m_c + (1 << chunk_shift) - 1) >> chunk_shift);
         f[3] = count0[c];
     };
     int pre[4] = {0, 0, 0, 0};                      // this thread's share of the clusters before c0
-#pragma unroll 4
+#pragma unroll 8
     for (int c = tid; c < c0; c += 1024) {
         int f[4];
         fields(c, f);
@@ -418,7 +419,7 @@ __global__ __launch_bounds__(1024) void k_scan_buckets(const int32_t* __restrict
 // offset arrays of k_scan_buckets for the kernels that follow; bucket_off / off0 are then outputs.
 struct ScanArgs {
     const int32_t* count; const int32_t* count0; const int64_t* off;
-    int unit_pairs, chunk_points;
+    int unit_shift, chunk_shift;      // log2 of the pairs and of the points of a scoring work item
     int32_t* tile_off; int32_t* unit_off;
 };
 template <bool SCAN>
@@ -441,7 +442,7 @@ __global__ __launch_bounds__(256) void k_scatter_pairs(const int32_t* __restrict
             const int m_c = (int)(sc.off[c + 1] - sc.off[c]);
             f[j][0] = in ? a : 0;
             f[j][1] = in ? (a + 15) >> 4 : 0;
-            f[j][2] = in ? ((a + sc.unit_pairs - 1) / sc.unit_pairs) * ((m_c + sc.chunk_points - 1) / sc.chunk_points) : 0;
+            f[j][2] = in ? ((a + (1 << sc.unit_shift) - 1) >> sc.unit_shift) * ((m_c + (1 << sc.chunk_shift) - 1) >> sc.chunk_shift) : 0;
             f[j][3] = in ? sc.count0[c] : 0;
 #pragma unroll
             for (int k = 0; k < 4; ++k) tot[k] += f[j][k];
