@@ -157,6 +157,29 @@ __global__ __launch_bounds__(256) void k_gemm_nt_f64(const float* __restrict__ X
     gemm_wave_tile<EPI, BM / 32>(X, W, out, nrm, M, N, K, vec_ok, out_bf, blockIdx.y * BM + wm * (BM / 2), blockIdx.x * GM_BN + wn * 32);
 }
 
+// The same contraction with both tile heights in one launch: the first n64 blocks take 64-row tiles over rows
+// [0, rows64), the others 32-row tiles over the rest.  rows64 is a whole number of rounds of the 256 CUs, so the
+// efficient tall tiles load every CU equally and the remainder is spread thinly over the machine by the small ones
+// (10 000 x 256: two tall blocks per CU and one small one on 228 CUs, instead of three tall ones on some CUs and two on
+// the others).  grid = n64 + (blocks of the remainder), block = 256.
+template <int EPI>
+__global__ __launch_bounds__(256) void k_gemm_nt_f64_two_heights(const float* __restrict__ X, const float* __restrict__ W,
+                                                                  float* __restrict__ out, const double* __restrict__ nrm,
+                                                                  int M, int N, int K, int vec_ok, __bf16* __restrict__ out_bf,
+                                                                  int n64, int rows64) {
+    const int wv = threadIdx.x >> 6;
+    const int wm = wv >> 1, wn = wv & 1;
+    const int nbx = (N + GM_BN - 1) / GM_BN;
+    const int b = (int)blockIdx.x;
+    if (b < n64) {                                   // uniform over the block
+        const int by = b / nbx, bx = b - by * nbx;
+        gemm_wave_tile<EPI, 2>(X, W, out, nrm, M, N, K, vec_ok, out_bf, by * 64 + wm * 32, bx * GM_BN + wn * 32);
+    } else {
+        const int by = (b - n64) / nbx, bx = (b - n64) - by * nbx;
+        gemm_wave_tile<EPI, 1>(X, W, out, nrm, M, N, K, vec_ok, out_bf, rows64 + by * 32 + wm * 16, bx * GM_BN + wn * 32);
+    }
+}
+
 // Tile height: the workgroups of this kernel are bound by the matrix cores of their CU, so the time follows the
 // largest number of workgroups any CU receives, times the work of one, over the rate the tile shape reaches (measured:
 // the 64-row tile, with four accumulators per wavefront and half the operand traffic, keeps the fp64 matrix cores

@@ -269,10 +269,18 @@ int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ
             hipLaunchKernelGGL(k_project_small<1>, dim3((unsigned)((dp + 3) / 4), (unsigned)nq), dim3(256), 0, s, dQ, ix->Pt, ws.qproj.as<float>(), (int)nq, dp, d, proj_bf);
         else if (nq <= kSmallBatch)
             hipLaunchKernelGGL(k_project_small<kSmallM>, dim3((unsigned)((dp + 3) / 4), (unsigned)((nq + kSmallM - 1) / kSmallM)), dim3(256), 0, s, dQ, ix->Pt, ws.qproj.as<float>(), (int)nq, dp, d, proj_bf);
-        else if (gemm_pick_bm(nq, dp) == 64)
-            hipLaunchKernelGGL((k_gemm_nt_f64<EPI_PLAIN, 64>), dim3((dp + 63) / 64, (unsigned)((nq + 63) / 64)), dim3(256), 0, s, dQ, ix->Pt, ws.qproj.as<float>(), (const double*)nullptr, (int)nq, dp, d, pvec, proj_bf);
-        else
-            hipLaunchKernelGGL((k_gemm_nt_f64<EPI_PLAIN, 32>), dim3((dp + 63) / 64, (unsigned)((nq + 31) / 32)), dim3(256), 0, s, dQ, ix->Pt, ws.qproj.as<float>(), (const double*)nullptr, (int)nq, dp, d, pvec, proj_bf);
+        else {
+            // tall tiles for as many whole rounds of the 256 CUs as the batch holds, the rest by whichever height suits it
+            const int nbx = (dp + 63) / 64;
+            const int64_t round_rows = (int64_t)64 * std::max(1, 256 / nbx);
+            const int64_t rows64_full = (nq / round_rows) * round_rows, rem = nq - rows64_full;
+            const bool rem_small = rem > 0 && gemm_pick_bm(rem, dp) == 32;
+            const int64_t rows64 = rem_small ? rows64_full : nq;
+            const int n64 = (int)((rows64 + 63) / 64) * nbx;
+            const int n32 = rem_small ? (int)((rem + 31) / 32) * nbx : 0;
+            hipLaunchKernelGGL(k_gemm_nt_f64_two_heights<EPI_PLAIN>, dim3((unsigned)(n64 + n32)), dim3(256), 0, s, dQ, ix->Pt, ws.qproj.as<float>(), (const double*)nullptr,
+                               (int)nq, dp, d, pvec, proj_bf, n64, (int)rows64);
+        }
         qp = ws.qproj.as<float>();
     }
     // Routing by screening (approximate scores on the bf16 matrix cores, exact evaluation of a short list) unless
