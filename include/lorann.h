@@ -232,9 +232,14 @@ typedef struct lorann_stages {
                            /*               (-1: the query was finished by the exact per-query kernel)    */
     const int64_t *y_off;  /* [nq*w + 1]    caller-chosen offsets into y (needs sel known beforehand)     */
     int32_t *y;            /* [y_off[nq*w]] int32 score accumulators of every point of every pair, in     */
-                           /*               cluster row order: y[y_off[slot] + t] (Sec. 3.3, 4.2)         */
+                           /*               cluster row order: y[y_off[slot] + t] (Sec. 3.3, 4.2); written */
+                           /*               by the batched matrix-core scoring kernel (by the per-query   */
+                           /*               kernel when exact selection is forced)                        */
     float *rho0;           /* [nq][w]       unquantized first component of each pair's intermediate vector */
                            /*               (zeros unless lorann_set_first_rows is in force; Sec. 4.2)     */
+    float *pmax;           /* [nq][w]       highest estimated score among the points of each pair's        */
+                           /*               cluster, as the batched matrix-core scoring kernel found it    */
+                           /*               (-inf: empty cluster); untouched when exact selection is forced */
 } lorann_stages;
 
 /* lorann_search that also exports the intermediate results named in `st`.  Same arguments and errors as

@@ -69,6 +69,8 @@ typedef struct {
     int64_t *cand_rows;  /* [nq][m]       candidate rows (score desc, row asc), -1 padded */
     float *cand_scores;  /* [nq][m]       their estimated scores (0 where padded) */
     float *rho0;         /* [nq][w]       mixed precision: unquantized first component of each pair's r */
+    float *pair_best;    /* [nq][w]       highest estimated score among the points of each pair's cluster */
+                         /*               (-inf for an empty cluster)                                     */
 } oracle_dump;
 
 /* ---- Step 1 (Sec. 4.1): q' = P^T q, double accumulation over i ascending, one rounding to float. ---- */
@@ -330,6 +332,7 @@ static void search_one(const oracle_index *ix, const float *q, int32_t k, int32_
             if (dump->rho0) dump->rho0[(size_t)qi * w + j] = rho0;
         }
         oracle_pair_accumulators(z, r, ix->B + (size_t)off * r, mc, Y);
+        float best = -INFINITY;
         for (int64_t t = 0; t < mc; ++t) {
             float sq = 0.0f;   /* Sec. 3.1: the norms |c_j|^2 "can be precomputed" */
             if (ix->metric == ORACLE_L2)
@@ -338,8 +341,10 @@ static void search_one(const oracle_index *ix, const float *q, int32_t k, int32_
                         : columns ? oracle_score_columns(Y[t], sigma, ix->pt_scale_B[off + t], ix->metric, sq)
                                   : oracle_score(Y[t], sigma, ix->metric, sq);
             sc[pos].idx = off + t;
+            if (sc[pos].key > best) best = sc[pos].key;
             ++pos;
         }
+        if (dump && dump->pair_best) dump->pair_best[(size_t)qi * w + j] = best;
     }
     /* step 6: the m highest estimated scores, order (score descending, row ascending) */
     qsort(sc, (size_t)total, sizeof(keyidx), cmp_key_desc);

@@ -27,7 +27,7 @@ class _Index(C.Structure):
 
 class _Dump(C.Structure):
     _fields_ = [(name, C.c_void_p) for name in
-                ("qproj", "q8", "dx", "sel", "sel_g", "R", "z", "sigma", "cand_rows", "cand_scores", "rho0")]
+                ("qproj", "q8", "dx", "sel", "sel_g", "R", "z", "sigma", "cand_rows", "cand_scores", "rho0", "pair_best")]
 
 
 def lib():
@@ -164,7 +164,8 @@ def search(oix: OracleIndex, Q, k: int, w: int, m: int, stages: bool = False, th
                   dx=np.zeros(nq, np.float32), sel=np.zeros((nq, w), np.int32), sel_g=np.zeros((nq, w), np.float32),
                   R=np.zeros((nq, w, oix.r), np.int32), z=np.zeros((nq, w, oix.r), np.int8),
                   sigma=np.zeros((nq, w), np.float32), cand_rows=np.zeros((nq, m), np.int64),
-                  cand_scores=np.zeros((nq, m), np.float32), rho0=np.zeros((nq, w), np.float32))
+                  cand_scores=np.zeros((nq, m), np.float32), rho0=np.zeros((nq, w), np.float32),
+                  pair_best=np.zeros((nq, w), np.float32))
         dump = _Dump(*[_p(st[f[0]]) for f in _Dump._fields_])
     rc = lib().oracle_search(C.byref(oix.c), _p(Q), C.c_int64(nq), C.c_int32(k), C.c_int32(w), C.c_int32(m),
                              _p(ids), _p(dists), C.byref(dump) if dump is not None else None,

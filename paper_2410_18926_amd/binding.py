@@ -35,7 +35,7 @@ class LorannError(RuntimeError):
 
 
 class _Stages(C.Structure):
-    _fields_ = [(n, C.c_void_p) for n in ("qproj", "q8", "dx", "sel", "z", "sigma", "cand_rows", "tau", "n_survivors", "y_off", "y", "rho0")]
+    _fields_ = [(n, C.c_void_p) for n in ("qproj", "q8", "dx", "sel", "z", "sigma", "cand_rows", "tau", "n_survivors", "y_off", "y", "rho0", "pmax")]
 
 
 class _KernelTime(C.Structure):
@@ -190,6 +190,12 @@ class Index:
         asynchronous=True (device tensors only) calls lorann_search_async: the results are complete once the
         index's stream has been synchronised.  lane=i calls lorann_search_lane (enqueue only, on lane i of the
         index); the results are complete on the index's stream after lane_join(i)."""
+        if asynchronous or lane is not None:
+            # the call returns before the kernels have read the queries: a converted temporary would be released (and
+            # its memory handed out again) while a library-owned stream may still read it
+            # (host arrays are passed on as they are: the library refuses them)
+            if _is_torch(queries) and queries.is_cuda and not (queries.dtype == torch.float32 and queries.is_contiguous()):
+                raise ValueError("asynchronous / lane searches need a contiguous float32 device tensor (no copy is made)")
         qk, qptr = _prep(queries, np.float32, torch.float32 if torch else None)
         nq = int(qk.shape[0])
         if qk.ndim != 2 or int(qk.shape[1]) != self.d:
@@ -219,7 +225,8 @@ class Index:
         st = dict(qproj=np.zeros((nq, self.dp), np.float32), q8=np.zeros((nq, self.dp), np.int8),
                   dx=np.zeros(nq, np.float32), sel=np.zeros((nq, w), np.int32), z=np.zeros((nq, w, self.r), np.int8),
                   sigma=np.zeros((nq, w), np.float32), cand_rows=np.zeros((nq, m), np.int32),
-                  tau=np.zeros(nq, np.float32), n_survivors=np.zeros(nq, np.int32), rho0=np.zeros((nq, w), np.float32))
+                  tau=np.zeros(nq, np.float32), n_survivors=np.zeros(nq, np.int32), rho0=np.zeros((nq, w), np.float32),
+                  pmax=np.full((nq, w), np.nan, np.float32))
         cs = _Stages()
         for name in st:
             setattr(cs, name, st[name].ctypes.data)

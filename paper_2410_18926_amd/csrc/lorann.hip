@@ -59,11 +59,24 @@ bool is_device_ptr(const void* p) {
     return at.type == hipMemoryTypeDevice || at.type == hipMemoryTypeManaged;
 }
 
-// Device buffer that grows on demand and is freed with its owner.
+// A fixed region of device memory that buffers are carved from, one after the other (no allocation).
+struct Arena {
+    unsigned char* base = nullptr;
+    size_t cap = 0, used = 0;
+};
+
+// Device buffer that grows on demand and is freed with its owner - or, given an arena, a slice of it.
 struct DevBuf {
     void* p = nullptr;
     size_t cap = 0;
-    int reserve(size_t bytes) {
+    int reserve(size_t bytes, Arena* arena = nullptr) {
+        if (arena) {
+            const size_t at = (arena->used + 255) & ~(size_t)255;
+            arena->used = at + bytes;
+            if (arena->used > arena->cap) return LORANN_E_UNSUPPORTED;     // the caller reports the total
+            p = arena->base + at; cap = bytes;
+            return LORANN_OK;
+        }
         if (bytes <= cap) return LORANN_OK;
         if (p) { (void)hipFree(p); p = nullptr; cap = 0; }
         size_t want = bytes + bytes / 8 + 256;
@@ -83,7 +96,9 @@ struct Workspace {
     hipStream_t stream = nullptr;          // lanes >= 1: created on first use, default priority
     hipEvent_t fork = nullptr, join = nullptr;
     hipEvent_t gather_done = nullptr;      // recorded after this lane's latest re-rank gather
+    Arena* arena = nullptr;                // set: every buffer is a slice of this fixed region, nothing is allocated or freed
     void release() {
+        if (arena) return;
         DevBuf* bufs[] = {&qproj, &qbf, &q8, &dx, &gscore, &sel, &count, &rank_in_bucket, &qrank, &qorder, &qorder2, &off0, &base_tab, &bucket_off, &tile_off,
                           &unit_off, &slot_of_pos, &pos_of_slot, &Z, &sigma, &rho0, &cand, &tau, &n_kept, &fb_list, &pmax, &qkey, &u_row, &u_mask, &u_pos, &u_count, &rdist, &rcid, &rccount};
         for (DevBuf* b : bufs) b->release();
@@ -226,41 +241,122 @@ constexpr int kChunkTiles = 16;       // 32-point tiles per scoring work item
 constexpr int ilog2_exact(int v) { return v == 1 ? 0 : 1 + ilog2_exact(v / 2); }
 constexpr int kUnitShift = ilog2_exact(kUnitPairs), kChunkShift = ilog2_exact(32 * kChunkTiles);
 static_assert((1 << kUnitShift) == kUnitPairs && (1 << kChunkShift) == 32 * kChunkTiles, "work items are powers of two");
+// which shape the pair-maxima kernel takes: at most 16 pairs per cluster on average -> one wavefront streams a cluster
+inline bool pair_max_streams(int64_t npairs, int L) { return npairs <= (int64_t)16 * L; }
+
+// S7 on the int8 matrix cores: the best score of every (query, cluster) pair.  With y_off / y (verification) the
+// instantiation that also stores every accumulator is launched instead.
+void launch_pair_max(lorann_index* ix, Workspace& ws, hipStream_t s, int64_t npairs, const int64_t* y_off, int32_t* y) {
+    const int L = ix->L;
+    const bool l2 = ix->metric == LORANN_L2, mixed = ix->A_first != nullptr;
+    const int ks = ix->r_pad / 32;
+    ScoreArgs sc;
+    sc.Bp = ix->Bp; sc.Z = ws.Z.as<int8_t>(); sc.sigma = ws.sigma.as<float>(); sc.off = ix->off;
+    sc.bucket_off = ws.bucket_off.as<int32_t>(); sc.unit_off = ws.unit_off.as<int32_t>();
+    sc.sqnorm = l2 ? ix->sqnorm : nullptr; sc.pt_scale = ix->sB_pts; sc.pt_first = ix->B_first; sc.rho0 = mixed ? ws.rho0.as<float>() : nullptr; sc.pmax = ws.pmax.as<uint32_t>(); sc.L = L; sc.chunk_tiles = kChunkTiles;
+    sc.slot_of_pos = ws.slot_of_pos.as<int32_t>(); sc.y_off = y_off; sc.y = y;
+    // few pairs per cluster: the kernel streams the codes of the touched clusters, one wavefront per cluster
+    const bool stream = pair_max_streams(npairs, L);
+    const dim3 gs((unsigned)((L + 3) / 4)), gp(2048);   // persistent shape: 8192 wavefronts stride over the work items
+#define LAUNCH_PM4(KS_, L2_, COLS_, MIX_, DUMP_)                                                                      \
+    do {                                                                                                             \
+        if (stream) hipLaunchKernelGGL((k_pair_max<1, KS_, L2_, 8 / KS_, true, 4, COLS_, MIX_, DUMP_>), gs, dim3(256), 0, s, sc); \
+        else hipLaunchKernelGGL((k_pair_max<kNZ, KS_, L2_, 4, false, 4, COLS_, MIX_, DUMP_>), gp, dim3(256), 0, s, sc); \
+    } while (0)
+#define LAUNCH_PM3(KS_, L2_, DUMP_)                                                                                   \
+    do {                                                                                                             \
+        if (mixed) LAUNCH_PM4(KS_, L2_, true, true, DUMP_);                                                          \
+        else if (ix->sB_pts) LAUNCH_PM4(KS_, L2_, true, false, DUMP_);                                               \
+        else LAUNCH_PM4(KS_, L2_, false, false, DUMP_);                                                              \
+    } while (0)
+#define LAUNCH_PM(KS_, L2_) do { if (y) LAUNCH_PM3(KS_, L2_, true); else LAUNCH_PM3(KS_, L2_, false); } while (0)
+    if (ks == 1) { if (l2) LAUNCH_PM(1, true); else LAUNCH_PM(1, false); }
+    else         { if (l2) LAUNCH_PM(2, true); else LAUNCH_PM(2, false); }
+#undef LAUNCH_PM
+#undef LAUNCH_PM3
+#undef LAUNCH_PM4
+}
+
+// What one batch will run, decided before anything is enqueued.
+struct ChunkPlan {
+    bool mixed, screen, fused_quant, big_matrix, lds_hist, grouped;
+    int group_q;        // queries per re-rank group (0: rows too long to share)
+    int nbb;            // blocks of the bucket-count kernel
+    int64_t ngroups;
+};
+
+ChunkPlan plan_chunk(const lorann_index* ix, int64_t nq, int w, int m) {
+    ChunkPlan pl;
+    const int L = ix->L;
+    pl.mixed = ix->A_first != nullptr;      // Sec. 4.2: first component of q' and of every r stay in float
+    // Routing by screening (approximate scores on the bf16 matrix cores, exact evaluation of a short list) unless
+    // verification asks for the plain route or the row of values does not fit the registers of a block.
+    pl.screen = !ix->force_exact && L <= 16384;
+    // With a projection and routing by screening: the projection also writes the bfloat16 copy of q', the selection
+    // kernel also quantizes its query and clears the batch's counters - one pass over the queries less.
+    pl.fused_quant = pl.screen && ix->Pt != nullptr && !pl.mixed;
+    // an approximate-score matrix beyond the caches (256 MB) is streamed: written and read once, nothing of it is worth keeping
+    pl.big_matrix = pl.screen && L > 4096 && (int64_t)nq * L * 4 > (int64_t(256) << 20);
+    pl.lds_hist = (size_t)L * 8 <= 64 * 1024;
+    pl.nbb = (int)((nq + kBucketQueries - 1) / kBucketQueries);
+    pl.group_q = rerank_group_size(ix->d);
+    pl.grouped = ix->rerank_mode != LORANN_RERANK_NONE && m <= 512 && !ix->force_exact && pl.group_q > 0;
+    pl.ngroups = pl.grouped ? (nq + pl.group_q - 1) / pl.group_q : 0;
+    return pl;
+}
+
+// Every device buffer of one batch.  All of them are reserved here, before the first launch, so that a workspace
+// that cannot hold the batch is refused while nothing has been enqueued yet.
+int reserve_workspace(const lorann_index* ix, Workspace& ws, const ChunkPlan& pl, int64_t nq, int w, int m) {
+    const int L = ix->L, dp = ix->dp, r_pad = ix->r_pad;
+    const size_t npairs = (size_t)nq * w, q = (size_t)nq;
+    Arena* ar = ws.arena;
+    if (ar) ar->used = 0;
+    struct Want { DevBuf* b; size_t bytes; bool on; };
+    const size_t gm = (size_t)pl.group_q * m;
+    const bool no_rerank = ix->rerank_mode == LORANN_RERANK_NONE;
+    const Want wants[] = {
+        {&ws.qproj, q * dp * 4, true}, {&ws.q8, q * dp, true}, {&ws.dx, q * 4, true}, {&ws.gscore, q * L * 4, true},
+        {&ws.sel, npairs * 4, true},
+        {&ws.count, (size_t)(2 * L + 1) * 4, true},   // [L] pair counters, [L] nearest-cluster counters, fallback-list counter
+        {&ws.rank_in_bucket, npairs * 4, true}, {&ws.qrank, q * 4, true}, {&ws.qorder, q * 4, true}, {&ws.qorder2, q * 4, true},
+        {&ws.off0, (size_t)L * 4, true}, {&ws.pmax, npairs * 4, true}, {&ws.bucket_off, (size_t)(L + 1) * 4, true},
+        {&ws.tile_off, (size_t)(L + 1) * 4, true}, {&ws.unit_off, (size_t)(L + 1) * 4, true},
+        {&ws.slot_of_pos, npairs * 4, true}, {&ws.pos_of_slot, npairs * 4, true}, {&ws.Z, npairs * r_pad, true},
+        {&ws.sigma, npairs * 4, true}, {&ws.rho0, npairs * 4, pl.mixed}, {&ws.cand, q * m * 4, true},
+        {&ws.qbf, q * dp * 2, pl.screen}, {&ws.base_tab, (size_t)2 * pl.nbb * L * 4, pl.lds_hist},
+        {&ws.tau, q * 4, !ix->force_exact}, {&ws.n_kept, q * 4, !ix->force_exact}, {&ws.fb_list, q * 4, !ix->force_exact},
+        {&ws.qkey, q * 4, !ix->force_exact},
+        {&ws.u_row, (size_t)pl.ngroups * gm * 4, pl.grouped}, {&ws.u_mask, (size_t)pl.ngroups * gm * 2, pl.grouped},
+        {&ws.u_pos, (size_t)pl.ngroups * gm * pl.group_q * 2, pl.grouped}, {&ws.u_count, (size_t)pl.ngroups * 4, pl.grouped},
+        {&ws.rdist, q * m * 4, pl.grouped || no_rerank}, {&ws.rcid, q * m * 8, pl.grouped || no_rerank},
+        {&ws.rccount, q * 4, pl.grouped || no_rerank},
+    };
+    bool fits = true;
+    for (const Want& wt : wants) {
+        if (!wt.on) continue;
+        const int rc = wt.b->reserve(wt.bytes, ar);
+        if (rc == LORANN_OK) continue;
+        if (!ar) return rc;
+        fits = false;           // keep adding up: the message states the whole requirement
+    }
+    if (!fits)
+        return fail(LORANN_E_UNSUPPORTED, "this search needs %zu bytes of workspace, the fixed scratch region holds %zu (nq = %lld, w = %d, m = %d)",
+                    ar->used, ar->cap, (long long)nq, w, m);
+    return LORANN_OK;
+}
 
 // One batch of at most `chunk` queries, device pointers only.
 int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ, int64_t nq, int k, int w, int m, int64_t* d_ids,
                  float* d_dists, const lorann_stages* st, int64_t q_base, int32_t* fb_total) {
     const int L = ix->L, dp = ix->dp, d = ix->d, r_pad = ix->r_pad;
     const int64_t npairs = nq * w;
-    int rc;
-    if ((rc = ws.qproj.reserve((size_t)nq * dp * 4))) return rc;
-    if ((rc = ws.q8.reserve((size_t)nq * dp))) return rc;
-    if ((rc = ws.dx.reserve((size_t)nq * 4))) return rc;
-    if ((rc = ws.gscore.reserve((size_t)nq * L * 4))) return rc;
-    if ((rc = ws.sel.reserve((size_t)npairs * 4))) return rc;
-    if ((rc = ws.count.reserve((size_t)(2 * L + 1) * 4))) return rc;   // [L] pair counters, [L] nearest-cluster counters, fallback-list counter
-    if ((rc = ws.rank_in_bucket.reserve((size_t)npairs * 4))) return rc;
-    if ((rc = ws.qrank.reserve((size_t)nq * 4))) return rc;
-    if ((rc = ws.qorder.reserve((size_t)nq * 4))) return rc;
-    if ((rc = ws.qorder2.reserve((size_t)nq * 4))) return rc;
-    if ((rc = ws.off0.reserve((size_t)L * 4))) return rc;
-    if ((rc = ws.pmax.reserve((size_t)npairs * 4))) return rc;
-    if ((rc = ws.bucket_off.reserve((size_t)(L + 1) * 4))) return rc;
-    if ((rc = ws.tile_off.reserve((size_t)(L + 1) * 4))) return rc;
-    if ((rc = ws.unit_off.reserve((size_t)(L + 1) * 4))) return rc;
-    if ((rc = ws.slot_of_pos.reserve((size_t)npairs * 4))) return rc;
-    if ((rc = ws.pos_of_slot.reserve((size_t)npairs * 4))) return rc;
-    if ((rc = ws.Z.reserve((size_t)npairs * r_pad))) return rc;
-    if ((rc = ws.sigma.reserve((size_t)npairs * 4))) return rc;
-    const bool mixed = ix->A_first != nullptr;      // Sec. 4.2: first component of q' and of every r stay in float
-    if (mixed && (rc = ws.rho0.reserve((size_t)npairs * 4))) return rc;
-    if ((rc = ws.cand.reserve((size_t)nq * m * 4))) return rc;
+    const ChunkPlan pl = plan_chunk(ix, nq, w, m);
+    { const int rc = reserve_workspace(ix, ws, pl, nq, w, m); if (rc) return rc; }
+    const bool mixed = pl.mixed;
 
     const float* qp = dQ;   // projected queries
-    // With a projection and routing by screening: the projection also writes the bfloat16 copy of q', the selection
-    // kernel also quantizes its query and clears the batch's counters - one pass over the queries less.
-    const bool fused_quant = !ix->force_exact && L <= 16384 && ix->Pt != nullptr && !mixed;
-    if (fused_quant && (rc = ws.qbf.reserve((size_t)nq * dp * 2))) return rc;
+    const bool fused_quant = pl.fused_quant;
     __bf16* proj_bf = fused_quant ? ws.qbf.as<__bf16>() : nullptr;
     if (ix->Pt) {
         Prof p(ix, K_PROJECT, s);
@@ -283,17 +379,13 @@ int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ
         }
         qp = ws.qproj.as<float>();
     }
-    // Routing by screening (approximate scores on the bf16 matrix cores, exact evaluation of a short list) unless
-    // verification asks for the plain route or the row of values does not fit the registers of a block.
-    const bool screen = !ix->force_exact && L <= 16384;
-    if (screen && !fused_quant && (rc = ws.qbf.reserve((size_t)nq * dp * 2))) return rc;
+    const bool screen = pl.screen;
     if (!fused_quant) {
         Prof p(ix, K_QUANTIZE, s);
         hipLaunchKernelGGL(k_quantize_rows, dim3((unsigned)((nq + 3) / 4)), dim3(256), 0, s, qp, ws.q8.as<int8_t>(), ws.dx.as<float>(), (int)nq, dp,
                            ws.count.as<int32_t>(), 2 * L + 1, screen ? ws.qbf.as<__bf16>() : (__bf16*)nullptr, mixed ? 1 : 0);
     }
-    // an approximate-score matrix beyond the caches (256 MB) is streamed: written and read once, nothing of it is worth keeping
-    const bool big_matrix = screen && L > 4096 && (int64_t)nq * L * 4 > (int64_t(256) << 20);
+    const bool big_matrix = pl.big_matrix;
     if (screen) {
         {
             Prof p(ix, K_CENTROID_BF16, s);
@@ -350,9 +442,8 @@ int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ
             hipLaunchKernelGGL(k_select_clusters, dim3((unsigned)nq), dim3(256), 0, s, ws.gscore.as<float>(), L, w, ws.sel.as<int32_t>());
     }
     }
-    const bool lds_hist = (size_t)L * 8 <= 64 * 1024;
-    const int nbb = (int)((nq + kBucketQueries - 1) / kBucketQueries);
-    if (lds_hist && (rc = ws.base_tab.reserve((size_t)2 * nbb * L * 4))) return rc;
+    const bool lds_hist = pl.lds_hist;
+    const int nbb = pl.nbb;
     int32_t* base_tab = lds_hist ? ws.base_tab.as<int32_t>() : nullptr;
     int32_t* base0_tab = lds_hist ? base_tab + (size_t)nbb * L : nullptr;
     {
@@ -406,8 +497,8 @@ int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ
 #undef LAUNCH_SA
     }
     // Scores + candidate selection.  Batched path: pair maxima (MFMA) -> per-query walk over the few clusters whose maximum reaches the running m-th best score; the exact per-query kernel finishes what the batched path cannot.
-    const int kGroupQ = rerank_group_size(d);    // queries per re-rank group (0: rows too long to share)
-    const bool grouped = ix->rerank_mode != LORANN_RERANK_NONE && m <= 512 && !ix->force_exact && kGroupQ > 0;
+    const int kGroupQ = pl.group_q;
+    const bool grouped = pl.grouped;
     SelectArgs sa_;
     sa_.qlist = nullptr; sa_.qcount = nullptr; sa_.fb_total = nullptr; sa_.sel = ws.sel.as<int32_t>(); sa_.pos_of_slot = ws.pos_of_slot.as<int32_t>();
     sa_.Z = ws.Z.as<int8_t>(); sa_.sigma = ws.sigma.as<float>(); sa_.Bp = ix->Bp; sa_.off = ix->off;
@@ -418,34 +509,11 @@ int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ
         if (r_pad == 32) hipLaunchKernelGGL(k_select_exact<2>, dim3(grid), dim3(256), 0, s, sa_, (int)nq);
         else hipLaunchKernelGGL(k_select_exact<4>, dim3(grid), dim3(256), 0, s, sa_, (int)nq);
     } else {
-        if ((rc = ws.tau.reserve((size_t)nq * 4))) return rc;
-        if ((rc = ws.n_kept.reserve((size_t)nq * 4))) return rc;
-        if ((rc = ws.fb_list.reserve((size_t)nq * 4))) return rc;
-        if ((rc = ws.qkey.reserve((size_t)nq * 4))) return rc;
         const bool l2 = ix->metric == LORANN_L2;
         const int ks = r_pad / 32;
         {
             Prof p(ix, K_PAIR_MAX, s);
-            ScoreArgs sc;
-            sc.Bp = ix->Bp; sc.Z = ws.Z.as<int8_t>(); sc.sigma = ws.sigma.as<float>(); sc.off = ix->off;
-            sc.bucket_off = ws.bucket_off.as<int32_t>(); sc.unit_off = ws.unit_off.as<int32_t>();
-            sc.sqnorm = l2 ? ix->sqnorm : nullptr; sc.pt_scale = ix->sB_pts; sc.pt_first = ix->B_first; sc.rho0 = mixed ? ws.rho0.as<float>() : nullptr; sc.pmax = ws.pmax.as<uint32_t>(); sc.L = L; sc.chunk_tiles = kChunkTiles;
-            // few pairs per cluster: the kernel streams the codes of the touched clusters, one wavefront per cluster
-            const bool stream = npairs <= (int64_t)16 * L;
-#define LAUNCH_PM(KS_, L2_)                                                                                          \
-    do {                                                                                                             \
-        if (mixed) {                                                                                                 \
-            if (stream) hipLaunchKernelGGL((k_pair_max<1, KS_, L2_, 8 / KS_, true, 4, true, true>), dim3((unsigned)((L + 3) / 4)), dim3(256), 0, s, sc); \
-            else hipLaunchKernelGGL((k_pair_max<kNZ, KS_, L2_, 4, false, 4, true, true>), dim3(2048), dim3(256), 0, s, sc); \
-        } else if (ix->sB_pts) {                                                                                     \
-            if (stream) hipLaunchKernelGGL((k_pair_max<1, KS_, L2_, 8 / KS_, true, 4, true>), dim3((unsigned)((L + 3) / 4)), dim3(256), 0, s, sc); \
-            else hipLaunchKernelGGL((k_pair_max<kNZ, KS_, L2_, 4, false, 4, true>), dim3(2048), dim3(256), 0, s, sc); \
-        } else if (stream) hipLaunchKernelGGL((k_pair_max<1, KS_, L2_, 8 / KS_, true, 4>), dim3((unsigned)((L + 3) / 4)), dim3(256), 0, s, sc); \
-        else hipLaunchKernelGGL((k_pair_max<kNZ, KS_, L2_, 4, false, 4>), dim3(2048), dim3(256), 0, s, sc);   /* persistent: 8192 wavefronts stride over the work items */ \
-    } while (0)
-            if (ks == 1) { if (l2) LAUNCH_PM(1, true); else LAUNCH_PM(1, false); }
-            else         { if (l2) LAUNCH_PM(2, true); else LAUNCH_PM(2, false); }
-#undef LAUNCH_PM
+            launch_pair_max(ix, ws, s, npairs, nullptr, nullptr);
         }
         {
             Prof p(ix, K_SELECT_QUERY, s);
@@ -477,9 +545,6 @@ int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ
     const bool half_rows = ix->rerank_mode == LORANN_RERANK_F16;
     if (ix->rerank_mode == LORANN_RERANK_NONE) {
         // no re-ranking step: the candidates (m == k here) are the answer, ordered by their estimated scores
-        if ((rc = ws.rdist.reserve((size_t)nq * m * 4))) return rc;
-        if ((rc = ws.rcid.reserve((size_t)nq * m * 8))) return rc;
-        if ((rc = ws.rccount.reserve((size_t)nq * 4))) return rc;
         sa_.qlist = nullptr; sa_.qcount = nullptr; sa_.fb_total = nullptr;
         {
             Prof p(ix, K_CAND_SCORES, s);
@@ -504,15 +569,8 @@ int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ
             if (r_pad == 32) hipLaunchKernelGGL(k_finish_and_order<2>, grid, dim3(256), 0, s, sa_, fb_blocks, ws.qorder.as<int32_t>(), ws.off0.as<int32_t>(), L, (int)nq, ws.qkey.as<int32_t>(), ws.qorder2.as<int32_t>());
             else hipLaunchKernelGGL(k_finish_and_order<4>, grid, dim3(256), 0, s, sa_, fb_blocks, ws.qorder.as<int32_t>(), ws.off0.as<int32_t>(), L, (int)nq, ws.qkey.as<int32_t>(), ws.qorder2.as<int32_t>());
         }
-        const int64_t ngroups = (nq + kGroupQ - 1) / kGroupQ;
+        const int64_t ngroups = pl.ngroups;
         const size_t gm = (size_t)kGroupQ * m;
-        if ((rc = ws.u_row.reserve(ngroups * gm * 4))) return rc;
-        if ((rc = ws.u_mask.reserve(ngroups * gm * 2))) return rc;
-        if ((rc = ws.u_pos.reserve(ngroups * gm * kGroupQ * 2))) return rc;
-        if ((rc = ws.u_count.reserve((size_t)ngroups * 4))) return rc;
-        if ((rc = ws.rdist.reserve((size_t)nq * m * 4))) return rc;
-        if ((rc = ws.rcid.reserve((size_t)nq * m * 8))) return rc;
-        if ((rc = ws.rccount.reserve((size_t)nq * 4))) return rc;
         GroupArgs ga;
         ga.Q = dQ; ga.corpus = half_rows ? (const void*)ix->corpus_h : (const void*)ix->corpus; ga.ids = ix->ids; ga.cand = ws.cand.as<int32_t>(); ga.qorder = ws.qorder2.as<int32_t>();
         ga.u_row = ws.u_row.as<int32_t>(); ga.u_mask = ws.u_mask.as<uint16_t>(); ga.u_pos = ws.u_pos.as<uint16_t>(); ga.u_count = ws.u_count.as<int32_t>();
@@ -528,7 +586,7 @@ int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ
         }
         // The gathers of different lanes take turns: each alone saturates HBM, so two at once only stretch each other,
         // while the other stages of the other lanes still run beside a gather.
-        const bool turns = ix->gather_turns != 0;
+        const bool turns = ix->gather_turns != 0 && !ws.arena;      // (creating the turn's event is an allocation)
         if (turns && ix->last_gather && ix->last_gather != ws.gather_done) HIP_TRY(hipStreamWaitEvent(s, ix->last_gather, 0));
         {
             Prof p(ix, K_RERANK, s);
@@ -612,6 +670,19 @@ int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ
             if (st->z) HIP_TRY(hipMemcpy(st->z + (size_t)q_base * w * ix->r, zo.data(), zo.size(), hipMemcpyDefault));
             if (st->sigma) HIP_TRY(hipMemcpy(st->sigma + (size_t)q_base * w, so.data(), so.size() * 4, hipMemcpyDefault));
         }
+        if (st->pmax && !ix->force_exact) {   // keys in bucket order -> scores in slot order
+            std::vector<int32_t> pos(npairs);
+            std::vector<uint32_t> key(npairs);
+            HIP_TRY(hipMemcpy(pos.data(), ws.pos_of_slot.p, (size_t)npairs * 4, hipMemcpyDeviceToHost));
+            HIP_TRY(hipMemcpy(key.data(), ws.pmax.p, (size_t)npairs * 4, hipMemcpyDeviceToHost));
+            std::vector<float> best(npairs);
+            for (int64_t p = 0; p < npairs; ++p) {
+                const uint32_t kk = key[pos[p]];
+                const uint32_t bits = kk == 0u ? 0xff800000u /* no point: -inf */ : (kk & 0x80000000u) ? (kk & 0x7fffffffu) : ~kk;
+                memcpy(&best[p], &bits, 4);
+            }
+            HIP_TRY(hipMemcpy(st->pmax + (size_t)q_base * w, best.data(), best.size() * 4, hipMemcpyDefault));
+        }
         if (st->y && st->y_off) {
             // the caller's offsets may live on the host: stage the slice of this chunk on the device
             std::vector<int64_t> yo(npairs + 1);
@@ -623,7 +694,10 @@ int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ
             hipError_t e = hipMalloc((void**)&d_y, std::max<size_t>((size_t)(y1 - y0), 1) * 4);
             if (e != hipSuccess) { (void)hipFree(d_yo); return fail(LORANN_E_NOMEM, "hipMalloc for the score dump failed"); }
             (void)hipMemcpy(d_yo, yo.data(), (size_t)(npairs + 1) * 8, hipMemcpyHostToDevice);
-            if (r_pad == 32) hipLaunchKernelGGL(k_dump_pair_scores<2>, dim3((unsigned)npairs), dim3(256), 0, s, ws.sel.as<int32_t>(), ws.pos_of_slot.as<int32_t>(), ws.Z.as<int8_t>(), ix->Bp, ix->off, d_yo, d_y);
+            // batched selection: the accumulators come from the matrix-core kernel itself (its storing instantiation,
+            // same launch shape as the timed one); exact selection forced: from the point-by-point kernel
+            if (!ix->force_exact) launch_pair_max(ix, ws, s, npairs, d_yo, d_y);
+            else if (r_pad == 32) hipLaunchKernelGGL(k_dump_pair_scores<2>, dim3((unsigned)npairs), dim3(256), 0, s, ws.sel.as<int32_t>(), ws.pos_of_slot.as<int32_t>(), ws.Z.as<int8_t>(), ix->Bp, ix->off, d_yo, d_y);
             else hipLaunchKernelGGL(k_dump_pair_scores<4>, dim3((unsigned)npairs), dim3(256), 0, s, ws.sel.as<int32_t>(), ws.pos_of_slot.as<int32_t>(), ws.Z.as<int8_t>(), ix->Bp, ix->off, d_yo, d_y);
             e = hipStreamSynchronize(s);
             if (e == hipSuccess) e = hipMemcpy(st->y + y0, d_y, (size_t)(y1 - y0) * 4, hipMemcpyDefault);
@@ -1052,6 +1126,7 @@ int lorann_set_rerank(lorann_index* ix, int32_t mode) {
 
 int lorann_set_exact_selection(lorann_index* ix, int32_t on) {
     if (!ix) return fail(LORANN_E_INVAL, "index is NULL");
+    { const int rc = sync_all(ix); if (rc) return rc; }   // searches in flight keep the path they were enqueued with
     ix->force_exact = on != 0;
     return LORANN_OK;
 }

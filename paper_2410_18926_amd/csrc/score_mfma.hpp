@@ -33,6 +33,11 @@ struct ScoreArgs {
     uint32_t* pmax;              // out: [npairs] order-preserving key of the pair's best score (0 on entry)
     int L;
     int chunk_tiles;             // 32-point tiles per work item
+    // verification only (DUMP instantiations): every int32 accumulator of the matrix-core product is written to
+    // y[y_off[slot_of_pos[pair]] + point]
+    const int32_t* slot_of_pos;  // [npairs] bucket position -> slot (query * w + rank)
+    const int64_t* y_off;        // [npairs + 1] offsets of the slots into y
+    int32_t* y;
 };
 
 // Row (within the 32-row tile) of result register v for lane half h.
@@ -57,7 +62,9 @@ __device__ __forceinline__ void wave_lds_sync() {
 // STREAM = false: items as above.  STREAM = true (few pairs per cluster: the kernel is a pure stream of the
 // codes from HBM): one wavefront per cluster takes all of its points, no search for the item's cluster, deeper
 // fetch-ahead; clusters without pairs cost nothing.
-template <int NZ, int KS, bool L2, int TB, bool STREAM, int WPB, bool COLS = false, bool MIX = false>
+// DUMP = true (verification): additionally stores every accumulator, so that a test can compare the matrix-core
+// product itself, element by element, with a reference.
+template <int NZ, int KS, bool L2, int TB, bool STREAM, int WPB, bool COLS = false, bool MIX = false, bool DUMP = false>
 __global__ __launch_bounds__(64 * WPB) void k_pair_max(ScoreArgs a) {
     static_assert(!MIX || COLS, "the mixed-precision decomposition builds on the column-wise step sizes");
     constexpr bool FLT = L2 || COLS;   // float-domain epilogue
@@ -73,8 +80,8 @@ __global__ __launch_bounds__(64 * WPB) void k_pair_max(ScoreArgs a) {
     const int j = lane & 31, h = lane >> 5;
     // no block-wide barrier below: the wavefronts of a block are independent
 
-    // pairs [pb, min(pb + NP, pend)) against rows [row0, row0 + m_c)
-    auto process = [&](int pb, int pend, int64_t row0, int m_c) {
+    // pairs [pb, min(pb + NP, pend)) against rows [row0, row0 + m_c); row0 is point pt0 of its cluster
+    auto process = [&](int pb, int pend, int64_t row0, int m_c, int pt0) {
         i32x4 zreg[NZ][KS];
 #pragma unroll
         for (int z = 0; z < NZ; ++z) {
@@ -157,6 +164,17 @@ __global__ __launch_bounds__(64 * WPB) void k_pair_max(ScoreArgs a) {
                         for (int ks = 0; ks < KS; ++ks) {
                             acc_a = __builtin_amdgcn_mfma_i32_32x32x32_i8(zreg[z][ks], breg[u][ks], acc_a, 0, 0, 0);
                             acc_b = __builtin_amdgcn_mfma_i32_32x32x32_i8(zreg[z][ks], breg[u + 1][ks], acc_b, 0, 0, 0);
+                        }
+                        if (DUMP) {
+#pragma unroll
+                            for (int v = 0; v < 16; ++v) {
+                                const int gp = pb + 32 * z + tile_row(v, h);
+                                if (gp < pend) {
+                                    const int64_t yo = a.y_off[a.slot_of_pos[gp]] + pt0;
+                                    if (ok_a) a.y[yo + 32 * t + j] = acc_a[v];
+                                    if (ok_b) a.y[yo + 32 * (t + 1) + j] = acc_b[v];
+                                }
+                            }
                         }
                         if (!FLT) {
                             if (full) {
@@ -254,7 +272,7 @@ __global__ __launch_bounds__(64 * WPB) void k_pair_max(ScoreArgs a) {
             if (pbeg == pend) continue;
             const int64_t row_c = a.off[c];
             const int m_all = (int)(a.off[c + 1] - row_c);
-            for (int pb = pbeg; pb < pend; pb += NP) process(pb, pend, row_c, m_all);
+            for (int pb = pbeg; pb < pend; pb += NP) process(pb, pend, row_c, m_all, 0);
         }
     } else {
         const int n_items = a.unit_off[a.L];
@@ -269,7 +287,7 @@ __global__ __launch_bounds__(64 * WPB) void k_pair_max(ScoreArgs a) {
             // so the chunk's codes are fetched from L2 once per block
             const int pk = local / n_groups, ug = local - pk * n_groups;
             process(pbeg + ug * NP, pend, row_c + (int64_t)pk * 32 * a.chunk_tiles,
-                    min(32 * a.chunk_tiles, m_all - pk * 32 * a.chunk_tiles));
+                    min(32 * a.chunk_tiles, m_all - pk * 32 * a.chunk_tiles), pk * 32 * a.chunk_tiles);
         }
     }
 }

@@ -1,5 +1,5 @@
-// Per-query candidate selection of the batched scoring path (Sec. 2.2: "the t highest scoring points are
-// selected into the candidate set"; t is called m here).
+// Per-query candidate selection of the batched scoring path (the candidate-selection step of Sec. 2.2; the
+// paper's candidate count t is called m here).
 //
 // k_pair_max has already computed, for every (query, cluster) pair, the best score of the cluster.  One block
 // per query now walks the query's pairs in descending order of that best score and keeps a running threshold T =

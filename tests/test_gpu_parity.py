@@ -9,7 +9,7 @@ import pytest
 import torch
 
 from oracle import oracle as O
-from tests.parity_util import assert_topk_equal, y_offsets
+from tests.parity_util import assert_topk_equal, oracle_distance_of, rounding_abs_tol, y_offsets
 
 pytestmark = pytest.mark.gpu
 
@@ -48,15 +48,20 @@ def _stagewise(B, wl, ix, queries, k=None, w=None, m=None, device_inputs=True):
         c = int(ost["sel"][qi, j])
         o0, o1 = int(a["cluster_offsets"][c]), int(a["cluster_offsets"][c + 1])
         y_ref[yo[s]:yo[s + 1]] = O.pair_accumulators(ost["z"][qi, j], a["B"][o0:o1])
-    np.testing.assert_array_equal(gst["y"], y_ref, err_msg=f"{tag}: int32 score accumulators")
+    np.testing.assert_array_equal(gst["y"], y_ref, err_msg=f"{tag}: int32 score accumulators (matrix-core kernel)")
+    # best estimated score of every pair, as the batched matrix-core kernel found it (it only prunes, so a wrong
+    # value would not show in the candidates): equal to the maximum of the oracle's step-5 scores
+    np.testing.assert_array_equal(gst["pmax"], ost["pair_best"], err_msg=f"{tag}: per-pair best scores")
     # candidate sets (the library returns them unordered)
     np.testing.assert_array_equal(np.sort(gst["cand_rows"].astype(np.int64), axis=1), np.sort(ost["cand_rows"], axis=1),
                                   err_msg=f"{tag}: candidate sets")
-    n_tie = assert_topk_equal(g_ids, g_d, o_ids, o_d, tag)
+    n_tie = assert_topk_equal(g_ids, g_d, o_ids, o_d, tag, abs_tol=rounding_abs_tol(queries, a["corpus"], a["metric"]),
+                              exact=oracle_distance_of(a, queries))
     # the exact per-query selection kernel (the fallback of the batched path) must give the same candidates
     gix.set_exact_selection(True)
-    e_ids, e_d, est = gix.search_stages(q_in, k, w, m)
+    e_ids, e_d, est = gix.search_stages(q_in, k, w, m, y_off=yo)
     gix.set_exact_selection(False)
+    np.testing.assert_array_equal(est["y"], y_ref, err_msg=f"{tag}: int32 score accumulators (per-query kernel)")
     np.testing.assert_array_equal(np.sort(est["cand_rows"].astype(np.int64), axis=1), np.sort(ost["cand_rows"], axis=1),
                                   err_msg=f"{tag}: candidate sets (per-query kernel)")
     np.testing.assert_array_equal(e_ids, g_ids)
@@ -105,6 +110,56 @@ def test_rank_and_dimension_variants(B, r, dp, d):
     corpus, queries = make_dataset(wl)
     ix = build_index(corpus, wl)
     _stagewise(B, wl, ix, queries.numpy())
+
+
+@pytest.mark.parametrize("metric", [0, 1, 2])
+@pytest.mark.parametrize("r", [32, 48])
+@pytest.mark.parametrize("dense", [False, True])
+def test_matrix_core_scores_per_pair_maxima_and_accumulators(B, metric, r, dense):
+    """The second 8-bit product on the matrix cores, compared directly: every int32 accumulator it forms and the best
+    score it reports for every (query, cluster) pair, bit for bit against the oracle's step 5 - in both launch shapes
+    (dense: work items of 64 pairs x 512 points on a persistent grid; else one wavefront streams a cluster), with one
+    and two k-steps (r = 32, 48), for the three metrics, on cluster sizes that end inside the first 32-point tile of
+    a pair of tiles, inside the second, and on a boundary, with empty clusters, and with scores that are all
+    negative (so that anything read beyond a cluster's end - zeros - would win the maximum)."""
+    rng = np.random.default_rng(40 + 7 * metric + r + (1 if dense else 0))
+    sizes = [1, 31, 32, 33, 63, 64, 65, 95, 96, 97, 0, 700, 1024, 1025, 1056, 1057, 0, 130]
+    L, d = len(sizes), 32
+    n = sum(sizes)
+    ix = _random_index(rng, n=n, d=d, L=L, r=r, metric=metric)
+    off = np.zeros(L + 1, np.int64)
+    np.cumsum(sizes, out=off[1:])
+    ix["cluster_offsets"] = off
+    nq = 400 if dense else 12
+    w, m, k = L, 50, 5
+    q = rng.normal(size=(nq, d)).astype(np.float32)
+    for variant in ("random", "negative"):
+        if variant == "negative":
+            # Euclidean only: large row norms make every score negative (for inner products the clusters of one
+            # point already give negative maxima about half of the time)
+            if metric != 1:
+                continue
+            ix = dict(ix)
+            ix["corpus"] = (ix["corpus"] * 50.0).astype(np.float32)
+        oix = O.OracleIndex(ix)
+        o_ids, o_d, ost = O.search(oix, q, k, w, m, stages=True)
+        yo = y_offsets(ost["sel"], off)
+        gix = B.Index(**ix)
+        g_ids, g_d, gst = gix.search_stages(q, k, w, m, y_off=yo)
+        gix.close()
+        np.testing.assert_array_equal(gst["sel"], ost["sel"])
+        np.testing.assert_array_equal(gst["z"], ost["z"])
+        y_ref = np.empty_like(gst["y"])
+        for s_ in range(nq * w):
+            qi, j = divmod(s_, w)
+            c = int(ost["sel"][qi, j])
+            y_ref[yo[s_]:yo[s_ + 1]] = O.pair_accumulators(ost["z"][qi, j], ix["B"][off[c]:off[c + 1]])
+        np.testing.assert_array_equal(gst["y"], y_ref, err_msg=f"{variant}: int32 accumulators of the matrix-core kernel")
+        np.testing.assert_array_equal(gst["pmax"], ost["pair_best"], err_msg=f"{variant}: per-pair best scores")
+        assert np.isneginf(ost["pair_best"]).any()          # the empty clusters
+        if variant == "negative":
+            assert (ost["pair_best"][np.isfinite(ost["pair_best"])] < 0).all()
+        np.testing.assert_array_equal(np.sort(gst["cand_rows"].astype(np.int64), axis=1), np.sort(ost["cand_rows"], axis=1))
 
 
 def test_probe_everything_equals_exact_knn(B, small_indexes):
@@ -310,10 +365,11 @@ def test_full_size_benchmark_configuration_sampled_parity(B, scheme):
     np.testing.assert_array_equal(gst["z"][sample], ost["z"], err_msg="re-quantized vectors")
     np.testing.assert_array_equal(gst["sigma"][sample], ost["sigma"], err_msg="pair scales")
     np.testing.assert_array_equal(gst["rho0"][sample], ost["rho0"], err_msg="unquantized first components")
+    np.testing.assert_array_equal(gst["pmax"][sample], ost["pair_best"], err_msg="per-pair best scores (matrix-core kernel)")
     assert (np.abs(ost["rho0"]).max() > 0) == (scheme == "mixed")
     np.testing.assert_array_equal(np.sort(gst["cand_rows"][sample].astype(np.int64), axis=1), np.sort(ost["cand_rows"], axis=1),
                                   err_msg="candidate sets")
-    assert_topk_equal(g_ids[sample], g_d[sample], o_ids, o_d, f"embed-ip full size, {scheme}")
+    assert_topk_equal(g_ids[sample], g_d[sample], o_ids, o_d, f"embed-ip full size, {scheme}", exact=oracle_distance_of(a, qh))
 
 
 @pytest.mark.parametrize("L,w,metric,case", [
@@ -607,8 +663,9 @@ def test_column_scales_rank_dimension_metric_variants(B, r, dp, metric, dense):
     g_ids, g_d, gst = gix.search_stages(q, k, w, m)
     np.testing.assert_array_equal(gst["z"], ost["z"], err_msg="re-quantized vectors")
     np.testing.assert_array_equal(gst["sigma"], ost["sigma"], err_msg="pair step sizes")
+    np.testing.assert_array_equal(gst["pmax"], ost["pair_best"], err_msg="per-pair best scores (matrix-core kernel)")
     np.testing.assert_array_equal(np.sort(gst["cand_rows"].astype(np.int64), axis=1), np.sort(ost["cand_rows"], axis=1), err_msg="candidates")
-    assert_topk_equal(g_ids, g_d, o_ids, o_d, "column scales")
+    assert_topk_equal(g_ids, g_d, o_ids, o_d, "column scales", abs_tol=rounding_abs_tol(q, ix["corpus"], metric), exact=oracle_distance_of(ix, q))
     gix.set_exact_selection(True)
     e_ids, e_d, est = gix.search_stages(q, k, w, m)
     gix.set_exact_selection(False)
@@ -689,8 +746,9 @@ def test_mixed_precision_rank_dimension_metric_variants(B, r, dp, metric, dense)
     np.testing.assert_array_equal(gst["rho0"], ost["rho0"], err_msg="unquantized first components")
     np.testing.assert_array_equal(gst["z"], ost["z"], err_msg="re-quantized vectors")
     np.testing.assert_array_equal(gst["sigma"], ost["sigma"], err_msg="pair step sizes")
+    np.testing.assert_array_equal(gst["pmax"], ost["pair_best"], err_msg="per-pair best scores (matrix-core kernel)")
     np.testing.assert_array_equal(np.sort(gst["cand_rows"].astype(np.int64), axis=1), np.sort(ost["cand_rows"], axis=1), err_msg="candidates")
-    assert_topk_equal(g_ids, g_d, o_ids, o_d, "mixed precision")
+    assert_topk_equal(g_ids, g_d, o_ids, o_d, "mixed precision", abs_tol=rounding_abs_tol(q, ix["corpus"], metric), exact=oracle_distance_of(ix, q))
     gix.set_exact_selection(True)
     e_ids, e_d, est = gix.search_stages(q, k, w, m)
     gix.set_exact_selection(False)
@@ -956,10 +1014,13 @@ def _randomized(B, rng, tag, mixed):
         for key in ("q8", "dx", "sel", "z", "sigma", "rho0"):
             np.testing.assert_array_equal(gst[key], ost[key], err_msg=f"{key}: {what}")
         np.testing.assert_array_equal(np.sort(gst["cand_rows"].astype(np.int64), axis=1), np.sort(ost["cand_rows"], axis=1), err_msg=what)
+        if "pmax" in gst:
+            np.testing.assert_array_equal(gst["pmax"], ost["pair_best"], err_msg=f"per-pair best scores: {what}")
         # k can reach most of the scored points here, so the results include inner products that cancel to almost
-        # nothing: their float rounding is measured against 5 % of |q| |x|, not against their own size
-        floor = 0.05 * float(np.linalg.norm(q, axis=1).max() * np.linalg.norm(ix["corpus"], axis=1).max()) if metric == 0 else 0.05
-        assert_topk_equal(g_ids, g_d, o_ids, o_d, what, floor=max(floor, 1e-3))
+        # nothing: those carry the float rounding of their terms (bound d 2^-24 |q| |x|) whatever their own size
+        rr = oracle_ix.get("rerank_corpus")
+        assert_topk_equal(g_ids, g_d, o_ids, o_d, what, abs_tol=rounding_abs_tol(q, ix["corpus"], metric),
+                          exact=oracle_distance_of(ix, q, rerank_corpus=rr))
     gix.close()
 
 
@@ -992,6 +1053,6 @@ def test_batches_beyond_the_small_projection_use_the_matrix_cores(B, nq, d, dp):
     g_ids, g_d, gst = gix.search_stages(q, 5, 4, 30)
     for key in ("qproj", "q8", "dx", "sel", "z", "sigma"):
         np.testing.assert_array_equal(gst[key], ost[key], err_msg=key)
-    floor = 0.05 * float(np.linalg.norm(q, axis=1).max() * np.linalg.norm(ix["corpus"], axis=1).max()) if ix["metric"] == 0 else 0.05
-    assert_topk_equal(g_ids, g_d, o_ids, o_d, f"nq={nq}", floor=max(floor, 1e-3))
+    assert_topk_equal(g_ids, g_d, o_ids, o_d, f"nq={nq}", abs_tol=rounding_abs_tol(q, ix["corpus"], ix["metric"]),
+                      exact=oracle_distance_of(ix, q))
     gix.close()

@@ -613,7 +613,10 @@ def test_candidate_set_and_rerank_follow_the_template(small_indexes):
                     s = (Y.astype(np.float64) * float(sg)).astype(np.float32)
                 rows.append(np.arange(o0, o1))
                 scores.append(s)
+                # the exported best score of the pair is the largest of these (-inf for an empty cluster)
+                assert st["pair_best"][qi, j] == (s.max() if s.size else -np.inf), name
             rows, scores = np.concatenate(rows), np.concatenate(scores)
+            assert st["cand_scores"][qi, 0] == st["pair_best"][qi].max()
             order = np.lexsort((rows, -scores.astype(np.float64)))[:wl.m]
             nc = len(order)
             np.testing.assert_array_equal(st["cand_rows"][qi, :nc], rows[order], err_msg=name)
