@@ -134,6 +134,26 @@ int lorann_search_async(lorann_index *ix, const float *queries, int64_t nq, int3
 int lorann_search_lane(lorann_index *ix, int32_t lane, const float *queries, int64_t nq, int32_t k, int32_t w, int32_t m,
                        int64_t *out_ids, float *out_dists);
 
+/*
+ * lorann_search_noalloc - lorann_search_async for callers that cannot allocate: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, results and ordering as lorann_search_async (device
+ * pointers only; enqueues on the index's stream and returns), but the call allocates nothing - no device memory, no
+ * events, no streams: every intermediate buffer of the search (projected queries, codes, approximate centroid scores,
+ * the counting-sort tables, the pairs' vectors and scales, candidate lists, the row unions and distances of the
+ * re-rank) is a slice of ONE fixed region of LORANN_NOALLOC_SCRATCH_BYTES that is part of the library's device code;
+ * each GPU the library runs on holds that region until the process ends.
+ *   - A search whose buffers do not fit is refused with LORANN_E_UNSUPPORTED before anything is enqueued; the message
+ *     states the bytes needed.  (The need grows with nq * (L + w * (r + 24) + m * (8 * 2 + 22)) roughly: 32 MiB hold
+ *     about 2000 queries at L = 1024, w = 32, m = 200, or 256 queries at L = 16384, w = 64, m = 200.)
+ *   - All indexes on a GPU share the region and it keeps the previous call's contents; the kernels clear what
+ *     must start at zero.  Calls that overlap on one GPU (other streams, other indexes, other threads) race: run
+ *     them one after the other on one stream, and not beside lorann_search_lane traffic that has not been joined.
+ *   - Not available while profiling is enabled (LORANN_E_INVAL).  The current device must be the index's.
+ */
+#define LORANN_NOALLOC_SCRATCH_BYTES (32u << 20)
+int lorann_search_noalloc(lorann_index *ix, const float *queries, int64_t nq, int32_t k, int32_t w, int32_t m,
+                          int64_t *out_ids, float *out_dists);
+
 /* Make the index's stream wait (on the device; the host does not block) for everything enqueued so far on `lane`.
  * After it, work enqueued on the index's stream - or a synchronisation of that stream - sees the lane's results. */
 int lorann_lane_join(lorann_index *ix, int32_t lane);

@@ -23,7 +23,8 @@ LORANN_OK, LORANN_E_INVAL, LORANN_E_NOMEM, LORANN_E_DEVICE, LORANN_E_UNSUPPORTED
 
 EXPORTS = ["lorann_load_index", "lorann_load_index_file", "lorann_search", "lorann_search_async", "lorann_free_index", "lorann_last_error", "lorann_set_stream",
            "lorann_search_stages", "lorann_profile_enable", "lorann_profile_get", "lorann_set_exact_selection",
-           "lorann_profile_fallback_queries", "lorann_set_rerank", "lorann_set_column_scales", "lorann_set_first_rows", "lorann_search_lane", "lorann_lane_join", "lorann_set_gather_turns"]
+           "lorann_profile_fallback_queries", "lorann_set_rerank", "lorann_set_column_scales", "lorann_set_first_rows", "lorann_search_lane", "lorann_lane_join", "lorann_set_gather_turns", "lorann_search_noalloc"]
+NOALLOC_SCRATCH_BYTES = 32 << 20
 LANES = 4
 RERANK_F32, RERANK_F16, RERANK_NONE = 0, 1, 2
 
@@ -59,6 +60,8 @@ def lib() -> C.CDLL:
         L.lorann_search.argtypes = [vp, vp, i64, i32, i32, i32, vp, vp]
         L.lorann_search_async.restype = C.c_int
         L.lorann_search_async.argtypes = [vp, vp, i64, i32, i32, i32, vp, vp]
+        L.lorann_search_noalloc.restype = C.c_int
+        L.lorann_search_noalloc.argtypes = [vp, vp, i64, i32, i32, i32, vp, vp]
         L.lorann_search_stages.restype = C.c_int
         L.lorann_search_stages.argtypes = [vp, vp, i64, i32, i32, i32, vp, vp, C.POINTER(_Stages)]
         L.lorann_load_index_file.restype = C.c_int
@@ -209,6 +212,17 @@ class Index:
             _check(lib().lorann_search_lane(self._h, int(lane), qptr, nq, k, w, m, ip, dptr))
         else:
             _check((lib().lorann_search_async if asynchronous else lib().lorann_search)(self._h, qptr, nq, k, w, m, ip, dptr))
+        return ids, dists
+
+    def search_noalloc(self, queries, k: int, w: int, m: int, out):
+        """lorann_search_noalloc: enqueue only, nothing is allocated (not here either: the caller passes contiguous
+        float32 device queries and the two output tensors)."""
+        ids, dists = out
+        if not (_is_torch(queries) and queries.is_cuda and queries.dtype == torch.float32 and queries.is_contiguous()):
+            raise ValueError("search_noalloc needs a contiguous float32 device tensor")
+        if queries.ndim != 2 or int(queries.shape[1]) != self.d:
+            raise ValueError(f"queries must be [nq, {self.d}]")
+        _check(lib().lorann_search_noalloc(self._h, queries.data_ptr(), int(queries.shape[0]), k, w, m, ids.data_ptr(), dists.data_ptr()))
         return ids, dists
 
     def set_gather_turns(self, on: bool):

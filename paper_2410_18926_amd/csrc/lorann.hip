@@ -27,6 +27,12 @@
 
 using namespace lorann;
 
+// Workspace of lorann_search_noalloc: one fixed region per GPU, part of the loaded code object (every GPU the
+// library runs on holds it until the process ends).  In host code this name is only a stand-in for the symbol:
+// the device address comes from hipGetSymbolAddress (scratch_of_device below) and only that pointer is ever
+// passed to kernels.
+static __device__ __align__(256) unsigned char scratch[LORANN_NOALLOC_SCRATCH_BYTES];
+
 namespace {
 
 thread_local std::string g_err;
@@ -117,6 +123,25 @@ const char* const kKernelNames[K_COUNT] = {"project_f64", "quantize_rows", "cent
 
 struct EventPair { hipEvent_t a, b; int kid; };
 
+// Device address of `scratch` on each GPU (every GPU holds its own copy at its own address), looked up once per
+// device with that device current.
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {nullptr};
+
+int scratch_of_device(int dev, void** out) {
+    if (dev < 0 || dev >= kMaxDevices) return fail(LORANN_E_UNSUPPORTED, "device %d is beyond the %d devices the library keeps a scratch pointer for", dev, kMaxDevices);
+    if (!g_scratch_ptr[dev]) {
+        int cur = -1;
+        HIP_TRY(hipGetDevice(&cur));
+        if (cur != dev) return fail(LORANN_E_INVAL, "device %d must be current to look up its scratch region (current: %d)", dev, cur);
+        void* ptr = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return LORANN_OK;
+}
+
 }  // namespace
 
 struct lorann_index {
@@ -148,6 +173,9 @@ struct lorann_index {
     // One workspace per lane.  Lane 0 runs on `stream` (lorann_search, lorann_search_async, lorann_search_stages);
     // the other lanes run on streams of their own, so that batches on different lanes overlap on the GPU.
     Workspace ws[LORANN_LANES];
+    int device = 0;                 // the GPU that holds the index
+    Workspace ws_fixed;             // lorann_search_noalloc: buffers carved from that GPU's fixed scratch region
+    Arena fixed_arena;
     hipEvent_t last_gather = nullptr;   // gather_done of the lane that enqueued the latest gather (owned by that lane)
     int32_t gather_turns = 1;       // the re-rank gathers of different lanes run one after the other
     int32_t force_exact = 0;        // 1: score + select with the per-query kernel only (verification)
@@ -730,9 +758,12 @@ int sync_all(lorann_index* ix) {
     return LORANN_OK;
 }
 
+// fixed = the non-allocating variant: lane 0's stream, buffers from the GPU's fixed scratch region, no allocation of
+// any kind (device memory, events, streams) and no host wait.
 int search_impl(lorann_index* ix, const float* queries, int64_t nq, int32_t k, int32_t w, int32_t m, int64_t* out_ids,
-                float* out_dists, const lorann_stages* st, bool async = false, int lane = 0) {
+                float* out_dists, const lorann_stages* st, bool async = false, int lane = 0, bool fixed = false) {
     if (!ix) return fail(LORANN_E_INVAL, "index is NULL");
+    if (fixed && ix->prof_on) return fail(LORANN_E_INVAL, "lorann_search_noalloc cannot run while profiling is enabled (profiling creates events)");
     if (lane < 0 || lane >= LORANN_LANES) return fail(LORANN_E_INVAL, "lane = %d is outside 0..%d", lane, LORANN_LANES - 1);
     if (nq < 0) return fail(LORANN_E_INVAL, "nq = %lld is negative", (long long)nq);
     if (ix->rerank_mode == LORANN_RERANK_NONE && k >= 1 && m >= k) m = k;    // the candidates are the answer
@@ -756,9 +787,17 @@ int search_impl(lorann_index* ix, const float* queries, int64_t nq, int32_t k, i
     const bool q_dev = is_device_ptr(queries), i_dev = is_device_ptr(out_ids), d_dev = is_device_ptr(out_dists);
     if (async && !(q_dev && i_dev && d_dev)) return fail(LORANN_E_INVAL, "lorann_search_async / lorann_search_lane need device pointers");
     if (async && ix->prof_on && (rc0 = ix->fb_total.reserve(4))) return rc0;
-    Workspace& ws = ix->ws[lane];
+    Workspace& ws = fixed ? ix->ws_fixed : ix->ws[lane];
     hipStream_t stream = nullptr;
     if ((rc0 = lane_stream(ix, lane, &stream))) return rc0;
+    if (fixed) {     // refuse before anything is enqueued if one of the chunks does not fit the scratch region
+        int cur = -1;
+        HIP_TRY(hipGetDevice(&cur));
+        if (cur != ix->device) return fail(LORANN_E_INVAL, "the index lives on device %d, the current device is %d", ix->device, cur);
+        const int64_t cn = std::min(chunk, nq);
+        const ChunkPlan pl = plan_chunk(ix, cn, w, m);
+        if ((rc0 = reserve_workspace(ix, ws, pl, cn, w, m))) return rc0;
+    }
     if (lane > 0) {     // the lane starts after what the index's stream holds now (the caller's queries)
         HIP_TRY(hipEventRecord(ws.fork, ix->stream));
         HIP_TRY(hipStreamWaitEvent(stream, ws.fork, 0));
@@ -859,6 +898,16 @@ int lorann_load_index(lorann_index** out, int32_t metric, int64_t n, int32_t d, 
 
     lorann_index* ix = new (std::nothrow) lorann_index();
     if (!ix) return fail(LORANN_E_NOMEM, "out of host memory");
+    {   // set-up of the non-allocating entry point: this GPU's address of the fixed scratch region
+        void* sp = nullptr;
+        int rcs = LORANN_OK;
+        if (hipGetDevice(&ix->device) != hipSuccess) { (void)hipGetLastError(); rcs = fail(LORANN_E_DEVICE, "hipGetDevice failed"); }
+        else rcs = scratch_of_device(ix->device, &sp);
+        if (rcs != LORANN_OK) { delete ix; return rcs; }
+        ix->fixed_arena.base = static_cast<unsigned char*>(sp);
+        ix->fixed_arena.cap = LORANN_NOALLOC_SCRATCH_BYTES;
+        ix->ws_fixed.arena = &ix->fixed_arena;
+    }
     ix->metric = metric; ix->n = n; ix->d = d; ix->dp = dp; ix->r = r; ix->L = L;
     ix->r_pad = r <= 32 ? 32 : 64;
     int rc = LORANN_OK;
@@ -1015,6 +1064,11 @@ int lorann_search_async(lorann_index* ix, const float* queries, int64_t nq, int3
 int lorann_search_lane(lorann_index* ix, int32_t lane, const float* queries, int64_t nq, int32_t k, int32_t w, int32_t m,
                        int64_t* out_ids, float* out_dists) {
     return search_impl(ix, queries, nq, k, w, m, out_ids, out_dists, nullptr, true, lane);
+}
+
+int lorann_search_noalloc(lorann_index* ix, const float* queries, int64_t nq, int32_t k, int32_t w, int32_t m,
+                          int64_t* out_ids, float* out_dists) {
+    return search_impl(ix, queries, nq, k, w, m, out_ids, out_dists, nullptr, true, 0, true);
 }
 
 int lorann_lane_join(lorann_index* ix, int32_t lane) {
