@@ -29,11 +29,14 @@ def oracle_distance_of(index_arrays, queries, rerank_corpus=None):
     judging a returned id that the oracle's own list does not contain."""
     corpus = np.asarray(index_arrays["corpus"] if rerank_corpus is None else rerank_corpus, np.float32)
     ids = index_arrays.get("ids")
-    row_of = None if ids is None else {int(v): i for i, v in enumerate(np.asarray(ids))}
     metric = int(index_arrays["metric"])
+    row_of = {}
 
     def f(qi, pid):
-        row = int(pid) if row_of is None else row_of[int(pid)]
+        if ids is not None and not row_of:        # built on first use: most comparisons never ask
+            inv = np.argsort(np.asarray(ids), kind="stable")
+            row_of["sorted"], row_of["rows"] = np.asarray(ids)[inv], inv
+        row = int(pid) if ids is None else int(row_of["rows"][np.searchsorted(row_of["sorted"], int(pid))])
         return float(O.exact_dissim(queries[qi], corpus[row], metric))
     return f
 

@@ -329,47 +329,82 @@ def test_many_clusters_routing_variants(B, L, plateau):
     gix.close()
 
 
-@pytest.mark.parametrize("scheme", ["cluster", "mixed"])
-def test_full_size_benchmark_configuration_sampled_parity(B, scheme):
+def _sampled_full_size_parity(B, gix, a, queries, k, w, m, n_sample, tag, mixed=False):
+    """One whole batch through lorann_search_stages and through the entry point the benchmark calls, then the oracle
+    on a sample of the batch (it handles a query on its own, so any subset can be checked one by one): integer stages,
+    per-pair best scores of the matrix-core kernel and candidate sets bit-exact, distances and ids to the usual bars."""
+    g_ids, g_d, gst = gix.search_stages(queries, k, w, m)
+    p_ids, p_d = gix.search(queries, k, w, m)
+    np.testing.assert_array_equal(p_ids.cpu().numpy(), g_ids)
+    np.testing.assert_array_equal(p_d.cpu().numpy(), g_d)
+    nq = queries.shape[0]
+    sample = np.sort(np.random.default_rng(7).choice(nq, size=min(n_sample, nq), replace=False))
+    oix = O.OracleIndex(a)
+    qh = queries.cpu().numpy()[sample]
+    o_ids, o_d, ost = O.search(oix, qh, k, w, m, stages=True)
+    np.testing.assert_array_equal(gst["qproj"][sample], ost["qproj"], err_msg=f"{tag}: projected queries")
+    np.testing.assert_array_equal(gst["q8"][sample], ost["q8"], err_msg=f"{tag}: query codes")
+    np.testing.assert_array_equal(gst["sel"][sample], ost["sel"], err_msg=f"{tag}: selected clusters")
+    np.testing.assert_array_equal(gst["z"][sample], ost["z"], err_msg=f"{tag}: re-quantized vectors")
+    np.testing.assert_array_equal(gst["sigma"][sample], ost["sigma"], err_msg=f"{tag}: pair scales")
+    np.testing.assert_array_equal(gst["rho0"][sample], ost["rho0"], err_msg=f"{tag}: unquantized first components")
+    np.testing.assert_array_equal(gst["pmax"][sample], ost["pair_best"], err_msg=f"{tag}: per-pair best scores (matrix-core kernel)")
+    assert (np.abs(ost["rho0"]).max() > 0) == mixed
+    np.testing.assert_array_equal(np.sort(gst["cand_rows"][sample].astype(np.int64), axis=1), np.sort(ost["cand_rows"], axis=1),
+                                  err_msg=f"{tag}: candidate sets")
+    assert_topk_equal(g_ids[sample], g_d[sample], o_ids, o_d, tag, abs_tol=rounding_abs_tol(qh, a["corpus"][:50000], a["metric"]),
+                      exact=oracle_distance_of(a, qh))
+    return gst
+
+
+@pytest.mark.parametrize("workload,scheme,n_sample", [("embed-ip", "cluster", 192), ("embed-ip", "mixed", 192),
+                                                      ("highdim-cos", "cluster", 96), ("lowdim-l2", "cluster", 96)])
+def test_full_size_benchmark_configuration_sampled_parity(B, workload, scheme, n_sample):
     """(scheme: the configured step sizes per cluster, or the mixed-precision decomposition on column-wise step sizes.)
-    The benchmark configuration at its full size (1M x 768, batch 10000, w=32, m=200, k=10) in the launch
-    configuration bench.py times - device-resident inputs, one whole batch per call, hence the cluster-batched
-    scoring, the per-query walk and the grouped re-rank - against the oracle on a sample of the batch: the
-    oracle handles a query on its own, so any subset can be checked one by one.  Integer stages and candidate
-    sets bit-exact, distances and ids to the usual bars."""
+    The configured workloads at their full size - 1M x 768 inner product (the benchmark configuration: batch 10000,
+    w=32, m=200), 1M x 1024 cosine (r=48, w=48, m=300: two k-steps on the matrix cores, rows of 4 KB in the re-rank),
+    1M x 128 squared Euclidean without projection (r=24, w=64: the regime where a query's best estimates are spread over
+    most of its clusters) - in the launch configuration bench.py times: device-resident inputs, one whole batch of
+    10000 per call, hence the cluster-batched scoring, the per-query walk and the grouped re-rank with their
+    full-size grids and work-item splits."""
     from paper_2410_18926_amd.synth import get_workload, make_dataset, build_index
-    wl = get_workload("embed-ip")
+    wl = get_workload(workload)
     dev = torch.device("cuda:0")
     corpus, queries = make_dataset(wl, dev)
     ix = build_index(corpus, wl, mixed_precision=(scheme == "mixed"))
     del corpus
     gix = B.Index.from_arrays(ix)
-    k, w, m = wl.k, wl.w, wl.m
-    g_ids, g_d, gst = gix.search_stages(queries, k, w, m)
-    p_ids, p_d = gix.search(queries, k, w, m)                      # the entry point the benchmark calls
-    np.testing.assert_array_equal(p_ids.cpu().numpy(), g_ids)
-    np.testing.assert_array_equal(p_d.cpu().numpy(), g_d)
-    gix.close()
-
-    sample = np.random.default_rng(7).choice(wl.nq, size=192, replace=False)
-    sample.sort()
     a = ix.numpy()
     del ix
     torch.cuda.empty_cache()
-    oix = O.OracleIndex(a)
-    qh = queries.cpu().numpy()[sample]
-    o_ids, o_d, ost = O.search(oix, qh, k, w, m, stages=True)
-    np.testing.assert_array_equal(gst["qproj"][sample], ost["qproj"], err_msg="projected queries")
-    np.testing.assert_array_equal(gst["q8"][sample], ost["q8"], err_msg="query codes")
-    np.testing.assert_array_equal(gst["sel"][sample], ost["sel"], err_msg="selected clusters")
-    np.testing.assert_array_equal(gst["z"][sample], ost["z"], err_msg="re-quantized vectors")
-    np.testing.assert_array_equal(gst["sigma"][sample], ost["sigma"], err_msg="pair scales")
-    np.testing.assert_array_equal(gst["rho0"][sample], ost["rho0"], err_msg="unquantized first components")
-    np.testing.assert_array_equal(gst["pmax"][sample], ost["pair_best"], err_msg="per-pair best scores (matrix-core kernel)")
-    assert (np.abs(ost["rho0"]).max() > 0) == (scheme == "mixed")
-    np.testing.assert_array_equal(np.sort(gst["cand_rows"][sample].astype(np.int64), axis=1), np.sort(ost["cand_rows"], axis=1),
-                                  err_msg="candidate sets")
-    assert_topk_equal(g_ids[sample], g_d[sample], o_ids, o_d, f"embed-ip full size, {scheme}", exact=oracle_distance_of(a, qh))
+    _sampled_full_size_parity(B, gix, a, queries, wl.k, wl.w, wl.m, n_sample, f"{workload} full size, {scheme}", mixed=(scheme == "mixed"))
+    gix.close()
+
+
+@pytest.mark.parametrize("nq", [1024, 32768])
+def test_many_clusters_full_launch_shapes_sampled_parity(B, nq):
+    """The launch shapes of the 10M-point workload - L = 16384 clusters, w = 64, d' = 192, r = 32, m = 200, a batch of
+    1024 (few pairs per cluster: the streaming shape of the scoring kernel, block-per-query cluster selection) and one
+    whole chunk of 32768 queries (a 2 GB approximate-score matrix that is streamed past the caches, the dense scoring
+    shape, 128 pairs per cluster on average) - on a corpus small enough for the host oracle (1M x 384, random factors
+    and codes, clusters of 40..82 points), checked against the oracle on a sample of the batch."""
+    from paper_2410_18926_amd.synth import get_workload, random_index
+    import dataclasses
+    wl = dataclasses.replace(get_workload("scale-ip"), n=1_000_000, nq=nq)
+    dev = torch.device("cuda:0")
+    g = torch.Generator(device=dev)
+    g.manual_seed(5150 + nq)
+    corpus = torch.randn(wl.n, wl.d, generator=g, device=dev)
+    corpus /= corpus.norm(dim=1, keepdim=True)
+    queries = torch.randn(nq, wl.d, generator=g, device=dev)
+    ix = random_index(corpus, wl)
+    del corpus
+    gix = B.Index.from_arrays(ix)
+    a = ix.numpy()
+    del ix
+    torch.cuda.empty_cache()
+    _sampled_full_size_parity(B, gix, a, queries, wl.k, wl.w, wl.m, 64, f"L=16384 launch shapes, nq={nq}")
+    gix.close()
 
 
 @pytest.mark.parametrize("L,w,metric,case", [
