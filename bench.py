@@ -1,21 +1,31 @@
 #!/usr/bin/env python3
 """Benchmark of the LoRANN query phase on one MI355X.
 
-A "step" is one lorann_search call over one batch of synthetic queries (all stages: projection, routing,
-int8 scoring, top-m, exact re-rank), with index, queries and outputs resident in HBM.  Prints ONE JSON line.
+A "step" is one search over one batch of synthetic queries (all stages: projection, routing, int8 scoring,
+top-m, exact re-rank), with index, queries and outputs resident in HBM.  Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload embed-ip]
+
+The headline (`value`, `ms_per_step`, `roofline`) is the workload named by --workload (default: the 1M x 768
+inner-product configuration the metric is quoted on).  The default run adds, in the same JSON line:
+  `b_scoring_hbm_regime`  the B_c scoring kernel where it is bound by HBM (the 10M x 384 shapes, batch 1024),
+  `other_workloads`       the other configured workloads that fit a short run (step time, queries/s, recall@10,
+                          a sampled comparison with the oracle),
+  `cpu_baseline`          the oracle timed on the host cores.
 """
 from __future__ import annotations
 
 import argparse
 import dataclasses
 import json
-import os
+import pathlib
+import re
 import sys
 import time
 
 import numpy as np
+
+ROOT = pathlib.Path(__file__).resolve().parent
 
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 PEAK_BF16_MFMA_TFLOPS = 2500.0 # dense bf16 MFMA
@@ -23,9 +33,7 @@ PEAK_FP64_MFMA_TFLOPS = 78.6
 PEAK_INT8_MFMA_TOPS = 5000.0
 PEAK_VALU_LANE_TOPS = 256 * 64 * 2.4e9 / 1e12   # 256 CUs x 64 lanes x 2.4 GHz = 39.3 T lane-ops/s
 
-# HBM bytes per launch (GB) measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by the copy-kernel
-# calibration (profiles/hbm_traffic_embed-ip_pmc.txt).  Valid for the default workload only.
-MEASURED_TRAFFIC_GB = {("embed-ip", 1.0, "rerank"): 3.26}
+RERANK_ELEM_BYTES = {"f32": 4, "f16": 2}
 
 
 def log(*a):
@@ -40,24 +48,83 @@ def recall_at_k(ids, dists, gt_dists):
     return float(ok.mean())
 
 
-def kernel_models(wl, nq, touched_rows, npairs, column_scales=False, mixed=False):
-    """Algorithmic work of one launch of each kernel: (bound, amount, unit-peak)."""
+def recall_by_id(ids, gt_ids, k, stride=1):
+    return float(np.mean([len(set(ids[i]) & set(gt_ids[i])) / k for i in range(0, ids.shape[0], stride)]))
+
+
+def tracked_traffic_gb(workload, kernel_prefix):
+    """HBM bytes per launch of a kernel from the tracked rocprofv3 --pmc summary of this workload
+    (profiles/hbm_traffic_<workload>_pmc.txt: calibrated read MB + written MB), or None when no summary covers it."""
+    f = ROOT / "profiles" / f"hbm_traffic_{workload}_pmc.txt"
+    if not f.exists():
+        return None
+    for line in f.read_text().splitlines():
+        if line.startswith(kernel_prefix):
+            nums = re.findall(r"[-+]?\d+\.\d+", line[44:] if len(line) > 44 else line)
+            if len(nums) >= 4:
+                return round((float(nums[-2]) + float(nums[-1])) / 1e3, 3)
+    return None
+
+
+def kernel_models(wl, nq, touched_rows, npairs, scores, column_scales=False, mixed=False):
+    """Work of one STEP of each kernel and the resource that bounds it: (bound, amount, peak, unit), or
+    (bound, None, None, None) where no roof is meaningful (short kernels that wait on dependent memory round trips)."""
     d, dp, r, L, m = wl.d, wl.dp, wl.r, wl.L, wl.m
     b_bytes = touched_rows * (r + (4 if wl.metric == 1 else 0) + (4 if column_scales else 0) + (4 if mixed else 0)) + npairs * (r + 4 + (4 if mixed else 0))
+    # few pairs per cluster: the B_c scoring streams the codes from HBM; many: one half of a three-operand maximum per
+    # score on the vector ALUs (16 lanes per SIMD and clock)
+    pm = ("hbm", b_bytes / 1e9, PEAK_HBM_GBS, "GB/s") if npairs <= 16 * L else ("alu", 0.5 * scores / 1e12, PEAK_VALU_LANE_TOPS, "T lane-ops/s")
+    lat = ("latency", None, None, None)
     return {
         "project_f64": ("mfma", 2.0 * nq * d * dp / 1e12, PEAK_FP64_MFMA_TFLOPS, "TFLOP/s"),
         "centroid_dissim_f64": ("mfma", 2.0 * nq * dp * L / 1e12, PEAK_FP64_MFMA_TFLOPS, "TFLOP/s"),
-        # approximate scores on the bf16 matrix cores; in practice bound by writing the nq x L float matrix
         "centroid_screen_bf16": ("mfma", 2.0 * nq * dp * L / 1e12, PEAK_BF16_MFMA_TFLOPS, "TFLOP/s"),
-        "quantize_rows": ("hbm", nq * dp * 5 / 1e9, PEAK_HBM_GBS, "GB/s"),
-        "select_clusters": ("hbm", nq * L * 4 / 1e9, PEAK_HBM_GBS, "GB/s"),
-        "scatter_pairs": ("hbm", npairs * 12 / 1e9, PEAK_HBM_GBS, "GB/s"),
-        "stage_a_i8": ("hbm", (L * dp * r + npairs * (dp + r + 4)) / 1e9, PEAK_HBM_GBS, "GB/s"),
-        # B_c scoring (each of the two passes): every touched code once + the pairs' z / sigma (+ |c|^2 for Euclidean)
-        "pair_max_i8": ("hbm", b_bytes / 1e9, PEAK_HBM_GBS, "GB/s"),
-        "score_select_exact": ("hbm", b_bytes / 1e9, PEAK_HBM_GBS, "GB/s"),
-        "rerank": ("hbm", nq * m * d * 4 / 1e9, PEAK_HBM_GBS, "GB/s"),
+        "route_fused_bf16": ("mfma", 2.0 * nq * dp * L / 1e12, PEAK_BF16_MFMA_TFLOPS, "TFLOP/s"),
+        "quantize_rows": lat, "select_clusters": lat, "bucket_count": lat, "scan_buckets": lat, "scatter_pairs": lat,
+        "stage_a_i8": lat, "select_query": lat, "order_queries": lat, "group_union": lat, "topk": lat,
+        "score_select_exact": lat, "candidate_scores": lat,
+        "pair_max_i8": pm,
+        "rerank": ("hbm", nq * m * d * 4 / 1e9, PEAK_HBM_GBS, "GB/s"),     # algorithmic; the headline uses the bytes the kernel requests
     }
+
+
+def gather_accounting(gix, wl, queries, k, w, m, elem_bytes):
+    """Bytes of the re-rank gather for one batch, taken from this run (lane 0, synchronous):
+      algorithmic  every query gathers its m rows (the method as stated, Sec. 2.2): nq * m * d * elem
+      requested    what the kernel asks the memory system for: each row once per GROUP of queries that share it
+                   (sum over groups of their distinct rows), the queries, the row lists and the results
+      floor        each distinct candidate row of the whole batch once - no kernel can read less."""
+    nq, d = queries.shape[0], wl.d
+    st = gix.search_stages(queries, k, w, m)[2]
+    cand = st["cand_rows"]
+    valid = int((cand >= 0).sum())
+    distinct = int(np.unique(cand[cand >= 0]).size)
+    union_rows = gix.profile_gather_rows()
+    acc = {"algorithmic_bytes": nq * m * d * elem_bytes, "floor_bytes": distinct * d * elem_bytes,
+           "candidate_rows": valid, "distinct_rows": distinct, "rows_fetched": union_rows if union_rows >= 0 else None}
+    if union_rows >= 0:
+        # per fetched row: the row, its number (4 B), query mask (2 B) and output positions (8 x 2 B); per query: the
+        # query itself; per candidate: distance (4 B) and id (8 B) written
+        acc["requested_bytes"] = union_rows * (d * elem_bytes + 22) + nq * d * 4 + valid * 12
+    else:
+        acc["requested_bytes"] = acc["algorithmic_bytes"]           # the one-query-per-block re-rank fetches every row
+    return acc
+
+
+def time_steps(torch, gix, batches, outs, k, w, m, n_steps, first, n_lanes):
+    """n_steps steps enqueued round-robin over the lanes, joined onto the index's stream; returns seconds."""
+    nb = len(batches)
+
+    def run(n, f):
+        for s in range(n):
+            gix.search(batches[(f + s) % nb], k, w, m, out=outs[s % n_lanes], lane=s % n_lanes)
+        for l in range(n_lanes):
+            gix.lane_join(l)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(n_steps, first)
+    torch.cuda.synchronize()
+    return time.perf_counter() - t0
 
 
 def batch_sweep(torch, gix, wl, dev, batch_sizes, k, w, m, cluster_sizes, draw_queries):
@@ -99,6 +166,7 @@ def batch_sweep(torch, gix, wl, dev, batch_sizes, k, w, m, cluster_sizes, draw_q
                "latency_ms_p99": round(float(np.percentile(lat, 99)), 4), "latency_ms_best": round(float(lat[0]), 4),
                "queries_per_s": round(b / (float(np.median(lat)) / 1e3), 1),
                "touched_clusters": int(touched.sum()) if frac_seen == 1.0 else None,
+               "launches_per_search": sum(c for _, c in prof.values()) / n_ev,
                "kernels_ms": {n: round(ms / max(1, c), 5) for n, (ms, c) in prof.items() if c}}
         pm = prof.get("pair_max_i8")
         if pm and pm[1]:
@@ -111,6 +179,115 @@ def batch_sweep(torch, gix, wl, dev, batch_sizes, k, w, m, cluster_sizes, draw_q
         rows.append(row)
         del pool, out
     return rows
+
+
+def b_scoring_hbm_regime(torch, binding, dev, steps=60):
+    """The metric's second clause - HBM GB/s of the B_c scoring - where that kernel IS bound by HBM: few pairs per
+    cluster.  Shapes of the 10M x 384 workload (320 MB of codes, more than the 256 MB last-level cache; L = 16384,
+    d' = 192, r = 32, w = 64), batch 1024 = 4 pairs per cluster, random factors and codes (the kernel's time and bytes
+    do not depend on the values; fitting that index takes minutes).  The searches are enqueued back to back and HIP
+    events bracket the scoring kernel only.  Bytes: every code of every touched cluster once + z and sigma of the
+    pairs."""
+    from paper_2410_18926_amd.synth import get_workload, random_index
+    wl = dataclasses.replace(get_workload("scale-ip"), nq=1024)
+    t0 = time.time()
+    g = torch.Generator(device=dev)
+    g.manual_seed(5005)
+    corpus = torch.randn(wl.n, wl.d, generator=g, device=dev)
+    corpus /= corpus.norm(dim=1, keepdim=True)
+    nb = 8
+    batches = [torch.randn(wl.nq, wl.d, generator=g, device=dev) for _ in range(nb)]
+    ix = random_index(corpus, wl)
+    del corpus
+    gix = binding.Index.from_arrays(ix)
+    sizes = (ix.cluster_offsets[1:] - ix.cluster_offsets[:-1]).cpu().numpy()
+    del ix
+    torch.cuda.empty_cache()
+    gix.use_torch_stream()
+    k, w, m, nq = wl.k, wl.w, wl.m, wl.nq
+    out = (torch.empty((nq, k), dtype=torch.int64, device=dev), torch.empty((nq, k), dtype=torch.float32, device=dev))
+    for s in range(3):
+        gix.search(batches[s % nb], k, w, m, out=out, asynchronous=True)
+    torch.cuda.synchronize()
+    gix.profile_enable(3)
+    for s in range(steps):
+        gix.search(batches[s % nb], k, w, m, out=out, asynchronous=True)
+    torch.cuda.synchronize()
+    ms, launches = gix.profile_get()["pair_max_i8"]
+    gix.profile_enable(0)
+    sel = gix.search_stages(batches[0], k, w, m)[2]["sel"]
+    touched = np.zeros(wl.L, bool)
+    touched[np.unique(sel)] = True
+    b_bytes = int(sizes[touched].sum()) * wl.r + nq * w * (wl.r + 4)
+    gix.close()
+    avg_ms = ms / max(1, launches)
+    rate = b_bytes / 1e9 / (avg_ms / 1e3)
+    res = {"kernel": "pair_max_i8", "workload": f"scale-ip shapes: {wl.n}x{wl.d}, L={wl.L}, d'={wl.dp}, r={wl.r}, w={w}; batch {nq} "
+           f"({nq * w / wl.L:.1f} pairs per cluster); random factors and codes", "touched_clusters": int(touched.sum()),
+           "bytes_per_launch": b_bytes, "avg_ms": round(avg_ms, 5), "launches": int(launches), "bound": "hbm",
+           "achieved": round(rate, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(rate / PEAK_HBM_GBS, 4),
+           "traffic": None, "setup_s": round(time.time() - t0, 1)}
+    log(f"[bench] B_c scoring, HBM-bound regime: {res}")
+    return res
+
+
+def measure_other_workload(torch, binding, dev, name, steps, n_lanes, oracle_queries):
+    """One of the other configured workloads, timed like the headline (fewer steps): step time, queries/s, recall@10
+    against brute force, and the oracle on a sample of the first batch."""
+    from paper_2410_18926_amd.synth import get_workload, make_dataset, build_index
+    from paper_2410_18926_amd.synth.data import brute_force_topk
+    t0 = time.time()
+    wl = get_workload(name)
+    nb = 4
+    corpus, queries, extra = make_dataset(wl, dev, extra_batches=nb - 1)
+    batches = [queries] + list(extra)
+    ix = build_index(corpus, wl)
+    n_rec = min(wl.nq, 2000)
+    gt_ids, gt_d = brute_force_topk(corpus, queries[:n_rec], wl.metric, wl.k)
+    gt_ids, gt_d = gt_ids.cpu().numpy(), gt_d.cpu().numpy()
+    del corpus
+    gix = binding.Index.from_arrays(ix)
+    gix.use_torch_stream()
+    nq, k, w, m = wl.nq, wl.k, min(wl.w, wl.L), wl.m
+    outs = [(torch.empty((nq, k), dtype=torch.int64, device=dev), torch.empty((nq, k), dtype=torch.float32, device=dev)) for _ in range(n_lanes)]
+    time_steps(torch, gix, batches, outs, k, w, m, max(2, n_lanes), 0, n_lanes)
+    dt = time_steps(torch, gix, batches, outs, k, w, m, steps, 0, n_lanes)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for s in range(steps):
+        gix.search(batches[s % nb], k, w, m, out=outs[0], asynchronous=True)
+    torch.cuda.synchronize()
+    dt_one = time.perf_counter() - t1
+    gix.profile_enable(1)
+    for s in range(min(steps, 5)):
+        gix.search(batches[s % nb], k, w, m, out=outs[0])
+    prof = gix.profile_get()
+    gix.profile_enable(0)
+    ids, dists = gix.search(queries, k, w, m)
+    ids_h, dists_h = ids.cpu().numpy(), dists.cpu().numpy()
+    rec = recall_at_k(ids_h[:n_rec], dists_h[:n_rec], gt_d)
+    gix.close()
+    res = {"workload": f"{wl.name}: {wl.n}x{wl.d}, L={wl.L}, d'={wl.dp}, r={wl.r}, batch {nq}, w={w}, m={m}, k={k}",
+           "steps": steps, "ms_per_step": round(dt / steps * 1e3, 4), "queries_per_s": round(nq * steps / dt, 1),
+           "ms_per_step_one_batch_at_a_time": round(dt_one / steps * 1e3, 4),
+           "recall_at_10": round(rec, 4), "recall_at_10_by_id": round(recall_by_id(ids_h[:n_rec], gt_ids, k), 4),
+           "recall_target_met": bool(rec >= 0.9),
+           "largest_kernels_ms": dict(sorted(((n, round(ms / c, 4)) for n, (ms, c) in prof.items() if c), key=lambda t: -t[1])[:4])}
+    if not res["recall_target_met"]:
+        res["note"] = ("the configured rank and candidate count do not reach recall@10 = 0.9 on this synthetic data; the "
+                       "configuration is reported as given, not tuned (the library and the oracle agree on it)")
+    if oracle_queries > 0:
+        from oracle import oracle as O
+        a = ix.numpy()
+        sample = np.sort(np.random.default_rng(11).choice(nq, size=min(oracle_queries, nq), replace=False))
+        o_ids, o_d = O.search(O.OracleIndex(a), queries.cpu().numpy()[sample], k, w, m)
+        res["oracle_match"] = {"queries": int(sample.size), "id_lists_identical": float(np.mean(np.all(o_ids == ids_h[sample], axis=1))),
+                               "max_rel_dist_err": float(np.max(np.abs(o_d - dists_h[sample]) / np.maximum(np.abs(o_d), 1e-3)))}
+    res["total_s"] = round(time.time() - t0, 1)
+    log(f"[bench] other workload {name}: {res}")
+    del ix
+    torch.cuda.empty_cache()
+    return res
 
 
 def main():
@@ -143,10 +320,14 @@ def main():
                          "(lorann_search_lane), each with its own workspace and stream; 1 = one batch at a time")
     ap.add_argument("--timed-only", action="store_true",
                     help="run the warm-up, the timed steps and one result pass only - no context loops, no per-kernel "
-                         "event pass, no other modes - so that a profiler attached to the process sees the timed "
-                         "configuration and little else")
+                         "event pass, no other modes or workloads - so that a profiler attached to the process sees the "
+                         "timed configuration and little else")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain 1 GiB elementwise copy (calibrates the HBM byte counters under rocprofv3 --pmc)")
+    ap.add_argument("--other-workloads", default="default",
+                    help="comma-separated workloads also reported under 'other_workloads' (default: tiny,lowdim-l2,highdim-cos "
+                         "when the headline is embed-ip at full size; 'none' to skip)")
+    ap.add_argument("--no-b-scoring-regime", action="store_true", help="skip the HBM-bound measurement of the B_c scoring kernel")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (query-sharded data parallelism would "
@@ -169,6 +350,8 @@ def main():
     if args.batch:
         wl = dataclasses.replace(wl, nq=args.batch)
     K, W = args.steps, args.warmup
+    headline_default = args.workload == "embed-ip" and args.scale == 1.0 and not args.batch and not args.random_index \
+        and args.rerank == "f32" and not (args.column_scales or args.mixed_precision) and not args.timed_only
 
     t0 = time.time()
     nb = max(1, min(K + W, 8))
@@ -200,26 +383,14 @@ def main():
     n_lanes = max(1, min(args.lanes, binding.LANES))
     outs = [out] + [(torch.empty_like(out[0]), torch.empty_like(out[1])) for _ in range(n_lanes - 1)]
 
-    def run_steps(n_steps, first):
-        """Enqueue n_steps steps round-robin over the lanes and join the lanes onto the index's stream; no host wait."""
-        for s in range(n_steps):
-            gix.search(batches[(first + s) % nb], k, w, m, out=outs[s % n_lanes], lane=s % n_lanes)
-        for l in range(n_lanes):
-            gix.lane_join(l)
-
-    run_steps(max(W, n_lanes), 0)          # warm-up (every lane sizes its workspace)
-    torch.cuda.synchronize()
+    time_steps(torch, gix, batches, outs, k, w, m, max(W, n_lanes), 0, n_lanes)      # warm-up (every lane sizes its workspace)
     # Timed region: K steps.  HIP events bracket the dominant kernel (the re-rank gather) only, so that timing
     # the kernels does not slow the step being timed.
     # The steps are enqueued without a host wait in between, round-robin on the index's lanes (lorann_search_lane),
     # as a serving loop would: up to n_lanes batches are in flight, each one passing through the whole path; the
-    # timed region ends with the device synchronisation below.
+    # timed region ends with a device synchronisation.
     gix.profile_enable(2)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    run_steps(K, W)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
+    elapsed = time_steps(torch, gix, batches, outs, k, w, m, K, W, n_lanes)
     prof_dom = gix.profile_get()
     fallback_queries = gix.profile_fallback_queries()
     # for context: the same loop with the gathers of different lanes allowed to overlap (each launch then takes
@@ -228,12 +399,8 @@ def main():
     if n_lanes > 1 and not args.timed_only:
         gix.profile_enable(0)
         gix.set_gather_turns(False)
-        run_steps(n_lanes, 0)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        run_steps(K, W)
-        torch.cuda.synchronize()
-        dt = time.perf_counter() - t0
+        time_steps(torch, gix, batches, outs, k, w, m, n_lanes, 0, n_lanes)
+        dt = time_steps(torch, gix, batches, outs, k, w, m, K, W, n_lanes)
         gix.set_gather_turns(True)
         overlapped = {"queries_per_s": round(nq * K / dt, 1), "ms_per_step": round(dt / K * 1e3, 4)}
     elapsed_one_lane, elapsed_allev, prof_one, prof = float("nan"), float("nan"), {}, dict(prof_dom)
@@ -260,22 +427,27 @@ def main():
     ids, dists = gix.search(queries, k, w, m)
     ids_h, dists_h = ids.cpu().numpy(), dists.cpu().numpy()
     recall = recall_at_k(ids_h[:n_rec], dists_h[:n_rec], gt_d)
-    # map returned ids (original corpus indices) check: true top-k ids overlap, as a second recall definition
+    # second recall definition: overlap of the returned ids (original corpus indices) with the true top-k ids
     gt_ids_h = gt_ids.cpu().numpy()
-    recall_ids = float(np.mean([len(set(ids_h[i]) & set(gt_ids_h[i])) / k for i in range(0, n_rec, max(1, n_rec // 2000))]))
+    recall_ids = recall_by_id(ids_h[:n_rec], gt_ids_h, k, stride=max(1, n_rec // 2000))
     if args.rerank != "f32":
         recall = recall_ids          # the returned distances are not the exact ones: count by id only
 
-    # per-kernel roofline figures from the events recorded over the timed region
+    # per-kernel figures from the events recorded over the timed region
     sizes = (ix.cluster_offsets[1:] - ix.cluster_offsets[:-1]).cpu().numpy()
     # clusters touched by the batch (their codes are what the scoring kernel has to read at least once)
     touched = np.ones(wl.L, bool)
+    scores = float(nq) * w * float(sizes.mean())
+    gather = None
     if not args.timed_only:
         sel_all = gix.search_stages(queries[:20000], k, w, m)[2]["sel"]
         touched[:] = False
         touched[np.unique(sel_all)] = True
+        scores = float(sizes[sel_all.reshape(-1)].sum()) * (nq / sel_all.shape[0])
+        if args.rerank != "none":
+            gather = gather_accounting(gix, wl, queries[:32768], k, w, m, RERANK_ELEM_BYTES[args.rerank])
     touched_rows = int(sizes[touched].sum())
-    models = kernel_models(wl, nq, touched_rows, nq * w, args.column_scales or args.mixed_precision, args.mixed_precision)
+    models = kernel_models(wl, nq, touched_rows, nq * w, scores, args.column_scales or args.mixed_precision, args.mixed_precision)
     if args.rerank == "f16":
         bound, amount, peak, unit = models["rerank"]
         models["rerank"] = (bound, amount / 2, peak, unit)           # two bytes per gathered element
@@ -288,27 +460,55 @@ def main():
         if name in models:
             # the models give the work of one STEP (a batch larger than 32768 queries runs in several launches)
             bound, amount, peak, unit = models[name]
-            ach = amount / (ms / K / 1e3)
-            ent.update({"bound": bound, "achieved": round(ach, 3), "peak": peak, "unit": unit, "frac": round(ach / peak, 4)})
+            ent["bound"] = bound
+            if amount is not None:
+                ach = amount / (ms / K / 1e3)
+                ent.update({"achieved": round(ach, 3), "peak": round(peak, 1), "unit": unit, "frac": round(ach / peak, 4)})
+                if name == "rerank":
+                    ent["note"] = "algorithmic bytes (every query gathers its m rows); see roofline for the bytes the kernel requests"
         kernels.append(ent)
     kernels.sort(key=lambda e: -e["avg_ms"])
-    dom = next((e for e in kernels if "bound" in e), None)
+    dom = kernels[0] if kernels else None
     roofline = None
-    if dom:
-        # the dominant kernel's figures come from the events of the timed region itself
-        ms, launches = prof_dom.get(dom["kernel"], (0.0, 0))
-        if launches:
-            bound, amount, peak, unit = models[dom["kernel"]]
-            ach = amount / (ms / K / 1e3)
-            dom = dict(dom, avg_ms=round(ms / launches, 5), achieved=round(ach, 3), frac=round(ach / peak, 4))
-        roofline = {"kernel": dom["kernel"], "bound": dom["bound"], "achieved": dom["achieved"], "peak": dom["peak"],
-                    "unit": dom["unit"], "frac": dom["frac"], "avg_ms": dom["avg_ms"],
-                    "traffic": MEASURED_TRAFFIC_GB.get((args.workload, args.scale, dom["kernel"])) if args.rerank == "f32" else None}
-        if roofline["traffic"] and roofline["avg_ms"]:
-            # the kernel shares row reads between neighbouring queries, so it moves fewer bytes than the algorithmic
-            # count: the rate of the bytes it really moved is the figure to hold against the HBM peak
-            roofline["traffic_rate"] = round(roofline["traffic"] / (roofline["avg_ms"] / 1e3), 1)
+    if dom and dom["kernel"] == "rerank":
+        # The dominant kernel: duration from the events of the timed region itself.  Numerator: the bytes the kernel
+        # requests from the memory system in this run (each row once per group of queries that share it), so that the
+        # fraction is a fraction of the HBM peak; the algorithmic rate (every query gathers its m rows) is kept beside
+        # it, and so is the floor (each distinct candidate row of the batch once).
+        ms, launches = prof_dom.get("rerank", (0.0, 0))
+        if not launches:
+            ms, launches = prof.get("rerank", (0.0, 0))
+        avg_ms = ms / max(1, launches)
+        per_step_ms = ms / K if prof_dom.get("rerank", (0, 0))[1] else avg_ms * dom["launches_per_step"]
+        acc = gather or {"algorithmic_bytes": nq * m * wl.d * RERANK_ELEM_BYTES.get(args.rerank, 4), "requested_bytes": None,
+                         "floor_bytes": None, "rows_fetched": None, "distinct_rows": None, "candidate_rows": None}
+        scale_b = nq / min(nq, 32768)            # the accounting pass covers one launch (at most 32768 queries)
+        req = acc["requested_bytes"] * scale_b if acc["requested_bytes"] else None
+        alg = nq * m * wl.d * RERANK_ELEM_BYTES.get(args.rerank, 4)
+        num = req if req else alg
+        rate = num / 1e9 / (per_step_ms / 1e3)
+        traffic = tracked_traffic_gb(args.workload, "k_group_gather") if (args.scale == 1.0 and not args.batch and args.rerank == "f32") else None
+        roofline = {"kernel": "rerank", "bound": "hbm", "achieved": round(rate, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                    "frac": round(rate / PEAK_HBM_GBS, 4), "avg_ms": round(avg_ms, 5),
+                    "bytes": "requested by the kernel in this run: each candidate row once per group of 8 queries that share it, plus queries, row lists and results" if req else "algorithmic",
+                    "requested_gb": round(num / 1e9, 4), "algorithmic_gb": round(alg / 1e9, 4),
+                    "algorithmic_rate": round(alg / 1e9 / (per_step_ms / 1e3), 1),
+                    "floor_gb": round(acc["floor_bytes"] * scale_b / 1e9, 4) if acc["floor_bytes"] else None,
+                    "requested_over_floor": round(req / (acc["floor_bytes"] * scale_b), 3) if req and acc["floor_bytes"] else None,
+                    "rows_fetched": acc["rows_fetched"], "distinct_rows": acc["distinct_rows"], "candidate_rows": acc["candidate_rows"],
+                    "traffic": traffic,
+                    "traffic_source": f"profiles/hbm_traffic_{args.workload}_pmc.txt (rocprofv3 FETCH_SIZE + WRITE_SIZE, calibrated)" if traffic else None}
+        if traffic:
+            roofline["traffic_rate"] = round(traffic / (avg_ms / 1e3), 1)
             roofline["traffic_frac"] = round(roofline["traffic_rate"] / PEAK_HBM_GBS, 4)
+            if acc["floor_bytes"]:
+                roofline["traffic_over_floor"] = round(traffic * 1e9 / (acc["floor_bytes"] * scale_b), 3)
+    elif dom and "frac" in dom:
+        roofline = {"kernel": dom["kernel"], "bound": dom["bound"], "achieved": dom["achieved"], "peak": dom["peak"],
+                    "unit": dom["unit"], "frac": dom["frac"], "avg_ms": dom["avg_ms"], "traffic": None}
+    elif dom:
+        roofline = {"kernel": dom["kernel"], "bound": dom.get("bound", "latency"), "achieved": None, "peak": None, "unit": None,
+                    "frac": None, "avg_ms": dom["avg_ms"], "traffic": None}
 
     # The other two modes of the last step, timed the same way (fewer steps), with recall by id against the true
     # neighbours: context for the headline figure, which is always the mode selected by --rerank.
@@ -319,18 +519,12 @@ def main():
         gix.set_rerank(mode)
         for s in range(2):
             gix.search(batches[s % nb], k, w, m, out=out)
-        torch.cuda.synchronize()
         Km = max(1, min(K, 10))
-        run_steps(n_lanes, 0)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        run_steps(Km, 0)
-        torch.cuda.synchronize()
-        dt = time.perf_counter() - t0
+        time_steps(torch, gix, batches, outs, k, w, m, n_lanes, 0, n_lanes)
+        dt = time_steps(torch, gix, batches, outs, k, w, m, Km, 0, n_lanes)
         mi = gix.search(queries[:n_rec], k, w, m)[0].cpu().numpy()
-        rec = float(np.mean([len(set(mi[i]) & set(gt_ids_h[i])) / k for i in range(n_rec)]))
         other_modes[name] = {"queries_per_s": round(nq * Km / dt, 1), "ms_per_step": round(dt / Km * 1e3, 4), "steps": Km,
-                             "recall_at_10_by_id": None if args.random_index else round(rec, 4)}
+                             "recall_at_10_by_id": None if args.random_index else round(recall_by_id(mi, gt_ids_h, k), 4)}
         log(f"[bench] rerank mode {name}: {other_modes[name]}")
     gix.set_rerank(rerank_modes[args.rerank])
 
@@ -366,6 +560,7 @@ def main():
         oracle_match = {"queries": n_m, "id_lists_identical": float(np.mean(np.all(o_ids[:n_m] == ids_h[:n_m], axis=1))),
                         "ids_equal": float(np.mean(o_ids[:n_m] == ids_h[:n_m])),
                         "max_rel_dist_err": float(np.max(np.abs(o_d[:n_m] - dists_h[:n_m]) / np.maximum(np.abs(o_d[:n_m]), 1e-3)))}
+        del a, oix
         log(f"[bench] oracle baseline done in {time.time() - t0:.1f}s")
 
     if args.copy_probe:
@@ -376,9 +571,26 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    gix.close()
+    del ix
+    torch.cuda.empty_cache()
+
+    b_regime = None
+    if headline_default and not args.no_b_scoring_regime:
+        b_regime = b_scoring_hbm_regime(torch, binding, dev)
+        b_regime["traffic_source"] = "profiles/pair_max_scale-ip_streaming.txt holds the rocprofv3 duration and FETCH_SIZE of the same command"
+    others = None
+    names = [] if args.other_workloads == "none" else (["tiny", "lowdim-l2", "highdim-cos"] if args.other_workloads == "default" else args.other_workloads.split(","))
+    if names and (headline_default or args.other_workloads != "default"):
+        others = {n: measure_other_workload(torch, binding, dev, n, steps=10, n_lanes=n_lanes,
+                                            oracle_queries=0 if args.no_cpu_baseline else 64) for n in names}
+        others["scale-ip"] = {"note": "10M x 384: fitting its index takes about three minutes, so it is not part of the default run; "
+                                      "`--workload scale-ip --batch-sweep 1,64,1024,4096` measures it; its "
+                                      "B_c scoring shapes are measured above under b_scoring_hbm_regime"}
+
     metric_names = {0: "inner product", 1: "squared Euclidean", 2: "cosine"}
     res = {
-        "metric": "queries/sec at recall@10>=0.9 (1 MI355X, batch 10k)",
+        "metric": "queries/sec at recall@10>=0.9 (1 MI355X, batch 10k); HBM GB/s of B_c scoring",
         "value": round(nq * K / elapsed, 1),
         "unit": "queries/s",
         "n_gpus": 1, "steps": K, "warmup": W,
@@ -393,17 +605,21 @@ def main():
                    "rerank": {"f32": "float corpus", "f16": "half-precision copy of the corpus", "none": "no re-ranking step"}[args.rerank]},
         "recall_at_10": None if args.random_index else round(recall, 4),
         "recall_at_10_by_id": None if args.random_index else round(recall_ids, 4),
+        "recall_target_met": None if args.random_index else bool(recall >= 0.9),
         "index": "random factors and codes (timing only)" if args.random_index else "fitted",
         "roofline": roofline, "cpu_baseline": cpu_baseline,
+        "b_scoring_hbm_regime": b_regime,
         "kernels": kernels, "oracle_match": oracle_match,
         "batches_in_flight": n_lanes,
         "with_overlapping_gathers": overlapped,
         "ms_per_step_one_batch_at_a_time": None if args.timed_only else round(elapsed_one_lane / K * 1e3, 4),
+        "queries_per_s_one_batch_at_a_time": None if args.timed_only else round(nq * K / elapsed_one_lane, 1),
         "rerank_avg_ms_one_batch_at_a_time": round(prof_one["rerank"][0] / max(1, prof_one["rerank"][1]), 5) if "rerank" in prof_one else None,
         "ms_per_step_with_events_on_every_kernel": None if args.timed_only else round(elapsed_allev / K * 1e3, 4),
         "fallback_queries_per_step": fallback_queries / K,
         "index_build_s": round(build_s, 1),
         "other_rerank_modes": other_modes,
+        "other_workloads": others,
     }
     if sweep is not None:
         res["batch_sweep"] = sweep

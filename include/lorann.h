@@ -270,7 +270,8 @@ int lorann_search_stages(lorann_index *ix, const float *queries, int64_t nq, int
 /*
  * Per-kernel timing of the searches of one index, taken with HIP events on the index's stream.
  * lorann_profile_enable(ix, 1) starts recording every kernel (and clears the totals), 2 records only the
- * re-rank gather kernel (two events per batch: negligible overhead inside a timed run), 0 stops.
+ * re-rank gather kernel (two events per batch: negligible overhead inside a timed run), 3 only the int8
+ * matrix-core scoring kernel (the B_c product), 0 stops.
  * lorann_profile_get writes up to `cap` records and returns how many kernels exist (or a negative error code).
  */
 typedef struct lorann_kernel_time {
@@ -284,6 +285,13 @@ int lorann_profile_get(lorann_index *ix, lorann_kernel_time *out, int32_t cap);
 /* Number of queries that the batched selection handed to the exact per-query kernel since profiling was
  * enabled (-1 if ix is NULL). */
 int64_t lorann_profile_fallback_queries(lorann_index *ix);
+
+/* Corpus rows the re-rank of the latest batch on lane 0 actually fetched (Sec. 2.2 re-ranking): queries that are
+ * neighbours in the visiting order share candidate rows and a shared row is fetched once per group, so this is
+ * at most nq * m and at least the number of distinct candidate rows of the batch.  Multiply by the row size for the
+ * bytes the gather kernel requests.  Waits for all work on the index.  -1: ix is NULL, or the latest batch did not
+ * take the grouped re-rank. */
+int64_t lorann_profile_gather_rows(lorann_index *ix);
 
 #ifdef __cplusplus
 }

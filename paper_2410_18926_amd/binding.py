@@ -23,7 +23,7 @@ LORANN_OK, LORANN_E_INVAL, LORANN_E_NOMEM, LORANN_E_DEVICE, LORANN_E_UNSUPPORTED
 
 EXPORTS = ["lorann_load_index", "lorann_load_index_file", "lorann_search", "lorann_search_async", "lorann_free_index", "lorann_last_error", "lorann_set_stream",
            "lorann_search_stages", "lorann_profile_enable", "lorann_profile_get", "lorann_set_exact_selection",
-           "lorann_profile_fallback_queries", "lorann_set_rerank", "lorann_set_column_scales", "lorann_set_first_rows", "lorann_search_lane", "lorann_lane_join", "lorann_set_gather_turns", "lorann_search_noalloc"]
+           "lorann_profile_fallback_queries", "lorann_set_rerank", "lorann_set_column_scales", "lorann_set_first_rows", "lorann_search_lane", "lorann_lane_join", "lorann_set_gather_turns", "lorann_search_noalloc", "lorann_profile_gather_rows"]
 NOALLOC_SCRATCH_BYTES = 32 << 20
 LANES = 4
 RERANK_F32, RERANK_F16, RERANK_NONE = 0, 1, 2
@@ -89,6 +89,8 @@ def lib() -> C.CDLL:
         L.lorann_profile_enable.argtypes = [vp, i32]
         L.lorann_profile_fallback_queries.restype = C.c_int64
         L.lorann_profile_fallback_queries.argtypes = [vp]
+        L.lorann_profile_gather_rows.restype = C.c_int64
+        L.lorann_profile_gather_rows.argtypes = [vp]
         L.lorann_profile_get.restype = C.c_int
         L.lorann_profile_get.argtypes = [vp, C.POINTER(_KernelTime), i32]
         _lib = L
@@ -281,6 +283,10 @@ class Index:
 
     def profile_fallback_queries(self) -> int:
         return int(lib().lorann_profile_fallback_queries(self._h))
+
+    def profile_gather_rows(self) -> int:
+        """Rows the grouped re-rank of the latest lane-0 batch fetched (-1: it did not run)."""
+        return int(lib().lorann_profile_gather_rows(self._h))
 
     def profile_get(self) -> dict:
         """{kernel name: (total ms, launches)} since profiling was enabled."""

@@ -103,6 +103,7 @@ struct Workspace {
     hipEvent_t fork = nullptr, join = nullptr;
     hipEvent_t gather_done = nullptr;      // recorded after this lane's latest re-rank gather
     Arena* arena = nullptr;                // set: every buffer is a slice of this fixed region, nothing is allocated or freed
+    int64_t last_ngroups = 0;              // groups of the latest grouped re-rank on this workspace (0: none)
     void release() {
         if (arena) return;
         DevBuf* bufs[] = {&qproj, &qbf, &q8, &dx, &gscore, &sel, &count, &rank_in_bucket, &qrank, &qorder, &qorder2, &off0, &base_tab, &bucket_off, &tile_off,
@@ -605,6 +606,7 @@ int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ
         ga.dist = ws.rdist.as<float>(); ga.cid = ws.rcid.as<int64_t>(); ga.ccount = ws.rccount.as<int32_t>();
         ga.out_ids = d_ids; ga.out_dists = d_dists; ga.nq = (int)nq; ga.d = d; ga.m = m; ga.k = k;
         ga.ht = rerank_group_ht(kGroupQ, m);
+        ws.last_ngroups = ngroups;
         // enough gather blocks to keep every CU evenly busy: about 2 MiB of rows per block at most
         ga.slices = (int)std::min<int64_t>(16, std::max<int64_t>(1, ((int64_t)gm * d * 4 / 2) / (2 << 20) + 1));
         while ((int64_t)ga.slices * ngroups < 4096 && ga.slices < 16) ++ga.slices;
@@ -1189,7 +1191,7 @@ int lorann_profile_enable(lorann_index* ix, int32_t on) {
     if (!ix) return fail(LORANN_E_INVAL, "index is NULL");
     { const int rc = prof_settle(ix); if (rc) return rc; }
     ix->prof_on = on != 0;
-    ix->prof_only = on == 2 ? (int)K_RERANK : -1;
+    ix->prof_only = on == 2 ? (int)K_RERANK : on == 3 ? (int)K_PAIR_MAX : -1;
     if (on) { for (int i = 0; i < K_COUNT; ++i) { ix->prof_ms[i] = 0.0; ix->prof_launches[i] = 0; } ix->prof_fallback_queries = 0; }
     return LORANN_OK;
 }
@@ -1198,6 +1200,18 @@ int64_t lorann_profile_fallback_queries(lorann_index* ix) {
     if (!ix) return -1;
     if (prof_settle(ix) != LORANN_OK) return -1;
     return ix->prof_fallback_queries;
+}
+
+int64_t lorann_profile_gather_rows(lorann_index* ix) {
+    if (!ix) return -1;
+    if (sync_all(ix) != LORANN_OK) return -1;
+    const Workspace& ws = ix->ws[0];
+    if (ws.last_ngroups <= 0 || !ws.u_count.p) return -1;
+    std::vector<int32_t> h((size_t)ws.last_ngroups);
+    if (hipMemcpy(h.data(), ws.u_count.p, h.size() * 4, hipMemcpyDeviceToHost) != hipSuccess) { (void)hipGetLastError(); return -1; }
+    int64_t tot = 0;
+    for (int32_t v : h) tot += v;
+    return tot;
 }
 
 int lorann_profile_get(lorann_index* ix, lorann_kernel_time* out, int32_t cap) {
