@@ -36,7 +36,6 @@ static __device__ __align__(256) unsigned char scratch[LORANN_NOALLOC_SCRATCH_BY
 namespace {
 
 thread_local std::string g_err;
-long long* g_dbg_walk = nullptr;   // TEMPORARY
 
 int fail(int code, const char* fmt, ...) {
     char buf[512];
@@ -99,7 +98,7 @@ struct DevBuf {
 // Device buffers of one search in flight, sized for one chunk of queries, grown on demand.
 struct Workspace {
     DevBuf qproj, qbf, q8, dx, gscore, sel, count, rank_in_bucket, qrank, qorder, qorder2, off0, base_tab, bucket_off, tile_off, unit_off, slot_of_pos, pos_of_slot, Z, sigma, rho0, cand;
-    DevBuf tau, n_kept, fb_list, pmax, cmax, cm_off, cm_base, qkey, u_row, u_mask, u_pos, u_count, rdist, rcid, rccount;
+    DevBuf tau, n_kept, fb_list, pmax, qkey, u_row, u_mask, u_pos, u_count, rdist, rcid, rccount;
     hipStream_t stream = nullptr;          // lanes >= 1: created on first use, default priority
     hipEvent_t fork = nullptr, join = nullptr;
     hipEvent_t gather_done = nullptr;      // recorded after this lane's latest re-rank gather
@@ -108,7 +107,7 @@ struct Workspace {
     void release() {
         if (arena) return;
         DevBuf* bufs[] = {&qproj, &qbf, &q8, &dx, &gscore, &sel, &count, &rank_in_bucket, &qrank, &qorder, &qorder2, &off0, &base_tab, &bucket_off, &tile_off,
-                          &unit_off, &slot_of_pos, &pos_of_slot, &Z, &sigma, &rho0, &cand, &tau, &n_kept, &fb_list, &pmax, &cmax, &cm_off, &cm_base, &qkey, &u_row, &u_mask, &u_pos, &u_count, &rdist, &rcid, &rccount};
+                          &unit_off, &slot_of_pos, &pos_of_slot, &Z, &sigma, &rho0, &cand, &tau, &n_kept, &fb_list, &pmax, &qkey, &u_row, &u_mask, &u_pos, &u_count, &rdist, &rcid, &rccount};
         for (DevBuf* b : bufs) b->release();
         if (fork) (void)hipEventDestroy(fork);
         if (gather_done) (void)hipEventDestroy(gather_done);
@@ -149,7 +148,6 @@ int scratch_of_device(int dev, void** out) {
 struct lorann_index {
     int32_t metric = 0, d = 0, dp = 0, r = 0, r_pad = 0, L = 0;
     int64_t n = 0;
-    int64_t max_cluster = 0;        // points of the largest cluster
     hipStream_t stream = nullptr;
     // index data (device)
     float* centroids = nullptr;     // [L][dp]
@@ -277,7 +275,7 @@ inline bool pair_max_streams(int64_t npairs, int L) { return npairs <= (int64_t)
 
 // S7 on the int8 matrix cores: the best score of every (query, cluster) pair.  With y_off / y (verification) the
 // instantiation that also stores every accumulator is launched instead.
-void launch_pair_max(lorann_index* ix, Workspace& ws, hipStream_t s, int64_t npairs, int64_t cm_cap, const int64_t* y_off, int32_t* y) {
+void launch_pair_max(lorann_index* ix, Workspace& ws, hipStream_t s, int64_t npairs, const int64_t* y_off, int32_t* y) {
     const int L = ix->L;
     const bool l2 = ix->metric == LORANN_L2, mixed = ix->A_first != nullptr;
     const int ks = ix->r_pad / 32;
@@ -286,7 +284,6 @@ void launch_pair_max(lorann_index* ix, Workspace& ws, hipStream_t s, int64_t npa
     sc.bucket_off = ws.bucket_off.as<int32_t>(); sc.unit_off = ws.unit_off.as<int32_t>();
     sc.sqnorm = l2 ? ix->sqnorm : nullptr; sc.pt_scale = ix->sB_pts; sc.pt_first = ix->B_first; sc.rho0 = mixed ? ws.rho0.as<float>() : nullptr; sc.pmax = ws.pmax.as<uint32_t>(); sc.L = L; sc.chunk_tiles = kChunkTiles;
     sc.slot_of_pos = ws.slot_of_pos.as<int32_t>(); sc.y_off = y_off; sc.y = y;
-    sc.cmax = cm_cap > 0 ? ws.cmax.as<uint32_t>() : nullptr; sc.cm_off = ws.cm_off.as<uint32_t>();
     // few pairs per cluster: the kernel streams the codes of the touched clusters, one wavefront per cluster
     const bool stream = pair_max_streams(npairs, L);
     const dim3 gs((unsigned)((L + 3) / 4)), gp(2048);   // persistent shape: 8192 wavefronts stride over the work items
@@ -315,10 +312,9 @@ struct ChunkPlan {
     int group_q;        // queries per re-rank group (0: rows too long to share)
     int nbb;            // blocks of the bucket-count kernel
     int64_t ngroups;
-    int64_t cm_cap;     // entries of the chunk-maxima table (0: none)
 };
 
-ChunkPlan plan_chunk(const lorann_index* ix, int64_t nq, int w, int m, bool fixed_region = false) {
+ChunkPlan plan_chunk(const lorann_index* ix, int64_t nq, int w, int m) {
     ChunkPlan pl;
     const int L = ix->L;
     pl.mixed = ix->A_first != nullptr;      // Sec. 4.2: first component of q' and of every r stay in float
@@ -335,14 +331,6 @@ ChunkPlan plan_chunk(const lorann_index* ix, int64_t nq, int w, int m, bool fixe
     pl.group_q = rerank_group_size(ix->d);
     pl.grouped = ix->rerank_mode != LORANN_RERANK_NONE && m <= 512 && !ix->force_exact && pl.group_q > 0;
     pl.ngroups = pl.grouped ? (nq + pl.group_q - 1) / pl.group_q : 0;
-    // The scoring kernel keeps the best score of every 64-point chunk of every pair's cluster; a pair's row has one
-    // entry per chunk (rounded up to 8).  The table is sized for the batch's pairs times the row of the LARGEST
-    // cluster, but never beyond 1 GiB (2^28 entries; 2^21 in the fixed scratch region): rows are handed out on the
-    // device, and pairs that find the table full go without (the selection then dismisses their cluster as a whole).
-    const int64_t stride = ((ix->max_cluster + kScoreChunk - 1) / kScoreChunk + 7) / 8 * 8;
-    pl.cm_cap = ix->force_exact ? 0 : std::min<int64_t>((int64_t)nq * w * stride, int64_t(1) << 28);
-    if (fixed_region) pl.cm_cap = std::min<int64_t>(pl.cm_cap, int64_t(1) << 21);
-    if (getenv("LORANN_DBG_NOCMAX")) pl.cm_cap = 0;   // TEMPORARY development switch
     return pl;
 }
 
@@ -366,7 +354,6 @@ int reserve_workspace(const lorann_index* ix, Workspace& ws, const ChunkPlan& pl
         {&ws.slot_of_pos, npairs * 4, true}, {&ws.pos_of_slot, npairs * 4, true}, {&ws.Z, npairs * r_pad, true},
         {&ws.sigma, npairs * 4, true}, {&ws.rho0, npairs * 4, pl.mixed}, {&ws.cand, q * m * 4, true},
         {&ws.qbf, q * dp * 2, pl.screen}, {&ws.base_tab, (size_t)2 * pl.nbb * L * 4, pl.lds_hist},
-        {&ws.cmax, (size_t)pl.cm_cap * 4, pl.cm_cap > 0}, {&ws.cm_off, npairs * 4, pl.cm_cap > 0}, {&ws.cm_base, (size_t)L * 4, pl.cm_cap > 0},
         {&ws.tau, q * 4, !ix->force_exact}, {&ws.n_kept, q * 4, !ix->force_exact}, {&ws.fb_list, q * 4, !ix->force_exact},
         {&ws.qkey, q * 4, !ix->force_exact},
         {&ws.u_row, (size_t)pl.ngroups * gm * 4, pl.grouped}, {&ws.u_mask, (size_t)pl.ngroups * gm * 2, pl.grouped},
@@ -393,7 +380,7 @@ int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ
                  float* d_dists, const lorann_stages* st, int64_t q_base, int32_t* fb_total) {
     const int L = ix->L, dp = ix->dp, d = ix->d, r_pad = ix->r_pad;
     const int64_t npairs = nq * w;
-    const ChunkPlan pl = plan_chunk(ix, nq, w, m, ws.arena != nullptr);
+    const ChunkPlan pl = plan_chunk(ix, nq, w, m);
     { const int rc = reserve_workspace(ix, ws, pl, nq, w, m); if (rc) return rc; }
     const bool mixed = pl.mixed;
 
@@ -502,14 +489,13 @@ int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ
     if (!fused_scan) {
         Prof p(ix, K_SCAN, s);
         hipLaunchKernelGGL(k_scan_buckets, dim3((unsigned)((L + 1023) / 1024)), dim3(1024), 0, s, ws.count.as<int32_t>(), ws.count.as<int32_t>() + L, ix->off, L, kUnitShift, kChunkShift, ws.bucket_off.as<int32_t>(),
-                           ws.tile_off.as<int32_t>(), ws.unit_off.as<int32_t>(), ws.off0.as<int32_t>(), pl.cm_cap > 0 ? ws.cm_base.as<int32_t>() : (int32_t*)nullptr);
+                           ws.tile_off.as<int32_t>(), ws.unit_off.as<int32_t>(), ws.off0.as<int32_t>());
     }
     {
         Prof p(ix, K_SCATTER, s);
         ScanArgs sc;
         sc.count = ws.count.as<int32_t>(); sc.count0 = ws.count.as<int32_t>() + L; sc.off = ix->off; sc.unit_shift = kUnitShift; sc.chunk_shift = kChunkShift;
         sc.tile_off = ws.tile_off.as<int32_t>(); sc.unit_off = ws.unit_off.as<int32_t>();
-        sc.cm_off = pl.cm_cap > 0 ? ws.cm_off.as<uint32_t>() : nullptr; sc.cm_cap = pl.cm_cap; sc.cm_base = ws.cm_base.as<int32_t>();
         if (fused_scan)
             hipLaunchKernelGGL(k_scatter_pairs<true>, dim3((unsigned)((npairs + 255) / 256)), dim3(256), 0, s, ws.sel.as<int32_t>(), npairs, w, L, ws.bucket_off.as<int32_t>(),
                                ws.rank_in_bucket.as<int32_t>(), ws.off0.as<int32_t>(), ws.qrank.as<int32_t>(), base_tab, base0_tab, ws.slot_of_pos.as<int32_t>(),
@@ -521,18 +507,16 @@ int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ
     }
     {
         Prof p(ix, K_STAGE_A, s);
-        // about five tiles of 16 pairs per wavefront on average; skewed clusters just loop longer
-        const int64_t avg_tiles = npairs / 16 / L + 1;
-        // ... and with few clusters at least ~1024 blocks, so that a cluster that attracts many pairs is shared out
-        const int64_t by_load = (avg_tiles + 19) / 20, by_count = (1024 + L - 1) / L;
-        const dim3 grid((unsigned)L, (unsigned)std::max<int64_t>(1, std::min<int64_t>(32, std::max(by_load, by_count))));
+        // four tiles of 16 pairs per wavefront, dealt from the list of all clusters' tiles (at most npairs / 16 + L of them)
+        const int tpw = 4;
+        const dim3 grid((unsigned)((npairs / 16 + L + 4 * tpw - 1) / (4 * tpw)));
 #define LAUNCH_SA(RT_, RES_)                                                                                   \
     do {                                                                                                       \
         if (ix->sA_cols) hipLaunchKernelGGL((k_stage_a<RT_, RES_, true>), grid, dim3(256), 0, s, ws.q8.as<int8_t>(), ws.dx.as<float>(), ix->A, ix->sA_cols, ix->sB, \
-                                            ws.bucket_off.as<int32_t>(), ws.slot_of_pos.as<int32_t>(), L, dp, ix->r, w, ws.Z.as<int8_t>(), ws.sigma.as<float>(), \
+                                            ws.bucket_off.as<int32_t>(), ws.tile_off.as<int32_t>(), tpw, (int)(npairs / 16 + L / 2), ws.slot_of_pos.as<int32_t>(), L, dp, ix->r, w, ws.Z.as<int8_t>(), ws.sigma.as<float>(), \
                                             qp, (const float*)ix->A_first, mixed ? ws.rho0.as<float>() : (float*)nullptr); \
         else hipLaunchKernelGGL((k_stage_a<RT_, RES_, false>), grid, dim3(256), 0, s, ws.q8.as<int8_t>(), ws.dx.as<float>(), ix->A, ix->sA, ix->sB, \
-                                ws.bucket_off.as<int32_t>(), ws.slot_of_pos.as<int32_t>(), L, dp, ix->r, w, ws.Z.as<int8_t>(), ws.sigma.as<float>(), \
+                                ws.bucket_off.as<int32_t>(), ws.tile_off.as<int32_t>(), tpw, (int)(npairs / 16 + L / 2), ws.slot_of_pos.as<int32_t>(), L, dp, ix->r, w, ws.Z.as<int8_t>(), ws.sigma.as<float>(), \
                                 (const float*)nullptr, (const float*)nullptr, (float*)nullptr); \
     } while (0)
         if (r_pad == 32) { if (dp <= 256) LAUNCH_SA(2, true); else LAUNCH_SA(2, false); }
@@ -556,21 +540,19 @@ int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ
         const int ks = r_pad / 32;
         {
             Prof p(ix, K_PAIR_MAX, s);
-            launch_pair_max(ix, ws, s, npairs, pl.cm_cap, nullptr, nullptr);
+            launch_pair_max(ix, ws, s, npairs, nullptr, nullptr);
         }
         {
             Prof p(ix, K_SELECT_QUERY, s);
             QuerySelectArgs qa;
             qa.sel = ws.sel.as<int32_t>(); qa.pos_of_slot = ws.pos_of_slot.as<int32_t>(); qa.pmax = ws.pmax.as<uint32_t>();
-            qa.cmax = pl.cm_cap > 0 ? ws.cmax.as<uint32_t>() : nullptr; qa.cm_off = ws.cm_off.as<uint32_t>(); qa.int_domain = (!l2 && !ix->sB_pts) ? 1 : 0;
             qa.Z = ws.Z.as<int8_t>(); qa.sigma = ws.sigma.as<float>(); qa.Bp = ix->Bp; qa.off = ix->off; qa.sqnorm = l2 ? ix->sqnorm : nullptr; qa.pt_scale = ix->sB_pts; qa.pt_first = ix->B_first; qa.rho0 = mixed ? ws.rho0.as<float>() : nullptr;
             qa.cand = ws.cand.as<int32_t>(); qa.tau = ws.tau.as<float>(); qa.n_kept = ws.n_kept.as<int32_t>(); qa.qkey = ws.qkey.as<int32_t>();
             qa.fb_list = ws.fb_list.as<int32_t>(); qa.fb_count = ws.count.as<int32_t>() + 2 * L; qa.qorder = ws.qorder.as<int32_t>(); qa.nq = (int)nq; qa.w = w; qa.m = m; qa.cap = select_query_cap(m);
-            qa.dbg = nullptr;
-            if (getenv("LORANN_DBG_WALK")) { if (!g_dbg_walk) (void)hipMalloc((void**)&g_dbg_walk, (size_t)32768 * 64); long long* dbg_buf = g_dbg_walk; qa.dbg = dbg_buf; (void)hipMemsetAsync(dbg_buf, 0, (size_t)nq * 64, s); }
-            qa.wpad = (w + 63) / 64 * 64;
-            const size_t qlds = select_query_lds(qa.cap, qa.wpad);
-            const dim3 qgrid((unsigned)(512 * ((nq + 511) / 512)));
+            const size_t qlds = (size_t)qa.cap * 8;
+            qa.run_shift = 6;
+            const int64_t round = (int64_t)8 << qa.run_shift;
+            const dim3 qgrid((unsigned)(round * ((nq + round - 1) / round)));
             if (qa.cap == 2048) {
                 if (ks == 1) hipLaunchKernelGGL((k_select_query<2, 2>), qgrid, dim3(256), qlds, s, qa);
                 else hipLaunchKernelGGL((k_select_query<4, 2>), qgrid, dim3(256), qlds, s, qa);
@@ -689,16 +671,6 @@ int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ
 #undef LAUNCH_RR
     }
     HIP_TRY(hipGetLastError());
-    if (getenv("LORANN_DBG_WALK") && st) {
-        (void)hipStreamSynchronize(s);
-        static long long* dbg_buf2 = nullptr;
-        std::vector<long long> h((size_t)nq * 8);
-        // the buffer pointer lives in the block above: re-derive through a second static is not possible, so read via symbol below
-        if (g_dbg_walk) { (void)hipMemcpy(h.data(), g_dbg_walk, h.size() * 8, hipMemcpyDeviceToHost);
-            double sum[8] = {0}; for (int64_t i = 0; i < nq; ++i) for (int j = 0; j < 8; ++j) sum[j] += (double)h[i * 8 + j];
-            fprintf(stderr, "[walk dbg] mean (100MHz ticks): setup %.0f score %.0f compact %.0f | n_win %.1f n_bat %.1f n_flagged %.1f n_compact %.1f | total %.0f\n", sum[0]/nq, sum[1]/nq, sum[2]/nq, sum[3]/nq, sum[4]/nq, sum[5]/nq, sum[6]/nq, sum[7]/nq); }
-        (void)dbg_buf2;
-    }
 
     if (st) {   // export intermediate results (verification only; not part of the timed path)
         HIP_TRY(hipStreamSynchronize(s));
@@ -754,7 +726,7 @@ int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ
             (void)hipMemcpy(d_yo, yo.data(), (size_t)(npairs + 1) * 8, hipMemcpyHostToDevice);
             // batched selection: the accumulators come from the matrix-core kernel itself (its storing instantiation,
             // same launch shape as the timed one); exact selection forced: from the point-by-point kernel
-            if (!ix->force_exact) launch_pair_max(ix, ws, s, npairs, pl.cm_cap, d_yo, d_y);
+            if (!ix->force_exact) launch_pair_max(ix, ws, s, npairs, d_yo, d_y);
             else if (r_pad == 32) hipLaunchKernelGGL(k_dump_pair_scores<2>, dim3((unsigned)npairs), dim3(256), 0, s, ws.sel.as<int32_t>(), ws.pos_of_slot.as<int32_t>(), ws.Z.as<int8_t>(), ix->Bp, ix->off, d_yo, d_y);
             else hipLaunchKernelGGL(k_dump_pair_scores<4>, dim3((unsigned)npairs), dim3(256), 0, s, ws.sel.as<int32_t>(), ws.pos_of_slot.as<int32_t>(), ws.Z.as<int8_t>(), ix->Bp, ix->off, d_yo, d_y);
             e = hipStreamSynchronize(s);
@@ -825,7 +797,7 @@ int search_impl(lorann_index* ix, const float* queries, int64_t nq, int32_t k, i
         HIP_TRY(hipGetDevice(&cur));
         if (cur != ix->device) return fail(LORANN_E_INVAL, "the index lives on device %d, the current device is %d", ix->device, cur);
         const int64_t cn = std::min(chunk, nq);
-        const ChunkPlan pl = plan_chunk(ix, cn, w, m, true);
+        const ChunkPlan pl = plan_chunk(ix, cn, w, m);
         if ((rc0 = reserve_workspace(ix, ws, pl, cn, w, m))) return rc0;
     }
     if (lane > 0) {     // the lane starts after what the index's stream holds now (the caller's queries)
@@ -905,11 +877,8 @@ int lorann_load_index(lorann_index** out, int32_t metric, int64_t n, int32_t d, 
         memcpy(off.data(), cluster_offsets, (size_t)(L + 1) * 8);
     }
     if (off[0] != 0 || off[L] != n) return fail(LORANN_E_INVAL, "cluster_offsets must start at 0 and end at n");
-    int64_t max_cluster = 0;
-    for (int c = 0; c < L; ++c) {
+    for (int c = 0; c < L; ++c)
         if (off[c + 1] < off[c]) return fail(LORANN_E_INVAL, "cluster_offsets decrease at cluster %d", c);
-        max_cluster = std::max(max_cluster, off[c + 1] - off[c]);
-    }
 
     {   // absmax step sizes are non-negative by construction; the integer-domain score comparisons rely on it
         std::vector<float> sc(2 * (size_t)L);
@@ -941,7 +910,6 @@ int lorann_load_index(lorann_index** out, int32_t metric, int64_t n, int32_t d, 
         ix->fixed_arena.cap = LORANN_NOALLOC_SCRATCH_BYTES;
         ix->ws_fixed.arena = &ix->fixed_arena;
     }
-    ix->max_cluster = max_cluster;
     ix->metric = metric; ix->n = n; ix->d = d; ix->dp = dp; ix->r = r; ix->L = L;
     ix->r_pad = r <= 32 ? 32 : 64;
     int rc = LORANN_OK;

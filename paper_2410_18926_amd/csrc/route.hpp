@@ -357,72 +357,56 @@ __global__ __launch_bounds__(256) void k_bucket_count_global(const int32_t* __re
 // grid = ceil(L / 1024), block = 1024: block b scans clusters [1024 b, 1024 b + 1024) and first adds up, on its
 // own, everything that precedes them (at most L - 1024 independent loads spread over its threads), so the blocks
 // need no communication and none of them waits for another.
-// Sum of two non-negative ints that stops at INT_MAX (the chunk-maxima table offsets may exceed any table: everything
-// beyond the table's size only has to stay beyond it).
-__device__ __forceinline__ int sat_add(int a, int b) { return (int)min((unsigned)a + (unsigned)b, 0x7fffffffu); }
-// Entries a cluster's pairs take in the chunk-maxima table: one per 64 points, rounded up to 8, per pair.
-__device__ __forceinline__ int cm_row(int m_c) { return (((m_c + 63) >> 6) + 7) & ~7; }
-__device__ __forceinline__ int cm_need(int pairs, int m_c) { return (int)min((long long)pairs * cm_row(m_c), 0x7fffffffll); }
-
 __global__ __launch_bounds__(1024) void k_scan_buckets(const int32_t* __restrict__ count, const int32_t* __restrict__ count0,
                                                         const int64_t* __restrict__ off, int L, int unit_shift, int chunk_shift,
                                                         int32_t* __restrict__ bucket_off, int32_t* __restrict__ tile_off,
-                                                        int32_t* __restrict__ unit_off, int32_t* __restrict__ off0,
-                                                        int32_t* __restrict__ cm_base) {
-    constexpr int NF = 5;
-    __shared__ int wtot[NF][16], wpre[NF][16];
+                                                        int32_t* __restrict__ unit_off, int32_t* __restrict__ off0) {
+    __shared__ int wtot[4][16], wpre[4][16];
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int c0 = blockIdx.x * 1024;
-    auto fields = [&](int c, int (&f)[NF]) {         // c < L
+    auto fields = [&](int c, int (&f)[4]) {         // c < L
         const int a = count[c];
         const int m_c = (int)(off[c + 1] - off[c]);
         f[0] = a; f[1] = (a + 15) >> 4;
         f[2] = ((a + (1 << unit_shift) - 1) >> unit_shift) * ((m_c + (1 << chunk_shift) - 1) >> chunk_shift);
         f[3] = count0[c];
-        f[4] = cm_need(a, m_c);
     };
-    int pre[NF] = {0, 0, 0, 0, 0};                  // this thread's share of the clusters before c0
+    int pre[4] = {0, 0, 0, 0};                      // this thread's share of the clusters before c0
 #pragma unroll 8
     for (int c = tid; c < c0; c += 1024) {
-        int f[NF];
+        int f[4];
         fields(c, f);
 #pragma unroll
-        for (int k = 0; k < NF; ++k) pre[k] = k == 4 ? sat_add(pre[k], f[k]) : pre[k] + f[k];
+        for (int k = 0; k < 4; ++k) pre[k] += f[k];
     }
     const int c = c0 + tid;
-    int v[NF] = {0, 0, 0, 0, 0};
+    int v[4] = {0, 0, 0, 0};
     if (c < L) fields(c, v);
-    int incl[NF];
+    int incl[4];
 #pragma unroll
-    for (int k = 0; k < NF; ++k) {
+    for (int k = 0; k < 4; ++k) {
         int x = v[k], y = pre[k];
 #pragma unroll
         for (int o = 1; o < 64; o <<= 1) {
             const int t = __shfl_up(x, o, 64);
-            if (lane >= o) x = k == 4 ? sat_add(x, t) : x + t;
-            const int u = __shfl_xor(y, o, 64);
-            y = k == 4 ? sat_add(y, u) : y + u;
+            if (lane >= o) x += t;
+            y += __shfl_xor(y, o, 64);
         }
         incl[k] = x;
         if (lane == 63) wtot[k][wv] = x;
         if (lane == 0) wpre[k][wv] = y;
     }
     __syncthreads();
-    int total[NF];
+    int total[4];
 #pragma unroll
-    for (int k = 0; k < NF; ++k) {
+    for (int k = 0; k < 4; ++k) {
         int before = 0, tot = 0;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int t = wtot[k][i], pr = wpre[k][i];
-            if (k == 4) { if (i < wv) before = sat_add(before, t); tot = sat_add(tot, sat_add(t, pr)); before = sat_add(before, pr); }
-            else { if (i < wv) before += t; tot += t + pr; before += pr; }
-        }
-        // exclusive, including everything before this block (saturating: subtract only where nothing saturated)
-        incl[k] = k == 4 ? (sat_add(incl[k], before) == 0x7fffffff ? 0x7fffffff : incl[k] + before - v[k]) : incl[k] + before - v[k];
+        for (int i = 0; i < 16; ++i) { const int t = wtot[k][i]; if (i < wv) before += t; tot += t + wpre[k][i]; before += wpre[k][i]; }
+        incl[k] += before - v[k];                   // exclusive, including everything before this block
         total[k] = tot;
     }
-    if (c < L) { bucket_off[c] = incl[0]; tile_off[c] = incl[1]; unit_off[c] = incl[2]; off0[c] = incl[3]; if (cm_base) cm_base[c] = incl[4]; }
+    if (c < L) { bucket_off[c] = incl[0]; tile_off[c] = incl[1]; unit_off[c] = incl[2]; off0[c] = incl[3]; }
     if (blockIdx.x == gridDim.x - 1 && tid == 0) { bucket_off[L] = total[0]; tile_off[L] = total[1]; unit_off[L] = total[2]; }
 }
 
@@ -437,11 +421,6 @@ struct ScanArgs {
     const int32_t* count; const int32_t* count0; const int64_t* off;
     int unit_shift, chunk_shift;      // log2 of the pairs and of the points of a scoring work item
     int32_t* tile_off; int32_t* unit_off;
-    // Rows of the chunk-maxima table (one entry per 64 points of the pair's cluster, rounded up to a multiple of 8
-    // entries): the rows of a cluster's pairs follow each other, the clusters follow each other (cm_base: scan above).
-    uint32_t* cm_off;                 // out [npairs] by bucket position: first entry of the pair's row, or ~0u (beyond the table), or NULL
-    int32_t* cm_base;                 // [L] first entry of each cluster's rows (SCAN: an output, else from k_scan_buckets)
-    long long cm_cap;                 // entries the table holds
 };
 template <bool SCAN>
 __global__ __launch_bounds__(256) void k_scatter_pairs(const int32_t* __restrict__ sel, int64_t npairs, int w, int L,
@@ -450,12 +429,11 @@ __global__ __launch_bounds__(256) void k_scatter_pairs(const int32_t* __restrict
                                                         const int32_t* __restrict__ base_tab, const int32_t* __restrict__ base0_tab,
                                                         int32_t* __restrict__ slot_of_pos, int32_t* __restrict__ pos_of_slot,
                                                         uint32_t* __restrict__ pmax, int32_t* __restrict__ qorder, ScanArgs sc) {
-    __shared__ int s_boff[SCAN ? 1024 : 1], s_off0[SCAN ? 1024 : 1], s_cm[SCAN ? 1024 : 1];
-    __shared__ int wtot[5][4];
+    __shared__ int s_boff[SCAN ? 1024 : 1], s_off0[SCAN ? 1024 : 1];
+    __shared__ int wtot[4][4];
     if (SCAN) {
-        constexpr int NF = 5;
         const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-        int f[4][NF], tot[NF] = {0, 0, 0, 0, 0};              // thread t owns clusters 4t .. 4t+3
+        int f[4][4], tot[4] = {0, 0, 0, 0};                   // thread t owns clusters 4t .. 4t+3
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int c = min(4 * tid + j, L - 1);
@@ -466,43 +444,37 @@ __global__ __launch_bounds__(256) void k_scatter_pairs(const int32_t* __restrict
             f[j][1] = in ? (a + 15) >> 4 : 0;
             f[j][2] = in ? ((a + (1 << sc.unit_shift) - 1) >> sc.unit_shift) * ((m_c + (1 << sc.chunk_shift) - 1) >> sc.chunk_shift) : 0;
             f[j][3] = in ? sc.count0[c] : 0;
-            f[j][4] = in ? cm_need(a, m_c) : 0;
 #pragma unroll
-            for (int k = 0; k < NF; ++k) tot[k] = k == 4 ? sat_add(tot[k], f[j][k]) : tot[k] + f[j][k];
+            for (int k = 0; k < 4; ++k) tot[k] += f[j][k];
         }
-        int incl[NF];
+        int incl[4];
 #pragma unroll
-        for (int k = 0; k < NF; ++k) {
+        for (int k = 0; k < 4; ++k) {
             int x = tot[k];
 #pragma unroll
-            for (int o = 1; o < 64; o <<= 1) { const int t = __shfl_up(x, o, 64); if (lane >= o) x = k == 4 ? sat_add(x, t) : x + t; }
+            for (int o = 1; o < 64; o <<= 1) { const int t = __shfl_up(x, o, 64); if (lane >= o) x += t; }
             incl[k] = x;
             if (lane == 63) wtot[k][wv] = x;
         }
         __syncthreads();
-        int run[NF], total[NF];
+        int run[4], total[4];
 #pragma unroll
-        for (int k = 0; k < NF; ++k) {
+        for (int k = 0; k < 4; ++k) {
             int before = 0, all = 0;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int t = wtot[k][i];
-                if (k == 4) { if (i < wv) before = sat_add(before, t); all = sat_add(all, t); }
-                else { if (i < wv) before += t; all += t; }
-            }
-            // exclusive prefix of this thread's first cluster
-            run[k] = k == 4 ? (sat_add(incl[k], before) == 0x7fffffff ? 0x7fffffff : incl[k] - tot[k] + before) : incl[k] - tot[k] + before;
+            for (int i = 0; i < 4; ++i) { const int t = wtot[k][i]; if (i < wv) before += t; all += t; }
+            run[k] = incl[k] - tot[k] + before;                 // exclusive prefix of this thread's first cluster
             total[k] = all;
         }
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int c = 4 * tid + j;
             if (c < L) {
-                s_boff[c] = run[0]; s_off0[c] = run[3]; s_cm[c] = run[4];
+                s_boff[c] = run[0]; s_off0[c] = run[3];
                 if (blockIdx.x == 0) { bucket_off[c] = run[0]; sc.tile_off[c] = run[1]; sc.unit_off[c] = run[2]; off0[c] = run[3]; }
             }
 #pragma unroll
-            for (int k = 0; k < NF; ++k) run[k] = k == 4 ? sat_add(run[k], f[j][k]) : run[k] + f[j][k];
+            for (int k = 0; k < 4; ++k) run[k] += f[j][k];
         }
         if (blockIdx.x == 0 && tid == 0) { bucket_off[L] = total[0]; sc.tile_off[L] = total[1]; sc.unit_off[L] = total[2]; }
         __syncthreads();
@@ -512,17 +484,11 @@ __global__ __launch_bounds__(256) void k_scatter_pairs(const int32_t* __restrict
     const int c = sel[p];
     const int q = (int)(p / w);
     const size_t tb = (size_t)(q / kBucketQueries) * L + c;
-    const int boff = SCAN ? s_boff[c] : bucket_off[c];
-    const int pos = boff + (base_tab ? base_tab[tb] : 0) + rank_in_bucket[p];
+    const int pos = (SCAN ? s_boff[c] : bucket_off[c]) + (base_tab ? base_tab[tb] : 0) + rank_in_bucket[p];
     slot_of_pos[pos] = (int32_t)p;
     pos_of_slot[p] = pos;
     pmax[p] = 0u;
     if (p % w == 0) qorder[(SCAN ? s_off0[c] : off0[c]) + (base0_tab ? base0_tab[tb] : 0) + qrank[q]] = q;
-    if (sc.cm_off) {
-        const long long row = cm_row((int)(sc.off[c + 1] - sc.off[c]));
-        const long long at = (long long)(SCAN ? s_cm[c] : sc.cm_base[c]) + (long long)(pos - boff) * row;
-        sc.cm_off[pos] = at + row <= sc.cm_cap ? (uint32_t)at : ~0u;
-    }
 }
 
 __global__ void k_zero_i32(int32_t* __restrict__ p, int64_t n) {

@@ -42,9 +42,22 @@ __device__ __forceinline__ int find_bucket_wave(const int32_t* __restrict__ off,
     return lo;
 }
 
-// grid = (L, slices), block = 256.  Block (c, y) serves cluster c: its wavefronts take the cluster's 16-pair tiles
-// 4 y + wv, 4 y + wv + 4 slices, ...  (no search for the cluster of a tile; clusters without pairs cost one scalar
-// load).  A_c stays in registers across the tiles of a wavefront when d' <= 256.
+// The same search started from a guess: if t lies within the 63 buckets from c_guess - 31 on, ONE round of probes
+// finds it (buckets of similar size make an interpolated guess land that close); otherwise the full search runs.
+__device__ __forceinline__ int find_bucket_near(const int32_t* __restrict__ off, int L, int t, int c_guess) {
+    const int lane = threadIdx.x & 63;
+    const int lo = max(0, min(c_guess - 31, L - 63));
+    const int probe = min(lo + lane, L);
+    const int n = __popcll(__ballot(off[probe] <= t));     // off is non-decreasing: the first n probes are <= t
+    if (n >= 1 && n <= 63 && lo + n <= L) return lo + n - 1;     // off[lo + n - 1] <= t < off[lo + n]
+    return find_bucket_wave(off, L, t);
+}
+
+// grid = ceil((npairs / 16 + L) / (4 * tpw)) blocks of 256: the 16-pair tiles of all clusters form one list
+// (tile_off: tiles before each cluster) and every wavefront takes tpw consecutive tiles of it, so the work per
+// wavefront is the same however unevenly the pairs are spread over the clusters; a wavefront whose tiles span
+// several clusters serves them one after the other.  A_c stays in registers across the tiles of one cluster when
+// d' <= 256.
 // RT = r_pad / 16 result tiles (2 or 4); RES: d' <= 256, A_c resident.  A is [L][r][dp]; Z is [npairs][r_pad] in
 // bucket order.
 // COLS: column-wise quantization (Sec. 3.3 as printed) - sA is [L][r], one step size per column of A_c; the float
@@ -57,17 +70,26 @@ template <int RT, bool RES, bool COLS = false>
 __global__ __launch_bounds__(256) void k_stage_a(const int8_t* __restrict__ q8, const float* __restrict__ dx,
                                                   const int8_t* __restrict__ A, const float* __restrict__ sA,
                                                   const float* __restrict__ sB, const int32_t* __restrict__ bucket_off,
+                                                  const int32_t* __restrict__ tile_off, int tpw, int tiles_guess,
                                                   const int32_t* __restrict__ slot_of_pos,
                                                   int L, int dp, int r, int w, int8_t* __restrict__ Z, float* __restrict__ sigma,
                                                   const float* __restrict__ qproj = nullptr, const float* __restrict__ A_first = nullptr,
                                                   float* __restrict__ rho0 = nullptr) {
     const int lane = threadIdx.x & 63;
-    const int c = blockIdx.x;
-    const int pbeg = bucket_off[c], end = bucket_off[c + 1];
-    const int ntiles = (end - pbeg + 15) >> 4;
-    const int first = blockIdx.y * 4 + __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    if (first >= ntiles) return;                       // wavefronts are independent: no block barrier below
     const int i = lane & 15, g = lane >> 4;
+    // this wavefront's tiles [g0, g1) of the list of all tiles; wavefronts are independent: no block barrier below
+    const int gw = (int)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    int g0 = gw * tpw;
+    const int g1 = min(g0 + tpw, tile_off[L]);
+    if (g0 >= g1) return;
+    // (tiles_guess: about how many tiles there are, for the first guess of the cluster that holds tile g0)
+    int c = __builtin_amdgcn_readfirstlane(find_bucket_near(tile_off, L, g0, (int)((long long)g0 * L / max(1, tiles_guess))));
+    for (; g0 < g1; ++c) {                                // clusters this wavefront's tiles belong to
+    const int t_beg = tile_off[c], t_end = c + 1 < L ? tile_off[c + 1] : tile_off[L];
+    if (t_end <= g0) continue;                            // (a cluster without pairs)
+    const int first = g0 - t_beg, last = min(g1, t_end) - t_beg;      // its tiles [first, last) are ours
+    g0 = t_beg + last;
+    const int pbeg = bucket_off[c], end = bucket_off[c + 1];
     const int8_t* Ac = A + (size_t)c * r * dp;
     constexpr int SB = 4;                                // k-steps whose operands are requested together
     const int steps = (dp + 63) >> 6;                    // uniform trip count: the MFMA runs with all lanes on
@@ -93,12 +115,12 @@ __global__ __launch_bounds__(256) void k_stage_a(const int8_t* __restrict__ q8, 
     if constexpr (RES) fetch_a(0, bres);
 
     int slot_next = slot_of_pos[min(pbeg + first * 16 + i, end - 1)];
-    for (int tile = first; tile < ntiles; tile += 4 * gridDim.y) {
+    for (int tile = first; tile < last; ++tile) {
     const int base = pbeg + tile * 16;
     const bool row_ok = base + i < end;
     const int8_t* qrow = q8 + (size_t)(slot_next / w) * dp;
     // the next tile's pair numbers are requested now, its query rows when this tile is done
-    slot_next = slot_of_pos[min(base + 16 * 4 * (int)gridDim.y + i, end - 1)];
+    slot_next = slot_of_pos[min(base + 16 + i, end - 1)];
 
     i32x4 acc[RT];
 #pragma unroll
@@ -196,7 +218,8 @@ __global__ __launch_bounds__(256) void k_stage_a(const int8_t* __restrict__ q8, 
             }
         }
     }
-    }   // tiles of this wavefront
+    }   // tiles of this cluster
+    }   // clusters of this wavefront
 }
 
 }  // namespace lorann
