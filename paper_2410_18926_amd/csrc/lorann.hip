@@ -98,7 +98,7 @@ struct DevBuf {
 // Device buffers of one search in flight, sized for one chunk of queries, grown on demand.
 struct Workspace {
     DevBuf qproj, qbf, q8, dx, gscore, sel, count, rank_in_bucket, qrank, qorder, qorder2, off0, base_tab, bucket_off, tile_off, unit_off, slot_of_pos, pos_of_slot, Z, sigma, rho0, cand;
-    DevBuf tau, n_kept, fb_list, pmax, qkey, u_row, u_mask, u_pos, u_count, rdist, rcid, rccount;
+    DevBuf tau, n_kept, fb_list, pmax, voff, qkey, u_row, u_mask, u_pos, u_count, rdist, rcid, rccount;
     hipStream_t stream = nullptr;          // lanes >= 1: created on first use, default priority
     hipEvent_t fork = nullptr, join = nullptr;
     hipEvent_t gather_done = nullptr;      // recorded after this lane's latest re-rank gather
@@ -107,7 +107,7 @@ struct Workspace {
     void release() {
         if (arena) return;
         DevBuf* bufs[] = {&qproj, &qbf, &q8, &dx, &gscore, &sel, &count, &rank_in_bucket, &qrank, &qorder, &qorder2, &off0, &base_tab, &bucket_off, &tile_off,
-                          &unit_off, &slot_of_pos, &pos_of_slot, &Z, &sigma, &rho0, &cand, &tau, &n_kept, &fb_list, &pmax, &qkey, &u_row, &u_mask, &u_pos, &u_count, &rdist, &rcid, &rccount};
+                          &unit_off, &slot_of_pos, &pos_of_slot, &Z, &sigma, &rho0, &cand, &tau, &n_kept, &fb_list, &pmax, &voff, &qkey, &u_row, &u_mask, &u_pos, &u_count, &rdist, &rcid, &rccount};
         for (DevBuf* b : bufs) b->release();
         if (fork) (void)hipEventDestroy(fork);
         if (gather_done) (void)hipEventDestroy(gather_done);
@@ -264,6 +264,7 @@ int prof_settle(lorann_index* ix) {
 
 int next_pow2(int v) { int p = 1; while (p < v) p <<= 1; return p; }
 
+constexpr int kSmallPathQueries = 64;   // batches up to this size take the query-major path
 constexpr int kNZ = 2;                 // 32-pair tiles per scoring unit
 constexpr int kUnitPairs = 32 * kNZ;
 constexpr int kChunkTiles = 16;       // 32-point tiles per scoring work item
@@ -275,8 +276,8 @@ inline bool pair_max_streams(int64_t npairs, int L) { return npairs <= (int64_t)
 
 // S7 on the int8 matrix cores: the best score of every (query, cluster) pair.  With y_off / y (verification) the
 // instantiation that also stores every accumulator is launched instead.
-void launch_pair_max(lorann_index* ix, Workspace& ws, hipStream_t s, int64_t npairs, const int64_t* y_off, int32_t* y) {
-    const int L = ix->L;
+void launch_pair_max(lorann_index* ix, Workspace& ws, hipStream_t s, int64_t npairs, const int64_t* y_off, int32_t* y, bool small = false) {
+    const int L = small ? (int)npairs : ix->L;       // small batches: every pair is a cluster of its own
     const bool l2 = ix->metric == LORANN_L2, mixed = ix->A_first != nullptr;
     const int ks = ix->r_pad / 32;
     ScoreArgs sc;
@@ -284,8 +285,9 @@ void launch_pair_max(lorann_index* ix, Workspace& ws, hipStream_t s, int64_t npa
     sc.bucket_off = ws.bucket_off.as<int32_t>(); sc.unit_off = ws.unit_off.as<int32_t>();
     sc.sqnorm = l2 ? ix->sqnorm : nullptr; sc.pt_scale = ix->sB_pts; sc.pt_first = ix->B_first; sc.rho0 = mixed ? ws.rho0.as<float>() : nullptr; sc.pmax = ws.pmax.as<uint32_t>(); sc.L = L; sc.chunk_tiles = kChunkTiles;
     sc.slot_of_pos = ws.slot_of_pos.as<int32_t>(); sc.y_off = y_off; sc.y = y;
+    sc.voff = small ? ws.voff.as<int64_t>() : nullptr;
     // few pairs per cluster: the kernel streams the codes of the touched clusters, one wavefront per cluster
-    const bool stream = pair_max_streams(npairs, L);
+    const bool stream = small || pair_max_streams(npairs, L);
     const dim3 gs((unsigned)((L + 3) / 4)), gp(2048);   // persistent shape: 8192 wavefronts stride over the work items
 #define LAUNCH_PM4(KS_, L2_, COLS_, MIX_, DUMP_)                                                                      \
     do {                                                                                                             \
@@ -309,6 +311,7 @@ void launch_pair_max(lorann_index* ix, Workspace& ws, hipStream_t s, int64_t npa
 // What one batch will run, decided before anything is enqueued.
 struct ChunkPlan {
     bool mixed, screen, fused_quant, big_matrix, lds_hist, grouped;
+    bool small;         // query-major path of small batches (no bucketing)
     int group_q;        // queries per re-rank group (0: rows too long to share)
     int nbb;            // blocks of the bucket-count kernel
     int64_t ngroups;
@@ -330,6 +333,10 @@ ChunkPlan plan_chunk(const lorann_index* ix, int64_t nq, int w, int m) {
     pl.nbb = (int)((nq + kBucketQueries - 1) / kBucketQueries);
     pl.group_q = rerank_group_size(ix->d);
     pl.grouped = ix->rerank_mode != LORANN_RERANK_NONE && m <= 512 && !ix->force_exact && pl.group_q > 0;
+    // A few dozen queries: hardly two pairs share a cluster, so the pairs stay in slot order and every launch that only
+    // serves the bucketing is left out (per-cluster step sizes only; the re-rank then runs one query per block).
+    pl.small = nq <= kSmallPathQueries && pl.screen && !pl.mixed && ix->sA_cols == nullptr && ix->rerank_mode != LORANN_RERANK_NONE;
+    if (pl.small) pl.grouped = false;
     pl.ngroups = pl.grouped ? (nq + pl.group_q - 1) / pl.group_q : 0;
     return pl;
 }
@@ -353,7 +360,7 @@ int reserve_workspace(const lorann_index* ix, Workspace& ws, const ChunkPlan& pl
         {&ws.tile_off, (size_t)(L + 1) * 4, true}, {&ws.unit_off, (size_t)(L + 1) * 4, true},
         {&ws.slot_of_pos, npairs * 4, true}, {&ws.pos_of_slot, npairs * 4, true}, {&ws.Z, npairs * r_pad, true},
         {&ws.sigma, npairs * 4, true}, {&ws.rho0, npairs * 4, pl.mixed}, {&ws.cand, q * m * 4, true},
-        {&ws.qbf, q * dp * 2, pl.screen}, {&ws.base_tab, (size_t)2 * pl.nbb * L * 4, pl.lds_hist},
+        {&ws.qbf, q * dp * 2, pl.screen}, {&ws.voff, npairs * 16, pl.small}, {&ws.base_tab, (size_t)2 * pl.nbb * L * 4, pl.lds_hist},
         {&ws.tau, q * 4, !ix->force_exact}, {&ws.n_kept, q * 4, !ix->force_exact}, {&ws.fb_list, q * 4, !ix->force_exact},
         {&ws.qkey, q * 4, !ix->force_exact},
         {&ws.u_row, (size_t)pl.ngroups * gm * 4, pl.grouped}, {&ws.u_mask, (size_t)pl.ngroups * gm * 2, pl.grouped},
@@ -431,12 +438,21 @@ int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ
         {
             Prof p(ix, K_SELECT_W, s);
             ScreenArgs sa;
+            sa.small.Z = nullptr;
             sa.ghat = ws.gscore.as<float>(); sa.qp = qp; sa.centroids = ix->centroids;
             sa.cent_sqnorm = ix->metric == LORANN_L2 ? ix->cent_sqnorm : nullptr; sa.sel = ws.sel.as<int32_t>();
             sa.L = L; sa.dp = dp; sa.w = w; sa.mu_max = ix->mu_max; sa.dmu_max = ix->dmu_max; sa.nrm_max = ix->metric == LORANN_L2 ? ix->nrm_max : 0.0f;
             sa.q8 = fused_quant ? ws.q8.as<int8_t>() : nullptr; sa.dx = ws.dx.as<float>();
             sa.zero = fused_quant ? ws.count.as<int32_t>() : nullptr; sa.nzero = 2 * L + 1;
             const size_t lds = (size_t)dp * 4;
+            if (pl.small) {
+                SmallArgs& sm = sa.small;
+                sm.q8 = ws.q8.as<int8_t>(); sm.dx = ws.dx.as<float>(); sm.A = ix->A; sm.sA = ix->sA; sm.sB = ix->sB; sm.off = ix->off; sm.r = ix->r; sm.r_pad = r_pad;
+                sm.Z = ws.Z.as<int8_t>(); sm.sigma = ws.sigma.as<float>(); sm.pmax = ws.pmax.as<uint32_t>(); sm.pos_of_slot = ws.pos_of_slot.as<int32_t>();
+                sm.slot_of_pos = ws.slot_of_pos.as<int32_t>(); sm.voff = ws.voff.as<int64_t>(); sm.qorder = ws.qorder.as<int32_t>();
+                if (L <= 4096) hipLaunchKernelGGL((k_select_clusters_screen<16, false, true>), dim3((unsigned)nq), dim3(256), lds + dp, s, sa);
+                else hipLaunchKernelGGL((k_select_clusters_screen<64, false, true>), dim3((unsigned)nq), dim3(256), lds + dp, s, sa);
+            } else
             if (L <= 1024) hipLaunchKernelGGL(k_select_clusters_screen_wave<16>, dim3((unsigned)((nq + 3) / 4)), dim3(256), 4 * lds, s, sa, (int)nq);
             else if (L <= 4096) hipLaunchKernelGGL(k_select_clusters_screen<16>, dim3((unsigned)nq), dim3(256), lds, s, sa);
             else if (big_matrix) hipLaunchKernelGGL((k_select_clusters_screen<64, true>), dim3((unsigned)nq), dim3(256), lds, s, sa);
@@ -471,6 +487,7 @@ int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ
             hipLaunchKernelGGL(k_select_clusters, dim3((unsigned)nq), dim3(256), 0, s, ws.gscore.as<float>(), L, w, ws.sel.as<int32_t>());
     }
     }
+    if (!pl.small) {       // (small batches: the selection kernel has done the A stage, pairs stay in slot order)
     const bool lds_hist = pl.lds_hist;
     const int nbb = pl.nbb;
     int32_t* base_tab = lds_hist ? ws.base_tab.as<int32_t>() : nullptr;
@@ -523,6 +540,7 @@ int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ
         else { if (dp <= 256) LAUNCH_SA(4, true); else LAUNCH_SA(4, false); }
 #undef LAUNCH_SA
     }
+    }
     // Scores + candidate selection.  Batched path: pair maxima (MFMA) -> per-query walk over the few clusters whose maximum reaches the running m-th best score; the exact per-query kernel finishes what the batched path cannot.
     const int kGroupQ = pl.group_q;
     const bool grouped = pl.grouped;
@@ -540,7 +558,7 @@ int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ
         const int ks = r_pad / 32;
         {
             Prof p(ix, K_PAIR_MAX, s);
-            launch_pair_max(ix, ws, s, npairs, nullptr, nullptr);
+            launch_pair_max(ix, ws, s, npairs, nullptr, nullptr, pl.small);
         }
         {
             Prof p(ix, K_SELECT_QUERY, s);
@@ -553,7 +571,13 @@ int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ
             qa.run_shift = 6;
             const int64_t round = (int64_t)8 << qa.run_shift;
             const dim3 qgrid((unsigned)(round * ((nq + round - 1) / round)));
-            if (qa.cap == 2048) {
+            if (pl.small && qa.cap == 2048) {
+                if (ks == 1) hipLaunchKernelGGL((k_select_query<2, 2, true>), qgrid, dim3(256), qlds, s, qa);
+                else hipLaunchKernelGGL((k_select_query<4, 2, true>), qgrid, dim3(256), qlds, s, qa);
+            } else if (pl.small) {
+                if (ks == 1) hipLaunchKernelGGL((k_select_query<2, 6, true>), qgrid, dim3(256), qlds, s, qa);
+                else hipLaunchKernelGGL((k_select_query<4, 6, true>), qgrid, dim3(256), qlds, s, qa);
+            } else if (qa.cap == 2048) {
                 if (ks == 1) hipLaunchKernelGGL((k_select_query<2, 2>), qgrid, dim3(256), qlds, s, qa);
                 else hipLaunchKernelGGL((k_select_query<4, 2>), qgrid, dim3(256), qlds, s, qa);
             } else {
@@ -563,7 +587,7 @@ int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ
         }
         sa_.qlist = ws.fb_list.as<int32_t>(); sa_.qcount = ws.count.as<int32_t>() + 2 * L;
         sa_.fb_total = fb_total;      // asynchronous searches being profiled: the count is added up on the device
-        if (!grouped) {               // (the grouped re-rank finishes these queries in the launch that orders the queries)
+        if (!grouped && !pl.small) {  // (the grouped re-rank finishes these queries in the launch that orders the queries; small batches inline)
             Prof p(ix, K_SELECT_M, s);
             const unsigned grid = (unsigned)std::min<int64_t>(nq, 1024);
             if (r_pad == 32) hipLaunchKernelGGL(k_select_exact<2>, dim3(grid), dim3(256), 0, s, sa_, (int)nq);
@@ -726,7 +750,7 @@ int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ
             (void)hipMemcpy(d_yo, yo.data(), (size_t)(npairs + 1) * 8, hipMemcpyHostToDevice);
             // batched selection: the accumulators come from the matrix-core kernel itself (its storing instantiation,
             // same launch shape as the timed one); exact selection forced: from the point-by-point kernel
-            if (!ix->force_exact) launch_pair_max(ix, ws, s, npairs, d_yo, d_y);
+            if (!ix->force_exact) launch_pair_max(ix, ws, s, npairs, d_yo, d_y, pl.small);
             else if (r_pad == 32) hipLaunchKernelGGL(k_dump_pair_scores<2>, dim3((unsigned)npairs), dim3(256), 0, s, ws.sel.as<int32_t>(), ws.pos_of_slot.as<int32_t>(), ws.Z.as<int8_t>(), ix->Bp, ix->off, d_yo, d_y);
             else hipLaunchKernelGGL(k_dump_pair_scores<4>, dim3((unsigned)npairs), dim3(256), 0, s, ws.sel.as<int32_t>(), ws.pos_of_slot.as<int32_t>(), ws.Z.as<int8_t>(), ix->Bp, ix->off, d_yo, d_y);
             e = hipStreamSynchronize(s);

@@ -31,6 +31,8 @@ struct ScoreArgs {
     const float* pt_first;       // [n] unquantized first row of B_c (mixed-precision decomposition) or NULL
     const float* rho0;           // [npairs] bucket order: unquantized first component of each pair's r, or NULL
     uint32_t* pmax;              // out: [npairs] order-preserving key of the pair's best score (0 on entry)
+    const int64_t* voff;         // small batches (STREAM shape only): [L][2] first and end row of "cluster" c, which
+                                 // is then simply pair c (bucket_off is not read: pairs [c, c + 1)); else NULL
     int L;
     int chunk_tiles;             // 32-point tiles per work item
     // verification only (DUMP instantiations): every int32 accumulator of the matrix-core product is written to
@@ -268,10 +270,10 @@ __global__ __launch_bounds__(64 * WPB) void k_pair_max(ScoreArgs a) {
     if (STREAM) {
         // the cluster number is uniform over the wavefront: say so, and its offsets come through scalar loads
         for (int c = blockIdx.x * WPB + __builtin_amdgcn_readfirstlane(wv); c < a.L; c += gridDim.x * WPB) {
-            const int pbeg = a.bucket_off[c], pend = a.bucket_off[c + 1];
+            const int pbeg = a.voff ? c : a.bucket_off[c], pend = a.voff ? c + 1 : a.bucket_off[c + 1];
             if (pbeg == pend) continue;
-            const int64_t row_c = a.off[c];
-            const int m_all = (int)(a.off[c + 1] - row_c);
+            const int64_t row_c = a.voff ? a.voff[2 * c] : a.off[c];
+            const int m_all = (int)((a.voff ? a.voff[2 * c + 1] : a.off[c + 1]) - row_c);
             for (int pb = pbeg; pb < pend; pb += NP) process(pb, pend, row_c, m_all, 0);
         }
     } else {

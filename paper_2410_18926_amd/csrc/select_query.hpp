@@ -103,7 +103,9 @@ struct QuerySelectArgs {
 // Queries are visited grouped by nearest cluster (workgroups are dealt round-robin over the 8 XCDs): queries that
 // score the same cluster run together and share its codes in L2.
 // PT = points a thread scores between two capacity checks = cap / 1024.
-template <int RB, int PT>
+// INLINE_FB (small batches): a query whose survivor list overflows is finished right here by the exact per-query
+// routine instead of being handed to a later launch.
+template <int RB, int PT, bool INLINE_FB = false>
 __global__ __launch_bounds__(256) void k_select_query(QuerySelectArgs a) {
     constexpr int ZW = RB * 4;
     extern __shared__ __align__(16) unsigned char qs_smem[];
@@ -241,6 +243,16 @@ __global__ __launch_bounds__(256) void k_select_query(QuerySelectArgs a) {
     }
 
     int32_t* out = a.cand + (size_t)q * m;
+    if (overflow && INLINE_FB) {       // uniform
+        if (tid == 0) { a.n_kept[q] = -1; a.tau[q] = key_to_float(T); a.qkey[q] = 0; }
+        SelectArgs sa;
+        sa.qlist = nullptr; sa.qcount = nullptr; sa.sel = a.sel; sa.pos_of_slot = a.pos_of_slot; sa.Z = a.Z; sa.sigma = a.sigma;
+        sa.Bp = a.Bp; sa.off = a.off; sa.sqnorm = a.sqnorm; sa.pt_scale = a.pt_scale; sa.pt_first = a.pt_first; sa.rho0 = a.rho0;
+        sa.cand = a.cand; sa.fb_total = nullptr; sa.w = w; sa.m = m;
+        __syncthreads();
+        select_exact_query<RB>(sa, q);
+        return;
+    }
     if (overflow) {
         if (tid == 0) {
             a.fb_list[atomicAdd(a.fb_count, 1)] = q; a.n_kept[q] = -1; a.tau[q] = key_to_float(T);

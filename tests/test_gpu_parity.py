@@ -75,6 +75,20 @@ def _stagewise(B, wl, ix, queries, k=None, w=None, m=None, device_inputs=True):
     np.testing.assert_array_equal(p_d, g_d)
     np.testing.assert_array_equal(p_ids2, p_ids)
     np.testing.assert_array_equal(p_d2, p_d)
+    if nq <= 64:
+        # batches of up to 64 queries take the query-major path (no bucketing); the same queries three times over
+        # form a batch that takes the cluster-batched path: every copy must come out the same
+        reps = 64 // nq + 1
+        t_in = torch.from_numpy(np.tile(queries, (reps, 1))).cuda() if device_inputs else np.tile(queries, (reps, 1))
+        t_ids, t_d, tst = gix.search_stages(t_in, k, w, m)
+        for rep in range(reps):
+            sl = slice(rep * nq, (rep + 1) * nq)
+            np.testing.assert_array_equal(t_ids[sl], g_ids, err_msg=f"{tag}: cluster-batched path, copy {rep}")
+            np.testing.assert_array_equal(t_d[sl], g_d)
+            np.testing.assert_array_equal(tst["z"][sl], gst["z"])
+            np.testing.assert_array_equal(tst["sigma"][sl], gst["sigma"])
+            np.testing.assert_array_equal(tst["pmax"][sl], gst["pmax"])
+            np.testing.assert_array_equal(np.sort(tst["cand_rows"][sl], axis=1), np.sort(gst["cand_rows"], axis=1))
     gix.close()
     return n_tie
 
@@ -250,7 +264,7 @@ def test_survivor_overflow_falls_back_to_exact_kernel(B):
               A=rng.integers(-127, 128, size=(L, r, d)).astype(np.int8), B=np.ones((n, r), np.int8),
               scale_A=np.full(L, 0.01, np.float32), scale_B=np.full(L, 0.02, np.float32),
               cluster_offsets=np.array([0, 3000, 5000, 5000, n], np.int64), corpus=corpus, ids=None)
-    q = rng.normal(size=(40, d)).astype(np.float32)
+    q = rng.normal(size=(80, d)).astype(np.float32)          # (more than 64: the cluster-batched path)
     gix = B.Index(**ix)
     oix = O.OracleIndex(ix)
     for (k, w, m) in [(10, 3, 64), (5, 4, 200)]:
@@ -258,6 +272,12 @@ def test_survivor_overflow_falls_back_to_exact_kernel(B):
         g_ids, g_d, gst = gix.search_stages(q, k, w, m)
         np.testing.assert_array_equal(np.sort(gst["cand_rows"].astype(np.int64), axis=1), np.sort(ost["cand_rows"], axis=1))
         assert_topk_equal(g_ids, g_d, o_ids, o_d, "overflow")
+        # a small batch finishes such queries inside its selection kernel
+        s_ids, s_d, sst = gix.search_stages(q[:40], k, w, m)
+        assert (sst["n_survivors"] == -1).any()
+        np.testing.assert_array_equal(np.sort(sst["cand_rows"].astype(np.int64), axis=1), np.sort(ost["cand_rows"][:40], axis=1))
+        np.testing.assert_array_equal(s_ids, g_ids[:40])
+        np.testing.assert_array_equal(s_d, g_d[:40])
     # the count of queries finished by the per-query kernel, from synchronous, asynchronous and lane searches
     n_fb = int((gix.search_stages(q, 10, 3, 64)[2]["n_survivors"] == -1).sum())
     assert n_fb > 0
@@ -265,7 +285,7 @@ def test_survivor_overflow_falls_back_to_exact_kernel(B):
     gix.search(q, 10, 3, 64)
     assert gix.profile_fallback_queries() == n_fb
     qd = torch.from_numpy(q).cuda()
-    outs = [(torch.empty((40, 10), dtype=torch.int64, device="cuda"), torch.empty((40, 10), dtype=torch.float32, device="cuda")) for _ in range(3)]
+    outs = [(torch.empty((80, 10), dtype=torch.int64, device="cuda"), torch.empty((80, 10), dtype=torch.float32, device="cuda")) for _ in range(3)]
     gix.search(qd, 10, 3, 64, out=outs[0], lane=1)
     gix.search(qd, 10, 3, 64, out=outs[1], lane=2)
     gix.search(qd, 10, 3, 64, out=outs[2], asynchronous=True)
@@ -285,10 +305,11 @@ def test_mixed_batch_some_queries_fall_back(B, small_indexes):
     gix = B.Index.from_arrays(ix.to("cuda"))
     for (k, w, m) in [(10, 2, 70), (10, 1, 40), (10, 3, 1000), (10, wl.L, 2900), (3, 4, 31)]:
         o_ids, o_d, ost = O.search(oix, queries, k, w, m, stages=True)
-        g_ids, g_d, gst = gix.search_stages(queries, k, w, m)
-        np.testing.assert_array_equal(np.sort(gst["cand_rows"].astype(np.int64), axis=1), np.sort(ost["cand_rows"], axis=1),
-                                      err_msg=f"k={k} w={w} m={m}")
-        assert_topk_equal(g_ids, g_d, o_ids, o_d, f"k={k} w={w} m={m}")
+        for reps in (1, 2):          # 40 queries: the query-major path of small batches; 80: the cluster-batched path
+            g_ids, g_d, gst = gix.search_stages(np.tile(queries, (reps, 1)), k, w, m)
+            np.testing.assert_array_equal(np.sort(gst["cand_rows"][:len(queries)].astype(np.int64), axis=1), np.sort(ost["cand_rows"], axis=1),
+                                          err_msg=f"k={k} w={w} m={m} reps={reps}")
+            assert_topk_equal(g_ids[:len(queries)], g_d[:len(queries)], o_ids, o_d, f"k={k} w={w} m={m} reps={reps}")
     gix.close()
 
 
@@ -378,6 +399,51 @@ def test_full_size_benchmark_configuration_sampled_parity(B, workload, scheme, n
     del ix
     torch.cuda.empty_cache()
     _sampled_full_size_parity(B, gix, a, queries, wl.k, wl.w, wl.m, n_sample, f"{workload} full size, {scheme}", mixed=(scheme == "mixed"))
+    gix.close()
+
+
+@pytest.mark.parametrize("metric", [0, 1, 2])
+@pytest.mark.parametrize("nq", [1, 2, 17, 64])
+def test_small_batches_take_the_query_major_path(B, nq, metric):
+    """Batches of up to 64 queries skip the bucketing: the block that selects a query's clusters also forms the
+    first 8-bit product and re-quantizes it for the query's pairs, every pair is scored as a cluster of its own, a
+    query whose survivor list overflows is finished in place, and the re-rank runs one query per block.  L = 16384
+    clusters, w = 64, d' = 192, r = 32, m = 200 as in the 10M-point workload (150 000 points here), the three
+    metrics; every stage against the oracle, and the same queries inside a larger batch (the cluster-batched
+    path) give the same bits."""
+    rng = np.random.default_rng(900 + 10 * metric + nq)
+    ix = _random_index(rng, n=150_000, d=384, L=16384, r=32, metric=metric, dp=192)
+    q = rng.normal(size=(nq, 384)).astype(np.float32)
+    k, w, m = 10, 64, 200
+    gix = B.Index(**ix)
+    oix = O.OracleIndex(ix)
+    o_ids, o_d, ost = O.search(oix, q, k, w, m, stages=True)
+    yo = y_offsets(ost["sel"], ix["cluster_offsets"])
+    g_ids, g_d, gst = gix.search_stages(q, k, w, m, y_off=yo)
+    for key in ("qproj", "q8", "dx", "sel", "z", "sigma"):
+        np.testing.assert_array_equal(gst[key], ost[key], err_msg=key)
+    np.testing.assert_array_equal(gst["pmax"], ost["pair_best"], err_msg="per-pair best scores")
+    y_ref = np.concatenate([O.pair_accumulators(ost["z"][s_ // w, s_ % w], ix["B"][ix["cluster_offsets"][c]:ix["cluster_offsets"][c + 1]])
+                            for s_, c in enumerate(ost["sel"].reshape(-1))]) if yo[-1] else np.zeros(0, np.int32)
+    np.testing.assert_array_equal(gst["y"], y_ref, err_msg="int32 accumulators")
+    np.testing.assert_array_equal(np.sort(gst["cand_rows"].astype(np.int64), axis=1), np.sort(ost["cand_rows"], axis=1), err_msg="candidates")
+    assert_topk_equal(g_ids, g_d, o_ids, o_d, f"nq={nq} metric={metric}", abs_tol=rounding_abs_tol(q, ix["corpus"], metric),
+                      exact=oracle_distance_of(ix, q))
+    big = np.concatenate([q, rng.normal(size=(70, 384)).astype(np.float32)])
+    b_ids, b_d = gix.search(big, k, w, m)
+    np.testing.assert_array_equal(b_ids[:nq], g_ids)
+    np.testing.assert_array_equal(b_d[:nq], g_d)
+    # device pointers, the asynchronous entry point and the one that allocates nothing
+    qd = torch.from_numpy(q).cuda()
+    for entry in ("async", "noalloc"):
+        out = (torch.empty((nq, k), dtype=torch.int64, device="cuda"), torch.empty((nq, k), dtype=torch.float32, device="cuda"))
+        if entry == "async":
+            gix.search(qd, k, w, m, out=out, asynchronous=True)
+        else:
+            gix.search_noalloc(qd, k, w, m, out=out)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(out[0].cpu().numpy(), g_ids, err_msg=entry)
+        np.testing.assert_array_equal(out[1].cpu().numpy(), g_d, err_msg=entry)
     gix.close()
 
 
