@@ -23,6 +23,7 @@
 #include "screen.hpp"
 #include "select_exact.hpp"
 #include "select_query.hpp"
+#include "small_batch.hpp"
 #include "stage_a.hpp"
 
 using namespace lorann;
@@ -334,9 +335,8 @@ ChunkPlan plan_chunk(const lorann_index* ix, int64_t nq, int w, int m) {
     pl.group_q = rerank_group_size(ix->d);
     pl.grouped = ix->rerank_mode != LORANN_RERANK_NONE && m <= 512 && !ix->force_exact && pl.group_q > 0;
     // A few dozen queries: hardly two pairs share a cluster, so the pairs stay in slot order and every launch that only
-    // serves the bucketing is left out (per-cluster step sizes only; the re-rank then runs one query per block).
+    // serves the bucketing is left out (per-cluster step sizes only).
     pl.small = nq <= kSmallPathQueries && pl.screen && !pl.mixed && ix->sA_cols == nullptr && ix->rerank_mode != LORANN_RERANK_NONE;
-    if (pl.small) pl.grouped = false;
     pl.ngroups = pl.grouped ? (nq + pl.group_q - 1) / pl.group_q : 0;
     return pl;
 }
@@ -438,21 +438,12 @@ int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ
         {
             Prof p(ix, K_SELECT_W, s);
             ScreenArgs sa;
-            sa.small.Z = nullptr;
             sa.ghat = ws.gscore.as<float>(); sa.qp = qp; sa.centroids = ix->centroids;
             sa.cent_sqnorm = ix->metric == LORANN_L2 ? ix->cent_sqnorm : nullptr; sa.sel = ws.sel.as<int32_t>();
             sa.L = L; sa.dp = dp; sa.w = w; sa.mu_max = ix->mu_max; sa.dmu_max = ix->dmu_max; sa.nrm_max = ix->metric == LORANN_L2 ? ix->nrm_max : 0.0f;
             sa.q8 = fused_quant ? ws.q8.as<int8_t>() : nullptr; sa.dx = ws.dx.as<float>();
             sa.zero = fused_quant ? ws.count.as<int32_t>() : nullptr; sa.nzero = 2 * L + 1;
             const size_t lds = (size_t)dp * 4;
-            if (pl.small) {
-                SmallArgs& sm = sa.small;
-                sm.q8 = ws.q8.as<int8_t>(); sm.dx = ws.dx.as<float>(); sm.A = ix->A; sm.sA = ix->sA; sm.sB = ix->sB; sm.off = ix->off; sm.r = ix->r; sm.r_pad = r_pad;
-                sm.Z = ws.Z.as<int8_t>(); sm.sigma = ws.sigma.as<float>(); sm.pmax = ws.pmax.as<uint32_t>(); sm.pos_of_slot = ws.pos_of_slot.as<int32_t>();
-                sm.slot_of_pos = ws.slot_of_pos.as<int32_t>(); sm.voff = ws.voff.as<int64_t>(); sm.qorder = ws.qorder.as<int32_t>();
-                if (L <= 4096) hipLaunchKernelGGL((k_select_clusters_screen<16, false, true>), dim3((unsigned)nq), dim3(256), lds + dp, s, sa);
-                else hipLaunchKernelGGL((k_select_clusters_screen<64, false, true>), dim3((unsigned)nq), dim3(256), lds + dp, s, sa);
-            } else
             if (L <= 1024) hipLaunchKernelGGL(k_select_clusters_screen_wave<16>, dim3((unsigned)((nq + 3) / 4)), dim3(256), 4 * lds, s, sa, (int)nq);
             else if (L <= 4096) hipLaunchKernelGGL(k_select_clusters_screen<16>, dim3((unsigned)nq), dim3(256), lds, s, sa);
             else if (big_matrix) hipLaunchKernelGGL((k_select_clusters_screen<64, true>), dim3((unsigned)nq), dim3(256), lds, s, sa);
@@ -487,7 +478,15 @@ int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ
             hipLaunchKernelGGL(k_select_clusters, dim3((unsigned)nq), dim3(256), 0, s, ws.gscore.as<float>(), L, w, ws.sel.as<int32_t>());
     }
     }
-    if (!pl.small) {       // (small batches: the selection kernel has done the A stage, pairs stay in slot order)
+    if (pl.small) {        // small batches: the A stage pair by pair, pairs stay in slot order
+        Prof p(ix, K_STAGE_A, s);
+        SmallArgs sm;
+        sm.q8 = ws.q8.as<int8_t>(); sm.dx = ws.dx.as<float>(); sm.A = ix->A; sm.sA = ix->sA; sm.sB = ix->sB; sm.off = ix->off; sm.r = ix->r; sm.r_pad = r_pad;
+        sm.Z = ws.Z.as<int8_t>(); sm.sigma = ws.sigma.as<float>(); sm.pmax = ws.pmax.as<uint32_t>(); sm.pos_of_slot = ws.pos_of_slot.as<int32_t>();
+        sm.slot_of_pos = ws.slot_of_pos.as<int32_t>(); sm.voff = ws.voff.as<int64_t>(); sm.qorder = ws.qorder.as<int32_t>();
+        const int ppw = r_pad <= 32 ? 2 : 1;
+        hipLaunchKernelGGL(k_small_stage_a, dim3((unsigned)((npairs + 4 * ppw - 1) / (4 * ppw))), dim3(256), 0, s, sm, ws.sel.as<int32_t>(), (int)nq, w, dp);
+    } else {
     const bool lds_hist = pl.lds_hist;
     const int nbb = pl.nbb;
     int32_t* base_tab = lds_hist ? ws.base_tab.as<int32_t>() : nullptr;
@@ -615,7 +614,7 @@ int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ
         }
     } else if (grouped) {
         // grouped re-rank: neighbours in the visiting order share candidate rows, each distinct row is gathered once
-        {
+        if (!pl.small) {          // (small batches: no overflow list to finish, and the queries keep their given order)
             Prof p(ix, K_ORDER, s);
             const int fb_blocks = (int)std::min<int64_t>(nq, 1024);
             const dim3 grid((unsigned)(fb_blocks + L));
@@ -625,7 +624,7 @@ int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ
         const int64_t ngroups = pl.ngroups;
         const size_t gm = (size_t)kGroupQ * m;
         GroupArgs ga;
-        ga.Q = dQ; ga.corpus = half_rows ? (const void*)ix->corpus_h : (const void*)ix->corpus; ga.ids = ix->ids; ga.cand = ws.cand.as<int32_t>(); ga.qorder = ws.qorder2.as<int32_t>();
+        ga.Q = dQ; ga.corpus = half_rows ? (const void*)ix->corpus_h : (const void*)ix->corpus; ga.ids = ix->ids; ga.cand = ws.cand.as<int32_t>(); ga.qorder = pl.small ? ws.qorder.as<int32_t>() : ws.qorder2.as<int32_t>();
         ga.u_row = ws.u_row.as<int32_t>(); ga.u_mask = ws.u_mask.as<uint16_t>(); ga.u_pos = ws.u_pos.as<uint16_t>(); ga.u_count = ws.u_count.as<int32_t>();
         ga.dist = ws.rdist.as<float>(); ga.cid = ws.rcid.as<int64_t>(); ga.ccount = ws.rccount.as<int32_t>();
         ga.out_ids = d_ids; ga.out_dists = d_dists; ga.nq = (int)nq; ga.d = d; ga.m = m; ga.k = k;

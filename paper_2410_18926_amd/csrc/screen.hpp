@@ -28,7 +28,6 @@
 #pragma once
 #include "common.hpp"
 #include "route.hpp"
-#include "small_batch.hpp"
 
 namespace lorann {
 
@@ -156,7 +155,6 @@ struct ScreenArgs {
     int32_t* zero;               // [nzero] cleared by this launch, or NULL
     int nzero;
     float nrm_max;               // >= max_l |mu_l|_2^2 (Euclidean; else 0)
-    SmallArgs small;             // small batches (SMALL instantiation of the block kernel): the query's pairs go on to the A stage here
 };
 
 // Bound on |<qb, mub> - <q, mu>| for every centroid (see the header): qe >= |dq|_2, qb >= |qb|_2.
@@ -166,9 +164,8 @@ __device__ __forceinline__ float screen_eps_ip(float qe, float qb, float mu_max,
 }
 
 // One block (256 threads) per query; KPT approximate values per thread in registers (256 * KPT >= L).
-// dynamic LDS = dp * 4 bytes (the query).  SMALL: the block then computes the first 8-bit product and the
-// re-quantization for the query's w pairs (small_batch.hpp); dynamic LDS = dp * 4 + dp bytes.
-template <int KPT, bool NT = false, bool SMALL = false>
+// dynamic LDS = dp * 4 bytes (the query).
+template <int KPT, bool NT = false>
 __global__ __launch_bounds__(256) void k_select_clusters_screen(ScreenArgs a) {
     constexpr int CAP = 2048;
     extern __shared__ __align__(16) unsigned char scr_smem[];
@@ -369,13 +366,6 @@ __global__ __launch_bounds__(256) void k_select_clusters_screen(ScreenArgs a) {
             }
             if (r < w) out[r] = (int)(unsigned)(me & 0xFFFFFFFFull);
         }
-    }
-    if (SMALL) {
-        // the selected clusters (and, when this block quantized the query, its codes) were written through global
-        // memory by other threads of this block
-        __threadfence_block();
-        __syncthreads();
-        small_stage_a_block(a.small, (int)blockIdx.x, out, w, dp, reinterpret_cast<int8_t*>(scr_smem + (size_t)dp * 4));
     }
 }
 

@@ -405,9 +405,9 @@ def test_full_size_benchmark_configuration_sampled_parity(B, workload, scheme, n
 @pytest.mark.parametrize("metric", [0, 1, 2])
 @pytest.mark.parametrize("nq", [1, 2, 17, 64])
 def test_small_batches_take_the_query_major_path(B, nq, metric):
-    """Batches of up to 64 queries skip the bucketing: the block that selects a query's clusters also forms the
-    first 8-bit product and re-quantizes it for the query's pairs, every pair is scored as a cluster of its own, a
-    query whose survivor list overflows is finished in place, and the re-rank runs one query per block.  L = 16384
+    """Batches of up to 64 queries skip the bucketing: one launch forms the first 8-bit product and re-quantizes it
+    pair by pair in slot order, every pair is scored as a cluster of its own, a query whose survivor list overflows
+    is finished in place, and the grouped re-rank takes the queries in their given order.  L = 16384
     clusters, w = 64, d' = 192, r = 32, m = 200 as in the 10M-point workload (150 000 points here), the three
     metrics; every stage against the oracle, and the same queries inside a larger batch (the cluster-batched
     path) give the same bits."""
