@@ -337,7 +337,8 @@ ChunkPlan plan_chunk(const lorann_index* ix, int64_t nq, int w, int m) {
     // A few dozen queries: hardly two pairs share a cluster, so the pairs stay in slot order and every launch that only
     // serves the bucketing is left out (per-cluster step sizes only).
     pl.small = nq <= kSmallPathQueries && pl.screen && !pl.mixed && ix->sA_cols == nullptr && ix->rerank_mode != LORANN_RERANK_NONE;
-    pl.ngroups = pl.grouped ? (nq + pl.group_q - 1) / pl.group_q : 0;
+    // (small batches: a group per query - nothing to share, and the union and the gather of a group are latency chains)
+    pl.ngroups = !pl.grouped ? 0 : pl.small ? nq : (nq + pl.group_q - 1) / pl.group_q;
     return pl;
 }
 
@@ -628,7 +629,8 @@ int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ
         ga.u_row = ws.u_row.as<int32_t>(); ga.u_mask = ws.u_mask.as<uint16_t>(); ga.u_pos = ws.u_pos.as<uint16_t>(); ga.u_count = ws.u_count.as<int32_t>();
         ga.dist = ws.rdist.as<float>(); ga.cid = ws.rcid.as<int64_t>(); ga.ccount = ws.rccount.as<int32_t>();
         ga.out_ids = d_ids; ga.out_dists = d_dists; ga.nq = (int)nq; ga.d = d; ga.m = m; ga.k = k;
-        ga.ht = rerank_group_ht(kGroupQ, m);
+        ga.gq = pl.small ? 1 : kGroupQ;
+        ga.ht = rerank_group_ht(ga.gq, m);
         ws.last_ngroups = ngroups;
         // enough gather blocks to keep every CU evenly busy: about 2 MiB of rows per block at most
         ga.slices = (int)std::min<int64_t>(16, std::max<int64_t>(1, ((int64_t)gm * d * 4 / 2) / (2 << 20) + 1));

@@ -92,6 +92,7 @@ struct GroupArgs {
     int nq, d, m, k;
     int ht;                      // hash table slots (rerank_group_ht)
     int slices;                  // gather blocks per group
+    int gq;                      // queries per group in this launch, <= G (the buffers keep their G-wide strides)
 };
 
 inline int rerank_group_ht(int G, int m) {      // hash table slots: power of two, load factor <= 0.8
@@ -120,8 +121,8 @@ __global__ __launch_bounds__(kUnionThreads) void k_group_union(GroupArgs a) {
     __shared__ int s_q[kGroupQ], s_rcount[kGroupQ], s_nuniq;
     const int tid = threadIdx.x;
     const int grp = blockIdx.x;
-    const int g0 = grp * kGroupQ;
-    const int ng = min(kGroupQ, a.nq - g0);
+    const int g0 = grp * a.gq;
+    const int ng = min(a.gq, a.nq - g0);
     if (tid < kGroupQ) { s_q[tid] = tid < ng ? a.qorder[g0 + tid] : -1; s_rcount[tid] = 0; }
     if (tid == 0) s_nuniq = 0;
     for (int s = tid; s < ht; s += kUnionThreads) tkey[s] = -1;
@@ -206,8 +207,8 @@ __global__ __launch_bounds__(kGatherThreads) void k_group_gather(GroupArgs a) {
     const int d = a.d, m = a.m;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int grp = blockIdx.x / a.slices, sl = blockIdx.x - grp * a.slices;
-    const int g0 = grp * kGroupQ;
-    const int ng = min(kGroupQ, a.nq - g0);
+    const int g0 = grp * a.gq;
+    const int ng = min(a.gq, a.nq - g0);
     const int nuniq = a.u_count[grp];
     const int per = (nuniq + a.slices - 1) / a.slices;
     const int ubeg = sl * per, uend = min(nuniq, ubeg + per);
