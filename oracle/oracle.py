@@ -33,7 +33,7 @@ class _Dump(C.Structure):
 def lib():
     global _lib
     if _lib is None:
-        path = _build.build(force=False)
+        path = os.environ.get("LORANN_ORACLE_LIB") or _build.build(force=False)   # (the sanitized build, for the test that runs the pins under it)
         _lib = C.CDLL(str(path))
         _lib.oracle_search.restype = C.c_int
         _lib.oracle_exact_knn.restype = C.c_int
