@@ -334,7 +334,7 @@ static void search_one(const oracle_index *ix, const float *q, int32_t k, int32_
         oracle_pair_accumulators(z, r, ix->B + (size_t)off * r, mc, Y);
         float best = -INFINITY;
         for (int64_t t = 0; t < mc; ++t) {
-            float sq = 0.0f;   /* Sec. 3.1: the norms |c_j|^2 "can be precomputed" */
+            float sq = 0.0f;   /* Sec. 3.1: the norms |c_j|^2 may be computed ahead of the search */
             if (ix->metric == ORACLE_L2)
                 sq = ix->sqnorms ? ix->sqnorms[off + t] : oracle_row_sqnorm(ix->corpus + (size_t)(off + t) * d, d);
             sc[pos].key = mixed ? oracle_score_mixed(Y[t], sigma, ix->pt_scale_B[off + t], rho0, ix->first_row_B[off + t], ix->metric, sq)
