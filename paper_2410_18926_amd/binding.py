@@ -22,11 +22,12 @@ LORANN_IP, LORANN_L2, LORANN_COS = 0, 1, 2
 LORANN_OK, LORANN_E_INVAL, LORANN_E_NOMEM, LORANN_E_DEVICE, LORANN_E_UNSUPPORTED = 0, -1, -2, -3, -4
 
 EXPORTS = ["lorann_load_index", "lorann_load_index_file", "lorann_search", "lorann_search_async", "lorann_free_index", "lorann_last_error", "lorann_set_stream",
-           "lorann_search_stages", "lorann_profile_enable", "lorann_profile_get", "lorann_set_exact_selection",
+           "lorann_search_stages", "lorann_profile_enable", "lorann_profile_get", "lorann_set_exact_selection", "lorann_set_screen_mode",
            "lorann_profile_fallback_queries", "lorann_set_rerank", "lorann_set_column_scales", "lorann_set_first_rows", "lorann_search_lane", "lorann_lane_join", "lorann_set_gather_turns", "lorann_search_noalloc", "lorann_profile_gather_rows"]
 NOALLOC_SCRATCH_BYTES = 32 << 20
 LANES = 4
 RERANK_F32, RERANK_F16, RERANK_NONE = 0, 1, 2
+SCREEN_AUTO, SCREEN_MATRIX, SCREEN_DIGEST = 0, 1, 2
 
 
 class LorannError(RuntimeError):
@@ -73,6 +74,8 @@ def lib() -> C.CDLL:
         L.lorann_set_stream.argtypes = [vp, vp]
         L.lorann_set_exact_selection.restype = C.c_int
         L.lorann_set_exact_selection.argtypes = [vp, i32]
+        L.lorann_set_screen_mode.restype = C.c_int
+        L.lorann_set_screen_mode.argtypes = [vp, i32]
         L.lorann_set_column_scales.restype = C.c_int
         L.lorann_set_column_scales.argtypes = [vp, vp, vp]
         L.lorann_set_first_rows.restype = C.c_int
@@ -256,6 +259,9 @@ class Index:
 
     def set_exact_selection(self, on: bool):
         _check(lib().lorann_set_exact_selection(self._h, 1 if on else 0))
+
+    def set_screen_mode(self, mode: int):
+        _check(lib().lorann_set_screen_mode(self._h, int(mode)))
 
     def set_column_scales(self, scale_A_columns, scale_B_points):
         """One step size per column of A_c ([L, r]) and per corpus row ([n]) instead of one per cluster; None, None

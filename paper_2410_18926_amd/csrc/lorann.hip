@@ -24,6 +24,7 @@
 #include "select_exact.hpp"
 #include "select_query.hpp"
 #include "small_batch.hpp"
+#include "screen_fused.hpp"
 #include "stage_a.hpp"
 
 using namespace lorann;
@@ -100,6 +101,7 @@ struct DevBuf {
 struct Workspace {
     DevBuf qproj, qbf, q8, dx, gscore, sel, count, rank_in_bucket, qrank, qorder, qorder2, off0, base_tab, bucket_off, tile_off, unit_off, slot_of_pos, pos_of_slot, Z, sigma, rho0, cand;
     DevBuf tau, n_kept, fb_list, pmax, voff, qkey, u_row, u_mask, u_pos, u_count, rdist, rcid, rccount;
+    DevBuf smin, thr, hit_val, hit_grp, hit_cnt;      // screening without the matrix of approximate values
     hipStream_t stream = nullptr;          // lanes >= 1: created on first use, default priority
     hipEvent_t fork = nullptr, join = nullptr;
     hipEvent_t gather_done = nullptr;      // recorded after this lane's latest re-rank gather
@@ -181,6 +183,7 @@ struct lorann_index {
     hipEvent_t last_gather = nullptr;   // gather_done of the lane that enqueued the latest gather (owned by that lane)
     int32_t gather_turns = 1;       // the re-rank gathers of different lanes run one after the other
     int32_t force_exact = 0;        // 1: score + select with the per-query kernel only (verification)
+    int32_t screen_mode = 0;        // LORANN_SCREEN_AUTO / _MATRIX / _DIGEST
     DevBuf stage_q, stage_ids, stage_dists;   // staging when the caller passes host memory
     DevBuf fb_total;                // while profiling asynchronous searches: device-side sum of the fallback counts
     bool fb_total_live = false;
@@ -313,6 +316,7 @@ void launch_pair_max(lorann_index* ix, Workspace& ws, hipStream_t s, int64_t npa
 struct ChunkPlan {
     bool mixed, screen, fused_quant, big_matrix, lds_hist, grouped;
     bool small;         // query-major path of small batches (no bucketing)
+    bool digest;        // screening from subset minima and hit lists: the matrix of approximate values is never written
     int group_q;        // queries per re-rank group (0: rows too long to share)
     int nbb;            // blocks of the bucket-count kernel
     int64_t ngroups;
@@ -330,6 +334,12 @@ ChunkPlan plan_chunk(const lorann_index* ix, int64_t nq, int w, int m) {
     pl.fused_quant = pl.screen && ix->Pt != nullptr && !pl.mixed;
     // an approximate-score matrix beyond the caches (256 MB) is streamed: written and read once, nothing of it is worth keeping
     pl.big_matrix = pl.screen && L > 4096 && (int64_t)nq * L * 4 > (int64_t(256) << 20);
+    // Many queries x many clusters: the matrix would be written and read once through HBM; two passes of the product
+    // that keep only digests are cheaper.  Needs the query operand resident in registers (d' of 128 or 192) and enough
+    // centroid tiles for every run of the second grid dimension.
+    const bool digest_ok = pl.screen && (ix->dp == 128 || ix->dp == 192) && L >= 128 * kFusedSplits && w <= kFusedSubsets / 2;
+    pl.digest = digest_ok && (ix->screen_mode == LORANN_SCREEN_DIGEST || (ix->screen_mode == LORANN_SCREEN_AUTO && nq >= 2048 && L >= 4096));
+    if (pl.digest) pl.big_matrix = false;
     pl.lds_hist = (size_t)L * 8 <= 64 * 1024;
     pl.nbb = (int)((nq + kBucketQueries - 1) / kBucketQueries);
     pl.group_q = rerank_group_size(ix->d);
@@ -368,6 +378,9 @@ int reserve_workspace(const lorann_index* ix, Workspace& ws, const ChunkPlan& pl
         {&ws.u_pos, (size_t)pl.ngroups * gm * pl.group_q * 2, pl.grouped}, {&ws.u_count, (size_t)pl.ngroups * 4, pl.grouped},
         {&ws.rdist, q * m * 4, pl.grouped || no_rerank}, {&ws.rcid, q * m * 8, pl.grouped || no_rerank},
         {&ws.rccount, q * 4, pl.grouped || no_rerank},
+        {&ws.smin, q * kFusedSubsets * 4, pl.digest}, {&ws.thr, q * 4, pl.digest},
+        {&ws.hit_val, q * kFusedLists * kFusedCap * 64, pl.digest}, {&ws.hit_grp, q * kFusedLists * kFusedCap * 4, pl.digest},
+        {&ws.hit_cnt, q * kFusedLists * 4, pl.digest},
     };
     bool fits = true;
     for (const Want& wt : wants) {
@@ -424,7 +437,24 @@ int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ
     }
     const bool big_matrix = pl.big_matrix;
     if (screen) {
-        {
+        if (pl.digest) {
+            Prof p(ix, K_CENTROID_BF16, s);
+            ScreenPassArgs pa;
+            pa.Q = ws.qbf.as<__bf16>(); pa.C = ix->cent_bf16; pa.nrm = ix->metric == LORANN_L2 ? ix->cent_nrm_f32 : nullptr;
+            pa.nq = (int)nq; pa.L = L; pa.tiles_per_split = ((L + 63) / 64 + kFusedSplits - 1) / kFusedSplits;
+            pa.smin = ws.smin.as<float>(); pa.thr = ws.thr.as<float>(); pa.hit_val = ws.hit_val.as<float>();
+            pa.hit_grp = ws.hit_grp.as<int32_t>(); pa.hit_cnt = ws.hit_cnt.as<int32_t>();
+            const bool l2 = ix->metric == LORANN_L2;
+#define LAUNCH_SP(KS_, L2_, EMIT_, W_) hipLaunchKernelGGL((k_screen_pass<KS_, L2_, EMIT_, W_>), dim3((unsigned)((nq + 64 * W_ - 1) / (64 * W_)), kFusedSplits), dim3(64 * W_), (size_t)2 * (64 * (32 * KS_ + 16) + 256), s, pa)
+#define LAUNCH_SP2(EMIT_, W_) do { if (dp == 128) { if (l2) LAUNCH_SP(8, true, EMIT_, W_); else LAUNCH_SP(8, false, EMIT_, W_); } \
+                               else { if (l2) LAUNCH_SP(12, true, EMIT_, W_); else LAUNCH_SP(12, false, EMIT_, W_); } } while (0)
+            LAUNCH_SP2(false, 8);
+            hipLaunchKernelGGL(k_screen_threshold, dim3((unsigned)((nq + 3) / 4)), dim3(256), 0, s, ws.smin.as<float>(), qp, (int)nq, dp, w, l2, ix->mu_max, ix->dmu_max,
+                               l2 ? ix->nrm_max : 0.0f, ws.thr.as<float>());
+            LAUNCH_SP2(true, 8);
+#undef LAUNCH_SP2
+#undef LAUNCH_SP
+        } else {
             Prof p(ix, K_CENTROID_BF16, s);
             const int64_t blocks2 = (int64_t)((L + 127) / 128) * ((nq + 127) / 128);
             const int ti = blocks2 >= 256 ? 2 : 1;          // tiny problems: twice the blocks of half the height
@@ -445,7 +475,10 @@ int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ
             sa.q8 = fused_quant ? ws.q8.as<int8_t>() : nullptr; sa.dx = ws.dx.as<float>();
             sa.zero = fused_quant ? ws.count.as<int32_t>() : nullptr; sa.nzero = 2 * L + 1;
             const size_t lds = (size_t)dp * 4;
-            if (L <= 1024) hipLaunchKernelGGL(k_select_clusters_screen_wave<16>, dim3((unsigned)((nq + 3) / 4)), dim3(256), 4 * lds, s, sa, (int)nq);
+            sa.thr = ws.thr.as<float>(); sa.hit_val = ws.hit_val.as<float>(); sa.hit_grp = ws.hit_grp.as<int32_t>(); sa.hit_cnt = ws.hit_cnt.as<int32_t>();
+            sa.nlist = kFusedLists; sa.cap = kFusedCap;
+            if (pl.digest) hipLaunchKernelGGL((k_select_clusters_screen<1, false, true>), dim3((unsigned)nq), dim3(256), lds, s, sa);
+            else if (L <= 1024) hipLaunchKernelGGL(k_select_clusters_screen_wave<16>, dim3((unsigned)((nq + 3) / 4)), dim3(256), 4 * lds, s, sa, (int)nq);
             else if (L <= 4096) hipLaunchKernelGGL(k_select_clusters_screen<16>, dim3((unsigned)nq), dim3(256), lds, s, sa);
             else if (big_matrix) hipLaunchKernelGGL((k_select_clusters_screen<64, true>), dim3((unsigned)nq), dim3(256), lds, s, sa);
             else hipLaunchKernelGGL(k_select_clusters_screen<64>, dim3((unsigned)nq), dim3(256), lds, s, sa);
@@ -1209,6 +1242,14 @@ int lorann_set_exact_selection(lorann_index* ix, int32_t on) {
     if (!ix) return fail(LORANN_E_INVAL, "index is NULL");
     { const int rc = sync_all(ix); if (rc) return rc; }   // searches in flight keep the path they were enqueued with
     ix->force_exact = on != 0;
+    return LORANN_OK;
+}
+
+int lorann_set_screen_mode(lorann_index* ix, int32_t mode) {
+    if (!ix) return fail(LORANN_E_INVAL, "index is NULL");
+    if (mode != LORANN_SCREEN_AUTO && mode != LORANN_SCREEN_MATRIX && mode != LORANN_SCREEN_DIGEST) return fail(LORANN_E_INVAL, "unknown screening mode %d", (int)mode);
+    { const int rc = sync_all(ix); if (rc) return rc; }   // searches in flight keep the path they were enqueued with
+    ix->screen_mode = mode;
     return LORANN_OK;
 }
 

@@ -155,6 +155,15 @@ struct ScreenArgs {
     int32_t* zero;               // [nzero] cleared by this launch, or NULL
     int nzero;
     float nrm_max;               // >= max_l |mu_l|_2^2 (Euclidean; else 0)
+    // LISTS instantiation of the block kernel (screen_fused.hpp): the approximate values at or below thr[q] arrive
+    // as lists of 16-value groups instead of a row of ghat (ghat is then only written and read when everything has
+    // to be evaluated exactly)
+    const float* thr;            // [nq]
+    const float* hit_val;        // [nq][nlist][cap][16]
+    const int32_t* hit_grp;      // [nq][nlist][cap]  2 * (64-centroid tile) + row half; value v of a group written by
+                                 //                   lane half h = list % 2 is centroid 64 tile + 32 half + 8 (v/4) + 4 h + v%4
+    const int32_t* hit_cnt;      // [nq][nlist]       groups found; more than cap: the list overflowed
+    int nlist, cap;
 };
 
 // Bound on |<qb, mub> - <q, mu>| for every centroid (see the header): qe >= |dq|_2, qb >= |qb|_2.
@@ -165,7 +174,7 @@ __device__ __forceinline__ float screen_eps_ip(float qe, float qb, float mu_max,
 
 // One block (256 threads) per query; KPT approximate values per thread in registers (256 * KPT >= L).
 // dynamic LDS = dp * 4 bytes (the query).
-template <int KPT, bool NT = false>
+template <int KPT, bool NT = false, bool LISTS = false>
 __global__ __launch_bounds__(256) void k_select_clusters_screen(ScreenArgs a) {
     constexpr int CAP = 2048;
     extern __shared__ __align__(16) unsigned char scr_smem[];
@@ -174,7 +183,7 @@ __global__ __launch_bounds__(256) void k_select_clusters_screen(ScreenArgs a) {
     __shared__ __align__(16) unsigned long long cand[CAP + 2];     // (key, cluster) of the first, then the final list
     __shared__ int clist[CAP];                                       // clusters evaluated exactly
     __shared__ float s_part[16];
-    __shared__ int s_cnt, s_cnt2;
+    __shared__ int s_cnt, s_cnt2, s_over;
     __shared__ uint32_t s_bound, s_gw;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int L = a.L, dp = a.dp, w = a.w;
@@ -186,7 +195,7 @@ __global__ __launch_bounds__(256) void k_select_clusters_screen(ScreenArgs a) {
     // the query, its norm (rounded up), the approximate values
     float v[KPT];
 #pragma unroll
-    for (int i = 0; i < KPT; ++i) v[i] = NT ? __builtin_nontemporal_load(&row[min(i * 256 + tid, L - 1)]) : row[min(i * 256 + tid, L - 1)];
+    for (int i = 0; i < KPT; ++i) v[i] = LISTS ? 0.0f : NT ? __builtin_nontemporal_load(&row[min(i * 256 + tid, L - 1)]) : row[min(i * 256 + tid, L - 1)];
     if (a.zero) for (int i = blockIdx.x * 256 + tid; i < a.nzero; i += gridDim.x * 256) a.zero[i] = 0;
     float nn = 0.0f, ne = 0.0f, nb = 0.0f;      // |q|^2, |dq|^2, |qb|^2
     float amax = 0.0f;
@@ -199,7 +208,7 @@ __global__ __launch_bounds__(256) void k_select_clusters_screen(ScreenArgs a) {
     }
     nn = wave_sum_f32(nn); ne = wave_sum_f32(ne); nb = wave_sum_f32(nb); amax = wave_max_f32(amax);
     if (lane == 0) { s_part[wv] = nn; s_part[4 + wv] = ne; s_part[8 + wv] = nb; s_part[12 + wv] = amax; }
-    if (tid == 0) { s_cnt = 0; s_cnt2 = 0; }
+    if (tid == 0) { s_cnt = 0; s_cnt2 = 0; s_over = 0; }
     uint32_t mn = 0xFFFFFFFFu;
 #pragma unroll
     for (int i = 0; i < KPT; ++i) {
@@ -228,7 +237,7 @@ __global__ __launch_bounds__(256) void k_select_clusters_screen(ScreenArgs a) {
     eps += 1e-30f;
     // w-th smallest of the 256 per-thread minima: an upper bound of the w-th smallest approximate value
     int rank = 0;
-    {
+    if (!LISTS) {
         const ulonglong2* t2 = reinterpret_cast<const ulonglong2*>(tmin);
 #pragma unroll 16
         for (int u = 0; u < 128; ++u) {
@@ -236,25 +245,50 @@ __global__ __launch_bounds__(256) void k_select_clusters_screen(ScreenArgs a) {
             rank += (t.x < mine ? 1 : 0) + (t.y < mine ? 1 : 0);
         }
     }
-    if (rank == w - 1) s_bound = mn;
+    if (!LISTS && rank == w - 1) s_bound = mn;
     __syncthreads();
     auto widen = [&](float t) {                           // t + 2 eps, rounded up generously
         const float s = t + 2.0f * eps;
         return s + 1e-6f * (fabsf(s) + eps);
     };
-    const float tf1 = widen(key_to_float(s_bound));
     // first list: everything that may lie below (w-th smallest approximate value) + 2 eps
+    if (LISTS) {
+        // eight threads per list, a thread takes every eighth group; the threshold is the one the lists were made with
+        const float tf1 = a.thr[blockIdx.x];
+        for (int li = tid >> 3; li < a.nlist; li += 32) {
+            const size_t lb = (size_t)blockIdx.x * a.nlist + li;
+            const int n = a.hit_cnt[lb];
+            if (n > a.cap && (tid & 7) == 0) s_over = 1;
+            for (int sl = tid & 7; sl < min(n, a.cap); sl += 8) {
+                const int grp = a.hit_grp[lb * a.cap + sl];
+                const float4* val = reinterpret_cast<const float4*>(a.hit_val + (lb * a.cap + sl) * 16);
+                float g[16];
 #pragma unroll
-    for (int i = 0; i < KPT; ++i) {
-        const int l = i * 256 + tid;
-        if (l < L && !(v[i] > tf1)) {
-            const int p = atomicAdd(&s_cnt, 1);
-            if (p < CAP) cand[p] = ((unsigned long long)float_key_asc(v[i]) << 32) | (unsigned)l;
+                for (int g4 = 0; g4 < 4; ++g4) { const float4 x = val[g4]; g[4 * g4] = x.x; g[4 * g4 + 1] = x.y; g[4 * g4 + 2] = x.z; g[4 * g4 + 3] = x.w; }
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int l = (grp >> 1) * 64 + (grp & 1) * 32 + 8 * (e >> 2) + 4 * (li & 1) + (e & 3);
+                    if (l < L && !(g[e] > tf1)) {
+                        const int p = atomicAdd(&s_cnt, 1);
+                        if (p < CAP) cand[p] = ((unsigned long long)float_key_asc(g[e]) << 32) | (unsigned)l;
+                    }
+                }
+            }
+        }
+    } else {
+        const float tf1 = widen(key_to_float(s_bound));
+#pragma unroll
+        for (int i = 0; i < KPT; ++i) {
+            const int l = i * 256 + tid;
+            if (l < L && !(v[i] > tf1)) {
+                const int p = atomicAdd(&s_cnt, 1);
+                if (p < CAP) cand[p] = ((unsigned long long)float_key_asc(v[i]) << 32) | (unsigned)l;
+            }
         }
     }
     __syncthreads();
     const int c1 = s_cnt;
-    bool all_exact = c1 > CAP;                            // uniform
+    bool all_exact = c1 > CAP || (LISTS && (s_over != 0 || c1 < w));      // uniform
     int c2 = 0;
     if (!all_exact) {
         // the w-th smallest approximate value itself (it is in the list), then the final list

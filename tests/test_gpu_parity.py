@@ -529,6 +529,70 @@ def test_routing_by_screening_adversarial(B, L, w, metric, case):
     gix.close()
 
 
+@pytest.mark.parametrize("L,w,metric,dp,nq,case", [
+    (2048, 32, 0, 128, 40, "plain"), (2500, 64, 1, 128, 300, "near_ties"), (2500, 48, 2, 192, 70, "plateau"),
+    (12000, 64, 0, 192, 300, "near_ties"), (12000, 128, 1, 192, 40, "plain"), (16384, 64, 0, 192, 600, "plain"),
+    (5000, 40, 0, 128, 40, "outlier"), (5000, 40, 1, 192, 40, "outlier"), (4097, 100, 2, 128, 129, "near_ties"),
+])
+def test_routing_by_screening_from_digests(B, L, w, metric, dp, nq, case):
+    """The screening that never writes the nq x L matrix of approximate values (two passes of the bf16 product: minima
+    of 256 subsets of the clusters, then lists of the values below a per-query threshold), forced for batches far
+    smaller than those that take it by themselves.  Cluster counts that are no multiple of the 64-cluster tile or of
+    the 16 runs, batches that end inside a wavefront's 64 queries, and the inputs that stress the lists: hundreds of
+    centroids within 1e-6 of each other (near_ties), 400 identical ones (plateau: a lane's list or the block's list
+    overflows, every cluster is evaluated exactly), centroids of huge norm (outlier: the bound is useless, everything
+    is listed).  The selected clusters must equal the oracle's, in order, and those of the matrix route."""
+    rng = np.random.default_rng(77 * L + w + metric + nq)
+    d, r = (dp, 8) if metric != 0 else (dp + 40, 8)          # inner product: with a projection
+    sizes = rng.integers(1, 4, size=L)
+    n = int(sizes.sum())
+    corpus = rng.normal(size=(n, d)).astype(np.float32)
+    cent = rng.normal(size=(L, dp)).astype(np.float32)
+    cent /= np.linalg.norm(cent, axis=1, keepdims=True)
+    P = None if dp == d else np.linalg.qr(rng.normal(size=(d, d)))[0][:, :dp].astype(np.float32)
+    q = rng.normal(size=(nq, d)).astype(np.float32)
+    q /= np.linalg.norm(q, axis=1, keepdims=True)
+    qp0 = q[0] if P is None else (q[0].astype(np.float64) @ P.astype(np.float64)).astype(np.float32)
+    base = qp0 / np.linalg.norm(qp0)
+    if case == "near_ties":
+        idx = rng.choice(L, size=300, replace=False)
+        cent[idx] = (base[None, :] * (1.0 + 1e-6 * rng.normal(size=(idx.size, 1))) + 1e-6 * rng.normal(size=(idx.size, dp))).astype(np.float32)
+        q[1:20] = q[0][None, :] + 0.05 * rng.normal(size=(19, d)).astype(np.float32)
+    elif case == "plateau":
+        idx = rng.choice(L, size=400, replace=False)
+        cent[idx] = base
+        q[1:20] = q[0][None, :] + 0.01 * rng.normal(size=(19, d)).astype(np.float32)
+    elif case == "outlier":
+        cent[L // 3] *= 3.0e4
+        cent[L // 3 + 1] *= -2.0e4
+    if metric == 2:
+        corpus /= np.linalg.norm(corpus, axis=1, keepdims=True)
+    off = np.zeros(L + 1, np.int64)
+    np.cumsum(sizes, out=off[1:])
+    ix = dict(metric=metric, n=n, d=d, dp=dp, r=r, L=L, centroids=cent, P=P,
+              A=rng.integers(-127, 128, size=(L, r, dp)).astype(np.int8), B=rng.integers(-127, 128, size=(n, r)).astype(np.int8),
+              scale_A=rng.uniform(0.01, 0.1, L).astype(np.float32), scale_B=rng.uniform(0.01, 0.1, L).astype(np.float32),
+              cluster_offsets=off, corpus=corpus, ids=None)
+    gix = B.Index(**ix)
+    oix = O.OracleIndex(ix)
+    m = 50
+    o_ids, o_d, ost = O.search(oix, q, 10, w, m, stages=True)
+    gix.set_screen_mode(B.SCREEN_DIGEST)
+    g_ids, g_d, gst = gix.search_stages(q, 10, w, m)
+    np.testing.assert_array_equal(gst["sel"], ost["sel"], err_msg=f"selected clusters ({case})")
+    np.testing.assert_array_equal(gst["q8"], ost["q8"])
+    np.testing.assert_array_equal(gst["z"], ost["z"])
+    assert_topk_equal(g_ids, g_d, o_ids, o_d, f"digests: L={L} w={w} metric={metric} {case}")
+    gix.set_screen_mode(B.SCREEN_MATRIX)
+    m_ids, m_d, mst = gix.search_stages(q, 10, w, m)
+    np.testing.assert_array_equal(mst["sel"], gst["sel"])
+    np.testing.assert_array_equal(m_ids, g_ids)
+    np.testing.assert_array_equal(m_d, g_d)
+    with pytest.raises(B.LorannError):
+        gix.set_screen_mode(7)
+    gix.close()
+
+
 def _random_index(rng, n, d, L, r, metric, dp=None, with_ids=True):
     dp = dp or d
     cuts = np.sort(rng.choice(np.arange(1, n), size=L - 1, replace=False))
