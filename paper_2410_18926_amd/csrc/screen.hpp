@@ -176,10 +176,10 @@ __device__ __forceinline__ float screen_eps_ip(float qe, float qb, float mu_max,
 // dynamic LDS = dp * 4 bytes (the query).
 template <int KPT, bool NT = false, bool LISTS = false>
 __global__ __launch_bounds__(256) void k_select_clusters_screen(ScreenArgs a) {
-    constexpr int CAP = 2048;
+    constexpr int CAP = LISTS ? 512 : 2048;     // (lists hold a few more than w entries; less LDS, more blocks per CU)
     extern __shared__ __align__(16) unsigned char scr_smem[];
     float* qs = reinterpret_cast<float*>(scr_smem);                  // [dp]
-    __shared__ __align__(16) unsigned long long tmin[256];
+    __shared__ __align__(16) unsigned long long tmin[LISTS ? 2 : 256];
     __shared__ __align__(16) unsigned long long cand[CAP + 2];     // (key, cluster) of the first, then the final list
     __shared__ int clist[CAP];                                       // clusters evaluated exactly
     __shared__ float s_part[16];
@@ -215,7 +215,7 @@ __global__ __launch_bounds__(256) void k_select_clusters_screen(ScreenArgs a) {
         if (i * 256 + tid < L) mn = min(mn, float_key_asc(v[i]));
     }
     const unsigned long long mine = ((unsigned long long)mn << 32) | (unsigned)tid;
-    tmin[tid] = mine;
+    if (!LISTS) tmin[tid] = mine;
     __syncthreads();
     if (a.q8) {     // uniform: absmax codes of the query, exactly as k_quantize_rows computes them
         const float am = fmaxf(fmaxf(s_part[12], s_part[13]), fmaxf(s_part[14], s_part[15]));
@@ -253,13 +253,13 @@ __global__ __launch_bounds__(256) void k_select_clusters_screen(ScreenArgs a) {
     };
     // first list: everything that may lie below (w-th smallest approximate value) + 2 eps
     if (LISTS) {
-        // eight threads per list, a thread takes every eighth group; the threshold is the one the lists were made with
+        // 16 threads per list, a thread takes every 16th group; the threshold is the one the lists were made with
         const float tf1 = a.thr[blockIdx.x];
-        for (int li = tid >> 3; li < a.nlist; li += 32) {
+        for (int li = tid >> 4; li < a.nlist; li += 16) {
             const size_t lb = (size_t)blockIdx.x * a.nlist + li;
             const int n = a.hit_cnt[lb];
-            if (n > a.cap && (tid & 7) == 0) s_over = 1;
-            for (int sl = tid & 7; sl < min(n, a.cap); sl += 8) {
+            if (n > a.cap && (tid & 15) == 0) s_over = 1;
+            for (int sl = tid & 15; sl < min(n, a.cap); sl += 16) {
                 const int grp = a.hit_grp[lb * a.cap + sl];
                 const float4* val = reinterpret_cast<const float4*>(a.hit_val + (lb * a.cap + sl) * 16);
                 float g[16];

@@ -1,7 +1,7 @@
 // Routing by screening (Sec. 2.2, 4.1) for many queries x many clusters WITHOUT writing the nq x L matrix of
 // approximate dissimilarities: the bf16 matrix-core product is computed twice and only digests leave the chip.
 //
-//   pass A (k_screen_pass<.., false>)  every approximate value is folded into the minimum of one of S = 16 * nsplit
+//   pass A (k_screen_pass<.., false>)  every approximate value is folded into the minimum of one of S = 32 * nsplit
 //                                      disjoint subsets of the clusters; out: smin [nq][S].
 //   threshold (k_screen_threshold)     the w-th smallest of the S subset minima is an upper bound of the w-th smallest
 //                                      approximate value (w distinct clusters do not exceed it); thr = that bound
@@ -31,10 +31,11 @@
 
 namespace lorann {
 
-constexpr int kFusedSplits = 16;               // runs of centroid tiles = blocks along y; S = 16 * kFusedSplits subsets
-constexpr int kFusedSubsets = 16 * kFusedSplits;
+constexpr int kFusedSplits = 8;                // runs of centroid tiles = blocks along y (long runs: a block's set-up - its
+                                               // queries into registers, the first tile - is paid once per run)
+constexpr int kFusedSubsets = 32 * kFusedSplits;   // subset = (run, lane half, result register): 256
 constexpr int kFusedLists = 2 * kFusedSplits;   // lists per query: (run, lane half)
-constexpr int kFusedCap = 16;                  // 16-value groups a list can hold
+constexpr int kFusedCap = 32;                  // 16-value groups a list can hold
 
 struct ScreenPassArgs {
     const __bf16* Q;             // [nq][dp] queries rounded to bfloat16
@@ -103,7 +104,7 @@ __global__ __launch_bounds__(64 * WAVES) void k_screen_pass(ScreenPassArgs a) {
         if (L2 && tid < 64) reinterpret_cast<float*>(tb + 64 * ROWB)[tid] = nstage;
     };
 
-    float mn[2][8];
+    float mn[2][16];
     int cnt[2] = {0, 0};
     float thr[2] = {0.0f, 0.0f};
     bool qok[2];
@@ -111,7 +112,7 @@ __global__ __launch_bounds__(64 * WAVES) void k_screen_pass(ScreenPassArgs a) {
     for (int qt = 0; qt < 2; ++qt) {
         qok[qt] = q0 + 32 * qt + i < a.nq;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) mn[qt][j] = INFINITY;
+        for (int j = 0; j < 16; ++j) mn[qt][j] = INFINITY;
         if (EMIT) thr[qt] = a.thr[min(q0 + 32 * qt + i, a.nq - 1)];
     }
 
@@ -164,12 +165,12 @@ __global__ __launch_bounds__(64 * WAVES) void k_screen_pass(ScreenPassArgs a) {
                 }
                 if (!EMIT) {
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) mn[qt][j] = fminf(mn[qt][j], fminf(g[j], g[j + 8]));
+                    for (int v = 0; v < 16; ++v) mn[qt][v] = __builtin_fminimum_numf(mn[qt][v], g[v]);     // (minimumnum: no quieting of each input)
                 } else {
-                    bool hit = false;                       // (compares, not minima: no NaN canonicalization per value)
+                    float gm = __builtin_fminimum_numf(g[0], g[1]);        // (three-operand minima, no quieting of each input)
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) hit |= !(g[v] > thr[qt]);
-                    if (qok[qt] && hit) {
+                    for (int v = 2; v < 16; ++v) gm = __builtin_fminimum_numf(gm, g[v]);
+                    if (qok[qt] && !(gm > thr[qt])) {
                         const int sl = cnt[qt]++;
                         if (sl < kFusedCap) {
                             const size_t li = ((size_t)(q0 + 32 * qt + i) * kFusedLists + 2 * split + h) * kFusedCap + sl;
@@ -190,9 +191,9 @@ __global__ __launch_bounds__(64 * WAVES) void k_screen_pass(ScreenPassArgs a) {
         if (!qok[qt]) continue;
         const int q = q0 + 32 * qt + i;
         if (!EMIT) {
-            float4* dst = reinterpret_cast<float4*>(a.smin + (size_t)q * kFusedSubsets + (2 * split + h) * 8);
-            dst[0] = make_float4(mn[qt][0], mn[qt][1], mn[qt][2], mn[qt][3]);
-            dst[1] = make_float4(mn[qt][4], mn[qt][5], mn[qt][6], mn[qt][7]);
+            float4* dst = reinterpret_cast<float4*>(a.smin + (size_t)q * kFusedSubsets + (2 * split + h) * 16);
+#pragma unroll
+            for (int g4 = 0; g4 < 4; ++g4) dst[g4] = make_float4(mn[qt][4 * g4], mn[qt][4 * g4 + 1], mn[qt][4 * g4 + 2], mn[qt][4 * g4 + 3]);
         } else {
             a.hit_cnt[(size_t)q * kFusedLists + 2 * split + h] = cnt[qt];
         }
