@@ -335,10 +335,11 @@ ChunkPlan plan_chunk(const lorann_index* ix, int64_t nq, int w, int m) {
     // an approximate-score matrix beyond the caches (256 MB) is streamed: written and read once, nothing of it is worth keeping
     pl.big_matrix = pl.screen && L > 4096 && (int64_t)nq * L * 4 > (int64_t(256) << 20);
     // Many queries x many clusters: the matrix would be written and read once through HBM; two passes of the product
-    // that keep only digests are cheaper.  Needs the query operand resident in registers (d' of 128 or 192) and enough
+    // that keep only digests are cheaper (measured at L = 16384: from about 5000 queries on; below, the 8 x ceil(nq/512)
+    // blocks of a pass leave most CUs idle).  Needs the query operand resident in registers (d' of 128 or 192) and enough
     // centroid tiles for every run of the second grid dimension.
     const bool digest_ok = pl.screen && (ix->dp == 128 || ix->dp == 192) && L >= 128 * kFusedSplits && w <= kFusedSubsets / 2;
-    pl.digest = digest_ok && (ix->screen_mode == LORANN_SCREEN_DIGEST || (ix->screen_mode == LORANN_SCREEN_AUTO && nq >= 2048 && L >= 4096));
+    pl.digest = digest_ok && (ix->screen_mode == LORANN_SCREEN_DIGEST || (ix->screen_mode == LORANN_SCREEN_AUTO && nq >= 6144 && L >= 4096));
     if (pl.digest) pl.big_matrix = false;
     pl.lds_hist = (size_t)L * 8 <= 64 * 1024;
     pl.nbb = (int)((nq + kBucketQueries - 1) / kBucketQueries);

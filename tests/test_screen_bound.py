@@ -88,3 +88,42 @@ def test_the_list_contains_the_exact_w_best():
         listed = approx[i] <= gw + 2.0 * eps[i]
         assert listed[best].all()
         assert listed.sum() >= w
+
+
+def test_subset_minima_bound_and_lists_give_the_same_list():
+    """The route that never forms the full row of approximate values: the w-th smallest of the minima of 256 disjoint
+    subsets of the clusters bounds the w-th smallest approximate value from above, so the entries at or below that
+    bound + 2 eps - even when they come from a second evaluation whose float additions ran in another order, i.e. differ
+    from the first within eps - contain the w-th smallest approximate value and the whole final list of the rule above;
+    the final list built from them is the list built from the full row."""
+    rng = np.random.default_rng(8)
+    dp, L, w, S = 64, 5000, 64, 256
+    c = rng.normal(size=(L, dp)).astype(np.float32)
+    c /= np.linalg.norm(c, axis=1, keepdims=True)
+    c[700:1000] = c[700] * (1.0 + 1e-6 * rng.normal(size=(300, 1))).astype(np.float32)
+    q = (c[700][None, :] + 0.05 * rng.normal(size=(24, dp))).astype(np.float32)
+    q[12:] = rng.normal(size=(12, dp)).astype(np.float32)
+    exact = (-(q.astype(np.float64) @ c.astype(np.float64).T)).astype(np.float32)
+    qb, cb = _bf16(q), _bf16(c)
+    first = -(qb @ cb.T)                                                   # float accumulation, one order
+    second = -np.add.reduce((qb[:, None, ::-1] * cb[None, :, ::-1]).astype(np.float32), axis=2, dtype=np.float32)   # another order
+    eps = _eps_ip(q, c)
+    assert np.all(np.abs(second.astype(np.float64) - exact) <= eps[:, None])
+    # subsets as the kernel forms them: clusters with equal (l mod 64 row pattern, run of tiles) - any disjoint partition will do
+    subset = (np.arange(L) % 32) + 32 * np.minimum((np.arange(L) // 64) // ((L // 64 + 8) // 8), 7)
+    assert subset.max() < S
+    for i in range(q.shape[0]):
+        mins = np.full(S, np.inf, np.float32)
+        np.minimum.at(mins, subset, first[i])
+        bound = np.sort(mins)[w - 1]
+        assert bound >= np.sort(first[i])[w - 1]
+        thr = bound + 2.0 * eps[i]
+        listed = second[i] <= thr
+        best = np.argsort(exact[i], kind="stable")[:w]
+        assert listed[best].all() and listed.sum() >= w
+        gw_list = np.sort(second[i][listed])[w - 1]
+        assert gw_list == np.sort(second[i])[w - 1]                        # the w-th smallest approximate value is in the list
+        final_from_list = np.flatnonzero(listed)[second[i][listed] <= gw_list + 2.0 * eps[i]]
+        final_from_row = np.flatnonzero(second[i] <= gw_list + 2.0 * eps[i])
+        np.testing.assert_array_equal(final_from_list, final_from_row)
+        assert np.isin(best, final_from_list).all()
