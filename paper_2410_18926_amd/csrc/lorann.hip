@@ -449,10 +449,12 @@ int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ
 #define LAUNCH_SP(KS_, L2_, EMIT_, W_) hipLaunchKernelGGL((k_screen_pass<KS_, L2_, EMIT_, W_>), dim3((unsigned)((nq + 64 * W_ - 1) / (64 * W_)), kFusedSplits), dim3(64 * W_), (size_t)2 * (64 * (32 * KS_ + 16) + 256), s, pa)
 #define LAUNCH_SP2(EMIT_, W_) do { if (dp == 128) { if (l2) LAUNCH_SP(8, true, EMIT_, W_); else LAUNCH_SP(8, false, EMIT_, W_); } \
                                else { if (l2) LAUNCH_SP(12, true, EMIT_, W_); else LAUNCH_SP(12, false, EMIT_, W_); } } while (0)
-            LAUNCH_SP2(false, 8);
+            // blocks of 512 queries when they fill the 256 CUs at least once, else of 256 (twice the blocks)
+            const bool wide = ((nq + 511) / 512) * kFusedSplits >= 256;
+            if (wide) LAUNCH_SP2(false, 8); else LAUNCH_SP2(false, 4);
             hipLaunchKernelGGL(k_screen_threshold, dim3((unsigned)((nq + 3) / 4)), dim3(256), 0, s, ws.smin.as<float>(), qp, (int)nq, dp, w, l2, ix->mu_max, ix->dmu_max,
                                l2 ? ix->nrm_max : 0.0f, ws.thr.as<float>());
-            LAUNCH_SP2(true, 8);
+            if (wide) LAUNCH_SP2(true, 8); else LAUNCH_SP2(true, 4);
 #undef LAUNCH_SP2
 #undef LAUNCH_SP
         } else {
