@@ -346,11 +346,8 @@ __global__ __launch_bounds__(kGatherThreads) void k_group_gather(GroupArgs a) {
 // LDS traffic) and a ballot; only when several lanes hold that distance are their ids compared.
 // grid = ceil(nq / 4), block = 256.
 template <int EPL>
-__global__ __launch_bounds__(256) void k_topk_wave(GroupArgs a) {
+__device__ __forceinline__ void topk_wave_query(const GroupArgs& a, int64_t q, int cnt) {
     const int lane = threadIdx.x & 63;
-    const int64_t q = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (q >= a.nq) return;
-    const int cnt = a.ccount[q];
     uint32_t kv[EPL];                       // order-preserving key of the distance; 0xFFFFFFFF = retired / padding
     int64_t iv[EPL];
 #pragma unroll
@@ -397,6 +394,13 @@ __global__ __launch_bounds__(256) void k_topk_wave(GroupArgs a) {
     }
 }
 
+template <int EPL>
+__global__ __launch_bounds__(256) void k_topk_wave(GroupArgs a) {
+    const int64_t q = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (q >= a.nq) return;
+    topk_wave_query<EPL>(a, q, a.ccount[q]);
+}
+
 // The k smallest (distance, id) of each query: bitonic sort in LDS.  grid = nq, block = 256,
 // dynamic LDS = mp2 * 12 bytes (mp2 = power of two >= m, >= 256).
 __global__ __launch_bounds__(256) void k_topk(GroupArgs a, int mp2) {
@@ -430,6 +434,84 @@ __global__ __launch_bounds__(256) void k_topk(GroupArgs a, int mp2) {
         a.out_ids[(size_t)q * a.k + t] = id == kPadId ? -1 : id;
         a.out_dists[(size_t)q * a.k + t] = id == kPadId ? INFINITY : sdist[t];
     }
+}
+
+// Re-rank and top-k of a SMALL batch in one launch: a query's candidates are distinct rows, so no union is needed;
+// `slices` blocks per query each take a run of its candidate list (one wavefront per row, two rows in flight, the
+// query's elements in registers), write distances and ids at the candidates' own positions, and the block that
+// finishes a query last - a ticket per query, device-scope fences around it: a handful of blocks, not the thousands for
+// which such fences are ruinous - orders the query's results with the wavefront top-k.  The distance arithmetic is that
+// of k_group_gather, lane for lane (same element ownership, same order, same reduction): bit-identical results.
+// grid = nq * slices, block = 256.  done [nq]: zero on entry.  NV = ceil(d / 256) <= 4, d % 4 == 0; m <= 64 * EPL.
+template <int METRIC, int NV, typename T, int EPL>
+__global__ __launch_bounds__(256) void k_small_rerank(GroupArgs a, int slices, int32_t* __restrict__ done) {
+    using V = typename Row4<T>::type;
+    __shared__ int s_last;
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int q = (int)blockIdx.x / slices, sl = (int)blockIdx.x - q * slices;
+    const int d = a.d, d4 = d >> 2, m = a.m;
+    const int per = (m + slices - 1) / slices;
+    const int t_beg = sl * per, t_end = min(m, t_beg + per);
+    const T* corpus = reinterpret_cast<const T*>(a.corpus);
+    const float4* q4 = reinterpret_cast<const float4*>(a.Q + (size_t)q * d);
+    float4 y[NV];
+#pragma unroll
+    for (int v = 0; v < NV; ++v) y[v] = q4[min(lane + 64 * v, d4 - 1)];
+    float qn = 0.0f;
+    if (METRIC == 2) {
+        float acc = 0.0f;
+        for (int i = lane; i < d; i += 64) acc = fmaf(a.Q[(size_t)q * d + i], a.Q[(size_t)q * d + i], acc);
+        qn = sqrtf(wave_sum_f32(acc));
+    }
+    for (int t0 = t_beg + wv; t0 < t_end; t0 += 8) {
+        int row[2];
+        V x[2][NV];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {                       // clamped: a repeat of the run's last candidate, not stored
+            row[u] = a.cand[(size_t)q * m + min(t0 + 4 * u, t_end - 1)];
+            const V* p4 = reinterpret_cast<const V*>(corpus + (size_t)max(row[u], 0) * d);
+#pragma unroll
+            for (int v = 0; v < NV; ++v) x[u][v] = row_load(p4 + min(lane + 64 * v, d4 - 1));
+        }
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int t = t0 + 4 * u;
+            if (t >= t_end || row[u] < 0) continue;         // uniform over the wavefront
+            float acc = 0.0f;
+#pragma unroll
+            for (int v = 0; v < NV; ++v) {
+                if (v + 1 < NV || lane + 64 * v < d4) {
+                    const float4 yy = y[v], xv = widen4(x[u][v]);
+                    if (METRIC == 1) {
+                        const float a0 = yy.x - xv.x, a1 = yy.y - xv.y, a2 = yy.z - xv.z, a3 = yy.w - xv.w;
+                        acc = fmaf(a0, a0, acc); acc = fmaf(a1, a1, acc); acc = fmaf(a2, a2, acc); acc = fmaf(a3, a3, acc);
+                    } else {
+                        acc = fmaf(xv.x, yy.x, acc); acc = fmaf(xv.y, yy.y, acc); acc = fmaf(xv.z, yy.z, acc); acc = fmaf(xv.w, yy.w, acc);
+                    }
+                }
+            }
+            acc = wave_sum_f32_lane63(acc);
+            if (lane == 63) {
+                float dist;
+                if (METRIC == 1) dist = acc;
+                else if (METRIC == 0) dist = -acc;
+                else dist = qn > 0.0f ? 1.0f - acc / qn : 1.0f;
+                a.dist[(size_t)q * m + t] = dist;
+                a.cid[(size_t)q * m + t] = a.ids ? a.ids[row[u]] : (int64_t)row[u];
+            }
+        }
+    }
+    __threadfence();
+    __syncthreads();
+    if (tid == 0) s_last = atomicAdd(&done[q], 1) == slices - 1 ? 1 : 0;
+    __syncthreads();
+    if (!s_last || wv != 0) return;
+    __threadfence();
+    int cnt = 0;                                             // valid candidates come first
+    for (int t = lane; t < m; t += 64) cnt += a.cand[(size_t)q * m + t] >= 0 ? 1 : 0;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) cnt += __shfl_xor(cnt, o, 64);
+    topk_wave_query<EPL>(a, q, cnt);
 }
 
 }  // namespace lorann

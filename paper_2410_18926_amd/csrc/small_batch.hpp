@@ -28,6 +28,7 @@ struct SmallArgs {
     int32_t* slot_of_pos;        // [nq*w] identity
     int64_t* voff;               // [nq*w][2] first row and end row of the pair's cluster
     int32_t* qorder;             // [nq] identity
+    int32_t* done;               // [nq] cleared here: tickets of the query's re-rank blocks
 };
 
 // grid = ceil(npairs / (4 * ppw)), block = 256; ppw = pairs per wavefront: 2 when r_pad <= 32 (lanes 0..31 the columns
@@ -88,7 +89,7 @@ __global__ __launch_bounds__(256) void k_small_stage_a(SmallArgs s, const int32_
         s.slot_of_pos[p] = p;
         s.voff[2 * (size_t)p] = s.off[c];
         s.voff[2 * (size_t)p + 1] = s.off[c + 1];
-        if (p % w == 0) s.qorder[q] = q;
+        if (p % w == 0) { s.qorder[q] = q; s.done[q] = 0; }
     }
 }
 

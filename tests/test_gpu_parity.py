@@ -731,6 +731,35 @@ def test_half_precision_rerank_row_lengths(B, d, metric):
     gix.close()
 
 
+@pytest.mark.parametrize("d,metric,nq,m,half", [(64, 1, 1, 100, False), (300, 0, 5, 60, False), (768, 2, 8, 200, False), (1024, 0, 3, 300, True),
+                                               (1024, 1, 8, 512, False), (96, 2, 2, 40, True), (1028, 0, 4, 100, False)])
+def test_a_handful_of_queries_rerank_in_one_launch(B, d, metric, nq, m, half):
+    """Up to eight queries: the re-rank computes distances and orders the results in ONE launch (blocks per query,
+    the last one to finish orders).  One to four register slices per row, float and half-precision rows, caller ids,
+    fewer than m candidates, a row length that takes the general path instead; against the oracle, and the same
+    queries inside a batch of 100 (grouped gather + separate top-k) must give the same bits."""
+    rng = np.random.default_rng(5000 + d + metric + nq)
+    ix = _random_index(rng, n=1500, d=d, L=12, r=8, metric=metric, dp=64 if d >= 64 else 32)
+    if half and metric != 2:
+        ix["corpus"] = (ix["corpus"] * np.float32(0.25)).astype(np.float32)
+    big = rng.normal(size=(100, d)).astype(np.float32)
+    q = big[:nq].copy()
+    w, k = (2 if m >= 300 else 5), 10         # (two clusters of about 125 points: fewer than m candidates)
+    gix = B.Index(**ix)
+    if half:
+        gix.set_rerank(B.RERANK_F16)
+    for rep in range(2):                      # twice: the tickets of the first call must not linger
+        s_ids, s_d, sst = gix.search_stages(q, k, w, m)
+        b_ids, b_d = gix.search(big, k, w, m)
+        np.testing.assert_array_equal(s_ids, b_ids[:nq])
+        np.testing.assert_array_equal(s_d.view(np.uint32), b_d[:nq].view(np.uint32))
+    if m >= 300:
+        assert (sst["cand_rows"] < 0).any(), "the case is meant to have queries with fewer than m candidates"
+    o_ids, o_d = O.search(O.OracleIndex(O.with_half_precision_corpus(ix) if half else ix), q, k, w, m)
+    assert_topk_equal(s_ids, s_d, o_ids, o_d, f"handful d={d} metric={metric} nq={nq} half={half}")
+    gix.close()
+
+
 def test_half_precision_rerank_refuses_values_out_of_range(B):
     rng = np.random.default_rng(77)
     ix = _random_index(rng, n=600, d=32, L=6, r=8, metric=0)
