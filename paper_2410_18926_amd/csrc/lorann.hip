@@ -378,7 +378,7 @@ int reserve_workspace(const lorann_index* ix, Workspace& ws, const ChunkPlan& pl
         {&ws.u_row, (size_t)pl.ngroups * gm * 4, pl.grouped}, {&ws.u_mask, (size_t)pl.ngroups * gm * 2, pl.grouped},
         {&ws.u_pos, (size_t)pl.ngroups * gm * pl.group_q * 2, pl.grouped}, {&ws.u_count, (size_t)pl.ngroups * 4, pl.grouped},
         {&ws.rdist, q * m * 4, pl.grouped || no_rerank}, {&ws.rcid, q * m * 8, pl.grouped || no_rerank},
-        {&ws.rccount, q * 4, pl.grouped || no_rerank},
+        {&ws.rccount, q * 4, pl.grouped || no_rerank || pl.small},      // (small batches: also the tickets of the one-launch re-rank)
         {&ws.smin, q * kFusedSubsets * 4, pl.digest}, {&ws.thr, q * 4, pl.digest},
         {&ws.hit_val, q * kFusedLists * kFusedCap * 64, pl.digest}, {&ws.hit_grp, q * kFusedLists * kFusedCap * 4, pl.digest},
         {&ws.hit_cnt, q * kFusedLists * 4, pl.digest},
@@ -482,6 +482,7 @@ int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ
             sa.nlist = kFusedLists; sa.cap = kFusedCap;
             if (pl.digest) hipLaunchKernelGGL((k_select_clusters_screen<1, false, true>), dim3((unsigned)nq), dim3(256), lds, s, sa);
             else if (L <= 1024) hipLaunchKernelGGL(k_select_clusters_screen_wave<16>, dim3((unsigned)((nq + 3) / 4)), dim3(256), 4 * lds, s, sa, (int)nq);
+            else if (L <= 2048) hipLaunchKernelGGL(k_select_clusters_screen_wave<32>, dim3((unsigned)((nq + 3) / 4)), dim3(256), 4 * lds, s, sa, (int)nq);
             else if (L <= 4096) hipLaunchKernelGGL(k_select_clusters_screen<16>, dim3((unsigned)nq), dim3(256), lds, s, sa);
             else if (big_matrix) hipLaunchKernelGGL((k_select_clusters_screen<64, true>), dim3((unsigned)nq), dim3(256), lds, s, sa);
             else hipLaunchKernelGGL(k_select_clusters_screen<64>, dim3((unsigned)nq), dim3(256), lds, s, sa);
