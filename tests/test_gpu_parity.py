@@ -732,11 +732,12 @@ def test_half_precision_rerank_row_lengths(B, d, metric):
 
 
 @pytest.mark.parametrize("d,metric,nq,m,half", [(64, 1, 1, 100, False), (300, 0, 5, 60, False), (768, 2, 8, 200, False), (1024, 0, 3, 300, True),
-                                               (1024, 1, 8, 512, False), (96, 2, 2, 40, True), (1028, 0, 4, 100, False)])
+                                               (1024, 1, 8, 512, False), (96, 2, 2, 40, True), (1028, 0, 4, 100, False), (64, 0, 2, 600, False)])
 def test_a_handful_of_queries_rerank_in_one_launch(B, d, metric, nq, m, half):
     """Up to eight queries: the re-rank computes distances and orders the results in ONE launch (blocks per query,
     the last one to finish orders).  One to four register slices per row, float and half-precision rows, caller ids,
-    fewer than m candidates, a row length that takes the general path instead; against the oracle, and the same
+    fewer than m candidates, a row length and a candidate count (m = 600) that take the general path instead; against
+    the oracle, and the same
     queries inside a batch of 100 (grouped gather + separate top-k) must give the same bits."""
     rng = np.random.default_rng(5000 + d + metric + nq)
     ix = _random_index(rng, n=1500, d=d, L=12, r=8, metric=metric, dp=64 if d >= 64 else 32)
