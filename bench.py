@@ -78,9 +78,9 @@ def kernel_models(wl, nq, touched_rows, npairs, scores, column_scales=False, mix
     return {
         "project_f64": ("mfma", 2.0 * nq * d * dp / 1e12, PEAK_FP64_MFMA_TFLOPS, "TFLOP/s"),
         "centroid_dissim_f64": ("mfma", 2.0 * nq * dp * L / 1e12, PEAK_FP64_MFMA_TFLOPS, "TFLOP/s"),
-        # (launches of at least 6144 queries over at least 4096 clusters with d' of 128 or 192 compute the product twice
+        # (launches of at least 6144 queries over at least 4096 clusters with d' of 128, 192 or 256 compute the product twice
         # and keep only digests: lorann_set_screen_mode)
-        "centroid_screen_bf16": ("mfma", (2.0 if min(nq, 32768) >= 6144 and L >= 4096 and dp in (128, 192) and wl.w <= 128 else 1.0) * 2.0 * nq * dp * L / 1e12,
+        "centroid_screen_bf16": ("mfma", (2.0 if min(nq, 32768) >= 6144 and L >= 4096 and dp in (128, 192, 256) and wl.w <= 128 else 1.0) * 2.0 * nq * dp * L / 1e12,
                                  PEAK_BF16_MFMA_TFLOPS, "TFLOP/s"),
         "route_fused_bf16": ("mfma", 2.0 * nq * dp * L / 1e12, PEAK_BF16_MFMA_TFLOPS, "TFLOP/s"),
         "quantize_rows": lat, "select_clusters": lat, "bucket_count": lat, "scan_buckets": lat, "scatter_pairs": lat,

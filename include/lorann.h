@@ -186,7 +186,7 @@ int lorann_set_exact_selection(lorann_index *ix, int32_t on);
  *   LORANN_SCREEN_MATRIX  all nq x L values are written to device memory and read back by the selection;
  *   LORANN_SCREEN_DIGEST  the bf16 product is computed twice and only digests are kept (minima of 256 disjoint
  *                         subsets of the clusters, then the values at or below a per-query threshold); needs
- *                         d' of 128 or 192, L >= 1024 and w <= 128, otherwise the matrix route is taken;
+ *                         d' of 128, 192 or 256, L >= 1024 and w <= 128, otherwise the matrix route is taken;
  *   LORANN_SCREEN_AUTO    (default) digests for launches of at least 6144 queries over at least 4096 clusters.
  * Waits for the index's searches in flight.  Errors: LORANN_E_INVAL for an unknown mode. */
 enum { LORANN_SCREEN_AUTO = 0, LORANN_SCREEN_MATRIX = 1, LORANN_SCREEN_DIGEST = 2 };

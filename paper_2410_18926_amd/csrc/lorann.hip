@@ -336,9 +336,9 @@ ChunkPlan plan_chunk(const lorann_index* ix, int64_t nq, int w, int m) {
     pl.big_matrix = pl.screen && L > 4096 && (int64_t)nq * L * 4 > (int64_t(256) << 20);
     // Many queries x many clusters: the matrix would be written and read once through HBM; two passes of the product
     // that keep only digests are cheaper (measured at L = 16384: from about 5000 queries on; below, the 8 x ceil(nq/512)
-    // blocks of a pass leave most CUs idle).  Needs the query operand resident in registers (d' of 128 or 192) and enough
+    // blocks of a pass leave most CUs idle).  Needs the query operand resident in registers (d' of 128, 192 or 256) and enough
     // centroid tiles for every run of the second grid dimension.
-    const bool digest_ok = pl.screen && (ix->dp == 128 || ix->dp == 192) && L >= 128 * kFusedSplits && w <= kFusedSubsets / 2;
+    const bool digest_ok = pl.screen && (ix->dp == 128 || ix->dp == 192 || ix->dp == 256) && L >= 128 * kFusedSplits && w <= kFusedSubsets / 2;
     pl.digest = digest_ok && (ix->screen_mode == LORANN_SCREEN_DIGEST || (ix->screen_mode == LORANN_SCREEN_AUTO && nq >= 6144 && L >= 4096));
     if (pl.digest) pl.big_matrix = false;
     pl.lds_hist = (size_t)L * 8 <= 64 * 1024;
@@ -446,9 +446,10 @@ int search_chunk(lorann_index* ix, Workspace& ws, hipStream_t s, const float* dQ
             pa.smin = ws.smin.as<float>(); pa.thr = ws.thr.as<float>(); pa.hit_val = ws.hit_val.as<float>();
             pa.hit_grp = ws.hit_grp.as<int32_t>(); pa.hit_cnt = ws.hit_cnt.as<int32_t>();
             const bool l2 = ix->metric == LORANN_L2;
-#define LAUNCH_SP(KS_, L2_, EMIT_, W_) hipLaunchKernelGGL((k_screen_pass<KS_, L2_, EMIT_, W_>), dim3((unsigned)((nq + 64 * W_ - 1) / (64 * W_)), kFusedSplits), dim3(64 * W_), (size_t)2 * (64 * (32 * KS_ + 16) + 256), s, pa)
+#define LAUNCH_SP(KS_, L2_, EMIT_, W_) hipLaunchKernelGGL((k_screen_pass<KS_, L2_, EMIT_, W_>), dim3((unsigned)((nq + 64 * W_ - 1) / (64 * W_)), kFusedSplits), dim3(64 * W_), (size_t)2 * (KS_ == 16 ? 64 * 512 : 64 * (32 * KS_ + 16) + 256), s, pa)
 #define LAUNCH_SP2(EMIT_, W_) do { if (dp == 128) { if (l2) LAUNCH_SP(8, true, EMIT_, W_); else LAUNCH_SP(8, false, EMIT_, W_); } \
-                               else { if (l2) LAUNCH_SP(12, true, EMIT_, W_); else LAUNCH_SP(12, false, EMIT_, W_); } } while (0)
+                               else if (dp == 192) { if (l2) LAUNCH_SP(12, true, EMIT_, W_); else LAUNCH_SP(12, false, EMIT_, W_); } \
+                               else { if (l2) LAUNCH_SP(16, true, EMIT_, W_); else LAUNCH_SP(16, false, EMIT_, W_); } } while (0)
             // blocks of 512 queries when they fill the 256 CUs at least once, else of 256 (twice the blocks)
             const bool wide = ((nq + 511) / 512) * kFusedSplits >= 256;
             if (wide) LAUNCH_SP2(false, 8); else LAUNCH_SP2(false, 4);

@@ -59,8 +59,12 @@ template <int KS, bool L2, bool EMIT, int WAVES>
 __global__ __launch_bounds__(64 * WAVES) void k_screen_pass(ScreenPassArgs a) {
     constexpr int DP = 16 * KS;
     constexpr int NT = 64 * WAVES;
-    constexpr int ROWB = DP * 2 + 16;             // bytes of a staged centroid row (16 of padding: conflict-free 16-byte reads)
-    constexpr int TILEB = 64 * ROWB + 256;        // + the tile's 64 norms
+    // A staged centroid row is padded by 16 bytes so that the 16-byte reads of 8 consecutive rows fall into different
+    // banks; at d' = 256 two padded tiles would exceed 64 KB of LDS, so there the 16-byte pieces of a row are permuted
+    // instead (piece p of row i sits in slot p ^ (i % 8): same effect, no padding) and the norms come from memory.
+    constexpr bool SWZ = KS == 16;
+    constexpr int ROWB = DP * 2 + (SWZ ? 0 : 16);
+    constexpr int TILEB = 64 * ROWB + (SWZ ? 0 : 256);        // + the tile's 64 norms
     constexpr int RP = DP / 8;                    // 16-byte pieces per row
     constexpr int PPT = 64 * RP / NT;             // pieces per thread
     static_assert(64 * RP % NT == 0, "tile pieces divide over the block");
@@ -92,16 +96,16 @@ __global__ __launch_bounds__(64 * WAVES) void k_screen_pass(ScreenPassArgs a) {
             const int p = tid + NT * u, row = p / RP, pc = p - row * RP;
             stage[u] = *reinterpret_cast<const uint4*>(a.C + (size_t)min(tile * 64 + row, a.L - 1) * DP + 8 * pc);
         }
-        if (L2 && tid < 64) nstage = a.nrm[min(tile * 64 + tid, a.L - 1)];
+        if (L2 && !SWZ && tid < 64) nstage = a.nrm[min(tile * 64 + tid, a.L - 1)];
     };
     auto s_store = [&](int buf) {
         unsigned char* tb = sf_smem + buf * TILEB;
 #pragma unroll
         for (int u = 0; u < PPT; ++u) {
             const int p = tid + NT * u, row = p / RP, pc = p - row * RP;
-            *reinterpret_cast<uint4*>(tb + row * ROWB + pc * 16) = stage[u];
+            *reinterpret_cast<uint4*>(tb + row * ROWB + (SWZ ? (pc ^ (row & 7)) : pc) * 16) = stage[u];
         }
-        if (L2 && tid < 64) reinterpret_cast<float*>(tb + 64 * ROWB)[tid] = nstage;
+        if (L2 && !SWZ && tid < 64) reinterpret_cast<float*>(tb + 64 * ROWB)[tid] = nstage;
     };
 
     float mn[2][16];
@@ -134,8 +138,9 @@ __global__ __launch_bounds__(64 * WAVES) void k_screen_pass(ScreenPassArgs a) {
                 for (int v = 0; v < 16; ++v) acc[ct][qt][v] = 0.0f;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-            const bf16x8 a0 = *reinterpret_cast<const bf16x8*>(tb + i * ROWB + ks * 32 + h * 16);
-            const bf16x8 a1 = *reinterpret_cast<const bf16x8*>(tb + (32 + i) * ROWB + ks * 32 + h * 16);
+            const int piece = SWZ ? ((2 * ks + h) ^ (i & 7)) : 2 * ks + h;        // ((32 + i) % 8 == i % 8)
+            const bf16x8 a0 = *reinterpret_cast<const bf16x8*>(tb + i * ROWB + piece * 16);
+            const bf16x8 a1 = *reinterpret_cast<const bf16x8*>(tb + (32 + i) * ROWB + piece * 16);
             acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, qreg[0][ks], acc[0][0], 0, 0, 0);
             acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, qreg[1][ks], acc[0][1], 0, 0, 0);
             acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, qreg[0][ks], acc[1][0], 0, 0, 0);
@@ -145,7 +150,10 @@ __global__ __launch_bounds__(64 * WAVES) void k_screen_pass(ScreenPassArgs a) {
 #pragma unroll
         for (int ct = 0; ct < 2; ++ct) {
             float nv[16];
-            if (L2) {
+            if (L2 && SWZ) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) nv[v] = a.nrm[min(t * 64 + 32 * ct + 8 * (v >> 2) + 4 * h + (v & 3), a.L - 1)];
+            } else if (L2) {
                 const float4* n4 = reinterpret_cast<const float4*>(tb + 64 * ROWB) + (32 * ct + 4 * h) / 4;
 #pragma unroll
                 for (int g4 = 0; g4 < 4; ++g4) {
