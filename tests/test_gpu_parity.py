@@ -473,6 +473,38 @@ def test_many_clusters_full_launch_shapes_sampled_parity(B, nq):
     gix.close()
 
 
+@pytest.mark.parametrize("metric,d,dp,L", [(1, 128, 128, 4096), (2, 320, 256, 4500), (0, 200, 128, 6000)])
+def test_wide_launches_of_the_digest_screening_sampled_parity(B, metric, d, dp, L):
+    """Launches large enough for the 512-query blocks of the screening passes (16384 queries) in the shapes the 10M-point
+    workload does not cover: squared Euclidean (norms staged with the centroid tiles) and cosine, d' = 128 and 256 (the
+    permuted tile layout), cluster counts that are no multiple of the tile - random factors and codes on 200 000 points,
+    checked against the oracle on a sample of the batch."""
+    from paper_2410_18926_amd.synth import get_workload, random_index
+    import dataclasses
+    nq = 16384
+    wl = dataclasses.replace(get_workload("scale-ip"), n=200_000, d=d, dp=dp, L=L, metric=metric, nq=nq, w=32, m=100, r=16)
+    dev = torch.device("cuda:0")
+    g = torch.Generator(device=dev)
+    g.manual_seed(6100 + metric + dp)
+    corpus = torch.randn(wl.n, wl.d, generator=g, device=dev)
+    if metric == 2:
+        corpus /= corpus.norm(dim=1, keepdim=True)
+    queries = torch.randn(nq, wl.d, generator=g, device=dev)
+    ix = random_index(corpus, wl)
+    del corpus
+    gix = B.Index.from_arrays(ix)
+    a = ix.numpy()
+    del ix
+    torch.cuda.empty_cache()
+    _sampled_full_size_parity(B, gix, a, queries, wl.k, wl.w, wl.m, 48, f"wide digest launch metric={metric} d'={dp} L={L}")
+    gix.set_screen_mode(B.SCREEN_MATRIX)
+    m_ids, m_d, mst = gix.search_stages(queries[:4096], wl.k, wl.w, wl.m)
+    gix.set_screen_mode(B.SCREEN_AUTO)
+    d_ids, d_d, dst = gix.search_stages(queries, wl.k, wl.w, wl.m)
+    np.testing.assert_array_equal(dst["sel"][:4096], mst["sel"])
+    gix.close()
+
+
 @pytest.mark.parametrize("L,w,metric,case", [
     (700, 32, 0, "near_ties"), (700, 32, 1, "near_ties"), (700, 32, 2, "plateau"), (512, 100, 0, "plain"),
     (512, 100, 1, "near_ties"), (900, 40, 0, "outlier"), (900, 40, 1, "outlier"), (64, 64, 0, "plain"),
