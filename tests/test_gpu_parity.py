@@ -566,6 +566,7 @@ def test_routing_by_screening_adversarial(B, L, w, metric, case):
     (12000, 64, 0, 192, 300, "near_ties"), (12000, 128, 1, 192, 40, "plain"), (16384, 64, 0, 192, 600, "plain"),
     (5000, 40, 0, 128, 40, "outlier"), (5000, 40, 1, 192, 40, "outlier"), (4097, 100, 2, 128, 129, "near_ties"),
     (3000, 48, 0, 256, 300, "near_ties"), (9000, 64, 1, 256, 70, "plain"), (2049, 32, 2, 256, 600, "plateau"),
+    (1024, 128, 0, 128, 513, "plain"), (1100, 16, 1, 192, 512, "plain"), (1500, 1, 2, 128, 65, "plain"),
 ])
 def test_routing_by_screening_from_digests(B, L, w, metric, dp, nq, case):
     """The screening that never writes the nq x L matrix of approximate values (two passes of the bf16 product: minima
