@@ -84,18 +84,22 @@ def test_every_entry_point_rejects_a_null_index(B):
              lambda: lib.lorann_set_column_scales(None, None, None),
              lambda: lib.lorann_set_first_rows(None, None, None),
              lambda: lib.lorann_set_exact_selection(None, 1),
+             lambda: lib.lorann_set_screen_mode(None, 0),
+             lambda: lib.lorann_search_noalloc(None, None, 1, 1, 1, 1, None, None),
              lambda: lib.lorann_set_stream(None, None),
              lambda: lib.lorann_profile_enable(None, 1)]
     for call in calls:
         assert call() == B.LORANN_E_INVAL
         assert b"NULL" in lib.lorann_last_error()
     assert lib.lorann_profile_fallback_queries(None) == -1
+    assert lib.lorann_profile_gather_rows(None) == -1
 
 
 def test_header_constants_match_binding(B):
     header = (ROOT / "include" / "lorann.h").read_text()
     assert int(re.search(r"#define LORANN_LANES (\d+)", header).group(1)) == B.LANES
-    for name, val in (("LORANN_RERANK_F32", B.RERANK_F32), ("LORANN_RERANK_F16", B.RERANK_F16), ("LORANN_RERANK_NONE", B.RERANK_NONE)):
+    for name, val in (("LORANN_RERANK_F32", B.RERANK_F32), ("LORANN_RERANK_F16", B.RERANK_F16), ("LORANN_RERANK_NONE", B.RERANK_NONE),
+                      ("LORANN_SCREEN_AUTO", B.SCREEN_AUTO), ("LORANN_SCREEN_MATRIX", B.SCREEN_MATRIX), ("LORANN_SCREEN_DIGEST", B.SCREEN_DIGEST)):
         assert re.search(rf"{name}\s*=\s*{val}\b", header), name
 
 
