@@ -795,6 +795,29 @@ def test_a_handful_of_queries_rerank_in_one_launch(B, d, metric, nq, m, half):
     gix.close()
 
 
+def test_rows_requested_by_the_grouped_rerank_are_counted(B):
+    """lorann_profile_gather_rows (the numerator of the benchmark's roofline): the rows the last grouped re-rank fetched
+    lie between the distinct candidate rows of the batch (every row at least once) and the candidates themselves (no
+    sharing at all); with one query per group (a batch of 40 takes groups of one) it is exactly the candidates."""
+    rng = np.random.default_rng(321)
+    ix = _random_index(rng, n=4000, d=64, L=10, r=8, metric=0, dp=32)
+    gix = B.Index(**ix)
+    for nq in (200, 40):
+        q = rng.normal(size=(nq, 64)).astype(np.float32)
+        q[1::2] = q[0::2] + np.float32(0.01) * rng.normal(size=(nq // 2, 64)).astype(np.float32)     # neighbours share rows
+        ids, d, st = gix.search_stages(q, 10, 4, 120)
+        gix.search(q, 10, 4, 120)
+        rows = gix.profile_gather_rows()
+        cand = st["cand_rows"]
+        valid = int((cand >= 0).sum())
+        distinct = int(np.unique(cand[cand >= 0]).size)
+        if nq == 40:
+            assert rows == valid
+        else:
+            assert distinct <= rows < valid, (distinct, rows, valid)
+    gix.close()
+
+
 def test_half_precision_rerank_refuses_values_out_of_range(B):
     rng = np.random.default_rng(77)
     ix = _random_index(rng, n=600, d=32, L=6, r=8, metric=0)
