@@ -7,6 +7,7 @@ library has not been built (`python -m paper_2410_18926_amd.build`): there is no
 from __future__ import annotations
 
 import ctypes as C
+import os
 import pathlib
 
 import numpy as np
@@ -16,7 +17,8 @@ try:
 except Exception:  # pragma: no cover - torch is part of the image
     torch = None
 
-LIB_PATH = pathlib.Path(__file__).resolve().parent / "liblorann.so"
+# (LORANN_LIB names another build of the same library: the host-sanitized one of build.build_sanitized)
+LIB_PATH = pathlib.Path(os.environ.get("LORANN_LIB") or pathlib.Path(__file__).resolve().parent / "liblorann.so")
 
 LORANN_IP, LORANN_L2, LORANN_COS = 0, 1, 2
 LORANN_OK, LORANN_E_INVAL, LORANN_E_NOMEM, LORANN_E_DEVICE, LORANN_E_UNSUPPORTED = 0, -1, -2, -3, -4

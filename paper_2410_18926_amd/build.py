@@ -20,6 +20,29 @@ FLAGS = [
 ]
 
 
+SAN_LIB = HERE / "liblorann_san.so"
+
+
+def build_sanitized() -> pathlib.Path:
+    """The same library with AddressSanitizer and UndefinedBehaviorSanitizer in its HOST code (argument checks, index
+    loading, workspace planning; device code is compiled as usual).  Load it with LORANN_LIB=<path> and clang's
+    sanitizer runtime first in the process (sanitizer_runtime())."""
+    hipcc = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
+    flags = [f for f in FLAGS if f != "-O3"] + ["-O1", "-g", "-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+                                                 "-Xarch_host", "-fno-sanitize-recover=all", "-Xarch_host", "-fno-omit-frame-pointer"]
+    res = subprocess.run([hipcc, *flags, "-o", str(SAN_LIB), str(SRC)], capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + "\n".join(l for l in res.stderr.splitlines() if "packed-fp32-ops" not in l))
+    return SAN_LIB
+
+
+def sanitizer_runtime() -> str:
+    clang = pathlib.Path(shutil.which("hipcc") or "/opt/rocm/bin/hipcc").resolve().parent.parent / "llvm" / "bin" / "clang"
+    if not clang.exists():
+        clang = pathlib.Path("/opt/rocm/llvm/bin/clang")
+    return subprocess.run([str(clang), "--print-file-name=libclang_rt.asan-x86_64.so"], check=True, capture_output=True, text=True).stdout.strip()
+
+
 def sources():
     return [SRC] + sorted((HERE / "csrc").glob("*.hpp")) + [HERE.parent / "include" / "lorann.h"]
 
